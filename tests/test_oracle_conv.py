@@ -1,0 +1,187 @@
+"""Pins for the oracle's integer convolutions and de-quantization.
+
+The oracle's loops are the definition of the two gradient products (Eq. "gx",
+Eq. "gw").  They are pinned against: an independently derived scatter form
+(pure Python, written from the forward convolution), the exact integer adjoint
+identity, torch's CPU float64 gradient routines applied to the integer codes
+(exact below 2^53), and plain integer matrix products for 1x1 kernels.
+"""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+CASES = [
+    # N Cin H  W Cout k  s  p  d  g
+    (2, 3, 5, 6, 4, 3, 1, 1, 1, 1),
+    (1, 4, 7, 5, 6, 3, 2, 1, 1, 1),
+    (2, 2, 9, 9, 3, 7, 2, 3, 1, 1),
+    (1, 3, 6, 6, 2, 1, 1, 0, 1, 1),
+    (2, 4, 6, 7, 4, 1, 2, 0, 1, 1),
+    (1, 2, 8, 8, 2, 3, 1, 2, 2, 1),
+    (2, 4, 6, 6, 4, 3, 1, 1, 1, 4),   # depthwise
+    (1, 4, 7, 7, 8, 3, 2, 1, 1, 2),   # grouped
+    (1, 3, 5, 5, 2, 3, 1, 0, 1, 1),   # no padding
+    (1, 2, 6, 5, 3, 3, 1, 3, 1, 1),   # padding larger than the kernel reach
+]
+
+
+def _desc(ref, c):
+    N, Cin, H, W, Cout, k, s, p, d, g = c
+    return ref.ConvDesc(N, Cin, H, W, Cout, k, k, s, s, p, p, d, d, g)
+
+
+def _rand_codes(rng, shape):
+    return rng.integers(-127, 128, size=shape, dtype=np.int64).astype(np.int8)
+
+
+def _forward_python(d, qX, qW):
+    """Forward convolution straight from its definition (pure Python, int)."""
+    Ho, Wo = d.Ho, d.Wo
+    cig, cog = d.Cin // d.groups, d.Cout // d.groups
+    Y = np.zeros(d.y_shape, dtype=np.int64)
+    for n, co, ho, wo in itertools.product(range(d.N), range(d.Cout), range(Ho), range(Wo)):
+        g = co // cog
+        a = 0
+        for cl, kh, kw in itertools.product(range(cig), range(d.kH), range(d.kW)):
+            h = ho * d.strideH + kh * d.dilH - d.padH
+            w = wo * d.strideW + kw * d.dilW - d.padW
+            if 0 <= h < d.Hin and 0 <= w < d.Win:
+                a += int(qX[n, g * cig + cl, h, w]) * int(qW[co, cl, kh, kw])
+        Y[n, co, ho, wo] = a
+    return Y
+
+
+def _backward_scatter_python(d, qX, qW, qG):
+    """dX and dW as the adjoint of the forward loop: every forward product x*w that feeds y
+    sends g*w to dX and g*x to dW (scatter form, no index inversion)."""
+    Ho, Wo = d.Ho, d.Wo
+    cig, cog = d.Cin // d.groups, d.Cout // d.groups
+    dX = np.zeros(d.x_shape, dtype=np.int64)
+    dW = np.zeros(d.w_shape, dtype=np.int64)
+    for n, co, ho, wo in itertools.product(range(d.N), range(d.Cout), range(Ho), range(Wo)):
+        g = co // cog
+        gv = int(qG[n, co, ho, wo])
+        for cl, kh, kw in itertools.product(range(cig), range(d.kH), range(d.kW)):
+            h = ho * d.strideH + kh * d.dilH - d.padH
+            w = wo * d.strideW + kw * d.dilW - d.padW
+            if 0 <= h < d.Hin and 0 <= w < d.Win:
+                dX[n, g * cig + cl, h, w] += gv * int(qW[co, cl, kh, kw])
+                dW[co, cl, kh, kw] += gv * int(qX[n, g * cig + cl, h, w])
+    return dX, dW
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_against_scatter_form_and_torch(ref, case):
+    d = _desc(ref, case)
+    rng = np.random.default_rng(hash(case) % 2 ** 32)
+    qX, qW, qG = _rand_codes(rng, d.x_shape), _rand_codes(rng, d.w_shape), _rand_codes(rng, d.y_shape)
+
+    accY, o1 = ref.conv_fwd_acc(d, qX, qW)
+    accX, o2 = ref.conv_bwd_data_acc(d, qG, qW)
+    accW, o3 = ref.conv_bwd_filter_acc(d, qX, qG)
+    assert not (o1 or o2 or o3)
+
+    # brute force, independent derivation
+    assert np.array_equal(accY, _forward_python(d, qX, qW))
+    dXs, dWs = _backward_scatter_python(d, qX, qW, qG)
+    assert np.array_equal(accX, dXs)
+    assert np.array_equal(accW, dWs)
+
+    # exact adjoint identity  <fwd(X,W), G> = <X, dX> = <W, dW>
+    lhs = int(np.sum(accY.astype(np.int64) * qG.astype(np.int64)))
+    assert lhs == int(np.sum(accX.astype(np.int64) * qX.astype(np.int64)))
+    assert lhs == int(np.sum(accW.astype(np.int64) * qW.astype(np.int64)))
+
+    # library special case: float64 autograd routines on the integer codes are exact here
+    tX, tW, tG = (torch.from_numpy(a.astype(np.float64)) for a in (qX, qW, qG))
+    kw = dict(stride=(d.strideH, d.strideW), padding=(d.padH, d.padW), dilation=(d.dilH, d.dilW), groups=d.groups)
+    tY = torch.nn.functional.conv2d(tX, tW, **kw)
+    assert np.array_equal(accY, tY.numpy().astype(np.int64))
+    tdX = torch.nn.grad.conv2d_input(d.x_shape, tW, tG, **kw)
+    tdW = torch.nn.grad.conv2d_weight(tX, d.w_shape, tG, **kw)
+    assert np.array_equal(accX, tdX.numpy().astype(np.int64))
+    assert np.array_equal(accW, tdW.numpy().astype(np.int64))
+
+
+def test_one_by_one_is_a_matrix_product(ref):
+    d = ref.ConvDesc(3, 8, 5, 4, 6, 1, 1)
+    rng = np.random.default_rng(11)
+    qX, qW, qG = _rand_codes(rng, d.x_shape), _rand_codes(rng, d.w_shape), _rand_codes(rng, d.y_shape)
+    Xm = qX.astype(np.int64).transpose(1, 0, 2, 3).reshape(8, -1)    # [Cin, N*H*W]   (the transformed X')
+    Gm = qG.astype(np.int64).transpose(1, 0, 2, 3).reshape(6, -1)    # [Cout, N*H*W]  (the transformed G')
+    Wm = qW.astype(np.int64).reshape(6, 8)
+    accW, _ = ref.conv_bwd_filter_acc(d, qX, qG)
+    accX, _ = ref.conv_bwd_data_acc(d, qG, qW)
+    assert np.array_equal(accW.reshape(6, 8), Gm @ Xm.T)
+    assert np.array_equal(accX.transpose(1, 0, 2, 3).reshape(8, -1), Wm.T @ Gm)
+
+
+def test_int32_wraparound_is_flagged(ref):
+    # K * 127^2 > 2^31 needs K > 133144: a 1x1 layer with 140000 positions of +127 * +127
+    d = ref.ConvDesc(1, 1, 350, 400, 1, 1, 1)
+    qX = np.full(d.x_shape, 127, np.int8)
+    qG = np.full(d.y_shape, 127, np.int8)
+    acc, ovf = ref.conv_bwd_filter_acc(d, qX, qG)
+    true = 140000 * 127 * 127
+    assert ovf and int(acc[0, 0, 0, 0]) == ((true + 2 ** 31) % 2 ** 32) - 2 ** 31
+    qG.reshape(-1)[:7000] = 0
+    acc, ovf = ref.conv_bwd_filter_acc(d, qX, qG)
+    assert not ovf and int(acc[0, 0, 0, 0]) == 133000 * 127 * 127
+
+
+def test_dequantization_closed_form(ref):
+    # G_W[co] = acc * s_x/127 * s_co/127 ;  G_X = acc * s_w/127 * s_g/127  -- within 3 ulp of the fp64 value
+    d = ref.ConvDesc(2, 4, 6, 6, 5, 3, 3, 1, 1, 1, 1)
+    rng = np.random.default_rng(12)
+    qX, qW, qG = _rand_codes(rng, d.x_shape), _rand_codes(rng, d.w_shape), _rand_codes(rng, d.y_shape)
+    s_x, s_w, s_g = np.float32(2.37), np.float32(0.113), np.float32(4.2e-3)
+    s_c = (10.0 ** rng.uniform(-4, -1, d.Cout)).astype(np.float32)
+    dW, accW, _ = ref.conv_bwd_filter_int8(d, qX, float(s_x), qG, s_c)
+    dX, accX, _ = ref.conv_bwd_data_int8(d, qG, float(s_g), qW, float(s_w))
+    eW = accW.astype(np.float64) * (float(s_x) / 127) * (s_c.astype(np.float64).reshape(-1, 1, 1, 1) / 127)
+    eX = accX.astype(np.float64) * (float(s_w) / 127) * (float(s_g) / 127)
+    tol = 3 * 2.0 ** -24
+    assert np.all(np.abs(dW - eW) <= tol * np.abs(eW) + 1e-45)
+    assert np.all(np.abs(dX - eX) <= tol * np.abs(eX) + 1e-45)
+    # the filter gradient is scaled per OUTPUT channel, the data gradient by two scalars
+    assert np.array_equal(accW, ref.conv_bwd_filter_acc(d, qX, qG)[0])
+    assert np.array_equal(accX, ref.conv_bwd_data_acc(d, qG, qW)[0])
+
+
+def test_forward_layer(ref):
+    d = ref.ConvDesc(2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1)
+    rng = np.random.default_rng(13)
+    X = rng.standard_normal(d.x_shape).astype(np.float32)
+    W = (0.1 * rng.standard_normal(d.w_shape)).astype(np.float32)
+    f = ref.conv_fwd_int8(d, X, W)
+    assert f.s_x == np.abs(X).max() and f.s_w == np.abs(W).max()
+    assert np.abs(f.qX).max() == 127 and np.abs(f.qW).max() == 127
+    # the int8 layer approximates the fp32 layer to about a quantization step per operand
+    Yf = torch.nn.functional.conv2d(torch.from_numpy(X), torch.from_numpy(W), padding=1).numpy()
+    rel = np.linalg.norm(f.Y - Yf) / np.linalg.norm(Yf)
+    assert rel < 0.02
+    assert np.array_equal(f.acc, ref.conv_fwd_acc(d, f.qX, f.qW)[0])
+
+
+def test_end_to_end_gradients_approximate_fp32(ref):
+    # Sanity, not a parity pin: the INT8 backward pass tracks the fp32 gradients, and the per-channel
+    # scales of the filter gradient do better than a single global scale on mixed-distribution dY.
+    from paper_2102_04782_amd import workloads as wl
+
+    layer, X, W, dY, st = wl.make_inputs(1)
+    d = ref.ConvDesc(*layer.desc_fields())
+    f = ref.conv_fwd_int8(d, X, W)
+    q = ref.quantize_grad(dY, st)
+    dW, _, _ = ref.conv_bwd_filter_int8(d, f.qX, f.s_x, q.vq, q.s_chan)
+    dWg, _, _ = ref.conv_bwd_filter_int8(d, f.qX, f.s_x, q.qg, np.full(d.Cout, q.s_global, np.float32))
+    dX, _, _ = ref.conv_bwd_data_int8(d, q.qg, q.s_global, f.qW, f.s_w)
+    tX, tW, tG = torch.from_numpy(X).double(), torch.from_numpy(W).double(), torch.from_numpy(dY).double()
+    rdW = torch.nn.grad.conv2d_weight(tX, d.w_shape, tG, padding=1).numpy()
+    rdX = torch.nn.grad.conv2d_input(d.x_shape, tW, tG, padding=1).numpy()
+    # per output channel relative error of dW
+    err = lambda a: np.linalg.norm((a - rdW).reshape(d.Cout, -1), axis=1) / np.linalg.norm(rdW.reshape(d.Cout, -1), axis=1)
+    assert np.median(err(dW)) < 0.1
+    assert np.median(err(dW)) < 0.25 * np.median(err(dWg))
+    assert np.linalg.norm(dX - rdX) / np.linalg.norm(rdX) < 0.2
