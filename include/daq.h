@@ -1,0 +1,230 @@
+/*
+ * daq.h -- C ABI of the INT8 convolution backward path with Distribution
+ * Adaptive gradient quantization (arXiv 2102.04782) for AMD MI355X (gfx950).
+ *
+ * One conv layer's backward pass (the paper's Algorithm 1) is three calls:
+ *
+ *     daq_quantize_grad        statistics, discriminator, clip values, the
+ *                              vectorized (per-channel) and the global int8
+ *                              copies of the output gradient dY
+ *     daq_conv_bwd_filter_int8 q(G_W) = q(X') (x) vq(G'), vectorized de-quantization
+ *     daq_conv_bwd_data_int8   q(G_X) = q(G) (.) q(W),    global de-quantization
+ *
+ * and the forward pass that saves q(X), q(W), s_X, s_W for them is
+ *
+ *     daq_conv_fwd_int8
+ *
+ * Conventions, valid for every entry point:
+ *   - Every data pointer is DEVICE memory owned by the caller.  The library
+ *     allocates nothing, never synchronises the stream and never copies a
+ *     scalar to the host: scales are passed between calls as device pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it in order; the call returns before it completes.
+ *   - `workspace` is caller-provided scratch of at least daq_workspace_bytes()
+ *     bytes, 256-byte aligned, private to the call until the stream reaches
+ *     its end.  Its previous contents do not matter.
+ *   - The return value is the only error channel.  Arguments are validated on
+ *     the host before anything is launched; on an error no output is touched.
+ *   - fp32 tensors are dense NCHW / [Cout][Cin/groups][kH][kW].  int8 tensors
+ *     use the layouts described by daq_layout_* below; bytes of those buffers
+ *     that hold no element are written as zero by the producing call and must
+ *     stay zero.
+ *   - Inputs are assumed finite (no NaN/Inf).
+ */
+#ifndef DAQ_H
+#define DAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Convolution problem, in the notation of the paper's method section:
+ * X in (N, Cin, Hin, Win), W in (Cout, Cin/groups, kH, kW), Y and G = dY in (N, Cout, Hout, Wout). */
+typedef struct {
+    int32_t N, Cin, Hin, Win;
+    int32_t Cout, kH, kW;
+    int32_t strideH, strideW;
+    int32_t padH, padW;
+    int32_t dilH, dilW;
+    int32_t groups;
+} daq_conv_desc;
+
+typedef enum {
+    DAQ_OK = 0,
+    DAQ_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, inconsistent descriptor, bad enum */
+    DAQ_ERR_WORKSPACE = 2,   /* workspace missing, misaligned or smaller than daq_workspace_bytes() */
+    DAQ_ERR_UNSUPPORTED = 3, /* valid problem the library has no kernel for (sizes beyond 2^31 elements) */
+    DAQ_ERR_HIP = 4          /* a HIP call or kernel launch reported an error */
+} daq_status;
+
+/* Rounding of the gradient quantizer (text after Eq. "suq": stochastic rounding for
+ * gradients, nearest for weights and activations).  Nearest is ties-to-even. */
+typedef enum { DAQ_ROUND_NEAREST = 0, DAQ_ROUND_STOCHASTIC = 1 } daq_round;
+
+/* Channel classes of the gradient discriminator, Eq. "judge". */
+enum { DAQ_CLASS_GAUSS = 0, DAQ_CLASS_INVT = 1 };
+
+typedef enum { DAQ_OP_QUANTIZE_GRAD = 0, DAQ_OP_CONV_FWD = 1, DAQ_OP_CONV_BWD_DATA = 2, DAQ_OP_CONV_BWD_FILTER = 3 } daq_op;
+
+/* ---------------------------------------------------------------------------------------------
+ * int8 tensor layouts
+ *
+ * Two families.  Which one a buffer uses, and its parameters, are a pure function of the
+ * convolution descriptor; ask with daq_layout_*().
+ *
+ * DAQ_LAYOUT_NHWC -- channels innermost, the reduction axis of the data-gradient and forward
+ *   products.  Element (n, c, h, w) is byte  ((n*H + h)*W + w) * c_pitch + c ;
+ *   c_pitch = C rounded up to 16, bytes c >= C are zero.
+ *
+ * DAQ_LAYOUT_CNHW -- the paper's dimension transformation X -> X' in (Cin, N, H, W),
+ *   G -> G' in (Cout, N, Hout, Wout): channel outermost, so the reduction axis (n, h, w) of the
+ *   filter-gradient product is contiguous.  Images sit in slots of img_rows x row_pitch bytes that
+ *   are at least as large as the image; the extra bytes are zero and provide the convolution's
+ *   zero padding.  With  hh = h + org_h, ww = w + org_w  element (n, c, h, w) is byte
+ *       c*chan_pitch + ((hh % phases_h)*phases_w + (ww % phases_w)) * plane_pitch + lead
+ *         + (n*img_rows + hh / phases_h) * row_pitch + ww / phases_w .
+ *   phases_* > 1 only for the saved activation of a strided convolution (one plane per stride
+ *   phase, so every filter tap reads one plane at a constant offset).
+ * ------------------------------------------------------------------------------------------- */
+typedef enum { DAQ_LAYOUT_NHWC = 0, DAQ_LAYOUT_CNHW = 1 } daq_layout_kind;
+
+typedef struct {
+    int32_t kind;       /* daq_layout_kind */
+    int32_t C, N, H, W; /* logical extents of the tensor */
+    int64_t bytes;      /* size of the buffer */
+    int32_t c_pitch;    /* NHWC only */
+    int32_t img_rows, row_pitch; /* CNHW only, as are the fields below */
+    int32_t phases_h, phases_w;
+    int32_t org_h, org_w;
+    int64_t chan_pitch, plane_pitch, lead;
+} daq_layout;
+
+/* Layout of the per-channel quantized gradient vq(G') (always CNHW). */
+daq_status daq_layout_vq(const daq_conv_desc* desc, daq_layout* out);
+/* Layout of the globally quantized gradient q(G): NHWC, or CNHW for depthwise layers (groups == Cin == Cout). */
+daq_status daq_layout_qg(const daq_conv_desc* desc, daq_layout* out);
+/* Layout of the saved activation q(X) consumed by the forward and data-gradient side (NHWC). */
+daq_status daq_layout_qx_nhwc(const daq_conv_desc* desc, daq_layout* out);
+/* Layout of the saved, dimension-transformed activation q(X') consumed by the filter gradient (CNHW). */
+daq_status daq_layout_qx_cnhw(const daq_conv_desc* desc, daq_layout* out);
+
+/* Packed int8 filter q(W): three copies in one buffer.
+ *   plain  at off_plain: [Cout][Cin/groups][kH][kW]
+ *   fwd    at off_fwd  : [kH*kW][Cout][cig_pitch]   (input channel of the group innermost)
+ *   bwd    at off_bwd  : [kH*kW][Cin][cog_pitch]    (output channel of the group innermost)
+ * cig_pitch / cog_pitch = Cin/groups, Cout/groups rounded up to 16; padding bytes are zero. */
+typedef struct {
+    int64_t bytes;
+    int64_t off_plain, off_fwd, off_bwd;
+    int32_t cig_pitch, cog_pitch;
+} daq_wpack_layout;
+daq_status daq_layout_qw(const daq_conv_desc* desc, daq_wpack_layout* out);
+
+/* Output spatial size of the convolution; 0 if the descriptor is invalid. */
+int32_t daq_out_h(const daq_conv_desc* desc);
+int32_t daq_out_w(const daq_conv_desc* desc);
+
+/* Scratch bytes an entry point needs for this problem (host function, no GPU call).
+ * Returns 0 for an invalid descriptor or op. */
+size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad -- Algorithm 1, the per-channel loop and the two quantizations.
+ *
+ * For every output channel c of dY (fp32 [N][Cout][Hout][Wout]):
+ *   |g|max_c, sigma_c (population std about the channel mean, fp64 accumulation),
+ *   P_c = #{|g| > sigma_c} / (N*Hout*Wout),
+ *   class_c = GAUSS if P_c > lambda else INVT                         (Eq. "judge"),
+ *   s_c = |g|max_c                                   for GAUSS        (Eq. "gaus"),
+ *   s_c = (1 - k*A) * s_state[c] + A * |g|max_c      for INVT         (Eq. "fats"),
+ *         where a non-positive s_state[c] ("no history") or result is replaced by |g|max_c,
+ *   s_state[c] <- s_c (both classes).
+ * Then  vq = Q(dY, s_c) per channel,  qg = Q(dY, s_global),  s_global = max_c |g|max_c,
+ * Q being Eq. "suq" evaluated in fp32 as round(clamp(x * (127/s), -127, 127)).
+ * A scale below 2^-100 is reported as 0 and produces all-zero codes.
+ * Stochastic rounding draws u in [0,1) from SplitMix64's output function applied to
+ *   seed + 0x9E3779B97F4A7C15*(i+1) + 0xD1B54A32D192ED03*t   (i = NCHW index, t = 0 for vq, 1 for qg),
+ * keeps the top 24 bits, and rounds up iff frac(x*127/s) > u.
+ *
+ *   dY        in   fp32 NCHW
+ *   s_state   i/o  fp32 [Cout]  clip values of the previous iteration, replaced by this iteration's
+ *   vq        out  int8, layout daq_layout_vq
+ *   qg        out  int8, layout daq_layout_qg
+ *   s_chan    out  fp32 [Cout];  s_global out fp32 [1];  cls out u8 [Cout]
+ *   stats     out  optional (may be NULL) fp32 [Cout][4] = |g|max, mean, sigma, P
+ * Hyper-parameters of the paper: k = 1, A = 0.8, lambda = 0.3.
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
+                             float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg, float* s_chan,
+                             float* s_global, uint8_t* cls, float* stats, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_conv_fwd_int8 -- forward pass of the quantized layer (dataflow figure; the inputs that
+ * Algorithm 1 requires).  s_x = max|X|, s_w = max|W| (global quantization, nearest rounding),
+ * Y = (int32 conv of the codes) * (s_x/127) * (s_w/127).
+ *
+ *   X, W        in   fp32
+ *   qx_nhwc     out  int8 daq_layout_qx_nhwc      qx_cnhw out int8 daq_layout_qx_cnhw
+ *   qw_packed   out  int8 daq_layout_qw
+ *   s_x, s_w    out  fp32 [1] each
+ *   Y           out  fp32 NCHW
+ *   acc_out     out  optional (may be NULL) int32 NCHW raw accumulators, for verification
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
+                             int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y, int32_t* acc_out,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_conv_bwd_data_int8 -- Eq. "gx" on int8 codes with int32 accumulation:
+ *   acc[n,ci,h,w] = sum over (co in the group, kh, kw) of qg[n,co,ho,wo] * qW[co,ci,kh,kw]
+ *   with ho*strideH + kh*dilH - padH == h (same for w), ho, wo inside the output;
+ *   dX = acc * ((s_w/127) * (s_global/127)).
+ * Accumulators wrap modulo 2^32 (not reachable below 133144 taps per output).
+ *
+ *   qg        in   int8 daq_layout_qg        s_global in fp32 [1]
+ *   qw_packed in   int8 daq_layout_qw        s_w      in fp32 [1]
+ *   dX        out  fp32 NCHW
+ *   acc_out   out  optional int32 NCHW
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,
+                                  const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_conv_bwd_filter_int8 -- Eq. "gw" on int8 codes with the vectorized de-quantization:
+ *   acc[co,cl,kh,kw] = sum over (n,ho,wo) of qX[n,ci,ho*strideH+kh*dilH-padH, wo*strideW+kw*dilW-padW] * vq[n,co,ho,wo]
+ *   dW[co,...] = acc[co,...] * ((s_x/127) * (s_chan[co]/127)).
+ *
+ *   qx_cnhw   in   int8 daq_layout_qx_cnhw   s_x    in fp32 [1]
+ *   vq        in   int8 daq_layout_vq        s_chan in fp32 [Cout]
+ *   dW        out  fp32 [Cout][Cin/groups][kH][kW]
+ *   acc_out   out  optional int32, same shape
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
+                                    const int8_t* vq, const float* s_chan, float* dW, int32_t* acc_out,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every
+ * kernel the library launches is bracketed by a HIP event pair on its stream.  daq_prof_end()
+ * waits for those events and fills one row per distinct kernel name.  Not thread-safe.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    char name[64];
+    double total_ms;
+    int32_t launches;
+} daq_prof_row;
+daq_status daq_prof_begin(void);
+daq_status daq_prof_end(daq_prof_row* rows, int32_t max_rows, int32_t* n_rows);
+
+/* Human-readable name of a status code (static storage). */
+const char* daq_status_string(daq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DAQ_H */

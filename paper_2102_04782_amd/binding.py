@@ -1,0 +1,321 @@
+"""Thin ctypes binding of ``libdaq.so`` (argument marshalling only).
+
+Every step of the path runs in the library's HIP kernels; PyTorch is used for
+device memory and streams.  The module raises at import time if the library has
+not been built -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdaq.so")
+
+OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(5)
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+CLASS_GAUSS, CLASS_INVT = 0, 1
+OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER = range(4)
+LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
+
+EXPORTS = [
+    "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
+    "daq_conv_bwd_filter_int8", "daq_prof_begin", "daq_prof_end", "daq_status_string",
+]
+
+
+class DaqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {status_string(code)} (code {code})")
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "Cin", "Hin", "Win", "Cout", "kH", "kW", "strideH", "strideW", "padH",
+                                         "padW", "dilH", "dilW", "groups")]
+
+    @classmethod
+    def make(cls, N, Cin, Hin, Win, Cout, kH, kW, strideH=1, strideW=1, padH=0, padW=0, dilH=1, dilW=1, groups=1):
+        return cls(N, Cin, Hin, Win, Cout, kH, kW, strideH, strideW, padH, padW, dilH, dilW, groups)
+
+    @property
+    def Ho(self):
+        return int(lib().daq_out_h(C.byref(self)))
+
+    @property
+    def Wo(self):
+        return int(lib().daq_out_w(C.byref(self)))
+
+    @property
+    def x_shape(self):
+        return (self.N, self.Cin, self.Hin, self.Win)
+
+    @property
+    def w_shape(self):
+        return (self.Cout, self.Cin // self.groups, self.kH, self.kW)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.Cout, self.Ho, self.Wo)
+
+
+class Layout(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("C", C.c_int32), ("N", C.c_int32), ("H", C.c_int32), ("W", C.c_int32),
+                ("bytes", C.c_int64), ("c_pitch", C.c_int32), ("img_rows", C.c_int32), ("row_pitch", C.c_int32),
+                ("phases_h", C.c_int32), ("phases_w", C.c_int32), ("org_h", C.c_int32), ("org_w", C.c_int32),
+                ("chan_pitch", C.c_int64), ("plane_pitch", C.c_int64), ("lead", C.c_int64)]
+
+    def offsets(self) -> np.ndarray:
+        """Byte offset of every logical element, as an int64 array of shape (N, C, H, W)."""
+        n = np.arange(self.N, dtype=np.int64).reshape(-1, 1, 1, 1)
+        c = np.arange(self.C, dtype=np.int64).reshape(1, -1, 1, 1)
+        h = np.arange(self.H, dtype=np.int64).reshape(1, 1, -1, 1)
+        w = np.arange(self.W, dtype=np.int64).reshape(1, 1, 1, -1)
+        if self.kind == LAYOUT_NHWC:
+            return ((n * self.H + h) * self.W + w) * self.c_pitch + c
+        hh, ww = h + self.org_h, w + self.org_w
+        plane = (hh % self.phases_h) * self.phases_w + (ww % self.phases_w)
+        return (c * self.chan_pitch + plane * self.plane_pitch + self.lead
+                + (n * self.img_rows + hh // self.phases_h) * self.row_pitch + ww // self.phases_w)
+
+    def unpack(self, buf) -> np.ndarray:
+        """Device/host int8 buffer in this layout -> logical int8 NCHW numpy array."""
+        flat = buf.detach().cpu().numpy().view(np.int8).ravel() if isinstance(buf, torch.Tensor) else np.asarray(buf).view(np.int8).ravel()
+        return flat[self.offsets()]
+
+    def pack(self, codes: np.ndarray) -> np.ndarray:
+        """Logical int8 NCHW array -> flat int8 buffer in this layout (padding bytes zero)."""
+        codes = np.ascontiguousarray(codes, dtype=np.int8)
+        assert codes.shape == (self.N, self.C, self.H, self.W)
+        out = np.zeros(self.bytes, dtype=np.int8)
+        out[self.offsets()] = codes
+        return out
+
+    def padding_is_zero(self, buf) -> bool:
+        flat = buf.detach().cpu().numpy().view(np.int8).ravel().copy()
+        flat[self.offsets().ravel()] = 0
+        return not flat.any()
+
+
+class WPackLayout(C.Structure):
+    _fields_ = [("bytes", C.c_int64), ("off_plain", C.c_int64), ("off_fwd", C.c_int64), ("off_bwd", C.c_int64),
+                ("cig_pitch", C.c_int32), ("cog_pitch", C.c_int32)]
+
+    def pack(self, d: ConvDesc, qW: np.ndarray) -> np.ndarray:
+        qW = np.ascontiguousarray(qW, dtype=np.int8)
+        Cout, cig, kH, kW = d.w_shape
+        assert qW.shape == (Cout, cig, kH, kW)
+        cog, taps = Cout // d.groups, kH * kW
+        out = np.zeros(self.bytes, dtype=np.int8)
+        out[self.off_plain:self.off_plain + qW.size] = qW.ravel()
+        fwd = np.zeros((taps, Cout, self.cig_pitch), np.int8)
+        fwd[:, :, :cig] = qW.reshape(Cout, cig, taps).transpose(2, 0, 1)
+        out[self.off_fwd:self.off_fwd + fwd.size] = fwd.ravel()
+        bwd = np.zeros((taps, d.Cin, self.cog_pitch), np.int8)
+        for g in range(d.groups):
+            blk = qW[g * cog:(g + 1) * cog].reshape(cog, cig, taps)      # [col][cl][tap]
+            bwd[:, g * cig:(g + 1) * cig, :cog] = blk.transpose(2, 1, 0)  # [tap][cl][col]
+        out[self.off_bwd:self.off_bwd + bwd.size] = bwd.ravel()
+        return out
+
+    def unpack_plain(self, d: ConvDesc, buf) -> np.ndarray:
+        flat = buf.detach().cpu().numpy().view(np.int8).ravel()
+        n = int(np.prod(d.w_shape))
+        return flat[self.off_plain:self.off_plain + n].reshape(d.w_shape)
+
+
+class ProfRow(C.Structure):
+    _fields_ = [("name", C.c_char * 64), ("total_ms", C.c_double), ("launches", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(LIB_PATH)
+        for name in EXPORTS:
+            getattr(L, name)  # AttributeError if a declared symbol is not exported
+        L.daq_out_h.restype = C.c_int32
+        L.daq_out_w.restype = C.c_int32
+        L.daq_workspace_bytes.restype = C.c_size_t
+        L.daq_workspace_bytes.argtypes = [C.c_int, C.POINTER(ConvDesc)]
+        L.daq_status_string.restype = C.c_char_p
+        L.daq_status_string.argtypes = [C.c_int]
+        vp, f32, u64, sz = C.c_void_p, C.c_float, C.c_uint64, C.c_size_t
+        L.daq_quantize_grad.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, vp, vp, vp, vp, vp,
+                                        vp, vp, sz, vp]
+        L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
+        L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
+        L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
+        L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().daq_status_string(code).decode()
+
+
+def _check(code: int, what: str):
+    if code != OK:
+        raise DaqError(code, what)
+
+
+def _layout(fn_name: str, d: ConvDesc) -> Layout:
+    L = Layout()
+    _check(getattr(lib(), fn_name)(C.byref(d), C.byref(L)), fn_name)
+    return L
+
+
+def layout_vq(d): return _layout("daq_layout_vq", d)
+def layout_qg(d): return _layout("daq_layout_qg", d)
+def layout_qx_nhwc(d): return _layout("daq_layout_qx_nhwc", d)
+def layout_qx_cnhw(d): return _layout("daq_layout_qx_cnhw", d)
+
+
+def layout_qw(d: ConvDesc) -> WPackLayout:
+    L = WPackLayout()
+    _check(lib().daq_layout_qw(C.byref(d), C.byref(L)), "daq_layout_qw")
+    return L
+
+
+def workspace_bytes(op: int, d: ConvDesc) -> int:
+    return int(lib().daq_workspace_bytes(op, C.byref(d)))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ws(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------------------------------------
+# the four entry points (same names as the C ABI, without the prefix)
+# ------------------------------------------------------------------------------------------------
+@dataclass
+class QuantGrad:
+    vq: torch.Tensor        # int8, layout_vq
+    qg: torch.Tensor        # int8, layout_qg
+    s_chan: torch.Tensor    # fp32 [Cout]
+    s_global: torch.Tensor  # fp32 [1]
+    cls: torch.Tensor       # u8 [Cout]
+    stats: Optional[torch.Tensor]  # fp32 [Cout,4]
+    workspace: torch.Tensor
+
+
+def alloc_quantize_grad(d: ConvDesc, device="cuda", want_stats=True) -> QuantGrad:
+    i8 = dict(dtype=torch.int8, device=device)
+    return QuantGrad(
+        vq=torch.empty(layout_vq(d).bytes, **i8), qg=torch.empty(layout_qg(d).bytes, **i8),
+        s_chan=torch.empty(d.Cout, dtype=torch.float32, device=device),
+        s_global=torch.empty(1, dtype=torch.float32, device=device),
+        cls=torch.empty(d.Cout, dtype=torch.uint8, device=device),
+        stats=torch.empty((d.Cout, 4), dtype=torch.float32, device=device) if want_stats else None,
+        workspace=_ws(workspace_bytes(OP_QUANTIZE_GRAD, d), device))
+
+
+def quantize_grad(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST,
+                  seed=0, out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
+    """daq_quantize_grad.  ``s_state`` is updated in place."""
+    assert dY.is_cuda and dY.dtype == torch.float32 and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    if out is None:
+        out = alloc_quantize_grad(d, dY.device)
+    rc = lib().daq_quantize_grad(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, _ptr(out.vq), _ptr(out.qg),
+                                 _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
+                                 _ptr(out.workspace), out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_quantize_grad")
+    return out
+
+
+@dataclass
+class Fwd:
+    qx_nhwc: torch.Tensor
+    qx_cnhw: torch.Tensor
+    qw: torch.Tensor
+    s_x: torch.Tensor
+    s_w: torch.Tensor
+    Y: torch.Tensor
+    acc: Optional[torch.Tensor]
+    workspace: torch.Tensor
+
+
+def alloc_fwd(d: ConvDesc, device="cuda", want_acc=False) -> Fwd:
+    i8 = dict(dtype=torch.int8, device=device)
+    f32 = dict(dtype=torch.float32, device=device)
+    return Fwd(qx_nhwc=torch.empty(layout_qx_nhwc(d).bytes, **i8), qx_cnhw=torch.empty(layout_qx_cnhw(d).bytes, **i8),
+               qw=torch.empty(layout_qw(d).bytes, **i8), s_x=torch.empty(1, **f32), s_w=torch.empty(1, **f32),
+               Y=torch.empty(d.y_shape, **f32),
+               acc=torch.empty(d.y_shape, dtype=torch.int32, device=device) if want_acc else None,
+               workspace=_ws(workspace_bytes(OP_CONV_FWD, d), device))
+
+
+def conv_fwd_int8(d: ConvDesc, X: torch.Tensor, W: torch.Tensor, out: Optional[Fwd] = None, want_acc=False,
+                  stream=None) -> Fwd:
+    assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and tuple(X.shape) == d.x_shape
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == d.w_shape
+    if out is None:
+        out = alloc_fwd(d, X.device, want_acc)
+    rc = lib().daq_conv_fwd_int8(C.byref(d), _ptr(X), _ptr(W), _ptr(out.qx_nhwc), _ptr(out.qx_cnhw), _ptr(out.qw),
+                                 _ptr(out.s_x), _ptr(out.s_w), _ptr(out.Y), _ptr(out.acc), _ptr(out.workspace),
+                                 out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_fwd_int8")
+    return out
+
+
+def conv_bwd_data_int8(d: ConvDesc, qg: torch.Tensor, s_global: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,
+                       dX: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if dX is None:
+        dX = torch.empty(d.x_shape, dtype=torch.float32, device=qg.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD_DATA, d), qg.device)
+    rc = lib().daq_conv_bwd_data_int8(C.byref(d), _ptr(qg), _ptr(s_global), _ptr(qw), _ptr(s_w), _ptr(dX), _ptr(acc),
+                                      _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_data_int8")
+    return dX
+
+
+def conv_bwd_filter_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, vq: torch.Tensor,
+                         s_chan: torch.Tensor, dW: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if dW is None:
+        dW = torch.empty(d.w_shape, dtype=torch.float32, device=vq.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD_FILTER, d), vq.device)
+    rc = lib().daq_conv_bwd_filter_int8(C.byref(d), _ptr(qx_cnhw), _ptr(s_x), _ptr(vq), _ptr(s_chan), _ptr(dW),
+                                        _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_filter_int8")
+    return dW
+
+
+# ------------------------------------------------------------------------------------------------
+# measurement aid
+# ------------------------------------------------------------------------------------------------
+def prof_begin():
+    _check(lib().daq_prof_begin(), "daq_prof_begin")
+
+
+def prof_end(max_rows: int = 64):
+    rows = (ProfRow * max_rows)()
+    n = C.c_int32(0)
+    _check(lib().daq_prof_end(rows, max_rows, C.byref(n)), "daq_prof_end")
+    return {rows[i].name.decode(): (rows[i].total_ms, rows[i].launches) for i in range(n.value)}

@@ -1,0 +1,50 @@
+// Entry points of the three convolutions: argument validation and kernel selection.
+#include "daq_internal.h"
+
+using namespace daq;
+
+namespace {
+bool ws_ok(const void* ws, size_t have, size_t need) { return ws && have >= need && ((uintptr_t)ws & 255u) == 0; }
+}  // namespace
+
+extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
+                                        int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y,
+                                        int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !X || !W || !qx_nhwc || !qx_cnhw || !qw_packed || !s_x || !s_w || !Y)
+        return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_FWD, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    daq_status rc = quantize_activation(*desc, X, qx_nhwc, qx_cnhw, s_x, workspace, st);
+    if (rc != DAQ_OK) return rc;
+    rc = quantize_filter(*desc, W, qw_packed, s_w, workspace, st);
+    if (rc != DAQ_OK) return rc;
+    if (fwd_mfma_supported(*desc)) return conv_fwd_mfma(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
+    return conv_fwd_generic(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
+}
+
+extern "C" daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,
+                                             const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
+                                             void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !qg || !s_global || !qw_packed || !s_w || !dX) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (bwd_data_mfma_supported(*desc)) return conv_bwd_data_mfma(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
+    return conv_bwd_data_generic(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
+}
+
+extern "C" daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
+                                               const int8_t* vq, const float* s_chan, float* dW, int32_t* acc_out,
+                                               void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !qx_cnhw || !s_x || !vq || !s_chan || !dW) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_FILTER, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    if (bwd_filter_mfma_supported(*desc))
+        return conv_bwd_filter_mfma(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
+    return conv_bwd_filter_generic(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, st);
+}

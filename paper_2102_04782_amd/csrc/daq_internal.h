@@ -1,0 +1,93 @@
+// Internal declarations shared by the translation units of libdaq.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "daq.h"
+
+namespace daq {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kXcd = 8;              // accelerator complex dies; workgroup i is dispatched to XCD i % 8
+constexpr float kTinyScale = 7.888609052210118e-31f;  // 2^-100: below this a scale is reported as 0
+constexpr int kKAlign = 256;         // the flattened (n,h,w) axis of a CNHW buffer is padded to this many bytes
+
+inline int64_t round_up(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+bool desc_valid(const daq_conv_desc* d);
+inline bool is_depthwise(const daq_conv_desc& d) { return d.groups > 1 && d.groups == d.Cin && d.groups == d.Cout; }
+
+// ---- profiling hooks (prof.hip) ------------------------------------------------------------
+bool prof_active();
+void prof_push(const char* name, hipStream_t s);  // records the start event
+void prof_pop(hipStream_t s);                     // records the stop event
+
+// Launch helper: brackets the launch with profiling events when enabled and maps launch errors.
+#define DAQ_LAUNCH(name, stream, ...)                          \
+    do {                                                       \
+        if (::daq::prof_active()) ::daq::prof_push(name, stream); \
+        __VA_ARGS__;                                           \
+        if (::daq::prof_active()) ::daq::prof_pop(stream);     \
+        if (hipGetLastError() != hipSuccess) return DAQ_ERR_HIP; \
+    } while (0)
+
+// ---- device-side view of an int8 layout ----------------------------------------------------
+struct CnhwView {
+    int64_t chan_pitch, plane_pitch, lead;
+    int32_t img_rows, row_pitch;
+    int32_t phases_h, phases_w, org_h, org_w;
+    int32_t C, N, H, W;
+    __host__ __device__ int64_t offset(int n, int c, int h, int w) const {
+        const int hh = h + org_h, ww = w + org_w;
+        const int ph = hh % phases_h, pw = ww % phases_w;
+        return (int64_t)c * chan_pitch + (int64_t)(ph * phases_w + pw) * plane_pitch + lead +
+               ((int64_t)n * img_rows + hh / phases_h) * row_pitch + ww / phases_w;
+    }
+};
+
+struct NhwcView {
+    int32_t c_pitch, C, N, H, W;
+    __host__ __device__ int64_t offset(int n, int c, int h, int w) const {
+        return (((int64_t)n * H + h) * W + w) * c_pitch + c;
+    }
+};
+
+inline CnhwView cnhw_view(const daq_layout& L) {
+    return CnhwView{L.chan_pitch, L.plane_pitch, L.lead, L.img_rows, L.row_pitch, L.phases_h, L.phases_w,
+                    L.org_h, L.org_w, L.C, L.N, L.H, L.W};
+}
+inline NhwcView nhwc_view(const daq_layout& L) { return NhwcView{L.c_pitch, L.C, L.N, L.H, L.W}; }
+
+// ---- kernels behind the entry points (one translation unit each) -----------------------------
+// quantize.hip
+size_t quantize_grad_ws_bytes(const daq_conv_desc& d);
+size_t fwd_quant_ws_bytes(const daq_conv_desc& d);
+daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* qx_nhwc, int8_t* qx_cnhw, float* s_x,
+                               void* ws, hipStream_t st);
+daq_status quantize_filter(const daq_conv_desc& d, const float* W, int8_t* qw_packed, float* s_w, void* ws,
+                           hipStream_t st);
+
+// conv_generic.hip: direct kernels, any descriptor
+daq_status conv_fwd_generic(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
+                            const float* s_w, float* Y, int32_t* acc, hipStream_t st);
+daq_status conv_bwd_data_generic(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
+                                 const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+daq_status conv_bwd_filter_generic(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
+                                   const float* s_chan, float* dW, int32_t* acc, hipStream_t st);
+
+// conv_mfma_*.hip: int8 MFMA kernels; *_supported() says whether a descriptor is covered
+bool bwd_filter_mfma_supported(const daq_conv_desc& d);
+size_t bwd_filter_mfma_ws_bytes(const daq_conv_desc& d);
+daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
+                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st);
+bool bwd_data_mfma_supported(const daq_conv_desc& d);
+daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+bool fwd_mfma_supported(const daq_conv_desc& d);
+daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
+                         const float* s_w, float* Y, int32_t* acc, hipStream_t st);
+
+}  // namespace daq

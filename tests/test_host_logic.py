@@ -1,0 +1,146 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host
+logic (layouts, workspace sizes, argument validation) behaves.  No kernel is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2102_04782_amd import binding as daq
+from paper_2102_04782_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "daq.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(daq_[a-z0-9_]+)\s*\(", hdr))
+    assert {"daq_quantize_grad", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8", "daq_conv_bwd_filter_int8"} <= declared
+    L = C.CDLL(daq.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} declared in daq.h but not exported"
+    assert declared == set(daq.EXPORTS)
+
+
+CASES = [
+    dict(N=2, Cin=3, Hin=9, Win=7, Cout=5, kH=3, kW=3, strideH=1, strideW=1, padH=1, padW=1),
+    dict(N=2, Cin=4, Hin=9, Win=8, Cout=6, kH=3, kW=3, strideH=2, strideW=2, padH=1, padW=1),
+    dict(N=1, Cin=3, Hin=15, Win=15, Cout=4, kH=7, kW=7, strideH=2, strideW=2, padH=3, padW=3),
+    dict(N=3, Cin=8, Hin=5, Win=5, Cout=8, kH=1, kW=1),
+    dict(N=2, Cin=8, Hin=6, Win=6, Cout=16, kH=1, kW=1, strideH=2, strideW=2),
+    dict(N=2, Cin=6, Hin=7, Win=7, Cout=6, kH=3, kW=3, padH=1, padW=1, groups=6),
+    dict(N=1, Cin=2, Hin=8, Win=8, Cout=2, kH=3, kW=3, padH=2, padW=2, dilH=2, dilW=2),
+    dict(N=1, Cin=2, Hin=6, Win=5, Cout=3, kH=3, kW=3, padH=3, padW=3),
+]
+
+
+@pytest.mark.parametrize("kw", CASES)
+def test_layouts_are_injective_in_bounds_and_tap_shifts_are_constant(kw):
+    d = daq.ConvDesc.make(**kw)
+    Ho, Wo = d.Ho, d.Wo
+    layouts = [daq.layout_vq(d), daq.layout_qg(d), daq.layout_qx_nhwc(d), daq.layout_qx_cnhw(d)]
+    for L in layouts:
+        off = L.offsets().ravel()
+        assert off.min() >= 0 and off.max() < L.bytes
+        assert len(np.unique(off)) == off.size
+        rng = np.random.default_rng(0)
+        codes = rng.integers(-127, 128, (L.N, L.C, L.H, L.W)).astype(np.int8)
+        assert np.array_equal(L.unpack(L.pack(codes)), codes)
+    # the property the filter-gradient kernel relies on: for a fixed tap, the activation element that
+    # multiplies gradient element f sits at f + const in the activation's plane, or is zero padding
+    Lg, Lx = daq.layout_vq(d), daq.layout_qx_cnhw(d)
+    assert (Lg.img_rows, Lg.row_pitch) == (Lx.img_rows, Lx.row_pitch) and Lg.lead == 0
+    rng = np.random.default_rng(1)
+    X = rng.integers(1, 128, (d.N, d.Cin, d.Hin, d.Win)).astype(np.int8)  # strictly positive: zero means padding
+    buf = Lx.pack(X)
+    for kh in range(d.kH):
+        for kw_ in range(d.kW):
+            hh, ww = kh * d.dilH, kw_ * d.dilW
+            if d.strideH == 1 and d.strideW == 1:
+                plane, delta = 0, Lx.lead - Lx.lead + hh * Lx.row_pitch + ww  # lead already holds the padding shift
+                base = 0
+            else:
+                plane = (hh % d.strideH) * d.strideW + (ww % d.strideW)
+                delta = (hh // d.strideH) * Lx.row_pitch + ww // d.strideW
+                base = 0
+            for n in range(d.N):
+                for ho in range(Ho):
+                    for wo in range(Wo):
+                        f = (n * Lg.img_rows + ho) * Lg.row_pitch + wo
+                        h = ho * d.strideH + hh - d.padH
+                        w = wo * d.strideW + ww - d.padW
+                        inside = 0 <= h < d.Hin and 0 <= w < d.Win
+                        got = buf[0 * Lx.chan_pitch + plane * Lx.plane_pitch + base + f + delta]
+                        assert got == (X[n, 0, h, w] if inside else 0)
+    # reading 16 bytes past any gradient position plus the largest tap shift stays inside the plane
+    max_delta = ((d.kH - 1) * d.dilH // d.strideH) * Lx.row_pitch + (d.kW - 1) * d.dilW // d.strideW
+    assert Lg.plane_pitch % 256 == 0 and Lg.plane_pitch + max_delta + 16 <= Lx.plane_pitch
+
+
+def test_weight_packing_roundtrip():
+    for kw in CASES:
+        d = daq.ConvDesc.make(**kw)
+        L = daq.layout_qw(d)
+        rng = np.random.default_rng(2)
+        qW = rng.integers(-127, 128, d.w_shape).astype(np.int8)
+        buf = L.pack(d, qW)
+        cig, cog, taps = d.Cin // d.groups, d.Cout // d.groups, d.kH * d.kW
+        fwd = buf[L.off_fwd:L.off_fwd + taps * d.Cout * L.cig_pitch].reshape(taps, d.Cout, L.cig_pitch)
+        bwd = buf[L.off_bwd:L.off_bwd + taps * d.Cin * L.cog_pitch].reshape(taps, d.Cin, L.cog_pitch)
+        for co in range(d.Cout):
+            g = co // cog
+            for cl in range(cig):
+                for t in range(taps):
+                    v = qW[co, cl, t // d.kW, t % d.kW]
+                    assert fwd[t, co, cl] == v and bwd[t, g * cig + cl, co % cog] == v
+
+
+def test_workspace_and_validation_without_a_gpu():
+    d = daq.ConvDesc.make(N=2, Cin=4, Hin=8, Win=8, Cout=4, kH=3, kW=3, padH=1, padW=1)
+    for op in range(4):
+        assert daq.workspace_bytes(op, d) >= 256
+    assert daq.workspace_bytes(7, d) == 0
+    bad = daq.ConvDesc.make(N=0, Cin=4, Hin=8, Win=8, Cout=4, kH=3, kW=3)
+    assert daq.workspace_bytes(0, bad) == 0
+    L = daq.Layout()
+    assert daq.lib().daq_layout_vq(C.byref(bad), C.byref(L)) == daq.ERR_INVALID_ARG
+    for kw in (dict(Cin=5, groups=2), dict(kH=9), dict(strideH=0), dict(padH=-1), dict(dilW=0)):
+        base = dict(N=1, Cin=4, Hin=8, Win=8, Cout=4, kH=3, kW=3)
+        base.update(kw)
+        assert daq.workspace_bytes(0, daq.ConvDesc.make(**base)) == 0
+    # null pointers / bad enums / short workspace are rejected on the host, before any launch
+    lib = daq.lib()
+    one = C.c_void_p(256)  # never dereferenced: validation fails first
+    assert lib.daq_quantize_grad(C.byref(d), None, one, 1.0, 0.8, 0.3, 0, 0, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_quantize_grad(C.byref(d), one, one, 1.0, 0.8, 0.3, 5, 0, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_quantize_grad(C.byref(d), one, one, 1.0, 0.8, 0.3, 0, 0, one, one, one, one, one, None, one, 8, None) == daq.ERR_WORKSPACE
+    assert lib.daq_quantize_grad(C.byref(d), one, one, 1.0, 0.8, 0.3, 0, 0, one, one, one, one, one, None, C.c_void_p(257), 1 << 20, None) == daq.ERR_WORKSPACE
+    assert lib.daq_quantize_grad(C.byref(bad), one, one, 1.0, 0.8, 0.3, 0, 0, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_conv_bwd_data_int8(C.byref(d), None, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, None, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, one, None, None, 0, None) == daq.ERR_WORKSPACE
+    assert lib.daq_conv_fwd_int8(C.byref(d), one, None, one, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert daq.status_string(daq.ERR_WORKSPACE).startswith("workspace")
+
+
+def test_workload_tables():
+    r50 = wl.config4()
+    assert len(r50) == 53 and len({(l.Cin, l.Hin, l.Cout, l.kH, l.stride) for l in r50}) == 23
+    total = sum(l.macs for l in r50)
+    assert abs(total - 261.6e9) / 261.6e9 < 0.01          # 2 x 261.6 GMAC x 2 convs = 1046 GOP backward
+    assert sum(int(np.prod(l.y_shape)) for l in r50) == 711_262_208 or abs(sum(int(np.prod(l.y_shape)) for l in r50) - 711.3e6) < 1e6
+    mb = wl.config5()
+    assert len(mb) == 50 and sum(1 for l in mb if l.groups > 1) == 17
+    assert abs(sum(int(np.prod(l.y_shape)) for l in mb) - 795.4e6) < 1e6
+    l2 = wl.config2()[0]
+    assert l2.y_shape == (32, 64, 56, 56) and 2 * l2.macs == 7_398_752_256 or abs(2 * l2.macs - 7.40e9) < 1e7
+    # generators are seeded and follow the recipe: even channels bell-shaped, odd channels long-tailed
+    layer, X, W, dY, st = wl.make_inputs(1)
+    _, _, _, dY2, _ = wl.make_inputs(1)
+    assert np.array_equal(dY, dY2) and dY.dtype == np.float32
+    kurt = lambda v: np.mean((v - v.mean()) ** 4) / np.var(v) ** 2
+    assert all(kurt(dY[:, c].ravel()) < 4 for c in range(0, 16, 2))
+    assert all(kurt(dY[:, c].ravel()) > 20 for c in range(1, 16, 2))
+    assert np.all(st > 0)
