@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the INT8 conv backward hot path on one MI355X.
+
+One step = Algorithm 1 for one layer: daq_quantize_grad (statistics, discriminator, clip values,
+per-channel and global int8 copies of dY) + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8.
+Inputs (fp32 dY, the saved int8 activation/filter of the forward pass, the clip state) are resident
+in HBM before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--rotate R]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
+PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
+# kernel of known size; keyed by (workload, kernel).  See profiles/ for the runs these come from.
+MEASURED_TRAFFIC = {}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--rotate", type=int, default=1, help="number of dY buffer sets cycled through (cold-cache runs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2102_04782_amd import binding as daq
+    from paper_2102_04782_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    daq.lib()  # fail loudly if the HIP library is missing
+
+    layer, X, W, dY, st = wl.make_inputs(args.config, args.layer)
+    d = daq.ConvDesc.make(*layer.desc_fields())
+    X_d, W_d = torch.from_numpy(X).to(dev), torch.from_numpy(W).to(dev)
+    fwd = daq.conv_fwd_int8(d, X_d, W_d)            # produces the saved q(X), q(W), s_X, s_W
+    del X_d
+    R = max(1, args.rotate)
+    dYs = [torch.from_numpy(dY).to(dev)] + [torch.from_numpy(dY).to(dev).clone() for _ in range(R - 1)]
+    states = [torch.from_numpy(st.copy()).to(dev) for _ in range(R)]
+    outs = [daq.alloc_quantize_grad(d, dev, want_stats=False) for _ in range(R)]
+    dWs = [torch.empty(d.w_shape, dtype=torch.float32, device=dev) for _ in range(R)]
+    dXs = [torch.empty(d.x_shape, dtype=torch.float32, device=dev) for _ in range(R)]
+    ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
+    ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i: int):
+        r = i % R
+        q = daq.quantize_grad(d, dYs[r], states[r], out=outs[r], stream=stream)
+        daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=stream)
+        daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1e3 * wall / args.steps
+
+    # per-kernel durations: the same K steps with a HIP event pair around every launch
+    daq.prof_begin()
+    for i in range(args.steps):
+        step(i)
+    rows = daq.prof_end()
+    torch.cuda.synchronize()
+
+    E_Y = int(np.prod(d.y_shape))
+    E_X = int(np.prod(d.x_shape))
+    E_W = int(np.prod(d.w_shape))
+    Lv = daq.layout_vq(d)
+    ops_per_conv = 2.0 * layer.macs
+    ops_per_step = 2.0 * ops_per_conv          # dX + dW
+    # algorithmic bytes / ops of one launch of each kernel
+    alg_bytes = {
+        "stats": 4.0 * E_Y,
+        "count_qg": 5.0 * E_Y if daq.layout_qg(d).kind == daq.LAYOUT_NHWC else 4.0 * E_Y,
+        "pack_vq": 4.0 * E_Y + Lv.bytes,
+        "pack_qg": 4.0 * E_Y + Lv.bytes,
+    }
+    kernels = {}
+    for name, (total_ms, launches) in rows.items():
+        avg_us = 1e3 * total_ms / max(launches, 1)
+        per_step = launches / args.steps
+        entry = {"avg_us": round(avg_us, 3), "launches_per_step": per_step}
+        if name in alg_bytes:
+            entry["GBps"] = round(alg_bytes[name] / (avg_us * 1e-6) / 1e9, 1)
+        if name.startswith("conv_bwd"):
+            entry["TOPs"] = round(ops_per_conv / (avg_us * 1e-6) / 1e12, 2)
+        kernels[name] = entry
+    dom = max(rows.items(), key=lambda kv: kv[1][0])[0] if rows else None
+    roofline = None
+    if dom is not None:
+        avg_s = 1e-3 * rows[dom][0] / max(rows[dom][1], 1)
+        if dom in alg_bytes:
+            ach = alg_bytes[dom] / avg_s / 1e9
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(ach / PEAK_HBM_GBS, 4)}
+        else:
+            # the convolutions run as split launches (zero / gemm / epilogue); price the dominant one on its conv's ops
+            ach = ops_per_conv / avg_s / 1e12
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_INT8_TOPS,
+                        "unit": "TOP/s", "frac": round(ach / PEAK_INT8_TOPS, 4)}
+        roofline["traffic"] = MEASURED_TRAFFIC.get((f"config{args.config}", dom))
+        roofline["avg_us"] = round(1e6 * avg_s, 3)
+
+    value = ops_per_step / (ms_per_step * 1e-3) / 1e12
+    quant_us = sum(v["avg_us"] * v["launches_per_step"] for k, v in kernels.items()
+                   if k in ("fill", "stats", "count_qg", "pack_vq", "pack_qg"))
+    result = {
+        "metric": "INT8 conv-backward TOPS incl. grad quantization",
+        "value": round(value, 3),
+        "unit": "TOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{layer.name} N={layer.N} {layer.Cin}->{layer.Cout} "
+                               f"{layer.Hin}x{layer.Win} k{layer.kH} s{layer.stride} p{layer.pad}",
+                   "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3},
+        "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
+        "quant_GBps_effective_6B": round(6.0 * E_Y / (quant_us * 1e-6) / 1e9, 1) if quant_us else None,
+        "quant_us": round(quant_us, 2),
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import daq_ref as ref
+
+        rd = ref.ConvDesc(*layer.desc_fields())
+        qX = daq.layout_qx_cnhw(d).unpack(fwd.qx_cnhw)
+        qW = daq.layout_qw(d).unpack_plain(d, fwd.qw)
+        s_x, s_w = float(fwd.s_x.item()), float(fwd.s_w.item())
+        # bounded sample: shrink the batch until the oracle needs roughly <= 30 s
+        n_s = layer.N
+        while n_s > 1 and 2.0 * layer.macs * n_s / layer.N > 60e9:
+            n_s //= 2
+        sub = wl.shrink(layer, n_s)
+        rds = ref.ConvDesc(*sub.desc_fields())
+        t0 = time.perf_counter()
+        rq = ref.quantize_grad(dY[:n_s], st, want_fragile=False)
+        ref.conv_bwd_filter_int8(rds, qX[:n_s], s_x, rq.vq, rq.s_chan)
+        ref.conv_bwd_data_int8(rds, rq.qg, rq.s_global, qW, s_w)
+        cpu_s = time.perf_counter() - t0
+        result["cpu_baseline"] = {
+            "value": round(2.0 * 2.0 * sub.macs / cpu_s / 1e12, 6), "unit": "TOP/s", "cores": ref.num_threads(),
+            "kind": "oracle", "sample": f"same layer, first {n_s} of {layer.N} images, one pass ({cpu_s:.2f} s)"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -14,45 +14,43 @@ namespace daq {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kMaxChunks = 64;
+constexpr int kStatsElems = 4096;  // elements swept by one statistics workgroup (16 per thread, all loads in flight)
 
 // ---------------------------------------------------------------------------------------------
 // workspace carving
 // ---------------------------------------------------------------------------------------------
 struct QuantWs {
-    uint32_t* count;       // [C]   #{|g| > sigma}
-    uint32_t* done_stats;  // [C]   chunks finished in the statistics pass
-    uint32_t* done_count;  // [CB]  workgroups finished in the count pass, per 64-channel block
-    uint32_t* gmax_bits;   // [1]   bit pattern of max_c |g|max (non-negative floats order like uints)
-    int64_t zero_bytes;    // size of the region above (starts at `count`)
-    float* gmax;           // [C]
-    float* mean;           // [C]
-    float* sigma;          // [C]
-    float* part_max;       // [C][chunks]
-    double* part_s1;       // [C][chunks]
-    double* part_s2;       // [C][chunks]
+    uint32_t* gmax_bits;  // [1]   bit pattern of max_c |g|max (non-negative floats order like uints)
+    float* gmax;          // [C]
+    float* mean;          // [C]
+    float* sigma;         // [C]
+    float* part_max;      // [C][chunks]
+    double* part_s1;      // [C][chunks]
+    double* part_s2;      // [C][chunks]
+    uint32_t* part_cnt;   // [C][slots]  #{|g| > sigma} per (image, 64-pixel tile)
+    int chunks, slots;
     int64_t total_bytes;
 };
 
-QuantWs carve_quant_ws(void* base, int C) {
+QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     QuantWs w{};
     char* p = (char*)base;
-    const int CB = (int)ceil_div(C, 64);
-    w.count = (uint32_t*)p;
-    w.done_stats = w.count + C;
-    w.done_count = w.done_stats + C;
-    w.gmax_bits = w.done_count + CB;
-    w.zero_bytes = round_up((int64_t)(2 * C + CB + 1) * 4, 256);
-    p += w.zero_bytes;
+    const int64_t M = (int64_t)N * HW;
+    w.chunks = (int)ceil_div(M, kStatsElems);
+    w.slots = N * (int)ceil_div(HW, kWave);
+    w.gmax_bits = (uint32_t*)p;
+    p += 256;
     w.gmax = (float*)p;
     w.mean = w.gmax + C;
     w.sigma = w.mean + C;
     p += round_up((int64_t)3 * C * 4, 256);
     w.part_s1 = (double*)p;
-    w.part_s2 = w.part_s1 + (int64_t)C * kMaxChunks;
-    p += round_up((int64_t)2 * C * kMaxChunks * 8, 256);
+    w.part_s2 = w.part_s1 + (int64_t)C * w.chunks;
+    p += round_up((int64_t)2 * C * w.chunks * 8, 256);
     w.part_max = (float*)p;
-    p += round_up((int64_t)C * kMaxChunks * 4, 256);
+    p += round_up((int64_t)C * w.chunks * 4, 256);
+    w.part_cnt = (uint32_t*)p;
+    p += round_up((int64_t)C * w.slots * 4, 256);
     w.total_bytes = p - (char*)base;
     return w;
 }
@@ -99,97 +97,129 @@ __device__ __forceinline__ double wave_sum(double v) {
     for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
     return v;
 }
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    return v;
+}
 
 __global__ void k_fill_u32(uint32_t* p, int64_t n, uint32_t v) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
 }
 
+// Fixed-shape workgroup reduction of (max, sum, sum); the result is valid in thread 0.
+__device__ __forceinline__ void block_reduce(float& mx, double& s1, double& s2) {
+    __shared__ float l_mx[kBlock / kWave];
+    __shared__ double l_s1[kBlock / kWave], l_s2[kBlock / kWave];
+    mx = wave_max(mx);
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    if (lane == 0) { l_mx[wave] = mx; l_s1[wave] = s1; l_s2[wave] = s2; }
+    __syncthreads();
+    if (threadIdx.x == 0)
+        for (int w = 1; w < kBlock / kWave; ++w) { mx = fmaxf(mx, l_mx[w]); s1 += l_s1[w]; s2 += l_s2[w]; }
+}
+
 // ---------------------------------------------------------------------------------------------
-// S1: per-channel |g|max, sum, sum of squares.  Workgroup (c, j) sweeps chunk j of channel c's
-// flattened (n, h*w) axis; the last chunk of a channel to finish reduces the partials in chunk
-// order and writes |g|max, mean, sigma.  Channel c runs on XCD c % 8.
+// S1: per-channel |g|max, sum, sum of squares.  Workgroup (c, j) sweeps elements
+// [j*4096, (j+1)*4096) of channel c's flattened (n, h*w) axis with every load issued up front,
+// and stores one partial.  k_stats_final reduces a channel's partials with a fixed tree.
+// Channel c runs on XCD c % 8 in every pass over dY.
 // ---------------------------------------------------------------------------------------------
 template <bool VEC4>
-__global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, int chunks,
-                                                  int chunk_len, QuantWs ws) {
+__global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, QuantWs ws) {
     const int b = blockIdx.x;
     const int xcd = b % kXcd, q = b / kXcd;
-    const int c = (q / chunks) * kXcd + xcd;
-    const int j = q % chunks;
+    const int c = (q / ws.chunks) * kXcd + xcd;
+    const int j = q % ws.chunks;
+    if (b == 0 && threadIdx.x == 0) *ws.gmax_bits = 0u;  // consumed by k_stats_final, a later launch
     if (c >= C) return;
     const int M = N * HW;
-    const int m0 = j * chunk_len;
-    const int m1 = min(M, m0 + chunk_len);
+    const int m0 = j * kStatsElems;
     const int tid = threadIdx.x;
 
     float mx = 0.0f;
     double s1 = 0.0, s2 = 0.0;
     if (VEC4) {
-        for (int m = m0 + 4 * tid; m < m1; m += 4 * kBlock) {
-            const int n = m / HW, i = m - n * HW;
-            const float4 v = *reinterpret_cast<const float4*>(g + ((int64_t)n * C + c) * HW + i);
-            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-            const double a = v.x, bq = v.y, cq = v.z, d = v.w;
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int m = m0 + 4 * (tid + u * kBlock);
+            if (m < M) {
+                const int n = m / HW, i = m - n * HW;
+                v[u] = *reinterpret_cast<const float4*>(g + ((int64_t)n * C + c) * HW + i);
+            } else {
+                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
+            const double a = v[u].x, bq = v[u].y, cq = v[u].z, d = v[u].w;
             s1 += a; s1 += bq; s1 += cq; s1 += d;
             s2 += a * a; s2 += bq * bq; s2 += cq * cq; s2 += d * d;
         }
     } else {
-        for (int m = m0 + tid; m < m1; m += kBlock) {
-            const int n = m / HW, i = m - n * HW;
-            const float v = g[((int64_t)n * C + c) * HW + i];
-            mx = fmaxf(mx, fabsf(v));
-            const double a = v;
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int m = m0 + tid + u * kBlock;
+            if (m < M) {
+                const int n = m / HW, i = m - n * HW;
+                v[u] = g[((int64_t)n * C + c) * HW + i];
+            } else {
+                v[u] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            mx = fmaxf(mx, fabsf(v[u]));
+            const double a = v[u];
             s1 += a;
             s2 += a * a;
         }
     }
-    mx = wave_max(mx);
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
-    __shared__ float l_mx[kBlock / kWave];
-    __shared__ double l_s1[kBlock / kWave], l_s2[kBlock / kWave];
-    __shared__ int l_last;
-    const int wave = tid / kWave, lane = tid % kWave;
-    if (lane == 0) { l_mx[wave] = mx; l_s1[wave] = s1; l_s2[wave] = s2; }
-    __syncthreads();
+    block_reduce(mx, s1, s2);
     if (tid == 0) {
-        for (int w = 1; w < kBlock / kWave; ++w) { mx = fmaxf(mx, l_mx[w]); s1 += l_s1[w]; s2 += l_s2[w]; }
-        const int64_t slot = (int64_t)c * kMaxChunks + j;
+        const int64_t slot = (int64_t)c * ws.chunks + j;
         ws.part_max[slot] = mx;
         ws.part_s1[slot] = s1;
         ws.part_s2[slot] = s2;
-        __threadfence();
-        const uint32_t old = atomicAdd(&ws.done_stats[c], 1u);
-        l_last = (old == (uint32_t)chunks - 1u);
-        if (l_last) {
-            __threadfence();
-            const volatile float* pm = ws.part_max + (int64_t)c * kMaxChunks;
-            const volatile double* p1 = ws.part_s1 + (int64_t)c * kMaxChunks;
-            const volatile double* p2 = ws.part_s2 + (int64_t)c * kMaxChunks;
-            float gm = 0.0f;
-            double t1 = 0.0, t2 = 0.0;
-            for (int jj = 0; jj < chunks; ++jj) { gm = fmaxf(gm, pm[jj]); t1 += p1[jj]; t2 += p2[jj]; }
-            const double Md = (double)M;
-            const double mu = t1 / Md;
-            double var = t2 / Md - mu * mu;
-            if (var < 0.0) var = 0.0;
-            ws.gmax[c] = gm;
-            ws.mean[c] = (float)mu;
-            ws.sigma[c] = (float)sqrt(var);
-            atomicMax(ws.gmax_bits, __float_as_uint(gm));
-        }
+    }
+}
+
+// One workgroup per channel: partials -> |g|max, mean, sigma (population std, fp64, rounded once).
+__global__ __launch_bounds__(kBlock) void k_stats_final(int N, int C, int HW, QuantWs ws) {
+    const int c = blockIdx.x;
+    float mx = 0.0f;
+    double s1 = 0.0, s2 = 0.0;
+    for (int j = threadIdx.x; j < ws.chunks; j += kBlock) {
+        const int64_t slot = (int64_t)c * ws.chunks + j;
+        mx = fmaxf(mx, ws.part_max[slot]);
+        s1 += ws.part_s1[slot];
+        s2 += ws.part_s2[slot];
+    }
+    block_reduce(mx, s1, s2);
+    if (threadIdx.x == 0) {
+        const double Md = (double)N * (double)HW;
+        const double mu = s1 / Md;
+        double var = s2 / Md - mu * mu;
+        if (var < 0.0) var = 0.0;
+        ws.gmax[c] = mx;
+        ws.mean[c] = (float)mu;
+        ws.sigma[c] = (float)sqrt(var);
+        atomicMax(ws.gmax_bits, __float_as_uint(mx));
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// S2 (+S3, S4, and the global copy of S5): tail-mass count per channel, optionally fused with the
-// globally quantized NHWC copy, followed -- in the last workgroup of each 64-channel block -- by the
-// discriminator and the clip rule.
-//
-// A wave owns 64 pixels (one per lane) of one image and walks 64 channels; every load is a
-// 256-byte contiguous run of one channel.  The lane's 64 codes are 64 contiguous bytes of the
-// NHWC output.  Counts are wave ballots; lane i keeps the count of channel c0+i.
+// S2 (+ the global copy of S5): tail-mass count per channel, fused with the globally quantized
+// NHWC copy.  A workgroup owns 64 pixels of one image and 64 channels; wave w walks channels
+// 16w..16w+15 with lane = pixel, so every load is a 256-byte run of one channel and the lane's 16
+// codes are 16 contiguous bytes of the NHWC output.  Counts are wave ballots, stored per
+// (channel, image, pixel tile) and summed by k_clip_final: no atomics anywhere.
 // ---------------------------------------------------------------------------------------------
 struct ClipArgs {
     float k, A, lambda;
@@ -203,141 +233,145 @@ struct ClipArgs {
 template <bool STOCH, bool WRITE_QG, bool COUNT>
 __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g, int N, int C, int HW, int c_pitch,
                                                      int ptiles, QuantWs ws, const float* __restrict__ scale_ptr,
-                                                     int8_t* __restrict__ qg, uint64_t seed, ClipArgs ca) {
+                                                     int8_t* __restrict__ qg, uint64_t seed) {
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     int b = blockIdx.x;
     const int pt = b % ptiles; b /= ptiles;
     const int n = b % N;
     const int cb = b / N;
-    const int c0 = cb * 64;
-    const int px = pt * kBlock + wave * kWave + lane;
+    const int c0 = cb * 64 + 16 * wave;
+    const int px = pt * kWave + lane;
     const bool vpx = px < HW;
 
     // scale of the global copy: max_c |g|max from the statistics pass, or an explicit per-tensor scale
-    float sg;
-    if (scale_ptr) sg = *scale_ptr;
-    else sg = __uint_as_float(*ws.gmax_bits);
-    if (!(sg >= kTinyScale)) sg = 0.0f;
+    float sg = 0.0f;
+    if (WRITE_QG) {
+        sg = scale_ptr ? *scale_ptr : __uint_as_float(*ws.gmax_bits);
+        if (!(sg >= kTinyScale)) sg = 0.0f;
+    }
     const float inv = inv_scale(sg);
 
-    uint32_t mycnt = 0;
     const float* gp = g + ((int64_t)n * C + c0) * HW + px;
-    int8_t* outp = WRITE_QG ? qg + ((int64_t)n * HW + px) * c_pitch + c0 : nullptr;
-#pragma unroll 1
-    for (int q = 0; q < 4; ++q) {
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
+    float x[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int cl = 16 * q + i;
-            const int c = c0 + cl;
-            const bool ok = vpx && c < C;
-            const float x = ok ? gp[(int64_t)cl * HW] : 0.0f;
-            if (COUNT) {
-                const float sig = (c < C) ? ws.sigma[c] : 0.0f;
-                const unsigned long long bal = __ballot(ok && fabsf(x) > sig);
-                if (lane == cl) mycnt += (uint32_t)__popcll(bal);
-            }
-            if (WRITE_QG) {
-                const uint64_t idx = (uint64_t)(((int64_t)n * C + c) * HW + px);
-                const int code = quant_code<STOCH>(x, inv, seed, 1u, idx);
-                w[i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
-            }
-        }
-        if (WRITE_QG && vpx && c0 + 16 * q < c_pitch) {
-            *reinterpret_cast<uint4*>(outp + 16 * q) = make_uint4(w[0], w[1], w[2], w[3]);
-        }
-    }
+    for (int i = 0; i < 16; ++i) x[i] = (vpx && c0 + i < C) ? gp[(int64_t)i * HW] : 0.0f;
 
-    if (!COUNT) return;
-    __shared__ uint32_t l_cnt[64];
-    __shared__ int l_last;
-    if (tid < 64) l_cnt[tid] = 0;
-    __syncthreads();
-    if (mycnt) atomicAdd(&l_cnt[lane], mycnt);
-    __syncthreads();
-    if (tid < 64 && c0 + tid < C && l_cnt[tid]) atomicAdd(&ws.count[c0 + tid], l_cnt[tid]);
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) {
-        const uint32_t old = atomicAdd(&ws.done_count[cb], 1u);
-        l_last = (old == (uint32_t)(N * ptiles) - 1u);
+    uint32_t mycnt = 0;
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int c = c0 + i;
+        if (COUNT) {
+            const float sig = (c < C) ? ws.sigma[c] : 0.0f;
+            const unsigned long long bal = __ballot(vpx && c < C && fabsf(x[i]) > sig);
+            if (lane == i) mycnt = (uint32_t)__popcll(bal);
+        }
+        if (WRITE_QG) {
+            const uint64_t idx = (uint64_t)(((int64_t)n * C + c) * HW + px);
+            const int code = quant_code<STOCH>(x[i], inv, seed, 1u, idx);
+            w[i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
+        }
     }
+    if (WRITE_QG && vpx && c0 < c_pitch)
+        *reinterpret_cast<uint4*>(qg + ((int64_t)n * HW + px) * c_pitch + c0) = make_uint4(w[0], w[1], w[2], w[3]);
+    if (COUNT && lane < 16 && c0 + lane < C)
+        ws.part_cnt[(int64_t)(c0 + lane) * ws.slots + n * ptiles + pt] = mycnt;
+}
+
+// S2 (sum of the partial counts) + S3 discriminator + S4 clip rule, one workgroup per channel.
+__global__ __launch_bounds__(kBlock) void k_clip_final(int N, int C, int HW, QuantWs ws, ClipArgs ca) {
+    const int c = blockIdx.x;
+    uint32_t cnt = 0;
+    for (int j = threadIdx.x; j < ws.slots; j += kBlock) cnt += ws.part_cnt[(int64_t)c * ws.slots + j];
+    cnt = wave_sum_u32(cnt);
+    __shared__ uint32_t l_cnt[kBlock / kWave];
+    if (threadIdx.x % kWave == 0) l_cnt[threadIdx.x / kWave] = cnt;
     __syncthreads();
-    if (blockIdx.x == 0 && tid == 0) *ca.s_global = sg;
-    if (!l_last) return;
-    __threadfence();
-    // S3 + S4 for this block's channels
-    if (tid < 64 && c0 + tid < C) {
-        const int c = c0 + tid;
-        const uint32_t cnt = *((volatile uint32_t*)&ws.count[c]);
-        const double Md = (double)N * (double)HW;
-        const int klass = ((double)cnt > (double)ca.lambda * Md) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
-        const float gm = ws.gmax[c];
-        float s = gm;
-        if (klass == DAQ_CLASS_INVT) {
-            float p = ca.s_state[c];
-            if (!(p > 0.0f)) p = gm;
-            s = (float)((1.0 - (double)ca.k * (double)ca.A) * (double)p + (double)ca.A * (double)gm);
-            if (!(s > 0.0f)) s = gm;
-        }
-        ca.s_state[c] = s;
-        ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
-        ca.cls[c] = (uint8_t)klass;
-        if (ca.stats) {
-            ca.stats[4 * c + 0] = gm;
-            ca.stats[4 * c + 1] = ws.mean[c];
-            ca.stats[4 * c + 2] = ws.sigma[c];
-            ca.stats[4 * c + 3] = (float)((double)cnt / Md);
-        }
+    if (threadIdx.x != 0) return;
+    for (int w = 1; w < kBlock / kWave; ++w) cnt += l_cnt[w];
+
+    float sg = __uint_as_float(*ws.gmax_bits);
+    if (!(sg >= kTinyScale)) sg = 0.0f;
+    if (c == 0) *ca.s_global = sg;
+    const double Md = (double)N * (double)HW;
+    const int klass = ((double)cnt > (double)ca.lambda * Md) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
+    const float gm = ws.gmax[c];
+    float s = gm;
+    if (klass == DAQ_CLASS_INVT) {
+        float p = ca.s_state[c];
+        if (!(p > 0.0f)) p = gm;
+        s = (float)((1.0 - (double)ca.k * (double)ca.A) * (double)p + (double)ca.A * (double)gm);
+        if (!(s > 0.0f)) s = gm;
+    }
+    ca.s_state[c] = s;
+    ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
+    ca.cls[c] = (uint8_t)klass;
+    if (ca.stats) {
+        ca.stats[4 * c + 0] = gm;
+        ca.stats[4 * c + 1] = ws.mean[c];
+        ca.stats[4 * c + 2] = ws.sigma[c];
+        ca.stats[4 * c + 3] = (float)((double)cnt / Md);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // S5, channel-major copy: fp32 NCHW -> int8 CNHW (the dimension transformation G -> G', X -> X').
-// Output driven: each thread produces one aligned dword of the destination plane, including the
-// zero bytes that serve as convolution padding, so stores are fully coalesced and every byte of
-// the buffer is written exactly once.
+// Output driven: each thread produces 16 aligned bytes of the destination plane, including the
+// zero bytes that serve as convolution padding, so stores are fully coalesced, every byte of the
+// buffer is written exactly once and all 16 loads of a thread are in flight together.
 // ---------------------------------------------------------------------------------------------
 template <bool STOCH>
 __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ src, CnhwView L,
                                                       const float* __restrict__ scale, int per_channel,
-                                                      int8_t* __restrict__ dst, uint64_t seed, uint32_t tensor) {
-    const int c = blockIdx.y;
+                                                      int8_t* __restrict__ dst, uint64_t seed, uint32_t tensor,
+                                                      int per_chan) {
+    const int b = blockIdx.x;
+    const int xcd = b % kXcd, q = b / kXcd;
+    const int c = (q / per_chan) * kXcd + xcd;  // channel c runs on XCD c % 8
+    const int jb = q % per_chan;                // block of 16-byte units along the flattened axis
     const int phase = blockIdx.z;
-    const int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x;  // dword inside the plane
-    if (4 * j >= L.plane_pitch) return;
+    if (c >= L.C) return;
+    const int64_t j = (int64_t)jb * kBlock + threadIdx.x;  // 16-byte unit inside the plane
+    if (16 * j >= L.plane_pitch) return;
     const int ph = phase / L.phases_w, pw = phase % L.phases_w;
-    float s = per_channel ? scale[c] : scale[0];
-    const float inv = inv_scale(s);
+    const float inv = inv_scale(per_channel ? scale[c] : scale[0]);
 
     const int slot = L.img_rows * L.row_pitch;
-    int64_t o = 4 * j - L.lead;
-    uint32_t word = 0;
+    int64_t o = 16 * j - L.lead;
     int n = 0, r = 0, col = 0;
-    bool have = false;
+    if (o > 0) {
+        n = (int)(o / slot);
+        const int rem = (int)(o - (int64_t)n * slot);
+        r = rem / L.row_pitch;
+        col = rem - r * L.row_pitch;
+    }
+    float x[16];
+    int64_t idx[16];
 #pragma unroll
-    for (int i = 0; i < 4; ++i, ++o) {
-        if (o < 0) continue;
-        if (!have) {
-            n = (int)(o / slot);
-            const int rem = (int)(o - (int64_t)n * slot);
-            r = rem / L.row_pitch;
-            col = rem - r * L.row_pitch;
-            have = true;
-        }
-        const int h = r * L.phases_h + ph - L.org_h;
-        const int w = col * L.phases_w + pw - L.org_w;
-        if (n < L.N && h >= 0 && h < L.H && w >= 0 && w < L.W) {
-            const int64_t idx = (((int64_t)n * L.C + c) * L.H + h) * L.W + w;
-            const int code = quant_code<STOCH>(src[idx], inv, seed, tensor, (uint64_t)idx);
-            word |= ((uint32_t)code & 0xFFu) << (8 * i);
-        }
-        if (++col == L.row_pitch) {
-            col = 0;
-            if (++r == L.img_rows) { r = 0; ++n; }
+    for (int i = 0; i < 16; ++i) {
+        x[i] = 0.0f;
+        idx[i] = -1;
+        if (o + i >= 0) {
+            const int h = r * L.phases_h + ph - L.org_h;
+            const int w = col * L.phases_w + pw - L.org_w;
+            if (n < L.N && h >= 0 && h < L.H && w >= 0 && w < L.W) {
+                idx[i] = (((int64_t)n * L.C + c) * L.H + h) * L.W + w;
+                x[i] = src[idx[i]];
+            }
+            if (++col == L.row_pitch) {
+                col = 0;
+                if (++r == L.img_rows) { r = 0; ++n; }
+            }
         }
     }
-    *reinterpret_cast<uint32_t*>(dst + (int64_t)c * L.chan_pitch + (int64_t)phase * L.plane_pitch + 4 * j) = word;
+    uint32_t w4[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int code = (idx[i] >= 0) ? quant_code<STOCH>(x[i], inv, seed, tensor, (uint64_t)idx[i]) : 0;
+        w4[i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
+    }
+    *reinterpret_cast<uint4*>(dst + (int64_t)c * L.chan_pitch + (int64_t)phase * L.plane_pitch + 16 * j) =
+        make_uint4(w4[0], w4[1], w4[2], w4[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -376,20 +410,18 @@ __global__ __launch_bounds__(kBlock) void k_pack_w(const float* __restrict__ W, 
     out[L.off_bwd + ((int64_t)tap * Cin + ci) * L.cog_pitch + col] = code;
 }
 
-int pick_chunks(int M, int C) {
-    int64_t chunks = ceil_div(M, 8192);
-    const int64_t want = ceil_div(2048, C);  // aim for a couple of thousand workgroups
-    if (chunks < want) chunks = want;
-    const int64_t cap = ceil_div(M, 1024);   // but never less than 1024 elements per workgroup
-    if (chunks > cap) chunks = cap;
-    if (chunks > kMaxChunks) chunks = kMaxChunks;
-    if (chunks < 1) chunks = 1;
-    return (int)chunks;
+// grid of k_pack_cnhw: x enumerates (channel, block of 16-byte units) with the channel's XCD in the low bits,
+// z the stride phase
+int pack_per_chan(const daq_layout& L) { return (int)ceil_div(L.plane_pitch / 16, kBlock); }
+dim3 pack_grid(const daq_layout& L) {
+    return dim3((unsigned)(round_up(L.C, kXcd) * pack_per_chan(L)), 1u, (unsigned)(L.phases_h * L.phases_w));
 }
 
 }  // namespace
 
-size_t quantize_grad_ws_bytes(const daq_conv_desc& d) { return (size_t)carve_quant_ws(nullptr, d.Cout).total_bytes; }
+size_t quantize_grad_ws_bytes(const daq_conv_desc& d) {
+    return (size_t)carve_quant_ws(nullptr, d.Cout, d.N, daq_out_h(&d) * daq_out_w(&d)).total_bytes;
+}
 
 size_t fwd_quant_ws_bytes(const daq_conv_desc&) { return 256; }
 
@@ -408,20 +440,15 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
     daq_layout Ln, Lc;
     if (daq_layout_qx_nhwc(&d, &Ln) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lc) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
     const int HW = d.Hin * d.Win;
-    const int ptiles = (int)ceil_div(HW, kBlock);
+    const int ptiles = (int)ceil_div(HW, kWave);
     const int CB = (int)ceil_div(d.Cin, 64);
     QuantWs none{};
-    ClipArgs ca{};
     DAQ_LAUNCH("quant_nhwc", st,
                hipLaunchKernelGGL((k_count_qg<false, true, false>), dim3(CB * d.N * ptiles), dim3(kBlock), 0, st, X,
-                                  d.N, d.Cin, HW, Ln.c_pitch, ptiles, none, (const float*)s_x, qx_nhwc, (uint64_t)0,
-                                  ca));
-    const CnhwView V = cnhw_view(Lc);
-    const int phases = Lc.phases_h * Lc.phases_w;
-    dim3 grid((unsigned)ceil_div(Lc.plane_pitch / 4, kBlock), (unsigned)d.Cin, (unsigned)phases);
+                                  d.N, d.Cin, HW, Ln.c_pitch, ptiles, none, (const float*)s_x, qx_nhwc, (uint64_t)0));
     DAQ_LAUNCH("pack_cnhw", st,
-               hipLaunchKernelGGL((k_pack_cnhw<false>), grid, dim3(kBlock), 0, st, X, V, (const float*)s_x, 0,
-                                  qx_cnhw, (uint64_t)0, 0u));
+               hipLaunchKernelGGL((k_pack_cnhw<false>), pack_grid(Lc), dim3(kBlock), 0, st, X, cnhw_view(Lc),
+                                  (const float*)s_x, 0, qx_cnhw, (uint64_t)0, 0u, pack_per_chan(Lc)));
     return DAQ_OK;
 }
 
@@ -471,37 +498,28 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     const int HW = Ho * Wo, M = N * HW;
     const bool stoch = (mode == DAQ_ROUND_STOCHASTIC);
     const bool qg_nhwc = (Lg.kind == DAQ_LAYOUT_NHWC);
-    QuantWs ws = carve_quant_ws(workspace, C);
+    QuantWs ws = carve_quant_ws(workspace, C, N, HW);
+    (void)M;
 
-    // counters and the running global maximum start at zero
-    DAQ_LAUNCH("fill", st,
-               hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)ceil_div(ws.zero_bytes / 4, kBlock)), dim3(kBlock), 0, st,
-                                  ws.count, ws.zero_bytes / 4, 0u));
-
-    // S1
-    const int chunks = pick_chunks(M, C);
-    int chunk_len = (int)round_up(ceil_div(M, chunks), 4);
+    // S1: partial statistics, then one workgroup per channel folds them
     const bool vec4 = (HW % 4 == 0) && (((uintptr_t)dY & 15u) == 0);
-    const unsigned sblocks = (unsigned)(round_up(C, kXcd) * chunks);
+    const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.chunks);
     if (vec4)
-        DAQ_LAUNCH("stats", st,
-                   hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, chunks,
-                                      chunk_len, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
     else
-        DAQ_LAUNCH("stats", st,
-                   hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, chunks,
-                                      chunk_len, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
+    DAQ_LAUNCH("stats_final", st, hipLaunchKernelGGL(k_stats_final, dim3(C), dim3(kBlock), 0, st, N, C, HW, ws));
 
-    // S2-S4 (+ the NHWC global copy)
+    // S2 (+ the NHWC global copy), then S3 + S4
     ClipArgs ca{k, A, lambda, s_state, s_chan, s_global, cls, stats};
-    const int ptiles = (int)ceil_div(HW, kBlock);
+    const int ptiles = (int)ceil_div(HW, kWave);
     const int CB = (int)ceil_div(C, 64);
     const dim3 cgrid((unsigned)(CB * N * ptiles));
     const float* no_scale = nullptr;
 #define DAQ_COUNT_LAUNCH(S, Q)                                                                                       \
     DAQ_LAUNCH("count_qg", st,                                                                                       \
                hipLaunchKernelGGL((k_count_qg<S, Q, true>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,                \
-                                  qg_nhwc ? Lg.c_pitch : 0, ptiles, ws, no_scale, qg, seed, ca))
+                                  qg_nhwc ? Lg.c_pitch : 0, ptiles, ws, no_scale, qg, seed))
     if (qg_nhwc) {
         if (stoch) DAQ_COUNT_LAUNCH(true, true);
         else DAQ_COUNT_LAUNCH(false, true);
@@ -509,27 +527,28 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
         DAQ_COUNT_LAUNCH(false, false);
     }
 #undef DAQ_COUNT_LAUNCH
+    DAQ_LAUNCH("clip_final", st, hipLaunchKernelGGL(k_clip_final, dim3(C), dim3(kBlock), 0, st, N, C, HW, ws, ca));
 
     // S5: per-channel copy (and the global copy for depthwise layers) in CNHW
     const CnhwView V = cnhw_view(Lv);
-    const dim3 pgrid((unsigned)ceil_div(Lv.plane_pitch / 4, kBlock), (unsigned)C, 1u);
+    const dim3 pgrid = pack_grid(Lv);
     if (stoch)
         DAQ_LAUNCH("pack_vq", st,
                    hipLaunchKernelGGL((k_pack_cnhw<true>), pgrid, dim3(kBlock), 0, st, dY, V, (const float*)s_chan, 1,
-                                      vq, seed, 0u));
+                                      vq, seed, 0u, pack_per_chan(Lv)));
     else
         DAQ_LAUNCH("pack_vq", st,
                    hipLaunchKernelGGL((k_pack_cnhw<false>), pgrid, dim3(kBlock), 0, st, dY, V, (const float*)s_chan,
-                                      1, vq, seed, 0u));
+                                      1, vq, seed, 0u, pack_per_chan(Lv)));
     if (!qg_nhwc) {
         if (stoch)
             DAQ_LAUNCH("pack_qg", st,
                        hipLaunchKernelGGL((k_pack_cnhw<true>), pgrid, dim3(kBlock), 0, st, dY, V,
-                                          (const float*)s_global, 0, qg, seed, 1u));
+                                          (const float*)s_global, 0, qg, seed, 1u, pack_per_chan(Lv)));
         else
             DAQ_LAUNCH("pack_qg", st,
                        hipLaunchKernelGGL((k_pack_cnhw<false>), pgrid, dim3(kBlock), 0, st, dY, V,
-                                          (const float*)s_global, 0, qg, seed, 1u));
+                                          (const float*)s_global, 0, qg, seed, 1u, pack_per_chan(Lv)));
     }
     return DAQ_OK;
 }
