@@ -9,15 +9,17 @@
 //     acc[co][ci][kh][kw] = sum_f  G[co][f] * X[ci][f + kh*row_pitch + kw]
 //
 // i.e. a GEMM with M = Cout, N = Cin*kH*kW, K = the flat axis, whose B operand is the same bytes
-// read at kH*kW offsets.  v_mfma_i32_16x16x64_i8 wants 16 consecutive K bytes per lane: for G they
-// are an aligned 16-byte LDS read; for X they start at an arbitrary byte, so a lane reads the six
-// dwords that cover the three kw windows of one kh once and realigns with v_alignbyte_b32.
+// read at kH*kW offsets.  v_mfma_i32_16x16x64_i8 wants 16 consecutive K bytes per lane.  For G they
+// are an aligned 16-byte LDS read.  For X one LDS copy per kh is staged, fetched from global memory
+// at the dword below f + kh*row_pitch, so that a lane reads 24 aligned bytes (b128 + b64) per kh and
+// derives the kW windows with v_alignbyte_b32 (shift (kh*row_pitch mod 4) + kw).
 //
-// Workgroup = 4 waves.  A wave owns a 64 (co) x 16 (ci) x kH*kW accumulator tile (144 VGPRs for
-// 3x3).  The four waves either take four ci blocks (WGK = 1) or share one ci block and split the
-// K steps of every staged chunk (WGK = 4, reduced through LDS at the end); the latter keeps all 256
-// CUs busy on layers with few channels.  K is also split across workgroups; partial tiles are
-// combined with int32 atomics (exact, order independent) and de-quantized by a small epilogue.
+// Workgroup = 4 waves.  A wave owns a 64 (co) x 16*NB (ci) x kH*kW accumulator tile (144 VGPRs for
+// 3x3, NB = 1).  The four waves either take four ci blocks (WGK = 1) or share one ci block and split
+// the K steps of every staged chunk (WGK = 4, reduced through LDS at the end); the latter keeps all
+// 256 CUs busy on layers with few channels.  K may also be split across workgroups: each writes its
+// partial tile with coalesced stores and a second kernel sums the partials (exact, order independent)
+// and de-quantizes.  Global loads run PF chunks ahead of the MFMAs through a register FIFO.
 #include "daq_internal.h"
 
 namespace daq {
@@ -25,9 +27,12 @@ namespace daq {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
 
 constexpr int kKC = 256;          // K bytes staged per chunk (4 MFMA K-steps of 64)
-constexpr int kPA = kKC + 16;     // LDS row pitch of the G tile: +16 B rotates banks between rows
+constexpr int kPA = kKC + 16;     // LDS row pitch: +16 B holds the realignment slack and rotates banks between rows
 constexpr int kBM = 64;           // co rows per workgroup
 
 struct DwArgs {
@@ -36,12 +41,11 @@ struct DwArgs {
     int64_t klen;         // bytes of the flat axis (multiple of 256)
     int64_t x_chan_pitch;
     int Cout, Cin;
-    int row_pitch;        // Wq
-    int pb;               // LDS row pitch of the X tile (bytes, multiple of 16)
+    int row_pitch;        // bytes per image row of both operands
     int nchunks;          // klen / kKC
     int splits;           // workgroups along K
-    int tiles_n;          // ci tiles
-    int32_t* ws;          // int32 accumulators [Cout][Cin][kH*kW], zeroed beforehand (splits > 1 only)
+    int tiles_n, tiles_m; // ci tiles, co tiles
+    int32_t* part;        // splits > 1: partial tiles [tile][split][wave-of-ci][reg][lane]
     // splits == 1: the tile is complete, de-quantize and store it directly
     const float* s_x;
     const float* s_chan;
@@ -53,138 +57,161 @@ __device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
     return (int)__builtin_amdgcn_alignbyte((unsigned)hi, (unsigned)lo, (unsigned)sh);
 }
 
-template <int KH, int KW, int WQ4, int WGK>
+template <int KH, int KW, int WQ4, int WGK, int NB, int PF>
 __global__ __launch_bounds__(256) void k_dw_mfma(DwArgs p) {
-    constexpr int WGN = 4 / WGK;         // waves along ci
-    constexpr int BN = 16 * WGN;         // ci rows per workgroup
+    constexpr int WGN = 4 / WGK;          // waves along ci
+    constexpr int BN = 16 * NB * WGN;     // ci rows per workgroup
     constexpr int T = KH * KW;
+    constexpr int NT = NB * T;            // accumulator tiles per co block
+    constexpr int UR = kPA / 16;          // 16-byte units per staged row (17)
+    constexpr int A_UNITS = kBM * (kKC / 16);
+    constexpr int B_UNITS = KH * BN * UR;
+    constexpr int A_PER_T = A_UNITS / 256;
+    constexpr int B_PER_T = (B_UNITS + 255) / 256;
+    constexpr int A_BYTES = kBM * kPA;
+    constexpr int STAGE = A_BYTES + KH * BN * kPA;
     extern __shared__ __align__(16) int8_t lds[];
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int wn = wave % WGN, wk = wave / WGN;
     const int li = lane & 15, lg = lane >> 4;
 
-    int b = blockIdx.x;
-    const int split = b % p.splits; b /= p.splits;
-    const int tn = b % p.tiles_n;
-    const int tm = b / p.tiles_n;
+    // Workgroup i runs on XCD i % 8.  All output tiles of one K split are placed on one XCD, so a slice
+    // of the two operands is fetched from HBM into a single L2 and shared there by the tiles.
+    int split, tile;
+    {
+        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+        const int full = (p.splits / kXcd) * kXcd;       // splits that fill whole rounds of 8
+        const int x = b % kXcd, q = b / kXcd;
+        if (q < (full / kXcd) * tiles) {
+            split = (q / tiles) * kXcd + x;
+            tile = q % tiles;
+        } else {                                           // remainder: plain order
+            const int rb = b - full * tiles;
+            split = full + rb % (p.splits - full);
+            tile = rb / (p.splits - full);
+        }
+    }
+    const int tn = tile % p.tiles_n;
+    const int tm = tile / p.tiles_n;
     const int co0 = tm * kBM, ci0 = tn * BN;
-    // chunks [c_begin, c_end) of this split
     const int per = p.nchunks / p.splits, rem = p.nchunks % p.splits;
     const int c_begin = split * per + min(split, rem);
     const int c_end = c_begin + per + (split < rem ? 1 : 0);
 
-    const int a_bytes = kBM * kPA;
-    const int b_bytes = BN * p.pb;
-    const int stage_bytes = a_bytes + b_bytes;
-    const int ub = p.pb / 16;            // 16-byte units per X row
-    const int a_units = kBM * (kKC / 16);
-    const int b_units = BN * ub;
-    constexpr int A_PER_T = kBM * (kKC / 16) / 256;  // 4
-    const int b_per_t = (b_units + 255) / 256;
-
-    v4i acc[4][T];
+    v4i acc[4][NT];
 #pragma unroll
     for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int t = 0; t < T; ++t) acc[m][t] = v4i{0, 0, 0, 0};
+        for (int t = 0; t < NT; ++t) acc[m][t] = v4i{0, 0, 0, 0};
 
-    // ---- staging helpers (global -> registers -> LDS) ----
-    constexpr int MAXB = 12;             // enough for pb <= 768 with BN = 64
-    uint4 ra[A_PER_T];
-    uint4 rb[MAXB];
-    auto load_chunk = [&](int chunk) {
+    // ---- staging: global -> register FIFO -> LDS ----
+    uint4 ra[PF][A_PER_T];
+    uint4 rb[PF][B_PER_T];
+    // per-thread source offsets of the units this thread stages (relative to the chunk start)
+    int64_t a_off[A_PER_T], b_off[B_PER_T];
+    int a_lds[A_PER_T], b_lds[B_PER_T];
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+        const int u = tid + 256 * i;
+        const int row = u / (kKC / 16), c16 = u % (kKC / 16);
+        a_off[i] = (co0 + row < p.Cout) ? (int64_t)(co0 + row) * p.klen + 16 * c16 : -1;
+        a_lds[i] = row * kPA + 16 * c16;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER_T; ++i) {
+        const int u = tid + 256 * i;
+        const int c16 = u % UR;
+        const int row = (u / UR) % BN;
+        const int kh = u / (UR * BN);
+        const int r0 = (kh * p.row_pitch) & 3;
+        b_off[i] = (u < B_UNITS && ci0 + row < p.Cin)
+                       ? (int64_t)(ci0 + row) * p.x_chan_pitch + kh * p.row_pitch - r0 + 16 * c16 : -1;
+        b_lds[i] = (u < B_UNITS) ? A_BYTES + (kh * BN + row) * kPA + 16 * c16 : -1;
+    }
+    auto load_chunk = [&](int chunk, int set) {
         const int64_t k0 = (int64_t)chunk * kKC;
 #pragma unroll
-        for (int i = 0; i < A_PER_T; ++i) {
-            const int u = tid + 256 * i;
-            const int row = u / (kKC / 16), c16 = u % (kKC / 16);
-            const int co = co0 + row;
-            ra[i] = (co < p.Cout) ? *reinterpret_cast<const uint4*>(p.g + (int64_t)co * p.klen + k0 + 16 * c16)
-                                  : make_uint4(0, 0, 0, 0);
-        }
+        for (int i = 0; i < A_PER_T; ++i)
+            ra[set][i] = (a_off[i] >= 0) ? *reinterpret_cast<const uint4*>(p.g + a_off[i] + k0) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < MAXB; ++i) {
-            if (i < b_per_t) {
-                const int u = tid + 256 * i;
-                const int row = u / ub, c16 = u - row * ub;
-                const int ci = ci0 + row;
-                rb[i] = (u < b_units && ci < p.Cin)
-                            ? *reinterpret_cast<const uint4*>(p.x + (int64_t)ci * p.x_chan_pitch + k0 + 16 * c16)
-                            : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < B_PER_T; ++i) {
+            if (b_off[i] >= 0) {
+                const v4i_a4 v = *reinterpret_cast<const v4i_a4*>(p.x + b_off[i] + k0);  // dword aligned only
+                rb[set][i] = make_uint4((unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]);
+            } else {
+                rb[set][i] = make_uint4(0, 0, 0, 0);
             }
         }
     };
-    auto store_chunk = [&](int buf) {
-        int8_t* A = lds + buf * stage_bytes;
-        int8_t* B = A + a_bytes;
+    auto store_chunk = [&](int buf, int set) {
+        int8_t* base = lds + buf * STAGE;
 #pragma unroll
-        for (int i = 0; i < A_PER_T; ++i) {
-            const int u = tid + 256 * i;
-            const int row = u / (kKC / 16), c16 = u % (kKC / 16);
-            *reinterpret_cast<uint4*>(A + row * kPA + 16 * c16) = ra[i];
-        }
+        for (int i = 0; i < A_PER_T; ++i) *reinterpret_cast<uint4*>(base + a_lds[i]) = ra[set][i];
 #pragma unroll
-        for (int i = 0; i < MAXB; ++i) {
-            if (i < b_per_t) {
-                const int u = tid + 256 * i;
-                if (u < b_units) {
-                    const int row = u / ub, c16 = u - row * ub;
-                    *reinterpret_cast<uint4*>(B + row * p.pb + 16 * c16) = rb[i];
-                }
-            }
-        }
+        for (int i = 0; i < B_PER_T; ++i)
+            if (b_lds[i] >= 0) *reinterpret_cast<uint4*>(base + b_lds[i]) = rb[set][i];
     };
 
     if (c_begin < c_end) {
-        load_chunk(c_begin);
-        store_chunk(0);
+        load_chunk(c_begin, 0);
+        store_chunk(0, 0);
+#pragma unroll
+        for (int i = 1; i <= PF; ++i)
+            if (c_begin + i < c_end) load_chunk(c_begin + i, i % PF);
     }
     __syncthreads();
 
-    for (int chunk = c_begin; chunk < c_end; ++chunk) {
-        const int buf = (chunk - c_begin) & 1;
-        const bool more = chunk + 1 < c_end;
-        if (more) load_chunk(chunk + 1);
-
-        const int8_t* A = lds + buf * stage_bytes;
-        const int8_t* B = A + a_bytes + (wn * 16 + li) * p.pb;
+    for (int base = c_begin; base < c_end; base += PF) {
 #pragma unroll
-        for (int ks = wk; ks < kKC / 64; ks += WGK) {
-            v4i a[4];
+        for (int u = 0; u < PF; ++u) {
+            const int chunk = base + u;
+            if (chunk < c_end) {
+                const int buf = (chunk - c_begin) & 1;
+                const int8_t* A = lds + buf * STAGE;
+                const int8_t* B = A + A_BYTES;
 #pragma unroll
-            for (int m = 0; m < 4; ++m)
-                a[m] = *reinterpret_cast<const v4i*>(A + (16 * m + li) * kPA + ks * 64 + 16 * lg);
-#pragma unroll
-            for (int kh = 0; kh < KH; ++kh) {
-                constexpr int dummy = 0;
-                (void)dummy;
-                const int r0 = (kh * WQ4) & 3;  // (kh*row_pitch) mod 4, known at compile time
-                const int byte0 = ks * 64 + 16 * lg + kh * p.row_pitch;
-                const int* src = reinterpret_cast<const int*>(B + (byte0 - r0));
-                int d[6];
-#pragma unroll
-                for (int i = 0; i < 6; ++i) d[i] = src[i];
-#pragma unroll
-                for (int kw = 0; kw < KW; ++kw) {
-                    const int s = r0 + kw;
-                    const int j = s >> 2, sh = s & 3;
-                    v4i bf;
-                    if (sh == 0) {
-                        bf = v4i{d[j], d[j + 1], d[j + 2], d[j + 3]};
-                    } else {
-                        bf = v4i{alignbyte(d[j + 1], d[j], sh), alignbyte(d[j + 2], d[j + 1], sh),
-                                 alignbyte(d[j + 3], d[j + 2], sh), alignbyte(d[j + 4], d[j + 3], sh)};
-                    }
+                for (int ks = wk; ks < kKC / 64; ks += WGK) {
+                    v4i a[4];
 #pragma unroll
                     for (int m = 0; m < 4; ++m)
-                        acc[m][kh * KW + kw] =
-                            __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m], bf, acc[m][kh * KW + kw], 0, 0, 0);
+                        a[m] = *reinterpret_cast<const v4i*>(A + (16 * m + li) * kPA + ks * 64 + 16 * lg);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int kh = 0; kh < KH; ++kh) {
+                            const int8_t* src = B + (kh * BN + (wn * NB + nb) * 16 + li) * kPA + ks * 64 + 16 * lg;
+                            const v4i lo = *reinterpret_cast<const v4i*>(src);
+                            int d[6] = {lo[0], lo[1], lo[2], lo[3], 0, 0};
+                            if (KW > 1 || ((kh * WQ4) & 3) != 0) {
+                                const v2i hi = *reinterpret_cast<const v2i*>(src + 16);
+                                d[4] = hi[0];
+                                d[5] = hi[1];
+                            }
+#pragma unroll
+                            for (int kw = 0; kw < KW; ++kw) {
+                                const int s = ((kh * WQ4) & 3) + kw;  // byte shift of this tap's window
+                                const int j = s >> 2, sh = s & 3;
+                                v4i bf;
+                                if (sh == 0)
+                                    bf = v4i{d[j], d[j + 1], d[j + 2], d[j + 3]};
+                                else
+                                    bf = v4i{alignbyte(d[j + 1], d[j], sh), alignbyte(d[j + 2], d[j + 1], sh),
+                                             alignbyte(d[j + 3], d[j + 2], sh), alignbyte(d[j + 4], d[j + 3], sh)};
+                                const int t = nb * T + kh * KW + kw;
+#pragma unroll
+                                for (int m = 0; m < 4; ++m)
+                                    acc[m][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m], bf, acc[m][t], 0, 0, 0);
+                            }
+                        }
                 }
+                // chunk+1 goes to the other LDS buffer; its register set is then refilled PF chunks ahead
+                const int nset = (u + 1) % PF;  // a constant once the loop is unrolled
+                if (chunk + 1 < c_end) store_chunk(buf ^ 1, nset);
+                if (chunk + 1 + PF < c_end) load_chunk(chunk + 1 + PF, nset);
+                __syncthreads();
             }
         }
-        if (more) store_chunk(buf ^ 1);
-        __syncthreads();
     }
 
     // ---- reduce the WGK waves that share a tile (through LDS, one wave at a time) ----
@@ -196,71 +223,287 @@ __global__ __launch_bounds__(256) void k_dw_mfma(DwArgs p) {
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
 #pragma unroll
-                    for (int t = 0; t < T; ++t)
+                    for (int t = 0; t < NT; ++t)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) red[((m * T + t) * 4 + r) * kWave + lane] = acc[m][t][r];
+                        for (int r = 0; r < 4; ++r) red[((m * NT + t) * 4 + r) * kWave + lane] = acc[m][t][r];
             }
             __syncthreads();
             if (wk == 0) {
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
 #pragma unroll
-                    for (int t = 0; t < T; ++t)
+                    for (int t = 0; t < NT; ++t)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[m][t][r] += red[((m * T + t) * 4 + r) * kWave + lane];
+                        for (int r = 0; r < 4; ++r) acc[m][t][r] += red[((m * NT + t) * 4 + r) * kWave + lane];
             }
         }
         if (wk != 0) return;
     }
 
-    // ---- a complete tile is de-quantized here; a partial one is added into the int32 accumulators ----
-    const int ci = ci0 + wn * 16 + li;
-    if (ci >= p.Cin) return;
-    const bool direct = (p.splits == 1);
-    const float sx = direct ? (*p.s_x / 127.0f) : 0.0f;
+    if (p.splits > 1) {
+        // partial tile: register q of lane l at [((tile*splits + split)*WGN + wn)*16*NT + q][l]
+        int32_t* dst = p.part + (((int64_t)(tm * p.tiles_n + tn) * p.splits + split) * WGN + wn) * (16 * NT) * kWave + lane;
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
+        for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int co = co0 + 16 * m + 4 * lg + r;
-            if (co < p.Cout) {
-                const int64_t off = ((int64_t)co * p.Cin + ci) * T;
-                if (direct) {
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[((m * NT + t) * 4 + r) * kWave] = acc[m][t][r];
+        return;
+    }
+
+    // complete tile: de-quantize and store
+    const float sx = *p.s_x / 127.0f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int ci = ci0 + (wn * NB + nb) * 16 + li;
+        if (ci >= p.Cin) continue;
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int co = co0 + 16 * m + 4 * lg + r;
+                if (co < p.Cout) {
+                    const int64_t off = ((int64_t)co * p.Cin + ci) * T;
                     const float sc = sx * (p.s_chan[co] / 127.0f);
 #pragma unroll
                     for (int t = 0; t < T; ++t) {
-                        p.dW[off + t] = (float)acc[m][t][r] * sc;
-                        if (p.acc_out) p.acc_out[off + t] = acc[m][t][r];
+                        p.dW[off + t] = (float)acc[m][nb * T + t][r] * sc;
+                        if (p.acc_out) p.acc_out[off + t] = acc[m][nb * T + t][r];
+                    }
+                }
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Split-K variant for layers with few channels (one output tile per 64 x 16*NB block, many K slices).
+// The four waves of a workgroup work on four disjoint runs of K steps with no barrier between them:
+// a lane's MFMA fragments are 16 contiguous bytes of one channel row, so they are fetched straight
+// from global memory into registers (G aligned, X at the dword below its shifted window), PFD steps
+// ahead.  At the end wave m keeps co block m: the other waves hand it their part through LDS.
+// ---------------------------------------------------------------------------------------------
+template <int KH, int KW, int WQ4, int NB, int PFD>
+__global__ __launch_bounds__(256) void k_dw_direct(DwArgs p) {
+    constexpr int T = KH * KW;
+    constexpr int NT = NB * T;
+    extern __shared__ __align__(16) int8_t lds[];
+    int* red = reinterpret_cast<int*>(lds);  // [owner 4][source 3][NT*4][64]
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int li = lane & 15, lg = lane >> 4;
+    int split, tile;
+    {
+        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+        const int full = (p.splits / kXcd) * kXcd;
+        const int x = b % kXcd, q = b / kXcd;
+        if (q < (full / kXcd) * tiles) {
+            split = (q / tiles) * kXcd + x;
+            tile = q % tiles;
+        } else {
+            const int rb = b - full * tiles;
+            split = full + rb % (p.splits - full);
+            tile = rb / (p.splits - full);
+        }
+    }
+    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    const int co0 = tm * kBM, ci0 = tn * 16 * NB;
+    // K steps (64 bytes each) of this wave
+    const int nsteps = p.nchunks * (kKC / 64);
+    const int units = p.splits * 4, unit = split * 4 + wave;
+    const int per = nsteps / units, rem = nsteps % units;
+    const int s_begin = unit * per + min(unit, rem);
+    const int s_end = s_begin + per + (unit < rem ? 1 : 0);
+
+    const int8_t* ga[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int co = co0 + 16 * m + li;
+        ga[m] = (co < p.Cout) ? p.g + (int64_t)co * p.klen + 16 * lg : nullptr;
+    }
+    const int8_t* xb[NB][KH];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int kh = 0; kh < KH; ++kh) {
+            const int ci = ci0 + 16 * nb + li;
+            const int r0 = (kh * p.row_pitch) & 3;
+            xb[nb][kh] = (ci < p.Cin) ? p.x + (int64_t)ci * p.x_chan_pitch + 16 * lg + kh * p.row_pitch - r0 : nullptr;
+        }
+
+    v4i acc[4][NT];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[m][t] = v4i{0, 0, 0, 0};
+
+    v4i ra[PFD][4];
+    v4i rlo[PFD][NB][KH];
+    v2i rhi[PFD][NB][KH];
+    auto load_step = [&](int s, int slot) {
+        const int64_t k = (int64_t)s * 64;
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+            ra[slot][m] = ga[m] ? *reinterpret_cast<const v4i*>(ga[m] + k) : v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int kh = 0; kh < KH; ++kh) {
+                if (xb[nb][kh]) {
+                    const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(xb[nb][kh] + k);
+                    rlo[slot][nb][kh] = v4i{lo[0], lo[1], lo[2], lo[3]};
+                    if (KW > 1 || ((kh * WQ4) & 3) != 0) {
+                        const v2i_a4 hi = *reinterpret_cast<const v2i_a4*>(xb[nb][kh] + k + 16);
+                        rhi[slot][nb][kh] = v2i{hi[0], hi[1]};
+                    } else {
+                        rhi[slot][nb][kh] = v2i{0, 0};
                     }
                 } else {
+                    rlo[slot][nb][kh] = v4i{0, 0, 0, 0};
+                    rhi[slot][nb][kh] = v2i{0, 0};
+                }
+            }
+    };
+
 #pragma unroll
-                    for (int t = 0; t < T; ++t) atomicAdd(p.ws + off + t, acc[m][t][r]);
+    for (int i = 0; i < PFD; ++i)
+        if (s_begin + i < s_end) load_step(s_begin + i, i);
+
+    for (int base = s_begin; base < s_end; base += PFD) {
+#pragma unroll
+        for (int u = 0; u < PFD; ++u) {
+            const int s = base + u;
+            if (s < s_end) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int kh = 0; kh < KH; ++kh) {
+                        const v4i lo = rlo[u][nb][kh];
+                        const v2i hi = rhi[u][nb][kh];
+                        const int d[6] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
+#pragma unroll
+                        for (int kw = 0; kw < KW; ++kw) {
+                            const int sft = ((kh * WQ4) & 3) + kw;
+                            const int j = sft >> 2, sh = sft & 3;
+                            v4i bf;
+                            if (sh == 0)
+                                bf = v4i{d[j], d[j + 1], d[j + 2], d[j + 3]};
+                            else
+                                bf = v4i{alignbyte(d[j + 1], d[j], sh), alignbyte(d[j + 2], d[j + 1], sh),
+                                         alignbyte(d[j + 3], d[j + 2], sh), alignbyte(d[j + 4], d[j + 3], sh)};
+                            const int t = nb * T + kh * KW + kw;
+#pragma unroll
+                            for (int m = 0; m < 4; ++m)
+                                acc[m][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ra[u][m], bf, acc[m][t], 0, 0, 0);
+                        }
+                    }
+                if (s + PFD < s_end) load_step(s + PFD, u);
+            }
+        }
+    }
+
+    // ---- wave m collects co block m from the other three waves ----
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        if (wave != m) {
+            const int srcw = wave < m ? wave : wave - 1;
+            int* dst = red + ((m * 3 + srcw) * NT * 4) * kWave + lane;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[(t * 4 + r) * kWave] = acc[m][t][r];
+        }
+    }
+    __syncthreads();
+    const float sx = *p.s_x / 127.0f;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        if (wave == m) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w) {
+                const int* src = red + ((m * 3 + w) * NT * 4) * kWave + lane;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[m][t][r] += src[(t * 4 + r) * kWave];
+            }
+            if (p.splits > 1) {
+                // partial tile, same slot order as the reduction kernel expects: q = (m*NT + t)*4 + r
+                int32_t* dst = p.part + ((int64_t)tile * p.splits + split) * (16 * NT) * kWave + lane;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dst[((m * NT + t) * 4 + r) * kWave] = acc[m][t][r];
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int ci = ci0 + 16 * nb + li;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int co = co0 + 16 * m + 4 * lg + r;
+                        if (ci < p.Cin && co < p.Cout) {
+                            const int64_t off = ((int64_t)co * p.Cin + ci) * T;
+                            const float sc = sx * (p.s_chan[co] / 127.0f);
+#pragma unroll
+                            for (int t = 0; t < T; ++t) {
+                                p.dW[off + t] = (float)acc[m][nb * T + t][r] * sc;
+                                if (p.acc_out) p.acc_out[off + t] = acc[m][nb * T + t][r];
+                            }
+                        }
+                    }
                 }
             }
         }
+    }
 }
 
-__global__ __launch_bounds__(256) void k_zero_i32(int32_t* p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = 0;
-}
-
-// dW[co][...] = acc * ((s_x/127) * (s_chan[co]/127))
-__global__ __launch_bounds__(256) void k_dw_epilogue(const int32_t* __restrict__ ws, int64_t n, int per_co,
-                                                     const float* s_x, const float* __restrict__ s_chan,
-                                                     float* __restrict__ dW, int32_t* __restrict__ acc_out) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const int co = (int)(i / per_co);
-    const int32_t a = ws[i];
-    dW[i] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
-    if (acc_out) acc_out[i] = a;
+// Sum of the K-split partial tiles, then dW[co][...] = acc * ((s_x/127) * (s_chan[co]/127)).
+// A workgroup owns 64 consecutive slots of the partial layout (one 256-byte run per split); its four
+// waves take every fourth split with eight loads in flight each and combine through LDS.
+__global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wgn,
+                                                   int nb_per_wave, int T, int Cout, int Cin, const float* s_x,
+                                                   const float* __restrict__ s_chan, float* __restrict__ dW,
+                                                   int32_t* __restrict__ acc_out) {
+    const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
+    const int NT = nb_per_wave * T;
+    const int per_wave = 16 * NT * kWave;
+    const int64_t i = (int64_t)blockIdx.x * kWave + lane;   // slot
+    const int q = (int)((i / kWave) % (16 * NT));
+    const int wn = (int)((i / per_wave) % wgn);
+    const int tile = (int)(i / ((int64_t)per_wave * wgn));
+    const int64_t stride = (int64_t)per_wave * wgn;          // between consecutive splits of a tile
+    const int32_t* src = part + (int64_t)tile * splits * stride + (int64_t)wn * per_wave + (int64_t)q * kWave + lane;
+    int32_t a = 0;
+    int s = grp;
+    for (; s + 28 < splits; s += 32) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
+    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
+    __shared__ int32_t l_sum[4][kWave];
+    l_sum[grp][lane] = a;
+    __syncthreads();
+    if (grp != 0) return;
+    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
+    const int r = q & 3, t_all = (q >> 2) % NT, m = (q >> 2) / NT;
+    const int nb = t_all / T, t = t_all % T;
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int co = tm * kBM + 16 * m + 4 * (lane >> 4) + r;
+    const int ci = tn * (16 * nb_per_wave * wgn) + (wn * nb_per_wave + nb) * 16 + (lane & 15);
+    if (co >= Cout || ci >= Cin) return;
+    const int64_t off = ((int64_t)co * Cin + ci) * T + t;
+    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
+    if (acc_out) acc_out[off] = a;
 }
 
 struct Plan {
     bool ok;
-    int wgk, splits, tiles_m, tiles_n, pb, nchunks;
+    int kh, wgk, nb, pf, splits, tiles_m, tiles_n, nchunks;
     size_t lds_bytes;
+    int64_t part_slots;   // int32 slots of one split's worth of partial tiles
 };
 
 Plan make_plan(const daq_conv_desc& d) {
@@ -269,60 +512,88 @@ Plan make_plan(const daq_conv_desc& d) {
     if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1) return pl;
     if (!((d.kH == 3 && d.kW == 3) || (d.kH == 1 && d.kW == 1))) return pl;
     if (d.kH == 1 && (d.padH != 0 || d.padW != 0)) return pl;
-    daq_layout Lx, Lg;
-    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return pl;
-    const int halo = (d.kH - 1) * Lx.row_pitch + (d.kW - 1) + 3 + 8;  // +3 realignment, +8: six dwords are read
-    pl.pb = (int)round_up(kKC + halo, 16) + 16;
+    daq_layout Lg;
+    if (daq_layout_vq(&d, &Lg) != DAQ_OK) return pl;
+    pl.kh = d.kH;
     pl.nchunks = (int)(Lg.plane_pitch / kKC);
     pl.tiles_m = (int)ceil_div(d.Cout, kBM);
     const int T = d.kH * d.kW;
-    const int64_t outs = (int64_t)d.Cout * d.Cin * T;
-    // Prefer a shape with enough output tiles to fill the 256 CUs without splitting K (no atomics, one
-    // launch).  With few channels the four waves of a workgroup split K instead of ci, and K is also
-    // split across workgroups, bounded by the atomic traffic it causes.
-    const int64_t tiles1 = (int64_t)pl.tiles_m * ceil_div(d.Cin, 64);
-    const int64_t tiles4 = (int64_t)pl.tiles_m * ceil_div(d.Cin, 16);
+    pl.nb = (d.kH == 1) ? 4 : 1;                 // 1x1: a wave takes four ci blocks (64 x 64 tile)
+    const int ci_wave = 16 * pl.nb;
+    // Prefer a shape with enough output tiles to fill the 256 CUs without splitting K (one launch).
+    // With few channels the four waves of a workgroup split K instead of ci, and K is also split
+    // across workgroups, bounded by the partial-tile traffic it causes.
+    const int64_t tiles1 = (int64_t)pl.tiles_m * ceil_div(d.Cin, 4 * ci_wave);
+    const int64_t tiles4 = (int64_t)pl.tiles_m * ceil_div(d.Cin, ci_wave);
     int64_t s = 1;
     if (tiles1 >= 192) {
         pl.wgk = 1;
     } else {
         pl.wgk = 4;
         if (tiles4 < 192) {
-            s = ceil_div(384, tiles4);
+            s = ceil_div(256, tiles4);
             const int64_t max_by_chunks = pl.nchunks / 2 > 0 ? pl.nchunks / 2 : 1;
             if (s > max_by_chunks) s = max_by_chunks;
-            const int64_t max_by_atomics = (int64_t)4e6 / (outs > 0 ? outs : 1);
-            if (s > max_by_atomics) s = max_by_atomics;
+            // partial tiles are written and read once: keep that below ~2x the operand bytes
+            const int64_t operand = (int64_t)(d.Cout + d.Cin) * Lg.plane_pitch;
+            const int64_t tile_bytes = (int64_t)pl.tiles_m * kBM * ceil_div(d.Cin, ci_wave) * ci_wave * T * 4;
+            const int64_t max_by_traffic = operand / tile_bytes > 0 ? operand / tile_bytes : 1;
+            if (s > max_by_traffic) s = max_by_traffic;
             if (s < 1) s = 1;
         }
     }
-    const int bn = 16 * (4 / pl.wgk);
+    pl.pf = (pl.wgk == 4) ? 4 : 1;
+    const int wgn = 4 / pl.wgk;
+    const int bn = ci_wave * wgn;
     pl.tiles_n = (int)ceil_div(d.Cin, bn);
     pl.splits = (int)s;
-    const size_t stage = (size_t)kBM * kPA + (size_t)bn * pl.pb;
+    const size_t stage = (size_t)kBM * kPA + (size_t)d.kH * bn * kPA;
     pl.lds_bytes = 2 * stage;
-    const size_t red = (size_t)4 * T * 4 * kWave * 4;
-    if (pl.wgk > 1 && pl.lds_bytes < red) pl.lds_bytes = red;
-    const int b_units = bn * (pl.pb / 16);
-    if (pl.lds_bytes > 160 * 1024 || (b_units + 255) / 256 > 12) return pl;
+    if (pl.wgk > 1) pl.lds_bytes = (size_t)12 * pl.nb * T * 4 * kWave * 4;  // direct kernel: hand-over area only
+    if (pl.lds_bytes > 160 * 1024) return pl;
+    pl.part_slots = (int64_t)pl.tiles_m * pl.tiles_n * wgn * 16 * pl.nb * T * kWave;
     pl.ok = true;
     return pl;
 }
 
-template <int KH, int KW>
+template <int KH, int KW, int WGK, int NB, int PF>
 daq_status launch_dw(const Plan& pl, const DwArgs& a, int wq4, hipStream_t st) {
     const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
-#define DAQ_DW_CASE(Q, K)                                                                                         \
-    if (wq4 == Q && pl.wgk == K) {                                                                                \
-        auto kern = k_dw_mfma<KH, KW, Q, K>;                                                                      \
+#define DAQ_DW_CASE(Q)                                                                                            \
+    if (wq4 == Q) {                                                                                               \
+        auto kern = k_dw_mfma<KH, KW, Q, WGK, NB, PF>;                                                            \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
         DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
         return DAQ_OK;                                                                                            \
     }
-    DAQ_DW_CASE(0, 1) DAQ_DW_CASE(1, 1) DAQ_DW_CASE(2, 1) DAQ_DW_CASE(3, 1)
-    DAQ_DW_CASE(0, 4) DAQ_DW_CASE(1, 4) DAQ_DW_CASE(2, 4) DAQ_DW_CASE(3, 4)
+    if constexpr (KH == 1) {
+        DAQ_DW_CASE(0)
+    } else {
+        DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
+    }
+#undef DAQ_DW_CASE
+    return DAQ_ERR_UNSUPPORTED;
+}
+
+template <int KH, int KW, int NB, int PFD>
+daq_status launch_dw_direct(const Plan& pl, const DwArgs& a, int wq4, hipStream_t st) {
+    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+#define DAQ_DW_CASE(Q)                                                                                            \
+    if (wq4 == Q) {                                                                                               \
+        auto kern = k_dw_direct<KH, KW, Q, NB, PFD>;                                                              \
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
+                                (int)pl.lds_bytes) != hipSuccess)                                                 \
+            return DAQ_ERR_HIP;                                                                                   \
+        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
+        return DAQ_OK;                                                                                            \
+    }
+    if constexpr (KH == 1) {
+        DAQ_DW_CASE(0)
+    } else {
+        DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
+    }
 #undef DAQ_DW_CASE
     return DAQ_ERR_UNSUPPORTED;
 }
@@ -332,7 +603,9 @@ daq_status launch_dw(const Plan& pl, const DwArgs& a, int wq4, hipStream_t st) {
 bool bwd_filter_mfma_supported(const daq_conv_desc& d) { return make_plan(d).ok; }
 
 size_t bwd_filter_mfma_ws_bytes(const daq_conv_desc& d) {
-    return (size_t)round_up((int64_t)d.Cout * (d.Cin / d.groups) * d.kH * d.kW * 4, 256);
+    const Plan pl = make_plan(d);
+    if (!pl.ok || pl.splits == 1) return 0;
+    return (size_t)round_up(pl.part_slots * pl.splits * 4, 256);
 }
 
 daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
@@ -342,11 +615,6 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     daq_layout Lx, Lg;
     if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
     const int T = d.kH * d.kW;
-    const int64_t n = (int64_t)d.Cout * d.Cin * T;
-    int32_t* wsi = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
-    if (pl.splits > 1)
-        DAQ_LAUNCH("zero_acc", st,
-                   hipLaunchKernelGGL(k_zero_i32, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, wsi, n));
     DwArgs a{};
     a.g = vq;
     a.x = qx;
@@ -355,23 +623,29 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     a.Cout = d.Cout;
     a.Cin = d.Cin;
     a.row_pitch = Lx.row_pitch;
-    a.pb = pl.pb;
     a.nchunks = pl.nchunks;
     a.splits = pl.splits;
     a.tiles_n = pl.tiles_n;
-    a.ws = wsi;
+    a.tiles_m = pl.tiles_m;
+    a.part = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
     a.s_x = s_x;
     a.s_chan = s_chan;
     a.dW = dW;
     a.acc_out = acc;
     daq_status rc;
-    if (d.kH == 3) rc = launch_dw<3, 3>(pl, a, Lx.row_pitch & 3, st);
-    else rc = launch_dw<1, 1>(pl, a, 0, st);
+    const int wq4 = Lx.row_pitch & 3;
+    if (d.kH == 3)
+        rc = (pl.wgk == 4) ? launch_dw_direct<3, 3, 1, 3>(pl, a, wq4, st) : launch_dw<3, 3, 1, 1, 1>(pl, a, wq4, st);
+    else
+        rc = (pl.wgk == 4) ? launch_dw_direct<1, 1, 4, 4>(pl, a, 0, st) : launch_dw<1, 1, 1, 4, 1>(pl, a, 0, st);
     if (rc != DAQ_OK) return rc;
-    if (pl.splits > 1)
-        DAQ_LAUNCH("dw_epilogue", st,
-               hipLaunchKernelGGL(k_dw_epilogue, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, wsi, n,
-                                  d.Cin * T, s_x, s_chan, dW, acc));
+    if (pl.splits > 1) {
+        const int wgn = 4 / pl.wgk;
+        DAQ_LAUNCH("dw_reduce", st,
+                   hipLaunchKernelGGL(k_dw_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st,
+                                      a.part, pl.splits, pl.tiles_n, wgn, pl.nb, T, d.Cout, d.Cin, s_x, s_chan, dW,
+                                      acc));
+    }
     return DAQ_OK;
 }
 

@@ -9,8 +9,10 @@
 // so that an accumulator tile holds 16 consecutive pixels of one output channel per register and
 // the fp32 NCHW result is written in 64-byte runs.  Each lane fetches the 16 contiguous channel
 // bytes of its (pixel, tap) straight from global memory (L1/L2 absorb the tap re-reads) with
-// out-of-image and stride-skipped taps predicated to zero; the filter chunk is staged in LDS and
-// shared by the four waves.  A wave owns a 64 (rows) x 64 (pixels) tile, a workgroup 64 x 256.
+// out-of-image and stride-skipped taps predicated to zero, through a register ring nine steps deep
+// so that the fetches of a whole 3x3 tap set are in flight together; the filter slices of those
+// steps are staged in LDS and shared by the four waves.  A wave owns a 64 (rows) x 64 (pixels) tile,
+// a workgroup 64 x 256.
 #include "daq_internal.h"
 
 namespace daq {
@@ -24,7 +26,30 @@ constexpr int kPxWave = 64;      // pixels per wave
 constexpr int kPxWg = 256;       // pixels per workgroup
 constexpr int kKc = 64;          // contraction bytes per MFMA step
 constexpr int kWPitch = kKc + 16;  // LDS pitch of a filter row: rotates banks between rows
-constexpr int kTapGroup = 9;     // taps staged in LDS at a time
+constexpr int kRing = 9;         // (tap, channel chunk) steps in flight / staged at a time
+
+// Exact unsigned division by an invariant divisor (Granlund-Montgomery round-up multiplier).
+struct FastDiv {
+    uint32_t mul;
+    int32_t shift;
+    int32_t one;
+};
+FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f{};
+    f.one = (d == 1);
+    int L = 0;
+    while (((uint64_t)1 << L) < d) ++L;
+    f.shift = L > 0 ? L - 1 : 0;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << L) - d)) / d + 1);
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
+    if (f.one) return x;
+    const uint32_t t = __umulhi(x, f.mul);
+    return (t + ((x - t) >> 1)) >> f.shift;
+}
+
+constexpr int kMaxK = 8;  // largest filter extent the tap tables hold
 
 struct NhwcArgs {
     const int8_t* src;   // pixel operand, NHWC [N][Hs][Ws][cp]
@@ -35,14 +60,23 @@ struct NhwcArgs {
     int kH, kW, sH, sW, pH, pW, dH, dW;
     int backward;        // 1: source pixel = (dst + pad - tap*dil) / stride when divisible; 0: dst*stride + tap*dil - pad
     int tiles_px;
+    // Source coordinate of (dst, tap) without a division in the kernel.  Per destination coordinate the
+    // kernel keeps (A, R); per tap the host tabulates (dq, dr); source = A + dq, valid iff R == dr and
+    // 0 <= source < extent.  forward: A = dst*stride - pad, R = 0, dq = tap*dil, dr = 0.
+    // backward: A = (dst+pad)/stride, R = (dst+pad)%stride, dq = -(tap*dil/stride), dr = tap*dil%stride.
+    int16_t dq_h[kMaxK], dr_h[kMaxK], dq_w[kMaxK], dr_w[kMaxK];
+    FastDiv div_hw, div_w, div_sh, div_sw;
     const float* s_a;
     const float* s_b;
     float* out;          // fp32 [N][Crow][Hd][Wd]
     int32_t* acc_out;    // optional raw accumulators, same shape
 };
 
-__global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
-    __shared__ __align__(16) int8_t wl[kTapGroup * kRows * kWPitch];  // 46080 B
+// D = depth of the pixel-fragment register ring = number of (tap, channel chunk) steps whose filter
+// slices are staged in LDS at a time.
+template <int D>
+__global__ __launch_bounds__(256, 2) void k_nhwc_mfma(NhwcArgs p) {
+    __shared__ __align__(16) int8_t wl[D * kRows * kWPitch];
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int li = lane & 15, lg = lane >> 4;
@@ -52,19 +86,34 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
     const int taps = p.kH * p.kW;
     const int HWd = p.Hd * p.Wd;
     const int64_t total_px = (int64_t)p.N * HWd;
+    const int nkc = (p.cp + kKc - 1) / kKc;
+    const int NS = nkc * taps;  // steps: channel chunk outer, tap inner
 
-    // the four 16-pixel groups of this lane's wave: image base, row, column
-    int pn[4], ph[4], pw[4];
+    // the four 16-pixel groups of this lane's wave: image base offset and the (A, R) pair of row and column
+    int64_t pbase[4];
+    int pn[4], ph[4], pw[4], ah[4], rh[4], aw[4], rw[4];
     bool pv[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int64_t P = (int64_t)tp * kPxWg + wave * kPxWave + b * 16 + li;
         pv[b] = P < total_px;
-        const int64_t Pc = pv[b] ? P : 0;
-        pn[b] = (int)(Pc / HWd);
-        const int r = (int)(Pc - (int64_t)pn[b] * HWd);
-        ph[b] = r / p.Wd;
-        pw[b] = r - ph[b] * p.Wd;
+        const uint32_t Pc = pv[b] ? (uint32_t)P : 0u;
+        pn[b] = (int)fdiv(Pc, p.div_hw);
+        const uint32_t r = Pc - (uint32_t)pn[b] * (uint32_t)HWd;
+        ph[b] = (int)fdiv(r, p.div_w);
+        pw[b] = (int)r - ph[b] * p.Wd;
+        pbase[b] = (int64_t)pn[b] * p.Hs * p.Ws * p.cp + 16 * lg;
+        if (p.backward) {
+            ah[b] = (int)fdiv((uint32_t)(ph[b] + p.pH), p.div_sh);
+            rh[b] = ph[b] + p.pH - ah[b] * p.sH;
+            aw[b] = (int)fdiv((uint32_t)(pw[b] + p.pW), p.div_sw);
+            rw[b] = pw[b] + p.pW - aw[b] * p.sW;
+        } else {
+            ah[b] = ph[b] * p.sH - p.pH;
+            rh[b] = 0;
+            aw[b] = pw[b] * p.sW - p.pW;
+            rw[b] = 0;
+        }
     }
 
     v4i acc[4][4];
@@ -73,76 +122,67 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
 #pragma unroll
         for (int b = 0; b < 4; ++b) acc[m][b] = v4i{0, 0, 0, 0};
 
-    // 16 channel bytes of (pixel group b, tap, channel chunk kc) for this lane, or zeros
-    auto load_b = [&](int tap, int kc, v4i (&out)[4]) {
-        const int kh = tap / p.kW, kw = tap - kh * p.kW;
-        const int k = kc + 16 * lg;
+    // 16 channel bytes of (pixel group b, tap (kh, kw), channel chunk kci) for this lane, or zeros
+    auto load_b = [&](int kci, int kh, int kw, v4i (&out)[4]) {
+        const int k = kci * kKc;
+        const bool kok = k + 16 * lg < p.cp;
+        const int dqh = p.dq_h[kh], drh = p.dr_h[kh], dqw = p.dq_w[kw], drw = p.dr_w[kw];
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
-            int hs, ws;
-            bool ok = pv[b] && k < p.cp;
-            if (p.backward) {
-                const int hn = ph[b] + p.pH - kh * p.dH, wn = pw[b] + p.pW - kw * p.dW;
-                hs = hn / p.sH;
-                ws = wn / p.sW;
-                ok = ok && hn >= 0 && wn >= 0 && hs * p.sH == hn && ws * p.sW == wn && hs < p.Hs && ws < p.Ws;
-            } else {
-                hs = ph[b] * p.sH + kh * p.dH - p.pH;
-                ws = pw[b] * p.sW + kw * p.dW - p.pW;
-                ok = ok && hs >= 0 && ws >= 0 && hs < p.Hs && ws < p.Ws;
-            }
-            if (ok) {
-                const int64_t off = (((int64_t)pn[b] * p.Hs + hs) * p.Ws + ws) * p.cp + k;
-                out[b] = *reinterpret_cast<const v4i*>(p.src + off);
-            } else {
+            const int hs = ah[b] + dqh, ws = aw[b] + dqw;
+            const bool ok = pv[b] && kok && rh[b] == drh && rw[b] == drw && (unsigned)hs < (unsigned)p.Hs &&
+                            (unsigned)ws < (unsigned)p.Ws;
+            if (ok)
+                out[b] = *reinterpret_cast<const v4i*>(p.src + pbase[b] + (int64_t)((hs * p.Ws + ws) * p.cp + k));
+            else
                 out[b] = v4i{0, 0, 0, 0};
-            }
         }
     };
 
-    const int nkc = (p.cp + kKc - 1) / kKc;
-    v4i bcur[4], bnext[4];
-    load_b(0, 0, bcur);
+    // Steps run channel chunk outer, (kh, kw) inner.  Two cursors walk them without divisions: one for
+    // the step being fetched (D ahead), one for the filter slices being staged.
+    int f_kci = 0, f_kh = 0, f_kw = 0, f_s = 0;
+    auto fetch_advance = [&]() {
+        ++f_s;
+        if (++f_kw == p.kW) { f_kw = 0; if (++f_kh == p.kH) { f_kh = 0; ++f_kci; } }
+    };
+    // fill the ring: the pixel fragments of the first D steps are all in flight together
+    v4i bf[D][4];
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        if (f_s < NS) load_b(f_kci, f_kh, f_kw, bf[d]);
+        fetch_advance();
+    }
 
-    for (int kci = 0; kci < nkc; ++kci) {
-        const int kc = kci * kKc;
-        for (int tg = 0; tg < taps; tg += kTapGroup) {
-            const int tcount = min(kTapGroup, taps - tg);
-            // stage Wp[tg .. tg+tcount)[row0 .. row0+64)[kc .. kc+64) into LDS
-            __syncthreads();
-            const int units = tcount * kRows * (kKc / 16);
-            for (int u = tid; u < units; u += 256) {
-                const int c16 = u & 3;
-                const int row = (u >> 2) % kRows;
-                const int t = (u >> 2) / kRows;
-                const int rg = row0 + row, k = kc + 16 * c16;
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (rg < p.Crow && k < p.kp)
-                    v = *reinterpret_cast<const uint4*>(p.wpk + ((int64_t)(tg + t) * p.Crow + rg) * p.kp + k);
-                *reinterpret_cast<uint4*>(wl + (t * kRows + row) * kWPitch + 16 * c16) = v;
-            }
-            __syncthreads();
-
-            for (int t = 0; t < tcount; ++t) {
-                // prefetch the pixel fragments of the next step while this one multiplies
-                int ntap = tg + t + 1, nkc_i = kci;
-                if (ntap == taps) { ntap = 0; ++nkc_i; }
-                const bool more = nkc_i < nkc;
-                if (more) load_b(ntap, nkc_i * kKc, bnext);
-
+    const int srow = tid >> 2, sc16 = tid & 3;  // this thread stages 16 bytes of filter row srow for every step
+    int w_kci = 0, w_tap = 0;
+    for (int g0 = 0; g0 < NS; g0 += D) {
+        __syncthreads();
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            const int rg = row0 + srow, k = w_kci * kKc + 16 * sc16;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (g0 + d < NS && rg < p.Crow && k < p.kp)
+                v = *reinterpret_cast<const uint4*>(p.wpk + ((int64_t)w_tap * p.Crow + rg) * p.kp + k);
+            *reinterpret_cast<uint4*>(wl + (d * kRows + srow) * kWPitch + 16 * sc16) = v;
+            if (++w_tap == taps) { w_tap = 0; ++w_kci; }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (g0 + d < NS) {
                 v4i a[4];
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
-                    a[m] = *reinterpret_cast<const v4i*>(wl + (t * kRows + 16 * m + li) * kWPitch + 16 * lg);
+                    a[m] = *reinterpret_cast<const v4i*>(wl + (d * kRows + 16 * m + li) * kWPitch + 16 * lg);
 #pragma unroll
                 for (int m = 0; m < 4; ++m)
 #pragma unroll
                     for (int b = 0; b < 4; ++b)
-                        acc[m][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m], bcur[b], acc[m][b], 0, 0, 0);
-                if (more) {
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) bcur[b] = bnext[b];
-                }
+                        acc[m][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m], bf[d][b], acc[m][b], 0, 0, 0);
+                // this ring slot is free: fetch the fragments of the step D ahead
+                if (f_s < NS) load_b(f_kci, f_kh, f_kw, bf[d]);
+                fetch_advance();
             }
         }
     }
@@ -169,15 +209,27 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
 daq_status launch(NhwcArgs& a, hipStream_t st, const char* name) {
     const int64_t total_px = (int64_t)a.N * a.Hd * a.Wd;
     a.tiles_px = (int)ceil_div(total_px, kPxWg);
+    for (int k = 0; k < a.kH; ++k) {
+        a.dq_h[k] = (int16_t)(a.backward ? -(k * a.dH / a.sH) : k * a.dH);
+        a.dr_h[k] = (int16_t)(a.backward ? (k * a.dH) % a.sH : 0);
+    }
+    for (int k = 0; k < a.kW; ++k) {
+        a.dq_w[k] = (int16_t)(a.backward ? -(k * a.dW / a.sW) : k * a.dW);
+        a.dr_w[k] = (int16_t)(a.backward ? (k * a.dW) % a.sW : 0);
+    }
+    a.div_hw = make_fastdiv((uint32_t)(a.Hd * a.Wd));
+    a.div_w = make_fastdiv((uint32_t)a.Wd);
+    a.div_sh = make_fastdiv((uint32_t)a.sH);
+    a.div_sw = make_fastdiv((uint32_t)a.sW);
     const int tiles_r = (int)ceil_div(a.Crow, kRows);
     const dim3 grid((unsigned)((int64_t)a.tiles_px * tiles_r));
-    DAQ_LAUNCH(name, st, hipLaunchKernelGGL(k_nhwc_mfma, grid, dim3(256), 0, st, a));
+    DAQ_LAUNCH(name, st, hipLaunchKernelGGL(k_nhwc_mfma<kRing>, grid, dim3(256), 0, st, a));
     return DAQ_OK;
 }
 
 }  // namespace
 
-bool bwd_data_mfma_supported(const daq_conv_desc& d) { return d.groups == 1; }
+bool bwd_data_mfma_supported(const daq_conv_desc& d) { return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK; }
 
 daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
                               const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
@@ -198,7 +250,7 @@ daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const fl
     return launch(a, st, "conv_bwd_data_mfma");
 }
 
-bool fwd_mfma_supported(const daq_conv_desc& d) { return d.groups == 1; }
+bool fwd_mfma_supported(const daq_conv_desc& d) { return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK; }
 
 daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx, const int8_t* qw, const float* s_x,
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st) {
