@@ -133,15 +133,13 @@ __global__ __launch_bounds__(256) void k_dw_mfma(DwArgs p) {
         const int64_t k0 = (int64_t)chunk * kKC;
 #pragma unroll
         for (int i = 0; i < A_PER_T; ++i)
-            ra[set][i] = (a_off[i] >= 0) ? *reinterpret_cast<const uint4*>(p.g + a_off[i] + k0) : make_uint4(0, 0, 0, 0);
+            ra[set][i] = ld16_or_zero(p.g + a_off[i] + k0, a_off[i] >= 0);
 #pragma unroll
         for (int i = 0; i < B_PER_T; ++i) {
-            if (b_off[i] >= 0) {
-                const v4i_a4 v = *reinterpret_cast<const v4i_a4*>(p.x + b_off[i] + k0);  // dword aligned only
-                rb[set][i] = make_uint4((unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]);
-            } else {
-                rb[set][i] = make_uint4(0, 0, 0, 0);
-            }
+            const bool ok = b_off[i] >= 0;
+            const v4i_a4 v = *reinterpret_cast<const v4i_a4*>(ok ? (const void*)(p.x + b_off[i] + k0)
+                                                                 : (const void*)g_zero64);  // dword aligned only
+            rb[set][i] = make_uint4((unsigned)v[0], (unsigned)v[1], (unsigned)v[2], (unsigned)v[3]);
         }
     };
     auto store_chunk = [&](int buf, int set) {
@@ -316,19 +314,23 @@ __global__ __launch_bounds__(256) void k_dw_direct(DwArgs p) {
     const int s_end = s_begin + per + (unit < rem ? 1 : 0);
 
     const int8_t* ga[4];
+    int gmask[4];
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         const int co = co0 + 16 * m + li;
-        ga[m] = (co < p.Cout) ? p.g + (int64_t)co * p.klen + 16 * lg : nullptr;
+        ga[m] = p.g + (int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * lg;  // rows past Cout read row 0, masked to zero
+        gmask[m] = (co < p.Cout) ? -1 : 0;
     }
     const int8_t* xb[NB][KH];
+    int xmask[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int kh = 0; kh < KH; ++kh) {
             const int ci = ci0 + 16 * nb + li;
             const int r0 = (kh * p.row_pitch) & 3;
-            xb[nb][kh] = (ci < p.Cin) ? p.x + (int64_t)ci * p.x_chan_pitch + 16 * lg + kh * p.row_pitch - r0 : nullptr;
+            xb[nb][kh] = p.x + (int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * lg + kh * p.row_pitch - r0;
+            xmask[nb] = (ci < p.Cin) ? -1 : 0;
         }
 
     v4i acc[4][NT];
@@ -344,22 +346,18 @@ __global__ __launch_bounds__(256) void k_dw_direct(DwArgs p) {
         const int64_t k = (int64_t)s * 64;
 #pragma unroll
         for (int m = 0; m < 4; ++m)
-            ra[slot][m] = ga[m] ? *reinterpret_cast<const v4i*>(ga[m] + k) : v4i{0, 0, 0, 0};
+            ra[slot][m] = *reinterpret_cast<const v4i*>(gmask[m] ? (const void*)(ga[m] + k) : (const void*)g_zero64);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int kh = 0; kh < KH; ++kh) {
-                if (xb[nb][kh]) {
-                    const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(xb[nb][kh] + k);
-                    rlo[slot][nb][kh] = v4i{lo[0], lo[1], lo[2], lo[3]};
-                    if (KW > 1 || ((kh * WQ4) & 3) != 0) {
-                        const v2i_a4 hi = *reinterpret_cast<const v2i_a4*>(xb[nb][kh] + k + 16);
-                        rhi[slot][nb][kh] = v2i{hi[0], hi[1]};
-                    } else {
-                        rhi[slot][nb][kh] = v2i{0, 0};
-                    }
+                const int8_t* src = xmask[nb] ? xb[nb][kh] + k : reinterpret_cast<const int8_t*>(g_zero64);
+                const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(src);
+                rlo[slot][nb][kh] = v4i{lo[0], lo[1], lo[2], lo[3]};
+                if (KW > 1 || ((kh * WQ4) & 3) != 0) {
+                    const v2i_a4 hi = *reinterpret_cast<const v2i_a4*>(src + 16);
+                    rhi[slot][nb][kh] = v2i{hi[0], hi[1]};
                 } else {
-                    rlo[slot][nb][kh] = v4i{0, 0, 0, 0};
                     rhi[slot][nb][kh] = v2i{0, 0};
                 }
             }

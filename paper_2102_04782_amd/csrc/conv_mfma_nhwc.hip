@@ -6,13 +6,19 @@
 //
 //     C[row channel][pixel] = sum over (tap, k)  Wp[tap][row][k] * P[src_pixel(pixel, tap)][k]
 //
-// so that an accumulator tile holds 16 consecutive pixels of one output channel per register and
-// the fp32 NCHW result is written in 64-byte runs.  Each lane fetches the 16 contiguous channel
-// bytes of its (pixel, tap) straight from global memory (L1/L2 absorb the tap re-reads) with
-// out-of-image and stride-skipped taps predicated to zero, through a register ring nine steps deep
-// so that the fetches of a whole 3x3 tap set are in flight together; the filter slices of those
-// steps are staged in LDS and shared by the four waves.  A wave owns a 64 (rows) x 64 (pixels) tile,
-// a workgroup 64 x 256.
+// so that an accumulator register holds 32 consecutive pixels of one output channel across 32 lanes
+// and the fp32 NCHW result is written in 128-byte runs.
+//
+// One step = one (channel chunk of 64, tap).  Per step the workgroup stages a 256-pixel x 64-byte
+// tile of the pixel operand (source pixels shifted by the tap; out-of-image and stride-skipped taps
+// are zero) and a rows x 64-byte filter slice into LDS with coalesced 16-byte loads (four adjacent
+// lanes fetch one pixel's 64 bytes), double buffered, through a register ring that keeps the
+// fetches of the next kRing steps in flight.  The waves multiply with v_mfma_i32_32x32x32_i8
+// (measured at twice the rate of the 16x16x64 form on this chip); fragments are read from LDS as
+// aligned 16-byte vectors, rows padded to 80 bytes so that eight lanes cover all banks.
+//
+// All per-tap index work is hoisted: a thread keeps, for each of the four pixels it stages, a base
+// offset and a bit mask of the taps that hit the image; a tap then only adds a uniform offset.
 #include "daq_internal.h"
 
 namespace daq {
@@ -20,13 +26,13 @@ namespace daq {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kRows = 64;        // row channels per workgroup
-constexpr int kPxWave = 64;      // pixels per wave
-constexpr int kPxWg = 256;       // pixels per workgroup
-constexpr int kKc = 64;          // contraction bytes per MFMA step
-constexpr int kWPitch = kKc + 16;  // LDS pitch of a filter row: rotates banks between rows
-constexpr int kRing = 9;         // (tap, channel chunk) steps in flight / staged at a time
+constexpr int kPxWg = 256;         // pixels per workgroup
+constexpr int kKc = 64;            // contraction bytes per step (two MFMA K-steps of 32)
+constexpr int kPitch = kKc + 16;   // LDS pitch of a staged row
+constexpr int kRing = 4;           // steps whose global loads are in flight beyond the one being staged
+constexpr int kMaxK = 8;           // largest filter extent (tap masks hold 64 taps)
 
 // Exact unsigned division by an invariant divisor (Granlund-Montgomery round-up multiplier).
 struct FastDiv {
@@ -49,8 +55,6 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
     return (t + ((x - t) >> 1)) >> f.shift;
 }
 
-constexpr int kMaxK = 8;  // largest filter extent the tap tables hold
-
 struct NhwcArgs {
     const int8_t* src;   // pixel operand, NHWC [N][Hs][Ws][cp]
     const int8_t* wpk;   // filter operand [taps][Crow][kp]
@@ -58,13 +62,13 @@ struct NhwcArgs {
     int Hd, Wd;          // extents of the result's spatial axes
     int Crow, kp;        // result channels; pitch of a filter row
     int kH, kW, sH, sW, pH, pW, dH, dW;
-    int backward;        // 1: source pixel = (dst + pad - tap*dil) / stride when divisible; 0: dst*stride + tap*dil - pad
+    int backward;        // 1: data gradient (source = (dst + pad - tap*dil) / stride when divisible); 0: forward
     int tiles_px;
     // Source coordinate of (dst, tap) without a division in the kernel.  Per destination coordinate the
     // kernel keeps (A, R); per tap the host tabulates (dq, dr); source = A + dq, valid iff R == dr and
     // 0 <= source < extent.  forward: A = dst*stride - pad, R = 0, dq = tap*dil, dr = 0.
     // backward: A = (dst+pad)/stride, R = (dst+pad)%stride, dq = -(tap*dil/stride), dr = tap*dil%stride.
-    int16_t dq_h[kMaxK], dr_h[kMaxK], dq_w[kMaxK], dr_w[kMaxK];
+    int16_t tab[4 * kMaxK];  // dq_h | dr_h | dq_w | dr_w, kMaxK entries each
     FastDiv div_hw, div_w, div_sh, div_sw;
     const float* s_a;
     const float* s_b;
@@ -72,135 +76,188 @@ struct NhwcArgs {
     int32_t* acc_out;    // optional raw accumulators, same shape
 };
 
-// D = depth of the pixel-fragment register ring = number of (tap, channel chunk) steps whose filter
-// slices are staged in LDS at a time.
-template <int D>
-__global__ __launch_bounds__(256, 2) void k_nhwc_mfma(NhwcArgs p) {
-    __shared__ __align__(16) int8_t wl[D * kRows * kWPitch];
+// WR = waves along the row (output channel) axis: 1 -> 64 rows x 256 pixels per workgroup with
+// 64 x 64 wave tiles, 2 -> 128 rows x 256 pixels with 64 x 128 wave tiles.
+template <int WR>
+__global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
+    constexpr int ROWS = 64 * WR;
+    constexpr int WPX = 4 / WR;               // waves along pixels
+    constexpr int PXW = kPxWg / WPX;          // pixels per wave
+    constexpr int BF = PXW / 32;              // pixel fragments per wave
+    constexpr int A_PER_T = ROWS * 4 / 256;   // 16-byte units of the filter slice per thread
+    constexpr int A_BYTES = ROWS * kPitch;
+    constexpr int STAGE = A_BYTES + kPxWg * kPitch;
+    __shared__ __align__(16) int8_t lds[2 * STAGE];
+    __shared__ int tap_off[kMaxK * kMaxK];  // byte offset a tap adds to a pixel's anchor (kept out of the vector-memory queue)
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int li = lane & 15, lg = lane >> 4;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wr = wave % WR, wp = wave / WR;
     const int tp = blockIdx.x % p.tiles_px;
     const int tr = blockIdx.x / p.tiles_px;
-    const int row0 = tr * kRows;
+    const int row0 = tr * ROWS;
     const int taps = p.kH * p.kW;
     const int HWd = p.Hd * p.Wd;
-    const int64_t total_px = (int64_t)p.N * HWd;
+    const uint32_t total_px = (uint32_t)p.N * (uint32_t)HWd;
     const int nkc = (p.cp + kKc - 1) / kKc;
     const int NS = nkc * taps;  // steps: channel chunk outer, tap inner
 
-    // the four 16-pixel groups of this lane's wave: image base offset and the (A, R) pair of row and column
-    int64_t pbase[4];
-    int pn[4], ph[4], pw[4], ah[4], rh[4], aw[4], rw[4];
-    bool pv[4];
+    // The tap tables go to LDS once: indexing the kernel-argument copy with a loop variable costs a
+    // vector-memory round trip per access.
+    __shared__ int tab[4 * kMaxK];
+    if (tid < 4 * kMaxK) tab[tid] = p.tab[tid];
+    __syncthreads();
+    const int* dq_h = tab;
+    const int* dr_h = tab + kMaxK;
+    const int* dq_w = tab + 2 * kMaxK;
+    const int* dr_w = tab + 3 * kMaxK;
+
+    // ---- staging assignment: this thread fetches chunk sc (16 bytes) of pixels spx + 64*i ----
+    const int sc = tid & 3, spx = tid >> 2;
+    int64_t poff[4];      // byte offset of the pixel's source anchor (A_h, A_w) in the source tensor, plus chunk
+    uint64_t pmask[4];    // bit t set: tap t reads inside the image for this pixel
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        const int64_t P = (int64_t)tp * kPxWg + wave * kPxWave + b * 16 + li;
-        pv[b] = P < total_px;
-        const uint32_t Pc = pv[b] ? (uint32_t)P : 0u;
-        pn[b] = (int)fdiv(Pc, p.div_hw);
-        const uint32_t r = Pc - (uint32_t)pn[b] * (uint32_t)HWd;
-        ph[b] = (int)fdiv(r, p.div_w);
-        pw[b] = (int)r - ph[b] * p.Wd;
-        pbase[b] = (int64_t)pn[b] * p.Hs * p.Ws * p.cp + 16 * lg;
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t P = (uint32_t)tp * kPxWg + spx + 64 * i;
+        const bool pv = P < total_px;
+        const uint32_t Pc = pv ? P : 0u;
+        const int n = (int)fdiv(Pc, p.div_hw);
+        const uint32_t r = Pc - (uint32_t)n * (uint32_t)HWd;
+        const int h = (int)fdiv(r, p.div_w);
+        const int w = (int)r - h * p.Wd;
+        int ah, rh, aw, rw;
         if (p.backward) {
-            ah[b] = (int)fdiv((uint32_t)(ph[b] + p.pH), p.div_sh);
-            rh[b] = ph[b] + p.pH - ah[b] * p.sH;
-            aw[b] = (int)fdiv((uint32_t)(pw[b] + p.pW), p.div_sw);
-            rw[b] = pw[b] + p.pW - aw[b] * p.sW;
+            ah = (int)fdiv((uint32_t)(h + p.pH), p.div_sh);
+            rh = h + p.pH - ah * p.sH;
+            aw = (int)fdiv((uint32_t)(w + p.pW), p.div_sw);
+            rw = w + p.pW - aw * p.sW;
         } else {
-            ah[b] = ph[b] * p.sH - p.pH;
-            rh[b] = 0;
-            aw[b] = pw[b] * p.sW - p.pW;
-            rw[b] = 0;
+            ah = h * p.sH - p.pH;
+            rh = 0;
+            aw = w * p.sW - p.pW;
+            rw = 0;
         }
+        poff[i] = (((int64_t)n * p.Hs + ah) * p.Ws + aw) * p.cp + 16 * sc;
+        uint64_t m = 0;
+        if (pv) {
+            for (int kh = 0; kh < p.kH; ++kh) {
+                const int hs = ah + dq_h[kh];
+                const bool hok = rh == dr_h[kh] && (unsigned)hs < (unsigned)p.Hs;
+                for (int kw = 0; kw < p.kW; ++kw) {
+                    const int ws = aw + dq_w[kw];
+                    const bool ok = hok && rw == dr_w[kw] && (unsigned)ws < (unsigned)p.Ws;
+                    m |= (uint64_t)ok << (kh * p.kW + kw);
+                }
+            }
+        }
+        pmask[i] = m;
     }
+    if (tid < taps) {
+        const int kh = tid / p.kW, kw = tid - kh * p.kW;
+        tap_off[tid] = (dq_h[kh] * p.Ws + dq_w[kw]) * p.cp;
+    }
+    __syncthreads();
+    // filter slice: unit j of this thread is row srow + 64*j, chunk sc
+    const int srow = tid >> 2;
 
-    v4i acc[4][4];
-#pragma unroll
-    for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[m][b] = v4i{0, 0, 0, 0};
-
-    // 16 channel bytes of (pixel group b, tap (kh, kw), channel chunk kci) for this lane, or zeros
-    auto load_b = [&](int kci, int kh, int kw, v4i (&out)[4]) {
-        const int k = kci * kKc;
-        const bool kok = k + 16 * lg < p.cp;
-        const int dqh = p.dq_h[kh], drh = p.dr_h[kh], dqw = p.dq_w[kw], drw = p.dr_w[kw];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int hs = ah[b] + dqh, ws = aw[b] + dqw;
-            const bool ok = pv[b] && kok && rh[b] == drh && rw[b] == drw && (unsigned)hs < (unsigned)p.Hs &&
-                            (unsigned)ws < (unsigned)p.Ws;
-            if (ok)
-                out[b] = *reinterpret_cast<const v4i*>(p.src + pbase[b] + (int64_t)((hs * p.Ws + ws) * p.cp + k));
-            else
-                out[b] = v4i{0, 0, 0, 0};
-        }
-    };
-
-    // Steps run channel chunk outer, (kh, kw) inner.  Two cursors walk them without divisions: one for
-    // the step being fetched (D ahead), one for the filter slices being staged.
+    // cursor over the steps being fetched
     int f_kci = 0, f_kh = 0, f_kw = 0, f_s = 0;
-    auto fetch_advance = [&]() {
+    uint4 ra[kRing][A_PER_T], rb[kRing][4];
+    // Always issues the same number of loads (past the last step they read the zero block), so the
+    // compiler can count outstanding loads exactly and the ring really stays kRing steps deep.
+    auto fetch = [&](int slot) {
+        const bool live = f_s < NS;
+        const int tap = f_kh * p.kW + f_kw;
+        const int k = f_kci * kKc;
+        const bool kok = live && k + 16 * sc < p.cp;
+        const int toff = tap_off[live ? tap : 0] + k;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = kok && ((pmask[i] >> tap) & 1u);
+            rb[slot][i] = ld16_or_zero(p.src + poff[i] + toff, ok);
+        }
+#pragma unroll
+        for (int j = 0; j < A_PER_T; ++j) {
+            const int rg = row0 + srow + 64 * j;
+            const bool ok = live && rg < p.Crow && k + 16 * sc < p.kp;
+            ra[slot][j] = ld16_or_zero(p.wpk + ((int64_t)tap * p.Crow + rg) * p.kp + k + 16 * sc, ok);
+        }
         ++f_s;
         if (++f_kw == p.kW) { f_kw = 0; if (++f_kh == p.kH) { f_kh = 0; ++f_kci; } }
     };
-    // fill the ring: the pixel fragments of the first D steps are all in flight together
-    v4i bf[D][4];
+    auto stage = [&](int buf, int slot) {
+        int8_t* A = lds + buf * STAGE;
+        int8_t* B = A + A_BYTES;
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
-        if (f_s < NS) load_b(f_kci, f_kh, f_kw, bf[d]);
-        fetch_advance();
-    }
+        for (int j = 0; j < A_PER_T; ++j)
+            *reinterpret_cast<uint4*>(A + (srow + 64 * j) * kPitch + 16 * sc) = ra[slot][j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<uint4*>(B + (spx + 64 * i) * kPitch + 16 * sc) = rb[slot][i];
+    };
 
-    const int srow = tid >> 2, sc16 = tid & 3;  // this thread stages 16 bytes of filter row srow for every step
-    int w_kci = 0, w_tap = 0;
-    for (int g0 = 0; g0 < NS; g0 += D) {
-        __syncthreads();
+    v16i acc[2][BF];
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            const int rg = row0 + srow, k = w_kci * kKc + 16 * sc16;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (g0 + d < NS && rg < p.Crow && k < p.kp)
-                v = *reinterpret_cast<const uint4*>(p.wpk + ((int64_t)w_tap * p.Crow + rg) * p.kp + k);
-            *reinterpret_cast<uint4*>(wl + (d * kRows + srow) * kWPitch + 16 * sc16) = v;
-            if (++w_tap == taps) { w_tap = 0; ++w_kci; }
-        }
-        __syncthreads();
+    for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (g0 + d < NS) {
-                v4i a[4];
+        for (int b = 0; b < BF; ++b)
 #pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    a[m] = *reinterpret_cast<const v4i*>(wl + (d * kRows + 16 * m + li) * kWPitch + 16 * lg);
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
+
+    // prologue: step 0 into LDS, steps 1..kRing in flight
+    fetch(0);
+    stage(0, 0);
 #pragma unroll
-                for (int m = 0; m < 4; ++m)
+    for (int d = 1; d <= kRing; ++d) fetch(d % kRing);
+    __syncthreads();
+
+    for (int base = 0; base < NS; base += kRing) {
 #pragma unroll
-                    for (int b = 0; b < 4; ++b)
-                        acc[m][b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[m], bf[d][b], acc[m][b], 0, 0, 0);
-                // this ring slot is free: fetch the fragments of the step D ahead
-                if (f_s < NS) load_b(f_kci, f_kh, f_kw, bf[d]);
-                fetch_advance();
+        for (int u = 0; u < kRing; ++u) {
+            const int s = base + u;
+            if (s < NS) {  // uniform; only the multiplies are skipped on the padded tail steps
+                const int8_t* A = lds + (s & 1) * STAGE + (wr * 64 + l32) * kPitch + 16 * lh;
+                const int8_t* B = lds + (s & 1) * STAGE + A_BYTES + (wp * PXW + l32) * kPitch + 16 * lh;
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    v4i a[2], b[BF];
+#pragma unroll
+                    for (int x = 0; x < 2; ++x) a[x] = *reinterpret_cast<const v4i*>(A + x * 32 * kPitch + 32 * sub);
+#pragma unroll
+                    for (int y = 0; y < BF; ++y) b[y] = *reinterpret_cast<const v4i*>(B + y * 32 * kPitch + 32 * sub);
+#pragma unroll
+                    for (int x = 0; x < 2; ++x)
+#pragma unroll
+                        for (int y = 0; y < BF; ++y)
+                            acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[x], b[y], acc[x][y], 0, 0, 0);
+                }
             }
+            // step s+1 moves from its ring slot to the other LDS buffer; the slot is refilled kRing steps ahead
+            const int nslot = (u + 1) % kRing;
+            stage((s + 1) & 1, nslot);
+            fetch(nslot);
+            __syncthreads();
         }
     }
 
-    // epilogue: register r of tile (m, b) is row 16m + 4*lg + r, pixel group b, pixel li
+    // epilogue: register r of tile (x, y) is row 32x + 8*(r/4) + 4*lh + r%4, pixel 32y + l32
     const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-        if (!pv[b]) continue;
+    for (int y = 0; y < BF; ++y) {
+        const uint32_t P = (uint32_t)tp * kPxWg + wp * PXW + 32 * y + l32;
+        if (P >= total_px) continue;
+        const int n = (int)fdiv(P, p.div_hw);
+        const uint32_t rem = P - (uint32_t)n * (uint32_t)HWd;
+        const int64_t pix = (int64_t)n * p.Crow * HWd + rem;
 #pragma unroll
-        for (int m = 0; m < 4; ++m)
+        for (int x = 0; x < 2; ++x)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = row0 + 16 * m + 4 * lg + r;
+            for (int r = 0; r < 16; ++r) {
+                const int row = row0 + wr * 64 + 32 * x + 8 * (r >> 2) + 4 * lh + (r & 3);
                 if (row < p.Crow) {
-                    const int64_t off = (((int64_t)pn[b] * p.Crow + row) * p.Hd + ph[b]) * p.Wd + pw[b];
-                    p.out[off] = (float)acc[m][b][r] * scale;
-                    if (p.acc_out) p.acc_out[off] = acc[m][b][r];
+                    const int64_t off = pix + (int64_t)row * HWd;
+                    p.out[off] = (float)acc[x][y][r] * scale;
+                    if (p.acc_out) p.acc_out[off] = acc[x][y][r];
                 }
             }
     }
@@ -210,26 +267,34 @@ daq_status launch(NhwcArgs& a, hipStream_t st, const char* name) {
     const int64_t total_px = (int64_t)a.N * a.Hd * a.Wd;
     a.tiles_px = (int)ceil_div(total_px, kPxWg);
     for (int k = 0; k < a.kH; ++k) {
-        a.dq_h[k] = (int16_t)(a.backward ? -(k * a.dH / a.sH) : k * a.dH);
-        a.dr_h[k] = (int16_t)(a.backward ? (k * a.dH) % a.sH : 0);
+        a.tab[k] = (int16_t)(a.backward ? -(k * a.dH / a.sH) : k * a.dH);
+        a.tab[kMaxK + k] = (int16_t)(a.backward ? (k * a.dH) % a.sH : 0);
     }
     for (int k = 0; k < a.kW; ++k) {
-        a.dq_w[k] = (int16_t)(a.backward ? -(k * a.dW / a.sW) : k * a.dW);
-        a.dr_w[k] = (int16_t)(a.backward ? (k * a.dW) % a.sW : 0);
+        a.tab[2 * kMaxK + k] = (int16_t)(a.backward ? -(k * a.dW / a.sW) : k * a.dW);
+        a.tab[3 * kMaxK + k] = (int16_t)(a.backward ? (k * a.dW) % a.sW : 0);
     }
     a.div_hw = make_fastdiv((uint32_t)(a.Hd * a.Wd));
     a.div_w = make_fastdiv((uint32_t)a.Wd);
     a.div_sh = make_fastdiv((uint32_t)a.sH);
     a.div_sw = make_fastdiv((uint32_t)a.sW);
-    const int tiles_r = (int)ceil_div(a.Crow, kRows);
-    const dim3 grid((unsigned)((int64_t)a.tiles_px * tiles_r));
-    DAQ_LAUNCH(name, st, hipLaunchKernelGGL(k_nhwc_mfma<kRing>, grid, dim3(256), 0, st, a));
+    if (a.Crow > 64) {
+        const dim3 grid((unsigned)((int64_t)a.tiles_px * ceil_div(a.Crow, 128)));
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(k_nhwc_mfma<2>, grid, dim3(256), 0, st, a));
+    } else {
+        const dim3 grid((unsigned)a.tiles_px);
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(k_nhwc_mfma<1>, grid, dim3(256), 0, st, a));
+    }
     return DAQ_OK;
+}
+
+bool nhwc_supported(const daq_conv_desc& d) {
+    return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK;
 }
 
 }  // namespace
 
-bool bwd_data_mfma_supported(const daq_conv_desc& d) { return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK; }
+bool bwd_data_mfma_supported(const daq_conv_desc& d) { return nhwc_supported(d); }
 
 daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
                               const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
@@ -250,7 +315,7 @@ daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const fl
     return launch(a, st, "conv_bwd_data_mfma");
 }
 
-bool fwd_mfma_supported(const daq_conv_desc& d) { return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK; }
+bool fwd_mfma_supported(const daq_conv_desc& d) { return nhwc_supported(d); }
 
 daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx, const int8_t* qw, const float* s_x,
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st) {

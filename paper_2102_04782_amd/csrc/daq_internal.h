@@ -34,6 +34,19 @@ void prof_pop(hipStream_t s);                     // records the stop event
         if (hipGetLastError() != hipSuccess) return DAQ_ERR_HIP; \
     } while (0)
 
+// ---- predicated loads without control flow ------------------------------------------------
+// A load guarded by an `if` becomes an exec-masked branch with a full memory wait at its join, and a
+// select applied to the loaded value makes the compiler wait right behind the load; either way a
+// software pipeline is serialised.  These helpers always issue the load and redirect a false
+// predicate to 64 bytes of zeros in device memory, so nothing depends on the value until it is used.
+static __device__ uint4 g_zero64[4];  // zero-initialised, never written (kept non-const so it shares the global address space)
+__device__ __forceinline__ uint4 ld16_or_zero(const void* p, bool ok) {
+    return *reinterpret_cast<const uint4*>(ok ? p : (const void*)g_zero64);
+}
+__device__ __forceinline__ float ldf_or_zero(const float* p, bool ok) {
+    return *(ok ? p : reinterpret_cast<const float*>(g_zero64));
+}
+
 // ---- device-side view of an int8 layout ----------------------------------------------------
 struct CnhwView {
     int64_t chan_pitch, plane_pitch, lead;

@@ -147,12 +147,12 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int m = m0 + 4 * (tid + u * kBlock);
-            if (m < M) {
-                const int n = m / HW, i = m - n * HW;
-                v[u] = *reinterpret_cast<const float4*>(g + ((int64_t)n * C + c) * HW + i);
-            } else {
-                v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+            const bool ok = m < M;
+            const int mc = ok ? m : 0;
+            const int n = mc / HW, i = mc - n * HW;
+            const uint4 raw = ld16_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
+            v[u] = make_float4(__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z),
+                               __uint_as_float(raw.w));
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -166,12 +166,10 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
             const int m = m0 + tid + u * kBlock;
-            if (m < M) {
-                const int n = m / HW, i = m - n * HW;
-                v[u] = g[((int64_t)n * C + c) * HW + i];
-            } else {
-                v[u] = 0.0f;
-            }
+            const bool ok = m < M;
+            const int mc = ok ? m : 0;
+            const int n = mc / HW, i = mc - n * HW;
+            v[u] = ldf_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
         }
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -254,7 +252,7 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
     const float* gp = g + ((int64_t)n * C + c0) * HW + px;
     float x[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) x[i] = (vpx && c0 + i < C) ? gp[(int64_t)i * HW] : 0.0f;
+    for (int i = 0; i < 16; ++i) x[i] = ldf_or_zero(gp + (int64_t)i * HW, vpx && c0 + i < C);
 
     uint32_t mycnt = 0;
     uint32_t w[4] = {0u, 0u, 0u, 0u};
@@ -354,10 +352,9 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
         if (o + i >= 0) {
             const int h = r * L.phases_h + ph - L.org_h;
             const int w = col * L.phases_w + pw - L.org_w;
-            if (n < L.N && h >= 0 && h < L.H && w >= 0 && w < L.W) {
-                idx[i] = (((int64_t)n * L.C + c) * L.H + h) * L.W + w;
-                x[i] = src[idx[i]];
-            }
+            const bool ok = n < L.N && h >= 0 && h < L.H && w >= 0 && w < L.W;
+            idx[i] = ok ? (((int64_t)n * L.C + c) * L.H + h) * L.W + w : -1;
+            x[i] = ldf_or_zero(src + idx[i], ok);
             if (++col == L.row_pitch) {
                 col = 0;
                 if (++r == L.img_rows) { r = 0; ++n; }
