@@ -58,23 +58,32 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
 struct NhwcArgs {
     const int8_t* src;   // pixel operand, NHWC [N][Hs][Ws][cp]
     const int8_t* wpk;   // filter operand [taps][Crow][kp]
+    uint32_t src_bytes, wpk_bytes;  // extents of the two buffers (below 2^31: offsets are 32-bit)
     int N, Hs, Ws, cp;   // source extents and channel pitch (the contraction length, multiple of 16)
     int Hd, Wd;          // extents of the result's spatial axes
     int Crow, kp;        // result channels; pitch of a filter row
-    int kH, kW, sH, sW, pH, pW, dH, dW;
+    int kH, kW, sH, sW, pH, pW;
     int backward;        // 1: data gradient (source = (dst + pad - tap*dil) / stride when divisible); 0: forward
     int tiles_px;
     // Source coordinate of (dst, tap) without a division in the kernel.  Per destination coordinate the
     // kernel keeps (A, R); per tap the host tabulates (dq, dr); source = A + dq, valid iff R == dr and
     // 0 <= source < extent.  forward: A = dst*stride - pad, R = 0, dq = tap*dil, dr = 0.
     // backward: A = (dst+pad)/stride, R = (dst+pad)%stride, dq = -(tap*dil/stride), dr = tap*dil%stride.
-    int16_t tab[4 * kMaxK];  // dq_h | dr_h | dq_w | dr_w, kMaxK entries each
+    // 32-bit entries: a uniform index then costs a scalar load, not a vector-memory round trip.
+    int dq_h[kMaxK], dr_h[kMaxK], dq_w[kMaxK], dr_w[kMaxK];
+    int tap_off[kMaxK * kMaxK];  // (dq_h*Ws + dq_w)*cp: byte offset a tap adds to a pixel's anchor
     FastDiv div_hw, div_w, div_sh, div_sw;
     const float* s_a;
     const float* s_b;
     float* out;          // fp32 [N][Crow][Hd][Wd]
     int32_t* acc_out;    // optional raw accumulators, same shape
 };
+
+constexpr uint32_t kOob = 0x80000000u;  // a buffer offset past every extent: such a load returns zeros
+
+__device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
+}
 
 // WR = waves along the row (output channel) axis: 1 -> 64 rows x 256 pixels per workgroup with
 // 64 x 64 wave tiles, 2 -> 128 rows x 256 pixels with 64 x 128 wave tiles.
@@ -88,7 +97,6 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
     constexpr int A_BYTES = ROWS * kPitch;
     constexpr int STAGE = A_BYTES + kPxWg * kPitch;
     __shared__ __align__(16) int8_t lds[2 * STAGE];
-    __shared__ int tap_off[kMaxK * kMaxK];  // byte offset a tap adds to a pixel's anchor (kept out of the vector-memory queue)
 
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int l32 = lane & 31, lh = lane >> 5;
@@ -102,20 +110,15 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
     const int nkc = (p.cp + kKc - 1) / kKc;
     const int NS = nkc * taps;  // steps: channel chunk outer, tap inner
 
-    // The tap tables go to LDS once: indexing the kernel-argument copy with a loop variable costs a
-    // vector-memory round trip per access.
-    __shared__ int tab[4 * kMaxK];
-    if (tid < 4 * kMaxK) tab[tid] = p.tab[tid];
-    __syncthreads();
-    const int* dq_h = tab;
-    const int* dr_h = tab + kMaxK;
-    const int* dq_w = tab + 2 * kMaxK;
-    const int* dr_w = tab + 3 * kMaxK;
+    // Both operands are read through buffer descriptors: an offset of kOob returns zeros, which is how
+    // padding taps, stride-skipped taps and ragged tiles are handled without branches or selects.
+    const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wpk, 0, (int)p.wpk_bytes, 0x00020000);
 
     // ---- staging assignment: this thread fetches chunk sc (16 bytes) of pixels spx + 64*i ----
     const int sc = tid & 3, spx = tid >> 2;
-    int64_t poff[4];      // byte offset of the pixel's source anchor (A_h, A_w) in the source tensor, plus chunk
-    uint64_t pmask[4];    // bit t set: tap t reads inside the image for this pixel
+    uint32_t poff[4];        // byte offset of the pixel's source anchor (A_h, A_w), plus the chunk
+    uint32_t pm_lo[4], pm_hi[4];  // bit t set: tap t reads inside the image for this pixel
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const uint32_t P = (uint32_t)tp * kPxWg + spx + 64 * i;
@@ -137,63 +140,65 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
             aw = w * p.sW - p.pW;
             rw = 0;
         }
-        poff[i] = (((int64_t)n * p.Hs + ah) * p.Ws + aw) * p.cp + 16 * sc;
-        uint64_t m = 0;
-        if (pv) {
-            for (int kh = 0; kh < p.kH; ++kh) {
-                const int hs = ah + dq_h[kh];
-                const bool hok = rh == dr_h[kh] && (unsigned)hs < (unsigned)p.Hs;
-                for (int kw = 0; kw < p.kW; ++kw) {
-                    const int ws = aw + dq_w[kw];
-                    const bool ok = hok && rw == dr_w[kw] && (unsigned)ws < (unsigned)p.Ws;
-                    m |= (uint64_t)ok << (kh * p.kW + kw);
-                }
-            }
+        poff[i] = (uint32_t)(((n * p.Hs + ah) * p.Ws + aw) * p.cp + 16 * sc);
+        // separable validity: rows that hit the image, columns that hit the image
+        uint32_t hm = 0, wm = 0;
+#pragma unroll
+        for (int k = 0; k < kMaxK; ++k) {
+            const bool hok = k < p.kH && rh == p.dr_h[k] && (unsigned)(ah + p.dq_h[k]) < (unsigned)p.Hs;
+            const bool wok = k < p.kW && rw == p.dr_w[k] && (unsigned)(aw + p.dq_w[k]) < (unsigned)p.Ws;
+            hm |= (uint32_t)hok << k;
+            wm |= (uint32_t)wok << k;
         }
-        pmask[i] = m;
+        uint64_t m = 0;
+#pragma unroll
+        for (int k = 0; k < kMaxK; ++k)
+            if (k < p.kH) m |= ((hm >> k) & 1u) ? ((uint64_t)wm << (k * p.kW)) : 0ull;
+        if (!pv) m = 0;
+        pm_lo[i] = (uint32_t)m;
+        pm_hi[i] = (uint32_t)(m >> 32);
     }
-    if (tid < taps) {
-        const int kh = tid / p.kW, kw = tid - kh * p.kW;
-        tap_off[tid] = (dq_h[kh] * p.Ws + dq_w[kw]) * p.cp;
-    }
-    __syncthreads();
     // filter slice: unit j of this thread is row srow + 64*j, chunk sc
     const int srow = tid >> 2;
+    uint32_t woff[A_PER_T];
+#pragma unroll
+    for (int j = 0; j < A_PER_T; ++j) {
+        const int rg = row0 + srow + 64 * j;
+        woff[j] = rg < p.Crow ? (uint32_t)(rg * p.kp + 16 * sc) : kOob;
+    }
 
-    // cursor over the steps being fetched
-    int f_kci = 0, f_kh = 0, f_kw = 0, f_s = 0;
-    uint4 ra[kRing][A_PER_T], rb[kRing][4];
-    // Always issues the same number of loads (past the last step they read the zero block), so the
-    // compiler can count outstanding loads exactly and the ring really stays kRing steps deep.
+    // cursor over the steps being fetched (uniform)
+    int f_tap = 0, f_k = 0, f_s = 0;
+    v4i ra[kRing][A_PER_T], rb[kRing][4];
+    // Always issues the same number of loads (past the last step they are out of bounds and return
+    // zeros), so the compiler can count outstanding loads exactly and the ring stays kRing steps deep.
     auto fetch = [&](int slot) {
         const bool live = f_s < NS;
-        const int tap = f_kh * p.kW + f_kw;
-        const int k = f_kci * kKc;
-        const bool kok = live && k + 16 * sc < p.cp;
-        const int toff = tap_off[live ? tap : 0] + k;
+        const int tap = live ? f_tap : 0;
+        const uint32_t toff = (uint32_t)p.tap_off[tap];
+        const uint32_t bit_lo = tap < 32 ? (1u << tap) : 0u, bit_hi = tap >= 32 ? (1u << (tap - 32)) : 0u;
+        const bool kok_b = live && f_k + 16 * sc < p.cp;
+        const bool kok_a = live && f_k + 16 * sc < p.kp;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bool ok = kok && ((pmask[i] >> tap) & 1u);
-            rb[slot][i] = ld16_or_zero(p.src + poff[i] + toff, ok);
+            const bool ok = kok_b && (((pm_lo[i] & bit_lo) | (pm_hi[i] & bit_hi)) != 0u);
+            rb[slot][i] = buffer_load16(rs_src, ok ? poff[i] + toff : kOob, (uint32_t)f_k);
         }
+        const uint32_t wbase = (uint32_t)(tap * p.Crow * p.kp + f_k);
 #pragma unroll
-        for (int j = 0; j < A_PER_T; ++j) {
-            const int rg = row0 + srow + 64 * j;
-            const bool ok = live && rg < p.Crow && k + 16 * sc < p.kp;
-            ra[slot][j] = ld16_or_zero(p.wpk + ((int64_t)tap * p.Crow + rg) * p.kp + k + 16 * sc, ok);
-        }
+        for (int j = 0; j < A_PER_T; ++j) ra[slot][j] = buffer_load16(rs_w, kok_a ? woff[j] : kOob, wbase);
         ++f_s;
-        if (++f_kw == p.kW) { f_kw = 0; if (++f_kh == p.kH) { f_kh = 0; ++f_kci; } }
+        if (++f_tap == taps) { f_tap = 0; f_k += kKc; }
     };
     auto stage = [&](int buf, int slot) {
         int8_t* A = lds + buf * STAGE;
         int8_t* B = A + A_BYTES;
 #pragma unroll
         for (int j = 0; j < A_PER_T; ++j)
-            *reinterpret_cast<uint4*>(A + (srow + 64 * j) * kPitch + 16 * sc) = ra[slot][j];
+            *reinterpret_cast<v4i*>(A + (srow + 64 * j) * kPitch + 16 * sc) = ra[slot][j];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4*>(B + (spx + 64 * i) * kPitch + 16 * sc) = rb[slot][i];
+            *reinterpret_cast<v4i*>(B + (spx + 64 * i) * kPitch + 16 * sc) = rb[slot][i];
     };
 
     v16i acc[2][BF];
@@ -242,38 +247,56 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
 
     // epilogue: register r of tile (x, y) is row 32x + 8*(r/4) + 4*lh + r%4, pixel 32y + l32
     const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
+    const int rowbase = row0 + wr * 64 + 4 * lh;
+    const bool full_rows = row0 + ROWS <= p.Crow;
 #pragma unroll
     for (int y = 0; y < BF; ++y) {
         const uint32_t P = (uint32_t)tp * kPxWg + wp * PXW + 32 * y + l32;
         if (P >= total_px) continue;
         const int n = (int)fdiv(P, p.div_hw);
         const uint32_t rem = P - (uint32_t)n * (uint32_t)HWd;
-        const int64_t pix = (int64_t)n * p.Crow * HWd + rem;
+        const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + rem;
+        float* o = p.out + pix;
+        if (full_rows) {
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < 2; ++x)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = row0 + wr * 64 + 32 * x + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (row < p.Crow) {
-                    const int64_t off = pix + (int64_t)row * HWd;
-                    p.out[off] = (float)acc[x][y][r] * scale;
-                    if (p.acc_out) p.acc_out[off] = acc[x][y][r];
+                for (int r = 0; r < 16; ++r) o[(32 * x + 8 * (r >> 2) + (r & 3)) * HWd] = (float)acc[x][y][r] * scale;
+        } else {
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr < p.Crow) o[dr * HWd] = (float)acc[x][y][r] * scale;
                 }
-            }
+        }
+        if (p.acc_out) {
+            int32_t* ao = p.acc_out + pix;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr < p.Crow) ao[dr * HWd] = acc[x][y][r];
+                }
+        }
     }
 }
 
-daq_status launch(NhwcArgs& a, hipStream_t st, const char* name) {
+daq_status launch(NhwcArgs& a, int dH, int dW, hipStream_t st, const char* name) {
     const int64_t total_px = (int64_t)a.N * a.Hd * a.Wd;
     a.tiles_px = (int)ceil_div(total_px, kPxWg);
+    for (int k = 0; k < kMaxK; ++k) a.dq_h[k] = a.dr_h[k] = a.dq_w[k] = a.dr_w[k] = 0;
     for (int k = 0; k < a.kH; ++k) {
-        a.tab[k] = (int16_t)(a.backward ? -(k * a.dH / a.sH) : k * a.dH);
-        a.tab[kMaxK + k] = (int16_t)(a.backward ? (k * a.dH) % a.sH : 0);
+        a.dq_h[k] = a.backward ? -(k * dH / a.sH) : k * dH;
+        a.dr_h[k] = a.backward ? (k * dH) % a.sH : 0;
     }
     for (int k = 0; k < a.kW; ++k) {
-        a.tab[2 * kMaxK + k] = (int16_t)(a.backward ? -(k * a.dW / a.sW) : k * a.dW);
-        a.tab[3 * kMaxK + k] = (int16_t)(a.backward ? (k * a.dW) % a.sW : 0);
+        a.dq_w[k] = a.backward ? -(k * dW / a.sW) : k * dW;
+        a.dr_w[k] = a.backward ? (k * dW) % a.sW : 0;
     }
+    for (int t = 0; t < a.kH * a.kW; ++t) a.tap_off[t] = (a.dq_h[t / a.kW] * a.Ws + a.dq_w[t % a.kW]) * a.cp;
     a.div_hw = make_fastdiv((uint32_t)(a.Hd * a.Wd));
     a.div_w = make_fastdiv((uint32_t)a.Wd);
     a.div_sh = make_fastdiv((uint32_t)a.sH);
@@ -289,7 +312,13 @@ daq_status launch(NhwcArgs& a, hipStream_t st, const char* name) {
 }
 
 bool nhwc_supported(const daq_conv_desc& d) {
-    return d.groups == 1 && d.kH <= kMaxK && d.kW <= kMaxK;
+    if (d.groups != 1 || d.kH > kMaxK || d.kW > kMaxK) return false;
+    daq_layout Lx, Lg;
+    daq_wpack_layout Lw;
+    if (daq_layout_qx_nhwc(&d, &Lx) != DAQ_OK || daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK)
+        return false;
+    const int64_t lim = (int64_t)1 << 31;  // 32-bit buffer offsets
+    return Lx.bytes < lim && Lg.bytes < lim && Lw.bytes < lim;
 }
 
 }  // namespace
@@ -308,11 +337,12 @@ daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const fl
     a.Hd = d.Hin; a.Wd = d.Win;
     a.Crow = d.Cin; a.kp = Lw.cog_pitch;
     a.kH = d.kH; a.kW = d.kW; a.sH = d.strideH; a.sW = d.strideW; a.pH = d.padH; a.pW = d.padW;
-    a.dH = d.dilH; a.dW = d.dilW;
     a.backward = 1;
     a.s_a = s_w; a.s_b = s_g;
     a.out = dX; a.acc_out = acc;
-    return launch(a, st, "conv_bwd_data_mfma");
+    a.src_bytes = (uint32_t)Lg.bytes;
+    a.wpk_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd);
+    return launch(a, d.dilH, d.dilW, st, "conv_bwd_data_mfma");
 }
 
 bool fwd_mfma_supported(const daq_conv_desc& d) { return nhwc_supported(d); }
@@ -329,11 +359,12 @@ daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     a.Hd = daq_out_h(&d); a.Wd = daq_out_w(&d);
     a.Crow = d.Cout; a.kp = Lw.cig_pitch;
     a.kH = d.kH; a.kW = d.kW; a.sH = d.strideH; a.sW = d.strideW; a.pH = d.padH; a.pW = d.padW;
-    a.dH = d.dilH; a.dW = d.dilW;
     a.backward = 0;
     a.s_a = s_x; a.s_b = s_w;
     a.out = Y; a.acc_out = acc;
-    return launch(a, st, "conv_fwd_mfma");
+    a.src_bytes = (uint32_t)Lx.bytes;
+    a.wpk_bytes = (uint32_t)(Lw.bytes - Lw.off_fwd);
+    return launch(a, d.dilH, d.dilW, st, "conv_fwd_mfma");
 }
 
 }  // namespace daq
