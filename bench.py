@@ -24,7 +24,13 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
 # kernel of known size; keyed by (workload, kernel).  See profiles/ for the runs these come from.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    ("config2", "conv_bwd_data_mfma"): 35.53e6,
+    ("config2", "conv_bwd_filter_mfma"): 23.65e6,
+    ("config2", "stats"): 25.79e6,
+    ("config2", "count_qg"): 35.38e6,
+    ("config2", "pack_vq"): 32.66e6,
+}
 
 
 def main() -> int:
@@ -36,6 +42,9 @@ def main() -> int:
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=1, help="number of dY buffer sets cycled through (cold-cache runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="after the timed region, run 5 device-to-device copies of this many MiB: the plain copy "
+                         "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -93,19 +102,29 @@ def main() -> int:
     rows = daq.prof_end()
     torch.cuda.synchronize()
 
+    if args.copy_calib_mib > 0:
+        ca = torch.zeros(args.copy_calib_mib << 20, dtype=torch.uint8, device=dev)
+        cb = torch.empty_like(ca)
+        for _ in range(5):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        del ca, cb
+
     E_Y = int(np.prod(d.y_shape))
     E_X = int(np.prod(d.x_shape))
     E_W = int(np.prod(d.w_shape))
-    Lv = daq.layout_vq(d)
     ops_per_conv = 2.0 * layer.macs
     ops_per_step = 2.0 * ops_per_conv          # dX + dW
     # algorithmic bytes / ops of one launch of each kernel
     alg_bytes = {
         "stats": 4.0 * E_Y,
         "count_qg": 5.0 * E_Y if daq.layout_qg(d).kind == daq.LAYOUT_NHWC else 4.0 * E_Y,
-        "pack_vq": 4.0 * E_Y + Lv.bytes,
-        "pack_qg": 4.0 * E_Y + Lv.bytes,
+        "pack_vq": 5.0 * E_Y,
+        "pack_qg": 5.0 * E_Y,
     }
+    # convolutions: int8 operands read once, fp32 result written once
+    conv_bytes = {"conv_bwd_data": E_Y + E_W + 4.0 * E_X, "conv_bwd_filter": E_X + E_Y + 4.0 * E_W}
+    ridge = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)   # ops per byte above which the MFMA peak binds
     kernels = {}
     # what an event pair adds by itself (measured by the library with empty pairs), removed from every span
     ev_ms, ev_n = rows.pop("(empty event pair)", (0.0, 0))
@@ -130,10 +149,17 @@ def main() -> int:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                         "frac": round(ach / PEAK_HBM_GBS, 4)}
         else:
-            # the convolutions run as split launches (zero / gemm / epilogue); price the dominant one on its conv's ops
-            ach = ops_per_conv / avg_s / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_INT8_TOPS,
-                        "unit": "TOP/s", "frac": round(ach / PEAK_INT8_TOPS, 4)}
+            # a convolution is priced on the roofline its arithmetic intensity puts it under
+            cb = next((b for k, b in conv_bytes.items() if dom.startswith(k)), None)
+            if cb is not None and ops_per_conv / cb < ridge:
+                ach = cb / avg_s / 1e9
+                roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS,
+                            "unit": "GB/s", "frac": round(ach / PEAK_HBM_GBS, 4),
+                            "ops_per_byte": round(ops_per_conv / cb, 1)}
+            else:
+                ach = ops_per_conv / avg_s / 1e12
+                roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_INT8_TOPS,
+                            "unit": "TOP/s", "frac": round(ach / PEAK_INT8_TOPS, 4)}
         roofline["traffic"] = MEASURED_TRAFFIC.get((f"config{args.config}", dom))
         roofline["avg_us"] = round(1e6 * avg_s, 3)
 
