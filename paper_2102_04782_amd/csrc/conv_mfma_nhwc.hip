@@ -34,27 +34,6 @@ constexpr int kPitch = kKc + 16;   // LDS pitch of a staged row
 constexpr int kRing = 4;           // steps whose global loads are in flight beyond the one being staged
 constexpr int kMaxK = 8;           // largest filter extent (tap masks hold 64 taps)
 
-// Exact unsigned division by an invariant divisor (Granlund-Montgomery round-up multiplier).
-struct FastDiv {
-    uint32_t mul;
-    int32_t shift;
-    int32_t one;
-};
-FastDiv make_fastdiv(uint32_t d) {
-    FastDiv f{};
-    f.one = (d == 1);
-    int L = 0;
-    while (((uint64_t)1 << L) < d) ++L;
-    f.shift = L > 0 ? L - 1 : 0;
-    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << L) - d)) / d + 1);
-    return f;
-}
-__device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
-    if (f.one) return x;
-    const uint32_t t = __umulhi(x, f.mul);
-    return (t + ((x - t) >> 1)) >> f.shift;
-}
-
 struct NhwcArgs {
     const int8_t* src;   // pixel operand, NHWC [N][Hs][Ws][cp]
     const int8_t* wpk;   // filter operand [taps][Crow][kp]

@@ -47,6 +47,28 @@ __device__ __forceinline__ float ldf_or_zero(const float* p, bool ok) {
     return *(ok ? p : reinterpret_cast<const float*>(g_zero64));
 }
 
+// ---- division by a launch-invariant divisor ---------------------------------------------------
+// Exact unsigned division by an invariant divisor (Granlund-Montgomery round-up multiplier).
+struct FastDiv {
+    uint32_t mul;
+    int32_t shift;
+    int32_t one;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f{};
+    f.one = (d == 1);
+    int L = 0;
+    while (((uint64_t)1 << L) < d) ++L;
+    f.shift = L > 0 ? L - 1 : 0;
+    f.mul = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << L) - d)) / d + 1);
+    return f;
+}
+__device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
+    if (f.one) return x;
+    const uint32_t t = __umulhi(x, f.mul);
+    return (t + ((x - t) >> 1)) >> f.shift;
+}
+
 // ---- device-side view of an int8 layout ----------------------------------------------------
 struct CnhwView {
     int64_t chan_pitch, plane_pitch, lead;

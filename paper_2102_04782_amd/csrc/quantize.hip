@@ -13,22 +13,30 @@ namespace daq {
 
 namespace {
 
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+
 constexpr int kBlock = 256;
-constexpr int kStatsElems = 4096;  // elements swept by one statistics workgroup (16 per thread, all loads in flight)
+constexpr int kStatsElems = 4096;  // elements one statistics workgroup sweeps per iteration (16 per thread, all in flight)
+constexpr int kMaxSlabs = 16;      // statistics partials per channel (every consumer re-folds them)
+constexpr int kCountGrid = 1024;   // workgroups the counting pass aims for; one count partial per channel each
 
 // ---------------------------------------------------------------------------------------------
 // workspace carving
 // ---------------------------------------------------------------------------------------------
 struct QuantWs {
-    uint32_t* gmax_bits;  // [1]   bit pattern of max_c |g|max (non-negative floats order like uints)
-    float* gmax;          // [C]
+    float* gmax;          // [C]  |g|max, mean, sigma: written by the counting pass for the packing pass
     float* mean;          // [C]
     float* sigma;         // [C]
-    float* part_max;      // [C][chunks]
-    double* part_s1;      // [C][chunks]
-    double* part_s2;      // [C][chunks]
-    uint32_t* part_cnt;   // [C][slots]  #{|g| > sigma} per (image, 64-pixel tile)
-    int chunks, slots;
+    float* s_prev;        // [C]  copy of the clip state taken before anything overwrites it
+    float* part_max;      // [C][slabs]
+    double* part_s1;      // [C][slabs]
+    double* part_s2;      // [C][slabs]
+    uint32_t* part_cnt;   // [C][cgroups]  #{|g| > sigma} seen by counting workgroup p of the channel's block
+    int chunks;           // 4096-element chunks of one channel
+    int slabs;            // statistics workgroups (partials) per channel
+    int tiles;            // 64-pixel tiles of the flattened (n, h*w) axis
+    int cgroups;          // counting workgroups per block of 64 channels
     int64_t total_bytes;
 };
 
@@ -37,20 +45,25 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     char* p = (char*)base;
     const int64_t M = (int64_t)N * HW;
     w.chunks = (int)ceil_div(M, kStatsElems);
-    w.slots = N * (int)ceil_div(HW, kWave);
-    w.gmax_bits = (uint32_t*)p;
-    p += 256;
+    const int iters = (int)ceil_div(w.chunks, kMaxSlabs);
+    w.slabs = (int)ceil_div(w.chunks, iters);
+    w.tiles = (int)ceil_div(M, kWave);
+    const int cb = (int)ceil_div(C, 64);
+    const int want = std::max(1, kCountGrid / cb);
+    const int titers = (int)ceil_div(w.tiles, want);
+    w.cgroups = (int)ceil_div(w.tiles, titers);
     w.gmax = (float*)p;
     w.mean = w.gmax + C;
     w.sigma = w.mean + C;
-    p += round_up((int64_t)3 * C * 4, 256);
+    w.s_prev = w.sigma + C;
+    p += round_up((int64_t)4 * C * 4, 256);
     w.part_s1 = (double*)p;
-    w.part_s2 = w.part_s1 + (int64_t)C * w.chunks;
-    p += round_up((int64_t)2 * C * w.chunks * 8, 256);
+    w.part_s2 = w.part_s1 + (int64_t)C * w.slabs;
+    p += round_up((int64_t)2 * C * w.slabs * 8, 256);
     w.part_max = (float*)p;
-    p += round_up((int64_t)C * w.chunks * 4, 256);
+    p += round_up((int64_t)C * w.slabs * 4, 256);
     w.part_cnt = (uint32_t*)p;
-    p += round_up((int64_t)C * w.slots * 4, 256);
+    p += round_up((int64_t)C * w.cgroups * 4, 256);
     w.total_bytes = p - (char*)base;
     return w;
 }
@@ -85,6 +98,34 @@ __device__ __forceinline__ int quant_code(float x, float inv, uint64_t seed, uin
         return (int)(f + (frac > u ? 1.0f : 0.0f));
     }
     return (int)rintf(t);
+}
+
+// The same code as quant_code, left in the low byte of a 32-bit word (upper bytes are don't-care).
+// Nearest: adding 1.5 * 2^23 to a value of magnitude <= 127 rounds it to an integer, ties to even,
+// and leaves that integer in two's complement in the low mantissa bits - one instruction instead of
+// round + convert + mask.
+template <bool STOCH>
+__device__ __forceinline__ uint32_t quant_bits(float x, float inv, uint64_t seed, uint32_t tensor, uint64_t idx) {
+    if (STOCH) return (uint32_t)quant_code<true>(x, inv, seed, tensor, idx);
+    const float t = __builtin_amdgcn_fmed3f(x * inv, -127.0f, 127.0f);
+    return __float_as_uint(t + 12582912.0f);
+}
+// Low bytes of four words -> one dword (a in byte 0).
+__device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const uint32_t lo = __builtin_amdgcn_perm(b, a, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(d, c, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
+// fp32 tensors are read through a buffer descriptor with 32-bit byte offsets: an offset of kOobOff (or
+// anything past the extent) returns 0.0f, which is how ragged tiles and padding positions are read
+// without branches or selects on the loaded value.  Tensors must be smaller than 2 GiB.
+constexpr uint32_t kOobOff = 0x80000000u;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t f32_rsrc(const float* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_ldf(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
 }
 
 __device__ __forceinline__ float wave_max(float v) {
@@ -123,252 +164,448 @@ __device__ __forceinline__ void block_reduce(float& mx, double& s1, double& s2) 
 }
 
 // ---------------------------------------------------------------------------------------------
-// S1: per-channel |g|max, sum, sum of squares.  Workgroup (c, j) sweeps elements
-// [j*4096, (j+1)*4096) of channel c's flattened (n, h*w) axis with every load issued up front,
-// and stores one partial.  k_stats_final reduces a channel's partials with a fixed tree.
-// Channel c runs on XCD c % 8 in every pass over dY.
+// S1: per-channel |g|max, sum, sum of squares.  Workgroup (c, j) sweeps the 4096-element chunks
+// j, j + slabs, ... of channel c's flattened (n, h*w) axis, the loads of the next chunk in flight
+// while the current one is reduced, and stores one partial.  A channel has at most 16 partials, so
+// the kernels that need mean and sigma fold them again themselves (fold_stats) in a fixed order
+// instead of waiting for a reduction launch.  Channel c runs on XCD c % 8 in every pass over dY.
 // ---------------------------------------------------------------------------------------------
 template <bool VEC4>
 __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, QuantWs ws) {
+    constexpr int NV = VEC4 ? 4 : 16;
     const int b = blockIdx.x;
     const int xcd = b % kXcd, q = b / kXcd;
-    const int c = (q / ws.chunks) * kXcd + xcd;
-    const int j = q % ws.chunks;
-    if (b == 0 && threadIdx.x == 0) *ws.gmax_bits = 0u;  // consumed by k_stats_final, a later launch
+    const int c = (q / ws.slabs) * kXcd + xcd;
+    const int j = q % ws.slabs;
     if (c >= C) return;
     const int M = N * HW;
-    const int m0 = j * kStatsElems;
     const int tid = threadIdx.x;
 
+    uint4 v[NV];   // VEC4: four floats each; otherwise only .x is used
+    auto fetch = [&](int chunk, uint4 (&dst)[NV]) {
+        const bool live = chunk < ws.chunks;
+        const int m0 = chunk * kStatsElems;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int m = VEC4 ? m0 + 4 * (tid + u * kBlock) : m0 + tid + u * kBlock;
+            const bool ok = live && m < M;
+            const int mc = ok ? m : 0;
+            const int n = mc / HW, i = mc - n * HW;
+            const float* src = g + ((int64_t)n * C + c) * HW + i;
+            if (VEC4) dst[u] = ld16_or_zero(src, ok);
+            else dst[u].x = __float_as_uint(ldf_or_zero(src, ok));
+        }
+    };
     float mx = 0.0f;
     double s1 = 0.0, s2 = 0.0;
-    if (VEC4) {
-        float4 v[4];
+    fetch(j, v);
+    for (int chunk = j; chunk < ws.chunks; chunk += ws.slabs) {
+        uint4 nv[NV];
+        fetch(chunk + ws.slabs, nv);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int m = m0 + 4 * (tid + u * kBlock);
-            const bool ok = m < M;
-            const int mc = ok ? m : 0;
-            const int n = mc / HW, i = mc - n * HW;
-            const uint4 raw = ld16_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
-            v[u] = make_float4(__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z),
-                               __uint_as_float(raw.w));
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            mx = fmaxf(mx, fmaxf(fmaxf(fabsf(v[u].x), fabsf(v[u].y)), fmaxf(fabsf(v[u].z), fabsf(v[u].w))));
-            const double a = v[u].x, bq = v[u].y, cq = v[u].z, d = v[u].w;
-            s1 += a; s1 += bq; s1 += cq; s1 += d;
-            s2 += a * a; s2 += bq * bq; s2 += cq * cq; s2 += d * d;
-        }
-    } else {
-        float v[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int m = m0 + tid + u * kBlock;
-            const bool ok = m < M;
-            const int mc = ok ? m : 0;
-            const int n = mc / HW, i = mc - n * HW;
-            v[u] = ldf_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
-        }
-#pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            mx = fmaxf(mx, fabsf(v[u]));
-            const double a = v[u];
+        for (int u = 0; u < NV; ++u) {
+            const float f0 = __uint_as_float(v[u].x);
+            mx = fmaxf(mx, fabsf(f0));
+            const double a = f0;
             s1 += a;
             s2 += a * a;
+            if (VEC4) {
+                const float f1 = __uint_as_float(v[u].y), f2 = __uint_as_float(v[u].z), f3 = __uint_as_float(v[u].w);
+                mx = fmaxf(mx, fmaxf(fabsf(f1), fmaxf(fabsf(f2), fabsf(f3))));
+                const double bq = f1, cq = f2, d = f3;
+                s1 += bq; s1 += cq; s1 += d;
+                s2 += bq * bq; s2 += cq * cq; s2 += d * d;
+            }
         }
+#pragma unroll
+        for (int u = 0; u < NV; ++u) v[u] = nv[u];
     }
     block_reduce(mx, s1, s2);
     if (tid == 0) {
-        const int64_t slot = (int64_t)c * ws.chunks + j;
+        const int64_t slot = (int64_t)c * ws.slabs + j;
         ws.part_max[slot] = mx;
         ws.part_s1[slot] = s1;
         ws.part_s2[slot] = s2;
     }
 }
 
-// One workgroup per channel: partials -> |g|max, mean, sigma (population std, fp64, rounded once).
-__global__ __launch_bounds__(kBlock) void k_stats_final(int N, int C, int HW, QuantWs ws) {
-    const int c = blockIdx.x;
+// Partials of channel c -> |g|max, mean, sigma (population std about the mean, fp64, rounded once).
+// Sequential in slab order, so every workgroup that calls it gets the same bits.
+__device__ __forceinline__ void fold_stats(const QuantWs& ws, int c, double Md, float& gmax, float& mean, float& sigma) {
     float mx = 0.0f;
     double s1 = 0.0, s2 = 0.0;
-    for (int j = threadIdx.x; j < ws.chunks; j += kBlock) {
-        const int64_t slot = (int64_t)c * ws.chunks + j;
+    for (int j = 0; j < ws.slabs; ++j) {
+        const int64_t slot = (int64_t)c * ws.slabs + j;
         mx = fmaxf(mx, ws.part_max[slot]);
         s1 += ws.part_s1[slot];
         s2 += ws.part_s2[slot];
     }
-    block_reduce(mx, s1, s2);
-    if (threadIdx.x == 0) {
-        const double Md = (double)N * (double)HW;
-        const double mu = s1 / Md;
-        double var = s2 / Md - mu * mu;
-        if (var < 0.0) var = 0.0;
-        ws.gmax[c] = mx;
-        ws.mean[c] = (float)mu;
-        ws.sigma[c] = (float)sqrt(var);
-        atomicMax(ws.gmax_bits, __float_as_uint(mx));
-    }
+    const double mu = s1 / Md;
+    double var = s2 / Md - mu * mu;
+    if (var < 0.0) var = 0.0;
+    gmax = mx;
+    mean = (float)mu;
+    sigma = (float)sqrt(var);
 }
 
 // ---------------------------------------------------------------------------------------------
 // S2 (+ the global copy of S5): tail-mass count per channel, fused with the globally quantized
-// NHWC copy.  A workgroup owns 64 pixels of one image and 64 channels; wave w walks channels
-// 16w..16w+15 with lane = pixel, so every load is a 256-byte run of one channel and the lane's 16
-// codes are 16 contiguous bytes of the NHWC output.  Counts are wave ballots, stored per
-// (channel, image, pixel tile) and summed by k_clip_final: no atomics anywhere.
+// NHWC copy.  A workgroup owns 64 channels and walks 64-pixel tiles p, p + cgroups, ... of the
+// flattened (n, h*w) axis; wave w handles channels 16w..16w+15 with lane = pixel, so every load is
+// a 256-byte run of one channel and the lane's 16 codes are 16 contiguous bytes of the NHWC output.
+// The workgroup first folds the statistics partials of its 64 channels (sigma) and of all channels
+// (the global scale max_c |g|max), then counts with wave ballots into registers and stores one
+// count partial per channel: no atomics, no reduction launch.
 // ---------------------------------------------------------------------------------------------
+template <bool STOCH, bool WRITE_QG, bool COUNT>
+__global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g, int N, int C, int HW, int c_pitch,
+                                                     FastDiv div_hw, QuantWs ws, const float* __restrict__ scale_ptr,
+                                                     int8_t* __restrict__ qg, uint64_t seed,
+                                                     const float* __restrict__ s_state, float* __restrict__ s_global) {
+    __shared__ float l_sigma[64];
+    __shared__ float l_max[kBlock / kWave];
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int p = blockIdx.x % ws.cgroups;
+    const int cb = blockIdx.x / ws.cgroups;
+    const int c0 = cb * 64 + 16 * wave;
+    const uint32_t M = (uint32_t)N * (uint32_t)HW;
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(g, (uint32_t)M * (uint32_t)C * 4u);
+    const uint32_t chan_bytes = (uint32_t)HW * 4u;
+
+    float x[16];
+    uint32_t n_cur = 0, px_cur = 0;
+    bool v_cur = false;
+    auto fetch = [&](int tile, float (&dst)[16], uint32_t& n, uint32_t& px, bool& valid) {
+        const uint32_t P = (uint32_t)tile * kWave + lane;
+        valid = tile < ws.tiles && P < M;
+        const uint32_t Pc = valid ? P : 0u;
+        n = fdiv(Pc, div_hw);
+        px = Pc - n * (uint32_t)HW;
+        const uint32_t off = valid ? ((n * (uint32_t)C + (uint32_t)c0) * (uint32_t)HW + px) * 4u : kOobOff;
+        if (c0 + 16 <= C) {   // uniform per wave
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dst[i] = buf_ldf(rs, off, (uint32_t)i * chan_bytes);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dst[i] = buf_ldf(rs, c0 + i < C ? off : kOobOff, (uint32_t)i * chan_bytes);
+        }
+    };
+    fetch(p, x, n_cur, px_cur, v_cur);
+
+    // scale of the global copy: max_c |g|max from the statistics pass, or an explicit per-tensor scale
+    float sg = 0.0f;
+    if (scale_ptr) {
+        sg = *scale_ptr;
+    } else {
+        float m = 0.0f;
+        for (int i = tid; i < C * ws.slabs; i += kBlock) m = fmaxf(m, ws.part_max[i]);
+        m = wave_max(m);
+        if (lane == 0) l_max[wave] = m;
+    }
+    if (COUNT && tid < 64) {
+        const int c = cb * 64 + tid;
+        float gm = 0.0f, mu = 0.0f, sig = 0.0f;
+        if (c < C) {
+            fold_stats(ws, c, (double)N * (double)HW, gm, mu, sig);
+            if (p == 0) { ws.gmax[c] = gm; ws.mean[c] = mu; ws.sigma[c] = sig; }
+        }
+        l_sigma[tid] = sig;
+    }
+    __syncthreads();
+    if (!scale_ptr) sg = fmaxf(fmaxf(l_max[0], l_max[1]), fmaxf(l_max[2], l_max[3]));
+    if (!(sg >= kTinyScale)) sg = 0.0f;
+    if (COUNT && blockIdx.x == 0) {
+        // the clip state is overwritten by the packing pass: keep what this iteration started from
+        for (int i = tid; i < C; i += kBlock) ws.s_prev[i] = s_state[i];
+        if (tid == 0) *s_global = sg;
+    }
+    const float inv = inv_scale(sg);
+    // sigma of the wave's 16 channels.  Lanes without a pixel and channels past C hold x = 0, and
+    // 0 > sigma is false for every sigma >= 0, so the comparison needs no validity mask.
+    float sig[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sig[i] = COUNT ? l_sigma[16 * wave + i] : 0.0f;
+
+    uint32_t cnt[16];   // wave-uniform counters
+#pragma unroll
+    for (int i = 0; i < 16; ++i) cnt[i] = 0;
+    for (int tile = p; tile < ws.tiles; tile += ws.cgroups) {
+        float nx[16];
+        uint32_t n_nxt, px_nxt;
+        bool v_nxt;
+        fetch(tile + ws.cgroups, nx, n_nxt, px_nxt, v_nxt);
+        uint32_t b[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (COUNT) cnt[i] += (uint32_t)__popcll(__ballot(fabsf(x[i]) > sig[i]));
+            if (WRITE_QG) {
+                const uint64_t idx = STOCH ? (uint64_t)(((int64_t)n_cur * C + c0 + i) * HW + px_cur) : 0;
+                b[i] = quant_bits<STOCH>(x[i], inv, seed, 1u, idx);
+            }
+        }
+        if (WRITE_QG && v_cur && c0 < c_pitch)
+            *reinterpret_cast<uint4*>(qg + ((int64_t)n_cur * HW + px_cur) * c_pitch + c0) =
+                make_uint4(pack4(b[0], b[1], b[2], b[3]), pack4(b[4], b[5], b[6], b[7]), pack4(b[8], b[9], b[10], b[11]),
+                           pack4(b[12], b[13], b[14], b[15]));
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = nx[i];
+        n_cur = n_nxt; px_cur = px_nxt; v_cur = v_nxt;
+    }
+    if (COUNT) {
+        uint32_t mine = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mine = (lane == i) ? cnt[i] : mine;
+        if (lane < 16 && c0 + lane < C) ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = mine;
+    }
+}
+
 struct ClipArgs {
     float k, A, lambda;
     float* s_state;
     float* s_chan;
-    float* s_global;
     uint8_t* cls;
     float* stats;
 };
 
-template <bool STOCH, bool WRITE_QG, bool COUNT>
-__global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g, int N, int C, int HW, int c_pitch,
-                                                     int ptiles, QuantWs ws, const float* __restrict__ scale_ptr,
-                                                     int8_t* __restrict__ qg, uint64_t seed) {
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    int b = blockIdx.x;
-    const int pt = b % ptiles; b /= ptiles;
-    const int n = b % N;
-    const int cb = b / N;
-    const int c0 = cb * 64 + 16 * wave;
-    const int px = pt * kWave + lane;
-    const bool vpx = px < HW;
-
-    // scale of the global copy: max_c |g|max from the statistics pass, or an explicit per-tensor scale
-    float sg = 0.0f;
-    if (WRITE_QG) {
-        sg = scale_ptr ? *scale_ptr : __uint_as_float(*ws.gmax_bits);
-        if (!(sg >= kTinyScale)) sg = 0.0f;
-    }
-    const float inv = inv_scale(sg);
-
-    const float* gp = g + ((int64_t)n * C + c0) * HW + px;
-    float x[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) x[i] = ldf_or_zero(gp + (int64_t)i * HW, vpx && c0 + i < C);
-
-    uint32_t mycnt = 0;
-    uint32_t w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int c = c0 + i;
-        if (COUNT) {
-            const float sig = (c < C) ? ws.sigma[c] : 0.0f;
-            const unsigned long long bal = __ballot(vpx && c < C && fabsf(x[i]) > sig);
-            if (lane == i) mycnt = (uint32_t)__popcll(bal);
-        }
-        if (WRITE_QG) {
-            const uint64_t idx = (uint64_t)(((int64_t)n * C + c) * HW + px);
-            const int code = quant_code<STOCH>(x[i], inv, seed, 1u, idx);
-            w[i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
-        }
-    }
-    if (WRITE_QG && vpx && c0 < c_pitch)
-        *reinterpret_cast<uint4*>(qg + ((int64_t)n * HW + px) * c_pitch + c0) = make_uint4(w[0], w[1], w[2], w[3]);
-    if (COUNT && lane < 16 && c0 + lane < C)
-        ws.part_cnt[(int64_t)(c0 + lane) * ws.slots + n * ptiles + pt] = mycnt;
-}
-
-// S2 (sum of the partial counts) + S3 discriminator + S4 clip rule, one workgroup per channel.
-__global__ __launch_bounds__(kBlock) void k_clip_final(int N, int C, int HW, QuantWs ws, ClipArgs ca) {
-    const int c = blockIdx.x;
+// ---------------------------------------------------------------------------------------------
+// S5, channel-major copy: fp32 NCHW -> int8 CNHW (the dimension transformation G -> G', X -> X'),
+// with S3 + S4 folded in for the per-channel copy of dY.
+//
+// Output driven: a workgroup produces 4096 consecutive bytes of one channel's plane, a thread four
+// aligned dwords (256 dwords apart), including the zero bytes that serve as convolution padding, so
+// every byte of the buffer is written exactly once, stores are 256-byte runs per wave and the loads
+// of neighbouring lanes fall into the same cache lines.  All 16 loads of a thread are in flight
+// before the scale is needed.
+//
+// CLIP: the scale is the channel's Magnitude-aware Clipping value.  Every workgroup of the channel
+// sums the count partials of the counting pass, applies the discriminator (Eq. "judge") and the clip
+// rule (Eq. "gaus" / Eq. "fats") to identical inputs in identical order, and the channel's first
+// workgroup publishes s_chan, the class, the new state and the optional statistics.
+// ---------------------------------------------------------------------------------------------
+// S2 (sum of the count partials) + S3 discriminator + S4 clip rule for channel c, evaluated by a whole
+// workgroup; every workgroup of the channel gets the same value, `publish` marks the one that writes it out.
+__device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& ca, int c, double Md, bool publish,
+                                            uint32_t* l_cnt) {
+    const int tid = threadIdx.x;
     uint32_t cnt = 0;
-    for (int j = threadIdx.x; j < ws.slots; j += kBlock) cnt += ws.part_cnt[(int64_t)c * ws.slots + j];
+    for (int i = tid; i < ws.cgroups; i += kBlock) cnt += ws.part_cnt[(int64_t)c * ws.cgroups + i];
     cnt = wave_sum_u32(cnt);
-    __shared__ uint32_t l_cnt[kBlock / kWave];
-    if (threadIdx.x % kWave == 0) l_cnt[threadIdx.x / kWave] = cnt;
+    if (tid % kWave == 0) l_cnt[tid / kWave] = cnt;
     __syncthreads();
-    if (threadIdx.x != 0) return;
-    for (int w = 1; w < kBlock / kWave; ++w) cnt += l_cnt[w];
-
-    float sg = __uint_as_float(*ws.gmax_bits);
-    if (!(sg >= kTinyScale)) sg = 0.0f;
-    if (c == 0) *ca.s_global = sg;
-    const double Md = (double)N * (double)HW;
+    cnt = l_cnt[0] + l_cnt[1] + l_cnt[2] + l_cnt[3];
     const int klass = ((double)cnt > (double)ca.lambda * Md) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
     const float gm = ws.gmax[c];
     float s = gm;
     if (klass == DAQ_CLASS_INVT) {
-        float p = ca.s_state[c];
-        if (!(p > 0.0f)) p = gm;
-        s = (float)((1.0 - (double)ca.k * (double)ca.A) * (double)p + (double)ca.A * (double)gm);
+        float prev = ws.s_prev[c];
+        if (!(prev > 0.0f)) prev = gm;
+        s = (float)((1.0 - (double)ca.k * (double)ca.A) * (double)prev + (double)ca.A * (double)gm);
         if (!(s > 0.0f)) s = gm;
     }
-    ca.s_state[c] = s;
-    ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
-    ca.cls[c] = (uint8_t)klass;
-    if (ca.stats) {
-        ca.stats[4 * c + 0] = gm;
-        ca.stats[4 * c + 1] = ws.mean[c];
-        ca.stats[4 * c + 2] = ws.sigma[c];
-        ca.stats[4 * c + 3] = (float)((double)cnt / Md);
+    if (publish && tid == 0) {
+        ca.s_state[c] = s;
+        ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
+        ca.cls[c] = (uint8_t)klass;
+        if (ca.stats) {
+            ca.stats[4 * c + 0] = gm;
+            ca.stats[4 * c + 1] = ws.mean[c];
+            ca.stats[4 * c + 2] = ws.sigma[c];
+            ca.stats[4 * c + 3] = (float)((double)cnt / Md);
+        }
+    }
+    return s;
+}
+
+struct PackArgs {
+    FastDiv div_slot, div_pitch;
+    int per_chan;          // workgroups per (channel, phase) plane
+    int per_channel_scale; // scale[c] instead of scale[0] (ignored with CLIP)
+    uint32_t tensor;       // random stream id
+    uint64_t seed;
+};
+
+template <bool STOCH, bool CLIP>
+__global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ src, CnhwView L,
+                                                      const float* __restrict__ scale, int8_t* __restrict__ dst,
+                                                      PackArgs pa, QuantWs ws, ClipArgs ca) {
+    __shared__ uint32_t l_cnt[kBlock / kWave];
+    const int b = blockIdx.x;
+    const int xcd = b % kXcd, q = b / kXcd;
+    const int c = (q / pa.per_chan) * kXcd + xcd;  // channel c runs on XCD c % 8
+    const int jb = q % pa.per_chan;                // block of 1024 dwords along the flattened axis
+    const int phase = blockIdx.z;
+    if (c >= L.C) return;
+    const int tid = threadIdx.x;
+    const int ph = phase / L.phases_w, pw = phase % L.phases_w;
+    const int plane_dw = (int)(L.plane_pitch >> 2);
+    const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
+    const uint32_t HW = (uint32_t)(L.H * L.W);
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * 4u);
+
+    // All index products below have factors under 2^24 and results under 2^31 (checked by the host), so the
+    // full-rate 24-bit multiplier serves.  A destination row (n, r) reads source row h = r*phases_h + ph - org_h
+    // of image n; stepping to the next destination row moves the source offset by one of two launch constants.
+    const uint32_t W4 = (uint32_t)L.W * 4u;
+    const uint32_t step_row = (uint32_t)L.phases_h * W4;                                  // next row, same image
+    const uint32_t step_img = (uint32_t)L.C * HW * 4u - (uint32_t)(L.img_rows - 1) * step_row;  // row 0 of the next image
+    const int h_first = ph - L.org_h, w_first = pw - L.org_w;
+
+    float x[4][4];
+    uint32_t eoff[4][4];   // byte offset of the element in the source (also its index * 4), or >= kOobOff
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int d = jb * 1024 + tid + 256 * u;   // dword inside the plane
+        // first byte of the dword as (image, row, column); shifted by one image so that the bytes in
+        // front of the first image (the leading padding) decompose to image -1
+        const uint32_t o = (uint32_t)(4 * d - (int)L.lead) + slot;
+        const uint32_t nq = fdiv(o, pa.div_slot);
+        const uint32_t rem = o - __umul24(nq, slot);
+        const uint32_t r = fdiv(rem, pa.div_pitch);
+        const int col = (int)(rem - __umul24(r, (uint32_t)L.row_pitch));
+        const int n = (int)nq - 1;
+        int h = (int)__umul24(r, (uint32_t)L.phases_h) + h_first;
+        // n and h may be negative here (leading padding): signed multiplies keep the offset linear modulo 2^32,
+        // so the row steps below land on the right value once the walk reaches a real row
+        uint32_t raw = (uint32_t)(__mul24(__mul24(n, L.C) + c, (int)HW) + __mul24(h, L.W)) * 4u;
+        int w = (int)__umul24((uint32_t)col, (uint32_t)L.phases_w) + w_first;
+        int nn = n, rr = (int)r, cc = col;
+        const bool live = d < plane_dw;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = live & ((unsigned)nn < (unsigned)L.N) & ((unsigned)h < (unsigned)L.H) & ((unsigned)w < (unsigned)L.W);
+            eoff[u][i] = ok ? raw + 4u * (uint32_t)w : kOobOff;
+            x[u][i] = buf_ldf(rs, eoff[u][i], 0u);
+            // step to the next byte of the plane: next column, possibly next row, possibly next image
+            const bool wrap = cc + 1 == L.row_pitch;
+            const bool last = wrap & (rr + 1 == L.img_rows);
+            cc = wrap ? 0 : cc + 1;
+            w = wrap ? w_first : w + L.phases_w;
+            raw += wrap ? (last ? step_img : step_row) : 0u;
+            h = wrap ? (last ? h_first : h + L.phases_h) : h;
+            rr = wrap ? (last ? 0 : rr + 1) : rr;
+            nn += last ? 1 : 0;
+        }
+    }
+
+    float s;
+    if (CLIP) s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb == 0 && phase == 0, l_cnt);
+    else s = pa.per_channel_scale ? scale[c] : scale[0];
+    const float inv = inv_scale(s);
+
+    // Padding positions were read as 0.0f and quantize to code 0 in either rounding mode
+    // (stochastic: floor(0) + (0 > u) = 0), so no select is needed here.
+    int8_t* plane = dst + (int64_t)c * L.chan_pitch + (int64_t)phase * L.plane_pitch;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int d = jb * 1024 + tid + 256 * u;
+        uint32_t bits[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u][i] >> 2));
+        if (d < plane_dw) *reinterpret_cast<uint32_t*>(plane + 4 * (int64_t)d) = pack4(bits[0], bits[1], bits[2], bits[3]);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// S5, channel-major copy: fp32 NCHW -> int8 CNHW (the dimension transformation G -> G', X -> X').
-// Output driven: each thread produces 16 aligned bytes of the destination plane, including the
-// zero bytes that serve as convolution padding, so stores are fully coalesced, every byte of the
-// buffer is written exactly once and all 16 loads of a thread are in flight together.
+// S5, channel-major copy, fast path for unsplit layouts (one stride phase) whose row length is a
+// multiple of V = 4 or 2.  Source driven: a thread loads V consecutive floats of one row with one
+// aligned vector load (neighbouring lanes are contiguous: 1 KiB per wave instruction for V = 4),
+// quantizes them and stores V consecutive bytes; no element needs a validity test and the index
+// arithmetic is shared by V elements.  The zero bytes between the rows are written by the thread
+// that owns the end of the row; the padding rows between images, the bytes in front of the first
+// row and behind the last one by one extra workgroup per channel.  Every byte of the buffer is
+// still written exactly once per call.
 // ---------------------------------------------------------------------------------------------
-template <bool STOCH>
-__global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ src, CnhwView L,
-                                                      const float* __restrict__ scale, int per_channel,
-                                                      int8_t* __restrict__ dst, uint64_t seed, uint32_t tensor,
-                                                      int per_chan) {
+struct RowsArgs {
+    FastDiv div_hwv, div_wv, div_prb;
+    int per_chan;          // data workgroups per channel (one more zeroes the padding)
+    int per_channel_scale;
+    uint32_t tensor;
+    uint64_t seed;
+};
+
+template <int V>
+__device__ __forceinline__ void store_codes(int8_t* p, uint32_t w) {
+    // the destination has no alignment beyond one byte; the compiler picks the widest legal store
+    if (V == 4) {
+        __builtin_memcpy(p, &w, 4);
+    } else {
+        const uint16_t h = (uint16_t)w;
+        __builtin_memcpy(p, &h, 2);
+    }
+}
+
+template <bool STOCH, bool CLIP, int V>
+__global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ src, CnhwView L,
+                                                      const float* __restrict__ scale, int8_t* __restrict__ dst,
+                                                      RowsArgs pa, QuantWs ws, ClipArgs ca) {
+    __shared__ uint32_t l_cnt[kBlock / kWave];
     const int b = blockIdx.x;
     const int xcd = b % kXcd, q = b / kXcd;
-    const int c = (q / per_chan) * kXcd + xcd;  // channel c runs on XCD c % 8
-    const int jb = q % per_chan;                // block of 16-byte units along the flattened axis
-    const int phase = blockIdx.z;
+    const int c = (q / (pa.per_chan + 1)) * kXcd + xcd;  // channel c runs on XCD c % 8
+    const int jb = q % (pa.per_chan + 1);
     if (c >= L.C) return;
-    const int64_t j = (int64_t)jb * kBlock + threadIdx.x;  // 16-byte unit inside the plane
-    if (16 * j >= L.plane_pitch) return;
-    const int ph = phase / L.phases_w, pw = phase % L.phases_w;
-    const float inv = inv_scale(per_channel ? scale[c] : scale[0]);
+    const int tid = threadIdx.x;
+    int8_t* plane = dst + (int64_t)c * L.chan_pitch;
+    const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
 
-    const int slot = L.img_rows * L.row_pitch;
-    int64_t o = 16 * j - L.lead;
-    int n = 0, r = 0, col = 0;
-    if (o > 0) {
-        n = (int)(o / slot);
-        const int rem = (int)(o - (int64_t)n * slot);
-        r = rem / L.row_pitch;
-        col = rem - r * L.row_pitch;
+    if (jb == pa.per_chan) {
+        // padding rows behind every image, then the bytes in front of the first row and behind the last image
+        const uint32_t prb = (uint32_t)(L.img_rows - L.H) * (uint32_t)L.row_pitch;
+        const uint32_t total = (uint32_t)L.N * prb;
+        for (uint32_t t = tid; t < total; t += kBlock) {
+            const uint32_t n = fdiv(t, pa.div_prb);
+            plane[(uint32_t)L.lead + n * slot + (uint32_t)L.H * (uint32_t)L.row_pitch + (t - n * prb)] = 0;
+        }
+        for (uint32_t t = tid; t < (uint32_t)L.lead; t += kBlock) plane[t] = 0;
+        for (uint32_t t = (uint32_t)L.lead + (uint32_t)L.N * slot + tid; t < (uint32_t)L.plane_pitch; t += kBlock) plane[t] = 0;
+        return;
     }
-    float x[16];
-    int64_t idx[16];
+
+    const uint32_t HW = (uint32_t)(L.H * L.W), HWV = HW / V, WV = (uint32_t)L.W / V;
+    const uint32_t groups = (uint32_t)L.N * HWV;
+    const int padw = L.row_pitch - L.W;
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * 4u);
+
+    float x[4][V];
+    uint32_t eoff[4], doff[4];
+    bool live[4], row_end[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        x[i] = 0.0f;
-        idx[i] = -1;
-        if (o + i >= 0) {
-            const int h = r * L.phases_h + ph - L.org_h;
-            const int w = col * L.phases_w + pw - L.org_w;
-            const bool ok = n < L.N && h >= 0 && h < L.H && w >= 0 && w < L.W;
-            idx[i] = ok ? (((int64_t)n * L.C + c) * L.H + h) * L.W + w : -1;
-            x[i] = ldf_or_zero(src + idx[i], ok);
-            if (++col == L.row_pitch) {
-                col = 0;
-                if (++r == L.img_rows) { r = 0; ++n; }
-            }
+    for (int u = 0; u < 4; ++u) {
+        const uint32_t gi = (uint32_t)jb * 1024u + tid + 256u * u;   // group of V elements inside the channel
+        live[u] = gi < groups;
+        const uint32_t gc = live[u] ? gi : 0u;
+        const uint32_t n = fdiv(gc, pa.div_hwv);
+        const uint32_t rem = gc - __umul24(n, HWV);
+        const uint32_t h = fdiv(rem, pa.div_wv);
+        const uint32_t wv = rem - __umul24(h, WV);
+        row_end[u] = live[u] & (wv + 1 == WV);
+        eoff[u] = live[u] ? __umul24(__umul24(n, (uint32_t)L.C) + (uint32_t)c, HW) * 4u + rem * (4u * V) : kOobOff;
+        doff[u] = (uint32_t)L.lead + __umul24(__umul24(n, (uint32_t)L.img_rows) + h, (uint32_t)L.row_pitch) + wv * V;
+        if (V == 4) {
+            const v4u raw = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)eoff[u], 0, 0);
+#pragma unroll
+            for (int i = 0; i < V; ++i) x[u][i] = __uint_as_float(raw[i]);
+        } else {
+            const v2u raw = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)eoff[u], 0, 0);
+#pragma unroll
+            for (int i = 0; i < V; ++i) x[u][i] = __uint_as_float(raw[i]);
         }
     }
-    uint32_t w4[4] = {0u, 0u, 0u, 0u};
+
+    float s;
+    if (CLIP) s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb == 0, l_cnt);
+    else s = pa.per_channel_scale ? scale[c] : scale[0];
+    const float inv = inv_scale(s);
+
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int code = (idx[i] >= 0) ? quant_code<STOCH>(x[i], inv, seed, tensor, (uint64_t)idx[i]) : 0;
-        w4[i >> 2] |= ((uint32_t)code & 0xFFu) << (8 * (i & 3));
+    for (int u = 0; u < 4; ++u) {
+        uint32_t bits[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u] >> 2) + i);
+        if (live[u]) store_codes<V>(plane + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
+        if (row_end[u])
+            for (int k = 0; k < padw; ++k) plane[doff[u] + V + k] = 0;
     }
-    *reinterpret_cast<uint4*>(dst + (int64_t)c * L.chan_pitch + (int64_t)phase * L.plane_pitch + 16 * j) =
-        make_uint4(w4[0], w4[1], w4[2], w4[3]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -407,11 +644,78 @@ __global__ __launch_bounds__(kBlock) void k_pack_w(const float* __restrict__ W, 
     out[L.off_bwd + ((int64_t)tap * Cin + ci) * L.cog_pitch + col] = code;
 }
 
-// grid of k_pack_cnhw: x enumerates (channel, block of 16-byte units) with the channel's XCD in the low bits,
+// grid of k_pack_cnhw: x enumerates (channel, block of 1024 dwords) with the channel's XCD in the low bits,
 // z the stride phase
-int pack_per_chan(const daq_layout& L) { return (int)ceil_div(L.plane_pitch / 16, kBlock); }
+int pack_per_chan(const daq_layout& L) { return (int)ceil_div(L.plane_pitch / 4, 4 * kBlock); }
 dim3 pack_grid(const daq_layout& L) {
     return dim3((unsigned)(round_up(L.C, kXcd) * pack_per_chan(L)), 1u, (unsigned)(L.phases_h * L.phases_w));
+}
+PackArgs pack_args(const daq_layout& L, int per_channel_scale, uint32_t tensor, uint64_t seed) {
+    PackArgs pa{};
+    pa.div_slot = make_fastdiv((uint32_t)(L.img_rows * L.row_pitch));
+    pa.div_pitch = make_fastdiv((uint32_t)L.row_pitch);
+    pa.per_chan = pack_per_chan(L);
+    pa.per_channel_scale = per_channel_scale;
+    pa.tensor = tensor;
+    pa.seed = seed;
+    return pa;
+}
+// The packing kernel indexes a plane with 32-bit integers.
+bool pack_supported(const daq_layout& L) {
+    const int64_t lim24 = (int64_t)1 << 24;
+    return L.plane_pitch + (int64_t)L.img_rows * L.row_pitch < ((int64_t)1 << 31) && (L.plane_pitch & 3) == 0 &&
+           (int64_t)L.img_rows * L.row_pitch < lim24 && (int64_t)(L.N + 1) * L.C < lim24 / 2 && (int64_t)L.H * L.W < lim24 / 2 &&
+           (int64_t)L.img_rows * L.phases_h < lim24 && (int64_t)L.row_pitch * L.phases_w < lim24;
+}
+// The quantization kernels read an fp32 tensor through a buffer descriptor with 32-bit offsets.
+bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31); }
+
+
+// Launches the channel-major packing of one fp32 NCHW tensor: the source-driven row kernel when the
+// layout allows it, the output-driven kernel otherwise.
+daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src, const daq_layout& Ld,
+                       const float* scale, int per_channel_scale, int8_t* dst, uint32_t tensor, uint64_t seed,
+                       const QuantWs& ws, const ClipArgs& ca, hipStream_t st) {
+    const CnhwView V = cnhw_view(Ld);
+    const int64_t lim24 = (int64_t)1 << 24;
+    const bool unsplit = Ld.phases_h == 1 && Ld.phases_w == 1 && Ld.org_h == 0 && Ld.org_w == 0 &&
+                         (int64_t)Ld.N * Ld.img_rows < lim24 && (int64_t)Ld.H * Ld.W < lim24 &&
+                         (int64_t)(Ld.N + 1) * Ld.C < lim24 && Ld.plane_pitch < ((int64_t)1 << 31);
+    int v = 0;
+    if (unsplit && Ld.W % 4 == 0 && ((uintptr_t)src & 15u) == 0) v = 4;
+    else if (unsplit && Ld.W % 2 == 0 && ((uintptr_t)src & 7u) == 0) v = 2;
+    if (v) {
+        RowsArgs ra{};
+        const uint32_t hwv = (uint32_t)(Ld.H * Ld.W / v);
+        ra.div_hwv = make_fastdiv(hwv);
+        ra.div_wv = make_fastdiv((uint32_t)(Ld.W / v));
+        ra.div_prb = make_fastdiv((uint32_t)std::max(1, (Ld.img_rows - Ld.H) * Ld.row_pitch));
+        ra.per_chan = (int)ceil_div((int64_t)Ld.N * hwv, 4 * kBlock);
+        ra.per_channel_scale = per_channel_scale;
+        ra.tensor = tensor;
+        ra.seed = seed;
+        const dim3 grid((unsigned)(round_up(Ld.C, kXcd) * (ra.per_chan + 1)));
+#define DAQ_ROWS(S, CL, VV) \
+    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_rows<S, CL, VV>), grid, dim3(kBlock), 0, st, src, V, scale, dst, ra, ws, ca))
+        if (v == 4) {
+            if (stoch) { if (clip) DAQ_ROWS(true, true, 4); else DAQ_ROWS(true, false, 4); }
+            else { if (clip) DAQ_ROWS(false, true, 4); else DAQ_ROWS(false, false, 4); }
+        } else {
+            if (stoch) { if (clip) DAQ_ROWS(true, true, 2); else DAQ_ROWS(true, false, 2); }
+            else { if (clip) DAQ_ROWS(false, true, 2); else DAQ_ROWS(false, false, 2); }
+        }
+#undef DAQ_ROWS
+        return DAQ_OK;
+    }
+    if (!pack_supported(Ld)) return DAQ_ERR_UNSUPPORTED;
+    const PackArgs pa = pack_args(Ld, per_channel_scale, tensor, seed);
+    const dim3 grid = pack_grid(Ld);
+#define DAQ_PACK(S, CL) \
+    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_cnhw<S, CL>), grid, dim3(kBlock), 0, st, src, V, scale, dst, pa, ws, ca))
+    if (stoch) { if (clip) DAQ_PACK(true, true); else DAQ_PACK(true, false); }
+    else { if (clip) DAQ_PACK(false, true); else DAQ_PACK(false, false); }
+#undef DAQ_PACK
+    return DAQ_OK;
 }
 
 }  // namespace
@@ -436,16 +740,16 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
 
     daq_layout Ln, Lc;
     if (daq_layout_qx_nhwc(&d, &Ln) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lc) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
+    if (!f32_tensor_supported(n)) return DAQ_ERR_UNSUPPORTED;
     const int HW = d.Hin * d.Win;
-    const int ptiles = (int)ceil_div(HW, kWave);
     const int CB = (int)ceil_div(d.Cin, 64);
-    QuantWs none{};
+    QuantWs geo = carve_quant_ws(nullptr, d.Cin, d.N, HW);  // only the tile geometry is used: nothing is counted here
     DAQ_LAUNCH("quant_nhwc", st,
-               hipLaunchKernelGGL((k_count_qg<false, true, false>), dim3(CB * d.N * ptiles), dim3(kBlock), 0, st, X,
-                                  d.N, d.Cin, HW, Ln.c_pitch, ptiles, none, (const float*)s_x, qx_nhwc, (uint64_t)0));
-    DAQ_LAUNCH("pack_cnhw", st,
-               hipLaunchKernelGGL((k_pack_cnhw<false>), pack_grid(Lc), dim3(kBlock), 0, st, X, cnhw_view(Lc),
-                                  (const float*)s_x, 0, qx_cnhw, (uint64_t)0, 0u, pack_per_chan(Lc)));
+               hipLaunchKernelGGL((k_count_qg<false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
+                                  d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
+                                  (uint64_t)0, (const float*)nullptr, (float*)nullptr));
+    const daq_status prc = launch_pack("pack_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st);
+    if (prc != DAQ_OK) return prc;
     return DAQ_OK;
 }
 
@@ -490,33 +794,34 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     const size_t need = daq_workspace_bytes(DAQ_OP_QUANTIZE_GRAD, desc);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return DAQ_ERR_WORKSPACE;
 
+    if (!f32_tensor_supported((int64_t)desc->N * desc->Cout * daq_out_h(desc) * daq_out_w(desc)))
+        return DAQ_ERR_UNSUPPORTED;
+
     hipStream_t st = (hipStream_t)stream;
     const int N = desc->N, C = desc->Cout, Ho = daq_out_h(desc), Wo = daq_out_w(desc);
-    const int HW = Ho * Wo, M = N * HW;
+    const int HW = Ho * Wo;
     const bool stoch = (mode == DAQ_ROUND_STOCHASTIC);
     const bool qg_nhwc = (Lg.kind == DAQ_LAYOUT_NHWC);
     QuantWs ws = carve_quant_ws(workspace, C, N, HW);
-    (void)M;
 
-    // S1: partial statistics, then one workgroup per channel folds them
+    // S1: statistics partials, at most 16 per channel
     const bool vec4 = (HW % 4 == 0) && (((uintptr_t)dY & 15u) == 0);
-    const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.chunks);
+    const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.slabs);
     if (vec4)
         DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
     else
         DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
-    DAQ_LAUNCH("stats_final", st, hipLaunchKernelGGL(k_stats_final, dim3(C), dim3(kBlock), 0, st, N, C, HW, ws));
 
-    // S2 (+ the NHWC global copy), then S3 + S4
-    ClipArgs ca{k, A, lambda, s_state, s_chan, s_global, cls, stats};
-    const int ptiles = (int)ceil_div(HW, kWave);
+    // S2 (+ the NHWC global copy); folds the statistics itself
     const int CB = (int)ceil_div(C, 64);
-    const dim3 cgrid((unsigned)(CB * N * ptiles));
+    const dim3 cgrid((unsigned)(CB * ws.cgroups));
     const float* no_scale = nullptr;
+    const FastDiv div_hw = make_fastdiv((uint32_t)HW);
 #define DAQ_COUNT_LAUNCH(S, Q)                                                                                       \
     DAQ_LAUNCH("count_qg", st,                                                                                       \
                hipLaunchKernelGGL((k_count_qg<S, Q, true>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,                \
-                                  qg_nhwc ? Lg.c_pitch : 0, ptiles, ws, no_scale, qg, seed))
+                                  qg_nhwc ? Lg.c_pitch : 0, div_hw, ws, no_scale, qg, seed, (const float*)s_state,   \
+                                  s_global))
     if (qg_nhwc) {
         if (stoch) DAQ_COUNT_LAUNCH(true, true);
         else DAQ_COUNT_LAUNCH(false, true);
@@ -524,28 +829,12 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
         DAQ_COUNT_LAUNCH(false, false);
     }
 #undef DAQ_COUNT_LAUNCH
-    DAQ_LAUNCH("clip_final", st, hipLaunchKernelGGL(k_clip_final, dim3(C), dim3(kBlock), 0, st, N, C, HW, ws, ca));
 
-    // S5: per-channel copy (and the global copy for depthwise layers) in CNHW
-    const CnhwView V = cnhw_view(Lv);
-    const dim3 pgrid = pack_grid(Lv);
-    if (stoch)
-        DAQ_LAUNCH("pack_vq", st,
-                   hipLaunchKernelGGL((k_pack_cnhw<true>), pgrid, dim3(kBlock), 0, st, dY, V, (const float*)s_chan, 1,
-                                      vq, seed, 0u, pack_per_chan(Lv)));
-    else
-        DAQ_LAUNCH("pack_vq", st,
-                   hipLaunchKernelGGL((k_pack_cnhw<false>), pgrid, dim3(kBlock), 0, st, dY, V, (const float*)s_chan,
-                                      1, vq, seed, 0u, pack_per_chan(Lv)));
-    if (!qg_nhwc) {
-        if (stoch)
-            DAQ_LAUNCH("pack_qg", st,
-                       hipLaunchKernelGGL((k_pack_cnhw<true>), pgrid, dim3(kBlock), 0, st, dY, V,
-                                          (const float*)s_global, 0, qg, seed, 1u, pack_per_chan(Lv)));
-        else
-            DAQ_LAUNCH("pack_qg", st,
-                       hipLaunchKernelGGL((k_pack_cnhw<false>), pgrid, dim3(kBlock), 0, st, dY, V,
-                                          (const float*)s_global, 0, qg, seed, 1u, pack_per_chan(Lv)));
-    }
-    return DAQ_OK;
+    // S3 + S4 + S5: discriminator, clip rule and the per-channel copy in CNHW (and the global copy for
+    // depthwise layers, whose data gradient also runs channel-major)
+    ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
+    rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, seed, ws, ca, st);
+    if (rc != DAQ_OK) return rc;
+    if (!qg_nhwc) rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);
+    return rc;
 }

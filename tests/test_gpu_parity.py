@@ -89,6 +89,9 @@ ODD_LAYERS = [
     wl.Layer("dw_s2", 2, 16, 12, 12, 16, 3, 3, 2, 1, 1, 16),
     wl.Layer("big_hw", 1, 4, 67, 67, 4, 3, 3, 1, 1),           # several pixel tiles with a ragged tail
     wl.Layer("one_px", 5, 4, 1, 1, 7, 1, 1, 1, 0),             # 1x1 images
+    wl.Layer("w14", 3, 8, 14, 14, 20, 3, 3, 1, 1),             # rows of 14: two codes per store
+    wl.Layer("w14_1x1", 4, 16, 14, 14, 70, 1, 1, 1, 0),        # no padding rows or columns at all
+    wl.Layer("long_m", 40, 4, 56, 56, 4, 3, 3, 1, 1),          # workgroups loop over several chunks / tiles
 ]
 
 
@@ -99,6 +102,27 @@ def test_quantize_grad_ragged_shapes(layer):
     st = wl.make_state(dY, seed)
     check_quantize_grad(layer, dY, st)
     check_quantize_grad(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=99)
+
+
+def test_quantize_grad_with_a_source_that_is_only_4_byte_aligned():
+    layer = wl.Layer("misaligned", 2, 8, 12, 12, 10, 3, 3, 1, 1)
+    seed = wl.seed_for(9, 77)
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    d, _ = descs(layer)
+    buf = torch.zeros(dY.size + 4, dtype=torch.float32, device="cuda")
+    for shift in (1, 2):
+        g = buf[shift:shift + dY.size].view(dY.shape)
+        g.copy_(t(dY))
+        assert g.data_ptr() % 16 != 0 and g.is_contiguous()
+        st_dev = t(st.copy())
+        out = daq.quantize_grad(d, g, st_dev)
+        torch.cuda.synchronize()
+        r = ref.quantize_grad(dY, st)
+        assert np.array_equal(daq.layout_vq(d).unpack(out.vq), r.vq)
+        assert np.array_equal(daq.layout_qg(d).unpack(out.qg), r.qg)
+        assert np.array_equal(out.cls.cpu().numpy(), r.cls)
+        assert daq.layout_vq(d).padding_is_zero(out.vq)
 
 
 def test_quantize_grad_degenerate_channels():
