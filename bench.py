@@ -42,6 +42,10 @@ def main() -> int:
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=1, help="number of dY buffer sets cycled through (cold-cache runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2: the two convolutions, which are independent once dY is quantized, run on two streams")
+    ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
+                    help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="after the timed region, run 5 device-to-device copies of this many MiB: the plain copy "
                          "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -77,28 +81,74 @@ def main() -> int:
     dXs = [torch.empty(d.x_shape, dtype=torch.float32, device=dev) for _ in range(R)]
     ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
     ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream()
+    main_s = torch.cuda.Stream()
+    side_s = torch.cuda.Stream() if args.streams == 2 else None
 
-    def step(i: int):
+    def step(i: int, fork: bool = True):
+        # Algorithm 1 for one layer.  dW needs the per-channel copy, dX the global copy: after the quantizer
+        # the two convolutions share no data, so with two streams they overlap.
         r = i % R
-        q = daq.quantize_grad(d, dYs[r], states[r], out=outs[r], stream=stream)
-        daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=stream)
-        daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=stream)
+        q = daq.quantize_grad(d, dYs[r], states[r], out=outs[r], stream=main_s)
+        if side_s is not None and fork:
+            side_s.wait_stream(main_s)
+            daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=side_s)
+            daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=main_s)
+            main_s.wait_stream(side_s)
+        else:
+            daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=main_s)
+            daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=main_s)
+
+    torch.cuda.synchronize()
+    graphs = None
+    if args.graph:
+        # one captured step per buffer set; every replay is checked against the eager result below
+        with torch.cuda.stream(main_s):
+            step(0)
+        torch.cuda.synchronize()
+        graphs = []
+        for r in range(R):
+            gph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gph, stream=main_s):
+                step(r)
+            graphs.append(gph)
+        torch.cuda.synchronize()
+
+    def run(i: int):
+        if graphs is not None:
+            graphs[i % R].replay()
+        else:
+            step(i)
 
     for i in range(args.warmup):
-        step(i)
+        run(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i)
+        run(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / args.steps
 
-    # per-kernel durations: the same K steps with a HIP event pair around every launch
+    # the schedule under test must reproduce the plain single-stream result bit for bit (state: same input each time)
+    chk_state = torch.from_numpy(st.copy()).to(dev)
+    states[0].copy_(chk_state)
+    torch.cuda.synchronize()
+    run(0)
+    torch.cuda.synchronize()
+    got = (dWs[0].clone(), dXs[0].clone(), outs[0].vq.clone(), outs[0].qg.clone())
+    states[0].copy_(chk_state)
+    torch.cuda.synchronize()
+    step(0, fork=False)
+    torch.cuda.synchronize()
+    same = all(torch.equal(a, b) for a, b in zip(got, (dWs[0], dXs[0], outs[0].vq, outs[0].qg)))
+    if not same:
+        print("bench.py: the timed schedule does not reproduce the single-stream result", file=sys.stderr)
+        return 3
+
+    # per-kernel durations: K single-stream steps with a HIP event pair around every launch
     daq.prof_begin()
     for i in range(args.steps):
-        step(i)
+        step(i, fork=False)
     rows = daq.prof_end()
     torch.cuda.synchronize()
 
@@ -181,7 +231,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config{args.config}:{layer.name} N={layer.N} {layer.Cin}->{layer.Cout} "
                                f"{layer.Hin}x{layer.Win} k{layer.kH} s{layer.stride} p{layer.pad}",
-                   "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3},
+                   "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3,
+                   "streams": args.streams, "hip_graph": bool(args.graph)},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "quant_GBps_effective_6B": round(6.0 * E_Y / (quant_us * 1e-6) / 1e9, 1) if quant_us else None,
         "quant_us": round(quant_us, 2),

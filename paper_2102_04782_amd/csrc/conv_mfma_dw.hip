@@ -20,6 +20,9 @@
 // 256 CUs busy on layers with few channels.  K may also be split across workgroups: each writes its
 // partial tile with coalesced stores and a second kernel sums the partials (exact, order independent)
 // and de-quantizes.  Global loads run PF chunks ahead of the MFMAs through a register FIFO.
+#include <algorithm>
+#include <type_traits>
+
 #include "daq_internal.h"
 
 namespace daq {
@@ -30,6 +33,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
+typedef int v4i_a1 __attribute__((ext_vector_type(4), aligned(1)));
 
 constexpr int kKC = 256;          // K bytes staged per chunk (4 MFMA K-steps of 64)
 constexpr int kPA = kKC + 16;     // LDS row pitch: +16 B holds the realignment slack and rotates banks between rows
@@ -455,6 +459,198 @@ __global__ __launch_bounds__(256) void k_dw_direct(DwArgs p) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// General form: any filter extent, stride and dilation.  A tap (kh, kw) pairs gradient position f
+// with byte  tap_off[t] + f  of an activation channel, where tap_off selects the stride-phase plane
+// the tap reads and its shift inside it; the host tabulates it, the kernel never looks at the
+// geometry.  Same barrier-free scheme as above: MFMA fragments straight from global memory (G
+// aligned, X with byte alignment), PFD steps ahead.  Either the four waves split the K steps and
+// every wave holds all taps (WTAPS = false, filters up to 3 x 3), or every wave runs all K steps
+// of the workgroup on its own share of the taps (WTAPS = true; 4 or 8 waves, up to 56 taps, e.g. 7 x 7).
+// Rows past Cout / Cin and unused tap slots compute on valid memory and are never stored.
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxTapSlots = 56;
+struct TapTable {
+    int64_t off[kMaxTapSlots];   // byte offset of the tap's window start inside an activation channel
+    int id[kMaxTapSlots];        // kh*kW + kw, or -1 for an unused slot
+    int T;                       // kH * kW
+};
+
+template <int TW, int NB, int PFD, bool WTAPS, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
+    static_assert(WTAPS || WAVES == 4, "the K-splitting form hands tiles over between exactly four waves");
+    static_assert(WAVES * TW <= kMaxTapSlots, "tap table too small");
+    constexpr int NT = NB * TW;
+    extern __shared__ __align__(16) int8_t lds[];
+    int* red = reinterpret_cast<int*>(lds);  // !WTAPS: [owner 4][source 3][NT*4][64]
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int li = lane & 15, lg = lane >> 4;
+    int split, tile;
+    {
+        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+        const int full = (p.splits / kXcd) * kXcd;
+        const int x = b % kXcd, q = b / kXcd;
+        if (q < (full / kXcd) * tiles) {
+            split = (q / tiles) * kXcd + x;
+            tile = q % tiles;
+        } else {
+            const int rb = b - full * tiles;
+            split = full + rb % (p.splits - full);
+            tile = rb / (p.splits - full);
+        }
+    }
+    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    const int co0 = tm * kBM, ci0 = tn * 16 * NB;
+    // K steps (64 bytes each) of this wave
+    const int nsteps = p.nchunks * (kKC / 64);
+    const int units = WTAPS ? p.splits : p.splits * 4;
+    const int unit = WTAPS ? split : split * 4 + wave;
+    const int per = nsteps / units, rem = nsteps % units;
+    const int s_begin = unit * per + min(unit, rem);
+    const int s_end = s_begin + per + (unit < rem ? 1 : 0);
+
+    // Addresses are a wave-uniform 64-bit base (operand + tap offset + K position, kept in scalar registers)
+    // plus a 32-bit per-lane offset (row and 16-byte K group); both operands are smaller than 2 GiB.
+    uint32_t va[4], vb[NB];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int co = co0 + 16 * m + li;
+        va[m] = (uint32_t)((int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * lg);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int ci = ci0 + 16 * nb + li;
+        vb[nb] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * lg);
+    }
+    // wave-uniform tap offsets and ids; the table is indexed with constants only (a run-time index into a
+    // by-value kernel argument would make the compiler copy it to scratch memory)
+    int64_t toff[TW];
+    int tid_of[TW];
+#pragma unroll
+    for (int j = 0; j < TW; ++j) {
+        toff[j] = tt.off[j];
+        tid_of[j] = tt.id[j];
+        if (WTAPS) {
+#pragma unroll
+            for (int w = 1; w < WAVES; ++w)
+                if (wave == w) { toff[j] = tt.off[w * TW + j]; tid_of[j] = tt.id[w * TW + j]; }
+        }
+    }
+
+    v4i acc[4][NT];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[m][t] = v4i{0, 0, 0, 0};
+
+    v4i ra[PFD][4];
+    v4i rb[PFD][NT];
+    auto load_step = [&](int s, int slot) {
+        const int64_t k = (int64_t)s * 64;
+        const int8_t* gk = p.g + k;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) ra[slot][m] = *reinterpret_cast<const v4i*>(gk + va[m]);
+#pragma unroll
+        for (int j = 0; j < TW; ++j) {
+            const int8_t* xk = p.x + (toff[j] + k);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const v4i_a1 v = *reinterpret_cast<const v4i_a1*>(xk + vb[nb]);
+                rb[slot][nb * TW + j] = v4i{v[0], v[1], v[2], v[3]};
+            }
+        }
+    };
+
+#pragma unroll
+    for (int i = 0; i < PFD; ++i)
+        if (s_begin + i < s_end) load_step(s_begin + i, i);
+
+    for (int base = s_begin; base < s_end; base += PFD) {
+#pragma unroll
+        for (int u = 0; u < PFD; ++u) {
+            const int s = base + u;
+            if (s < s_end) {
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int m = 0; m < 4; ++m)
+                        acc[m][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ra[u][m], rb[u][t], acc[m][t], 0, 0, 0);
+                if (s + PFD < s_end) load_step(s + PFD, u);
+            }
+        }
+    }
+
+    const float sx = *p.s_x / 127.0f;
+    const int T = tt.T;
+    // stores accumulator (m, nb, j) of this wave; partial layout q = (m*(NB*T) + nb*T + tap)*4 + r
+    auto emit = [&](auto mc) __attribute__((always_inline)) {
+        constexpr int m = decltype(mc)::value;
+        int32_t* part = p.part + ((int64_t)tile * p.splits + split) * (16 * NB * T) * kWave + lane;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int ci = ci0 + 16 * nb + li;
+#pragma unroll
+            for (int j = 0; j < TW; ++j) {
+                const int tap = tid_of[j];
+                if (tap < 0) continue;   // wave-uniform
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int v = acc[m][nb * TW + j][r];
+                    if (p.splits > 1) {
+                        part[(int64_t)((m * NB * T + nb * T + tap) * 4 + r) * kWave] = v;
+                    } else {
+                        const int co = co0 + 16 * m + 4 * lg + r;
+                        if (ci < p.Cin && co < p.Cout) {
+                            const int64_t off = ((int64_t)co * p.Cin + ci) * T + tap;
+                            p.dW[off] = (float)v * (sx * (p.s_chan[co] / 127.0f));
+                            if (p.acc_out) p.acc_out[off] = v;
+                        }
+                    }
+                }
+            }
+        }
+    };
+
+    if (WTAPS) {
+        emit(std::integral_constant<int, 0>{});
+        emit(std::integral_constant<int, 1>{});
+        emit(std::integral_constant<int, 2>{});
+        emit(std::integral_constant<int, 3>{});
+        return;
+    }
+    // ---- wave m collects co block m from the other three waves ----
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        if (wave != m) {
+            const int srcw = wave < m ? wave : wave - 1;
+            int* dst = red + ((m * 3 + srcw) * NT * 4) * kWave + lane;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dst[(t * 4 + r) * kWave] = acc[m][t][r];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        if (wave == m) {
+#pragma unroll
+            for (int w = 0; w < 3; ++w) {
+                const int* src = red + ((m * 3 + w) * NT * 4) * kWave + lane;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[m][t][r] += src[(t * 4 + r) * kWave];
+            }
+        }
+    }
+    if (wave == 0) emit(std::integral_constant<int, 0>{});
+    if (wave == 1) emit(std::integral_constant<int, 1>{});
+    if (wave == 2) emit(std::integral_constant<int, 2>{});
+    if (wave == 3) emit(std::integral_constant<int, 3>{});
+}
+
 // Sum of the K-split partial tiles, then dW[co][...] = acc * ((s_x/127) * (s_chan[co]/127)).
 // A workgroup owns 64 consecutive slots of the partial layout (one 256-byte run per split); its four
 // waves take every fourth split with eight loads in flight each and combine through LDS.
@@ -499,17 +695,55 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ p
 
 struct Plan {
     bool ok;
+    bool general;         // tap-table kernel (any extent, stride, dilation)
+    int tw;               // general: tap slots per wave
+    bool wtaps;           // general: waves split the taps instead of K
     int kh, wgk, nb, pf, splits, tiles_m, tiles_n, nchunks;
     size_t lds_bytes;
     int64_t part_slots;   // int32 slots of one split's worth of partial tiles
 };
 
+// Plan of the tap-table kernel.
+Plan make_general_plan(const daq_conv_desc& d) {
+    Plan pl{};
+    const int T = d.kH * d.kW;
+    if (d.groups != 1 || T > kMaxTapSlots) return pl;
+    daq_layout Lg;
+    if (daq_layout_vq(&d, &Lg) != DAQ_OK) return pl;
+    pl.general = true;
+    pl.kh = d.kH;
+    pl.nchunks = (int)(Lg.plane_pitch / kKC);
+    if (T == 1) { pl.tw = 1; pl.nb = 4; pl.wtaps = false; pl.pf = 4; }
+    else if (T <= 9) { pl.tw = 9; pl.nb = 1; pl.wtaps = false; pl.pf = 3; }
+    else { pl.tw = 7; pl.nb = 1; pl.wtaps = true; pl.pf = 2; }   // 4 waves up to 28 taps, 8 waves beyond
+    pl.wgk = pl.wtaps ? 1 : 4;
+    pl.tiles_m = (int)ceil_div(d.Cout, kBM);
+    pl.tiles_n = (int)ceil_div(d.Cin, 16 * pl.nb);
+    const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+    const int64_t nsteps = (int64_t)pl.nchunks * (kKC / 64);
+    int64_t s = ceil_div(512, tiles);
+    const int64_t max_by_steps = std::max<int64_t>(1, nsteps / (pl.wtaps ? 2 : 8));   // at least two steps per wave
+    if (s > max_by_steps) s = max_by_steps;
+    // partial tiles are written and read once: keep that below ~2x the operand bytes
+    const int64_t operand = (int64_t)d.Cout * Lg.plane_pitch + (int64_t)d.Cin * Lg.plane_pitch * d.strideH * d.strideW;
+    const int64_t tile_bytes = tiles * kBM * 16 * pl.nb * T * 4;
+    const int64_t max_by_traffic = std::max<int64_t>(1, operand / tile_bytes);
+    if (s > max_by_traffic) s = max_by_traffic;
+    pl.splits = (int)std::max<int64_t>(1, s);
+    pl.lds_bytes = pl.wtaps ? 256 : (size_t)12 * pl.nb * pl.tw * 4 * kWave * 4;
+    if (pl.lds_bytes > 160 * 1024) return pl;
+    pl.part_slots = tiles * 16 * pl.nb * T * kWave;
+    pl.ok = true;
+    return pl;
+}
+
 Plan make_plan(const daq_conv_desc& d) {
     Plan pl{};
     pl.ok = false;
-    if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1) return pl;
-    if (!((d.kH == 3 && d.kW == 3) || (d.kH == 1 && d.kW == 1))) return pl;
-    if (d.kH == 1 && (d.padH != 0 || d.padW != 0)) return pl;
+    if (d.groups != 1) return pl;
+    const bool unit = d.strideH == 1 && d.strideW == 1 && d.dilH == 1 && d.dilW == 1;
+    const bool tuned = unit && ((d.kH == 3 && d.kW == 3) || (d.kH == 1 && d.kW == 1 && d.padH == 0 && d.padW == 0));
+    if (!tuned) return make_general_plan(d);
     daq_layout Lg;
     if (daq_layout_vq(&d, &Lg) != DAQ_OK) return pl;
     pl.kh = d.kH;
@@ -596,6 +830,35 @@ daq_status launch_dw_direct(const Plan& pl, const DwArgs& a, int wq4, hipStream_
     return DAQ_ERR_UNSUPPORTED;
 }
 
+template <int TW, int NB, int PFD, bool WTAPS, int WAVES>
+daq_status launch_dw_taps(const Plan& pl, const DwArgs& a, const TapTable& tt, hipStream_t st) {
+    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+    auto kern = k_dw_taps<TW, NB, PFD, WTAPS, WAVES>;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
+        return DAQ_ERR_HIP;
+    DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WAVES), pl.lds_bytes, st, a, tt));
+    return DAQ_OK;
+}
+
+// Window start of every tap inside an activation channel: the stride-phase plane it reads plus its
+// shift there.  With P = padded coordinate (h + pad), tap kh reads P = ho*stride + kh*dil, i.e. phase
+// (kh*dil) % stride at row ho + (kh*dil) / stride; unit stride is the one-phase case.
+TapTable make_tap_table(const daq_conv_desc& d, const daq_layout& Lx, const Plan& pl) {
+    TapTable tt{};
+    tt.T = d.kH * d.kW;
+    for (int j = 0; j < kMaxTapSlots; ++j) { tt.off[j] = 0; tt.id[j] = -1; }
+    for (int kh = 0; kh < d.kH; ++kh)
+        for (int kw = 0; kw < d.kW; ++kw) {
+            const int t = kh * d.kW + kw;
+            const int ph = (kh * d.dilH) % Lx.phases_h, pw = (kw * d.dilW) % Lx.phases_w;
+            tt.off[t] = (int64_t)(ph * Lx.phases_w + pw) * Lx.plane_pitch +
+                        (int64_t)(kh * d.dilH / Lx.phases_h) * Lx.row_pitch + (kw * d.dilW / Lx.phases_w);
+            tt.id[t] = t;
+        }
+    (void)pl;
+    return tt;
+}
+
 }  // namespace
 
 bool bwd_filter_mfma_supported(const daq_conv_desc& d) { return make_plan(d).ok; }
@@ -632,13 +895,19 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     a.acc_out = acc;
     daq_status rc;
     const int wq4 = Lx.row_pitch & 3;
-    if (d.kH == 3)
+    if (pl.general) {
+        const TapTable tt = make_tap_table(d, Lx, pl);
+        if (pl.tw == 1) rc = launch_dw_taps<1, 4, 4, false, 4>(pl, a, tt, st);
+        else if (pl.tw == 9) rc = launch_dw_taps<9, 1, 3, false, 4>(pl, a, tt, st);
+        else if (T <= 28) rc = launch_dw_taps<7, 1, 2, true, 4>(pl, a, tt, st);
+        else rc = launch_dw_taps<7, 1, 2, true, 8>(pl, a, tt, st);
+    } else if (d.kH == 3)
         rc = (pl.wgk == 4) ? launch_dw_direct<3, 3, 1, 3>(pl, a, wq4, st) : launch_dw<3, 3, 1, 1, 1>(pl, a, wq4, st);
     else
         rc = (pl.wgk == 4) ? launch_dw_direct<1, 1, 4, 4>(pl, a, 0, st) : launch_dw<1, 1, 1, 4, 1>(pl, a, 0, st);
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1) {
-        const int wgn = 4 / pl.wgk;
+        const int wgn = pl.general ? 1 : 4 / pl.wgk;
         DAQ_LAUNCH("dw_reduce", st,
                    hipLaunchKernelGGL(k_dw_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st,
                                       a.part, pl.splits, pl.tiles_n, wgn, pl.nb, T, d.Cout, d.Cin, s_x, s_chan, dW,

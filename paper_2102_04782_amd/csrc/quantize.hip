@@ -171,7 +171,8 @@ __device__ __forceinline__ void block_reduce(float& mx, double& s1, double& s2) 
 // instead of waiting for a reduction launch.  Channel c runs on XCD c % 8 in every pass over dY.
 // ---------------------------------------------------------------------------------------------
 template <bool VEC4>
-__global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, QuantWs ws) {
+__global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, FastDiv div_hw,
+                                                  QuantWs ws) {
     constexpr int NV = VEC4 ? 4 : 16;
     const int b = blockIdx.x;
     const int xcd = b % kXcd, q = b / kXcd;
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
             const int m = VEC4 ? m0 + 4 * (tid + u * kBlock) : m0 + tid + u * kBlock;
             const bool ok = live && m < M;
             const int mc = ok ? m : 0;
-            const int n = mc / HW, i = mc - n * HW;
+            const int n = (int)fdiv((uint32_t)mc, div_hw), i = mc - n * HW;
             const float* src = g + ((int64_t)n * C + c) * HW + i;
             if (VEC4) dst[u] = ld16_or_zero(src, ok);
             else dst[u].x = __float_as_uint(ldf_or_zero(src, ok));
@@ -232,13 +233,24 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
 // Partials of channel c -> |g|max, mean, sigma (population std about the mean, fp64, rounded once).
 // Sequential in slab order, so every workgroup that calls it gets the same bits.
 __device__ __forceinline__ void fold_stats(const QuantWs& ws, int c, double Md, float& gmax, float& mean, float& sigma) {
+    // all partials are requested before the first one is used; slots past `slabs` read zeros, which change nothing
+    float pm[kMaxSlabs];
+    double p1[kMaxSlabs], p2[kMaxSlabs];
+#pragma unroll
+    for (int j = 0; j < kMaxSlabs; ++j) {
+        const bool ok = j < ws.slabs;
+        const int64_t slot = (int64_t)c * ws.slabs + j;
+        pm[j] = ldf_or_zero(ws.part_max + slot, ok);
+        p1[j] = *(ok ? ws.part_s1 + slot : reinterpret_cast<const double*>(g_zero64));
+        p2[j] = *(ok ? ws.part_s2 + slot : reinterpret_cast<const double*>(g_zero64));
+    }
     float mx = 0.0f;
     double s1 = 0.0, s2 = 0.0;
-    for (int j = 0; j < ws.slabs; ++j) {
-        const int64_t slot = (int64_t)c * ws.slabs + j;
-        mx = fmaxf(mx, ws.part_max[slot]);
-        s1 += ws.part_s1[slot];
-        s2 += ws.part_s2[slot];
+#pragma unroll
+    for (int j = 0; j < kMaxSlabs; ++j) {
+        mx = fmaxf(mx, pm[j]);
+        s1 += p1[j];
+        s2 += p2[j];
     }
     const double mu = s1 / Md;
     double var = s2 / Md - mu * mu;
@@ -298,7 +310,14 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
         sg = *scale_ptr;
     } else {
         float m = 0.0f;
-        for (int i = tid; i < C * ws.slabs; i += kBlock) m = fmaxf(m, ws.part_max[i]);
+        const int total = C * ws.slabs;
+        for (int base = 0; base < total; base += 8 * kBlock) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = ldf_or_zero(ws.part_max + base + u * kBlock + tid, base + u * kBlock + tid < total);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) m = fmaxf(m, v[u]);
+        }
         m = wave_max(m);
         if (lane == 0) l_max[wave] = m;
     }
@@ -388,7 +407,16 @@ __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& c
                                             uint32_t* l_cnt) {
     const int tid = threadIdx.x;
     uint32_t cnt = 0;
-    for (int i = tid; i < ws.cgroups; i += kBlock) cnt += ws.part_cnt[(int64_t)c * ws.cgroups + i];
+    static_assert(kCountGrid <= 4 * kBlock, "a thread sums at most four count partials");
+    {
+        uint32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = tid + u * kBlock;
+            v[u] = __float_as_uint(ldf_or_zero(reinterpret_cast<const float*>(ws.part_cnt + (int64_t)c * ws.cgroups + i), i < ws.cgroups));
+        }
+        cnt = v[0] + v[1] + v[2] + v[3];
+    }
     cnt = wave_sum_u32(cnt);
     if (tid % kWave == 0) l_cnt[tid / kWave] = cnt;
     __syncthreads();
@@ -805,18 +833,18 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     QuantWs ws = carve_quant_ws(workspace, C, N, HW);
 
     // S1: statistics partials, at most 16 per channel
+    const FastDiv div_hw = make_fastdiv((uint32_t)HW);
     const bool vec4 = (HW % 4 == 0) && (((uintptr_t)dY & 15u) == 0);
     const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.slabs);
     if (vec4)
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
     else
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
 
     // S2 (+ the NHWC global copy); folds the statistics itself
     const int CB = (int)ceil_div(C, 64);
     const dim3 cgrid((unsigned)(CB * ws.cgroups));
     const float* no_scale = nullptr;
-    const FastDiv div_hw = make_fastdiv((uint32_t)HW);
 #define DAQ_COUNT_LAUNCH(S, Q)                                                                                       \
     DAQ_LAUNCH("count_qg", st,                                                                                       \
                hipLaunchKernelGGL((k_count_qg<S, Q, true>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,                \

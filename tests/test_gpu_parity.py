@@ -174,6 +174,12 @@ CONV_LAYERS = [
     wl.Layer("c3x3_64", 4, 64, 14, 14, 64, 3, 3, 1, 1),
     wl.Layer("c3x3_7x7", 16, 128, 7, 7, 64, 3, 3, 1, 1),
     wl.Layer("c1x1_wide", 8, 256, 7, 7, 128, 1, 1, 1, 0),
+    wl.Layer("c5x5", 2, 20, 12, 12, 24, 5, 5, 1, 2),              # 25 taps: waves split the taps
+    wl.Layer("c3x3_s2_big", 8, 32, 28, 28, 96, 3, 3, 2, 1),       # strided, several tiles, K split across workgroups
+    wl.Layer("stem_big", 4, 3, 64, 64, 64, 7, 7, 2, 3),           # 49 taps on eight waves, K split
+    wl.Layer("c1x1_s2_big", 8, 64, 28, 28, 128, 1, 1, 2, 0),      # strided projection shortcut
+    wl.Layer("c3x3_s2_dil2", 2, 16, 15, 14, 16, 3, 3, 2, 2, 2),   # stride and dilation together
+    wl.Layer("c1x1_pad", 2, 16, 6, 6, 16, 1, 1, 1, 1),            # padded 1x1
 ]
 
 
