@@ -87,7 +87,9 @@ typedef enum { DAQ_OP_QUANTIZE_GRAD = 0, DAQ_OP_CONV_FWD = 1, DAQ_OP_CONV_BWD_DA
  *       c*chan_pitch + ((hh % phases_h)*phases_w + (ww % phases_w)) * plane_pitch + lead
  *         + (n*img_rows + hh / phases_h) * row_pitch + ww / phases_w .
  *   phases_* > 1 only for the saved activation of a strided convolution (one plane per stride
- *   phase, so every filter tap reads one plane at a constant offset).
+ *   phase, so every filter tap reads one plane at a constant offset).  The lead bytes in front of
+ *   the first image of a plane and the bytes behind its last image are zero as well, and cover
+ *   every position a filter tap can reach from a real element in either direction.
  * ------------------------------------------------------------------------------------------- */
 typedef enum { DAQ_LAYOUT_NHWC = 0, DAQ_LAYOUT_CNHW = 1 } daq_layout_kind;
 

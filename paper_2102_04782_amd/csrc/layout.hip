@@ -37,7 +37,9 @@ static bool sizes_ok(const daq_conv_desc& d) {
 // filter tap is a constant byte offset between the two flattened (n, row, col) axes.
 struct Slot {
     int img_rows, row_pitch, phases_h, phases_w, org_h, org_w;
-    int64_t lead, klen;  // klen: bytes of the flattened axis, padded to kKAlign
+    int64_t lead;   // distance from a gradient position to the activation position of tap (0, 0)
+    int64_t halo;   // zero bytes in front of and behind the images of every plane, gradient and activation alike
+    int64_t klen;   // bytes of a gradient plane: halo + images + halo, padded to kKAlign
 };
 
 static Slot slot_of(const daq_conv_desc& d) {
@@ -62,7 +64,10 @@ static Slot slot_of(const daq_conv_desc& d) {
         s.row_pitch = cp > Wo ? cp : Wo;
         s.lead = 0;
     }
-    s.klen = round_up((int64_t)d.N * s.img_rows * s.row_pitch, kKAlign);
+    // Every neighbour a filter tap can reach from a real element, in either direction, is an addressable zero:
+    // kernels that walk a plane with shifted reads (filter gradient, depthwise data gradient) need no bounds tests.
+    s.halo = round_up((int64_t)((d.kH - 1) * d.dilH + 1) * s.row_pitch + (int64_t)(d.kW - 1) * d.dilW + 16, 64);
+    s.klen = round_up(2 * s.halo + (int64_t)d.N * s.img_rows * s.row_pitch, kKAlign);
     return s;
 }
 
@@ -76,7 +81,7 @@ static void fill_cnhw(daq_layout* L, const Slot& s, int C, int N, int H, int W, 
     if (activation) {
         L->phases_h = s.phases_h; L->phases_w = s.phases_w;
         L->org_h = s.org_h; L->org_w = s.org_w;
-        L->lead = s.lead;
+        L->lead = s.halo + s.lead;
         // a tap reads up to (kH-1)*dilH rows and (kW-1)*dilW columns past the gradient's position
         const int64_t reach = (int64_t)((d.kH - 1) * d.dilH / d.strideH + 1) * s.row_pitch +
                               (int64_t)(d.kW - 1) * d.dilW / d.strideW + 64;
@@ -85,7 +90,7 @@ static void fill_cnhw(daq_layout* L, const Slot& s, int C, int N, int H, int W, 
     } else {
         L->phases_h = L->phases_w = 1;
         L->org_h = L->org_w = 0;
-        L->lead = 0;
+        L->lead = s.halo;
         L->plane_pitch = s.klen;
         L->chan_pitch = s.klen;
     }

@@ -447,6 +447,7 @@ __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& c
 struct PackArgs {
     FastDiv div_slot, div_pitch;
     int per_chan;          // workgroups per (channel, phase) plane
+    int lead_imgs;         // whole images that cover the leading zeros
     int per_channel_scale; // scale[c] instead of scale[0] (ignored with CLIP)
     uint32_t tensor;       // random stream id
     uint64_t seed;
@@ -483,14 +484,14 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int d = jb * 1024 + tid + 256 * u;   // dword inside the plane
-        // first byte of the dword as (image, row, column); shifted by one image so that the bytes in
-        // front of the first image (the leading padding) decompose to image -1
-        const uint32_t o = (uint32_t)(4 * d - (int)L.lead) + slot;
+        // first byte of the dword as (image, row, column); shifted by whole images so that the bytes in
+        // front of the first image (the leading zeros) decompose to negative image numbers
+        const uint32_t o = (uint32_t)(4 * d - (int)L.lead) + (uint32_t)pa.lead_imgs * slot;
         const uint32_t nq = fdiv(o, pa.div_slot);
         const uint32_t rem = o - __umul24(nq, slot);
         const uint32_t r = fdiv(rem, pa.div_pitch);
         const int col = (int)(rem - __umul24(r, (uint32_t)L.row_pitch));
-        const int n = (int)nq - 1;
+        const int n = (int)nq - pa.lead_imgs;
         int h = (int)__umul24(r, (uint32_t)L.phases_h) + h_first;
         // n and h may be negative here (leading padding): signed multiplies keep the offset linear modulo 2^32,
         // so the row steps below land on the right value once the walk reaches a real row
@@ -683,6 +684,7 @@ PackArgs pack_args(const daq_layout& L, int per_channel_scale, uint32_t tensor, 
     pa.div_slot = make_fastdiv((uint32_t)(L.img_rows * L.row_pitch));
     pa.div_pitch = make_fastdiv((uint32_t)L.row_pitch);
     pa.per_chan = pack_per_chan(L);
+    pa.lead_imgs = (int)ceil_div(L.lead, (int64_t)L.img_rows * L.row_pitch);
     pa.per_channel_scale = per_channel_scale;
     pa.tensor = tensor;
     pa.seed = seed;
@@ -691,8 +693,9 @@ PackArgs pack_args(const daq_layout& L, int per_channel_scale, uint32_t tensor, 
 // The packing kernel indexes a plane with 32-bit integers.
 bool pack_supported(const daq_layout& L) {
     const int64_t lim24 = (int64_t)1 << 24;
-    return L.plane_pitch + (int64_t)L.img_rows * L.row_pitch < ((int64_t)1 << 31) && (L.plane_pitch & 3) == 0 &&
-           (int64_t)L.img_rows * L.row_pitch < lim24 && (int64_t)(L.N + 1) * L.C < lim24 / 2 && (int64_t)L.H * L.W < lim24 / 2 &&
+    return L.plane_pitch + L.lead + (int64_t)L.img_rows * L.row_pitch < ((int64_t)1 << 31) && (L.plane_pitch & 3) == 0 &&
+           (int64_t)L.img_rows * L.row_pitch < lim24 &&
+           (int64_t)(L.N + 1 + ceil_div(L.lead, (int64_t)L.img_rows * L.row_pitch)) * L.C < lim24 / 2 && (int64_t)L.H * L.W < lim24 / 2 &&
            (int64_t)L.img_rows * L.phases_h < lim24 && (int64_t)L.row_pitch * L.phases_w < lim24;
 }
 // The quantization kernels read an fp32 tensor through a buffer descriptor with 32-bit offsets.

@@ -51,7 +51,12 @@ def test_layouts_are_injective_in_bounds_and_tap_shifts_are_constant(kw):
     # the property the filter-gradient kernel relies on: for a fixed tap, the activation element that
     # multiplies gradient element f sits at f + const in the activation's plane, or is zero padding
     Lg, Lx = daq.layout_vq(d), daq.layout_qx_cnhw(d)
-    assert (Lg.img_rows, Lg.row_pitch) == (Lx.img_rows, Lx.row_pitch) and Lg.lead == 0
+    assert (Lg.img_rows, Lg.row_pitch) == (Lx.img_rows, Lx.row_pitch)
+    # zero halo: whatever a tap can reach from a real gradient element, before the first image or behind the
+    # last one, is inside the plane (and zero, which the GPU tests check on real buffers)
+    reach = ((d.kH - 1) * d.dilH + 1) * Lg.row_pitch + (d.kW - 1) * d.dilW
+    assert Lg.lead >= reach and Lg.plane_pitch - (Lg.lead + d.N * Lg.img_rows * Lg.row_pitch) >= reach
+    assert Lx.lead >= Lg.lead
     rng = np.random.default_rng(1)
     X = rng.integers(1, 128, (d.N, d.Cin, d.Hin, d.Win)).astype(np.int8)  # strictly positive: zero means padding
     buf = Lx.pack(X)
@@ -59,7 +64,7 @@ def test_layouts_are_injective_in_bounds_and_tap_shifts_are_constant(kw):
         for kw_ in range(d.kW):
             hh, ww = kh * d.dilH, kw_ * d.dilW
             if d.strideH == 1 and d.strideW == 1:
-                plane, delta = 0, Lx.lead - Lx.lead + hh * Lx.row_pitch + ww  # lead already holds the padding shift
+                plane, delta = 0, hh * Lx.row_pitch + ww  # the activation's lead already holds the padding shift
                 base = 0
             else:
                 plane = (hh % d.strideH) * d.strideW + (ww % d.strideW)
@@ -68,7 +73,7 @@ def test_layouts_are_injective_in_bounds_and_tap_shifts_are_constant(kw):
             for n in range(d.N):
                 for ho in range(Ho):
                     for wo in range(Wo):
-                        f = (n * Lg.img_rows + ho) * Lg.row_pitch + wo
+                        f = Lg.lead + (n * Lg.img_rows + ho) * Lg.row_pitch + wo
                         h = ho * d.strideH + hh - d.padH
                         w = wo * d.strideW + ww - d.padW
                         inside = 0 <= h < d.Hin and 0 <= w < d.Win
