@@ -33,6 +33,7 @@ extern "C" daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const in
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     if (bwd_data_mfma_supported(*desc)) return conv_bwd_data_mfma(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
+    if (depthwise_dx_supported(*desc)) return conv_bwd_data_depthwise(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
     return conv_bwd_data_generic(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
 }
 
@@ -46,5 +47,7 @@ extern "C" daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const 
     hipStream_t st = (hipStream_t)stream;
     if (bwd_filter_mfma_supported(*desc))
         return conv_bwd_filter_mfma(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
+    if (depthwise_dw_supported(*desc))
+        return conv_bwd_filter_depthwise(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
     return conv_bwd_filter_generic(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, st);
 }

@@ -1,0 +1,296 @@
+// Depthwise (groups = channels) backward convolutions on channel-major int8 planes.
+//
+// With one input and one output channel per group there is no contraction over channels, so the
+// matrix cores have nothing to do: both products are bandwidth bound (data gradient: 1 byte read and
+// 4 written per element; filter gradient: 2 bytes read per element) and run on v_dot4_i32_i8.
+//
+// Both kernels lean on the plane layout: images sit in pitched slots whose spare rows / columns are
+// zero and every plane starts and ends with a zero halo, so a neighbour a filter tap reaches outside
+// the image is an addressable zero and no bounds test is needed anywhere.
+#include <algorithm>
+
+#include "daq_internal.h"
+
+namespace daq {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kMaxK = 7;            // largest filter extent of the general data-gradient kernel
+constexpr int kDwSlabBytes = 4096;  // bytes of the flat axis one filter-gradient workgroup covers per iteration
+
+typedef int v2i_a1 __attribute__((ext_vector_type(2), aligned(1)));
+typedef int v4i_a1 __attribute__((ext_vector_type(4), aligned(1)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ int dot4(int a, int b, int c) { return __builtin_amdgcn_sdot4(a, b, c, false); }
+
+struct DxArgs {
+    const int8_t* qg;      // planar gradient, [C][chan_pitch]
+    const int8_t* qw;      // plain filter copy, [C][kH*kW]
+    int64_t chan_pitch;
+    int lead, img_rows, row_pitch;
+    int N, C, Hin, Win;
+    int kH, kW, pH, pW, dH, dW;
+    int s_log2;            // log2 of the (square, power-of-two) stride
+    FastDiv div_wq, div_h, div_c;
+    int wq;                // quads of output columns per row
+    const float* s_g;
+    const float* s_w;
+    float* dX;
+    int32_t* acc_out;
+};
+
+// Data gradient, unit stride and dilation, kW <= 4: a thread produces four adjacent outputs of one row.
+// For filter row kh it reads the 8 gradient bytes that cover the windows of all four outputs with one
+// (byte-aligned) load, and each output is one dot4 of its 4-byte window with the reversed filter row.
+__global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t rows = (uint32_t)p.N * p.C * p.Hin;
+    const uint32_t row = fdiv(i, p.div_wq);
+    if (row >= rows) return;
+    const int w0 = 4 * (int)(i - row * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(row, p.div_h);
+    const int h = (int)(row - nc * (uint32_t)p.Hin);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+
+    const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
+    const int8_t* wrow = p.qw + c * (p.kH * p.kW);
+    const int T = p.kH * p.kW;
+    int acc[4] = {0, 0, 0, 0};
+    for (int kh = 0; kh < p.kH; ++kh) {
+        // reversed filter row in one dword: byte m = W[kh][kW-1-m], zero beyond kW
+        int wr = 0;
+        for (int m = 0; m < p.kW; ++m) wr |= ((int)(uint8_t)wrow[kh * p.kW + (p.kW - 1 - m)]) << (8 * m);
+        const int ho = h + p.pH - kh;
+        const int col0 = w0 + p.pW - (p.kW - 1);
+        const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(g + ((int64_t)((int)n * p.img_rows + ho) * p.row_pitch + col0));
+        const unsigned lo = (unsigned)v[0], hi = (unsigned)v[1];
+        acc[0] = dot4((int)lo, wr, acc[0]);
+        acc[1] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 1), wr, acc[1]);
+        acc[2] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 2), wr, acc[2]);
+        acc[3] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 3), wr, acc[3]);
+    }
+    (void)T;
+    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const int64_t o = (int64_t)row * p.Win + w0;
+    if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
+        *reinterpret_cast<float4*>(p.dX + o) =
+            make_float4((float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale);
+        if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (w0 + j < p.Win) {
+                p.dX[o + j] = (float)acc[j] * scale;
+                if (p.acc_out) p.acc_out[o + j] = acc[j];
+            }
+    }
+}
+
+// Data gradient, power-of-two stride, any dilation, extents up to 7: a thread produces four adjacent
+// outputs; a tap contributes where (h + pad - kh*dil) and (w + pad - kw*dil) are multiples of the stride.
+__global__ __launch_bounds__(kBlock) void k_dwise_dx_any(DxArgs p) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t rows = (uint32_t)p.N * p.C * p.Hin;
+    const uint32_t row = fdiv(i, p.div_wq);
+    if (row >= rows) return;
+    const int w0 = 4 * (int)(i - row * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(row, p.div_h);
+    const int h = (int)(row - nc * (uint32_t)p.Hin);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+
+    const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
+    const int8_t* wf = p.qw + c * (p.kH * p.kW);
+    const int smask = (1 << p.s_log2) - 1;
+    int acc[4] = {0, 0, 0, 0};
+    for (int kh = 0; kh < p.kH; ++kh) {
+        const int th = h + p.pH - kh * p.dH;
+        if (th & smask) continue;
+        const int64_t rbase = (int64_t)((int)n * p.img_rows + (th >> p.s_log2)) * p.row_pitch;
+        for (int kw = 0; kw < p.kW; ++kw) {
+            const int wv = wf[kh * p.kW + kw];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int tw = w0 + j + p.pW - kw * p.dW;
+                const bool ok = (tw & smask) == 0;
+                const int8_t* src = ok ? g + (rbase + (tw >> p.s_log2)) : reinterpret_cast<const int8_t*>(g_zero64);
+                acc[j] += (int)*src * wv;
+            }
+        }
+    }
+    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const int64_t o = (int64_t)row * p.Win + w0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (w0 + j < p.Win) {
+            p.dX[o + j] = (float)acc[j] * scale;
+            if (p.acc_out) p.acc_out[o + j] = acc[j];
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Filter gradient:  acc[c][t] = sum_f G[c][f] * X[c][tap_off[t] + f]  - per channel, T dot products
+// over the flat axis (the same shifted correlation the dense kernel computes, with M = N = 1).
+// Workgroup (c, slab) sweeps its part of the axis 4096 bytes at a time: a thread takes 16 aligned
+// bytes of G and, for every tap, the 16 activation bytes at the tap's offset (byte aligned; the nine
+// windows of a 3 x 3 filter overlap almost entirely, so they come from the same cache lines).
+// Partial sums go to [c][slab][t]; k_dwise_dw_reduce adds the slabs and de-quantizes.
+// ---------------------------------------------------------------------------------------------
+constexpr int kDwTaps = 9;
+struct DwiseDwArgs {
+    const int8_t* g;
+    const int8_t* x;
+    int64_t g_chan_pitch, x_chan_pitch;
+    int64_t klen;          // bytes of a gradient plane (multiple of 256)
+    int64_t off[kDwTaps];  // unused slots repeat slot 0 (computed, never stored)
+    int T, C, slabs;
+    int32_t* part;         // [C][slabs][kDwTaps]
+};
+
+__global__ __launch_bounds__(kBlock) void k_dwise_dw(DwiseDwArgs p) {
+    __shared__ int l_red[kBlock / kWave][kDwTaps];
+    const int c = blockIdx.x / p.slabs, slab = blockIdx.x % p.slabs;
+    const int tid = threadIdx.x;
+    const int64_t iters_total = p.klen / kDwSlabBytes + ((p.klen % kDwSlabBytes) ? 1 : 0);
+    const int64_t per = iters_total / p.slabs, rem = iters_total % p.slabs;
+    const int64_t it0 = slab * per + std::min<int64_t>(slab, rem);
+    const int64_t it1 = it0 + per + (slab < rem ? 1 : 0);
+    const int8_t* g = p.g + (int64_t)c * p.g_chan_pitch;
+    const int8_t* x = p.x + (int64_t)c * p.x_chan_pitch;
+
+    int acc[kDwTaps];
+#pragma unroll
+    for (int t = 0; t < kDwTaps; ++t) acc[t] = 0;
+    for (int64_t it = it0; it < it1; ++it) {
+        const int64_t f = it * kDwSlabBytes + 16 * tid;
+        const bool live = f < p.klen;   // klen is a multiple of 256, so a live thread has all 16 bytes
+        const int64_t fc = live ? f : 0;
+        v4i gv = *reinterpret_cast<const v4i*>(g + fc);
+        if (!live) gv = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < kDwTaps; ++t) {
+            const v4i_a1 xv = *reinterpret_cast<const v4i_a1*>(x + (p.off[t] + fc));
+            acc[t] = dot4(gv[0], xv[0], acc[t]);
+            acc[t] = dot4(gv[1], xv[1], acc[t]);
+            acc[t] = dot4(gv[2], xv[2], acc[t]);
+            acc[t] = dot4(gv[3], xv[3], acc[t]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kDwTaps; ++t) {
+        int v = acc[t];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+        if (tid % kWave == 0) l_red[tid / kWave][t] = v;
+    }
+    __syncthreads();
+    if (tid < kDwTaps)
+        p.part[((int64_t)c * p.slabs + slab) * kDwTaps + tid] = l_red[0][tid] + l_red[1][tid] + l_red[2][tid] + l_red[3][tid];
+}
+
+__global__ __launch_bounds__(kBlock) void k_dwise_dw_reduce(const int32_t* __restrict__ part, int C, int slabs, int T,
+                                                            const float* s_x, const float* __restrict__ s_chan,
+                                                            float* __restrict__ dW, int32_t* __restrict__ acc_out) {
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= C * T) return;
+    const int c = i / T, t = i % T;
+    int a = 0;
+    for (int s = 0; s < slabs; ++s) a += part[((int64_t)c * slabs + s) * kDwTaps + t];
+    dW[i] = (float)a * ((*s_x / 127.0f) * (s_chan[c] / 127.0f));
+    if (acc_out) acc_out[i] = a;
+}
+
+int log2_exact(int v) {
+    int l = 0;
+    while ((1 << l) < v) ++l;
+    return (1 << l) == v ? l : -1;
+}
+
+int dw_slabs(const daq_conv_desc& d, int64_t klen) {
+    const int64_t iters = ceil_div(klen, kDwSlabBytes);
+    int64_t s = ceil_div(2048, d.Cout);
+    if (s > iters) s = iters;
+    if (s > 256) s = 256;
+    return (int)std::max<int64_t>(1, s);
+}
+
+}  // namespace
+
+bool depthwise_dx_supported(const daq_conv_desc& d) {
+    if (!is_depthwise(d) || d.strideH != d.strideW || log2_exact(d.strideH) < 0) return false;
+    if (d.kH > kMaxK || d.kW > kMaxK) return false;
+    return (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
+}
+
+daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
+                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+    daq_layout Lg;
+    daq_wpack_layout Lw;
+    if (daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK || Lg.kind != DAQ_LAYOUT_CNHW)
+        return DAQ_ERR_INVALID_ARG;
+    DxArgs a{};
+    a.qg = qg;
+    a.qw = qw + Lw.off_plain;
+    a.chan_pitch = Lg.chan_pitch;
+    a.lead = (int)Lg.lead; a.img_rows = Lg.img_rows; a.row_pitch = Lg.row_pitch;
+    a.N = d.N; a.C = d.Cin; a.Hin = d.Hin; a.Win = d.Win;
+    a.kH = d.kH; a.kW = d.kW; a.pH = d.padH; a.pW = d.padW; a.dH = d.dilH; a.dW = d.dilW;
+    a.s_log2 = log2_exact(d.strideH);
+    a.wq = (int)ceil_div(d.Win, 4);
+    a.div_wq = make_fastdiv((uint32_t)a.wq);
+    a.div_h = make_fastdiv((uint32_t)d.Hin);
+    a.div_c = make_fastdiv((uint32_t)d.Cin);
+    a.s_g = s_g; a.s_w = s_w; a.dX = dX; a.acc_out = acc;
+    const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
+    const dim3 grid((unsigned)ceil_div(threads, kBlock));
+    const bool unit = d.strideH == 1 && d.dilH == 1 && d.dilW == 1 && d.kW <= 4;
+    if (unit)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_unit, grid, dim3(kBlock), 0, st, a));
+    else
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_any, grid, dim3(kBlock), 0, st, a));
+    return DAQ_OK;
+}
+
+bool depthwise_dw_supported(const daq_conv_desc& d) { return is_depthwise(d) && d.kH * d.kW <= kDwTaps; }
+
+size_t depthwise_dw_ws_bytes(const daq_conv_desc& d) {
+    daq_layout Lg;
+    if (!depthwise_dw_supported(d) || daq_layout_vq(&d, &Lg) != DAQ_OK) return 0;
+    return (size_t)round_up((int64_t)d.Cout * dw_slabs(d, Lg.plane_pitch) * kDwTaps * 4, 256);
+}
+
+daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
+                                     const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st) {
+    daq_layout Lx, Lg;
+    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
+    DwiseDwArgs a{};
+    a.g = vq;
+    a.x = qx;
+    a.g_chan_pitch = Lg.chan_pitch;
+    a.x_chan_pitch = Lx.chan_pitch;
+    a.klen = Lg.plane_pitch;
+    a.T = d.kH * d.kW;
+    a.C = d.Cout;
+    a.slabs = dw_slabs(d, Lg.plane_pitch);
+    a.part = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
+    // window start of every tap inside an activation channel (stride-phase plane + shift), as in the dense kernel
+    for (int t = 0; t < kDwTaps; ++t) a.off[t] = 0;
+    for (int kh = 0; kh < d.kH; ++kh)
+        for (int kw = 0; kw < d.kW; ++kw) {
+            const int ph = (kh * d.dilH) % Lx.phases_h, pw = (kw * d.dilW) % Lx.phases_w;
+            a.off[kh * d.kW + kw] = (int64_t)(ph * Lx.phases_w + pw) * Lx.plane_pitch +
+                                    (int64_t)(kh * d.dilH / Lx.phases_h) * Lx.row_pitch + (kw * d.dilW / Lx.phases_w);
+        }
+    for (int t = a.T; t < kDwTaps; ++t) a.off[t] = a.off[0];
+    DAQ_LAUNCH("conv_bwd_filter_depthwise", st,
+               hipLaunchKernelGGL(k_dwise_dw, dim3((unsigned)(d.Cout * a.slabs)), dim3(kBlock), 0, st, a));
+    DAQ_LAUNCH("dw_reduce", st,
+               hipLaunchKernelGGL(k_dwise_dw_reduce, dim3((unsigned)ceil_div(d.Cout * a.T, kBlock)), dim3(kBlock), 0, st,
+                                  a.part, d.Cout, a.slabs, a.T, s_x, s_chan, dW, acc));
+    return DAQ_OK;
+}
+
+}  // namespace daq

@@ -180,6 +180,11 @@ CONV_LAYERS = [
     wl.Layer("c1x1_s2_big", 8, 64, 28, 28, 128, 1, 1, 2, 0),      # strided projection shortcut
     wl.Layer("c3x3_s2_dil2", 2, 16, 15, 14, 16, 3, 3, 2, 2, 2),   # stride and dilation together
     wl.Layer("c1x1_pad", 2, 16, 6, 6, 16, 1, 1, 1, 1),            # padded 1x1
+    wl.Layer("dw_big", 6, 40, 28, 28, 40, 3, 3, 1, 1, 1, 40),     # depthwise, several slabs per channel
+    wl.Layer("dw_s2_big", 4, 24, 30, 30, 24, 3, 3, 2, 1, 1, 24),
+    wl.Layer("dw_5x5", 2, 8, 14, 14, 8, 5, 5, 1, 2, 1, 8),
+    wl.Layer("dw_w7", 3, 16, 7, 7, 16, 3, 3, 1, 1, 1, 16),        # rows that are not a multiple of four outputs
+    wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
 ]
 
 

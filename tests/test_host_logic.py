@@ -84,6 +84,43 @@ def test_layouts_are_injective_in_bounds_and_tap_shifts_are_constant(kw):
     assert Lg.plane_pitch % 256 == 0 and Lg.plane_pitch + max_delta + 16 <= Lx.plane_pitch
 
 
+@pytest.mark.parametrize("kw", [
+    dict(N=2, Cin=3, Hin=9, Win=7, Cout=3, kH=3, kW=3, padH=1, padW=1, groups=3),
+    dict(N=2, Cin=2, Hin=12, Win=11, Cout=2, kH=3, kW=3, strideH=2, strideW=2, padH=1, padW=1, groups=2),
+    dict(N=2, Cin=2, Hin=11, Win=12, Cout=2, kH=3, kW=3, strideH=2, strideW=2, padH=0, padW=0, groups=2),
+    dict(N=3, Cin=2, Hin=13, Win=13, Cout=2, kH=5, kW=5, strideH=2, strideW=2, padH=2, padW=2, groups=2),
+    dict(N=2, Cin=2, Hin=10, Win=10, Cout=2, kH=3, kW=3, padH=2, padW=2, dilH=2, dilW=2, groups=2),
+    dict(N=2, Cin=2, Hin=9, Win=9, Cout=2, kH=3, kW=3, padH=0, padW=0, groups=2),
+    dict(N=2, Cin=2, Hin=16, Win=16, Cout=2, kH=7, kW=7, strideH=4, strideW=4, padH=3, padW=3, groups=2),
+])
+def test_planar_gradient_neighbours_are_the_element_or_zero(kw):
+    """The depthwise data-gradient kernels read G'[c] at lead + (n*img_rows + ho)*row_pitch + wo for every
+    (ho, wo) a tap asks for, in range or not, without a bounds test."""
+    d = daq.ConvDesc.make(**kw)
+    L = daq.layout_qg(d)
+    assert L.kind == daq.LAYOUT_CNHW
+    rng = np.random.default_rng(5)
+    G = rng.integers(1, 128, (d.N, d.Cout, d.Ho, d.Wo)).astype(np.int8)   # strictly positive: zero means padding
+    buf = L.pack(G)
+    for c in range(d.Cout):
+        for n in range(d.N):
+            for h in range(d.Hin):
+                for w in range(d.Win):
+                    for kh in range(d.kH):
+                        th = h + d.padH - kh * d.dilH
+                        if th % d.strideH:
+                            continue
+                        for kw_ in range(d.kW):
+                            tw = w + d.padW - kw_ * d.dilW
+                            if tw % d.strideW:
+                                continue
+                            ho, wo = th // d.strideH, tw // d.strideW
+                            pos = c * L.chan_pitch + L.lead + (n * L.img_rows + ho) * L.row_pitch + wo
+                            assert 0 <= pos < L.bytes
+                            inside = 0 <= ho < d.Ho and 0 <= wo < d.Wo
+                            assert buf[pos] == (G[n, c, ho, wo] if inside else 0), (n, h, w, kh, kw_)
+
+
 def test_weight_packing_roundtrip():
     for kw in CASES:
         d = daq.ConvDesc.make(**kw)
