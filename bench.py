@@ -7,6 +7,7 @@ Inputs (fp32 dY, the saved int8 activation/filter of the forward pass, the clip 
 in HBM before the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--layer 0] [--rotate R]
+    python bench.py --sweep --config 4     # every layer of a network, one line with per-layer times
 """
 from __future__ import annotations
 
@@ -26,11 +27,90 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
 # kernel of known size; keyed by (workload, kernel).  See profiles/ for the runs these come from.
 MEASURED_TRAFFIC = {
     ("config2", "conv_bwd_data_mfma"): 35.53e6,
-    ("config2", "conv_bwd_filter_mfma"): 23.65e6,
-    ("config2", "stats"): 25.79e6,
-    ("config2", "count_qg"): 35.38e6,
-    ("config2", "pack_vq"): 32.66e6,
+    ("config2", "conv_bwd_filter_mfma"): 23.70e6,
+    ("config2", "stats"): 25.77e6,
+    ("config2", "count_qg"): 33.99e6,
+    ("config2", "pack_vq"): 32.78e6,
 }
+
+
+def sweep(args, dev) -> int:
+    """Whole-network pass: the backward step of every conv layer of a config, back to back per shape.
+
+    Inputs are generated on the GPU (random codes for the saved int8 tensors, Gaussian dY); parity of
+    these shapes is the business of the tests, this only measures."""
+    import torch
+
+    from paper_2102_04782_amd import binding as daq
+    from paper_2102_04782_amd import workloads as wl
+
+    layers = wl.config_layers(args.config)
+    steps = max(3, min(args.steps, 20))
+    seen, out_layers = {}, []
+    tot_wall = tot_ops = 0.0
+    tot = {"quantize": 0.0, "dW": 0.0, "dX": 0.0}
+    for li, L in enumerate(layers):
+        key = L.desc_fields()
+        if key not in seen:
+            d = daq.ConvDesc.make(*key)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(wl.seed_for(args.config, li))
+            dY = torch.randn(d.y_shape, device=dev, generator=gen) * 1e-2
+            st = torch.zeros(d.Cout, device=dev)
+            qx = torch.randint(-127, 128, (daq.layout_qx_cnhw(d).bytes,), dtype=torch.int8, device=dev, generator=gen)
+            qw = torch.randint(-127, 128, (daq.layout_qw(d).bytes,), dtype=torch.int8, device=dev, generator=gen)
+            one = torch.ones(1, device=dev)
+            out = daq.alloc_quantize_grad(d, dev, want_stats=False)
+            dW = torch.empty(d.w_shape, device=dev)
+            dX = torch.empty(d.x_shape, device=dev)
+            ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
+            ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
+
+            def step():
+                q = daq.quantize_grad(d, dY, st, out=out)
+                daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
+                daq.conv_bwd_data_int8(d, q.qg, q.s_global, qw, one, dX=dX, workspace=ws_d)
+
+            for _ in range(3):
+                step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            wall_us = 1e6 * (time.perf_counter() - t0) / steps
+            daq.prof_begin()
+            for _ in range(steps):
+                step()
+            rows = daq.prof_end()
+            ev = rows.pop("(empty event pair)", (0.0, 1))
+            ev_us = 1e3 * ev[0] / ev[1]
+            t = {k: 1e3 * v[0] / v[1] - ev_us for k, v in rows.items()}
+            seen[key] = (wall_us,
+                         sum(v for k, v in t.items() if k in ("stats", "count_qg", "pack_vq", "pack_qg")),
+                         sum(v for k, v in t.items() if k.startswith("conv_bwd_filter") or k == "dw_reduce"),
+                         sum(v for k, v in t.items() if k.startswith("conv_bwd_data")))
+            del dY, qx, qw, out, dW, dX, ws_f, ws_d
+        wall_us, q_us, dw_us, dx_us = seen[key]
+        tot_wall += wall_us
+        tot_ops += 4.0 * L.macs
+        tot["quantize"] += q_us
+        tot["dW"] += dw_us
+        tot["dX"] += dx_us
+        out_layers.append({"layer": L.name, "shape": f"N{L.N} {L.Cin}->{L.Cout} {L.Hin}x{L.Win} k{L.kH} s{L.stride} g{L.groups}",
+                           "step_us": round(wall_us, 1), "quantize_us": round(q_us, 1), "dW_us": round(dw_us, 1),
+                           "dX_us": round(dx_us, 1), "GOP": round(4e-9 * L.macs, 2)})
+    value = tot_ops / (tot_wall * 1e-6) / 1e12
+    print(json.dumps({
+        "metric": "INT8 conv-backward TOPS incl. grad quantization", "value": round(value, 3), "unit": "TOP/s",
+        "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": round(1e-3 * tot_wall, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": f"config{args.config}: all {len(layers)} conv layers, {len(seen)} distinct shapes, "
+                               f"N={layers[0].N}, one backward step each"},
+        "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
+        "kernel_us_total": {k: round(v, 1) for k, v in tot.items()},
+        "layers": out_layers}))
+    return 0
 
 
 def main() -> int:
@@ -42,10 +122,13 @@ def main() -> int:
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--rotate", type=int, default=1, help="number of dY buffer sets cycled through (cold-cache runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2: the two convolutions, which are independent once dY is quantized, run on two streams")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="2: the two convolutions, which are independent once dY is quantized, run on two streams "
+                         "(measured slower than one stream on this workload: the event waits cost more than the overlap gains)")
     ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
                     help="1: capture one step into a HIP graph and time replays of it")
+    ap.add_argument("--sweep", action="store_true",
+                    help="time the step of every layer of --config (distinct shapes once) and report the network total")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="after the timed region, run 5 device-to-device copies of this many MiB: the plain copy "
                          "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -67,6 +150,8 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     daq.lib()  # fail loudly if the HIP library is missing
+    if args.sweep:
+        return sweep(args, dev)
 
     layer, X, W, dY, st = wl.make_inputs(args.config, args.layer)
     d = daq.ConvDesc.make(*layer.desc_fields())
