@@ -117,11 +117,19 @@ daq_status daq_layout_qx_cnhw(const daq_conv_desc* desc, daq_layout* out);
  *   plain  at off_plain: [Cout][Cin/groups][kH][kW]
  *   fwd    at off_fwd  : [kH*kW][Cout][cig_pitch]   (input channel of the group innermost)
  *   bwd    at off_bwd  : [kH*kW][Cin][cog_pitch]    (output channel of the group innermost)
- * cig_pitch / cog_pitch = Cin/groups, Cout/groups rounded up to 16; padding bytes are zero. */
+ * cig_pitch / cog_pitch = Cin/groups, Cout/groups rounded up to 16; padding bytes are zero.
+ * For groups == 1 two more copies hold the filter in the register order of the matrix-core kernels
+ * ("fragment order"), so that a wavefront fetches a 32-row x 32-byte operand tile as one contiguous KiB:
+ *   fwd_frag at off_fwd_frag: rows = output channels, k = input channels
+ *   bwd_frag at off_bwd_frag: rows = input channels,  k = output channels
+ * element (tap, row, k) of a copy with RB = ceil(rows/32) row blocks and T = kH*kW taps is byte
+ *   ((((k/64)*T + tap)*RB + row/32)*2 + (k%64)/32)*1024 + (((k%32)/16)*32 + row%32)*16 + k%16 ;
+ * rows and k are padded with zeros to multiples of 32 and 64.  Both offsets equal `bytes` when groups > 1. */
 typedef struct {
     int64_t bytes;
     int64_t off_plain, off_fwd, off_bwd;
     int32_t cig_pitch, cog_pitch;
+    int64_t off_fwd_frag, off_bwd_frag;
 } daq_wpack_layout;
 daq_status daq_layout_qw(const daq_conv_desc* desc, daq_wpack_layout* out);
 

@@ -105,7 +105,18 @@ class Layout(C.Structure):
 
 class WPackLayout(C.Structure):
     _fields_ = [("bytes", C.c_int64), ("off_plain", C.c_int64), ("off_fwd", C.c_int64), ("off_bwd", C.c_int64),
-                ("cig_pitch", C.c_int32), ("cog_pitch", C.c_int32)]
+                ("cig_pitch", C.c_int32), ("cog_pitch", C.c_int32),
+                ("off_fwd_frag", C.c_int64), ("off_bwd_frag", C.c_int64)]
+
+    @staticmethod
+    def _frag(mat: np.ndarray) -> np.ndarray:
+        """[tap][row][k] -> fragment order (see daq.h): [k/64][tap][row/32][(k%64)/32][(k%32)/16][row%32][k%16]."""
+        taps, rows, K = mat.shape
+        RB, KC = -(-rows // 32), -(-K // 64)
+        pad = np.zeros((taps, RB * 32, KC * 64), np.int8)
+        pad[:, :rows, :K] = mat
+        v = pad.reshape(taps, RB, 32, KC, 2, 2, 16)          # tap, rb, r, kc, sub, kg, b
+        return np.ascontiguousarray(v.transpose(3, 0, 1, 4, 5, 2, 6)).ravel()
 
     def pack(self, d: ConvDesc, qW: np.ndarray) -> np.ndarray:
         qW = np.ascontiguousarray(qW, dtype=np.int8)
@@ -122,6 +133,11 @@ class WPackLayout(C.Structure):
             blk = qW[g * cog:(g + 1) * cog].reshape(cog, cig, taps)      # [col][cl][tap]
             bwd[:, g * cig:(g + 1) * cig, :cog] = blk.transpose(2, 1, 0)  # [tap][cl][col]
         out[self.off_bwd:self.off_bwd + bwd.size] = bwd.ravel()
+        if d.groups == 1:
+            ff = self._frag(fwd[:, :, :cig])
+            out[self.off_fwd_frag:self.off_fwd_frag + ff.size] = ff
+            bf = self._frag(bwd[:, :, :cog])
+            out[self.off_bwd_frag:self.off_bwd_frag + bf.size] = bf
         return out
 
     def unpack_plain(self, d: ConvDesc, buf) -> np.ndarray:

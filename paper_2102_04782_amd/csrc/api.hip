@@ -20,6 +20,7 @@ extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* 
     if (rc != DAQ_OK) return rc;
     rc = quantize_filter(*desc, W, qw_packed, s_w, workspace, st);
     if (rc != DAQ_OK) return rc;
+    if (fwd_halo_supported(*desc)) return conv_fwd_halo(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
     if (fwd_mfma_supported(*desc)) return conv_fwd_mfma(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
     return conv_fwd_generic(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
 }
@@ -32,6 +33,7 @@ extern "C" daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const in
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (bwd_data_halo_supported(*desc)) return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
     if (bwd_data_mfma_supported(*desc)) return conv_bwd_data_mfma(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
     if (depthwise_dx_supported(*desc)) return conv_bwd_data_depthwise(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);
     return conv_bwd_data_generic(*desc, qg, s_global, qw_packed, s_w, dX, acc_out, st);

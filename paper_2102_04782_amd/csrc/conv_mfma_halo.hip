@@ -1,0 +1,456 @@
+// Channel-contracting int8 implicit GEMM, halo-tile form: the data gradient q(G_X) = q(G) (.) q(W)
+// (Eq. "gx") for strides 1 and 2, and the unit-stride forward convolution.
+//
+//     C[row channel][pixel] = sum over (tap, k)  Wp[tap][row][k] * P[src_pixel(pixel, tap)][k]
+//
+// A workgroup owns NI images x (TH x TW) destination pixels (<= 256) and 64 or 128 row channels.
+// Per 64-byte chunk of the contraction axis it stages the SOURCE WINDOW of its tile in LDS once -
+// (TH + reach) x (TW + reach) pixel slots of 64 channel bytes - and every filter tap reads that
+// window at a shifted slot, so no pixel is staged more than once and the loop over the taps has no
+// LDS writes and no barrier.  The filter operand never goes through LDS: it is stored in fragment
+// order (see daq_wpack_layout), so a wave fetches each 32-row x 32-byte tile as one contiguous KiB
+// straight into the registers the MFMA reads, one step ahead.  The window of the next chunk is
+// fetched while the taps of the current one run and is written to the other LDS buffer at the
+// chunk's last tap: one barrier per chunk.
+//
+// Stride 2 (data gradient only): destination pixels are split by parity (h % 2, w % 2).  Pixels of
+// one parity class see the same subset of taps, each at a unit-stride position of the source, so a
+// workgroup handles one class and issues only the taps that are live for it - no multiplies by
+// stride-skipped zeros.
+#include <algorithm>
+
+#include "daq_internal.h"
+
+namespace daq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kPxWg = 256;         // destination pixels per workgroup
+constexpr int kKc = 64;            // contraction bytes per step (two MFMA K-steps of 32)
+constexpr int kPitch = kKc + 16;   // LDS pitch of a window slot: eight consecutive slots cover all banks
+constexpr int kMaxTaps = 49;
+constexpr int kMaxUnits = 8;       // 16-byte units of the window a thread stages: up to 512 slots
+constexpr int kMaxPhases = 4;
+constexpr int kRingA = 4;          // filter tiles are requested kRingA - 1 steps ahead of their use
+constexpr uint32_t kOob = 0x80000000u;  // a buffer offset past every extent: such a load returns zeros
+
+struct HaloArgs {
+    const int8_t* src;    // pixel operand, NHWC [N][Hs][Ws][cp]
+    const int8_t* wfrag;  // filter operand in fragment order
+    uint32_t src_bytes, wfrag_bytes;
+    int N, Hs, Ws, cp;
+    int Hd, Wd;
+    int Crow, RB, T;      // result channels, 32-row blocks of the filter copy, kH*kW
+    int stride;           // 1, or 2 (parity classes)
+    int TH, TW, NI;       // destination tile, in pixels of one parity class
+    int SH, SW;           // source window per image (the largest over the classes)
+    int tiles_h, tiles_w, groups;
+    int units;            // 16-byte window units per thread
+    int double_buffer;    // more than one contraction chunk: two window buffers
+    // per parity class: live taps, window origin relative to the tile's first pixel
+    int ph_taps[kMaxPhases], ph_org_h[kMaxPhases], ph_org_w[kMaxPhases];
+    // 32-bit entries: a uniform index then costs a scalar load, not a vector-memory round trip
+    int tap_slot[kMaxPhases][kMaxTaps];  // slot offset a tap adds inside the window
+    int tap_id[kMaxPhases][kMaxTaps];    // kh*kW + kw of the tap
+    FastDiv div_tw, div_thw, div_sw, div_si, div_tiles_w, div_tiles_hw, div_ptiles;
+    const float* s_a;
+    const float* s_b;
+    float* out;           // fp32 [N][Crow][Hd][Wd]
+    int32_t* acc_out;
+};
+
+__device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
+}
+
+// WR = waves along the row (output channel) axis: 1 -> 64 rows x 256 pixels per workgroup with
+// 64 x 64 wave tiles, 2 -> 128 rows x 256 pixels with 64 x 128 wave tiles.
+// DB = the contraction axis has more than one 64-byte chunk (two window buffers, restaged per chunk).
+template <int WR, bool DB>
+__global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
+    constexpr int ROWS = 64 * WR;
+    constexpr int WPX = 4 / WR;
+    constexpr int PXW = kPxWg / WPX;
+    constexpr int BF = PXW / 32;
+    extern __shared__ __align__(16) int8_t lds[];   // one or two window buffers of S slots
+
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wr = wave % WR, wp = wave / WR;
+    // block -> (row tile, parity class, image group, tile row, tile column)
+    const int per_phase = p.groups * p.tiles_h * p.tiles_w;
+    const int ptiles = per_phase * p.stride * p.stride;
+    const int tr = (int)fdiv(blockIdx.x, p.div_ptiles);
+    int tp = blockIdx.x - tr * ptiles;
+    const int phase = tp / per_phase;   // at most four classes: a plain division is fine here
+    tp -= phase * per_phase;
+    const int pa = phase / p.stride, pb = phase - pa * p.stride;
+    const int grp = (int)fdiv((uint32_t)tp, p.div_tiles_hw);
+    const int trem = tp - grp * p.tiles_h * p.tiles_w;
+    const int tih = (int)fdiv((uint32_t)trem, p.div_tiles_w);
+    const int tiw = trem - tih * p.tiles_w;
+    const int row0 = tr * ROWS;
+    const int n0 = grp * p.NI, h0 = tih * p.TH, w0 = tiw * p.TW;
+    const int SI = p.SH * p.SW, S = p.NI * SI;
+    const int halo_bytes = S * kPitch;
+    const int nkc = (p.cp + kKc - 1) / kKc;
+    const int taps = p.ph_taps[phase];
+    const int NS = nkc * taps;
+    const int org_h = p.ph_org_h[phase], org_w = p.ph_org_w[phase];
+
+    const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
+
+    // ---- window staging: unit tid + 256*i is chunk (tid & 3) of slot (tid >> 2) + 64*i ----
+    const int sc = tid & 3;
+    uint32_t hoff[kMaxUnits];
+#pragma unroll
+    for (int i = 0; i < kMaxUnits; ++i) {
+        hoff[i] = kOob;
+        if (i < p.units) {   // uniform
+            const int slot = (tid >> 2) + 64 * i;
+            const int img = (int)fdiv((uint32_t)slot, p.div_si);
+            const int rem = slot - img * SI;
+            const int r = (int)fdiv((uint32_t)rem, p.div_sw);
+            const int c = rem - r * p.SW;
+            const int n = n0 + img, hs = h0 + org_h + r, ws = w0 + org_w + c;
+            const bool ok = slot < S && n < p.N && (unsigned)hs < (unsigned)p.Hs && (unsigned)ws < (unsigned)p.Ws;
+            if (ok) hoff[i] = (uint32_t)(((n * p.Hs + hs) * p.Ws + ws) * p.cp + 16 * sc);
+        }
+    }
+    v4i rh[kMaxUnits];
+    auto fetch_halo = [&](int kci) {
+        const bool kok = kci < nkc && kci * kKc + 16 * sc < p.cp;
+#pragma unroll
+        for (int i = 0; i < kMaxUnits; ++i)
+            if (i < p.units) rh[i] = buffer_load16(rs_src, kok ? hoff[i] : kOob, (uint32_t)(kci * kKc));
+    };
+    auto stage_halo = [&](int buf) {
+        int8_t* H = lds + buf * halo_bytes;
+#pragma unroll
+        for (int i = 0; i < kMaxUnits; ++i) {
+            const int slot = (tid >> 2) + 64 * i;
+            if (i < p.units && slot < S) *reinterpret_cast<v4i*>(H + slot * kPitch + 16 * sc) = rh[i];
+        }
+    };
+
+    // ---- filter fragments: tile (x, sub) of this wave is 1 KiB at ((row block)*2 + sub)*1024, lane*16 inside ----
+    uint32_t aoff[2][2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int rb = (row0 + wr * 64) / 32 + x;
+            aoff[x][sub] = rb < p.RB ? (uint32_t)((rb * 2 + sub) * 1024 + lane * 16) : kOob;
+        }
+    v4i ra[kRingA][2][2];   // [ring slot][x][sub]
+    int f_j = 0, f_kc = 0, f_s = 0;
+    auto fetch_a = [&](int slot) {
+        const bool live = f_s < NS;
+        const int id = p.tap_id[phase][live ? f_j : 0];
+        const uint32_t base = live ? (uint32_t)(((f_kc * p.T + id) * p.RB) * 2048) : kOob;
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+        ++f_s;
+        if (++f_j == taps) { f_j = 0; ++f_kc; }
+    };
+
+    // ---- pixel fragments: destination pixel q of the tile -> slot of its window origin ----
+    int bslot[BF];
+#pragma unroll
+    for (int y = 0; y < BF; ++y) {
+        const int q = wp * PXW + 32 * y + l32;
+        const int img = (int)fdiv((uint32_t)q, p.div_thw);
+        const int rem = q - img * p.TH * p.TW;
+        const int th = (int)fdiv((uint32_t)rem, p.div_tw);
+        const int tw = rem - th * p.TW;
+        bslot[y] = (img < p.NI) ? img * SI + th * p.SW + tw : 0;
+    }
+
+    v16i acc[2][BF];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < BF; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
+
+    if (NS > 0) {
+        fetch_halo(0);
+#pragma unroll
+        for (int d = 0; d < kRingA - 1; ++d) fetch_a(d);
+        stage_halo(0);
+        __syncthreads();
+    }
+
+    // flat loop over steps (chunk outer, live tap inner), unrolled by the ring depth so that ring slots are constants
+    int j = 0, kci = 0;
+    for (int base = 0; base < NS; base += kRingA) {
+#pragma unroll
+        for (int u = 0; u < kRingA; ++u) {
+            if (base + u < NS) {   // uniform
+                fetch_a((u + kRingA - 1) % kRingA);                          // filter tiles of step s + kRingA - 1
+                if (DB && j == 0 && kci + 1 < nkc) fetch_halo(kci + 1);      // uniform; staged at the chunk's last tap
+                const int8_t* H = lds + (DB ? (kci & 1) * halo_bytes : 0) + 16 * lh;
+                const int ts = p.tap_slot[phase][j];
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    v4i b[BF];
+#pragma unroll
+                    for (int y = 0; y < BF; ++y)
+                        b[y] = *reinterpret_cast<const v4i*>(H + (bslot[y] + ts) * kPitch + 32 * sub);
+#pragma unroll
+                    for (int x = 0; x < 2; ++x)
+#pragma unroll
+                        for (int y = 0; y < BF; ++y)
+                            acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
+                }
+                if (j + 1 == taps) {
+                    if (DB && kci + 1 < nkc) {
+                        stage_halo((kci + 1) & 1);
+                        __syncthreads();
+                    }
+                    j = 0;
+                    ++kci;
+                } else {
+                    ++j;
+                }
+            }
+        }
+    }
+
+    // epilogue: register r of tile (x, y) is row 32x + 8*(r/4) + 4*lh + r%4, destination pixel q = wp*PXW + 32y + l32
+    const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
+    const int rowbase = row0 + wr * 64 + 4 * lh;
+    const int HWd = p.Hd * p.Wd;
+    const bool full_rows = row0 + ROWS <= p.Crow;
+#pragma unroll
+    for (int y = 0; y < BF; ++y) {
+        const int q = wp * PXW + 32 * y + l32;
+        const int img = (int)fdiv((uint32_t)q, p.div_thw);
+        const int rem = q - img * p.TH * p.TW;
+        const int th = (int)fdiv((uint32_t)rem, p.div_tw);
+        const int tw = rem - th * p.TW;
+        const int n = n0 + img, h = (h0 + th) * p.stride + pa, w = (w0 + tw) * p.stride + pb;
+        if (img >= p.NI || n >= p.N || h >= p.Hd || w >= p.Wd) continue;
+        const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w;
+        float* o = p.out + pix;
+        if (full_rows) {
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[(32 * x + 8 * (r >> 2) + (r & 3)) * HWd] = (float)acc[x][y][r] * scale;
+        } else {
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr < p.Crow) o[dr * HWd] = (float)acc[x][y][r] * scale;
+                }
+        }
+        if (p.acc_out) {
+            int32_t* ao = p.acc_out + pix;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr < p.Crow) ao[dr * HWd] = acc[x][y][r];
+                }
+        }
+    }
+}
+
+// floor division for possibly negative numerators
+int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
+
+struct Geometry {
+    bool ok;
+    HaloArgs a;
+    size_t lds_bytes;
+    int rows;
+};
+
+// backward: destination (h, w) of parity class (pa, pb), h = 2*th + pa, reads source row th + (pa + pad - kh*dil)/stride
+// for every kh that makes the quotient exact.  forward (unit stride): source row = h - pad + kh*dil.
+Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int Crow, int kH, int kW, int sH, int sW,
+              int pH, int pW, int dH, int dW) {
+    Geometry g{};
+    HaloArgs& a = g.a;
+    if (sH != sW || (sH != 1 && !(sH == 2 && backward)) || kH * kW > kMaxTaps) return g;
+    if (kH * kW == 1) return g;   // a single tap has no window to share
+    const int s = sH;
+    a.stride = s;
+    a.T = kH * kW;
+    int span_h = 0, span_w = 0;
+    struct Tap { int oh, ow, id; };
+    for (int ph = 0; ph < s * s; ++ph) {
+        const int pa = ph / s, pb = ph % s;
+        Tap taps[kMaxTaps];
+        int nt = 0, mn_h = 1 << 30, mx_h = -(1 << 30), mn_w = 1 << 30, mx_w = -(1 << 30);
+        for (int kh = 0; kh < kH; ++kh)
+            for (int kw = 0; kw < kW; ++kw) {
+                int oh, ow;
+                if (backward) {
+                    const int th = pa + pH - kh * dH, tw = pb + pW - kw * dW;
+                    if (((th % s) + s) % s || ((tw % s) + s) % s) continue;
+                    oh = floor_div(th, s);
+                    ow = floor_div(tw, s);
+                } else {
+                    oh = kh * dH - pH;
+                    ow = kw * dW - pW;
+                }
+                taps[nt++] = Tap{oh, ow, kh * kW + kw};
+                mn_h = std::min(mn_h, oh); mx_h = std::max(mx_h, oh);
+                mn_w = std::min(mn_w, ow); mx_w = std::max(mx_w, ow);
+            }
+        a.ph_taps[ph] = nt;
+        a.ph_org_h[ph] = nt ? mn_h : 0;
+        a.ph_org_w[ph] = nt ? mn_w : 0;
+        if (nt) {
+            span_h = std::max(span_h, mx_h - mn_h);
+            span_w = std::max(span_w, mx_w - mn_w);
+        }
+        for (int t = 0; t < nt; ++t) {
+            // slot offsets are filled in below, once the window width is known
+            a.tap_slot[ph][t] = ((taps[t].oh - a.ph_org_h[ph]) << 8) | (taps[t].ow - a.ph_org_w[ph]);
+            a.tap_id[ph][t] = taps[t].id;
+        }
+    }
+    if (span_h > 255 || span_w > 255) return g;
+    // tile of one parity class: best coverage of the class image by 256-pixel tiles whose window fits
+    const int PH = (int)ceil_div(Hd, s), PW = (int)ceil_div(Wd, s);
+    double best = 0.0;
+    int bTH = 0, bTW = 0, bNI = 0;
+    if (PH * PW <= kPxWg) {
+        bTH = PH; bTW = PW; bNI = kPxWg / (PH * PW);
+        if ((int64_t)bNI * (bTH + span_h) * (bTW + span_w) > 64 * kMaxUnits) bNI = (64 * kMaxUnits) / ((bTH + span_h) * (bTW + span_w));
+        if (bNI < 1) return g;
+    } else {
+        // widest tile among the best covers: the result is stored in runs of TW pixels
+        for (int tw = std::min(PW, 128); tw >= 4; --tw) {
+            const int th = std::min(kPxWg / tw, PH);
+            if (th < 1) continue;
+            if ((int64_t)(th + span_h) * (tw + span_w) > 64 * kMaxUnits) continue;
+            const double eff = (double)PH * PW / ((double)ceil_div(PH, th) * ceil_div(PW, tw) * kPxWg);
+            if (eff > best + 0.02) { best = eff; bTH = th; bTW = tw; }
+        }
+        bNI = 1;
+        if (bTH == 0) return g;
+    }
+    a.TH = bTH; a.TW = bTW; a.NI = bNI;
+    a.SH = bTH + span_h; a.SW = bTW + span_w;
+    for (int ph = 0; ph < s * s; ++ph)
+        for (int t = 0; t < a.ph_taps[ph]; ++t) {
+            const int v = a.tap_slot[ph][t];
+            a.tap_slot[ph][t] = (v >> 8) * a.SW + (v & 255);
+        }
+    const int S = a.NI * a.SH * a.SW;
+    a.units = (int)ceil_div(S, 64);
+    if (a.units > kMaxUnits) return g;
+    a.N = N; a.Hs = Hs; a.Ws = Ws; a.cp = cp; a.Hd = Hd; a.Wd = Wd; a.Crow = Crow;
+    a.RB = (int)ceil_div(Crow, 32);
+    a.tiles_h = (int)ceil_div(PH, a.TH);
+    a.tiles_w = (int)ceil_div(PW, a.TW);
+    a.groups = (int)ceil_div(N, a.NI);
+    a.double_buffer = cp > kKc;
+    g.lds_bytes = (size_t)(a.double_buffer ? 2 : 1) * S * kPitch;
+    if (g.lds_bytes > 150 * 1024) return g;
+    g.rows = Crow > 64 ? 128 : 64;
+    a.div_tw = make_fastdiv((uint32_t)a.TW);
+    a.div_thw = make_fastdiv((uint32_t)(a.TH * a.TW));
+    a.div_sw = make_fastdiv((uint32_t)a.SW);
+    a.div_si = make_fastdiv((uint32_t)(a.SH * a.SW));
+    a.div_tiles_w = make_fastdiv((uint32_t)a.tiles_w);
+    a.div_tiles_hw = make_fastdiv((uint32_t)(a.tiles_h * a.tiles_w));
+    a.div_ptiles = make_fastdiv((uint32_t)(a.groups * a.tiles_h * a.tiles_w * s * s));
+    const int64_t blocks = (int64_t)a.groups * a.tiles_h * a.tiles_w * s * s * ceil_div(Crow, g.rows);
+    if (blocks >= ((int64_t)1 << 31)) return g;
+    g.ok = true;
+    return g;
+}
+
+daq_status launch(Geometry& g, hipStream_t st, const char* name) {
+    const HaloArgs& a = g.a;
+    const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * a.stride * a.stride;
+    const dim3 grid((unsigned)(ptiles * ceil_div(a.Crow, g.rows)));
+#define DAQ_HALO_CASE(WRV, DBV)                                                                                      \
+    {                                                                                                                \
+        auto kern = k_conv_halo<WRV, DBV>;                                                                           \
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) !=  \
+            hipSuccess)                                                                                              \
+            return DAQ_ERR_HIP;                                                                                      \
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));                         \
+    }
+    if (g.rows == 128) {
+        if (a.double_buffer) DAQ_HALO_CASE(2, true) else DAQ_HALO_CASE(2, false)
+    } else {
+        if (a.double_buffer) DAQ_HALO_CASE(1, true) else DAQ_HALO_CASE(1, false)
+    }
+#undef DAQ_HALO_CASE
+    return DAQ_OK;
+}
+
+Geometry plan_bwd(const daq_conv_desc& d) {
+    daq_layout Lg;
+    daq_wpack_layout Lw;
+    Geometry g{};
+    if (d.groups != 1 || daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return g;
+    if (Lg.kind != DAQ_LAYOUT_NHWC || Lg.bytes >= ((int64_t)1 << 31) || Lw.bytes - Lw.off_bwd_frag >= ((int64_t)1 << 31)) return g;
+    g = plan(true, d.N, Lg.H, Lg.W, Lg.c_pitch, d.Hin, d.Win, d.Cin, d.kH, d.kW, d.strideH, d.strideW, d.padH, d.padW,
+             d.dilH, d.dilW);
+    g.a.src_bytes = (uint32_t)Lg.bytes;
+    g.a.wfrag_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd_frag);
+    return g;
+}
+
+Geometry plan_fwd(const daq_conv_desc& d) {
+    daq_layout Lx;
+    daq_wpack_layout Lw;
+    Geometry g{};
+    if (d.groups != 1 || daq_layout_qx_nhwc(&d, &Lx) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return g;
+    if (Lx.bytes >= ((int64_t)1 << 31) || Lw.off_bwd_frag - Lw.off_fwd_frag >= ((int64_t)1 << 31)) return g;
+    g = plan(false, d.N, d.Hin, d.Win, Lx.c_pitch, daq_out_h(&d), daq_out_w(&d), d.Cout, d.kH, d.kW, d.strideH, d.strideW,
+             d.padH, d.padW, d.dilH, d.dilW);
+    g.a.src_bytes = (uint32_t)Lx.bytes;
+    g.a.wfrag_bytes = (uint32_t)(Lw.off_bwd_frag - Lw.off_fwd_frag);
+    return g;
+}
+
+}  // namespace
+
+bool bwd_data_halo_supported(const daq_conv_desc& d) { return plan_bwd(d).ok; }
+
+daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+    Geometry g = plan_bwd(d);
+    daq_wpack_layout Lw;
+    if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
+    g.a.src = qg;
+    g.a.wfrag = qw + Lw.off_bwd_frag;
+    g.a.s_a = s_w; g.a.s_b = s_g;
+    g.a.out = dX; g.a.acc_out = acc;
+    return launch(g, st, "conv_bwd_data_mfma");
+}
+
+bool fwd_halo_supported(const daq_conv_desc& d) { return plan_fwd(d).ok; }
+
+daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx, const int8_t* qw, const float* s_x, const float* s_w,
+                         float* Y, int32_t* acc, hipStream_t st) {
+    Geometry g = plan_fwd(d);
+    daq_wpack_layout Lw;
+    if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
+    g.a.src = qx;
+    g.a.wfrag = qw + Lw.off_fwd_frag;
+    g.a.s_a = s_x; g.a.s_b = s_w;
+    g.a.out = Y; g.a.acc_out = acc;
+    return launch(g, st, "conv_fwd_mfma");
+}
+
+}  // namespace daq

@@ -126,6 +126,14 @@ daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx_nhwc, const in
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st);
 
 
+// conv_mfma_halo.hip: halo-tile form of the channel-contracting kernel (unit stride; stride 2 for the data gradient)
+bool bwd_data_halo_supported(const daq_conv_desc& d);
+daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+bool fwd_halo_supported(const daq_conv_desc& d);
+daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
+                         const float* s_w, float* Y, int32_t* acc, hipStream_t st);
+
 // conv_depthwise.hip: groups == channels, both operands channel-major
 bool depthwise_dx_supported(const daq_conv_desc& d);
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,

@@ -165,6 +165,11 @@ daq_status daq_layout_qw(const daq_conv_desc* d, daq_wpack_layout* out) {
     out->off_fwd = round_up((int64_t)d->Cout * cig * taps, 256);
     out->off_bwd = out->off_fwd + round_up(taps * d->Cout * out->cig_pitch, 256);
     out->bytes = out->off_bwd + round_up(taps * d->Cin * out->cog_pitch, 256);
+    out->off_fwd_frag = out->off_bwd_frag = out->bytes;
+    if (d->groups == 1) {
+        out->off_bwd_frag = out->off_fwd_frag + ceil_div(d->Cin, 64) * taps * ceil_div(d->Cout, 32) * 2048;
+        out->bytes = out->off_bwd_frag + ceil_div(d->Cout, 64) * taps * ceil_div(d->Cin, 32) * 2048;
+    }
     return DAQ_OK;
 }
 

@@ -671,6 +671,15 @@ __global__ __launch_bounds__(kBlock) void k_pack_w(const float* __restrict__ W, 
     out[L.off_plain + i] = code;
     out[L.off_fwd + ((int64_t)tap * Cout + co) * L.cig_pitch + cl] = code;
     out[L.off_bwd + ((int64_t)tap * Cin + ci) * L.cog_pitch + col] = code;
+    if (groups == 1) {
+        // fragment order: element (tap, row, k) of a copy with RB row blocks
+        auto frag = [&](int row, int k, int RB) -> int64_t {
+            return ((((int64_t)(k >> 6) * taps + tap) * RB + (row >> 5)) * 2 + ((k & 63) >> 5)) * 1024 +
+                   ((((k & 31) >> 4) * 32 + (row & 31)) * 16) + (k & 15);
+        };
+        out[L.off_fwd_frag + frag(co, ci, (Cout + 31) / 32)] = code;
+        out[L.off_bwd_frag + frag(ci, co, (Cin + 31) / 32)] = code;
+    }
 }
 
 // grid of k_pack_cnhw: x enumerates (channel, block of 1024 dwords) with the channel's XCD in the low bits,
