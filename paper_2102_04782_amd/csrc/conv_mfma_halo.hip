@@ -69,7 +69,8 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // WR = waves along the row (output channel) axis: 1 -> 64 rows x 256 pixels per workgroup with
 // 64 x 64 wave tiles, 2 -> 128 rows x 256 pixels with 64 x 128 wave tiles.
 // DB = the contraction axis has more than one 64-byte chunk (two window buffers, restaged per chunk).
-template <int WR, bool DB>
+// ST = stride (1 or 2): with one parity class its tables are indexed with constants.
+template <int WR, bool DB, int ST>
 __global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = 4 / WR;
@@ -82,12 +83,15 @@ __global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
     const int wr = wave % WR, wp = wave / WR;
     // block -> (row tile, parity class, image group, tile row, tile column)
     const int per_phase = p.groups * p.tiles_h * p.tiles_w;
-    const int ptiles = per_phase * p.stride * p.stride;
+    const int ptiles = per_phase * ST * ST;
     const int tr = (int)fdiv(blockIdx.x, p.div_ptiles);
     int tp = blockIdx.x - tr * ptiles;
-    const int phase = tp / per_phase;   // at most four classes: a plain division is fine here
-    tp -= phase * per_phase;
-    const int pa = phase / p.stride, pb = phase - pa * p.stride;
+    int phase = 0;
+    if (ST > 1) {
+        phase = (tp >= per_phase) + (tp >= 2 * per_phase) + (tp >= 3 * per_phase);
+        tp -= phase * per_phase;
+    }
+    const int pa = phase / ST, pb = phase % ST;
     const int grp = (int)fdiv((uint32_t)tp, p.div_tiles_hw);
     const int trem = tp - grp * p.tiles_h * p.tiles_w;
     const int tih = (int)fdiv((uint32_t)trem, p.div_tiles_w);
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
         const int rem = q - img * p.TH * p.TW;
         const int th = (int)fdiv((uint32_t)rem, p.div_tw);
         const int tw = rem - th * p.TW;
-        const int n = n0 + img, h = (h0 + th) * p.stride + pa, w = (w0 + tw) * p.stride + pb;
+        const int n = n0 + img, h = (h0 + th) * ST + pa, w = (w0 + tw) * ST + pb;
         if (img >= p.NI || n >= p.N || h >= p.Hd || w >= p.Wd) continue;
         const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w;
         float* o = p.out + pix;
@@ -382,7 +386,7 @@ daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     const dim3 grid((unsigned)(ptiles * ceil_div(a.Crow, g.rows)));
 #define DAQ_HALO_CASE(WRV, DBV)                                                                                      \
     {                                                                                                                \
-        auto kern = k_conv_halo<WRV, DBV>;                                                                           \
+        auto kern = a.stride == 2 ? k_conv_halo<WRV, DBV, 2> : k_conv_halo<WRV, DBV, 1>;                             \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) !=  \
             hipSuccess)                                                                                              \
             return DAQ_ERR_HIP;                                                                                      \

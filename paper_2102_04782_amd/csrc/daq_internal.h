@@ -64,9 +64,9 @@ inline FastDiv make_fastdiv(uint32_t d) {
     return f;
 }
 __device__ __forceinline__ uint32_t fdiv(uint32_t x, const FastDiv& f) {
-    if (f.one) return x;
     const uint32_t t = __umulhi(x, f.mul);
-    return (t + ((x - t) >> 1)) >> f.shift;
+    const uint32_t q = (t + ((x - t) >> 1)) >> f.shift;
+    return f.one ? x : q;   // a select, not a branch: branches here split the prologues that call this many times
 }
 
 // ---- device-side view of an int8 layout ----------------------------------------------------
