@@ -44,7 +44,11 @@ struct DxArgs {
 // Data gradient, unit stride and dilation, kW <= 4: a thread produces four adjacent outputs of one row.
 // For filter row kh it reads the 8 gradient bytes that cover the windows of all four outputs with one
 // (byte-aligned) load, and each output is one dot4 of its 4-byte window with the reversed filter row.
+// KH = KW = 3 is instantiated with constant extents (every load issued up front, filter rows fetched as dwords);
+// KH = 0 takes the extents from the arguments.
+template <int KH, int KW>
 __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
+    const int kH = KH ? KH : p.kH, kW = KW ? KW : p.kW;
     const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
     const uint32_t rows = (uint32_t)p.N * p.C * p.Hin;
     const uint32_t row = fdiv(i, p.div_wq);
@@ -56,15 +60,22 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
     const int c = (int)(nc - n * (uint32_t)p.C);
 
     const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
-    const int8_t* wrow = p.qw + c * (p.kH * p.kW);
-    const int T = p.kH * p.kW;
+    const int8_t* wrow = p.qw + c * (kH * kW);
     int acc[4] = {0, 0, 0, 0};
-    for (int kh = 0; kh < p.kH; ++kh) {
+#pragma unroll
+    for (int kh = 0; kh < kH; ++kh) {
         // reversed filter row in one dword: byte m = W[kh][kW-1-m], zero beyond kW
         int wr = 0;
-        for (int m = 0; m < p.kW; ++m) wr |= ((int)(uint8_t)wrow[kh * p.kW + (p.kW - 1 - m)]) << (8 * m);
+        if (KW == 3) {
+            // bytes W0 W1 W2 and one byte of whatever follows (the packed filter has further copies behind this one)
+            typedef int i1 __attribute__((ext_vector_type(1), aligned(1)));
+            const int raw = (*reinterpret_cast<const i1*>(wrow + kh * 3))[0];
+            wr = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, 0x0c000102u);
+        } else {
+            for (int m = 0; m < kW; ++m) wr |= ((int)(uint8_t)wrow[kh * kW + (kW - 1 - m)]) << (8 * m);
+        }
         const int ho = h + p.pH - kh;
-        const int col0 = w0 + p.pW - (p.kW - 1);
+        const int col0 = w0 + p.pW - (kW - 1);
         const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(g + ((int64_t)((int)n * p.img_rows + ho) * p.row_pitch + col0));
         const unsigned lo = (unsigned)v[0], hi = (unsigned)v[1];
         acc[0] = dot4((int)lo, wr, acc[0]);
@@ -72,7 +83,65 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
         acc[2] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 2), wr, acc[2]);
         acc[3] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 3), wr, acc[3]);
     }
-    (void)T;
+    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const int64_t o = (int64_t)row * p.Win + w0;
+    if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
+        *reinterpret_cast<float4*>(p.dX + o) =
+            make_float4((float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale);
+        if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (w0 + j < p.Win) {
+                p.dX[o + j] = (float)acc[j] * scale;
+                if (p.acc_out) p.acc_out[o + j] = acc[j];
+            }
+    }
+}
+
+// Data gradient, stride 2 or 4, unit dilation: a thread produces four adjacent outputs w0..w0+3 (w0 a multiple
+// of four).  For a live filter row (h + pad - kh a multiple of the stride) the gradient columns the four outputs
+// can touch lie within 8 bytes, fetched with one load.  Which taps are live for output j, and which of the 8
+// bytes they read, depends only on (j + pad - kw) - the same for every thread - so the selection is scalar
+// control flow and the work per live tap is one byte extract and one multiply-add.
+template <int KH, int KW>
+__global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
+    const int kH = KH ? KH : p.kH, kW = KW ? KW : p.kW;
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t rows = (uint32_t)p.N * p.C * p.Hin;
+    const uint32_t row = fdiv(i, p.div_wq);
+    if (row >= rows) return;
+    const int w0 = 4 * (int)(i - row * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(row, p.div_h);
+    const int h = (int)(row - nc * (uint32_t)p.Hin);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+
+    const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
+    const int8_t* wf = p.qw + c * (kH * kW);
+    const int smask = (1 << p.s_log2) - 1;
+    // first gradient column any of the four outputs can read, relative to w0 >> s_log2 (an arithmetic shift: floor)
+    const int c_first = (p.pW - (kW - 1)) >> p.s_log2;
+    int acc[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int kh = 0; kh < kH; ++kh) {
+        const int th = h + p.pH - kh;
+        if (th & smask) continue;
+        const int8_t* src = g + ((int64_t)((int)n * p.img_rows + (th >> p.s_log2)) * p.row_pitch + (w0 >> p.s_log2) + c_first);
+        const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(src);
+#pragma unroll
+        for (int kw = 0; kw < kW; ++kw) {
+            const int wv = wf[kh * kW + kw];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int t = j + p.pW - kw;              // uniform
+                if (t & smask) continue;
+                const int b = (t >> p.s_log2) - c_first;   // uniform byte index, 0..7
+                const int word = b < 4 ? v[0] : v[1];
+                acc[j] += __builtin_amdgcn_sbfe(word, 8 * (b & 3), 8) * wv;
+            }
+        }
+    }
     const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
@@ -247,8 +316,17 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
     const dim3 grid((unsigned)ceil_div(threads, kBlock));
     const bool unit = d.strideH == 1 && d.dilH == 1 && d.dilW == 1 && d.kW <= 4;
-    if (unit)
-        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_unit, grid, dim3(kBlock), 0, st, a));
+    // strided form: the columns four outputs can read, (3 + kW - 1) / stride + 1 of them, must fit the 8-byte load
+    const bool strided = d.strideH > 1 && d.dilH == 1 && d.dilW == 1 && (3 + d.kW - 1) / d.strideH + 2 <= 8;
+    const bool k33 = d.kH == 3 && d.kW == 3;
+    if (unit && k33)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_unit<3, 3>), grid, dim3(kBlock), 0, st, a));
+    else if (unit)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_unit<0, 0>), grid, dim3(kBlock), 0, st, a));
+    else if (strided && k33)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_strided<3, 3>), grid, dim3(kBlock), 0, st, a));
+    else if (strided)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_strided<0, 0>), grid, dim3(kBlock), 0, st, a));
     else
         DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_any, grid, dim3(kBlock), 0, st, a));
     return DAQ_OK;
