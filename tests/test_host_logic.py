@@ -172,12 +172,12 @@ def test_workload_tables():
     assert len(r50) == 53 and len({(l.Cin, l.Hin, l.Cout, l.kH, l.stride) for l in r50}) == 23
     total = sum(l.macs for l in r50)
     assert abs(total - 261.6e9) / 261.6e9 < 0.01          # 2 x 261.6 GMAC x 2 convs = 1046 GOP backward
-    assert sum(int(np.prod(l.y_shape)) for l in r50) == 711_262_208 or abs(sum(int(np.prod(l.y_shape)) for l in r50) - 711.3e6) < 1e6
+    assert sum(int(np.prod(l.y_shape)) for l in r50) == 711_294_976           # gradient elements the quantizer sweeps
     mb = wl.config5()
     assert len(mb) == 50 and sum(1 for l in mb if l.groups > 1) == 17
     assert abs(sum(int(np.prod(l.y_shape)) for l in mb) - 795.4e6) < 1e6
     l2 = wl.config2()[0]
-    assert l2.y_shape == (32, 64, 56, 56) and 2 * l2.macs == 7_398_752_256 or abs(2 * l2.macs - 7.40e9) < 1e7
+    assert l2.y_shape == (32, 64, 56, 56) and 2 * l2.macs == 7_398_752_256     # 7.40 GOP per GEMM
     # generators are seeded and follow the recipe: even channels bell-shaped, odd channels long-tailed
     layer, X, W, dY, st = wl.make_inputs(1)
     _, _, _, dY2, _ = wl.make_inputs(1)
