@@ -47,6 +47,8 @@ extern "C" daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const 
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (bwd_filter_lds_supported(*desc))
+        return conv_bwd_filter_lds(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
     if (bwd_filter_mfma_supported(*desc))
         return conv_bwd_filter_mfma(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
     if (depthwise_dw_supported(*desc))

@@ -1,0 +1,441 @@
+// Filter gradient  q(G_W) = q(X') (x) vq(G')  for 3 x 3 filters at unit stride and dilation, on the
+// full-rate v_mfma_i32_32x32x32_i8 with both operands staged through LDS.
+//
+// Same shifted-correlation form as conv_mfma_dw.hip:
+//     acc[co][ci][kh][kw] = sum_f  G[co][f] * X[ci][f + kh*row_pitch + kw]
+// A workgroup stages, per 256-byte chunk of the flat axis, 32*WM gradient rows and 32*WN activation
+// rows (the latter 256 + 2*row_pitch + 2 bytes long: every tap's window of the chunk) with
+// coalesced loads, double buffered in LDS behind a register ring that keeps the loads of the next
+// chunks in flight.  A wave owns a 32 (co) x 32 (ci) x 9 (tap) accumulator tile (144 registers).
+// Its gradient fragment is one aligned 16-byte LDS read; for each filter row it reads the 24 bytes
+// from the dword at or below the row's first window (activation rows have a pitch of 4 * odd bytes,
+// so the 32 rows of a fragment fall into different banks, at the price of dword-aligned accesses)
+// and derives the three kw windows with v_alignbyte_b32 (shift (kh*row_pitch mod 4) + kw, a
+// compile-time constant per instantiation).  Waves either hold different tiles (WK = 1, 64 x 64 per
+// workgroup) or share one tile and split the eight K steps of every chunk (WK = 4), combined in
+// parallel through LDS at the end; the latter keeps all CUs busy on layers with few channels.  K
+// can also be split across workgroups: partial tiles are written with coalesced stores and summed
+// by k_dw32_reduce.
+#include <algorithm>
+
+#include "daq_internal.h"
+
+namespace daq {
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
+
+constexpr int kKC = 256;        // K bytes staged per chunk (8 MFMA K-steps of 32)
+constexpr int kPA = kKC + 16;   // LDS pitch of a gradient row: 16-byte aligned, rotates banks between rows
+constexpr int kT = 9;
+
+struct Dw32Args {
+    const int8_t* g;      // vq, [Cout][klen]
+    const int8_t* x;      // q(X'), [Cin][x_chan_pitch]
+    int64_t klen;
+    int64_t x_chan_pitch;
+    int Cout, Cin;
+    int row_pitch;
+    int pb;               // LDS pitch of an activation row in bytes (a multiple of 4 with pb/4 odd)
+    int b_units;          // 16-byte units of an activation row that are staged per chunk
+    int nchunks, splits;
+    int tiles_n, tiles_m;
+    int32_t* part;        // splits > 1: [tile][split][wave tile][slot = tap*16 + reg][lane]
+    const float* s_x;
+    const float* s_chan;
+    float* dW;
+    int32_t* acc_out;
+};
+
+__device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
+    return (int)__builtin_amdgcn_alignbyte((unsigned)hi, (unsigned)lo, (unsigned)sh);
+}
+
+// WQ4 = row_pitch mod 4.  WM x WN x WK = 4 waves: tiles along co, along ci, split of the K steps.
+// PF = chunks whose global loads are in flight beyond the one being written to LDS (register ring).
+template <int WQ4, int WM, int WN, int WK, int PF>
+__global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
+    static_assert(WM * WN * WK == 4, "four waves");
+    constexpr int BM = 32 * WM, BN = 32 * WN;
+    constexpr int A_PER_T = BM * (kKC / 16) / 256;   // 16-byte units of the gradient tile per thread
+    constexpr int A_BYTES = BM * kPA;
+    constexpr int B_MAX = 4 * WN;                     // 16-byte units of the activation tile per thread, at most
+    extern __shared__ __align__(16) int8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int wk = wave % WK, wn = (wave / WK) % WN, wm = wave / (WK * WN);
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int B_BYTES = BN * p.pb;
+    const int STAGE = A_BYTES + B_BYTES;
+
+    // workgroup i runs on XCD i % 8: all tiles of one K split share an L2
+    int split, tile;
+    {
+        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+        const int full = (p.splits / kXcd) * kXcd;
+        const int x = b % kXcd, q = b / kXcd;
+        if (q < (full / kXcd) * tiles) {
+            split = (q / tiles) * kXcd + x;
+            tile = q % tiles;
+        } else {
+            const int rb = b - full * tiles;
+            split = full + rb % (p.splits - full);
+            tile = rb / (p.splits - full);
+        }
+    }
+    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    const int co0 = tm * BM, ci0 = tn * BN;
+    const int per = p.nchunks / p.splits, rem = p.nchunks % p.splits;
+    const int c_begin = split * per + min(split, rem);
+    const int c_end = c_begin + per + (split < rem ? 1 : 0);
+
+    // ---- staging assignment ----
+    // gradient: unit u = tid + 256*i -> row u / 16, 16-byte column u % 16
+    uint32_t a_src[A_PER_T];
+    int a_dst[A_PER_T];
+#pragma unroll
+    for (int i = 0; i < A_PER_T; ++i) {
+        const int u = tid + 256 * i;
+        const int row = u >> 4, c16 = u & 15;
+        const int co = co0 + row;
+        a_src[i] = (uint32_t)((int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * c16);   // rows past Cout recompute row 0, never stored
+        a_dst[i] = row * kPA + 16 * c16;
+    }
+    // activation: unit u = tid + 256*i of the BN x b_units tile (row-major): consecutive lanes, consecutive 16 bytes
+    uint32_t b_src[B_MAX];
+    int b_dst[B_MAX];
+    const int b_total = BN * p.b_units;
+#pragma unroll
+    for (int i = 0; i < B_MAX; ++i) {
+        const int u = tid + 256 * i;
+        const int uc = u < b_total ? u : 0;
+        const int row = uc / p.b_units, col = uc - row * p.b_units;
+        const int ci = ci0 + row;
+        b_src[i] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * col);
+        b_dst[i] = u < b_total ? A_BYTES + row * p.pb + 16 * col : -1;
+    }
+    // Every call issues the same loads (past the end the last chunk is fetched again, which the caches absorb):
+    // only then can the compiler count the loads in flight and wait for exactly the oldest set.
+    v4i ra[PF][A_PER_T], rb[PF][B_MAX];
+    const int c_last = max(c_end - 1, 0);
+    auto load_chunk = [&](int chunk, int set) {
+        const int64_t k0 = (int64_t)min(chunk, c_last) * kKC;
+        const int8_t* gk = p.g + k0;
+        const int8_t* xk = p.x + k0;
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i) ra[set][i] = *reinterpret_cast<const v4i*>(gk + a_src[i]);
+#pragma unroll
+        for (int i = 0; i < B_MAX; ++i) rb[set][i] = *reinterpret_cast<const v4i*>(xk + b_src[i]);
+        __builtin_amdgcn_sched_barrier(0);   // keep the sets in program order
+    };
+    auto store_chunk = [&](int buf, int set) {
+        int8_t* base = lds + buf * STAGE;
+#pragma unroll
+        for (int i = 0; i < A_PER_T; ++i) *reinterpret_cast<v4i*>(base + a_dst[i]) = ra[set][i];
+#pragma unroll
+        for (int i = 0; i < B_MAX; ++i)
+            if (b_dst[i] >= 0) *reinterpret_cast<v4i_a4*>(base + b_dst[i]) = rb[set][i];   // rows are only dword aligned
+    };
+
+    v16i acc[kT];
+#pragma unroll
+    for (int t = 0; t < kT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0;
+
+    // chunk c_begin goes to LDS; chunks c_begin+1 .. c_begin+PF stay in flight in ring sets 1 .. PF-1, 0
+    load_chunk(c_begin, 0);
+    store_chunk(0, 0);
+#pragma unroll
+    for (int i = 1; i <= PF; ++i) load_chunk(c_begin + i, i % PF);
+    __syncthreads();
+
+    const int arow = (wm * 32 + l32) * kPA + 16 * lh;
+    const int brow = A_BYTES + (wn * 32 + l32) * p.pb + 16 * lh;
+    for (int base = c_begin; base < c_end; base += PF) {
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int chunk = base + u;
+        if (chunk >= c_end) break;   // uniform
+        const int buf = (chunk - c_begin) & 1;
+        const int8_t* A = lds + buf * STAGE + arow;
+        const int8_t* B = lds + buf * STAGE + brow;
+        // All LDS reads of this wave's K steps are issued before the first multiply: with one wave per SIMD nothing
+        // else hides their latency.
+        constexpr int KS = (kKC / 32) / WK;
+        v4i fa[KS];
+        int fd[KS][3][6];
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            const int ks = wk + i * WK;
+            fa[i] = *reinterpret_cast<const v4i*>(A + 32 * ks);
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                // 24 bytes from the dword at or below this filter row's first window
+                const int8_t* src = B + 32 * ks + ((kh * p.row_pitch) & ~3);
+                const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(src);
+                const v2i_a4 hi = *reinterpret_cast<const v2i_a4*>(src + 16);
+                fd[i][kh][0] = lo[0]; fd[i][kh][1] = lo[1]; fd[i][kh][2] = lo[2]; fd[i][kh][3] = lo[3];
+                fd[i][kh][4] = hi[0]; fd[i][kh][5] = hi[1];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+#pragma unroll
+            for (int kh = 0; kh < 3; ++kh) {
+                const int r0 = (kh * WQ4) & 3;
+                const int* d = fd[i][kh];
+#pragma unroll
+                for (int kw = 0; kw < 3; ++kw) {
+                    const int s = r0 + kw, j = s >> 2, sh = s & 3;
+                    v4i bf;
+                    if (sh == 0)
+                        bf = v4i{d[j], d[j + 1], d[j + 2], d[j + 3]};
+                    else
+                        bf = v4i{alignbyte(d[j + 1], d[j], sh), alignbyte(d[j + 2], d[j + 1], sh),
+                                 alignbyte(d[j + 3], d[j + 2], sh), alignbyte(d[j + 4], d[j + 3], sh)};
+                    acc[kh * 3 + kw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], bf, acc[kh * 3 + kw], 0, 0, 0);
+                }
+            }
+        }
+        // chunk+1 sits in ring set (u+1) % PF: it goes to the other LDS buffer and the set is refilled PF chunks ahead
+        store_chunk(buf ^ 1, (u + 1) % PF);
+        load_chunk(chunk + 1 + PF, (u + 1) % PF);
+        __syncthreads();
+      }
+    }
+
+    // register r of a 32 x 32 tile: row (co) 8*(r/4) + 4*lh + r%4, column (ci) l32; slot = tap*16 + r
+    constexpr int SLOTS = kT * 16;
+    if (WK > 1) {
+        // ---- combine the WK waves that share a tile, in parallel: wave w owns slots [w*SLOTS/WK, (w+1)*SLOTS/WK);
+        // every wave hands the other owners their slots through LDS ([owner][source][slot][lane]) and keeps its own ----
+        constexpr int OWN = SLOTS / WK;
+        static_assert(SLOTS % WK == 0, "slots divide evenly among the waves");
+        int* red = reinterpret_cast<int*>(lds);
+        __syncthreads();   // the staging buffers are dead from here on
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+            const int owner = q / OWN;
+            if (owner != wk) {   // uniform
+                const int srcw = wk < owner ? wk : wk - 1;
+                red[((owner * (WK - 1) + srcw) * OWN + q % OWN) * kWave + lane] = acc[q / 16][q % 16];
+            }
+        }
+        __syncthreads();
+        int32_t* dst = p.part + ((int64_t)tile * p.splits + split) * SLOTS * kWave + lane;
+        int own[OWN];
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+            if (q / OWN != wk) continue;   // uniform
+            int v = acc[q / 16][q % 16];
+#pragma unroll
+            for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWN + q % OWN) * kWave + lane];
+            own[q % OWN] = v;
+            if (p.splits > 1) dst[q * kWave] = v;
+        }
+        if (p.splits > 1) return;
+        // Complete tile: dW[co][ci][t] has the 32 ci x 9 taps of one co contiguous (1152 bytes), but a lane holds one
+        // ci and a register one (co, t).  The tile is transposed through LDS so that the global stores are row runs.
+        __syncthreads();   // everyone is done reading the hand-over area
+        constexpr int ROWW = 32 * kT + 1;   // ints per co row in LDS (+1: lanes of a column hit different banks)
+#pragma unroll
+        for (int q = 0; q < SLOTS; ++q) {
+            if (q / OWN != wk) continue;
+            const int t = q / 16, r = q % 16;
+            red[(8 * (r >> 2) + 4 * lh + (r & 3)) * ROWW + l32 * kT + t] = own[q % OWN];
+        }
+        __syncthreads();
+        const float sx = *p.s_x / 127.0f;
+        const int ncol = min(32, p.Cin - ci0) * kT;   // valid ints of a row
+        for (int row = wave; row < 32; row += 4) {
+            const int co = co0 + row;
+            if (co >= p.Cout) break;
+            const float sc = sx * (p.s_chan[co] / 127.0f);
+            const int64_t off = ((int64_t)co * p.Cin + ci0) * kT;
+            for (int j = lane; j < ncol; j += kWave) {
+                const int v = red[row * ROWW + j];
+                p.dW[off + j] = (float)v * sc;
+                if (p.acc_out) p.acc_out[off + j] = v;
+            }
+        }
+        return;
+    }
+
+    if (p.splits > 1) {
+        int32_t* dst = p.part + (((int64_t)tile * p.splits + split) * (WM * WN) + wm * WN + wn) * SLOTS * kWave + lane;
+#pragma unroll
+        for (int t = 0; t < kT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) dst[(t * 16 + r) * kWave] = acc[t][r];
+        return;
+    }
+    const float sx = *p.s_x / 127.0f;
+    const int ci = ci0 + wn * 32 + l32;
+    if (ci >= p.Cin) return;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int co = co0 + wm * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        if (co < p.Cout) {
+            const int64_t off = ((int64_t)co * p.Cin + ci) * kT;
+            const float sc = sx * (p.s_chan[co] / 127.0f);
+#pragma unroll
+            for (int t = 0; t < kT; ++t) {
+                p.dW[off + t] = (float)acc[t][r] * sc;
+                if (p.acc_out) p.acc_out[off + t] = acc[t][r];
+            }
+        }
+    }
+}
+
+// Sum of the K-split partial tiles, then dW[co][ci][t] = acc * ((s_x/127) * (s_chan[co]/127)).
+// Workgroup = 64 consecutive (slot, lane) entries of one wave tile; its four waves take every fourth split.
+__global__ __launch_bounds__(256) void k_dw32_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wm_n,
+                                                     int wn_n, int Cout, int Cin, const float* s_x,
+                                                     const float* __restrict__ s_chan, float* __restrict__ dW,
+                                                     int32_t* __restrict__ acc_out) {
+    const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
+    const int per_wave = kT * 16;                       // slots of one wave tile
+    const int wtiles = wm_n * wn_n;
+    const int64_t e = blockIdx.x;                       // (tile, wave tile, slot)
+    const int slot = (int)(e % per_wave);
+    const int wt = (int)((e / per_wave) % wtiles);
+    const int tile = (int)(e / ((int64_t)per_wave * wtiles));
+    const int64_t stride = (int64_t)wtiles * per_wave * kWave;   // between consecutive splits of a tile
+    const int32_t* src = part + (int64_t)tile * splits * stride + ((int64_t)wt * per_wave + slot) * kWave + lane;
+    int32_t a = 0;
+    int s = grp;
+    for (; s + 28 < splits; s += 32) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
+    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
+    __shared__ int32_t l_sum[4][kWave];
+    l_sum[grp][lane] = a;
+    __syncthreads();
+    if (grp != 0) return;
+    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
+    const int t = slot / 16, r = slot % 16;
+    const int wm = wt / wn_n, wn = wt % wn_n;
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int co = (tm * wm_n + wm) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    const int ci = (tn * wn_n + wn) * 32 + (lane & 31);
+    if (co >= Cout || ci >= Cin) return;
+    const int64_t off = ((int64_t)co * Cin + ci) * kT + t;
+    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
+    if (acc_out) acc_out[off] = a;
+}
+
+struct Plan32 {
+    bool ok;
+    int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units;
+    size_t lds_bytes;
+    int64_t part_slots;   // int32 entries of one split's partial tiles
+};
+
+Plan32 make_plan32(const daq_conv_desc& d) {
+    Plan32 pl{};
+    if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1 || d.kH != 3 || d.kW != 3) return pl;
+    daq_layout Lg, Lx;
+    if (daq_layout_vq(&d, &Lg) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK) return pl;
+    if (Lg.bytes >= ((int64_t)1 << 32) || Lx.bytes >= ((int64_t)1 << 32)) return pl;   // 32-bit per-lane offsets
+    pl.nchunks = (int)(Lg.plane_pitch / kKC);
+    // bytes of an activation row a chunk needs: its own 256 plus the largest tap offset, plus the bytes the
+    // six-dword reads of the last K step touch beyond that
+    const int need = kKC + 2 * Lx.row_pitch + 2 + 8;
+    pl.b_units = (int)ceil_div(need, 16);
+    pl.pb = 16 * pl.b_units + 4;              // pitch/4 odd: the 32 rows of a fragment read fall into 32 different banks
+    const int64_t t64 = ceil_div(d.Cout, 64) * ceil_div(d.Cin, 64);
+    if (t64 >= 128) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
+    else { pl.wm = 1; pl.wn = 1; pl.wk = 4; }
+    const int bm = 32 * pl.wm, bn = 32 * pl.wn;
+    if ((int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile
+    pl.tiles_m = (int)ceil_div(d.Cout, bm);
+    pl.tiles_n = (int)ceil_div(d.Cin, bn);
+    const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+    int64_t s = ceil_div(256, tiles);
+    s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
+    pl.splits = (int)std::max<int64_t>(1, s);
+    const size_t stage = (size_t)bm * kPA + (size_t)bn * pl.pb;
+    // hand-over area of the parallel combine: [owner][source][slot][lane]
+    pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * kT * 16 * kWave * 4 : 0);
+    if (pl.lds_bytes > 150 * 1024) return pl;
+    pl.part_slots = tiles * pl.wm * pl.wn * kT * 16 * kWave;
+    pl.ok = true;
+    return pl;
+}
+
+template <int WM, int WN, int WK>
+daq_status launch32(const Plan32& pl, const Dw32Args& a, int wq4, hipStream_t st) {
+    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+#define DAQ_DW32_CASE(Q)                                                                                          \
+    if (wq4 == Q) {                                                                                               \
+        auto kern = k_dw32<Q, WM, WN, WK, 3>;                                                                        \
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
+                                (int)pl.lds_bytes) != hipSuccess)                                                 \
+            return DAQ_ERR_HIP;                                                                                   \
+        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
+        return DAQ_OK;                                                                                            \
+    }
+    DAQ_DW32_CASE(0) DAQ_DW32_CASE(1) DAQ_DW32_CASE(2) DAQ_DW32_CASE(3)
+#undef DAQ_DW32_CASE
+    return DAQ_ERR_UNSUPPORTED;
+}
+
+}  // namespace
+
+bool bwd_filter_lds_supported(const daq_conv_desc& d) { return make_plan32(d).ok; }
+
+size_t bwd_filter_lds_ws_bytes(const daq_conv_desc& d) {
+    const Plan32 pl = make_plan32(d);
+    if (!pl.ok || pl.splits == 1) return 0;
+    return (size_t)round_up(pl.part_slots * pl.splits * 4, 256);
+}
+
+daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
+                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st) {
+    const Plan32 pl = make_plan32(d);
+    if (!pl.ok) return DAQ_ERR_UNSUPPORTED;
+    daq_layout Lx, Lg;
+    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
+    Dw32Args a{};
+    a.g = vq;
+    a.x = qx;
+    a.klen = Lg.plane_pitch;
+    a.x_chan_pitch = Lx.chan_pitch;
+    a.Cout = d.Cout;
+    a.Cin = d.Cin;
+    a.row_pitch = Lx.row_pitch;
+    a.pb = pl.pb;
+    a.b_units = pl.b_units;
+    a.nchunks = pl.nchunks;
+    a.splits = pl.splits;
+    a.tiles_n = pl.tiles_n;
+    a.tiles_m = pl.tiles_m;
+    a.part = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
+    a.s_x = s_x;
+    a.s_chan = s_chan;
+    a.dW = dW;
+    a.acc_out = acc;
+    const int wq4 = Lx.row_pitch & 3;
+    const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1>(pl, a, wq4, st) : launch32<1, 1, 4>(pl, a, wq4, st);
+    if (rc != DAQ_OK) return rc;
+    if (pl.splits > 1) {
+        const unsigned blocks = (unsigned)(pl.part_slots / kWave);
+        DAQ_LAUNCH("dw_reduce", st,
+                   hipLaunchKernelGGL(k_dw32_reduce, dim3(blocks), dim3(256), 0, st, a.part, pl.splits, pl.tiles_n, pl.wm,
+                                      pl.wn, d.Cout, d.Cin, s_x, s_chan, dW, acc));
+    }
+    return DAQ_OK;
+}
+
+}  // namespace daq

@@ -179,7 +179,7 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* d) {
         case DAQ_OP_QUANTIZE_GRAD: return quantize_grad_ws_bytes(*d);
         case DAQ_OP_CONV_FWD: return fwd_quant_ws_bytes(*d);
         case DAQ_OP_CONV_BWD_DATA: return 256;
-        case DAQ_OP_CONV_BWD_FILTER: return 256 + std::max(bwd_filter_mfma_ws_bytes(*d), depthwise_dw_ws_bytes(*d));
+        case DAQ_OP_CONV_BWD_FILTER: return 256 + std::max({bwd_filter_mfma_ws_bytes(*d), bwd_filter_lds_ws_bytes(*d), depthwise_dw_ws_bytes(*d)});
         default: return 0;
     }
 }
