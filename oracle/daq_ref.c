@@ -444,6 +444,84 @@ int daq_ref_conv_bwd_filter_acc(const ref_conv_desc* d, const int8_t* qX, const 
 }
 
 /* ------------------------------------------------------------------------- */
+/* Single elements of the two gradients, for checks at sizes where the whole    */
+/* tensor is too much for the loops above.  Same definitions (Eq. "gx", "gw"),  */
+/* one output per index: idx[i] is the linear NCHW index into G_X, or the       */
+/* linear [Cout][Cin/groups][kH][kW] index into G_W.  Values wrap to int32.     */
+/* ------------------------------------------------------------------------- */
+int daq_ref_conv_bwd_data_acc_at(const ref_conv_desc* d, const int8_t* qG, const int8_t* qW, const int64_t* idx,
+                                 int64_t count, int32_t* out) {
+    if (!desc_ok(d) || !qG || !qW || !idx || !out || count < 0) return REF_BAD_ARG;
+    const int Ho = daq_ref_out_h(d), Wo = daq_ref_out_w(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    const int64_t total = (int64_t)d->N * d->Cin * d->Hin * d->Win;
+    for (int64_t i = 0; i < count; ++i)
+        if (idx[i] < 0 || idx[i] >= total) return REF_BAD_ARG;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t r = idx[i];
+        const int w = (int)(r % d->Win); r /= d->Win;
+        const int h = (int)(r % d->Hin); r /= d->Hin;
+        const int ci = (int)(r % d->Cin);
+        const int n = (int)(r / d->Cin);
+        const int g = ci / cig, cl = ci % cig;
+        int64_t a = 0;
+        for (int col = 0; col < cog; ++col) {
+            const int co = g * cog + col;
+            for (int kh = 0; kh < d->kH; ++kh) {
+                /* the output row that tap kh of this input row contributed to in the forward pass, if any */
+                const int hn = h + d->padH - kh * d->dilH;
+                if (hn < 0 || hn % d->strideH || hn / d->strideH >= Ho) continue;
+                for (int kw = 0; kw < d->kW; ++kw) {
+                    const int wn = w + d->padW - kw * d->dilW;
+                    if (wn < 0 || wn % d->strideW || wn / d->strideW >= Wo) continue;
+                    const int8_t gv = qG[(((size_t)n * d->Cout + co) * Ho + hn / d->strideH) * Wo + wn / d->strideW];
+                    const int8_t wv = qW[(((size_t)co * cig + cl) * d->kH + kh) * d->kW + kw];
+                    a += (int64_t)gv * (int64_t)wv;
+                }
+            }
+        }
+        int o = 0;
+        out[i] = wrap32(a, &o);
+    }
+    return REF_OK;
+}
+
+int daq_ref_conv_bwd_filter_acc_at(const ref_conv_desc* d, const int8_t* qX, const int8_t* qG, const int64_t* idx,
+                                   int64_t count, int32_t* out) {
+    if (!desc_ok(d) || !qX || !qG || !idx || !out || count < 0) return REF_BAD_ARG;
+    const int Ho = daq_ref_out_h(d), Wo = daq_ref_out_w(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    const int64_t total = (int64_t)d->Cout * cig * d->kH * d->kW;
+    for (int64_t i = 0; i < count; ++i)
+        if (idx[i] < 0 || idx[i] >= total) return REF_BAD_ARG;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t r = idx[i];
+        const int kw = (int)(r % d->kW); r /= d->kW;
+        const int kh = (int)(r % d->kH); r /= d->kH;
+        const int cl = (int)(r % cig);
+        const int co = (int)(r / cig);
+        const int ci = (co / cog) * cig + cl;
+        int64_t a = 0;
+        for (int n = 0; n < d->N; ++n)
+            for (int ho = 0; ho < Ho; ++ho) {
+                const int h = ho * d->strideH + kh * d->dilH - d->padH;
+                if (h < 0 || h >= d->Hin) continue;
+                for (int wo = 0; wo < Wo; ++wo) {
+                    const int w = wo * d->strideW + kw * d->dilW - d->padW;
+                    if (w < 0 || w >= d->Win) continue;
+                    a += (int64_t)qX[(((size_t)n * d->Cin + ci) * d->Hin + h) * d->Win + w] *
+                         (int64_t)qG[(((size_t)n * d->Cout + co) * Ho + ho) * Wo + wo];
+                }
+            }
+        int o = 0;
+        out[i] = wrap32(a, &o);
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* De-quantization of an accumulator: acc * (s_a/127) * (s_b/127), evaluated   */
 /* in fp32 as  (float)acc * ((s_a/127) * (s_b/127)).                           */
 /* ------------------------------------------------------------------------- */

@@ -238,6 +238,30 @@ def conv_bwd_filter_acc(d: ConvDesc, qX, qG):
     return acc, bool(ovf.value)
 
 
+def conv_bwd_data_acc_at(d: ConvDesc, qG, qW, idx):
+    """Accumulators of G_X at the linear NCHW indices ``idx`` only (same definition as conv_bwd_data_acc)."""
+    qG, qW = _i8(qG), _i8(qW)
+    assert qG.shape == d.y_shape and qW.shape == d.w_shape
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    out = np.zeros(idx.size, np.int32)
+    dd = d.c()
+    _chk(lib().daq_ref_conv_bwd_data_acc_at(C.byref(dd), _p(qG, C.c_int8), _p(qW, C.c_int8), _p(idx, C.c_int64),
+                                            C.c_int64(idx.size), _p(out, C.c_int32)), "conv_bwd_data_acc_at")
+    return out
+
+
+def conv_bwd_filter_acc_at(d: ConvDesc, qX, qG, idx):
+    """Accumulators of G_W at the linear [Cout][Cin/g][kH][kW] indices ``idx`` only."""
+    qX, qG = _i8(qX), _i8(qG)
+    assert qX.shape == d.x_shape and qG.shape == d.y_shape
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    out = np.zeros(idx.size, np.int32)
+    dd = d.c()
+    _chk(lib().daq_ref_conv_bwd_filter_acc_at(C.byref(dd), _p(qX, C.c_int8), _p(qG, C.c_int8), _p(idx, C.c_int64),
+                                              C.c_int64(idx.size), _p(out, C.c_int32)), "conv_bwd_filter_acc_at")
+    return out
+
+
 @dataclass
 class Fwd:
     qX: np.ndarray

@@ -104,6 +104,12 @@ def test_against_scatter_form_and_torch(ref, case):
     assert np.array_equal(accX, tdX.numpy().astype(np.int64))
     assert np.array_equal(accW, tdW.numpy().astype(np.int64))
 
+    # the single-element entry points (used for sampled checks at full size) against torch's routines, every element
+    ix = rng.permutation(accX.size)
+    assert np.array_equal(ref.conv_bwd_data_acc_at(d, qG, qW, ix), tdX.numpy().astype(np.int64).ravel()[ix])
+    iw = rng.permutation(accW.size)
+    assert np.array_equal(ref.conv_bwd_filter_acc_at(d, qX, qG, iw), tdW.numpy().astype(np.int64).ravel()[iw])
+
 
 def test_one_by_one_is_a_matrix_product(ref):
     d = ref.ConvDesc(3, 8, 5, 4, 6, 1, 1)
