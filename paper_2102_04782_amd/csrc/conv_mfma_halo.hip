@@ -366,7 +366,9 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     a.double_buffer = cp > kKc;
     g.lds_bytes = (size_t)(a.double_buffer ? 2 : 1) * S * kPitch;
     if (g.lds_bytes > 150 * 1024) return g;
-    g.rows = Crow > 64 ? 128 : 64;
+    // 128-row tiles reuse each pixel fragment twice as often, but only pay off when they still fill the chip
+    const int64_t blocks128 = (int64_t)a.groups * a.tiles_h * a.tiles_w * s * s * ceil_div(Crow, 128);
+    g.rows = (Crow > 64 && blocks128 >= 256) ? 128 : 64;
     a.div_tw = make_fastdiv((uint32_t)a.TW);
     a.div_thw = make_fastdiv((uint32_t)(a.TH * a.TW));
     a.div_sw = make_fastdiv((uint32_t)a.SW);
