@@ -11,8 +11,9 @@
 // from the dword at or below the row's first window (activation rows have a pitch of 4 * odd bytes,
 // so the 32 rows of a fragment fall into different banks, at the price of dword-aligned accesses)
 // and derives the three kw windows with v_alignbyte_b32 (shift (kh*row_pitch mod 4) + kw, a
-// compile-time constant per instantiation).  Waves either hold different tiles (WK = 1, 64 x 64 per
-// workgroup) or share one tile and split the eight K steps of every chunk (WK = 4), combined in
+// compile-time constant per instantiation).  Waves either hold different tiles (WK = 1, four waves,
+// 64 x 64 per workgroup) or share one tile and take one of the eight K steps of every chunk each
+// (WK = 8: two waves per SIMD, so that one's LDS phase overlaps the other's multiplies), combined in
 // parallel through LDS at the end; the latter keeps all CUs busy on layers with few channels.  K
 // can also be split across workgroups: partial tiles are written with coalesced stores and summed
 // by k_dw32_reduce.
@@ -55,15 +56,16 @@ __device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
     return (int)__builtin_amdgcn_alignbyte((unsigned)hi, (unsigned)lo, (unsigned)sh);
 }
 
-// WQ4 = row_pitch mod 4.  WM x WN x WK = 4 waves: tiles along co, along ci, split of the K steps.
+// WQ4 = row_pitch mod 4.  WM x WN x WK = 4 or 8 waves: tiles along co, along ci, split of the K steps.
 // PF = chunks whose global loads are in flight beyond the one being written to LDS (register ring).
 template <int WQ4, int WM, int WN, int WK, int PF>
-__global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
-    static_assert(WM * WN * WK == 4, "four waves");
+__global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
+    constexpr int WAVES = WM * WN * WK, NT = 64 * WAVES;
+    static_assert(WAVES == 4 || WAVES == 8, "four or eight waves");
     constexpr int BM = 32 * WM, BN = 32 * WN;
-    constexpr int A_PER_T = BM * (kKC / 16) / 256;   // 16-byte units of the gradient tile per thread
+    constexpr int A_PER_T = BM * (kKC / 16) / NT;    // 16-byte units of the gradient tile per thread
     constexpr int A_BYTES = BM * kPA;
-    constexpr int B_MAX = 4 * WN;                     // 16-byte units of the activation tile per thread, at most
+    constexpr int B_MAX = 4 * WN * 256 / NT;          // 16-byte units of the activation tile per thread, at most
     extern __shared__ __align__(16) int8_t lds[];
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
     int a_dst[A_PER_T];
 #pragma unroll
     for (int i = 0; i < A_PER_T; ++i) {
-        const int u = tid + 256 * i;
+        const int u = tid + NT * i;
         const int row = u >> 4, c16 = u & 15;
         const int co = co0 + row;
         a_src[i] = (uint32_t)((int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * c16);   // rows past Cout recompute row 0, never stored
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
     const int b_total = BN * p.b_units;
 #pragma unroll
     for (int i = 0; i < B_MAX; ++i) {
-        const int u = tid + 256 * i;
+        const int u = tid + NT * i;
         const int uc = u < b_total ? u : 0;
         const int row = uc / p.b_units, col = uc - row * p.b_units;
         const int ci = ci0 + row;
@@ -214,31 +216,38 @@ __global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
     // register r of a 32 x 32 tile: row (co) 8*(r/4) + 4*lh + r%4, column (ci) l32; slot = tap*16 + r
     constexpr int SLOTS = kT * 16;
     if (WK > 1) {
-        // ---- combine the WK waves that share a tile, in parallel: wave w owns slots [w*SLOTS/WK, (w+1)*SLOTS/WK);
-        // every wave hands the other owners their slots through LDS ([owner][source][slot][lane]) and keeps its own ----
-        constexpr int OWN = SLOTS / WK;
-        static_assert(SLOTS % WK == 0, "slots divide evenly among the waves");
+        // ---- combine the WK waves that share a tile, in parallel: every wave owns an equal share of the slots,
+        // hands the other owners theirs through LDS ([owner][source][slot][lane]) and keeps its own ----
+        // With eight waves the hand-over area for all slots would not fit: two rounds over half of the slots each.
+        constexpr int R = WK > 4 ? 2 : 1;
+        constexpr int PER = SLOTS / R;          // slots handed over per round
+        constexpr int OWNR = PER / WK;          // slots a wave owns per round
+        constexpr int OWN = R * OWNR;
+        static_assert(SLOTS % (R * WK) == 0, "slots divide evenly among rounds and waves");
         int* red = reinterpret_cast<int*>(lds);
-        __syncthreads();   // the staging buffers are dead from here on
-#pragma unroll
-        for (int q = 0; q < SLOTS; ++q) {
-            const int owner = q / OWN;
-            if (owner != wk) {   // uniform
-                const int srcw = wk < owner ? wk : wk - 1;
-                red[((owner * (WK - 1) + srcw) * OWN + q % OWN) * kWave + lane] = acc[q / 16][q % 16];
-            }
-        }
-        __syncthreads();
         int32_t* dst = p.part + ((int64_t)tile * p.splits + split) * SLOTS * kWave + lane;
         int own[OWN];
 #pragma unroll
-        for (int q = 0; q < SLOTS; ++q) {
-            if (q / OWN != wk) continue;   // uniform
-            int v = acc[q / 16][q % 16];
+        for (int rd = 0; rd < R; ++rd) {
+            __syncthreads();   // the staging buffers (or the previous round) are dead from here on
 #pragma unroll
-            for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWN + q % OWN) * kWave + lane];
-            own[q % OWN] = v;
-            if (p.splits > 1) dst[q * kWave] = v;
+            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
+                const int owner = (q - rd * PER) / OWNR;
+                if (owner != wk) {   // uniform
+                    const int srcw = wk < owner ? wk : wk - 1;
+                    red[((owner * (WK - 1) + srcw) * OWNR + (q - rd * PER) % OWNR) * kWave + lane] = acc[q / 16][q % 16];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
+                if ((q - rd * PER) / OWNR != wk) continue;   // uniform
+                int v = acc[q / 16][q % 16];
+#pragma unroll
+                for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWNR + (q - rd * PER) % OWNR) * kWave + lane];
+                own[rd * OWNR + (q - rd * PER) % OWNR] = v;
+                if (p.splits > 1) dst[q * kWave] = v;
+            }
         }
         if (p.splits > 1) return;
         // Complete tile: dW[co][ci][t] has the 32 ci x 9 taps of one co contiguous (1152 bytes), but a lane holds one
@@ -247,14 +256,14 @@ __global__ __launch_bounds__(256) void k_dw32(Dw32Args p) {
         constexpr int ROWW = 32 * kT + 1;   // ints per co row in LDS (+1: lanes of a column hit different banks)
 #pragma unroll
         for (int q = 0; q < SLOTS; ++q) {
-            if (q / OWN != wk) continue;
+            if ((q % PER) / OWNR != wk) continue;
             const int t = q / 16, r = q % 16;
-            red[(8 * (r >> 2) + 4 * lh + (r & 3)) * ROWW + l32 * kT + t] = own[q % OWN];
+            red[(8 * (r >> 2) + 4 * lh + (r & 3)) * ROWW + l32 * kT + t] = own[(q / PER) * OWNR + (q % PER) % OWNR];
         }
         __syncthreads();
         const float sx = *p.s_x / 127.0f;
         const int ncol = min(32, p.Cin - ci0) * kT;   // valid ints of a row
-        for (int row = wave; row < 32; row += 4) {
+        for (int row = wave; row < 32; row += WAVES) {
             const int co = co0 + row;
             if (co >= p.Cout) break;
             const float sc = sx * (p.s_chan[co] / 127.0f);
@@ -356,9 +365,9 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     pl.pb = 16 * pl.b_units + 4;              // pitch/4 odd: the 32 rows of a fragment read fall into 32 different banks
     const int64_t t64 = ceil_div(d.Cout, 64) * ceil_div(d.Cin, 64);
     if (t64 >= 128) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
-    else { pl.wm = 1; pl.wn = 1; pl.wk = 4; }
+    else { pl.wm = 1; pl.wn = 1; pl.wk = 8; }   // eight waves: two per SIMD, so that one's LDS phase overlaps the other's MFMAs
     const int bm = 32 * pl.wm, bn = 32 * pl.wn;
-    if ((int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile
+    if ((int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile (B_MAX * threads)
     pl.tiles_m = (int)ceil_div(d.Cout, bm);
     pl.tiles_n = (int)ceil_div(d.Cin, bn);
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
@@ -367,23 +376,24 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     pl.splits = (int)std::max<int64_t>(1, s);
     const size_t stage = (size_t)bm * kPA + (size_t)bn * pl.pb;
     // hand-over area of the parallel combine: [owner][source][slot][lane]
-    pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * kT * 16 * kWave * 4 : 0);
+    const int rounds = pl.wk > 4 ? 2 : 1;
+    pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * kT * 16 * kWave * 4 / rounds : 0);
     if (pl.lds_bytes > 150 * 1024) return pl;
     pl.part_slots = tiles * pl.wm * pl.wn * kT * 16 * kWave;
     pl.ok = true;
     return pl;
 }
 
-template <int WM, int WN, int WK>
+template <int WM, int WN, int WK, int PF>
 daq_status launch32(const Plan32& pl, const Dw32Args& a, int wq4, hipStream_t st) {
     const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
 #define DAQ_DW32_CASE(Q)                                                                                          \
     if (wq4 == Q) {                                                                                               \
-        auto kern = k_dw32<Q, WM, WN, WK, 3>;                                                                        \
+        auto kern = k_dw32<Q, WM, WN, WK, PF>;                                                                        \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
-        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
+        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WN * WK), pl.lds_bytes, st, a)); \
         return DAQ_OK;                                                                                            \
     }
     DAQ_DW32_CASE(0) DAQ_DW32_CASE(1) DAQ_DW32_CASE(2) DAQ_DW32_CASE(3)
@@ -427,7 +437,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.dW = dW;
     a.acc_out = acc;
     const int wq4 = Lx.row_pitch & 3;
-    const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1>(pl, a, wq4, st) : launch32<1, 1, 4>(pl, a, wq4, st);
+    const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1) {
         const unsigned blocks = (unsigned)(pl.part_slots / kWave);
