@@ -550,6 +550,11 @@ struct RowsArgs {
     int per_channel_scale;
     uint32_t tensor;
     uint64_t seed;
+    // optional second copy of the same tensor in the same layout, quantized with its own per-tensor scale
+    // (the globally quantized gradient of a depthwise layer): one read of the source serves both
+    int8_t* dst2;
+    const float* scale2;
+    uint32_t tensor2;
 };
 
 template <int V>
@@ -575,18 +580,22 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
     if (c >= L.C) return;
     const int tid = threadIdx.x;
     int8_t* plane = dst + (int64_t)c * L.chan_pitch;
+    int8_t* plane2 = pa.dst2 ? pa.dst2 + (int64_t)c * L.chan_pitch : nullptr;   // uniform
     const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
 
     if (jb == pa.per_chan) {
         // padding rows behind every image, then the bytes in front of the first row and behind the last image
         const uint32_t prb = (uint32_t)(L.img_rows - L.H) * (uint32_t)L.row_pitch;
         const uint32_t total = (uint32_t)L.N * prb;
-        for (uint32_t t = tid; t < total; t += kBlock) {
-            const uint32_t n = fdiv(t, pa.div_prb);
-            plane[(uint32_t)L.lead + n * slot + (uint32_t)L.H * (uint32_t)L.row_pitch + (t - n * prb)] = 0;
+        for (int copy = 0; copy < (plane2 ? 2 : 1); ++copy) {
+            int8_t* pl = copy ? plane2 : plane;
+            for (uint32_t t = tid; t < total; t += kBlock) {
+                const uint32_t n = fdiv(t, pa.div_prb);
+                pl[(uint32_t)L.lead + n * slot + (uint32_t)L.H * (uint32_t)L.row_pitch + (t - n * prb)] = 0;
+            }
+            for (uint32_t t = tid; t < (uint32_t)L.lead; t += kBlock) pl[t] = 0;
+            for (uint32_t t = (uint32_t)L.lead + (uint32_t)L.N * slot + tid; t < (uint32_t)L.plane_pitch; t += kBlock) pl[t] = 0;
         }
-        for (uint32_t t = tid; t < (uint32_t)L.lead; t += kBlock) plane[t] = 0;
-        for (uint32_t t = (uint32_t)L.lead + (uint32_t)L.N * slot + tid; t < (uint32_t)L.plane_pitch; t += kBlock) plane[t] = 0;
         return;
     }
 
@@ -634,6 +643,19 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
         if (live[u]) store_codes<V>(plane + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
         if (row_end[u])
             for (int k = 0; k < padw; ++k) plane[doff[u] + V + k] = 0;
+    }
+    if (plane2) {
+        const float inv2 = inv_scale(pa.scale2[0]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            uint32_t bits[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                bits[i] = quant_bits<STOCH>(x[u][i], inv2, pa.seed, pa.tensor2, (uint64_t)(eoff[u] >> 2) + i);
+            if (live[u]) store_codes<V>(plane2 + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
+            if (row_end[u])
+                for (int k = 0; k < padw; ++k) plane2[doff[u] + V + k] = 0;
+        }
     }
 }
 
@@ -713,9 +735,13 @@ bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31)
 
 // Launches the channel-major packing of one fp32 NCHW tensor: the source-driven row kernel when the
 // layout allows it, the output-driven kernel otherwise.
+// With dst2 the same pass also writes a second copy quantized with the per-tensor scale scale2 (random stream
+// tensor2); *fused tells whether that happened - the output-driven kernel writes one copy per launch.
 daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src, const daq_layout& Ld,
                        const float* scale, int per_channel_scale, int8_t* dst, uint32_t tensor, uint64_t seed,
-                       const QuantWs& ws, const ClipArgs& ca, hipStream_t st) {
+                       const QuantWs& ws, const ClipArgs& ca, hipStream_t st, int8_t* dst2 = nullptr,
+                       const float* scale2 = nullptr, uint32_t tensor2 = 0, bool* fused = nullptr) {
+    if (fused) *fused = false;
     const CnhwView V = cnhw_view(Ld);
     const int64_t lim24 = (int64_t)1 << 24;
     const bool unsplit = Ld.phases_h == 1 && Ld.phases_w == 1 && Ld.org_h == 0 && Ld.org_w == 0 &&
@@ -734,6 +760,10 @@ daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src
         ra.per_channel_scale = per_channel_scale;
         ra.tensor = tensor;
         ra.seed = seed;
+        ra.dst2 = dst2;
+        ra.scale2 = scale2;
+        ra.tensor2 = tensor2;
+        if (fused) *fused = dst2 != nullptr;
         const dim3 grid((unsigned)(round_up(Ld.C, kXcd) * (ra.per_chan + 1)));
 #define DAQ_ROWS(S, CL, VV) \
     DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_rows<S, CL, VV>), grid, dim3(kBlock), 0, st, src, V, scale, dst, ra, ws, ca))
@@ -873,8 +903,11 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     // S3 + S4 + S5: discriminator, clip rule and the per-channel copy in CNHW (and the global copy for
     // depthwise layers, whose data gradient also runs channel-major)
     ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
-    rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, seed, ws, ca, st);
+    bool fused = false;
+    rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, seed, ws, ca, st, qg_nhwc ? nullptr : qg, s_global,
+                     1u, &fused);
     if (rc != DAQ_OK) return rc;
-    if (!qg_nhwc) rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);
+    if (!qg_nhwc && !fused)
+        rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);
     return rc;
 }
