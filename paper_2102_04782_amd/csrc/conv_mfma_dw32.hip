@@ -1,5 +1,5 @@
-// Filter gradient  q(G_W) = q(X') (x) vq(G')  for 3 x 3 filters at unit stride and dilation, on the
-// full-rate v_mfma_i32_32x32x32_i8 with both operands staged through LDS.
+// Filter gradient  q(G_W) = q(X') (x) vq(G')  for 3 x 3 (k_dw32) and 1 x 1 (k_dw11) filters at unit stride and
+// dilation, on the full-rate v_mfma_i32_32x32x32_i8 with both operands staged through LDS.
 //
 // Same shifted-correlation form as conv_mfma_dw.hip:
 //     acc[co][ci][kh][kw] = sum_f  G[co][f] * X[ci][f + kh*row_pitch + kw]
@@ -344,8 +344,217 @@ __global__ __launch_bounds__(256) void k_dw32_reduce(const int32_t* __restrict__
     if (acc_out) acc_out[off] = a;
 }
 
+// ---------------------------------------------------------------------------------------------
+// 1 x 1 filters at unit stride: no tap shifts, so the product is a plain int8 GEMM over the flat axis,
+//     acc[co][ci] = sum_f  G[co][f] * X[ci][f] ,
+// with both operands staged the same way (rows of 256 + 16 bytes, aligned 16-byte fragment reads).
+// A wave owns 64 (co) x 64 (ci): four 32 x 32 tiles, so every fragment it reads feeds two multiplies.
+// Same ring, K-split and wave-combine scheme as above.
+// ---------------------------------------------------------------------------------------------
+template <int WM, int WN, int WK, int PF>
+__global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
+    constexpr int WAVES = WM * WN * WK, NT = 64 * WAVES;
+    static_assert(WAVES == 4 || WAVES == 8, "four or eight waves");
+    constexpr int BM = 64 * WM, BN = 64 * WN;
+    constexpr int UNITS = (BM + BN) * (kKC / 16) / NT;   // 16-byte units of the two tiles per thread
+    constexpr int STAGE = (BM + BN) * kPA;
+    extern __shared__ __align__(16) int8_t lds[];
+
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    const int wk = wave % WK, wn = (wave / WK) % WN, wm = wave / (WK * WN);
+    const int l32 = lane & 31, lh = lane >> 5;
+
+    int split, tile;
+    {
+        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+        const int full = (p.splits / kXcd) * kXcd;
+        const int x = b % kXcd, q = b / kXcd;
+        if (q < (full / kXcd) * tiles) {
+            split = (q / tiles) * kXcd + x;
+            tile = q % tiles;
+        } else {
+            const int rb = b - full * tiles;
+            split = full + rb % (p.splits - full);
+            tile = rb / (p.splits - full);
+        }
+    }
+    const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
+    const int co0 = tm * BM, ci0 = tn * BN;
+    const int per = p.nchunks / p.splits, rem = p.nchunks % p.splits;
+    const int c_begin = split * per + min(split, rem);
+    const int c_end = c_begin + per + (split < rem ? 1 : 0);
+    const int c_last = max(c_end - 1, 0);
+
+    // unit u = tid + NT*i -> row u / 16 of the stacked (gradient, activation) tile, 16-byte column u % 16
+    const int8_t* u_src[UNITS];
+    int u_dst[UNITS];
+#pragma unroll
+    for (int i = 0; i < UNITS; ++i) {
+        const int u = tid + NT * i;
+        const int row = u >> 4, c16 = u & 15;
+        if (row < BM) {   // rows past Cout / Cin recompute row 0 and are never stored
+            const int co = co0 + row;
+            u_src[i] = p.g + (int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * c16;
+        } else {
+            const int ci = ci0 + row - BM;
+            u_src[i] = p.x + (int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * c16;
+        }
+        u_dst[i] = row * kPA + 16 * c16;
+    }
+    v4i ring[PF][UNITS];
+    auto load_chunk = [&](int chunk, int set) {
+        const int64_t k0 = (int64_t)min(chunk, c_last) * kKC;
+#pragma unroll
+        for (int i = 0; i < UNITS; ++i) ring[set][i] = *reinterpret_cast<const v4i*>(u_src[i] + k0);
+        __builtin_amdgcn_sched_barrier(0);   // keep the sets in program order
+    };
+    auto store_chunk = [&](int buf, int set) {
+#pragma unroll
+        for (int i = 0; i < UNITS; ++i) *reinterpret_cast<v4i*>(lds + buf * STAGE + u_dst[i]) = ring[set][i];
+    };
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
+
+    load_chunk(c_begin, 0);
+    store_chunk(0, 0);
+#pragma unroll
+    for (int i = 1; i <= PF; ++i) load_chunk(c_begin + i, i % PF);
+    __syncthreads();
+
+    const int arow = (wm * 64 + l32) * kPA + 16 * lh;
+    const int brow = (BM + wn * 64 + l32) * kPA + 16 * lh;
+    for (int base = c_begin; base < c_end; base += PF) {
+#pragma unroll
+      for (int u = 0; u < PF; ++u) {
+        const int chunk = base + u;
+        if (chunk >= c_end) break;   // uniform
+        const int buf = (chunk - c_begin) & 1;
+        const int8_t* A = lds + buf * STAGE + arow;
+        const int8_t* B = lds + buf * STAGE + brow;
+        constexpr int KS = (kKC / 32) / WK;
+        v4i fa[KS][2], fb[KS][2];
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+            const int ks = wk + i * WK;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fa[i][t] = *reinterpret_cast<const v4i*>(A + t * 32 * kPA + 32 * ks);
+                fb[i][t] = *reinterpret_cast<const v4i*>(B + t * 32 * kPA + 32 * ks);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < KS; ++i)
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][a], fb[i][b], acc[a][b], 0, 0, 0);
+        store_chunk(buf ^ 1, (u + 1) % PF);
+        load_chunk(chunk + 1 + PF, (u + 1) % PF);
+        __syncthreads();
+      }
+    }
+
+    // slot q = (a*2 + b)*16 + r: tile (a, b) of the wave, register r -> row (co) 32a + 8*(r/4) + 4*lh + r%4, column (ci) 32b + l32
+    constexpr int SLOTS = 64;
+    int own[SLOTS / WK];
+    constexpr int R = WK > 4 ? 2 : 1;
+    constexpr int PER = SLOTS / R, OWNR = PER / WK;
+    if (WK > 1) {
+        // parallel combine of the WK waves, as in k_dw32
+        int* red = reinterpret_cast<int*>(lds);
+#pragma unroll
+        for (int rd = 0; rd < R; ++rd) {
+            __syncthreads();
+#pragma unroll
+            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
+                const int owner = (q - rd * PER) / OWNR;
+                if (owner != wk) {   // uniform
+                    const int srcw = wk < owner ? wk : wk - 1;
+                    red[((owner * (WK - 1) + srcw) * OWNR + (q - rd * PER) % OWNR) * kWave + lane] = acc[q / 32][(q / 16) % 2][q % 16];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
+                if ((q - rd * PER) / OWNR != wk) continue;   // uniform
+                int v = acc[q / 32][(q / 16) % 2][q % 16];
+#pragma unroll
+                for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWNR + (q - rd * PER) % OWNR) * kWave + lane];
+                own[rd * OWNR + (q - rd * PER) % OWNR] = v;
+            }
+        }
+    }
+    int32_t* dst = p.part + (((int64_t)tile * p.splits + split) * (WM * WN) + wm * WN + wn) * SLOTS * kWave + lane;
+    const float sx = *p.s_x / 127.0f;
+#pragma unroll
+    for (int q = 0; q < SLOTS; ++q) {
+        if (WK > 1 && (q % PER) / OWNR != wk) continue;   // uniform: not this wave's slot
+        const int v = WK > 1 ? own[(q / PER) * OWNR + (q % PER) % OWNR] : acc[q / 32][(q / 16) % 2][q % 16];
+        if (p.splits > 1) {
+            dst[q * kWave] = v;
+        } else {
+            const int r = q % 16;
+            const int co = co0 + wm * 64 + 32 * (q / 32) + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const int ci = ci0 + wn * 64 + 32 * ((q / 16) % 2) + l32;
+            if (co < p.Cout && ci < p.Cin) {
+                const int64_t off = (int64_t)co * p.Cin + ci;   // 32 lanes = 32 consecutive ci: 128-byte runs
+                p.dW[off] = (float)v * (sx * (p.s_chan[co] / 127.0f));
+                if (p.acc_out) p.acc_out[off] = v;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_dw11_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wm_n,
+                                                     int wn_n, int Cout, int Cin, const float* s_x,
+                                                     const float* __restrict__ s_chan, float* __restrict__ dW,
+                                                     int32_t* __restrict__ acc_out) {
+    const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
+    constexpr int per_wave = 64;
+    const int wtiles = wm_n * wn_n;
+    const int64_t e = blockIdx.x;                       // (tile, wave tile, slot)
+    const int slot = (int)(e % per_wave);
+    const int wt = (int)((e / per_wave) % wtiles);
+    const int tile = (int)(e / ((int64_t)per_wave * wtiles));
+    const int64_t stride = (int64_t)wtiles * per_wave * kWave;
+    const int32_t* src = part + (int64_t)tile * splits * stride + ((int64_t)wt * per_wave + slot) * kWave + lane;
+    int32_t a = 0;
+    int s = grp;
+    for (; s + 28 < splits; s += 32) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
+    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
+    __shared__ int32_t l_sum[4][kWave];
+    l_sum[grp][lane] = a;
+    __syncthreads();
+    if (grp != 0) return;
+    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
+    const int r = slot % 16;
+    const int wm = wt / wn_n, wn = wt % wn_n;
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int co = (tm * wm_n + wm) * 64 + 32 * (slot / 32) + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+    const int ci = (tn * wn_n + wn) * 64 + 32 * ((slot / 16) % 2) + (lane & 31);
+    if (co >= Cout || ci >= Cin) return;
+    const int64_t off = (int64_t)co * Cin + ci;
+    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
+    if (acc_out) acc_out[off] = a;
+}
+
 struct Plan32 {
     bool ok;
+    bool k11;             // 1 x 1 filter: the plain GEMM kernel
     int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units;
     size_t lds_bytes;
     int64_t part_slots;   // int32 entries of one split's partial tiles
@@ -353,11 +562,32 @@ struct Plan32 {
 
 Plan32 make_plan32(const daq_conv_desc& d) {
     Plan32 pl{};
-    if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1 || d.kH != 3 || d.kW != 3) return pl;
+    if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1) return pl;
+    const bool k33 = d.kH == 3 && d.kW == 3, k11 = d.kH == 1 && d.kW == 1;
+    if (!k33 && !k11) return pl;
     daq_layout Lg, Lx;
     if (daq_layout_vq(&d, &Lg) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK) return pl;
     if (Lg.bytes >= ((int64_t)1 << 32) || Lx.bytes >= ((int64_t)1 << 32)) return pl;   // 32-bit per-lane offsets
     pl.nchunks = (int)(Lg.plane_pitch / kKC);
+    if (k11) {
+        // plain GEMM: 64 x 64 per wave; 128 x 128 per workgroup when that alone fills the chip, else eight waves on one
+        // 64 x 64 tile with K split among them and across workgroups
+        pl.k11 = true;
+        const int64_t t128 = ceil_div(d.Cout, 128) * ceil_div(d.Cin, 128);
+        if (t128 >= 128) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
+        else { pl.wm = 1; pl.wn = 1; pl.wk = 8; }
+        pl.tiles_m = (int)ceil_div(d.Cout, 64 * pl.wm);
+        pl.tiles_n = (int)ceil_div(d.Cin, 64 * pl.wn);
+        const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+        int64_t s = ceil_div(256, tiles);
+        s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
+        pl.splits = (int)std::max<int64_t>(1, s);
+        const size_t stage = (size_t)64 * (pl.wm + pl.wn) * kPA;
+        pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 / 2 : 0);
+        pl.part_slots = tiles * pl.wm * pl.wn * 64 * kWave;
+        pl.ok = true;
+        return pl;
+    }
     // bytes of an activation row a chunk needs: its own 256 plus the largest tap offset, plus the bytes the
     // six-dword reads of the last K step touch beyond that
     const int need = kKC + 2 * Lx.row_pitch + 2 + 8;
@@ -437,6 +667,25 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.dW = dW;
     a.acc_out = acc;
     const int wq4 = Lx.row_pitch & 3;
+    if (pl.k11) {
+        const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+        if (pl.wk == 1) {
+            auto kern = k_dw11<2, 2, 1, 1>;
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
+                return DAQ_ERR_HIP;
+            DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));
+        } else {
+            auto kern = k_dw11<1, 1, 8, 3>;
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
+                return DAQ_ERR_HIP;
+            DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
+        }
+        if (pl.splits > 1)
+            DAQ_LAUNCH("dw_reduce", st,
+                       hipLaunchKernelGGL(k_dw11_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st, a.part,
+                                          pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, s_x, s_chan, dW, acc));
+        return DAQ_OK;
+    }
     const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1) {
