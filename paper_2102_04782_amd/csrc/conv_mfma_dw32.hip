@@ -562,8 +562,11 @@ struct Plan32 {
 
 Plan32 make_plan32(const daq_conv_desc& d) {
     Plan32 pl{};
-    if (d.groups != 1 || d.strideH != 1 || d.strideW != 1 || d.dilH != 1 || d.dilW != 1) return pl;
-    const bool k33 = d.kH == 3 && d.kW == 3, k11 = d.kH == 1 && d.kW == 1;
+    if (d.groups != 1) return pl;
+    const bool unit = d.strideH == 1 && d.strideW == 1 && d.dilH == 1 && d.dilW == 1;
+    // a 1 x 1 filter pairs gradient position f with byte f of the activation's first stride-phase plane whatever the
+    // stride (and dilation means nothing), so the plain GEMM serves strided shortcuts too
+    const bool k33 = unit && d.kH == 3 && d.kW == 3, k11 = d.kH == 1 && d.kW == 1;
     if (!k33 && !k11) return pl;
     daq_layout Lg, Lx;
     if (daq_layout_vq(&d, &Lg) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK) return pl;
@@ -574,7 +577,7 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         // 64 x 64 tile with K split among them and across workgroups
         pl.k11 = true;
         const int64_t t128 = ceil_div(d.Cout, 128) * ceil_div(d.Cin, 128);
-        if (t128 >= 128) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
+        if (t128 >= 256) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
         else { pl.wm = 1; pl.wn = 1; pl.wk = 8; }
         pl.tiles_m = (int)ceil_div(d.Cout, 64 * pl.wm);
         pl.tiles_n = (int)ceil_div(d.Cin, 64 * pl.wn);
@@ -594,7 +597,7 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     pl.b_units = (int)ceil_div(need, 16);
     pl.pb = 16 * pl.b_units + 4;              // pitch/4 odd: the 32 rows of a fragment read fall into 32 different banks
     const int64_t t64 = ceil_div(d.Cout, 64) * ceil_div(d.Cin, 64);
-    if (t64 >= 128) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
+    if (t64 >= 256) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
     else { pl.wm = 1; pl.wn = 1; pl.wk = 8; }   // eight waves: two per SIMD, so that one's LDS phase overlaps the other's MFMAs
     const int bm = 32 * pl.wm, bn = 32 * pl.wn;
     if ((int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile (B_MAX * threads)

@@ -185,6 +185,8 @@ CONV_LAYERS = [
     wl.Layer("dw_5x5", 2, 8, 14, 14, 8, 5, 5, 1, 2, 1, 8),
     wl.Layer("dw_w7", 3, 16, 7, 7, 16, 3, 3, 1, 1, 1, 16),        # rows that are not a multiple of four outputs
     wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
+    wl.Layer("c1x1_huge", 1, 2048, 4, 4, 2048, 1, 1, 1, 0),       # enough 128 x 128 tiles for the four-wave GEMM form
+    wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
 ]
 
 
