@@ -1,4 +1,5 @@
-// Filter gradient  q(G_W) = q(X') (x) vq(G')  on the gfx950 int8 matrix cores.
+// Filter gradient  q(G_W) = q(X') (x) vq(G')  on the gfx950 int8 matrix cores: the general tap-table kernel (any
+// stride, dilation, extent) and the 3 x 3 forms that serve rows too long for the LDS window of conv_mfma_dw32.hip.
 //
 // Both operands are channel-major (the paper's dimension transformation), with images in pitched
 // slots that carry the zero padding.  With f the flattened (n, row, col) position of a gradient
@@ -742,7 +743,7 @@ Plan make_plan(const daq_conv_desc& d) {
     pl.ok = false;
     if (d.groups != 1) return pl;
     const bool unit = d.strideH == 1 && d.strideW == 1 && d.dilH == 1 && d.dilW == 1;
-    const bool tuned = unit && ((d.kH == 3 && d.kW == 3) || (d.kH == 1 && d.kW == 1 && d.padH == 0 && d.padW == 0));
+    const bool tuned = unit && d.kH == 3 && d.kW == 3;
     if (!tuned) return make_general_plan(d);
     daq_layout Lg;
     if (daq_layout_vq(&d, &Lg) != DAQ_OK) return pl;
@@ -750,7 +751,7 @@ Plan make_plan(const daq_conv_desc& d) {
     pl.nchunks = (int)(Lg.plane_pitch / kKC);
     pl.tiles_m = (int)ceil_div(d.Cout, kBM);
     const int T = d.kH * d.kW;
-    pl.nb = (d.kH == 1) ? 4 : 1;                 // 1x1: a wave takes four ci blocks (64 x 64 tile)
+    pl.nb = 1;
     const int ci_wave = 16 * pl.nb;
     // Prefer a shape with enough output tiles to fill the 256 CUs without splitting K (one launch).
     // With few channels the four waves of a workgroup split K instead of ci, and K is also split
@@ -800,11 +801,7 @@ daq_status launch_dw(const Plan& pl, const DwArgs& a, int wq4, hipStream_t st) {
         DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
         return DAQ_OK;                                                                                            \
     }
-    if constexpr (KH == 1) {
-        DAQ_DW_CASE(0)
-    } else {
-        DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
-    }
+    DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
 #undef DAQ_DW_CASE
     return DAQ_ERR_UNSUPPORTED;
 }
@@ -821,11 +818,7 @@ daq_status launch_dw_direct(const Plan& pl, const DwArgs& a, int wq4, hipStream_
         DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
         return DAQ_OK;                                                                                            \
     }
-    if constexpr (KH == 1) {
-        DAQ_DW_CASE(0)
-    } else {
-        DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
-    }
+    DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
 #undef DAQ_DW_CASE
     return DAQ_ERR_UNSUPPORTED;
 }
@@ -901,10 +894,9 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
         else if (pl.tw == 9) rc = launch_dw_taps<9, 1, 3, false, 4>(pl, a, tt, st);
         else if (T <= 28) rc = launch_dw_taps<7, 1, 2, true, 4>(pl, a, tt, st);
         else rc = launch_dw_taps<7, 1, 2, true, 8>(pl, a, tt, st);
-    } else if (d.kH == 3)
+    } else {
         rc = (pl.wgk == 4) ? launch_dw_direct<3, 3, 1, 3>(pl, a, wq4, st) : launch_dw<3, 3, 1, 1, 1>(pl, a, wq4, st);
-    else
-        rc = (pl.wgk == 4) ? launch_dw_direct<1, 1, 4, 4>(pl, a, 0, st) : launch_dw<1, 1, 1, 4, 1>(pl, a, 0, st);
+    }
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1) {
         const int wgn = pl.general ? 1 : 4 / pl.wgk;

@@ -187,6 +187,8 @@ CONV_LAYERS = [
     wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
     wl.Layer("c1x1_huge", 1, 2048, 4, 4, 2048, 1, 1, 1, 0),       # enough 128 x 128 tiles for the four-wave GEMM form
     wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
+    wl.Layer("c3x3_wide", 1, 16, 8, 130, 16, 3, 3, 1, 1),         # rows too long for the LDS window: global-fragment form
+    wl.Layer("c3x3_wide_huge", 1, 768, 2, 130, 1024, 3, 3, 1, 1),  # the same with enough tiles for its LDS-staged sibling
 ]
 
 
