@@ -276,6 +276,7 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
                                                      const float* __restrict__ s_state, float* __restrict__ s_global) {
     __shared__ float l_sigma[64];
     __shared__ float l_max[kBlock / kWave];
+    __shared__ __align__(16) int8_t l_tile[64 * 80];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int p = blockIdx.x % ws.cgroups;
     const int cb = blockIdx.x / ws.cgroups;
@@ -362,10 +363,21 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
                 b[i] = quant_bits<STOCH>(x[i], inv, seed, 1u, idx);
             }
         }
-        if (WRITE_QG && v_cur && c0 < c_pitch)
-            *reinterpret_cast<uint4*>(qg + ((int64_t)n_cur * HW + px_cur) * c_pitch + c0) =
-                make_uint4(pack4(b[0], b[1], b[2], b[3]), pack4(b[4], b[5], b[6], b[7]), pack4(b[8], b[9], b[10], b[11]),
-                           pack4(b[12], b[13], b[14], b[15]));
+        if (WRITE_QG) {
+            // A lane holds 16 channel bytes of ONE pixel, so a direct store would put 16 bytes into each of 64 different
+            // lines.  The 64-pixel x 64-channel tile goes through LDS instead (80-byte pitch: conflict free both ways)
+            // and leaves as whole 64-byte runs: four adjacent lanes write the 64 channel bytes of one pixel.
+            const uint4 w = make_uint4(pack4(b[0], b[1], b[2], b[3]), pack4(b[4], b[5], b[6], b[7]),
+                                       pack4(b[8], b[9], b[10], b[11]), pack4(b[12], b[13], b[14], b[15]));
+            __syncthreads();   // the previous tile has been read out
+            *reinterpret_cast<uint4*>(l_tile + lane * 80 + 16 * wave) = w;
+            __syncthreads();
+            const int opx = tid >> 2, och = 16 * (tid & 3);
+            const uint32_t P = (uint32_t)tile * kWave + opx;   // pixels of a tile are consecutive in NHWC
+            if (P < M && cb * 64 + och < c_pitch)
+                *reinterpret_cast<uint4*>(qg + (int64_t)P * c_pitch + cb * 64 + och) =
+                    *reinterpret_cast<const uint4*>(l_tile + opx * 80 + och);
+        }
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = nx[i];
         n_cur = n_nxt; px_cur = px_nxt; v_cur = v_nxt;
