@@ -234,10 +234,8 @@ def test_backward_convs_on_random_codes(layer):
     run_convs_on_codes(layer, qX, qW, qG, 2.5, 0.11, 0.03, s_c)
 
 
-@pytest.mark.parametrize("layer", CONV_LAYERS, ids=lambda l: l.name)
-def test_forward_layer(layer):
+def check_forward(layer, seed):
     d, rd = descs(layer)
-    seed = wl.seed_for(7, CONV_LAYERS.index(layer))
     X, W = wl.make_X(layer, seed, post_relu=False), wl.make_W(layer, seed)
     f = daq.conv_fwd_int8(d, t(X), t(W), want_acc=True)
     torch.cuda.synchronize()
@@ -252,6 +250,11 @@ def test_forward_layer(layer):
     assert np.array_equal(f.qw.cpu().numpy(), Lw.pack(d, r.qW)), "packed filter (all three copies)"
     assert np.array_equal(f.acc.cpu().numpy(), r.acc)
     close(f.Y.cpu().numpy(), r.Y, "Y")
+
+
+@pytest.mark.parametrize("layer", CONV_LAYERS, ids=lambda l: l.name)
+def test_forward_layer(layer):
+    check_forward(layer, wl.seed_for(7, CONV_LAYERS.index(layer)))
 
 
 def full_layer_parity(config, index, layer=None):
@@ -312,3 +315,47 @@ def test_accumulator_wraparound_matches_two_complement():
     torch.cuda.synchronize()
     racc, ovf = ref.conv_bwd_filter_acc(rd, qX, qG)
     assert ovf and np.array_equal(acc.cpu().numpy(), racc)
+
+
+def _random_layers(count, seed):
+    """Seeded random small descriptors: every stride / dilation / padding / group / extent combination the entry
+    points accept, at sizes the oracle finishes instantly."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        k = int(rng.choice([1, 2, 3, 3, 3, 5, 7]))
+        s = int(rng.choice([1, 1, 2, 2, 3, 4]))
+        dil = int(rng.choice([1, 1, 1, 2, 3]))
+        pad = int(rng.integers(0, k * dil // 2 + 2))
+        kind = rng.choice(["dense", "dense", "dense", "depthwise", "grouped"])
+        if kind == "dense":
+            cin, cout, g = int(rng.integers(1, 90)), int(rng.integers(1, 90)), 1
+        elif kind == "depthwise":
+            cin = cout = g = int(rng.integers(1, 40))
+        else:
+            g = int(rng.choice([2, 3, 4]))
+            cin, cout = g * int(rng.integers(1, 9)), g * int(rng.integers(1, 9))
+        h, w = int(rng.integers(1, 24)), int(rng.integers(1, 24))
+        n = int(rng.integers(1, 5))
+        if (h + 2 * pad - dil * (k - 1) - 1) < 0 or (w + 2 * pad - dil * (k - 1) - 1) < 0:
+            continue
+        out.append(wl.Layer(f"rnd{len(out)}", n, cin, h, w, cout, k, k, s, pad, dil, g))
+    return out
+
+
+RANDOM_LAYERS = _random_layers(48, 20210204)
+
+
+@pytest.mark.parametrize("layer", RANDOM_LAYERS, ids=lambda l: f"{l.name}-N{l.N}c{l.Cin}>{l.Cout}h{l.Hin}w{l.Win}k{l.kH}s{l.stride}p{l.pad}d{l.dil}g{l.groups}")
+def test_random_descriptors(layer):
+    seed = wl.seed_for(6, RANDOM_LAYERS.index(layer))
+    rng = np.random.default_rng(seed)
+    qX = rng.integers(-127, 128, layer.x_shape).astype(np.int8)
+    qW = rng.integers(-127, 128, layer.w_shape).astype(np.int8)
+    qG = rng.integers(-127, 128, layer.y_shape).astype(np.int8)
+    s_c = (10.0 ** rng.uniform(-4, -1, layer.Cout)).astype(np.float32)
+    run_convs_on_codes(layer, qX, qW, qG, 1.5, 0.2, 0.07, s_c)
+    dY = wl.make_dY(layer, seed)
+    check_quantize_grad(layer, dY, wl.make_state(dY, seed), degenerate=True)
+    check_quantize_grad(layer, dY, wl.make_state(dY, seed), mode=daq.ROUND_STOCHASTIC, seed=seed, degenerate=True)
+    check_forward(layer, seed)
