@@ -66,14 +66,16 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
 }
 
-// WR = waves along the row (output channel) axis: 1 -> 64 rows x 256 pixels per workgroup with
-// 64 x 64 wave tiles, 2 -> 128 rows x 256 pixels with 64 x 128 wave tiles.
+// WR = waves along the row (output channel) axis, WAVES = waves per workgroup.  (1, 4): 64 rows x 256 pixels with
+// 64 x 64 wave tiles.  (2, 4): 128 rows x 256 pixels with 64 x 128 wave tiles.  (2, 8): the same workgroup tile with
+// 64 x 64 wave tiles on eight waves - two per SIMD, so that the LDS reads of one overlap the multiplies of the other.
 // DB = the contraction axis has more than one 64-byte chunk (two window buffers, restaged per chunk).
 // ST = stride (1 or 2): with one parity class its tables are indexed with constants.
-template <int WR, bool DB, int ST>
-__global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
+template <int WR, bool DB, int ST, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
-    constexpr int WPX = 4 / WR;
+    constexpr int WPX = WAVES / WR;
+    constexpr int SPT = 16 * WAVES;   // window slots one pass of the workgroup stages (four lanes per slot)
     constexpr int PXW = kPxWg / WPX;
     constexpr int BF = PXW / 32;
     extern __shared__ __align__(16) int8_t lds[];   // one or two window buffers of S slots
@@ -108,14 +110,14 @@ __global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
     const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
 
-    // ---- window staging: unit tid + 256*i is chunk (tid & 3) of slot (tid >> 2) + 64*i ----
+    // ---- window staging: unit i of a thread is chunk (tid & 3) of slot (tid >> 2) + SPT*i ----
     const int sc = tid & 3;
     uint32_t hoff[kMaxUnits];
 #pragma unroll
     for (int i = 0; i < kMaxUnits; ++i) {
         hoff[i] = kOob;
         if (i < p.units) {   // uniform
-            const int slot = (tid >> 2) + 64 * i;
+            const int slot = (tid >> 2) + SPT * i;
             const int img = (int)fdiv((uint32_t)slot, p.div_si);
             const int rem = slot - img * SI;
             const int r = (int)fdiv((uint32_t)rem, p.div_sw);
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(256) void k_conv_halo(HaloArgs p) {
         int8_t* H = lds + buf * halo_bytes;
 #pragma unroll
         for (int i = 0; i < kMaxUnits; ++i) {
-            const int slot = (tid >> 2) + 64 * i;
+            const int slot = (tid >> 2) + SPT * i;
             if (i < p.units && slot < S) *reinterpret_cast<v4i*>(H + slot * kPitch + 16 * sc) = rh[i];
         }
     };
@@ -356,7 +358,7 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
             a.tap_slot[ph][t] = (v >> 8) * a.SW + (v & 255);
         }
     const int S = a.NI * a.SH * a.SW;
-    a.units = (int)ceil_div(S, 64);
+    a.units = (int)ceil_div(S, 64);   // for four waves; the eight-wave form of 128-row tiles halves it at launch
     if (a.units > kMaxUnits) return g;
     a.N = N; a.Hs = Hs; a.Ws = Ws; a.cp = cp; a.Hd = Hd; a.Wd = Wd; a.Crow = Crow;
     a.RB = (int)ceil_div(Crow, 32);
@@ -386,18 +388,21 @@ daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     const HaloArgs& a = g.a;
     const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * a.stride * a.stride;
     const dim3 grid((unsigned)(ptiles * ceil_div(a.Crow, g.rows)));
-#define DAQ_HALO_CASE(WRV, DBV)                                                                                      \
+#define DAQ_HALO_CASE(WRV, DBV, WV)                                                                                  \
     {                                                                                                                \
-        auto kern = a.stride == 2 ? k_conv_halo<WRV, DBV, 2> : k_conv_halo<WRV, DBV, 1>;                             \
+        auto kern = a.stride == 2 ? k_conv_halo<WRV, DBV, 2, WV> : k_conv_halo<WRV, DBV, 1, WV>;                     \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) !=  \
             hipSuccess)                                                                                              \
             return DAQ_ERR_HIP;                                                                                      \
-        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));                         \
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(64 * WV), g.lds_bytes, st, a));                     \
     }
     if (g.rows == 128) {
-        if (a.double_buffer) DAQ_HALO_CASE(2, true) else DAQ_HALO_CASE(2, false)
+        HaloArgs a8 = g.a;   // eight waves stage the window in half as many passes
+        a8.units = (int)ceil_div((int64_t)g.a.NI * g.a.SH * g.a.SW, 128);
+        const HaloArgs& a = a8;
+        if (a.double_buffer) DAQ_HALO_CASE(2, true, 8) else DAQ_HALO_CASE(2, false, 8)
     } else {
-        if (a.double_buffer) DAQ_HALO_CASE(1, true) else DAQ_HALO_CASE(1, false)
+        if (a.double_buffer) DAQ_HALO_CASE(1, true, 4) else DAQ_HALO_CASE(1, false, 4)
     }
 #undef DAQ_HALO_CASE
     return DAQ_OK;
