@@ -104,9 +104,13 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
 // can touch lie within 8 bytes, fetched with one load.  Which taps are live for output j, and which of the 8
 // bytes they read, depends only on (j + pad - kw) - the same for every thread - so the selection is scalar
 // control flow and the work per live tap is one byte extract and one multiply-add.
-template <int KH, int KW>
+// SLOG2 / PAD >= 0 fix log2(stride) and the padding at compile time: the tap selection below then folds to constants
+// (the 3 x 3, stride 2, pad 1 layers of MobileNetV2 spend their time here).
+template <int KH, int KW, int SLOG2, int PAD>
 __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
     const int kH = KH ? KH : p.kH, kW = KW ? KW : p.kW;
+    const int s_log2 = SLOG2 >= 0 ? SLOG2 : p.s_log2;
+    const int pH = PAD >= 0 ? PAD : p.pH, pW = PAD >= 0 ? PAD : p.pW;
     const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
     const uint32_t rows = (uint32_t)p.N * p.C * p.Hin;
     const uint32_t row = fdiv(i, p.div_wq);
@@ -119,24 +123,24 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
 
     const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
     const int8_t* wf = p.qw + c * (kH * kW);
-    const int smask = (1 << p.s_log2) - 1;
+    const int smask = (1 << s_log2) - 1;
     // first gradient column any of the four outputs can read, relative to w0 >> s_log2 (an arithmetic shift: floor)
-    const int c_first = (p.pW - (kW - 1)) >> p.s_log2;
+    const int c_first = (pW - (kW - 1)) >> s_log2;
     int acc[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int kh = 0; kh < kH; ++kh) {
-        const int th = h + p.pH - kh;
+        const int th = h + pH - kh;
         if (th & smask) continue;
-        const int8_t* src = g + ((int64_t)((int)n * p.img_rows + (th >> p.s_log2)) * p.row_pitch + (w0 >> p.s_log2) + c_first);
+        const int8_t* src = g + ((int64_t)((int)n * p.img_rows + (th >> s_log2)) * p.row_pitch + (w0 >> s_log2) + c_first);
         const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(src);
 #pragma unroll
         for (int kw = 0; kw < kW; ++kw) {
             const int wv = wf[kh * kW + kw];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const int t = j + p.pW - kw;              // uniform
+                const int t = j + pW - kw;              // uniform
                 if (t & smask) continue;
-                const int b = (t >> p.s_log2) - c_first;   // uniform byte index, 0..7
+                const int b = (t >> s_log2) - c_first;   // uniform byte index, 0..7
                 const int word = b < 4 ? v[0] : v[1];
                 acc[j] += __builtin_amdgcn_sbfe(word, 8 * (b & 3), 8) * wv;
             }
@@ -323,10 +327,15 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
         DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_unit<3, 3>), grid, dim3(kBlock), 0, st, a));
     else if (unit)
         DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_unit<0, 0>), grid, dim3(kBlock), 0, st, a));
+    else if (strided && k33 && d.strideH == 2 && d.padH == 1 && d.padW == 1)
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st,
+                   hipLaunchKernelGGL((k_dwise_dx_strided<3, 3, 1, 1>), grid, dim3(kBlock), 0, st, a));
     else if (strided && k33)
-        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_strided<3, 3>), grid, dim3(kBlock), 0, st, a));
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st,
+                   hipLaunchKernelGGL((k_dwise_dx_strided<3, 3, -1, -1>), grid, dim3(kBlock), 0, st, a));
     else if (strided)
-        DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_strided<0, 0>), grid, dim3(kBlock), 0, st, a));
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st,
+                   hipLaunchKernelGGL((k_dwise_dx_strided<0, 0, -1, -1>), grid, dim3(kBlock), 0, st, a));
     else
         DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_any, grid, dim3(kBlock), 0, st, a));
     return DAQ_OK;
