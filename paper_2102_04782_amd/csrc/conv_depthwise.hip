@@ -19,11 +19,23 @@ constexpr int kBlock = 256;
 constexpr int kMaxK = 7;            // largest filter extent of the general data-gradient kernel
 constexpr int kDwSlabBytes = 4096;  // bytes of the flat axis one filter-gradient workgroup covers per iteration
 
-typedef int v2i_a1 __attribute__((ext_vector_type(2), aligned(1)));
-typedef int v4i_a1 __attribute__((ext_vector_type(4), aligned(1)));
+typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
+typedef int v4i_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int dot4(int a, int b, int c) { return __builtin_amdgcn_sdot4(a, b, c, false); }
+
+// The 8 bytes at base + off (any byte alignment, off may be negative inside the zero halo).  A byte-aligned vector
+// load runs at half the rate of a dword-aligned one on this chip, so 12 bytes are fetched from the dword below and
+// shifted; base must be dword aligned.
+__device__ __forceinline__ void load8(const int8_t* base, int64_t off, unsigned& lo, unsigned& hi) {
+    const int8_t* src = base + (off & ~(int64_t)3);
+    const unsigned sh = (unsigned)(off & 3);
+    const v2i_a4 d01 = *reinterpret_cast<const v2i_a4*>(src);
+    const unsigned d2 = *reinterpret_cast<const unsigned*>(src + 8);
+    lo = __builtin_amdgcn_alignbyte((unsigned)d01[1], (unsigned)d01[0], sh);
+    hi = __builtin_amdgcn_alignbyte(d2, (unsigned)d01[1], sh);
+}
 
 struct DxArgs {
     const int8_t* qg;      // planar gradient, [C][chan_pitch]
@@ -76,8 +88,8 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
         }
         const int ho = h + p.pH - kh;
         const int col0 = w0 + p.pW - (kW - 1);
-        const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(g + ((int64_t)((int)n * p.img_rows + ho) * p.row_pitch + col0));
-        const unsigned lo = (unsigned)v[0], hi = (unsigned)v[1];
+        unsigned lo, hi;
+        load8(g, (int64_t)((int)n * p.img_rows + ho) * p.row_pitch + col0, lo, hi);
         acc[0] = dot4((int)lo, wr, acc[0]);
         acc[1] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 1), wr, acc[1]);
         acc[2] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 2), wr, acc[2]);
@@ -131,8 +143,8 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
     for (int kh = 0; kh < kH; ++kh) {
         const int th = h + pH - kh;
         if (th & smask) continue;
-        const int8_t* src = g + ((int64_t)((int)n * p.img_rows + (th >> s_log2)) * p.row_pitch + (w0 >> s_log2) + c_first);
-        const v2i_a1 v = *reinterpret_cast<const v2i_a1*>(src);
+        unsigned v[2];
+        load8(g, (int64_t)((int)n * p.img_rows + (th >> s_log2)) * p.row_pitch + (w0 >> s_log2) + c_first, v[0], v[1]);
 #pragma unroll
         for (int kw = 0; kw < kW; ++kw) {
             const int wv = wf[kh * kW + kw];
@@ -141,7 +153,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
                 const int t = j + pW - kw;              // uniform
                 if (t & smask) continue;
                 const int b = (t >> s_log2) - c_first;   // uniform byte index, 0..7
-                const int word = b < 4 ? v[0] : v[1];
+                const int word = (int)(b < 4 ? v[0] : v[1]);
                 acc[j] += __builtin_amdgcn_sbfe(word, 8 * (b & 3), 8) * wv;
             }
         }
@@ -245,11 +257,21 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dw(DwiseDwArgs p) {
         if (!live) gv = v4i{0, 0, 0, 0};
 #pragma unroll
         for (int t = 0; t < kDwTaps; ++t) {
-            const v4i_a1 xv = *reinterpret_cast<const v4i_a1*>(x + (p.off[t] + fc));
-            acc[t] = dot4(gv[0], xv[0], acc[t]);
-            acc[t] = dot4(gv[1], xv[1], acc[t]);
-            acc[t] = dot4(gv[2], xv[2], acc[t]);
-            acc[t] = dot4(gv[3], xv[3], acc[t]);
+            // A byte-aligned 16-byte load runs at half the rate of a dword-aligned one here: fetch the 20 bytes from
+            // the dword below the window and shift (the shift is the same for every thread: f is a multiple of 16).
+            const int64_t o = p.off[t] + fc;
+            const int8_t* src = x + (o & ~(int64_t)3);
+            const unsigned sh = (unsigned)(p.off[t] & 3);
+            const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(src);
+            const int hi = *reinterpret_cast<const int*>(src + 16);
+            const int w0 = (int)__builtin_amdgcn_alignbyte((unsigned)lo[1], (unsigned)lo[0], sh);
+            const int w1 = (int)__builtin_amdgcn_alignbyte((unsigned)lo[2], (unsigned)lo[1], sh);
+            const int w2 = (int)__builtin_amdgcn_alignbyte((unsigned)lo[3], (unsigned)lo[2], sh);
+            const int w3 = (int)__builtin_amdgcn_alignbyte((unsigned)hi, (unsigned)lo[3], sh);
+            acc[t] = dot4(gv[0], w0, acc[t]);
+            acc[t] = dot4(gv[1], w1, acc[t]);
+            acc[t] = dot4(gv[2], w2, acc[t]);
+            acc[t] = dot4(gv[3], w3, acc[t]);
         }
     }
 #pragma unroll
@@ -264,14 +286,19 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dw(DwiseDwArgs p) {
         p.part[((int64_t)c * p.slabs + slab) * kDwTaps + tid] = l_red[0][tid] + l_red[1][tid] + l_red[2][tid] + l_red[3][tid];
 }
 
+// One wave per filter element: its lanes take the slabs (independent loads, all in flight), then a shuffle tree.
 __global__ __launch_bounds__(kBlock) void k_dwise_dw_reduce(const int32_t* __restrict__ part, int C, int slabs, int T,
                                                             const float* s_x, const float* __restrict__ s_chan,
                                                             float* __restrict__ dW, int32_t* __restrict__ acc_out) {
-    const int i = blockIdx.x * kBlock + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    const int i = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;   // filter element (c, t)
     if (i >= C * T) return;
     const int c = i / T, t = i % T;
     int a = 0;
-    for (int s = 0; s < slabs; ++s) a += part[((int64_t)c * slabs + s) * kDwTaps + t];
+    for (int s = lane; s < slabs; s += kWave) a += part[((int64_t)c * slabs + s) * kDwTaps + t];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) a += __shfl_down(a, o);
+    if (lane != 0) return;
     dW[i] = (float)a * ((*s_x / 127.0f) * (s_chan[c] / 127.0f));
     if (acc_out) acc_out[i] = a;
 }
@@ -375,7 +402,7 @@ daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, c
     DAQ_LAUNCH("conv_bwd_filter_depthwise", st,
                hipLaunchKernelGGL(k_dwise_dw, dim3((unsigned)(d.Cout * a.slabs)), dim3(kBlock), 0, st, a));
     DAQ_LAUNCH("dw_reduce", st,
-               hipLaunchKernelGGL(k_dwise_dw_reduce, dim3((unsigned)ceil_div(d.Cout * a.T, kBlock)), dim3(kBlock), 0, st,
+               hipLaunchKernelGGL(k_dwise_dw_reduce, dim3((unsigned)ceil_div(d.Cout * a.T, kBlock / kWave)), dim3(kBlock), 0, st,
                                   a.part, d.Cout, a.slabs, a.T, s_x, s_chan, dW, acc));
     return DAQ_OK;
 }
