@@ -339,14 +339,19 @@ def main() -> int:
             n_s //= 2
         sub = wl.shrink(layer, n_s)
         rds = ref.ConvDesc(*sub.desc_fields())
-        t0 = time.perf_counter()
-        rq = ref.quantize_grad(dY[:n_s], st, want_fragile=False)
-        ref.conv_bwd_filter_int8(rds, qX[:n_s], s_x, rq.vq, rq.s_chan)
-        ref.conv_bwd_data_int8(rds, rq.qg, rq.s_global, qW, s_w)
-        cpu_s = time.perf_counter() - t0
+        # whole passes of the same step on the sample until about ten seconds of CPU work have been timed
+        passes, cpu_s = 0, 0.0
+        while cpu_s < 10.0 and passes < 64:
+            t0 = time.perf_counter()
+            rq = ref.quantize_grad(dY[:n_s], st, want_fragile=False)
+            ref.conv_bwd_filter_int8(rds, qX[:n_s], s_x, rq.vq, rq.s_chan)
+            ref.conv_bwd_data_int8(rds, rq.qg, rq.s_global, qW, s_w)
+            cpu_s += time.perf_counter() - t0
+            passes += 1
         result["cpu_baseline"] = {
-            "value": round(2.0 * 2.0 * sub.macs / cpu_s / 1e12, 6), "unit": "TOP/s", "cores": ref.num_threads(),
-            "kind": "oracle", "sample": f"same layer, first {n_s} of {layer.N} images, one pass ({cpu_s:.2f} s)"}
+            "value": round(passes * 2.0 * 2.0 * sub.macs / cpu_s / 1e12, 6), "unit": "TOP/s", "cores": ref.num_threads(),
+            "kind": "oracle",
+            "sample": f"same layer, first {n_s} of {layer.N} images, {passes} passes of the whole step ({cpu_s:.1f} s)"}
     print(json.dumps(result))
     return 0
 

@@ -29,6 +29,9 @@
  *     use the layouts described by daq_layout_* below; bytes of those buffers
  *     that hold no element are written as zero by the producing call and must
  *     stay zero.
+ *   - int8 buffers and the fp32 / int32 outputs of the data gradient and the forward pass must be
+ *     16-byte aligned, every other fp32 tensor 4-byte aligned (the wider paths are taken when it is
+ *     16-byte aligned); anything else is DAQ_ERR_INVALID_ARG.
  *   - Inputs are assumed finite (no NaN/Inf).
  */
 #ifndef DAQ_H

@@ -5,12 +5,17 @@ using namespace daq;
 
 namespace {
 bool ws_ok(const void* ws, size_t have, size_t need) { return ws && have >= need && ((uintptr_t)ws & 255u) == 0; }
+// int8 buffers are read and written as 16-byte vectors, fp32 tensors at least as dwords
+bool a16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+bool a4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
 }  // namespace
 
 extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
                                         int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y,
                                         int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !X || !W || !qx_nhwc || !qx_cnhw || !qw_packed || !s_x || !s_w || !Y)
+        return DAQ_ERR_INVALID_ARG;
+    if (!a4(X) || !a4(W) || !a16(qx_nhwc) || !a16(qx_cnhw) || !a16(qw_packed) || !a16(Y) || !a16(acc_out))
         return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_FWD, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
@@ -29,6 +34,7 @@ extern "C" daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const in
                                              const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
                                              void* workspace, size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !qg || !s_global || !qw_packed || !s_w || !dX) return DAQ_ERR_INVALID_ARG;
+    if (!a16(qg) || !a16(qw_packed) || !a16(dX) || !a16(acc_out)) return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
@@ -43,6 +49,7 @@ extern "C" daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const 
                                                const int8_t* vq, const float* s_chan, float* dW, int32_t* acc_out,
                                                void* workspace, size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !qx_cnhw || !s_x || !vq || !s_chan || !dW) return DAQ_ERR_INVALID_ARG;
+    if (!a16(qx_cnhw) || !a16(vq) || !a4(dW) || !a4(acc_out)) return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_FILTER, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;

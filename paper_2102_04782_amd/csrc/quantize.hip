@@ -868,6 +868,7 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
+    if (((uintptr_t)dY & 3u) || ((uintptr_t)vq & 15u) || ((uintptr_t)qg & 15u)) return DAQ_ERR_INVALID_ARG;
     daq_layout Lv, Lg;
     daq_status rc = daq_layout_vq(desc, &Lv);
     if (rc != DAQ_OK) return rc;

@@ -164,6 +164,11 @@ def test_workspace_and_validation_without_a_gpu():
     assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, None, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
     assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, one, None, None, 0, None) == daq.ERR_WORKSPACE
     assert lib.daq_conv_fwd_int8(C.byref(d), one, None, one, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    # misaligned int8 buffers
+    odd = C.c_void_p(257)
+    assert lib.daq_conv_bwd_data_int8(C.byref(d), odd, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, odd, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    assert lib.daq_quantize_grad(C.byref(d), one, one, 1.0, 0.8, 0.3, 0, 0, odd, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
     assert daq.status_string(daq.ERR_WORKSPACE).startswith("workspace")
 
 
