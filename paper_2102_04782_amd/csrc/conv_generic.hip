@@ -1,5 +1,6 @@
-// Direct int8 convolution kernels for descriptors the MFMA kernels do not cover (grouped layers,
-// unusual strides/dilations, channel counts that are not multiples of 16, depthwise layers).
+// Direct int8 convolution kernels for descriptors nothing else covers (grouped layers that are not
+// depthwise, filters with more taps than the matrix-core kernels take, depthwise filter gradients with
+// more than nine taps, the depthwise forward pass).
 // Plain integer ALU work: one thread (or one workgroup) per output element, int32 accumulation,
 // de-quantization in the epilogue.  Correct for every valid descriptor.
 #include "daq_internal.h"

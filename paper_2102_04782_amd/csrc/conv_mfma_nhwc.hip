@@ -1,5 +1,7 @@
 // Channel-contracting int8 implicit GEMM on the gfx950 matrix cores: the data gradient
-// q(G_X) = q(G) (.) q(W)  (Eq. "gx") and the forward convolution share it.
+// q(G_X) = q(G) (.) q(W)  (Eq. "gx") and the forward convolution share it.  This is the per-tap
+// re-staging form, which handles every stride; conv_mfma_halo.hip serves the layers its window
+// scheme covers (unit stride, stride-2 data gradients) and is preferred there.
 //
 // The pixel operand is NHWC (the contraction axis, channels, is innermost), the filter operand is
 // the packed [tap][row channel][contraction channel] copy.  The GEMM is computed transposed,

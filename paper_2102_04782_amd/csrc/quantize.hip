@@ -2,8 +2,9 @@
 // and the int8 packing kernels (Algorithm 1, per-channel loop and the two quantizations), plus
 // the per-tensor quantization of X and W used by the forward pass.
 //
-// All kernels here are bandwidth bound.  Float reductions use fixed trees and a fixed-order
-// second stage (no float atomics), so results do not depend on scheduling.  Compile with
+// All kernels here are meant to be bandwidth bound, which on this chip takes care with the instruction count too
+// (buffer loads instead of selects, 24-bit multiplies, one-instruction rounding).  Float reductions use fixed
+// trees and a fixed-order second stage (no float atomics), so results do not depend on scheduling.  Compile with
 // -ffp-contract=off: the rounding of every fp32/fp64 expression below is part of the contract.
 #include <algorithm>
 
