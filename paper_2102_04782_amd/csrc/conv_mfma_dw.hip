@@ -475,6 +475,12 @@ struct TapTable {
     int64_t off[kMaxTapSlots];   // byte offset of the tap's window start inside an activation channel
     int id[kMaxTapSlots];        // kh*kW + kw, or -1 for an unused slot
     int T;                       // kH * kW
+    // Row mode, for layers with very few input channels (an RGB stem): the rows of the activation operand are the
+    // (ci, kw) pairs, row ci*kW + kw reading channel ci at row_off[kw], and the "taps" are the kh alone (T = kH,
+    // id = kh).  3 x 7 rows fill 21 of 32 lanes where channel rows would fill 3 of 16, and a tap slot covers a whole
+    // filter row.  0 = off.
+    int row_kw;
+    int64_t row_off[8];
 };
 
 template <int TW, int NB, int PFD, bool WTAPS, int WAVES>
@@ -521,8 +527,16 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-        const int ci = ci0 + 16 * nb + li;
-        vb[nb] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * lg);
+        if (tt.row_kw) {   // uniform
+            const int R = 16 * nb + li, ci = R / tt.row_kw, kw = R - ci * tt.row_kw;
+            int64_t ro = tt.row_off[0];
+#pragma unroll
+            for (int q = 1; q < 8; ++q) ro = (kw == q) ? tt.row_off[q] : ro;
+            vb[nb] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + (ci < p.Cin ? ro : 0) + 16 * lg);
+        } else {
+            const int ci = ci0 + 16 * nb + li;
+            vb[nb] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * lg);
+        }
     }
     // wave-uniform tap offsets and ids; the table is indexed with constants only (a run-time index into a
     // by-value kernel argument would make the compiler copy it to scratch memory)
@@ -602,8 +616,14 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
                         part[(int64_t)((m * NB * T + nb * T + tap) * 4 + r) * kWave] = v;
                     } else {
                         const int co = co0 + 16 * m + 4 * lg + r;
-                        if (ci < p.Cin && co < p.Cout) {
-                            const int64_t off = ((int64_t)co * p.Cin + ci) * T + tap;
+                        int cin = ci;
+                        int64_t off = ((int64_t)co * p.Cin + ci) * T + tap;
+                        if (tt.row_kw) {   // row (ci, kw), tap kh
+                            const int R = 16 * nb + li;
+                            cin = R / tt.row_kw;
+                            off = (((int64_t)co * p.Cin + cin) * T + tap) * tt.row_kw + (R - cin * tt.row_kw);
+                        }
+                        if (cin < p.Cin && co < p.Cout) {
                             p.dW[off] = (float)v * (sx * (p.s_chan[co] / 127.0f));
                             if (p.acc_out) p.acc_out[off] = v;
                         }
@@ -656,7 +676,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
 // A workgroup owns 64 consecutive slots of the partial layout (one 256-byte run per split); its four
 // waves take every fourth split with eight loads in flight each and combine through LDS.
 __global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wgn,
-                                                   int nb_per_wave, int T, int Cout, int Cin, const float* s_x,
+                                                   int nb_per_wave, int T, int row_kw, int Cout, int Cin, const float* s_x,
                                                    const float* __restrict__ s_chan, float* __restrict__ dW,
                                                    int32_t* __restrict__ acc_out) {
     const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
@@ -687,9 +707,14 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ p
     const int nb = t_all / T, t = t_all % T;
     const int tm = tile / tiles_n, tn = tile % tiles_n;
     const int co = tm * kBM + 16 * m + 4 * (lane >> 4) + r;
-    const int ci = tn * (16 * nb_per_wave * wgn) + (wn * nb_per_wave + nb) * 16 + (lane & 15);
+    int ci = tn * (16 * nb_per_wave * wgn) + (wn * nb_per_wave + nb) * 16 + (lane & 15);
+    int64_t off = ((int64_t)co * Cin + ci) * T + t;
+    if (row_kw) {   // row mode of the tap-table kernel: the row is (ci, kw), the tap is kh
+        const int R = nb * 16 + (lane & 15);
+        ci = R / row_kw;
+        off = (((int64_t)co * Cin + ci) * T + t) * row_kw + (R - ci * row_kw);
+    }
     if (co >= Cout || ci >= Cin) return;
-    const int64_t off = ((int64_t)co * Cin + ci) * T + t;
     dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
     if (acc_out) acc_out[off] = a;
 }
@@ -699,6 +724,7 @@ struct Plan {
     bool general;         // tap-table kernel (any extent, stride, dilation)
     int tw;               // general: tap slots per wave
     bool wtaps;           // general: waves split the taps instead of K
+    int row_kw;           // general: kW when the activation rows are (ci, kw) pairs (few input channels), else 0
     int kh, wgk, nb, pf, splits, tiles_m, tiles_n, nchunks;
     size_t lds_bytes;
     int64_t part_slots;   // int32 slots of one split's worth of partial tiles
@@ -714,12 +740,14 @@ Plan make_general_plan(const daq_conv_desc& d) {
     pl.general = true;
     pl.kh = d.kH;
     pl.nchunks = (int)(Lg.plane_pitch / kKC);
-    if (T == 1) { pl.tw = 1; pl.nb = 4; pl.wtaps = false; pl.pf = 4; }
+    const bool rowmode = T > 9 && d.Cin * d.kW <= 32 && d.kH <= 8 && d.kW <= 8;
+    if (rowmode) { pl.row_kw = d.kW; pl.tw = 2; pl.nb = 2; pl.wtaps = true; pl.pf = 3; }   // taps = kh, two per wave
+    else if (T == 1) { pl.tw = 1; pl.nb = 4; pl.wtaps = false; pl.pf = 4; }
     else if (T <= 9) { pl.tw = 9; pl.nb = 1; pl.wtaps = false; pl.pf = 3; }
     else { pl.tw = 7; pl.nb = 1; pl.wtaps = true; pl.pf = 2; }   // 4 waves up to 28 taps, 8 waves beyond
     pl.wgk = pl.wtaps ? 1 : 4;
     pl.tiles_m = (int)ceil_div(d.Cout, kBM);
-    pl.tiles_n = (int)ceil_div(d.Cin, 16 * pl.nb);
+    pl.tiles_n = pl.row_kw ? 1 : (int)ceil_div(d.Cin, 16 * pl.nb);
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     const int64_t nsteps = (int64_t)pl.nchunks * (kKC / 64);
     int64_t s = ceil_div(512, tiles);
@@ -727,13 +755,14 @@ Plan make_general_plan(const daq_conv_desc& d) {
     if (s > max_by_steps) s = max_by_steps;
     // partial tiles are written and read once: keep that below ~2x the operand bytes
     const int64_t operand = (int64_t)d.Cout * Lg.plane_pitch + (int64_t)d.Cin * Lg.plane_pitch * d.strideH * d.strideW;
-    const int64_t tile_bytes = tiles * kBM * 16 * pl.nb * T * 4;
+    const int64_t Tp = pl.row_kw ? d.kH : T;   // tap slots of the partial layout
+    const int64_t tile_bytes = tiles * kBM * 16 * pl.nb * Tp * 4;
     const int64_t max_by_traffic = std::max<int64_t>(1, operand / tile_bytes);
     if (s > max_by_traffic) s = max_by_traffic;
     pl.splits = (int)std::max<int64_t>(1, s);
     pl.lds_bytes = pl.wtaps ? 256 : (size_t)12 * pl.nb * pl.tw * 4 * kWave * 4;
     if (pl.lds_bytes > 160 * 1024) return pl;
-    pl.part_slots = tiles * 16 * pl.nb * T * kWave;
+    pl.part_slots = tiles * 16 * pl.nb * Tp * kWave;
     pl.ok = true;
     return pl;
 }
@@ -840,6 +869,20 @@ TapTable make_tap_table(const daq_conv_desc& d, const daq_layout& Lx, const Plan
     TapTable tt{};
     tt.T = d.kH * d.kW;
     for (int j = 0; j < kMaxTapSlots; ++j) { tt.off[j] = 0; tt.id[j] = -1; }
+    tt.row_kw = pl.row_kw;
+    for (int q = 0; q < 8; ++q) tt.row_off[q] = 0;
+    if (pl.row_kw) {
+        // offset = [phase_h plane + row shift] (the tap, kh) + [phase_w plane + column shift] (the row's kw)
+        tt.T = d.kH;
+        for (int kh = 0; kh < d.kH; ++kh) {
+            tt.off[kh] = (int64_t)((kh * d.dilH) % Lx.phases_h) * Lx.phases_w * Lx.plane_pitch +
+                         (int64_t)(kh * d.dilH / Lx.phases_h) * Lx.row_pitch;
+            tt.id[kh] = kh;
+        }
+        for (int kw = 0; kw < d.kW; ++kw)
+            tt.row_off[kw] = (int64_t)((kw * d.dilW) % Lx.phases_w) * Lx.plane_pitch + (kw * d.dilW / Lx.phases_w);
+        return tt;
+    }
     for (int kh = 0; kh < d.kH; ++kh)
         for (int kw = 0; kw < d.kW; ++kw) {
             const int t = kh * d.kW + kw;
@@ -890,7 +933,8 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     const int wq4 = Lx.row_pitch & 3;
     if (pl.general) {
         const TapTable tt = make_tap_table(d, Lx, pl);
-        if (pl.tw == 1) rc = launch_dw_taps<1, 4, 4, false, 4>(pl, a, tt, st);
+        if (pl.row_kw) rc = launch_dw_taps<2, 2, 3, true, 4>(pl, a, tt, st);
+        else if (pl.tw == 1) rc = launch_dw_taps<1, 4, 4, false, 4>(pl, a, tt, st);
         else if (pl.tw == 9) rc = launch_dw_taps<9, 1, 3, false, 4>(pl, a, tt, st);
         else if (T <= 28) rc = launch_dw_taps<7, 1, 2, true, 4>(pl, a, tt, st);
         else rc = launch_dw_taps<7, 1, 2, true, 8>(pl, a, tt, st);
@@ -902,8 +946,8 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
         const int wgn = pl.general ? 1 : 4 / pl.wgk;
         DAQ_LAUNCH("dw_reduce", st,
                    hipLaunchKernelGGL(k_dw_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st,
-                                      a.part, pl.splits, pl.tiles_n, wgn, pl.nb, T, d.Cout, d.Cin, s_x, s_chan, dW,
-                                      acc));
+                                      a.part, pl.splits, pl.tiles_n, wgn, pl.nb, pl.row_kw ? d.kH : T, pl.row_kw, d.Cout, d.Cin,
+                                      s_x, s_chan, dW, acc));
     }
     return DAQ_OK;
 }
