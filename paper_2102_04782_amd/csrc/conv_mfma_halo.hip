@@ -50,6 +50,7 @@ struct HaloArgs {
     int tiles_h, tiles_w, groups;
     int units;            // 16-byte window units per thread
     int double_buffer;    // more than one contraction chunk: two window buffers
+    int zfill;            // stride 2, only parity class (0, 0) has taps: its workgroups also write the zeros of the other three
     // per parity class: live taps, window origin relative to the tile's first pixel
     int ph_taps[kMaxPhases], ph_org_h[kMaxPhases], ph_org_w[kMaxPhases];
     // 32-bit entries: a uniform index then costs a scalar load, not a vector-memory round trip
@@ -85,11 +86,11 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
     const int wr = wave % WR, wp = wave / WR;
     // block -> (row tile, parity class, image group, tile row, tile column)
     const int per_phase = p.groups * p.tiles_h * p.tiles_w;
-    const int ptiles = per_phase * ST * ST;
+    const int ptiles = per_phase * (p.zfill ? 1 : ST * ST);
     const int tr = (int)fdiv(blockIdx.x, p.div_ptiles);
     int tp = blockIdx.x - tr * ptiles;
     int phase = 0;
-    if (ST > 1) {
+    if (ST > 1 && !p.zfill) {
         phase = (tp >= per_phase) + (tp >= 2 * per_phase) + (tp >= 3 * per_phase);
         tp -= phase * per_phase;
     }
@@ -246,7 +247,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
         if (img >= p.NI || n >= p.N || h >= p.Hd || w >= p.Wd) continue;
         const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w;
         float* o = p.out + pix;
-        if (full_rows) {
+        if (ST == 2 && p.zfill && (p.Wd & 1) == 0) {
+            // written below together with the zeros of the 2 x 2 block
+        } else if (full_rows) {
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -270,6 +273,33 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
                     if (rowbase + dr < p.Crow) ao[dr * HWd] = acc[x][y][r];
                 }
         }
+        if (ST == 2 && p.zfill) {
+            // the three neighbours of this pixel in its 2 x 2 block receive no tap at all
+            const bool w1 = w + 1 < p.Wd, h1 = h + 1 < p.Hd;
+            const bool pairs = (p.Wd & 1) == 0;   // even rows: (value, 0) and (0, 0) go out as aligned 8-byte stores
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr >= p.Crow) continue;
+                    float* z = o + (int64_t)dr * HWd;
+                    if (pairs) {
+                        *reinterpret_cast<float2*>(z) = make_float2((float)acc[x][y][r] * scale, 0.0f);
+                        if (h1) *reinterpret_cast<float2*>(z + p.Wd) = make_float2(0.0f, 0.0f);
+                    } else {
+                        if (w1) z[1] = 0.0f;
+                        if (h1) z[p.Wd] = 0.0f;
+                        if (h1 && w1) z[p.Wd + 1] = 0.0f;
+                    }
+                    if (p.acc_out) {
+                        int32_t* za = p.acc_out + pix + (int64_t)dr * HWd;
+                        if (w1) za[1] = 0;
+                        if (h1) za[p.Wd] = 0;
+                        if (h1 && w1) za[p.Wd + 1] = 0;
+                    }
+                }
+        }
     }
 }
 
@@ -290,7 +320,10 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     Geometry g{};
     HaloArgs& a = g.a;
     if (sH != sW || (sH != 1 && !(sH == 2 && backward)) || kH * kW > kMaxTaps) return g;
-    if (kH * kW == 1 && sH != 1) return g;   // strided 1x1: three of four parity classes are empty, measured slower here
+    // strided 1x1: three of four parity classes are empty; served when the live one is class (0, 0) (no padding),
+    // whose workgroups then write the zeros of the other three next to their own results
+    if (kH * kW == 1 && sH != 1 && (pH != 0 || pW != 0)) return g;
+    a.zfill = (kH * kW == 1 && sH == 2) ? 1 : 0;
     const int s = sH;
     a.stride = s;
     a.T = kH * kW;
@@ -369,7 +402,7 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     g.lds_bytes = (size_t)(a.double_buffer ? 2 : 1) * S * kPitch;
     if (g.lds_bytes > 150 * 1024) return g;
     // 128-row tiles reuse each pixel fragment twice as often, but only pay off when they still fill the chip
-    const int64_t blocks128 = (int64_t)a.groups * a.tiles_h * a.tiles_w * s * s * ceil_div(Crow, 128);
+    const int64_t blocks128 = (int64_t)a.groups * a.tiles_h * a.tiles_w * (a.zfill ? 1 : s * s) * ceil_div(Crow, 128);
     g.rows = (Crow > 64 && blocks128 >= 256) ? 128 : 64;
     a.div_tw = make_fastdiv((uint32_t)a.TW);
     a.div_thw = make_fastdiv((uint32_t)(a.TH * a.TW));
@@ -377,8 +410,9 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     a.div_si = make_fastdiv((uint32_t)(a.SH * a.SW));
     a.div_tiles_w = make_fastdiv((uint32_t)a.tiles_w);
     a.div_tiles_hw = make_fastdiv((uint32_t)(a.tiles_h * a.tiles_w));
-    a.div_ptiles = make_fastdiv((uint32_t)(a.groups * a.tiles_h * a.tiles_w * s * s));
-    const int64_t blocks = (int64_t)a.groups * a.tiles_h * a.tiles_w * s * s * ceil_div(Crow, g.rows);
+    const int classes = a.zfill ? 1 : s * s;
+    a.div_ptiles = make_fastdiv((uint32_t)(a.groups * a.tiles_h * a.tiles_w * classes));
+    const int64_t blocks = (int64_t)a.groups * a.tiles_h * a.tiles_w * classes * ceil_div(Crow, g.rows);
     if (blocks >= ((int64_t)1 << 31)) return g;
     g.ok = true;
     return g;
@@ -386,7 +420,7 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
 
 daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     const HaloArgs& a = g.a;
-    const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * a.stride * a.stride;
+    const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * (a.zfill ? 1 : a.stride * a.stride);
     const dim3 grid((unsigned)(ptiles * ceil_div(a.Crow, g.rows)));
 #define DAQ_HALO_CASE(WRV, DBV, WV)                                                                                  \
     {                                                                                                                \
