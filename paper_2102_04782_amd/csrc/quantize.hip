@@ -45,7 +45,9 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     QuantWs w{};
     char* p = (char*)base;
     const int64_t M = (int64_t)N * HW;
-    w.chunks = (int)ceil_div(M, kStatsElems);
+    // statistics sweep groups of four elements per plane (k_stats): the axis is padded to whole groups
+    const int64_t Mstats = HW >= 4 ? (int64_t)N * ((HW + 3) / 4) * 4 : M;
+    w.chunks = (int)ceil_div(Mstats, kStatsElems);
     const int iters = (int)ceil_div(w.chunks, kMaxSlabs);
     w.slabs = (int)ceil_div(w.chunks, iters);
     w.tiles = (int)ceil_div(M, kWave);
@@ -171,7 +173,8 @@ __device__ __forceinline__ void block_reduce(float& mx, double& s1, double& s2) 
 // the kernels that need mean and sigma fold them again themselves (fold_stats) in a fixed order
 // instead of waiting for a reduction launch.  Channel c runs on XCD c % 8 in every pass over dY.
 // ---------------------------------------------------------------------------------------------
-template <bool VEC4>
+// TAIL: the plane size is not a multiple of four (the last group of a plane needs the move-back and the mask).
+template <bool VEC4, bool TAIL>
 __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, FastDiv div_hw,
                                                   QuantWs ws) {
     constexpr int NV = VEC4 ? 4 : 16;
@@ -183,19 +186,38 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
     const int M = N * HW;
     const int tid = threadIdx.x;
 
+    // VEC4: a thread takes groups of four consecutive elements of one (image, channel) plane, any plane size >= 4:
+    // planes are cut into ceil(HW/4) groups and the last group of a plane is moved back to end with the plane (its
+    // leading elements, already covered by the group before, are zeroed), so every load is a dword-aligned 16-byte
+    // load inside the plane.  The flattened axis of a channel is then N * ceil(HW/4) * 4 element slots long.
+    const int G4 = (HW + 3) >> 2;
     uint4 v[NV];   // VEC4: four floats each; otherwise only .x is used
     auto fetch = [&](int chunk, uint4 (&dst)[NV]) {
         const bool live = chunk < ws.chunks;
         const int m0 = chunk * kStatsElems;
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int m = VEC4 ? m0 + 4 * (tid + u * kBlock) : m0 + tid + u * kBlock;
-            const bool ok = live && m < M;
-            const int mc = ok ? m : 0;
-            const int n = (int)fdiv((uint32_t)mc, div_hw), i = mc - n * HW;
-            const float* src = g + ((int64_t)n * C + c) * HW + i;
-            if (VEC4) dst[u] = ld16_or_zero(src, ok);
-            else dst[u].x = __float_as_uint(ldf_or_zero(src, ok));
+            if (VEC4) {
+                const int q4 = (m0 >> 2) + tid + u * kBlock;            // group index inside the channel
+                const bool ok = live && q4 < N * G4;
+                const int qc = ok ? q4 : 0;
+                const int n = (int)fdiv((uint32_t)qc, div_hw), gi = qc - n * G4;   // div_hw divides by G4 here
+                const int i = TAIL ? min(4 * gi, HW - 4) : 4 * gi;
+                uint4 r = ld16_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
+                if (TAIL) {
+                    const int skip = 4 * gi - i;   // > 0 only in a plane's last group
+                    r.x = skip > 0 ? 0u : r.x;
+                    r.y = skip > 1 ? 0u : r.y;
+                    r.z = skip > 2 ? 0u : r.z;
+                }
+                dst[u] = r;
+            } else {
+                const int m = m0 + tid + u * kBlock;
+                const bool ok = live && m < M;
+                const int mc = ok ? m : 0;
+                const int n = (int)fdiv((uint32_t)mc, div_hw), i = mc - n * HW;
+                dst[u].x = __float_as_uint(ldf_or_zero(g + ((int64_t)n * C + c) * HW + i, ok));
+            }
         }
     };
     float mx = 0.0f;
@@ -890,12 +912,15 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
 
     // S1: statistics partials, at most 16 per channel
     const FastDiv div_hw = make_fastdiv((uint32_t)HW);
-    const bool vec4 = (HW % 4 == 0) && (((uintptr_t)dY & 15u) == 0);
+    const bool vec4 = HW >= 4;   // dword-aligned 16-byte loads run at full rate; only tiny planes take the scalar path
     const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.slabs);
-    if (vec4)
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
+    const FastDiv div_g4 = make_fastdiv((uint32_t)((HW + 3) / 4));
+    if (vec4 && HW % 4 == 0)
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
+    else if (vec4)
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true, true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
     else
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
 
     // S2 (+ the NHWC global copy); folds the statistics itself
     const int CB = (int)ceil_div(C, 64);
