@@ -72,7 +72,11 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // 64 x 64 wave tiles on eight waves - two per SIMD, so that the LDS reads of one overlap the multiplies of the other.
 // DB = the contraction axis has more than one 64-byte chunk (two window buffers, restaged per chunk).
 // ST = stride (1 or 2): with one parity class its tables are indexed with constants.
-template <int WR, bool DB, int ST, int WAVES>
+// TAPS > 0 (unit stride only): the number of filter taps is this constant.  The loop over the taps of a chunk is
+// then unrolled, the ring of filter tiles has one slot per tap (slot = tap, so each tile is requested TAPS - 1
+// steps before its use), the tap tables are read once, and the pixel fragments of the next tap are read from LDS
+// before the multiplies of the current one: with a single wave per SIMD nothing else hides those latencies.
+template <int WR, bool DB, int ST, int WAVES, int TAPS = 0>
 __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = WAVES / WR;
@@ -187,45 +191,102 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
 
-    if (NS > 0) {
+    if constexpr (TAPS > 0) {
+        // tap tables: loop invariant, indexed with constants after unrolling
+        int t_id[TAPS], t_off[TAPS];
+#pragma unroll
+        for (int t = 0; t < TAPS; ++t) {
+            t_id[t] = p.tap_id[0][t];
+            t_off[t] = p.tap_slot[0][t] * kPitch;
+        }
+        int bbyte[BF];
+#pragma unroll
+        for (int y = 0; y < BF; ++y) bbyte[y] = bslot[y] * kPitch + 16 * lh;
+        v4i rt[TAPS][2][2];   // [tap][x][sub]
+        auto fetch_t = [&](int t, int kc) {
+            const uint32_t base = kc < nkc ? (uint32_t)(((kc * p.T + t_id[t]) * p.RB) * 2048) : kOob;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) rt[t][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+        };
+        v4i bq[2][2][BF];     // [set][sub][y]
+        auto read_b = [&](int set, int buf, int t) {
+            const int8_t* H = lds + (DB ? buf * halo_bytes : 0) + t_off[t];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int y = 0; y < BF; ++y)
+                    bq[set][sub][y] = *reinterpret_cast<const v4i*>(H + bbyte[y] + 32 * sub);
+        };
         fetch_halo(0);
 #pragma unroll
-        for (int d = 0; d < kRingA - 1; ++d) fetch_a(d);
+        for (int t = 0; t < TAPS - 1; ++t) fetch_t(t, 0);
         stage_halo(0);
         __syncthreads();
-    }
-
-    // flat loop over steps (chunk outer, live tap inner), unrolled by the ring depth so that ring slots are constants
-    int j = 0, kci = 0;
-    for (int base = 0; base < NS; base += kRingA) {
+        read_b(0, 0, 0);
+        for (int kc = 0; kc < nkc; ++kc) {
+            if (DB && kc + 1 < nkc) fetch_halo(kc + 1);
 #pragma unroll
-        for (int u = 0; u < kRingA; ++u) {
-            if (base + u < NS) {   // uniform
-                fetch_a((u + kRingA - 1) % kRingA);                          // filter tiles of step s + kRingA - 1
-                if (DB && j == 0 && kci + 1 < nkc) fetch_halo(kci + 1);      // uniform; staged at the chunk's last tap
-                const int8_t* H = lds + (DB ? (kci & 1) * halo_bytes : 0) + 16 * lh;
-                const int ts = p.tap_slot[phase][j];
+            for (int t = 0; t < TAPS; ++t) {
+                // the tile of the step TAPS - 1 ahead: the previous tap's slot, of the next chunk unless t == 0
+                fetch_t((t + TAPS - 1) % TAPS, t == 0 ? kc : kc + 1);
+                if (t + 1 < TAPS) read_b((t + 1) & 1, kc & 1, t + 1);
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) {
-                    v4i b[BF];
-#pragma unroll
-                    for (int y = 0; y < BF; ++y)
-                        b[y] = *reinterpret_cast<const v4i*>(H + (bslot[y] + ts) * kPitch + 32 * sub);
+                for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
                     for (int x = 0; x < 2; ++x)
 #pragma unroll
                         for (int y = 0; y < BF; ++y)
-                            acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
-                }
-                if (j + 1 == taps) {
-                    if (DB && kci + 1 < nkc) {
-                        stage_halo((kci + 1) & 1);
-                        __syncthreads();
+                            acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(rt[t][x][sub], bq[t & 1][sub][y], acc[x][y], 0, 0, 0);
+            }
+            if (DB && kc + 1 < nkc) {
+                stage_halo((kc + 1) & 1);
+                __syncthreads();
+                read_b(0, (kc + 1) & 1, 0);
+            }
+        }
+    } else {
+        if (NS > 0) {
+            fetch_halo(0);
+    #pragma unroll
+            for (int d = 0; d < kRingA - 1; ++d) fetch_a(d);
+            stage_halo(0);
+            __syncthreads();
+        }
+
+        // flat loop over steps (chunk outer, live tap inner), unrolled by the ring depth so that ring slots are constants
+        int j = 0, kci = 0;
+        for (int base = 0; base < NS; base += kRingA) {
+    #pragma unroll
+            for (int u = 0; u < kRingA; ++u) {
+                if (base + u < NS) {   // uniform
+                    fetch_a((u + kRingA - 1) % kRingA);                          // filter tiles of step s + kRingA - 1
+                    if (DB && j == 0 && kci + 1 < nkc) fetch_halo(kci + 1);      // uniform; staged at the chunk's last tap
+                    const int8_t* H = lds + (DB ? (kci & 1) * halo_bytes : 0) + 16 * lh;
+                    const int ts = p.tap_slot[phase][j];
+    #pragma unroll
+                    for (int sub = 0; sub < 2; ++sub) {
+                        v4i b[BF];
+    #pragma unroll
+                        for (int y = 0; y < BF; ++y)
+                            b[y] = *reinterpret_cast<const v4i*>(H + (bslot[y] + ts) * kPitch + 32 * sub);
+    #pragma unroll
+                        for (int x = 0; x < 2; ++x)
+    #pragma unroll
+                            for (int y = 0; y < BF; ++y)
+                                acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
                     }
-                    j = 0;
-                    ++kci;
-                } else {
-                    ++j;
+                    if (j + 1 == taps) {
+                        if (DB && kci + 1 < nkc) {
+                            stage_halo((kci + 1) & 1);
+                            __syncthreads();
+                        }
+                        j = 0;
+                        ++kci;
+                    } else {
+                        ++j;
+                    }
                 }
             }
         }
@@ -429,6 +490,16 @@ daq_status launch(Geometry& g, hipStream_t st, const char* name) {
             hipSuccess)                                                                                              \
             return DAQ_ERR_HIP;                                                                                      \
         DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(64 * WV), g.lds_bytes, st, a));                     \
+    }
+    // Layers with several contraction chunks and 3 x 3 filters at unit stride, on 64-row tiles: the form with a
+    // constant tap count.  (With a single chunk the kernel is all prologue and epilogue, and the dynamic form, which
+    // needs fewer registers, lets more workgroups overlap theirs; 128-row tiles stay on the eight-wave form.)
+    if (a.stride == 1 && a.ph_taps[0] == 9 && a.double_buffer && g.rows == 64) {
+        auto kern = k_conv_halo<1, true, 1, 4, 9>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
+            return DAQ_ERR_HIP;
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
+        return DAQ_OK;
     }
     if (g.rows == 128) {
         HaloArgs a8 = g.a;   // eight waves stage the window in half as many passes
