@@ -65,11 +65,15 @@ def sweep(args, dev) -> int:
             dX = torch.empty(d.x_shape, device=dev)
             ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
             ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
+            ws_b = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD, d)), dtype=torch.uint8, device=dev)
 
             def step():
                 q = daq.quantize_grad(d, dY, st, out=out)
-                daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
-                daq.conv_bwd_data_int8(d, q.qg, q.s_global, qw, one, dX=dX, workspace=ws_d)
+                if args.separate:
+                    daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
+                    daq.conv_bwd_data_int8(d, q.qg, q.s_global, qw, one, dX=dX, workspace=ws_d)
+                else:
+                    daq.conv_bwd_int8(d, qx, one, q.vq, q.s_chan, q.qg, q.s_global, qw, one, dW=dW, dX=dX, workspace=ws_b)
 
             for _ in range(3):
                 step()
@@ -90,7 +94,7 @@ def sweep(args, dev) -> int:
                          sum(v for k, v in t.items() if k in ("stats", "count_qg", "pack_vq", "pack_qg")),
                          sum(v for k, v in t.items() if k.startswith("conv_bwd_filter") or k == "dw_reduce"),
                          sum(v for k, v in t.items() if k.startswith("conv_bwd_data")))
-            del dY, qx, qw, out, dW, dX, ws_f, ws_d
+            del dY, qx, qw, out, dW, dX, ws_f, ws_d, ws_b
         wall_us, q_us, dw_us, dx_us = seen[key]
         tot_wall += wall_us
         tot_ops += 4.0 * L.macs
@@ -125,6 +129,9 @@ def main() -> int:
     ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
                     help="2: the two convolutions, which are independent once dY is quantized, run on two streams "
                          "(measured slower than one stream on this workload: the event waits cost more than the overlap gains)")
+    ap.add_argument("--separate", action="store_true",
+                    help="call daq_conv_bwd_filter_int8 and daq_conv_bwd_data_int8 one after the other instead of "
+                         "daq_conv_bwd_int8 (both gradients in one call, one launch fewer)")
     ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
                     help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--sweep", action="store_true",
@@ -166,15 +173,21 @@ def main() -> int:
     dXs = [torch.empty(d.x_shape, dtype=torch.float32, device=dev) for _ in range(R)]
     ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
     ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD, d)), dtype=torch.uint8, device=dev)
+    combined = not args.separate and args.streams == 1
     main_s = torch.cuda.Stream()
     side_s = torch.cuda.Stream() if args.streams == 2 else None
 
     def step(i: int, fork: bool = True):
         # Algorithm 1 for one layer.  dW needs the per-channel copy, dX the global copy: after the quantizer
-        # the two convolutions share no data, so with two streams they overlap.
+        # the two convolutions share no data.  fork=False is the plain reference schedule: the three entry points
+        # one after the other on one stream.
         r = i % R
         q = daq.quantize_grad(d, dYs[r], states[r], out=outs[r], stream=main_s)
-        if side_s is not None and fork:
+        if combined and fork:
+            daq.conv_bwd_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, q.qg, q.s_global, fwd.qw, fwd.s_w,
+                              dW=dWs[r], dX=dXs[r], workspace=ws_b, stream=main_s)
+        elif side_s is not None and fork:
             side_s.wait_stream(main_s)
             daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=side_s)
             daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=main_s)
@@ -230,10 +243,10 @@ def main() -> int:
         print("bench.py: the timed schedule does not reproduce the single-stream result", file=sys.stderr)
         return 3
 
-    # per-kernel durations: K single-stream steps with a HIP event pair around every launch
+    # per-kernel durations: K steps of the timed schedule on one stream with a HIP event pair around every launch
     daq.prof_begin()
     for i in range(args.steps):
-        step(i, fork=False)
+        step(i, fork=combined)
     rows = daq.prof_end()
     torch.cuda.synchronize()
 
@@ -317,7 +330,9 @@ def main() -> int:
         "config": {"workload": f"config{args.config}:{layer.name} N={layer.N} {layer.Cin}->{layer.Cout} "
                                f"{layer.Hin}x{layer.Win} k{layer.kH} s{layer.stride} p{layer.pad}",
                    "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3,
-                   "streams": args.streams, "hip_graph": bool(args.graph)},
+                   "streams": args.streams, "hip_graph": bool(args.graph),
+                   "calls": "daq_quantize_grad + daq_conv_bwd_int8" if combined else
+                            "daq_quantize_grad + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8"},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "quant_GBps_effective_6B": round(6.0 * E_Y / (quant_us * 1e-6) / 1e9, 1) if quant_us else None,
         "quant_us": round(quant_us, 2),

@@ -70,7 +70,10 @@ typedef enum { DAQ_ROUND_NEAREST = 0, DAQ_ROUND_STOCHASTIC = 1 } daq_round;
 /* Channel classes of the gradient discriminator, Eq. "judge". */
 enum { DAQ_CLASS_GAUSS = 0, DAQ_CLASS_INVT = 1 };
 
-typedef enum { DAQ_OP_QUANTIZE_GRAD = 0, DAQ_OP_CONV_FWD = 1, DAQ_OP_CONV_BWD_DATA = 2, DAQ_OP_CONV_BWD_FILTER = 3 } daq_op;
+typedef enum {
+    DAQ_OP_QUANTIZE_GRAD = 0, DAQ_OP_CONV_FWD = 1, DAQ_OP_CONV_BWD_DATA = 2, DAQ_OP_CONV_BWD_FILTER = 3,
+    DAQ_OP_CONV_BWD = 4 /* both gradients in one call */
+} daq_op;
 
 /* ---------------------------------------------------------------------------------------------
  * int8 tensor layouts
@@ -220,6 +223,23 @@ daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const int8_t* qg, c
 daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
                                     const int8_t* vq, const float* s_chan, float* dW, int32_t* acc_out,
                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_conv_bwd_int8 -- the last two steps of Algorithm 1 (Eq. "gw" with the vectorized
+ * de-quantization and Eq. "gx" with the global one) in one call: the same arguments, the same
+ * arithmetic and the same results, bit for bit, as daq_conv_bwd_filter_int8 followed by
+ * daq_conv_bwd_data_int8.  The two gradients do not depend on each other, which the library uses to
+ * save a launch: where the filter gradient splits its contraction axis across workgroups, the sum
+ * of the partial tiles and the de-quantization are done by extra workgroups of the data-gradient
+ * kernel instead of a launch of their own.
+ *
+ *   arguments as in the two calls above; dW_acc / dX_acc are their optional acc_out
+ *   workspace: daq_workspace_bytes(DAQ_OP_CONV_BWD, desc)
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_bwd_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x, const int8_t* vq,
+                             const float* s_chan, float* dW, int32_t* dW_acc, const int8_t* qg, const float* s_global,
+                             const int8_t* qw_packed, const float* s_w, float* dX, int32_t* dX_acc, void* workspace,
+                             size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every

@@ -20,13 +20,13 @@ LIB_PATH = os.path.join(_HERE, "libdaq.so")
 OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(5)
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 CLASS_GAUSS, CLASS_INVT = 0, 1
-OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER = range(4)
+OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER, OP_CONV_BWD = range(5)
 LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_prof_begin", "daq_prof_end", "daq_status_string",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_prof_begin", "daq_prof_end", "daq_status_string",
 ]
 
 
@@ -173,6 +173,7 @@ def lib():
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
+        L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
@@ -321,6 +322,25 @@ def conv_bwd_filter_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, 
                                         _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "daq_conv_bwd_filter_int8")
     return dW
+
+
+def conv_bwd_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, vq: torch.Tensor, s_chan: torch.Tensor,
+                  qg: torch.Tensor, s_global: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,
+                  dW: Optional[torch.Tensor] = None, dX: Optional[torch.Tensor] = None,
+                  dW_acc: Optional[torch.Tensor] = None, dX_acc: Optional[torch.Tensor] = None,
+                  workspace: Optional[torch.Tensor] = None, stream=None):
+    """Both gradients of a layer in one call; returns (dW, dX)."""
+    if dW is None:
+        dW = torch.empty(d.w_shape, dtype=torch.float32, device=vq.device)
+    if dX is None:
+        dX = torch.empty(d.x_shape, dtype=torch.float32, device=qg.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD, d), vq.device)
+    rc = lib().daq_conv_bwd_int8(C.byref(d), _ptr(qx_cnhw), _ptr(s_x), _ptr(vq), _ptr(s_chan), _ptr(dW), _ptr(dW_acc),
+                                 _ptr(qg), _ptr(s_global), _ptr(qw), _ptr(s_w), _ptr(dX), _ptr(dX_acc),
+                                 _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_int8")
+    return dW, dX
 
 
 # ------------------------------------------------------------------------------------------------

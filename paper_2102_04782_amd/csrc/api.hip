@@ -1,5 +1,6 @@
 // Entry points of the three convolutions: argument validation and kernel selection.
 #include "daq_internal.h"
+#include "dw_tail.h"
 
 using namespace daq;
 
@@ -61,4 +62,30 @@ extern "C" daq_status daq_conv_bwd_filter_int8(const daq_conv_desc* desc, const 
     if (depthwise_dw_supported(*desc))
         return conv_bwd_filter_depthwise(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, workspace, st);
     return conv_bwd_filter_generic(*desc, qx_cnhw, s_x, vq, s_chan, dW, acc_out, st);
+}
+
+extern "C" daq_status daq_conv_bwd_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
+                                        const int8_t* vq, const float* s_chan, float* dW, int32_t* dW_acc,
+                                        const int8_t* qg, const float* s_global, const int8_t* qw_packed,
+                                        const float* s_w, float* dX, int32_t* dX_acc, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !qx_cnhw || !s_x || !vq || !s_chan || !dW || !qg || !s_global || !qw_packed || !s_w || !dX)
+        return DAQ_ERR_INVALID_ARG;
+    if (!a16(qx_cnhw) || !a16(vq) || !a4(dW) || !a4(dW_acc) || !a16(qg) || !a16(qw_packed) || !a16(dX) || !a16(dX_acc))
+        return DAQ_ERR_INVALID_ARG;
+    const size_t need_f = daq_workspace_bytes(DAQ_OP_CONV_BWD_FILTER, desc);
+    const size_t need_d = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
+    if (need_f == 0 || need_d == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need_f + need_d)) return DAQ_ERR_WORKSPACE;
+    void* ws_d = static_cast<char*>(workspace) + need_f;   // need_f is a multiple of 256
+    if (bwd_filter_lds_supported(*desc) && bwd_data_halo_supported(*desc)) {
+        hipStream_t st = (hipStream_t)stream;
+        DwTail tail{};
+        const daq_status rc = conv_bwd_filter_lds(*desc, qx_cnhw, s_x, vq, s_chan, dW, dW_acc, workspace, st, &tail);
+        if (rc != DAQ_OK) return rc;
+        return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, dX, dX_acc, st, tail.blocks > 0 ? &tail : nullptr);
+    }
+    const daq_status rc = daq_conv_bwd_filter_int8(desc, qx_cnhw, s_x, vq, s_chan, dW, dW_acc, workspace, need_f, stream);
+    if (rc != DAQ_OK) return rc;
+    return daq_conv_bwd_data_int8(desc, qg, s_global, qw_packed, s_w, dX, dX_acc, ws_d, need_d, stream);
 }

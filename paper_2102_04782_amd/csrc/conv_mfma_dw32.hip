@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "daq_internal.h"
+#include "dw_tail.h"
 
 namespace daq {
 
@@ -645,7 +646,8 @@ size_t bwd_filter_lds_ws_bytes(const daq_conv_desc& d) {
 }
 
 daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st) {
+                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, DwTail* defer) {
+    if (defer) defer->blocks = 0;
     const Plan32 pl = make_plan32(d);
     if (!pl.ok) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lx, Lg;
@@ -683,7 +685,9 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
         }
-        if (pl.splits > 1)
+        if (pl.splits > 1 && defer)
+            *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
+        else if (pl.splits > 1)
             DAQ_LAUNCH("dw_reduce", st,
                        hipLaunchKernelGGL(k_dw11_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st, a.part,
                                           pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, s_x, s_chan, dW, acc));
@@ -691,7 +695,9 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     }
     const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
-    if (pl.splits > 1) {
+    if (pl.splits > 1 && defer) {
+        *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
+    } else if (pl.splits > 1) {
         const unsigned blocks = (unsigned)(pl.part_slots / kWave);
         DAQ_LAUNCH("dw_reduce", st,
                    hipLaunchKernelGGL(k_dw32_reduce, dim3(blocks), dim3(256), 0, st, a.part, pl.splits, pl.tiles_n, pl.wm,

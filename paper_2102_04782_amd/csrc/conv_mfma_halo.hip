@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "daq_internal.h"
+#include "dw_tail.h"
 
 namespace daq {
 
@@ -61,6 +62,8 @@ struct HaloArgs {
     const float* s_b;
     float* out;           // fp32 [N][Crow][Hd][Wd]
     int32_t* acc_out;
+    DwTail tail;          // tail.blocks > 0: that many workgroups behind the first main_blocks finish a deferred filter
+    int main_blocks;      // gradient instead (they are dispatched last and fill the slots this kernel's own tiles leave)
 };
 
 __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
@@ -85,14 +88,19 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
     constexpr int BF = PXW / 32;
     extern __shared__ __align__(16) int8_t lds[];   // one or two window buffers of S slots
 
+    if (p.tail.blocks > 0 && (int)blockIdx.x >= p.main_blocks) {   // uniform
+        dw_reduce_role(p.tail, (int)blockIdx.x - p.main_blocks, reinterpret_cast<int32_t*>(lds));
+        return;
+    }
+    const uint32_t bid = blockIdx.x;
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int l32 = lane & 31, lh = lane >> 5;
     const int wr = wave % WR, wp = wave / WR;
     // block -> (row tile, parity class, image group, tile row, tile column)
     const int per_phase = p.groups * p.tiles_h * p.tiles_w;
     const int ptiles = per_phase * (p.zfill ? 1 : ST * ST);
-    const int tr = (int)fdiv(blockIdx.x, p.div_ptiles);
-    int tp = blockIdx.x - tr * ptiles;
+    const int tr = (int)fdiv(bid, p.div_ptiles);
+    int tp = (int)bid - tr * ptiles;
     int phase = 0;
     if (ST > 1 && !p.zfill) {
         phase = (tp >= per_phase) + (tp >= 2 * per_phase) + (tp >= 3 * per_phase);
@@ -482,7 +490,11 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
 daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     const HaloArgs& a = g.a;
     const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * (a.zfill ? 1 : a.stride * a.stride);
-    const dim3 grid((unsigned)(ptiles * ceil_div(a.Crow, g.rows)));
+    const int64_t blocks = ptiles * ceil_div(a.Crow, g.rows) + a.tail.blocks;
+    if (blocks >= ((int64_t)1 << 31)) return DAQ_ERR_UNSUPPORTED;
+    g.a.main_blocks = (int)(blocks - a.tail.blocks);
+    if (a.tail.blocks > 0) g.lds_bytes = std::max<size_t>(g.lds_bytes, 8 * kWave * sizeof(int32_t));   // the role's scratch
+    const dim3 grid((unsigned)blocks);
 #define DAQ_HALO_CASE(WRV, DBV, WV)                                                                                  \
     {                                                                                                                \
         auto kern = a.stride == 2 ? k_conv_halo<WRV, DBV, 2, WV> : k_conv_halo<WRV, DBV, 1, WV>;                     \
@@ -544,8 +556,9 @@ Geometry plan_fwd(const daq_conv_desc& d) {
 bool bwd_data_halo_supported(const daq_conv_desc& d) { return plan_bwd(d).ok; }
 
 daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail) {
     Geometry g = plan_bwd(d);
+    if (tail) g.a.tail = *tail;
     daq_wpack_layout Lw;
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     g.a.src = qg;

@@ -129,13 +129,18 @@ daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx_nhwc, const in
 // conv_mfma_dw32.hip: 3 x 3 unit-stride filter gradient on the 32x32x32 MFMA, operands staged through LDS
 bool bwd_filter_lds_supported(const daq_conv_desc& d);
 size_t bwd_filter_lds_ws_bytes(const daq_conv_desc& d);
+// With `defer`, a K-split launch leaves its last stage (sum of the partial tiles, de-quantization) undone and
+// describes it in *defer (blocks == 0: nothing is left) for a later kernel's extra workgroups, see dw_tail.h.
+struct DwTail;
 daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st);
+                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st,
+                               DwTail* defer = nullptr);
 
 // conv_mfma_halo.hip: halo-tile form of the channel-contracting kernel (unit stride; stride 2 for the data gradient)
 bool bwd_data_halo_supported(const daq_conv_desc& d);
+// With `tail` (blocks > 0), extra workgroups of the launch finish a deferred filter gradient.
 daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail = nullptr);
 bool fwd_halo_supported(const daq_conv_desc& d);
 daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st);

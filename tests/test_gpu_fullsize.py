@@ -56,9 +56,13 @@ def test_sampled_outputs_at_full_size(config, index):
     q = daq.quantize_grad(d, G.float(), state, k=1.0, A=1.0)
     accW = torch.empty(d.w_shape, dtype=torch.int32, device=device)
     accX = torch.empty(d.x_shape, dtype=torch.int32, device=device)
-    dW = daq.conv_bwd_filter_int8(d, f.qx_cnhw, f.s_x, q.vq, q.s_chan, acc=accW)
-    dX = daq.conv_bwd_data_int8(d, q.qg, q.s_global, f.qw, f.s_w, acc=accX)
+    # the call the benchmark times: both gradients at once
+    dW, dX = daq.conv_bwd_int8(d, f.qx_cnhw, f.s_x, q.vq, q.s_chan, q.qg, q.s_global, f.qw, f.s_w, dW_acc=accW, dX_acc=accX)
+    # ... and the two separate entry points must give the same bits
+    dW1 = daq.conv_bwd_filter_int8(d, f.qx_cnhw, f.s_x, q.vq, q.s_chan)
+    dX1 = daq.conv_bwd_data_int8(d, q.qg, q.s_global, f.qw, f.s_w)
     torch.cuda.synchronize()
+    assert torch.equal(dW, dW1) and torch.equal(dX, dX1)
     assert f.s_x.item() == 127.0 and f.s_w.item() == 127.0 and q.s_global.item() == 127.0
     assert bool((q.s_chan == 127.0).all())
 

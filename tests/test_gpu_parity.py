@@ -222,6 +222,16 @@ def run_convs_on_codes(layer, qX, qW, qG, s_x, s_w, s_g, s_c):
     dX2 = daq.conv_bwd_data_int8(d, qg, s_g_d, qw, s_w_d)
     torch.cuda.synchronize()
     assert torch.equal(dW, dW2) and torch.equal(dX, dX2)
+    # both gradients in one call (the filter gradient's last stage may ride on the data-gradient launch)
+    accW3, accX3 = torch.full_like(accW, -1), torch.full_like(accX, -1)
+    dW3, dX3 = daq.conv_bwd_int8(d, qx_cnhw, s_x_d, vq, s_c_d, qg, s_g_d, qw, s_w_d, dW_acc=accW3, dX_acc=accX3)
+    dW4, dX4 = daq.conv_bwd_int8(d, qx_cnhw, s_x_d, vq, s_c_d, qg, s_g_d, qw, s_w_d)
+    torch.cuda.synchronize()
+    assert np.array_equal(accW3.cpu().numpy(), raccW), "dW accumulators, combined call"
+    assert np.array_equal(accX3.cpu().numpy(), raccX), "dX accumulators, combined call"
+    close(dW3.cpu().numpy(), rdW, "dW, combined call")
+    close(dX3.cpu().numpy(), rdX, "dX, combined call")
+    assert torch.equal(dW3, dW) and torch.equal(dX3, dX) and torch.equal(dW4, dW) and torch.equal(dX4, dX)
 
 
 @pytest.mark.parametrize("layer", CONV_LAYERS, ids=lambda l: l.name)
@@ -285,6 +295,11 @@ def full_layer_parity(config, index, layer=None):
     close(dW.cpu().numpy(), rdW, "dW")
     close(dX.cpu().numpy(), rdX, "dX")
     close(f.Y.cpu().numpy(), rf.Y, "Y")
+    accW2, accX2 = torch.full_like(accW, -1), torch.full_like(accX, -1)
+    dW2, dX2 = daq.conv_bwd_int8(d, f.qx_cnhw, f.s_x, q.vq, q.s_chan, q.qg, q.s_global, f.qw, f.s_w, dW_acc=accW2, dX_acc=accX2)
+    torch.cuda.synchronize()
+    assert np.array_equal(accW2.cpu().numpy(), raccW) and np.array_equal(accX2.cpu().numpy(), raccX)
+    assert torch.equal(dW2, dW) and torch.equal(dX2, dX), "combined call differs from the two separate calls"
 
 
 def test_config1_full_layer():

@@ -164,6 +164,12 @@ def test_workspace_and_validation_without_a_gpu():
     assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, None, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
     assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, one, one, one, None, None, 0, None) == daq.ERR_WORKSPACE
     assert lib.daq_conv_fwd_int8(C.byref(d), one, None, one, one, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    both = lambda **kw: lib.daq_conv_bwd_int8(C.byref(kw.get("desc", d)), kw.get("qx", one), one, kw.get("vq", one), one, kw.get("dW", one),
+                                              None, one, one, one, one, kw.get("dX", one), None, kw.get("ws", one), kw.get("wsb", 1 << 24), None)
+    assert both(dW=None) == daq.ERR_INVALID_ARG and both(dX=None) == daq.ERR_INVALID_ARG and both(desc=bad) == daq.ERR_INVALID_ARG
+    assert both(ws=None) == daq.ERR_WORKSPACE and both(wsb=256) == daq.ERR_WORKSPACE
+    assert both(vq=C.c_void_p(257)) == daq.ERR_INVALID_ARG
+    assert daq.workspace_bytes(daq.OP_CONV_BWD, d) == daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d) + daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)
     # misaligned int8 buffers
     odd = C.c_void_p(257)
     assert lib.daq_conv_bwd_data_int8(C.byref(d), odd, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
