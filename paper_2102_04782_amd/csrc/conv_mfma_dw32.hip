@@ -685,7 +685,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
         }
-        if (pl.splits > 1 && defer)
+        if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits))
             *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
         else if (pl.splits > 1)
             DAQ_LAUNCH("dw_reduce", st,
@@ -695,7 +695,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     }
     const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
-    if (pl.splits > 1 && defer) {
+    if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits)) {
         *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
     } else if (pl.splits > 1) {
         const unsigned blocks = (unsigned)(pl.part_slots / kWave);
