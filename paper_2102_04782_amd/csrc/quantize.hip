@@ -7,6 +7,8 @@
 // trees and a fixed-order second stage (no float atomics), so results do not depend on scheduling.  Compile with
 // -ffp-contract=off: the rounding of every fp32/fp64 expression below is part of the contract.
 #include <algorithm>
+#include <cmath>
+#include <cstdlib>
 
 #include "daq_internal.h"
 
@@ -21,6 +23,7 @@ constexpr int kBlock = 256;
 constexpr int kStatsElems = 4096;  // elements one statistics workgroup sweeps per iteration (16 per thread, all in flight)
 constexpr int kMaxSlabs = 16;      // statistics partials per channel (every consumer re-folds them)
 constexpr int kCountGrid = 1024;   // workgroups the counting pass aims for; one count partial per channel each
+constexpr int64_t kEarlyVqMinElems = (int64_t)16 << 20;   // gradients from this size on take the early per-channel copy
 
 // ---------------------------------------------------------------------------------------------
 // workspace carving
@@ -30,6 +33,7 @@ struct QuantWs {
     float* mean;          // [C]
     float* sigma;         // [C]
     float* s_prev;        // [C]  copy of the clip state taken before anything overwrites it
+    uint32_t* pred;       // [C]  class the counting pass assumed when it wrote the per-channel copy early (see k_count_qg)
     float* part_max;      // [C][slabs]
     double* part_s1;      // [C][slabs]
     double* part_s2;      // [C][slabs]
@@ -59,7 +63,8 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     w.mean = w.gmax + C;
     w.sigma = w.mean + C;
     w.s_prev = w.sigma + C;
-    p += round_up((int64_t)4 * C * 4, 256);
+    w.pred = (uint32_t*)(w.s_prev + C);
+    p += round_up((int64_t)5 * C * 4, 256);
     w.part_s1 = (double*)p;
     w.part_s2 = w.part_s1 + (int64_t)C * w.slabs;
     p += round_up((int64_t)2 * C * w.slabs * 8, 256);
@@ -283,6 +288,35 @@ __device__ __forceinline__ void fold_stats(const QuantWs& ws, int c, double Md, 
     sigma = (float)sqrt(var);
 }
 
+// S4: clip value of a channel of the given class (Eq. "gaus": |g|max; Eq. "fats": (1-kA) s_prev + A |g|max, with a
+// non-positive state meaning "no history" and a non-positive result replaced by |g|max).
+__device__ __forceinline__ float clip_rule(int klass, float gm, float prev, float k, float A) {
+    float s = gm;
+    if (klass == DAQ_CLASS_INVT) {
+        if (!(prev > 0.0f)) prev = gm;
+        s = (float)((1.0 - (double)k * (double)A) * (double)prev + (double)A * (double)gm);
+        if (!(s > 0.0f)) s = gm;
+    }
+    return s;
+}
+
+// What the counting pass needs to write the per-channel copy of channels whose class it can guess.
+struct EarlyVq {
+    int8_t* vq;            // nullptr: the counting pass does not write the per-channel copy
+    int64_t chan_pitch;
+    int32_t lead, img_rows, row_pitch, W;
+    FastDiv div_w;
+    float k, A;
+    float ratio;           // a channel with |g|max > ratio * sigma is taken for long-tailed
+    int quad;              // rows are a multiple of four pixels long: four adjacent lanes hold four pixels of one row
+};
+
+// Value of `v` in the lane whose number differs in bit 0 (XOR1) or bit 1 (otherwise), by DPP quad permutation.
+template <bool XOR1>
+__device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, XOR1 ? 0xB1 : 0x4E, 0xF, 0xF, false);
+}
+
 // ---------------------------------------------------------------------------------------------
 // S2 (+ the global copy of S5): tail-mass count per channel, fused with the globally quantized
 // NHWC copy.  A workgroup owns 64 channels and walks 64-pixel tiles p, p + cgroups, ... of the
@@ -292,12 +326,21 @@ __device__ __forceinline__ void fold_stats(const QuantWs& ws, int c, double Md, 
 // (the global scale max_c |g|max), then counts with wave ballots into registers and stores one
 // count partial per channel: no atomics, no reduction launch.
 // ---------------------------------------------------------------------------------------------
-template <bool STOCH, bool WRITE_QG, bool COUNT>
+//
+// EARLY: the pass also writes the per-channel copy vq.  The class of a channel is only known once the counts of all
+// its workgroups are in, but |g|max / sigma, known here, separates bell-shaped from long-tailed channels almost
+// always: every workgroup derives the same guess and the clip value that follows from it (same arithmetic as the
+// final decision), quantizes with it and stores the bytes of the real elements; the packing pass, which takes the
+// decision, then only rewrites the channels whose guess was wrong (and writes the padding).  A correct guess saves
+// the third sweep over dY for that channel; a wrong one costs nothing but the bytes written here.
+template <bool STOCH, bool WRITE_QG, bool COUNT, bool EARLY = false>
 __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g, int N, int C, int HW, int c_pitch,
                                                      FastDiv div_hw, QuantWs ws, const float* __restrict__ scale_ptr,
                                                      int8_t* __restrict__ qg, uint64_t seed,
-                                                     const float* __restrict__ s_state, float* __restrict__ s_global) {
+                                                     const float* __restrict__ s_state, float* __restrict__ s_global,
+                                                     EarlyVq ev) {
     __shared__ float l_sigma[64];
+    __shared__ float l_inv[64];
     __shared__ float l_max[kBlock / kWave];
     __shared__ __align__(16) int8_t l_tile[64 * 80];
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
@@ -351,6 +394,11 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
         if (c < C) {
             fold_stats(ws, c, (double)N * (double)HW, gm, mu, sig);
             if (p == 0) { ws.gmax[c] = gm; ws.mean[c] = mu; ws.sigma[c] = sig; }
+            if (EARLY) {
+                const int guess = gm > ev.ratio * sig ? DAQ_CLASS_INVT : DAQ_CLASS_GAUSS;
+                l_inv[tid] = inv_scale(clip_rule(guess, gm, s_state[c], ev.k, ev.A));
+                if (p == 0) ws.pred[c] = (uint32_t)guess;
+            }
         }
         l_sigma[tid] = sig;
     }
@@ -369,6 +417,10 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
 #pragma unroll
     for (int i = 0; i < 16; ++i) sig[i] = COUNT ? l_sigma[16 * wave + i] : 0.0f;
 
+    float inv_c[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) inv_c[i] = EARLY ? l_inv[16 * wave + i] : 0.0f;
+
     uint32_t cnt[16];   // wave-uniform counters
 #pragma unroll
     for (int i = 0; i < 16; ++i) cnt[i] = 0;
@@ -384,6 +436,55 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
             if (WRITE_QG) {
                 const uint64_t idx = STOCH ? (uint64_t)(((int64_t)n_cur * C + c0 + i) * HW + px_cur) : 0;
                 b[i] = quant_bits<STOCH>(x[i], inv, seed, 1u, idx);
+            }
+        }
+        if (EARLY) {
+            // channel-major copy: the lane's pixel sits at the same offset of each of its 16 channel planes
+            const uint32_t h = fdiv(px_cur, ev.div_w);
+            int8_t* dst = ev.vq + (int64_t)c0 * ev.chan_pitch + (uint32_t)ev.lead +
+                          (n_cur * (uint32_t)ev.img_rows + h) * (uint32_t)ev.row_pitch + (px_cur - h * (uint32_t)ev.W);
+            uint32_t vb[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint64_t idx = STOCH ? (uint64_t)(((int64_t)n_cur * C + c0 + i) * HW + px_cur) : 0;
+                vb[i] = quant_bits<STOCH>(x[i], inv_c[i], seed, 0u, idx);
+            }
+            if (ev.quad) {   // uniform
+                // Four adjacent lanes hold four consecutive pixels of one row.  Their 4 x 16 codes are transposed inside
+                // the quad - dwords between lanes, then bytes between dwords - so that lane r of the quad ends up with
+                // the four pixels of channels 4r .. 4r+3 as one dword each: four stores per lane instead of sixteen.
+                uint32_t wd[4];
+#pragma unroll
+                for (int k4 = 0; k4 < 4; ++k4) wd[k4] = pack4(vb[4 * k4], vb[4 * k4 + 1], vb[4 * k4 + 2], vb[4 * k4 + 3]);
+                const bool o1 = lane & 1, o2 = lane & 2;
+#pragma unroll
+                for (int k4 = 0; k4 < 4; k4 += 2) {
+                    const uint32_t got = quad_swap<true>(o1 ? wd[k4] : wd[k4 + 1]);
+                    wd[k4] = o1 ? got : wd[k4];
+                    wd[k4 + 1] = o1 ? wd[k4 + 1] : got;
+                }
+#pragma unroll
+                for (int k4 = 0; k4 < 2; ++k4) {
+                    const uint32_t got = quad_swap<false>(o2 ? wd[k4] : wd[k4 + 2]);
+                    wd[k4] = o2 ? got : wd[k4];
+                    wd[k4 + 2] = o2 ? wd[k4 + 2] : got;
+                }
+                // wd[q] = channels 4r .. 4r+3 of the quad's pixel q; now bytes: out[j] = pixels 0 .. 3 of channel 4r + j
+                const uint32_t t0 = __builtin_amdgcn_perm(wd[1], wd[0], 0x05010400u), t1 = __builtin_amdgcn_perm(wd[1], wd[0], 0x07030602u);
+                const uint32_t t2 = __builtin_amdgcn_perm(wd[3], wd[2], 0x05010400u), t3 = __builtin_amdgcn_perm(wd[3], wd[2], 0x07030602u);
+                const uint32_t out[4] = {__builtin_amdgcn_perm(t2, t0, 0x05040100u), __builtin_amdgcn_perm(t2, t0, 0x07060302u),
+                                         __builtin_amdgcn_perm(t3, t1, 0x05040100u), __builtin_amdgcn_perm(t3, t1, 0x07060302u)};
+                const int r = lane & 3;
+                int8_t* dq = dst - r + (int64_t)(4 * r) * ev.chan_pitch;   // first pixel of the quad, plane of channel c0 + 4r
+                if (v_cur) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (c0 + 4 * r + j < C) __builtin_memcpy(dq + (int64_t)j * ev.chan_pitch, &out[j], 4);   // byte aligned only
+                }
+            } else if (v_cur) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (c0 + i < C) dst[(int64_t)i * ev.chan_pitch] = (int8_t)vb[i];
             }
         }
         if (WRITE_QG) {
@@ -439,7 +540,7 @@ struct ClipArgs {
 // S2 (sum of the count partials) + S3 discriminator + S4 clip rule for channel c, evaluated by a whole
 // workgroup; every workgroup of the channel gets the same value, `publish` marks the one that writes it out.
 __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& ca, int c, double Md, bool publish,
-                                            uint32_t* l_cnt) {
+                                            uint32_t* l_cnt, int* klass_out = nullptr) {
     const int tid = threadIdx.x;
     uint32_t cnt = 0;
     static_assert(kCountGrid <= 4 * kBlock, "a thread sums at most four count partials");
@@ -457,14 +558,9 @@ __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& c
     __syncthreads();
     cnt = l_cnt[0] + l_cnt[1] + l_cnt[2] + l_cnt[3];
     const int klass = ((double)cnt > (double)ca.lambda * Md) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
+    if (klass_out) *klass_out = klass;   // every thread holds the same sum, hence the same class
     const float gm = ws.gmax[c];
-    float s = gm;
-    if (klass == DAQ_CLASS_INVT) {
-        float prev = ws.s_prev[c];
-        if (!(prev > 0.0f)) prev = gm;
-        s = (float)((1.0 - (double)ca.k * (double)ca.A) * (double)prev + (double)ca.A * (double)gm);
-        if (!(s > 0.0f)) s = gm;
-    }
+    const float s = clip_rule(klass, gm, ws.s_prev[c], ca.k, ca.A);
     if (publish && tid == 0) {
         ca.s_state[c] = s;
         ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
@@ -581,8 +677,10 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 struct RowsArgs {
     FastDiv div_hwv, div_wv, div_prb;
-    int per_chan;          // data workgroups per channel (one more zeroes the padding)
+    int per_chan;          // blocks of 1024 element groups per channel
+    int grid_per_chan;     // data workgroups per channel (one more zeroes the padding); fewer than per_chan: they loop
     int per_channel_scale;
+    int early;             // the counting pass has written the real elements of channels whose class it guessed
     uint32_t tensor;
     uint64_t seed;
     // optional second copy of the same tensor in the same layout, quantized with its own per-tensor scale
@@ -610,15 +708,15 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
     __shared__ uint32_t l_cnt[kBlock / kWave];
     const int b = blockIdx.x;
     const int xcd = b % kXcd, q = b / kXcd;
-    const int c = (q / (pa.per_chan + 1)) * kXcd + xcd;  // channel c runs on XCD c % 8
-    const int jb = q % (pa.per_chan + 1);
+    const int c = (q / (pa.grid_per_chan + 1)) * kXcd + xcd;  // channel c runs on XCD c % 8
+    const int jb0 = q % (pa.grid_per_chan + 1);
     if (c >= L.C) return;
     const int tid = threadIdx.x;
     int8_t* plane = dst + (int64_t)c * L.chan_pitch;
     int8_t* plane2 = pa.dst2 ? pa.dst2 + (int64_t)c * L.chan_pitch : nullptr;   // uniform
     const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
 
-    if (jb == pa.per_chan) {
+    if (jb0 == pa.grid_per_chan) {
         // padding rows behind every image, then the bytes in front of the first row and behind the last image
         const uint32_t prb = (uint32_t)(L.img_rows - L.H) * (uint32_t)L.row_pitch;
         const uint32_t total = (uint32_t)L.N * prb;
@@ -628,17 +726,38 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
                 const uint32_t n = fdiv(t, pa.div_prb);
                 pl[(uint32_t)L.lead + n * slot + (uint32_t)L.H * (uint32_t)L.row_pitch + (t - n * prb)] = 0;
             }
+            if (pa.early) {   // the data workgroups of a correctly guessed channel do not run: the bytes between the rows
+                const uint32_t pw = (uint32_t)(L.row_pitch - L.W), rows = (uint32_t)L.N * (uint32_t)L.H;
+                for (uint32_t t = tid; t < rows * pw; t += kBlock) {
+                    const uint32_t r = t / pw, n = r / (uint32_t)L.H;
+                    pl[(uint32_t)L.lead + (n * (uint32_t)L.img_rows + (r - n * (uint32_t)L.H)) * (uint32_t)L.row_pitch + (uint32_t)L.W + (t - r * pw)] = 0;
+                }
+            }
             for (uint32_t t = tid; t < (uint32_t)L.lead; t += kBlock) pl[t] = 0;
             for (uint32_t t = (uint32_t)L.lead + (uint32_t)L.N * slot + tid; t < (uint32_t)L.plane_pitch; t += kBlock) pl[t] = 0;
         }
         return;
     }
 
+    // The counting pass guessed this channel's class: its bytes are in place if the guess was right (same clip rule
+    // on the same inputs, hence the same scale and the same codes), and then nothing of dY is read here.
+    float s = 0.0f;
+    if (CLIP && pa.early) {
+        int klass;
+        s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt, &klass);
+        if ((uint32_t)klass == ws.pred[c]) return;   // uniform
+    }
+    if (CLIP && !pa.early) s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt);
+    else if (!CLIP) s = pa.per_channel_scale ? scale[c] : scale[0];
+    const float inv = inv_scale(s);
+
     const uint32_t HW = (uint32_t)(L.H * L.W), HWV = HW / V, WV = (uint32_t)L.W / V;
     const uint32_t groups = (uint32_t)L.N * HWV;
     const int padw = L.row_pitch - L.W;
     const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * 4u);
 
+  // one pass unless the grid was cut down (early mode: the few channels left to do are walked by a few workgroups)
+  for (int jb = jb0; jb < pa.per_chan; jb += pa.grid_per_chan) {
     float x[4][V];
     uint32_t eoff[4], doff[4];
     bool live[4], row_end[4];
@@ -665,11 +784,6 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
         }
     }
 
-    float s;
-    if (CLIP) s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb == 0, l_cnt);
-    else s = pa.per_channel_scale ? scale[c] : scale[0];
-    const float inv = inv_scale(s);
-
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         uint32_t bits[4] = {0u, 0u, 0u, 0u};
@@ -692,6 +806,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
                 for (int k = 0; k < padw; ++k) plane2[doff[u] + V + k] = 0;
         }
     }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -768,6 +883,17 @@ bool pack_supported(const daq_layout& L) {
 bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31); }
 
 
+// Elements per thread of the source-driven row kernel (4 or 2), or 0 when the layout needs the output-driven one.
+int rows_vector(const daq_layout& Ld, const float* src) {
+    const int64_t lim24 = (int64_t)1 << 24;
+    const bool unsplit = Ld.phases_h == 1 && Ld.phases_w == 1 && Ld.org_h == 0 && Ld.org_w == 0 &&
+                         (int64_t)Ld.N * Ld.img_rows < lim24 && (int64_t)Ld.H * Ld.W < lim24 &&
+                         (int64_t)(Ld.N + 1) * Ld.C < lim24 && Ld.plane_pitch < ((int64_t)1 << 31);
+    if (unsplit && Ld.W % 4 == 0 && ((uintptr_t)src & 15u) == 0) return 4;
+    if (unsplit && Ld.W % 2 == 0 && ((uintptr_t)src & 7u) == 0) return 2;
+    return 0;
+}
+
 // Launches the channel-major packing of one fp32 NCHW tensor: the source-driven row kernel when the
 // layout allows it, the output-driven kernel otherwise.
 // With dst2 the same pass also writes a second copy quantized with the per-tensor scale scale2 (random stream
@@ -775,16 +901,11 @@ bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31)
 daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src, const daq_layout& Ld,
                        const float* scale, int per_channel_scale, int8_t* dst, uint32_t tensor, uint64_t seed,
                        const QuantWs& ws, const ClipArgs& ca, hipStream_t st, int8_t* dst2 = nullptr,
-                       const float* scale2 = nullptr, uint32_t tensor2 = 0, bool* fused = nullptr) {
+                       const float* scale2 = nullptr, uint32_t tensor2 = 0, bool* fused = nullptr, bool early = false) {
     if (fused) *fused = false;
     const CnhwView V = cnhw_view(Ld);
-    const int64_t lim24 = (int64_t)1 << 24;
-    const bool unsplit = Ld.phases_h == 1 && Ld.phases_w == 1 && Ld.org_h == 0 && Ld.org_w == 0 &&
-                         (int64_t)Ld.N * Ld.img_rows < lim24 && (int64_t)Ld.H * Ld.W < lim24 &&
-                         (int64_t)(Ld.N + 1) * Ld.C < lim24 && Ld.plane_pitch < ((int64_t)1 << 31);
-    int v = 0;
-    if (unsplit && Ld.W % 4 == 0 && ((uintptr_t)src & 15u) == 0) v = 4;
-    else if (unsplit && Ld.W % 2 == 0 && ((uintptr_t)src & 7u) == 0) v = 2;
+    const int v = rows_vector(Ld, src);
+    if (early && !v) return DAQ_ERR_INVALID_ARG;   // the caller checks rows_vector before it asks for the early copy
     if (v) {
         RowsArgs ra{};
         const uint32_t hwv = (uint32_t)(Ld.H * Ld.W / v);
@@ -792,14 +913,16 @@ daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src
         ra.div_wv = make_fastdiv((uint32_t)(Ld.W / v));
         ra.div_prb = make_fastdiv((uint32_t)std::max(1, (Ld.img_rows - Ld.H) * Ld.row_pitch));
         ra.per_chan = (int)ceil_div((int64_t)Ld.N * hwv, 4 * kBlock);
+        ra.grid_per_chan = early ? std::min(ra.per_chan, 16) : ra.per_chan;
         ra.per_channel_scale = per_channel_scale;
+        ra.early = early ? 1 : 0;
         ra.tensor = tensor;
         ra.seed = seed;
         ra.dst2 = dst2;
         ra.scale2 = scale2;
         ra.tensor2 = tensor2;
         if (fused) *fused = dst2 != nullptr;
-        const dim3 grid((unsigned)(round_up(Ld.C, kXcd) * (ra.per_chan + 1)));
+        const dim3 grid((unsigned)(round_up(Ld.C, kXcd) * (ra.grid_per_chan + 1)));
 #define DAQ_ROWS(S, CL, VV) \
     DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_rows<S, CL, VV>), grid, dim3(kBlock), 0, st, src, V, scale, dst, ra, ws, ca))
         if (v == 4) {
@@ -852,7 +975,7 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
     DAQ_LAUNCH("quant_nhwc", st,
                hipLaunchKernelGGL((k_count_qg<false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
                                   d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
-                                  (uint64_t)0, (const float*)nullptr, (float*)nullptr));
+                                  (uint64_t)0, (const float*)nullptr, (float*)nullptr, EarlyVq{}));
     const daq_status prc = launch_pack("pack_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st);
     if (prc != DAQ_OK) return prc;
     return DAQ_OK;
@@ -926,16 +1049,33 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     const int CB = (int)ceil_div(C, 64);
     const dim3 cgrid((unsigned)(CB * ws.cgroups));
     const float* no_scale = nullptr;
-#define DAQ_COUNT_LAUNCH(S, Q)                                                                                       \
+    // Large gradients: the counting pass also writes the per-channel copy under a guessed class (see k_count_qg), so
+    // that the third sweep over dY only touches the channels whose guess was wrong.  Small ones are bound by launch
+    // latency, not by bytes, and keep the leaner counting kernel.
+    static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");   // tuning override, read once: smallest gradient (elements)
+    const int64_t early_min = early_env ? atoll(early_env) : kEarlyVqMinElems;
+    const bool early = qg_nhwc && rows_vector(Lv, dY) != 0 && (int64_t)N * C * HW >= early_min &&
+                       Lv.lead + (int64_t)N * Lv.img_rows * Lv.row_pitch < ((int64_t)1 << 32);
+    EarlyVq ev{};
+    if (early) {
+        // |g|max / sigma of M Gaussian samples is about sqrt(2 ln M), of M Laplace samples ln M / sqrt 2: halfway
+        const double lnM = std::log((double)N * HW);
+        ev = EarlyVq{vq, Lv.chan_pitch, (int32_t)Lv.lead, Lv.img_rows, Lv.row_pitch, Lv.W, make_fastdiv((uint32_t)Lv.W), k, A,
+                     (float)(0.5 * (std::sqrt(2.0 * lnM) + lnM / std::sqrt(2.0))), Lv.W % 4 == 0 ? 1 : 0};
+    }
+#define DAQ_COUNT_LAUNCH(S, Q, E)                                                                                    \
     DAQ_LAUNCH("count_qg", st,                                                                                       \
-               hipLaunchKernelGGL((k_count_qg<S, Q, true>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,                \
+               hipLaunchKernelGGL((k_count_qg<S, Q, true, E>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,             \
                                   qg_nhwc ? Lg.c_pitch : 0, div_hw, ws, no_scale, qg, seed, (const float*)s_state,   \
-                                  s_global))
-    if (qg_nhwc) {
-        if (stoch) DAQ_COUNT_LAUNCH(true, true);
-        else DAQ_COUNT_LAUNCH(false, true);
+                                  s_global, ev))
+    if (early) {
+        if (stoch) DAQ_COUNT_LAUNCH(true, true, true);
+        else DAQ_COUNT_LAUNCH(false, true, true);
+    } else if (qg_nhwc) {
+        if (stoch) DAQ_COUNT_LAUNCH(true, true, false);
+        else DAQ_COUNT_LAUNCH(false, true, false);
     } else {
-        DAQ_COUNT_LAUNCH(false, false);
+        DAQ_COUNT_LAUNCH(false, false, false);
     }
 #undef DAQ_COUNT_LAUNCH
 
@@ -944,7 +1084,7 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
     bool fused = false;
     rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, seed, ws, ca, st, qg_nhwc ? nullptr : qg, s_global,
-                     1u, &fused);
+                     1u, &fused, early);
     if (rc != DAQ_OK) return rc;
     if (!qg_nhwc && !fused)
         rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);

@@ -125,3 +125,30 @@ def test_quantize_grad_at_full_size(config, index):
     assert abs(out.s_global.item() - r.s_global) <= 1e-5 * r.s_global
     assert torch.equal(_logical_view(daq.layout_vq(d), out.vq), torch.from_numpy(r.vq).to(device)), "vq codes"
     assert torch.equal(_logical_view(daq.layout_qg(d), out.qg), torch.from_numpy(r.qg).to(device)), "qg codes"
+
+
+@pytest.mark.parametrize("shape,lam", [((64, 32, 92, 92), 1.0), ((64, 32, 92, 92), 0.0), ((64, 16, 130, 130), 1.0),
+                                       ((64, 16, 130, 130), 0.3)], ids=str)
+def test_quantize_grad_large_tensor_with_wrong_class_guesses(shape, lam):
+    """Gradients of 16 M elements and more: the counting pass writes the per-channel copy under a guessed class.
+    lambda = 1 (every channel long-tailed) and lambda = 0 (every channel bell-shaped) make half of the guesses
+    wrong, so the packing pass has to redo those channels; rows of 92 take the four-pixel stores, rows of 130
+    the single-byte ones."""
+    device = torch.device("cuda:0")
+    n, c, h, w = shape
+    layer = wl.Layer("big", n, 8, h, w, c, 1, 1, 1, 0)
+    d = daq.ConvDesc.make(*layer.desc_fields())
+    seed = wl.seed_for(9, 500 + c + w)
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    r = ref.quantize_grad(dY, st, 1.0, 0.8, lam, want_fragile=False)
+    assert lam == 0.3 or len(set(r.cls.tolist())) == 1
+    st_dev = torch.from_numpy(st.copy()).to(device)
+    out = daq.quantize_grad(d, torch.from_numpy(dY).to(device), st_dev, lam=lam)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cls.cpu().numpy(), r.cls)
+    assert np.allclose(out.s_chan.cpu().numpy(), r.s_chan, rtol=1e-5, atol=0)
+    assert np.allclose(st_dev.cpu().numpy(), r.s_state, rtol=1e-5, atol=0)
+    assert torch.equal(_logical_view(daq.layout_vq(d), out.vq), torch.from_numpy(r.vq).to(device)), "vq codes"
+    assert torch.equal(_logical_view(daq.layout_qg(d), out.qg), torch.from_numpy(r.qg).to(device)), "qg codes"
+    assert daq.layout_vq(d).padding_is_zero(out.vq), "vq padding bytes must be zero"

@@ -374,3 +374,18 @@ def test_random_descriptors(layer):
     check_quantize_grad(layer, dY, wl.make_state(dY, seed), degenerate=True)
     check_quantize_grad(layer, dY, wl.make_state(dY, seed), mode=daq.ROUND_STOCHASTIC, seed=seed, degenerate=True)
     check_forward(layer, seed)
+
+
+def test_early_per_channel_copy_on_small_shapes():
+    """The counting pass writes the per-channel copy itself only for large gradients; DAQ_EARLY_VQ_MIN=0 (read once
+    per process) turns that on for every size, so the quantizer tests above are run again in a child process with it:
+    ragged shapes, degenerate channels, both rounding modes, wrong guesses (lambda 0 and 1)."""
+    import os
+    import subprocess
+    import sys
+
+    env = dict(os.environ, DAQ_EARLY_VQ_MIN="0")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "gpu", "-p", "no:cacheprovider", __file__, "-k",
+                          "quantize_grad or state_carries"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+    assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-2000:]
