@@ -80,7 +80,7 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // steps before its use), the tap tables are read once, and the pixel fragments of the next tap are read from LDS
 // before the multiplies of the current one: with a single wave per SIMD nothing else hides those latencies.
 template <int WR, bool DB, int ST, int WAVES, int TAPS = 0>
-__global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
+__global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = WAVES / WR;
     constexpr int SPT = 16 * WAVES;   // window slots one pass of the workgroup stages (four lanes per slot)
@@ -199,7 +199,64 @@ __global__ __launch_bounds__(64 * WAVES) void k_conv_halo(HaloArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
 
-    if constexpr (TAPS > 0) {
+    if constexpr (TAPS == 1) {
+        // 1 x 1 filters: a step is a chunk, and every chunk needs a new window.  With the window requested only one
+        // step ahead each chunk would wait out a full memory latency; here window registers and filter tiles both
+        // sit in rings of kRing1 chunks (slot = chunk % kRing1), requested kRing1 - 1 chunks before their use.
+        constexpr int kRing1 = 4, kU1 = 4;   // kU1: 16-byte window units per thread (no halo: at most 256 slots)
+        v4i ra1[kRing1][2][2], rw[kRing1][kU1];
+        auto fetch_1 = [&](int slot, int kc) {
+            const bool live = kc < nkc;
+            const uint32_t base = live ? (uint32_t)((kc * p.RB) * 2048) : kOob;
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) ra1[slot][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+            const bool kok = live && kc * kKc + 16 * sc < p.cp;
+#pragma unroll
+            for (int i = 0; i < kU1; ++i)
+                if (i < p.units) rw[slot][i] = buffer_load16(rs_src, kok ? hoff[i] : kOob, (uint32_t)(kc * kKc));
+        };
+        auto stage_1 = [&](int buf, int slot) {
+            int8_t* H = lds + buf * halo_bytes;
+#pragma unroll
+            for (int i = 0; i < kU1; ++i) {
+                const int sl = (tid >> 2) + SPT * i;
+                if (i < p.units && sl < S) *reinterpret_cast<v4i*>(H + sl * kPitch + 16 * sc) = rw[slot][i];
+            }
+        };
+        int bbyte[BF];
+#pragma unroll
+        for (int y = 0; y < BF; ++y) bbyte[y] = bslot[y] * kPitch + 16 * lh;
+#pragma unroll
+        for (int c = 0; c < kRing1 - 1; ++c) fetch_1(c, c);
+        stage_1(0, 0);
+        __syncthreads();
+        for (int base = 0; base < nkc; base += kRing1) {
+#pragma unroll
+            for (int u = 0; u < kRing1; ++u) {
+                const int kc = base + u;
+                if (kc >= nkc) break;   // uniform
+                fetch_1((u + kRing1 - 1) % kRing1, kc + kRing1 - 1);
+                const int8_t* H = lds + (kc & 1) * halo_bytes;
+#pragma unroll
+                for (int sub = 0; sub < 2; ++sub) {
+                    v4i b[BF];
+#pragma unroll
+                    for (int y = 0; y < BF; ++y) b[y] = *reinterpret_cast<const v4i*>(H + bbyte[y] + 32 * sub);
+#pragma unroll
+                    for (int x = 0; x < 2; ++x)
+#pragma unroll
+                        for (int y = 0; y < BF; ++y)
+                            acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra1[u][x][sub], b[y], acc[x][y], 0, 0, 0);
+                }
+                if (kc + 1 < nkc) {
+                    stage_1((kc + 1) & 1, (u + 1) % kRing1);
+                    __syncthreads();
+                }
+            }
+        }
+    } else if constexpr (TAPS > 0) {
         // tap tables: loop invariant, indexed with constants after unrolling
         int t_id[TAPS], t_off[TAPS];
 #pragma unroll
@@ -506,6 +563,15 @@ daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     // Layers with several contraction chunks and 3 x 3 filters at unit stride, on 64-row tiles: the form with a
     // constant tap count.  (With a single chunk the kernel is all prologue and epilogue, and the dynamic form, which
     // needs fewer registers, lets more workgroups overlap theirs; 128-row tiles stay on the eight-wave form.)
+    // 1 x 1 filters at unit stride with several contraction chunks, on 64-row tiles: the form with rings of chunks
+    // (on 128-row tiles, which are chosen when the grid is large, it measured no better than the dynamic form)
+    if (a.stride == 1 && a.T == 1 && a.ph_taps[0] == 1 && a.tap_slot[0][0] == 0 && a.double_buffer && a.units <= 4 && g.rows == 64) {
+        auto kern = k_conv_halo<1, true, 1, 4, 1>;
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
+            return DAQ_ERR_HIP;
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
+        return DAQ_OK;
+    }
     if (a.stride == 1 && a.ph_taps[0] == 9 && a.double_buffer && g.rows == 64) {
         auto kern = k_conv_halo<1, true, 1, 4, 9>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
