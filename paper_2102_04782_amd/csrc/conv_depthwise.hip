@@ -37,6 +37,8 @@ __device__ __forceinline__ void load8(const int8_t* base, int64_t off, unsigned&
     hi = __builtin_amdgcn_alignbyte(d2, (unsigned)d01[1], sh);
 }
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 struct DxArgs {
     const int8_t* qg;      // planar gradient, [C][chan_pitch]
     const int8_t* qw;      // plain filter copy, [C][kH*kW]
@@ -51,6 +53,7 @@ struct DxArgs {
     const float* s_w;
     float* dX;
     int32_t* acc_out;
+    int nt;                // large result: streaming stores
 };
 
 // Data gradient, unit stride and dilation, kW <= 4: a thread produces four adjacent outputs of one row.
@@ -98,8 +101,9 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
     const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
-        *reinterpret_cast<float4*>(p.dX + o) =
-            make_float4((float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale);
+        const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
+        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
+        else *reinterpret_cast<v4f*>(p.dX + o) = res;
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
     } else {
 #pragma unroll
@@ -161,8 +165,9 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
     const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
-        *reinterpret_cast<float4*>(p.dX + o) =
-            make_float4((float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale);
+        const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
+        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
+        else *reinterpret_cast<v4f*>(p.dX + o) = res;
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
     } else {
 #pragma unroll
@@ -368,6 +373,7 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     a.div_h = make_fastdiv((uint32_t)d.Hin);
     a.div_c = make_fastdiv((uint32_t)d.Cin);
     a.s_g = s_g; a.s_w = s_w; a.dX = dX; a.acc_out = acc;
+    a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
     const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
     const dim3 grid((unsigned)ceil_div(threads, kBlock));
     const bool unit = d.strideH == 1 && d.dilH == 1 && d.dilW == 1 && d.kW <= 4;

@@ -247,7 +247,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
 #pragma unroll
                 for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWNR + (q - rd * PER) % OWNR) * kWave + lane];
                 own[rd * OWNR + (q - rd * PER) % OWNR] = v;
-                if (p.splits > 1) dst[q * kWave] = v;
+                if (p.splits > 1) __builtin_nontemporal_store(v, &dst[q * kWave]);   // read next by other CUs, not by this one
             }
         }
         if (p.splits > 1) return;

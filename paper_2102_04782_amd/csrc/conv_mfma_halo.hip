@@ -64,6 +64,7 @@ struct HaloArgs {
     int32_t* acc_out;
     DwTail tail;          // tail.blocks > 0: that many workgroups behind the first main_blocks finish a deferred filter
     int main_blocks;      // gradient instead (they are dispatched last and fill the slots this kernel's own tiles leave)
+    int nt;               // the result is large: streaming stores, so that it does not push the next kernels' operands out of the caches
 };
 
 __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
@@ -375,6 +376,12 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         float* o = p.out + pix;
         if (ST == 2 && p.zfill && (p.Wd & 1) == 0) {
             // written below together with the zeros of the 2 x 2 block
+        } else if (full_rows && p.nt) {
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __builtin_nontemporal_store((float)acc[x][y][r] * scale, &o[(32 * x + 8 * (r >> 2) + (r & 3)) * HWd]);
         } else if (full_rows) {
 #pragma unroll
             for (int x = 0; x < 2; ++x)
@@ -631,6 +638,7 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;
     g.a.out = dX; g.a.acc_out = acc;
+    g.a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
     return launch(g, st, "conv_bwd_data_mfma");
 }
 
@@ -645,6 +653,7 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     g.a.wfrag = qw + Lw.off_fwd_frag;
     g.a.s_a = s_x; g.a.s_b = s_w;
     g.a.out = Y; g.a.acc_out = acc;
+    g.a.nt = (int64_t)d.N * d.Cout * daq_out_h(&d) * daq_out_w(&d) * 4 >= kStreamBytes;
     return launch(g, st, "conv_fwd_mfma");
 }
 
