@@ -216,38 +216,46 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
 
     // register r of a 32 x 32 tile: row (co) 8*(r/4) + 4*lh + r%4, column (ci) l32; slot = tap*16 + r
     constexpr int SLOTS = kT * 16;
-    if (WK > 1) {
-        // ---- combine the WK waves that share a tile, in parallel: every wave owns an equal share of the slots,
-        // hands the other owners theirs through LDS ([owner][source][slot][lane]) and keeps its own ----
-        // With eight waves the hand-over area for all slots would not fit: two rounds over half of the slots each.
-        constexpr int R = WK > 4 ? 2 : 1;
-        constexpr int PER = SLOTS / R;          // slots handed over per round
-        constexpr int OWNR = PER / WK;          // slots a wave owns per round
-        constexpr int OWN = R * OWNR;
-        static_assert(SLOTS % (R * WK) == 0, "slots divide evenly among rounds and waves");
+    if constexpr (WK > 1) {
+        // ---- combine the eight waves that share a tile, in parallel: every wave owns a share of the slots, hands the
+        // other owners theirs through LDS and keeps its own.  The unit of exchange is a quad of slots (the four
+        // consecutive registers 4g .. 4g+3 of a tap: one 16-byte LDS access per lane instead of four 4-byte ones);
+        // the hand-over area [quad][source wave][lane] for all 36 quads would not fit, so there are two rounds of 18
+        // quads, of which waves 0 and 1 own three each and waves 2 .. 7 two each. ----
+        static_assert(WK == 8, "the combine below is laid out for eight waves");
+        constexpr int QR = SLOTS / 4 / 2;       // quads per round
+        auto owner_of = [](int j) { return j < 3 ? 0 : j < 6 ? 1 : 2 + (j - 6) / 2; };   // j: quad inside its round
+        auto index_of = [](int j) { return j < 6 ? j % 3 : (j - 6) % 2; };               // position among its owner's quads
+        v4i* red4 = reinterpret_cast<v4i*>(lds);
         int* red = reinterpret_cast<int*>(lds);
         int32_t* dst = p.part + ((int64_t)tile * p.splits + split) * SLOTS * kWave + lane;
-        int own[OWN];
+        v4i own[2 * 3];
 #pragma unroll
-        for (int rd = 0; rd < R; ++rd) {
+        for (int rd = 0; rd < 2; ++rd) {
             __syncthreads();   // the staging buffers (or the previous round) are dead from here on
 #pragma unroll
-            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
-                const int owner = (q - rd * PER) / OWNR;
+            for (int j = 0; j < QR; ++j) {
+                const int owner = owner_of(j);
                 if (owner != wk) {   // uniform
+                    const int Q = rd * QR + j, t = Q / 4, g4 = 4 * (Q % 4);
                     const int srcw = wk < owner ? wk : wk - 1;
-                    red[((owner * (WK - 1) + srcw) * OWNR + (q - rd * PER) % OWNR) * kWave + lane] = acc[q / 16][q % 16];
+                    red4[(j * (WK - 1) + srcw) * kWave + lane] = v4i{acc[t][g4], acc[t][g4 + 1], acc[t][g4 + 2], acc[t][g4 + 3]};
                 }
             }
             __syncthreads();
 #pragma unroll
-            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
-                if ((q - rd * PER) / OWNR != wk) continue;   // uniform
-                int v = acc[q / 16][q % 16];
+            for (int j = 0; j < QR; ++j) {
+                if (owner_of(j) != wk) continue;   // uniform
+                const int Q = rd * QR + j, t = Q / 4, g4 = 4 * (Q % 4);
+                v4i v = {acc[t][g4], acc[t][g4 + 1], acc[t][g4 + 2], acc[t][g4 + 3]};
 #pragma unroll
-                for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWNR + (q - rd * PER) % OWNR) * kWave + lane];
-                own[rd * OWNR + (q - rd * PER) % OWNR] = v;
-                if (p.splits > 1) __builtin_nontemporal_store(v, &dst[q * kWave]);   // read next by other CUs, not by this one
+                for (int w = 0; w < WK - 1; ++w) v += red4[(j * (WK - 1) + w) * kWave + lane];
+                own[rd * 3 + index_of(j)] = v;
+                if (p.splits > 1) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)   // read next by other CUs, not by this one: streaming stores
+                        __builtin_nontemporal_store(v[e], &dst[(4 * Q + e) * kWave]);
+                }
             }
         }
         if (p.splits > 1) return;
@@ -256,10 +264,13 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
         __syncthreads();   // everyone is done reading the hand-over area
         constexpr int ROWW = 32 * kT + 1;   // ints per co row in LDS (+1: lanes of a column hit different banks)
 #pragma unroll
-        for (int q = 0; q < SLOTS; ++q) {
-            if ((q % PER) / OWNR != wk) continue;
-            const int t = q / 16, r = q % 16;
-            red[(8 * (r >> 2) + 4 * lh + (r & 3)) * ROWW + l32 * kT + t] = own[(q / PER) * OWNR + (q % PER) % OWNR];
+        for (int Q = 0; Q < SLOTS / 4; ++Q) {
+            if (owner_of(Q % QR) != wk) continue;   // uniform
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = Q / 4, r = 4 * (Q % 4) + e;
+                red[(8 * (r >> 2) + 4 * lh + (r & 3)) * ROWW + l32 * kT + t] = own[(Q / QR) * 3 + index_of(Q % QR)][e];
+            }
         }
         __syncthreads();
         const float sx = *p.s_x / 127.0f;
@@ -465,42 +476,43 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
 
     // slot q = (a*2 + b)*16 + r: tile (a, b) of the wave, register r -> row (co) 32a + 8*(r/4) + 4*lh + r%4, column (ci) 32b + l32
     constexpr int SLOTS = 64;
-    int own[SLOTS / WK];
-    constexpr int R = WK > 4 ? 2 : 1;
-    constexpr int PER = SLOTS / R, OWNR = PER / WK;
-    if (WK > 1) {
-        // parallel combine of the WK waves, as in k_dw32
-        int* red = reinterpret_cast<int*>(lds);
+    v4i own[2];   // WK = 8: the two quads of slots (four consecutive registers of one tile) this wave owns
+    if constexpr (WK > 1) {
+        // parallel combine of the eight waves as in k_dw32, in one round: 16 quads, two per wave,
+        // hand-over area [quad][source wave][lane] of 16-byte entries
+        static_assert(WK == 8, "the combine below is laid out for eight waves");
+        v4i* red4 = reinterpret_cast<v4i*>(lds);
+        __syncthreads();   // the staging buffers are dead from here on
 #pragma unroll
-        for (int rd = 0; rd < R; ++rd) {
-            __syncthreads();
-#pragma unroll
-            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
-                const int owner = (q - rd * PER) / OWNR;
-                if (owner != wk) {   // uniform
-                    const int srcw = wk < owner ? wk : wk - 1;
-                    red[((owner * (WK - 1) + srcw) * OWNR + (q - rd * PER) % OWNR) * kWave + lane] = acc[q / 32][(q / 16) % 2][q % 16];
-                }
+        for (int Q = 0; Q < SLOTS / 4; ++Q) {
+            const int owner = Q / 2;
+            if (owner != wk) {   // uniform
+                const int srcw = wk < owner ? wk : wk - 1;
+                const int g4 = 4 * (Q % 4);
+                const v16i& tl = acc[Q / 8][(Q / 4) % 2];
+                red4[(Q * (WK - 1) + srcw) * kWave + lane] = v4i{tl[g4], tl[g4 + 1], tl[g4 + 2], tl[g4 + 3]};
             }
-            __syncthreads();
+        }
+        __syncthreads();
 #pragma unroll
-            for (int q = rd * PER; q < (rd + 1) * PER; ++q) {
-                if ((q - rd * PER) / OWNR != wk) continue;   // uniform
-                int v = acc[q / 32][(q / 16) % 2][q % 16];
+        for (int Q = 0; Q < SLOTS / 4; ++Q) {
+            if (Q / 2 != wk) continue;   // uniform
+            const int g4 = 4 * (Q % 4);
+            const v16i& tl = acc[Q / 8][(Q / 4) % 2];
+            v4i v = {tl[g4], tl[g4 + 1], tl[g4 + 2], tl[g4 + 3]};
 #pragma unroll
-                for (int w = 0; w < WK - 1; ++w) v += red[((wk * (WK - 1) + w) * OWNR + (q - rd * PER) % OWNR) * kWave + lane];
-                own[rd * OWNR + (q - rd * PER) % OWNR] = v;
-            }
+            for (int w = 0; w < WK - 1; ++w) v += red4[(Q * (WK - 1) + w) * kWave + lane];
+            own[Q % 2] = v;
         }
     }
     int32_t* dst = p.part + (((int64_t)tile * p.splits + split) * (WM * WN) + wm * WN + wn) * SLOTS * kWave + lane;
     const float sx = *p.s_x / 127.0f;
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
-        if (WK > 1 && (q % PER) / OWNR != wk) continue;   // uniform: not this wave's slot
-        const int v = WK > 1 ? own[(q / PER) * OWNR + (q % PER) % OWNR] : acc[q / 32][(q / 16) % 2][q % 16];
+        if (WK > 1 && q / 8 != wk) continue;   // uniform: not this wave's slot
+        const int v = WK > 1 ? own[(q / 4) % 2][q % 4] : acc[q / 32][(q / 16) % 2][q % 16];
         if (p.splits > 1) {
-            dst[q * kWave] = v;
+            __builtin_nontemporal_store(v, &dst[q * kWave]);   // read next by other CUs, not by this one
         } else {
             const int r = q % 16;
             const int co = co0 + wm * 64 + 32 * (q / 32) + 8 * (r >> 2) + 4 * lh + (r & 3);
@@ -587,7 +599,7 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
         pl.splits = (int)std::max<int64_t>(1, s);
         const size_t stage = (size_t)64 * (pl.wm + pl.wn) * kPA;
-        pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 / 2 : 0);
+        pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // one-round combine
         pl.part_slots = tiles * pl.wm * pl.wn * 64 * kWave;
         pl.ok = true;
         return pl;
