@@ -16,7 +16,7 @@
 // (WK = 8: two waves per SIMD, so that one's LDS phase overlaps the other's multiplies), combined in
 // parallel through LDS at the end; the latter keeps all CUs busy on layers with few channels.  K
 // can also be split across workgroups: partial tiles are written with coalesced stores and summed
-// by k_dw32_reduce.
+// by k_dw_reduce.
 #include <algorithm>
 
 #include "daq_internal.h"
@@ -34,6 +34,7 @@ typedef int v2i_a4 __attribute__((ext_vector_type(2), aligned(4)));
 constexpr int kKC = 256;        // K bytes staged per chunk (8 MFMA K-steps of 32)
 constexpr int kPA = kKC + 16;   // LDS pitch of a gradient row: 16-byte aligned, rotates banks between rows
 constexpr int kT = 9;
+constexpr int kDwReducePerWave = 16;   // up to this many K splits a wave of the reduction sums a group of results alone
 
 struct Dw32Args {
     const int8_t* g;      // vq, [Cout][klen]
@@ -315,45 +316,32 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
     }
 }
 
-// Sum of the K-split partial tiles, then dW[co][ci][t] = acc * ((s_x/127) * (s_chan[co]/127)).
-// Workgroup = 64 consecutive (slot, lane) entries of one wave tile; its four waves take every fourth split.
-__global__ __launch_bounds__(256) void k_dw32_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wm_n,
-                                                     int wn_n, int Cout, int Cin, const float* s_x,
-                                                     const float* __restrict__ s_chan, float* __restrict__ dW,
-                                                     int32_t* __restrict__ acc_out) {
-    const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
-    const int per_wave = kT * 16;                       // slots of one wave tile
-    const int wtiles = wm_n * wn_n;
-    const int64_t e = blockIdx.x;                       // (tile, wave tile, slot)
-    const int slot = (int)(e % per_wave);
-    const int wt = (int)((e / per_wave) % wtiles);
-    const int tile = (int)(e / ((int64_t)per_wave * wtiles));
-    const int64_t stride = (int64_t)wtiles * per_wave * kWave;   // between consecutive splits of a tile
-    const int32_t* src = part + (int64_t)tile * splits * stride + ((int64_t)wt * per_wave + slot) * kWave + lane;
-    int32_t a = 0;
-    int s = grp;
-    for (; s + 28 < splits; s += 32) {
-        int32_t v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) a += v[u];
+// Sum of the K-split partial tiles, then dW = acc * ((s_x/127) * (s_chan[co]/127)), for both kernels of this file
+// (the same code serves as a role inside the data-gradient kernel, see dw_tail.h).  With many splits a workgroup
+// takes one group of 64 results and its four waves share the splits; with few, every wave takes a group of its own
+// and keeps all of its loads in flight - no LDS, no barrier.
+__global__ __launch_bounds__(256) void k_dw_reduce(DwTail t) {
+    __shared__ int32_t l_sum[4 * kWave];
+    if (t.splits > kDwReducePerWave) {
+        dw_reduce_role(t, (int)blockIdx.x, l_sum);
+        return;
     }
-    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
-    __shared__ int32_t l_sum[4][kWave];
-    l_sum[grp][lane] = a;
-    __syncthreads();
-    if (grp != 0) return;
-    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
-    const int t = slot / 16, r = slot % 16;
-    const int wm = wt / wn_n, wn = wt % wn_n;
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
-    const int co = (tm * wm_n + wm) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    const int ci = (tn * wn_n + wn) * 32 + (lane & 31);
-    if (co >= Cout || ci >= Cin) return;
-    const int64_t off = ((int64_t)co * Cin + ci) * kT + t;
-    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
-    if (acc_out) acc_out[off] = a;
+    const int lane = threadIdx.x % kWave;
+    const int e = (int)blockIdx.x * 4 + (int)(threadIdx.x / kWave);
+    if (e >= t.blocks) return;
+    int64_t stride;
+    const int32_t* src = dw_tail_source(t, e, lane, stride);
+    int32_t v[kDwReducePerWave];
+#pragma unroll
+    for (int s = 0; s < kDwReducePerWave; ++s) v[s] = src[(int64_t)min(s, t.splits - 1) * stride];
+    int32_t a = 0;
+#pragma unroll
+    for (int s = 0; s < kDwReducePerWave; ++s) a += s < t.splits ? v[s] : 0;
+    int co;
+    const int64_t off = dw_tail_element(t, e, lane, co);
+    if (off < 0) return;
+    t.dW[off] = (float)a * ((*t.s_x / 127.0f) * (t.s_chan[co] / 127.0f));
+    if (t.acc_out) t.acc_out[off] = a;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -526,45 +514,6 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
     }
 }
 
-__global__ __launch_bounds__(256) void k_dw11_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wm_n,
-                                                     int wn_n, int Cout, int Cin, const float* s_x,
-                                                     const float* __restrict__ s_chan, float* __restrict__ dW,
-                                                     int32_t* __restrict__ acc_out) {
-    const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
-    constexpr int per_wave = 64;
-    const int wtiles = wm_n * wn_n;
-    const int64_t e = blockIdx.x;                       // (tile, wave tile, slot)
-    const int slot = (int)(e % per_wave);
-    const int wt = (int)((e / per_wave) % wtiles);
-    const int tile = (int)(e / ((int64_t)per_wave * wtiles));
-    const int64_t stride = (int64_t)wtiles * per_wave * kWave;
-    const int32_t* src = part + (int64_t)tile * splits * stride + ((int64_t)wt * per_wave + slot) * kWave + lane;
-    int32_t a = 0;
-    int s = grp;
-    for (; s + 28 < splits; s += 32) {
-        int32_t v[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) a += v[u];
-    }
-    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
-    __shared__ int32_t l_sum[4][kWave];
-    l_sum[grp][lane] = a;
-    __syncthreads();
-    if (grp != 0) return;
-    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
-    const int r = slot % 16;
-    const int wm = wt / wn_n, wn = wt % wn_n;
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
-    const int co = (tm * wm_n + wm) * 64 + 32 * (slot / 32) + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    const int ci = (tn * wn_n + wn) * 64 + 32 * ((slot / 16) % 2) + (lane & 31);
-    if (co >= Cout || ci >= Cin) return;
-    const int64_t off = (int64_t)co * Cin + ci;
-    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
-    if (acc_out) acc_out[off] = a;
-}
-
 struct Plan32 {
     bool ok;
     bool k11;             // 1 x 1 filter: the plain GEMM kernel
@@ -699,10 +648,11 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
         }
         if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits))
             *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
-        else if (pl.splits > 1)
-            DAQ_LAUNCH("dw_reduce", st,
-                       hipLaunchKernelGGL(k_dw11_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st, a.part,
-                                          pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, s_x, s_chan, dW, acc));
+        else if (pl.splits > 1) {
+            const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
+            const unsigned blocks = pl.splits > kDwReducePerWave ? (unsigned)t.blocks : (unsigned)ceil_div(t.blocks, 4);
+            DAQ_LAUNCH("dw_reduce", st, hipLaunchKernelGGL(k_dw_reduce, dim3(blocks), dim3(256), 0, st, t));
+        }
         return DAQ_OK;
     }
     const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
@@ -710,10 +660,9 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits)) {
         *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
     } else if (pl.splits > 1) {
-        const unsigned blocks = (unsigned)(pl.part_slots / kWave);
-        DAQ_LAUNCH("dw_reduce", st,
-                   hipLaunchKernelGGL(k_dw32_reduce, dim3(blocks), dim3(256), 0, st, a.part, pl.splits, pl.tiles_n, pl.wm,
-                                      pl.wn, d.Cout, d.Cin, s_x, s_chan, dW, acc));
+        const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
+        const unsigned blocks = pl.splits > kDwReducePerWave ? (unsigned)t.blocks : (unsigned)ceil_div(t.blocks, 4);
+        DAQ_LAUNCH("dw_reduce", st, hipLaunchKernelGGL(k_dw_reduce, dim3(blocks), dim3(256), 0, st, t));
     }
     return DAQ_OK;
 }
