@@ -645,11 +645,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
     for (int m = 0; m < 4; ++m) {
         if (wave != m) {
             const int srcw = wave < m ? wave : wave - 1;
-            int* dst = red + ((m * 3 + srcw) * NT * 4) * kWave + lane;
+            v4i* dst = reinterpret_cast<v4i*>(red) + ((m * 3 + srcw) * NT) * kWave + lane;   // [tile][lane]: 16-byte accesses
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) dst[(t * 4 + r) * kWave] = acc[m][t][r];
+            for (int t = 0; t < NT; ++t) dst[t * kWave] = acc[m][t];
         }
     }
     __syncthreads();
@@ -658,11 +656,9 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
         if (wave == m) {
 #pragma unroll
             for (int w = 0; w < 3; ++w) {
-                const int* src = red + ((m * 3 + w) * NT * 4) * kWave + lane;
+                const v4i* src = reinterpret_cast<const v4i*>(red) + ((m * 3 + w) * NT) * kWave + lane;
 #pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[m][t][r] += src[(t * 4 + r) * kWave];
+                for (int t = 0; t < NT; ++t) acc[m][t] += src[t * kWave];
             }
         }
     }
@@ -675,34 +671,46 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
 // Sum of the K-split partial tiles, then dW[co][...] = acc * ((s_x/127) * (s_chan[co]/127)).
 // A workgroup owns 64 consecutive slots of the partial layout (one 256-byte run per split); its four
 // waves take every fourth split with eight loads in flight each and combine through LDS.
-__global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ part, int splits, int tiles_n, int wgn,
+__global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ part, int64_t runs, int splits, int tiles_n, int wgn,
                                                    int nb_per_wave, int T, int row_kw, int Cout, int Cin, const float* s_x,
                                                    const float* __restrict__ s_chan, float* __restrict__ dW,
                                                    int32_t* __restrict__ acc_out) {
     const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
     const int NT = nb_per_wave * T;
     const int per_wave = 16 * NT * kWave;
-    const int64_t i = (int64_t)blockIdx.x * kWave + lane;   // slot
+    // with few splits every wave sums a run of 64 slots alone (all loads in flight, no LDS); else the four waves share one
+    const bool alone = splits <= 16;
+    const int64_t run = alone ? (int64_t)blockIdx.x * 4 + grp : (int64_t)blockIdx.x;
+    if (run >= runs) return;   // uniform per wave; only in the `alone` mode, which has no barrier
+    const int64_t i = run * kWave + lane;   // slot
     const int q = (int)((i / kWave) % (16 * NT));
     const int wn = (int)((i / per_wave) % wgn);
     const int tile = (int)(i / ((int64_t)per_wave * wgn));
     const int64_t stride = (int64_t)per_wave * wgn;          // between consecutive splits of a tile
     const int32_t* src = part + (int64_t)tile * splits * stride + (int64_t)wn * per_wave + (int64_t)q * kWave + lane;
     int32_t a = 0;
-    int s = grp;
-    for (; s + 28 < splits; s += 32) {
-        int32_t v[8];
+    if (alone) {
+        int32_t v[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
+        for (int u = 0; u < 16; ++u) v[u] = src[(int64_t)min(u, splits - 1) * stride];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a += v[u];
+        for (int u = 0; u < 16; ++u) a += u < splits ? v[u] : 0;
+    } else {
+        int s = grp;
+        for (; s + 28 < splits; s += 32) {
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(s + 4 * u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) a += v[u];
+        }
+        for (; s < splits; s += 4) a += src[(int64_t)s * stride];
+        __shared__ int32_t l_sum[4][kWave];
+        l_sum[grp][lane] = a;
+        __syncthreads();
+        if (grp != 0) return;
+        a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
     }
-    for (; s < splits; s += 4) a += src[(int64_t)s * stride];
-    __shared__ int32_t l_sum[4][kWave];
-    l_sum[grp][lane] = a;
-    __syncthreads();
-    if (grp != 0) return;
-    a = l_sum[0][lane] + l_sum[1][lane] + l_sum[2][lane] + l_sum[3][lane];
     const int r = q & 3, t_all = (q >> 2) % NT, m = (q >> 2) / NT;
     const int nb = t_all / T, t = t_all % T;
     const int tm = tile / tiles_n, tn = tile % tiles_n;
@@ -944,9 +952,11 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1) {
         const int wgn = pl.general ? 1 : 4 / pl.wgk;
+        const int64_t runs = pl.part_slots / kWave;
+        const unsigned rblocks = (unsigned)(pl.splits <= 16 ? ceil_div(runs, 4) : runs);
         DAQ_LAUNCH("dw_reduce", st,
-                   hipLaunchKernelGGL(k_dw_reduce, dim3((unsigned)(pl.part_slots / kWave)), dim3(256), 0, st,
-                                      a.part, pl.splits, pl.tiles_n, wgn, pl.nb, pl.row_kw ? d.kH : T, pl.row_kw, d.Cout, d.Cin,
+                   hipLaunchKernelGGL(k_dw_reduce, dim3(rblocks), dim3(256), 0, st,
+                                      a.part, runs, pl.splits, pl.tiles_n, wgn, pl.nb, pl.row_kw ? d.kH : T, pl.row_kw, d.Cout, d.Cin,
                                       s_x, s_chan, dW, acc));
     }
     return DAQ_OK;
