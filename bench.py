@@ -66,10 +66,21 @@ def sweep(args, dev) -> int:
             ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
             ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
             ws_b = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD, d)), dtype=torch.uint8, device=dev)
+            dXh, bf16_ok = None, False
+            if args.dx_bf16:
+                dXh = torch.empty(d.x_shape, dtype=torch.bfloat16, device=dev)
+                try:   # layers without a kernel for the narrow result keep fp32
+                    daq.conv_bwd_data_int8_bf16(d, out.qg, one, qw, one, dX=dXh, workspace=ws_d)
+                    bf16_ok = True
+                except daq.DaqError:
+                    pass
 
             def step():
                 q = daq.quantize_grad(d, dY, st, out=out)
-                if args.separate:
+                if args.dx_bf16 and bf16_ok:
+                    daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
+                    daq.conv_bwd_data_int8_bf16(d, q.qg, q.s_global, qw, one, dX=dXh, workspace=ws_d)
+                elif args.separate:
                     daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
                     daq.conv_bwd_data_int8(d, q.qg, q.s_global, qw, one, dX=dX, workspace=ws_d)
                 else:
@@ -132,6 +143,9 @@ def main() -> int:
     ap.add_argument("--separate", action="store_true",
                     help="call daq_conv_bwd_filter_int8 and daq_conv_bwd_data_int8 one after the other instead of "
                          "daq_conv_bwd_int8 (both gradients in one call, one launch fewer)")
+    ap.add_argument("--dx-bf16", action="store_true",
+                    help="store the data gradient as bfloat16 (daq_conv_bwd_data_int8_bf16: an option beside the method, "
+                         "which returns fp32 gradients; reported for comparison, never the default)")
     ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
                     help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--sweep", action="store_true",
@@ -174,7 +188,8 @@ def main() -> int:
     ws_f = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_FILTER, d)), dtype=torch.uint8, device=dev)
     ws_d = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD_DATA, d)), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(max(256, daq.workspace_bytes(daq.OP_CONV_BWD, d)), dtype=torch.uint8, device=dev)
-    combined = not args.separate and args.streams == 1
+    combined = not args.separate and args.streams == 1 and not args.dx_bf16
+    dXh = torch.empty(d.x_shape, dtype=torch.bfloat16, device=dev) if args.dx_bf16 else None
     main_s = torch.cuda.Stream()
     side_s = torch.cuda.Stream() if args.streams == 2 else None
 
@@ -187,6 +202,9 @@ def main() -> int:
         if combined and fork:
             daq.conv_bwd_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, q.qg, q.s_global, fwd.qw, fwd.s_w,
                               dW=dWs[r], dX=dXs[r], workspace=ws_b, stream=main_s)
+        elif args.dx_bf16 and fork:
+            daq.conv_bwd_filter_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, dW=dWs[r], workspace=ws_f, stream=main_s)
+            daq.conv_bwd_data_int8_bf16(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXh, workspace=ws_d, stream=main_s)
         elif side_s is not None and fork:
             side_s.wait_stream(main_s)
             daq.conv_bwd_data_int8(d, q.qg, q.s_global, fwd.qw, fwd.s_w, dX=dXs[r], workspace=ws_d, stream=side_s)
@@ -233,12 +251,13 @@ def main() -> int:
     torch.cuda.synchronize()
     run(0)
     torch.cuda.synchronize()
-    got = (dWs[0].clone(), dXs[0].clone(), outs[0].vq.clone(), outs[0].qg.clone())
+    got = (dWs[0].clone(), dXs[0].clone() if dXh is None else dXh.clone(), outs[0].vq.clone(), outs[0].qg.clone())
     states[0].copy_(chk_state)
     torch.cuda.synchronize()
     step(0, fork=False)
     torch.cuda.synchronize()
-    same = all(torch.equal(a, b) for a, b in zip(got, (dWs[0], dXs[0], outs[0].vq, outs[0].qg)))
+    want_dX = dXs[0] if dXh is None else dXs[0].to(torch.bfloat16)   # torch rounds to nearest even too
+    same = all(torch.equal(a, b) for a, b in zip(got, (dWs[0], want_dX, outs[0].vq, outs[0].qg)))
     if not same:
         print("bench.py: the timed schedule does not reproduce the single-stream result", file=sys.stderr)
         return 3
@@ -246,7 +265,7 @@ def main() -> int:
     # per-kernel durations: K steps of the timed schedule on one stream with a HIP event pair around every launch
     daq.prof_begin()
     for i in range(args.steps):
-        step(i, fork=combined)
+        step(i, fork=combined or args.dx_bf16)
     rows = daq.prof_end()
     torch.cuda.synchronize()
 
@@ -271,7 +290,7 @@ def main() -> int:
         "pack_qg": 5.0 * E_Y,
     }
     # convolutions: int8 operands read once, fp32 result written once
-    conv_bytes = {"conv_bwd_data": E_Y + E_W + 4.0 * E_X, "conv_bwd_filter": E_X + E_Y + 4.0 * E_W}
+    conv_bytes = {"conv_bwd_data": E_Y + E_W + (2.0 if args.dx_bf16 else 4.0) * E_X, "conv_bwd_filter": E_X + E_Y + 4.0 * E_W}
     ridge = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)   # ops per byte above which the MFMA peak binds
     kernels = {}
     # what an event pair adds by itself (measured by the library with empty pairs), removed from every span
@@ -331,6 +350,7 @@ def main() -> int:
                                f"{layer.Hin}x{layer.Win} k{layer.kH} s{layer.stride} p{layer.pad}",
                    "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3,
                    "streams": args.streams, "hip_graph": bool(args.graph),
+                   "dX": "bf16" if args.dx_bf16 else "fp32",
                    "calls": "daq_quantize_grad + daq_conv_bwd_int8" if combined else
                             "daq_quantize_grad + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8"},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),

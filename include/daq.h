@@ -247,6 +247,22 @@ daq_status daq_conv_bwd_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, c
                              size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_conv_bwd_data_int8_bf16 -- daq_conv_bwd_data_int8 with a narrow result: the same int32
+ * accumulators and the same fp32 product acc * ((s_w/127) * (s_global/127)), stored as bfloat16
+ * (round to nearest, ties to even).  An option beside the method, not part of it: Algorithm 1
+ * returns full-precision gradients; the data gradient's fp32 result is the largest stream of the
+ * backward pass (4 bytes per input element), and a consumer that takes bf16 halves it.
+ * Served for dense (groups = 1) layers at unit stride, and at stride 2 for the layers
+ * daq_conv_bwd_data_int8 runs on its halo-tile kernel; DAQ_ERR_UNSUPPORTED otherwise.
+ *
+ *   dX_bf16   out  bfloat16 NCHW, 4-byte aligned
+ *   other arguments and the workspace as for daq_conv_bwd_data_int8
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,
+                                       const int8_t* qw_packed, const float* s_w, uint16_t* dX_bf16, void* workspace,
+                                       size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every
  * kernel the library launches is bracketed by a HIP event pair on its stream.  daq_prof_end()
  * waits for those events and fills one row per distinct kernel name.  Not thread-safe.

@@ -315,3 +315,20 @@ def conv_bwd_filter_int8(d: ConvDesc, qX, s_x, vq, s_chan):
                                             _p(s_chan, C.c_float), _p(dW, C.c_float), _p(acc, C.c_int32),
                                             C.byref(ovf)), "conv_bwd_filter_int8")
     return dW, acc, bool(ovf.value)
+
+
+def bf16_bits(x) -> np.ndarray:
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest with ties to even, for finite inputs.
+
+    Not part of the paper's method: the storage rule of the optional narrow data-gradient output.  bfloat16 is the upper
+    half of an IEEE binary32; rounding adds half an ulp of the kept part (0x7FFF plus the kept part's last bit, which
+    settles ties towards even) and truncates."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def conv_bwd_data_int8_bf16(d: ConvDesc, qG, s_global, qW, s_w) -> np.ndarray:
+    """The data gradient of conv_bwd_data_int8, stored as bfloat16 bit patterns."""
+    dX, _, ovf = conv_bwd_data_int8(d, qG, s_global, qW, s_w)
+    assert not ovf
+    return bf16_bits(dX)

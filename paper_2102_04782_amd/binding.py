@@ -26,7 +26,7 @@ LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_prof_begin", "daq_prof_end", "daq_status_string",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_prof_begin", "daq_prof_end", "daq_status_string",
 ]
 
 
@@ -174,6 +174,7 @@ def lib():
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
+        L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
@@ -322,6 +323,20 @@ def conv_bwd_filter_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, 
                                         _ptr(acc), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "daq_conv_bwd_filter_int8")
     return dW
+
+
+def conv_bwd_data_int8_bf16(d: ConvDesc, qg: torch.Tensor, s_global: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,
+                            dX: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                            stream=None) -> torch.Tensor:
+    """The data gradient stored as bfloat16 (raises DaqError with ERR_UNSUPPORTED where no kernel has that epilogue)."""
+    if dX is None:
+        dX = torch.empty(d.x_shape, dtype=torch.bfloat16, device=qg.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD_DATA, d), qg.device)
+    rc = lib().daq_conv_bwd_data_int8_bf16(C.byref(d), _ptr(qg), _ptr(s_global), _ptr(qw), _ptr(s_w), _ptr(dX),
+                                           _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_data_int8_bf16")
+    return dX
 
 
 def conv_bwd_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, vq: torch.Tensor, s_chan: torch.Tensor,

@@ -89,3 +89,16 @@ extern "C" daq_status daq_conv_bwd_int8(const daq_conv_desc* desc, const int8_t*
     if (rc != DAQ_OK) return rc;
     return daq_conv_bwd_data_int8(desc, qg, s_global, qw_packed, s_w, dX, dX_acc, ws_d, need_d, stream);
 }
+
+extern "C" daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,
+                                                  const int8_t* qw_packed, const float* s_w, uint16_t* dX_bf16,
+                                                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !qg || !s_global || !qw_packed || !s_w || !dX_bf16) return DAQ_ERR_INVALID_ARG;
+    if (!a16(qg) || !a16(qw_packed) || !a4(dX_bf16)) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    if (!bwd_data_halo_supported(*desc)) return DAQ_ERR_UNSUPPORTED;   // only the halo-tile kernel has the narrow epilogue
+    return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, reinterpret_cast<float*>(dX_bf16), nullptr,
+                              (hipStream_t)stream, nullptr, true);
+}

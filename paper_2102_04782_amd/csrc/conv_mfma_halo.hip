@@ -64,8 +64,15 @@ struct HaloArgs {
     int32_t* acc_out;
     DwTail tail;          // tail.blocks > 0: that many workgroups behind the first main_blocks finish a deferred filter
     int main_blocks;      // gradient instead (they are dispatched last and fill the slots this kernel's own tiles leave)
+    int bf16;             // the result is stored as bfloat16 (round to nearest even) instead of fp32
     int nt;               // the result is large: streaming stores, so that it does not push the next kernels' operands out of the caches
 };
+
+// fp32 -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
 
 __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
@@ -373,6 +380,32 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         const int n = n0 + img, h = (h0 + th) * ST + pa, w = (w0 + tw) * ST + pb;
         if (img >= p.NI || n >= p.N || h >= p.Hd || w >= p.Wd) continue;
         const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w;
+        if (p.bf16) {   // uniform: the narrow result, same walk over the tile
+            uint16_t* ob = reinterpret_cast<uint16_t*>(p.out) + pix;
+            const bool w1 = w + 1 < p.Wd, h1 = h + 1 < p.Hd;
+            const bool pairs = (p.Wd & 1) == 0;   // even rows: (value, 0) and (0, 0) go out as aligned 4-byte stores
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr >= p.Crow) continue;
+                    uint16_t* z = ob + (int64_t)dr * HWd;
+                    const uint32_t v = bf16_bits((float)acc[x][y][r] * scale);
+                    if (ST == 2 && p.zfill && pairs) {
+                        *reinterpret_cast<uint32_t*>(z) = v;   // little endian: the value first, then the zero
+                        if (h1) *reinterpret_cast<uint32_t*>(z + p.Wd) = 0u;
+                    } else {
+                        z[0] = (uint16_t)v;
+                        if (ST == 2 && p.zfill) {
+                            if (w1) z[1] = 0;
+                            if (h1) z[p.Wd] = 0;
+                            if (h1 && w1) z[p.Wd + 1] = 0;
+                        }
+                    }
+                }
+            continue;
+        }
         float* o = p.out + pix;
         if (ST == 2 && p.zfill && (p.Wd & 1) == 0) {
             // written below together with the zeros of the 2 x 2 block
@@ -629,16 +662,17 @@ Geometry plan_fwd(const daq_conv_desc& d) {
 bool bwd_data_halo_supported(const daq_conv_desc& d) { return plan_bwd(d).ok; }
 
 daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail) {
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail, bool bf16) {
     Geometry g = plan_bwd(d);
     if (tail) g.a.tail = *tail;
+    g.a.bf16 = bf16 ? 1 : 0;
     daq_wpack_layout Lw;
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     g.a.src = qg;
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;
     g.a.out = dX; g.a.acc_out = acc;
-    g.a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
+    g.a.nt = !bf16 && (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
     return launch(g, st, "conv_bwd_data_mfma");
 }
 

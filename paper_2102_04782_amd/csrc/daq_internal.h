@@ -143,8 +143,10 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
 // conv_mfma_halo.hip: halo-tile form of the channel-contracting kernel (unit stride; stride 2 for the data gradient)
 bool bwd_data_halo_supported(const daq_conv_desc& d);
 // With `tail` (blocks > 0), extra workgroups of the launch finish a deferred filter gradient.
+// With `bf16`, dX points to bfloat16 storage (2 bytes per element) and receives the result rounded to nearest even.
 daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail = nullptr);
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, const DwTail* tail = nullptr,
+                              bool bf16 = false);
 bool fwd_halo_supported(const daq_conv_desc& d);
 daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st);

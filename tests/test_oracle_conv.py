@@ -191,3 +191,20 @@ def test_end_to_end_gradients_approximate_fp32(ref):
     assert np.median(err(dW)) < 0.1
     assert np.median(err(dW)) < 0.25 * np.median(err(dWg))
     assert np.linalg.norm(dX - rdX) / np.linalg.norm(rdX) < 0.2
+
+
+def test_bf16_rounding_matches_the_library_conversion_and_the_tie_rule(ref):
+    """Pin of the optional narrow output: the oracle's bfloat16 rounding against torch's conversion (a library routine)
+    on random values, and against hand-built ties (exactly halfway patterns go to the even neighbour)."""
+    import torch
+
+    rng = np.random.default_rng(5)
+    x = np.concatenate([rng.normal(0, 1, 100000), rng.normal(0, 1e-6, 1000), rng.normal(0, 1e6, 1000), [0.0, -0.0, 1.0, -1.0]]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ref.bf16_bits(x), want)
+    # ties: low half exactly 0x8000 -> up if the kept part is odd, down if it is even
+    even = np.array([0x3F800000 | 0x8000], np.uint32).view(np.float32)      # kept part 0x3F80 (even)
+    odd = np.array([0x3F810000 | 0x8000], np.uint32).view(np.float32)       # kept part 0x3F81 (odd)
+    assert ref.bf16_bits(even)[0] == 0x3F80 and ref.bf16_bits(odd)[0] == 0x3F82
+    just_above = np.array([0x3F800000 | 0x8001], np.uint32).view(np.float32)
+    assert ref.bf16_bits(just_above)[0] == 0x3F81
