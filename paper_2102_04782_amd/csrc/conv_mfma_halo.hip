@@ -106,13 +106,18 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     const int wr = wave % WR, wp = wave / WR;
     // block -> (row tile, parity class, image group, tile row, tile column)
     const int per_phase = p.groups * p.tiles_h * p.tiles_w;
-    const int ptiles = per_phase * (p.zfill ? 1 : ST * ST);
+    const int ptiles = (ST > 1 && !p.zfill) ? ((per_phase + 7) & ~7) * (ST * ST) : per_phase;
     const int tr = (int)fdiv(bid, p.div_ptiles);
     int tp = (int)bid - tr * ptiles;
     int phase = 0;
     if (ST > 1 && !p.zfill) {
-        phase = (tp >= per_phase) + (tp >= 2 * per_phase) + (tp >= 3 * per_phase);
-        tp -= phase * per_phase;
+        // The four parity classes of a tile interleave in memory (every other pixel of every other row), so each of them
+        // writes partial cache lines.  Their workgroups sit 8 blocks apart in groups of 32: same XCD (block i runs on
+        // XCD i % 8), dispatched together, and the partial lines meet in one L2 instead of going to memory one by one.
+        const int g8 = tp >> 5, r = tp & 31;
+        phase = r >> 3;
+        tp = g8 * 8 + (r & 7);
+        if (tp >= per_phase) return;   // uniform: padding of the last group of eight tiles
     }
     const int pa = phase / ST, pb = phase % ST;
     const int grp = (int)fdiv((uint32_t)tp, p.div_tiles_hw);
@@ -487,6 +492,14 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     }
 }
 
+// Workgroups of one row tile: one per pixel tile, times the parity classes of a strided data gradient (whose tiles are
+// padded to groups of eight, see the kernel's block decoding).
+int64_t blocks_per_row_tile(const HaloArgs& a) {
+    const int64_t per_phase = (int64_t)a.groups * a.tiles_h * a.tiles_w;
+    if (a.stride > 1 && !a.zfill) return round_up(per_phase, 8) * a.stride * a.stride;
+    return per_phase;
+}
+
 // floor division for possibly negative numerators
 int floor_div(int a, int b) { return a >= 0 ? a / b : -((-a + b - 1) / b); }
 
@@ -594,17 +607,16 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     a.div_si = make_fastdiv((uint32_t)(a.SH * a.SW));
     a.div_tiles_w = make_fastdiv((uint32_t)a.tiles_w);
     a.div_tiles_hw = make_fastdiv((uint32_t)(a.tiles_h * a.tiles_w));
-    const int classes = a.zfill ? 1 : s * s;
-    a.div_ptiles = make_fastdiv((uint32_t)(a.groups * a.tiles_h * a.tiles_w * classes));
-    const int64_t blocks = (int64_t)a.groups * a.tiles_h * a.tiles_w * classes * ceil_div(Crow, g.rows);
-    if (blocks >= ((int64_t)1 << 31)) return g;
+    const int64_t pt = blocks_per_row_tile(a);
+    if (pt * ceil_div(Crow, 64) >= ((int64_t)1 << 31)) return g;
+    a.div_ptiles = make_fastdiv((uint32_t)pt);
     g.ok = true;
     return g;
 }
 
 daq_status launch(Geometry& g, hipStream_t st, const char* name) {
     const HaloArgs& a = g.a;
-    const int64_t ptiles = (int64_t)a.groups * a.tiles_h * a.tiles_w * (a.zfill ? 1 : a.stride * a.stride);
+    const int64_t ptiles = blocks_per_row_tile(a);
     const int64_t blocks = ptiles * ceil_div(a.Crow, g.rows) + a.tail.blocks;
     if (blocks >= ((int64_t)1 << 31)) return DAQ_ERR_UNSUPPORTED;
     g.a.main_blocks = (int)(blocks - a.tail.blocks);
