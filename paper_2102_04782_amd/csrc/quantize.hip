@@ -726,13 +726,6 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
                 const uint32_t n = fdiv(t, pa.div_prb);
                 pl[(uint32_t)L.lead + n * slot + (uint32_t)L.H * (uint32_t)L.row_pitch + (t - n * prb)] = 0;
             }
-            if (pa.early) {   // the data workgroups of a correctly guessed channel do not run: the bytes between the rows
-                const uint32_t pw = (uint32_t)(L.row_pitch - L.W), rows = (uint32_t)L.N * (uint32_t)L.H;
-                for (uint32_t t = tid; t < rows * pw; t += kBlock) {
-                    const uint32_t r = t / pw, n = r / (uint32_t)L.H;
-                    pl[(uint32_t)L.lead + (n * (uint32_t)L.img_rows + (r - n * (uint32_t)L.H)) * (uint32_t)L.row_pitch + (uint32_t)L.W + (t - r * pw)] = 0;
-                }
-            }
             for (uint32_t t = tid; t < (uint32_t)L.lead; t += kBlock) pl[t] = 0;
             for (uint32_t t = (uint32_t)L.lead + (uint32_t)L.N * slot + tid; t < (uint32_t)L.plane_pitch; t += kBlock) pl[t] = 0;
         }
@@ -743,6 +736,15 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
     // on the same inputs, hence the same scale and the same codes), and then nothing of dY is read here.
     float s = 0.0f;
     if (CLIP && pa.early) {
+        // the data workgroups of a correctly guessed channel return below: the zero bytes between the rows, which they
+        // would have written along with the codes, are shared out among them first
+        const uint32_t pw = (uint32_t)(L.row_pitch - L.W), rows = (uint32_t)L.N * (uint32_t)L.H;
+        for (uint32_t t = (uint32_t)jb0 * kBlock + tid; t < rows * pw; t += (uint32_t)pa.grid_per_chan * kBlock) {
+            const uint32_t r = t / pw, n = r / (uint32_t)L.H;
+            const uint32_t at = (uint32_t)L.lead + (n * (uint32_t)L.img_rows + (r - n * (uint32_t)L.H)) * (uint32_t)L.row_pitch + (uint32_t)L.W + (t - r * pw);
+            plane[at] = 0;
+            if (plane2) plane2[at] = 0;
+        }
         int klass;
         s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt, &klass);
         if ((uint32_t)klass == ws.pred[c]) return;   // uniform
