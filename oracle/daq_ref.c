@@ -296,6 +296,154 @@ int daq_ref_quantize_grad(const float* dY, int N, int C, int H, int W, float* s_
 }
 
 /* ------------------------------------------------------------------------- */
+/* Ablation schemes (experiments section, "Ablation study"): what takes the    */
+/* place of the per-channel clip values of Algorithm 1 when one of its two     */
+/* ingredients is switched off.  The global copy qg and s_global are the same  */
+/* in every scheme.                                                            */
+/*   GQ   the baseline: the whole gradient is quantized with |g|max of the     */
+/*        tensor, for dW as well; s_chan[c] = max over channels of |g|max,c.   */
+/*   GVQ  vectorized quantization with GQ's rule per channel: s_chan[c] =      */
+/*        |g|max,c, no clipping.                                               */
+/*   MCS  Magnitude-aware Clipping on the layer-wise gradient, no vectors:     */
+/*        |g|max, sigma and the tail mass P of the whole tensor taken as one   */
+/*        population, one class from Eq. "judge", one clip value from Eq.      */
+/*        "gaus" / Eq. "fats", used for every channel.                         */
+/* Readings: in GQ and GVQ the class and the statistics are still reported     */
+/* per channel as Algorithm 1 computes them (they decide nothing); in MCS      */
+/* every channel's row of cls / stats holds the layer's values, the previous   */
+/* clip value is s_state[0], and all of s_state receives the new one.          */
+/* ------------------------------------------------------------------------- */
+#define REF_SCHEME_DAQ 0
+#define REF_SCHEME_GQ 1
+#define REF_SCHEME_GVQ 2
+#define REF_SCHEME_MCS 3
+
+/* |g|max, mean and population standard deviation of n values taken together */
+int daq_ref_layer_stats(const float* g, size_t n, float* gmax, float* mean, float* sigma) {
+    if (!g || !gmax || !mean || !sigma || n == 0) return REF_BAD_ARG;
+    float m = 0.0f;
+    double s1 = 0.0, s2 = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        float a = fabsf(g[i]);
+        if (a > m) m = a;
+        s1 += (double)g[i];
+        s2 += (double)g[i] * (double)g[i];
+    }
+    double mu = s1 / (double)n;
+    double var = s2 / (double)n - mu * mu;
+    if (var < 0.0) var = 0.0;
+    *gmax = m;
+    *mean = (float)mu;
+    *sigma = (float)sqrt(var);
+    return REF_OK;
+}
+
+/* #{ |g| > sigma } over n values */
+static uint32_t layer_tail_count(const float* g, size_t n, float sigma) {
+    uint32_t k = 0;
+    for (size_t i = 0; i < n; ++i)
+        if (fabsf(g[i]) > sigma) ++k;
+    return k;
+}
+
+int daq_ref_quantize_grad_scheme(const float* dY, int N, int C, int H, int W, float* s_state, float k, float A,
+                                 float lambda, int mode, uint64_t seed, int scheme, int8_t* vq, int8_t* qg,
+                                 float* s_chan, float* s_global, uint8_t* cls, float* stats, uint8_t* fragile) {
+    if (scheme == REF_SCHEME_DAQ)
+        return daq_ref_quantize_grad(dY, N, C, H, W, s_state, k, A, lambda, mode, seed, vq, qg, s_chan, s_global, cls,
+                                     stats, fragile);
+    if (scheme != REF_SCHEME_GQ && scheme != REF_SCHEME_GVQ && scheme != REF_SCHEME_MCS) return REF_BAD_ARG;
+    if (!dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls) return REF_BAD_ARG;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return REF_BAD_ARG;
+    if (mode != REF_ROUND_NEAREST && mode != REF_ROUND_STOCHASTIC) return REF_BAD_ARG;
+    const size_t HW = (size_t)H * (size_t)W;
+    const size_t total = (size_t)N * (size_t)C * HW;
+    const double M = (double)N * (double)HW;
+
+    float gmax[C], mean[C], sigma[C];
+    uint32_t count[C];
+    int rc = daq_ref_channel_stats(dY, N, C, H, W, gmax, mean, sigma);
+    if (rc) return rc;
+    rc = daq_ref_tail_count(dY, N, C, H, W, sigma, count);
+    if (rc) return rc;
+    float sg = 0.0f;
+    for (int c = 0; c < C; ++c)
+        if (gmax[c] > sg) sg = gmax[c];
+    *s_global = (sg >= REF_TINY_SCALE) ? sg : 0.0f;
+
+    if (scheme == REF_SCHEME_MCS) {
+        float gm_l, mu_l, sig_l;
+        rc = daq_ref_layer_stats(dY, total, &gm_l, &mu_l, &sig_l);
+        if (rc) return rc;
+        const uint32_t cnt = layer_tail_count(dY, total, sig_l);
+        const int cl = daq_ref_classify(cnt, (double)total, lambda);
+        const float s = daq_ref_clip_value(cl, gm_l, s_state[0], k, A);
+        int flip = 0;
+        if (fragile) {
+            if (daq_ref_classify(layer_tail_count(dY, total, nextafterf(sig_l, -INFINITY)), (double)total, lambda) != cl) flip = 1;
+            if (daq_ref_classify(layer_tail_count(dY, total, nextafterf(sig_l, INFINITY)), (double)total, lambda) != cl) flip = 1;
+        }
+        for (int c = 0; c < C; ++c) {
+            s_state[c] = s;
+            s_chan[c] = (s >= REF_TINY_SCALE) ? s : 0.0f;
+            cls[c] = (uint8_t)cl;
+            if (fragile) fragile[c] = (uint8_t)flip;
+            if (stats) {
+                stats[4 * c + 0] = gm_l;
+                stats[4 * c + 1] = mu_l;
+                stats[4 * c + 2] = sig_l;
+                stats[4 * c + 3] = (float)((double)cnt / (double)total);
+            }
+        }
+    } else {
+        for (int c = 0; c < C; ++c) {
+            const float s = (scheme == REF_SCHEME_GQ) ? sg : gmax[c];
+            s_state[c] = s;
+            s_chan[c] = (s >= REF_TINY_SCALE) ? s : 0.0f;
+            cls[c] = (uint8_t)daq_ref_classify(count[c], M, lambda);
+            if (stats) {
+                stats[4 * c + 0] = gmax[c];
+                stats[4 * c + 1] = mean[c];
+                stats[4 * c + 2] = sigma[c];
+                stats[4 * c + 3] = (float)((double)count[c] / M);
+            }
+            if (fragile) {
+                const float two[2] = {nextafterf(sigma[c], -INFINITY), nextafterf(sigma[c], INFINITY)};
+                int flip = 0;
+                for (int j = 0; j < 2; ++j) {
+                    uint32_t k2 = 0;
+                    for (int n = 0; n < N; ++n) {
+                        const float* p = dY + ((size_t)n * (size_t)C + (size_t)c) * HW;
+                        for (size_t i = 0; i < HW; ++i)
+                            if (fabsf(p[i]) > two[j]) ++k2;
+                    }
+                    if (daq_ref_classify(k2, M, lambda) != (int)cls[c]) flip = 1;
+                }
+                fragile[c] = (uint8_t)flip;
+            }
+        }
+    }
+
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < C; ++c) {
+        for (int n = 0; n < N; ++n) {
+            const size_t base = ((size_t)n * (size_t)C + (size_t)c) * HW;
+            for (size_t i = 0; i < HW; ++i) {
+                const size_t idx = base + i;
+                float u0 = 0.0f, u1 = 0.0f;
+                if (mode == REF_ROUND_STOCHASTIC) {
+                    u0 = daq_ref_uniform24(seed, 0u, (uint64_t)idx);
+                    u1 = daq_ref_uniform24(seed, 1u, (uint64_t)idx);
+                }
+                vq[idx] = daq_ref_quantize_one(dY[idx], s_chan[c], mode, u0);
+                qg[idx] = daq_ref_quantize_one(dY[idx], *s_global, mode, u1);
+            }
+        }
+    }
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Per-tensor ("global") quantization used in the forward pass for X and W:    */
 /* s = max|x| (reading: the paper defers the forward rule to earlier work and  */
 /* calls it global quantization; max-abs is taken), nearest rounding.          */

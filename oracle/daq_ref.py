@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libdaq_ref.so")
 
 GAUSS, INVT = 0, 1
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+SCHEME_DAQ, SCHEME_GQ, SCHEME_GVQ, SCHEME_MCS = 0, 1, 2, 3   # Algorithm 1 and the ablation study's three variants
 
 
 def build(force: bool = False) -> str:
@@ -174,7 +175,8 @@ class QuantGrad:
     fragile: np.ndarray   # u8 [C]
 
 
-def quantize_grad(dY, s_state, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0, want_fragile=True) -> QuantGrad:
+def quantize_grad(dY, s_state, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0, want_fragile=True,
+                  scheme=SCHEME_DAQ) -> QuantGrad:
     g = _f32(dY)
     N, Cc, H, W = g.shape
     st = np.array(s_state, dtype=np.float32, copy=True)
@@ -186,10 +188,11 @@ def quantize_grad(dY, s_state, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0
     cls = np.zeros(Cc, np.uint8)
     stats = np.zeros((Cc, 4), np.float32)
     frag = np.zeros(Cc, np.uint8) if want_fragile else None
-    rc = lib().daq_ref_quantize_grad(_p(g, C.c_float), N, Cc, H, W, _p(st, C.c_float), C.c_float(k), C.c_float(A),
-                                     C.c_float(lam), C.c_int(mode), C.c_uint64(seed), _p(vq, C.c_int8),
-                                     _p(qg, C.c_int8), _p(s_chan, C.c_float), _p(s_glob, C.c_float),
-                                     _p(cls, C.c_uint8), _p(stats, C.c_float), _p(frag, C.c_uint8))
+    rc = lib().daq_ref_quantize_grad_scheme(_p(g, C.c_float), N, Cc, H, W, _p(st, C.c_float), C.c_float(k),
+                                            C.c_float(A), C.c_float(lam), C.c_int(mode), C.c_uint64(seed),
+                                            C.c_int(scheme), _p(vq, C.c_int8), _p(qg, C.c_int8),
+                                            _p(s_chan, C.c_float), _p(s_glob, C.c_float), _p(cls, C.c_uint8),
+                                            _p(stats, C.c_float), _p(frag, C.c_uint8))
     _chk(rc, "quantize_grad")
     if frag is None:
         frag = np.zeros(Cc, np.uint8)

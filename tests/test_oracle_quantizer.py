@@ -342,3 +342,101 @@ def test_per_channel_scales_beat_a_global_scale_on_mixed_channels(ref):
     per_ch = lambda r: np.abs(r - dY).mean(axis=(0, 2, 3)) / np.abs(dY).mean(axis=(0, 2, 3))
     assert np.median(per_ch(rec_v)) < 0.2 * np.median(per_ch(rec_g))
     assert out.fragile.sum() == 0
+
+
+# ----------------------------------------------------------------------------- ablation schemes (experiments, "Ablation study")
+
+def _mixed_gradient(seed, shape=(3, 5, 9, 7)):
+    # channels of very different spread, one of them long-tailed
+    rng = np.random.default_rng(seed)
+    N, C, H, W = shape
+    g = rng.normal(0, 1.0, shape) * (10.0 ** rng.uniform(-4, -1, (1, C, 1, 1)))
+    lap = rng.laplace(0, 1e-3, (N, H, W))
+    g[:, C - 1] = np.where(rng.random((N, H, W)) < 0.02, 40 * lap, lap)
+    return g.astype(np.float32)
+
+
+def test_gq_scheme_is_the_global_copy_twice(ref):
+    # the baseline quantizes the whole gradient with |g|max of the tensor: with nearest rounding the copy
+    # for dW then holds the very codes of the copy for dX
+    g = _mixed_gradient(21)
+    C = g.shape[1]
+    out = ref.quantize_grad(g, np.full(C, 7.0, np.float32), scheme=ref.SCHEME_GQ)
+    top = np.abs(g).max()
+    assert out.s_global == top and np.all(out.s_chan == top) and np.all(out.s_state == top)
+    assert np.array_equal(out.vq, out.qg)
+    base = ref.quantize_grad(g, np.zeros(C, np.float32))
+    assert np.array_equal(out.qg, base.qg) and out.s_global == base.s_global
+    # what decides nothing is still reported per channel, as Algorithm 1 computes it
+    assert np.array_equal(out.cls, base.cls) and np.array_equal(out.stats, base.stats)
+
+
+def test_gvq_scheme_scales_every_channel_by_its_own_maximum(ref):
+    g = _mixed_gradient(22)
+    C = g.shape[1]
+    out = ref.quantize_grad(g, np.full(C, 7.0, np.float32), scheme=ref.SCHEME_GVQ)
+    gmax = np.abs(g).max(axis=(0, 2, 3))
+    assert np.array_equal(out.s_chan, gmax) and np.array_equal(out.s_state, gmax)   # no clipping, no history
+    for c in range(C):
+        assert np.abs(out.vq[:, c]).max() == 127                    # the largest element of a channel is a grid end
+        one = ref.quantize_grad(g[:, c:c + 1], np.zeros(1, np.float32), scheme=ref.SCHEME_GQ)
+        assert np.array_equal(out.vq[:, c:c + 1], one.qg)           # = the baseline applied to the channel alone
+    base = ref.quantize_grad(g, np.zeros(C, np.float32))
+    assert np.array_equal(out.qg, base.qg)
+    # Algorithm 1 differs from it only on the clipped (Inverted-T) channels
+    same = base.cls == ref.GAUSS
+    assert (~same).any() and np.array_equal(out.vq[:, same], base.vq[:, same])
+
+
+def test_mcs_scheme_is_algorithm_1_on_the_tensor_taken_as_one_channel(ref):
+    # layer-wise clipping: the whole tensor is one population.  Reshaped to a single channel (same memory order)
+    # the per-channel algorithm, pinned above, must give the same class, clip value and codes.
+    for seed, prev in ((23, 0.0), (24, 0.004)):
+        g = _mixed_gradient(seed)
+        N, C, H, W = g.shape
+        if seed == 24:
+            g[:] = np.random.default_rng(seed).laplace(0, 1e-3, g.shape) * np.where(
+                np.random.default_rng(seed + 1).random(g.shape) < 0.01, 30, 1)
+        st = np.full(C, prev, np.float32)
+        st[1:] = 99.0                                                   # only entry 0 is the layer's history
+        out = ref.quantize_grad(g, st, scheme=ref.SCHEME_MCS)
+        flat = ref.quantize_grad(g.reshape(1, 1, N * C * H, W), np.array([prev], np.float32))
+        assert np.all(out.cls == flat.cls[0]) and np.all(out.s_chan == flat.s_chan[0])
+        assert np.all(out.s_state == flat.s_state[0])
+        assert np.array_equal(out.vq.reshape(-1), flat.vq.reshape(-1))
+        assert np.array_equal(out.stats, np.broadcast_to(flat.stats, (C, 4)))
+        assert np.array_equal(out.qg.reshape(-1), flat.qg.reshape(-1)) and out.s_global == flat.s_global
+        if seed == 24:
+            assert flat.cls[0] == ref.INVT and out.s_chan[0] < out.s_global    # the clipped branch is exercised
+
+
+def test_schemes_in_stochastic_mode_and_scheme_zero(ref):
+    g = _mixed_gradient(25)
+    C = g.shape[1]
+    z = np.zeros(C, np.float32)
+    a = ref.quantize_grad(g, z, mode=ref.ROUND_STOCHASTIC, seed=5)
+    b = ref.quantize_grad(g, z, mode=ref.ROUND_STOCHASTIC, seed=5, scheme=ref.SCHEME_DAQ)
+    assert np.array_equal(a.vq, b.vq) and np.array_equal(a.s_chan, b.s_chan)
+    q = ref.quantize_grad(g, z, mode=ref.ROUND_STOCHASTIC, seed=5, scheme=ref.SCHEME_GQ)
+    # same scale, independent random numbers for the two copies: equal up to one step, not identical
+    d = np.abs(q.vq.astype(int) - q.qg.astype(int))
+    assert d.max() == 1 and 0.05 < (d > 0).mean() < 0.6
+    n, c, h, w = 2, 3, 4, 5
+    idx = ((n * C + c) * g.shape[2] + h) * g.shape[3] + w
+    assert q.vq[n, c, h, w] == ref.quantize_one(float(g[n, c, h, w]), q.s_global, 1, ref.uniform24(5, 0, idx))
+
+
+def test_ablation_ordering_of_quantization_error(ref):
+    # the ablation's first finding: treating channels separately lowers the quantization error of the baseline
+    g = _mixed_gradient(26, (4, 8, 12, 12))
+    C = g.shape[1]
+    err = {}
+    for name, sc in (("gq", ref.SCHEME_GQ), ("gvq", ref.SCHEME_GVQ), ("daq", ref.SCHEME_DAQ), ("mcs", ref.SCHEME_MCS)):
+        out = ref.quantize_grad(g, np.zeros(C, np.float32), scheme=sc)
+        rec = out.vq.astype(np.float64) * (out.s_chan.reshape(1, -1, 1, 1).astype(np.float64) / 127)
+        err[name] = (np.abs(rec - g).mean(axis=(0, 2, 3)) / np.abs(g).mean(axis=(0, 2, 3)))
+    assert np.median(err["gvq"]) < 0.2 * np.median(err["gq"])
+    assert np.all(err["gvq"] <= err["gq"] * (1 + 1e-9))
+    # without history the first iteration clips at |g|max everywhere: Algorithm 1 and its layer-wise form
+    # coincide with GVQ and GQ there
+    assert np.array_equal(err["daq"], err["gvq"]) and np.array_equal(err["mcs"], err["gq"])
