@@ -34,6 +34,20 @@ MEASURED_TRAFFIC = {
 }
 
 
+def quantizer_for(scheme: str):
+    """(callable, entry point name): daq_quantize_grad, or daq_quantize_grad_scheme bound to an ablation variant."""
+    from paper_2102_04782_amd import binding as daq
+
+    if scheme == "daq":
+        return daq.quantize_grad, "daq_quantize_grad"
+    code = {"gq": daq.SCHEME_GQ, "gvq": daq.SCHEME_GVQ, "mcs": daq.SCHEME_MCS}[scheme]
+
+    def quantize(d, dY, st, **kw):
+        return daq.quantize_grad_scheme(d, dY, st, code, **kw)
+
+    return quantize, f"daq_quantize_grad_scheme({scheme})"
+
+
 def sweep(args, dev) -> int:
     """Whole-network pass: the backward step of every conv layer of a config, back to back per shape.
 
@@ -45,6 +59,7 @@ def sweep(args, dev) -> int:
     from paper_2102_04782_amd import workloads as wl
 
     layers = wl.config_layers(args.config)
+    quantize, _ = quantizer_for(args.scheme)
     steps = max(3, min(args.steps, 20))
     seen, out_layers = {}, []
     tot_wall = tot_ops = 0.0
@@ -76,7 +91,7 @@ def sweep(args, dev) -> int:
                     pass
 
             def step():
-                q = daq.quantize_grad(d, dY, st, out=out)
+                q = quantize(d, dY, st, out=out)
                 if args.dx_bf16 and bf16_ok:
                     daq.conv_bwd_filter_int8(d, qx, one, q.vq, q.s_chan, dW=dW, workspace=ws_f)
                     daq.conv_bwd_data_int8_bf16(d, q.qg, q.s_global, qw, one, dX=dXh, workspace=ws_d)
@@ -146,6 +161,9 @@ def main() -> int:
     ap.add_argument("--dx-bf16", action="store_true",
                     help="store the data gradient as bfloat16 (daq_conv_bwd_data_int8_bf16: an option beside the method, "
                          "which returns fp32 gradients; reported for comparison, never the default)")
+    ap.add_argument("--scheme", default="daq", choices=("daq", "gq", "gvq", "mcs"),
+                    help="rule for the per-channel clip values: Algorithm 1 (default) or one of the ablation study's "
+                         "variants through daq_quantize_grad_scheme (global baseline, per-channel maximum, layer-wise clipping)")
     ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
                     help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--sweep", action="store_true",
@@ -173,6 +191,7 @@ def main() -> int:
     daq.lib()  # fail loudly if the HIP library is missing
     if args.sweep:
         return sweep(args, dev)
+    quantize, quantize_name = quantizer_for(args.scheme)
 
     layer, X, W, dY, st = wl.make_inputs(args.config, args.layer)
     d = daq.ConvDesc.make(*layer.desc_fields())
@@ -198,7 +217,7 @@ def main() -> int:
         # the two convolutions share no data.  fork=False is the plain reference schedule: the three entry points
         # one after the other on one stream.
         r = i % R
-        q = daq.quantize_grad(d, dYs[r], states[r], out=outs[r], stream=main_s)
+        q = quantize(d, dYs[r], states[r], out=outs[r], stream=main_s)
         if combined and fork:
             daq.conv_bwd_int8(d, fwd.qx_cnhw, fwd.s_x, q.vq, q.s_chan, q.qg, q.s_global, fwd.qw, fwd.s_w,
                               dW=dWs[r], dX=dXs[r], workspace=ws_b, stream=main_s)
@@ -351,8 +370,9 @@ def main() -> int:
                    "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3,
                    "streams": args.streams, "hip_graph": bool(args.graph),
                    "dX": "bf16" if args.dx_bf16 else "fp32",
-                   "calls": "daq_quantize_grad + daq_conv_bwd_int8" if combined else
-                            "daq_quantize_grad + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8"},
+                   "scheme": args.scheme,
+                   "calls": f"{quantize_name} + daq_conv_bwd_int8" if combined else
+                            f"{quantize_name} + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8"},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "quant_GBps_effective_6B": round(6.0 * E_Y / (quant_us * 1e-6) / 1e9, 1) if quant_us else None,
         "quant_us": round(quant_us, 2),
@@ -378,7 +398,8 @@ def main() -> int:
         passes, cpu_s = 0, 0.0
         while cpu_s < 10.0 and passes < 64:
             t0 = time.perf_counter()
-            rq = ref.quantize_grad(dY[:n_s], st, want_fragile=False)
+            rq = ref.quantize_grad(dY[:n_s], st, want_fragile=False,
+                                   scheme={"daq": ref.SCHEME_DAQ, "gq": ref.SCHEME_GQ, "gvq": ref.SCHEME_GVQ, "mcs": ref.SCHEME_MCS}[args.scheme])
             ref.conv_bwd_filter_int8(rds, qX[:n_s], s_x, rq.vq, rq.s_chan)
             ref.conv_bwd_data_int8(rds, rq.qg, rq.s_global, qW, s_w)
             cpu_s += time.perf_counter() - t0

@@ -184,6 +184,29 @@ daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* 
                              void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_scheme -- daq_quantize_grad with the rule for the per-channel clip values s_c
+ * chosen by the caller: Algorithm 1, or one of the three variants the experiments section compares
+ * it with ("Ablation study").  qg and s_global are the same under every scheme.
+ *   DAQ_SCHEME_DAQ  Algorithm 1 (what daq_quantize_grad computes).
+ *   DAQ_SCHEME_GQ   the baseline, global quantization: s_c = max over channels of |g|max_c, so the
+ *                   copy for dW is quantized like the copy for dX.
+ *   DAQ_SCHEME_GVQ  vectorized quantization with the baseline's rule per channel: s_c = |g|max_c.
+ *   DAQ_SCHEME_MCS  Magnitude-aware Clipping on the layer-wise gradient: |g|max, sigma and the tail
+ *                   mass P = #{|g| > sigma} / (N*Cout*Hout*Wout) of the whole tensor taken as one
+ *                   population give one class (Eq. "judge") and one clip value (Eq. "gaus" / Eq.
+ *                   "fats") that every channel uses.  The history is s_state[0].
+ * s_state[c] <- s_c under every scheme.  cls and stats: under GQ and GVQ the per-channel values of
+ * Algorithm 1 (they decide nothing there); under MCS every channel's entry holds the layer's.
+ * All other arguments, the workspace and the error codes as for daq_quantize_grad; an unknown scheme
+ * is DAQ_ERR_INVALID_ARG.
+ * ------------------------------------------------------------------------------------------- */
+typedef enum { DAQ_SCHEME_DAQ = 0, DAQ_SCHEME_GQ = 1, DAQ_SCHEME_GVQ = 2, DAQ_SCHEME_MCS = 3 } daq_scheme;
+daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
+                                    float lambda, daq_round mode, uint64_t seed, daq_scheme scheme, int8_t* vq,
+                                    int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * daq_conv_fwd_int8 -- forward pass of the quantized layer (dataflow figure; the inputs that
  * Algorithm 1 requires).  s_x = max|X|, s_w = max|W| (global quantization, nearest rounding),
  * Y = (int32 conv of the codes) * (s_x/127) * (s_w/127).

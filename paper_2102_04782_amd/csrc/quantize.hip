@@ -34,6 +34,9 @@ struct QuantWs {
     float* sigma;         // [C]
     float* s_prev;        // [C]  copy of the clip state taken before anything overwrites it
     uint32_t* pred;       // [C]  class the counting pass assumed when it wrote the per-channel copy early (see k_count_qg)
+    float* layer;         // [8]  whole-tensor values for the ablation schemes: |g|max (not zeroed when tiny), mean, sigma,
+                          //      tail mass P, clip value, class
+    uint32_t* layer_cnt;  // [counting waves]  #{|g| > sigma} over all 16 channels of a counting wave (layer-wise clipping)
     float* part_max;      // [C][slabs]
     double* part_s1;      // [C][slabs]
     double* part_s2;      // [C][slabs]
@@ -42,6 +45,7 @@ struct QuantWs {
     int slabs;            // statistics workgroups (partials) per channel
     int tiles;            // 64-pixel tiles of the flattened (n, h*w) axis
     int cgroups;          // counting workgroups per block of 64 channels
+    int scheme;           // daq_scheme the launches of this call follow
     int64_t total_bytes;
 };
 
@@ -64,7 +68,8 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     w.sigma = w.mean + C;
     w.s_prev = w.sigma + C;
     w.pred = (uint32_t*)(w.s_prev + C);
-    p += round_up((int64_t)5 * C * 4, 256);
+    w.layer = (float*)(w.pred + C);
+    p += round_up(((int64_t)5 * C + 8) * 4, 256);
     w.part_s1 = (double*)p;
     w.part_s2 = w.part_s1 + (int64_t)C * w.slabs;
     p += round_up((int64_t)2 * C * w.slabs * 8, 256);
@@ -72,6 +77,8 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     p += round_up((int64_t)C * w.slabs * 4, 256);
     w.part_cnt = (uint32_t*)p;
     p += round_up((int64_t)C * w.cgroups * 4, 256);
+    w.layer_cnt = (uint32_t*)p;
+    p += round_up((int64_t)cb * w.cgroups * (kBlock / kWave) * 4, 256);
     w.total_bytes = p - (char*)base;
     return w;
 }
@@ -400,15 +407,20 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
                 if (p == 0) ws.pred[c] = (uint32_t)guess;
             }
         }
-        l_sigma[tid] = sig;
+        // layer-wise clipping compares every element with the standard deviation of the whole tensor
+        l_sigma[tid] = ws.scheme == DAQ_SCHEME_MCS ? ws.layer[2] : sig;
     }
     __syncthreads();
     if (!scale_ptr) sg = fmaxf(fmaxf(l_max[0], l_max[1]), fmaxf(l_max[2], l_max[3]));
+    const float sg_raw = sg;
     if (!(sg >= kTinyScale)) sg = 0.0f;
     if (COUNT && blockIdx.x == 0) {
         // the clip state is overwritten by the packing pass: keep what this iteration started from
         for (int i = tid; i < C; i += kBlock) ws.s_prev[i] = s_state[i];
-        if (tid == 0) *s_global = sg;
+        if (tid == 0) {
+            *s_global = sg;
+            ws.layer[0] = sg_raw;
+        }
     }
     const float inv = inv_scale(sg);
     // sigma of the wave's 16 channels.  Lanes without a pixel and channels past C hold x = 0, and
@@ -510,7 +522,76 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
         uint32_t mine = 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) mine = (lane == i) ? cnt[i] : mine;
-        if (lane < 16 && c0 + lane < C) ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = mine;
+        const bool mine_ok = lane < 16 && c0 + lane < C;
+        if (mine_ok) ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = mine;
+        if (ws.scheme == DAQ_SCHEME_MCS) {   // uniform: one population; its count is the sum over all counting waves
+            const uint32_t all = wave_sum_u32(mine_ok ? mine : 0u);
+            if (lane == 0) ws.layer_cnt[blockIdx.x * (kBlock / kWave) + wave] = all;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Layer-wise Magnitude-aware Clipping (ablation study, the variant without vectorized quantization): the
+// tensor is one population.  Two single-workgroup launches around the counting pass: before it, the statistics
+// partials of all channels are folded into the tensor's mean and sigma (fixed summation order, so the result does
+// not depend on the launch); after it, the counts of the counting waves into the tail mass, the class (Eq.
+// "judge") and the clip value (Eq. "gaus" / Eq. "fats", with s_state[0] as the history).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_layer_stats(QuantWs ws, int C, double Mtot) {
+    __shared__ double l_1[kBlock], l_2[kBlock];
+    const int tid = threadIdx.x;
+    double s1 = 0.0, s2 = 0.0;
+    const int total = C * ws.slabs;
+    for (int i = tid; i < total; i += kBlock) {
+        s1 += ws.part_s1[i];
+        s2 += ws.part_s2[i];
+    }
+    l_1[tid] = s1;
+    l_2[tid] = s2;
+    __syncthreads();
+    for (int h = kBlock / 2; h > 0; h >>= 1) {
+        if (tid < h) {
+            l_1[tid] += l_1[tid + h];
+            l_2[tid] += l_2[tid + h];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const double mu = l_1[0] / Mtot;
+        double var = l_2[0] / Mtot - mu * mu;
+        if (var < 0.0) var = 0.0;
+        ws.layer[1] = (float)mu;
+        ws.layer[2] = (float)sqrt(var);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_layer_decide(QuantWs ws, int waves, double Mtot, float k, float A, float lambda) {
+    __shared__ uint32_t l_c[kBlock];
+    const int tid = threadIdx.x;
+    uint32_t cnt = 0;
+    for (int base = 0; base < waves; base += 8 * kBlock) {   // eight loads in flight per thread
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * kBlock + tid;
+            v[u] = i < waves ? ws.layer_cnt[i] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cnt += v[u];
+    }
+    l_c[tid] = cnt;
+    __syncthreads();
+    for (int h = kBlock / 2; h > 0; h >>= 1) {
+        if (tid < h) l_c[tid] += l_c[tid + h];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const double n = (double)l_c[0];
+        const int klass = (n > (double)lambda * Mtot) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
+        ws.layer[3] = (float)(n / Mtot);
+        ws.layer[4] = clip_rule(klass, ws.layer[0], ws.s_prev[0], k, A);
+        ws.layer[5] = (float)klass;
     }
 }
 
@@ -542,6 +623,22 @@ struct ClipArgs {
 __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& ca, int c, double Md, bool publish,
                                             uint32_t* l_cnt, int* klass_out = nullptr) {
     const int tid = threadIdx.x;
+    if (ws.scheme == DAQ_SCHEME_MCS) {   // uniform: the layer's clip value, decided by k_layer_decide, for every channel
+        const float s = ws.layer[4];
+        if (klass_out) *klass_out = (int)ws.layer[5];
+        if (publish && tid == 0) {
+            ca.s_state[c] = s;
+            ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
+            ca.cls[c] = (uint8_t)ws.layer[5];
+            if (ca.stats) {
+                ca.stats[4 * c + 0] = ws.layer[0];
+                ca.stats[4 * c + 1] = ws.layer[1];
+                ca.stats[4 * c + 2] = ws.layer[2];
+                ca.stats[4 * c + 3] = ws.layer[3];
+            }
+        }
+        return s;
+    }
     uint32_t cnt = 0;
     static_assert(kCountGrid <= 4 * kBlock, "a thread sums at most four count partials");
     {
@@ -560,7 +657,11 @@ __device__ __forceinline__ float clip_value(const QuantWs& ws, const ClipArgs& c
     const int klass = ((double)cnt > (double)ca.lambda * Md) ? DAQ_CLASS_GAUSS : DAQ_CLASS_INVT;
     if (klass_out) *klass_out = klass;   // every thread holds the same sum, hence the same class
     const float gm = ws.gmax[c];
-    const float s = clip_rule(klass, gm, ws.s_prev[c], ca.k, ca.A);
+    // ablation baselines: the tensor's |g|max for every channel (GQ) or the channel's own without clipping (GVQ);
+    // class and statistics are reported as Algorithm 1 computes them
+    const float s = ws.scheme == DAQ_SCHEME_GQ    ? ws.layer[0]
+                    : ws.scheme == DAQ_SCHEME_GVQ ? gm
+                                                  : clip_rule(klass, gm, ws.s_prev[c], ca.k, ca.A);
     if (publish && tid == 0) {
         ca.s_state[c] = s;
         ca.s_chan[c] = (s >= kTinyScale) ? s : 0.0f;
@@ -1009,13 +1110,15 @@ using namespace daq;
 // ---------------------------------------------------------------------------------------------
 // Algorithm 1, per-channel loop + vectorized and global quantization
 // ---------------------------------------------------------------------------------------------
-extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
-                                        float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg,
-                                        float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
-                                        size_t workspace_bytes, void* stream) {
+extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,
+                                               float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
+                                               int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
+                                               float* stats, void* workspace, size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
+    if (scheme != DAQ_SCHEME_DAQ && scheme != DAQ_SCHEME_GQ && scheme != DAQ_SCHEME_GVQ && scheme != DAQ_SCHEME_MCS)
+        return DAQ_ERR_INVALID_ARG;
     if (((uintptr_t)dY & 3u) || ((uintptr_t)vq & 15u) || ((uintptr_t)qg & 15u)) return DAQ_ERR_INVALID_ARG;
     daq_layout Lv, Lg;
     daq_status rc = daq_layout_vq(desc, &Lv);
@@ -1034,6 +1137,8 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     const bool stoch = (mode == DAQ_ROUND_STOCHASTIC);
     const bool qg_nhwc = (Lg.kind == DAQ_LAYOUT_NHWC);
     QuantWs ws = carve_quant_ws(workspace, C, N, HW);
+    ws.scheme = (int)scheme;
+    const double Mtot = (double)N * (double)C * (double)HW;
 
     // S1: statistics partials, at most 16 per channel
     const FastDiv div_hw = make_fastdiv((uint32_t)HW);
@@ -1047,6 +1152,9 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     else
         DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
 
+    if (scheme == DAQ_SCHEME_MCS)
+        DAQ_LAUNCH("layer_stats", st, hipLaunchKernelGGL(k_layer_stats, dim3(1), dim3(kBlock), 0, st, ws, C, Mtot));
+
     // S2 (+ the NHWC global copy); folds the statistics itself
     const int CB = (int)ceil_div(C, 64);
     const dim3 cgrid((unsigned)(CB * ws.cgroups));
@@ -1056,7 +1164,7 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     // latency, not by bytes, and keep the leaner counting kernel.
     static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");   // tuning override, read once: smallest gradient (elements)
     const int64_t early_min = early_env ? atoll(early_env) : kEarlyVqMinElems;
-    const bool early = qg_nhwc && rows_vector(Lv, dY) != 0 && (int64_t)N * C * HW >= early_min &&
+    const bool early = scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY) != 0 && (int64_t)N * C * HW >= early_min &&
                        Lv.lead + (int64_t)N * Lv.img_rows * Lv.row_pitch < ((int64_t)1 << 32);
     EarlyVq ev{};
     if (early) {
@@ -1080,6 +1188,10 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
         DAQ_COUNT_LAUNCH(false, false, false);
     }
 #undef DAQ_COUNT_LAUNCH
+    if (scheme == DAQ_SCHEME_MCS)
+        DAQ_LAUNCH("layer_decide", st,
+                   hipLaunchKernelGGL(k_layer_decide, dim3(1), dim3(kBlock), 0, st, ws, (int)cgrid.x * (kBlock / kWave), Mtot, k, A,
+                                      lambda));
 
     // S3 + S4 + S5: discriminator, clip rule and the per-channel copy in CNHW (and the global copy for
     // depthwise layers, whose data gradient also runs channel-major)
@@ -1091,4 +1203,12 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
     if (!qg_nhwc && !fused)
         rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);
     return rc;
+}
+
+extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
+                                        float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg,
+                                        float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+    return daq_quantize_grad_scheme(desc, dY, s_state, k, A, lambda, mode, seed, DAQ_SCHEME_DAQ, vq, qg, s_chan, s_global,
+                                    cls, stats, workspace, workspace_bytes, stream);
 }

@@ -152,3 +152,29 @@ def test_quantize_grad_large_tensor_with_wrong_class_guesses(shape, lam):
     assert torch.equal(_logical_view(daq.layout_vq(d), out.vq), torch.from_numpy(r.vq).to(device)), "vq codes"
     assert torch.equal(_logical_view(daq.layout_qg(d), out.qg), torch.from_numpy(r.qg).to(device)), "qg codes"
     assert daq.layout_vq(d).padding_is_zero(out.vq), "vq padding bytes must be zero"
+
+
+@pytest.mark.parametrize("scheme", [daq.SCHEME_GQ, daq.SCHEME_GVQ, daq.SCHEME_MCS], ids=["gq", "gvq", "mcs"])
+@pytest.mark.parametrize("config", [2, 3])
+def test_ablation_schemes_at_benchmark_sizes(config, scheme):
+    """The three ablation variants of the quantizer on the benchmark's gradient tensors, whole-tensor against the oracle."""
+    device = torch.device("cuda:0")
+    layer = wl.config_layers(config)[0]
+    d = daq.ConvDesc.make(*layer.desc_fields())
+    seed = wl.seed_for(config, 0)
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    r = ref.quantize_grad(dY, st, scheme=scheme)
+    assert r.fragile.sum() == 0
+    st_dev = torch.from_numpy(st.copy()).to(device)
+    out = daq.quantize_grad_scheme(d, torch.from_numpy(dY).to(device), st_dev, scheme)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.stats.cpu().numpy(), r.stats)
+    assert np.array_equal(out.cls.cpu().numpy(), r.cls)
+    assert np.array_equal(out.s_chan.cpu().numpy(), r.s_chan) and out.s_global.item() == r.s_global
+    assert np.array_equal(st_dev.cpu().numpy(), r.s_state)
+    Lv, Lg = daq.layout_vq(d), daq.layout_qg(d)
+    want_v = torch.from_numpy(r.vq).to(device)
+    want_g = torch.from_numpy(r.qg).to(device)
+    assert torch.equal(_logical_view(Lv, out.vq), want_v), "vq codes"
+    assert torch.equal(_logical_view(Lg, out.qg), want_g), "qg codes"

@@ -39,12 +39,16 @@ def t(a):
 
 # ------------------------------------------------------------------------------------------------ quantizer
 
-def check_quantize_grad(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, check_padding=True, degenerate=False):
+def check_quantize_grad(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, check_padding=True, degenerate=False,
+                        scheme=None):
     d, _ = descs(layer)
     st_dev = t(st.copy())
-    out = daq.quantize_grad(d, t(dY), st_dev, k, A, lam, mode, seed)
+    if scheme is None:
+        out = daq.quantize_grad(d, t(dY), st_dev, k, A, lam, mode, seed)
+    else:
+        out = daq.quantize_grad_scheme(d, t(dY), st_dev, scheme, k, A, lam, mode, seed)
     torch.cuda.synchronize()
-    r = ref.quantize_grad(dY, st, k, A, lam, mode, seed)
+    r = ref.quantize_grad(dY, st, k, A, lam, mode, seed, scheme=scheme or ref.SCHEME_DAQ)
     # sigma == 0 channels are fragile by construction (any negative threshold counts everything)
     assert degenerate or r.fragile.sum() == 0, "seed yields a channel whose class flips under a 1-ulp change of sigma"
     stats = out.stats.cpu().numpy()
@@ -155,6 +159,74 @@ def test_state_carries_across_iterations_and_runs_are_deterministic():
     r2 = ref.quantize_grad(dY, r1.s_state)
     close(s1.cpu().numpy(), r2.s_state, "state after two iterations")
     assert np.array_equal(daq.layout_vq(d).unpack(b.vq), r2.vq)
+
+
+# ------------------------------------------------------------------------------------------------ ablation schemes
+
+SCHEMES = [(daq.SCHEME_DAQ, "daq"), (daq.SCHEME_GQ, "gq"), (daq.SCHEME_GVQ, "gvq"), (daq.SCHEME_MCS, "mcs")]
+
+
+def test_scheme_constants_agree():
+    assert (daq.SCHEME_DAQ, daq.SCHEME_GQ, daq.SCHEME_GVQ, daq.SCHEME_MCS) == \
+           (ref.SCHEME_DAQ, ref.SCHEME_GQ, ref.SCHEME_GVQ, ref.SCHEME_MCS)
+
+
+@pytest.mark.parametrize("scheme", [s for s, _ in SCHEMES], ids=[n for _, n in SCHEMES])
+def test_quantize_grad_schemes_config1(scheme):
+    layer, X, W, dY, st = wl.make_inputs(1)
+    check_quantize_grad(layer, dY, st, scheme=scheme)
+    check_quantize_grad(layer, dY, np.zeros_like(st), scheme=scheme)
+    check_quantize_grad(layer, dY, st, k=1.5, A=0.8, scheme=scheme)
+    check_quantize_grad(layer, dY, 10 * st, k=1.5, A=0.8, scheme=scheme)
+    check_quantize_grad(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=7, scheme=scheme)
+    check_quantize_grad(layer, dY, st, lam=0.0, scheme=scheme)
+    check_quantize_grad(layer, dY, st, lam=1.0, scheme=scheme)          # the layer as a whole takes the clipped branch
+
+
+@pytest.mark.parametrize("scheme", [s for s, _ in SCHEMES[1:]], ids=[n for _, n in SCHEMES[1:]])
+@pytest.mark.parametrize("layer", ODD_LAYERS, ids=lambda l: l.name)
+def test_quantize_grad_schemes_ragged_shapes(layer, scheme):
+    seed = wl.seed_for(11, ODD_LAYERS.index(layer))
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    check_quantize_grad(layer, dY, st, scheme=scheme)
+    check_quantize_grad(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=5, scheme=scheme)
+
+
+@pytest.mark.parametrize("scheme", [s for s, _ in SCHEMES[1:]], ids=[n for _, n in SCHEMES[1:]])
+def test_quantize_grad_schemes_degenerate_tensors(scheme):
+    layer = wl.Layer("deg", 2, 4, 8, 8, 6, 3, 3, 1, 1)
+    rng = np.random.default_rng(3)
+    dY = rng.normal(0, 1e-2, layer.y_shape).astype(np.float32)
+    dY[:, 0] = 0.0
+    dY[:, 1] = 0.5
+    dY[:, 2] = np.float32(1e-38)
+    dY[:, 3, 0, 0] = 1e4
+    st = np.zeros(6, np.float32)
+    check_quantize_grad(layer, dY, st, degenerate=True, scheme=scheme)
+    check_quantize_grad(layer, np.zeros_like(dY), st, degenerate=True, scheme=scheme)
+    tiny = np.full_like(dY, np.float32(1e-38))                            # every scale below 2^-100
+    check_quantize_grad(layer, tiny, st, degenerate=True, scheme=scheme)
+
+
+def test_layerwise_clipping_takes_the_long_tailed_branch():
+    # a tensor that is long-tailed as a whole: the layer-wise scheme clips below |g|max, with s_state[0] as history
+    layer = wl.Layer("tail", 4, 8, 20, 20, 24, 3, 3, 1, 1)
+    rng = np.random.default_rng(17)
+    dY = (rng.laplace(0, 1e-3, layer.y_shape) * np.where(rng.random(layer.y_shape) < 0.01, 30, 1)).astype(np.float32)
+    st = np.full(24, 99.0, np.float32)
+    st[0] = 0.5 * np.abs(dY).max()
+    out, r = check_quantize_grad(layer, dY, st, scheme=daq.SCHEME_MCS)
+    assert r.cls[0] == ref.INVT and r.s_chan[0] < r.s_global
+    assert np.isclose(r.s_chan[0], 0.9 * np.abs(dY).max(), rtol=1e-6)        # (1 - kA) * history + A * |g|max
+    assert np.all(r.s_chan == r.s_chan[0]) and np.all(r.s_state == r.s_chan[0])
+
+
+def test_unknown_scheme_is_refused():
+    layer, X, W, dY, st = wl.make_inputs(1)
+    d, _ = descs(layer)
+    with pytest.raises(daq.DaqError):
+        daq.quantize_grad_scheme(d, t(dY), t(st.copy()), 4)
 
 
 # ------------------------------------------------------------------------------------------------ convolutions

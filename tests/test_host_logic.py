@@ -175,6 +175,10 @@ def test_workspace_and_validation_without_a_gpu():
     assert lib.daq_conv_bwd_data_int8(C.byref(d), odd, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
     assert lib.daq_conv_bwd_filter_int8(C.byref(d), one, one, odd, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
     assert lib.daq_quantize_grad(C.byref(d), one, one, 1.0, 0.8, 0.3, 0, 0, odd, one, one, one, one, None, one, 1 << 20, None) == daq.ERR_INVALID_ARG
+    sch = lambda scheme, ws=one, wsb=1 << 20: lib.daq_quantize_grad_scheme(C.byref(d), one, one, 1.0, 0.8, 0.3, 0, 0, scheme, one, one,
+                                                                            one, one, one, None, ws, wsb, None)
+    assert sch(4) == daq.ERR_INVALID_ARG and sch(-1) == daq.ERR_INVALID_ARG
+    assert all(sch(s, wsb=8) == daq.ERR_WORKSPACE for s in range(4))           # a known scheme gets as far as the workspace check
     assert daq.status_string(daq.ERR_WORKSPACE).startswith("workspace")
 
 
