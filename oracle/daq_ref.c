@@ -717,6 +717,26 @@ int daq_ref_conv_bwd_data_int8(const ref_conv_desc* d, const int8_t* qG, float s
     return REF_OK;
 }
 
+/* Depthwise variant (the MobileNetV2 paragraph's layers, groups = Cin = Cout): input-gradient channel c is
+ * a function of output-gradient channel c alone, so the per-channel copy and its clip values can serve for
+ * G_X too:  G_X[n,c] = (sum over taps of vq[n,c] * qW[c]) * s_w/127 * s_chan[c]/127.
+ * An option beside Algorithm 1, which quantizes G with the global |g|max for G_X. */
+int daq_ref_conv_bwd_data_int8_chan(const ref_conv_desc* d, const int8_t* vq, const float* s_chan, const int8_t* qW,
+                                    float s_w, float* dX, int32_t* acc_out, int* overflow) {
+    if (!desc_ok(d) || !dX || !acc_out || !s_chan) return REF_BAD_ARG;
+    if (d->groups != d->Cin || d->groups != d->Cout) return REF_BAD_ARG;
+    int rc = daq_ref_conv_bwd_data_acc(d, vq, qW, acc_out, overflow);
+    if (rc) return rc;
+    const size_t plane = (size_t)d->Hin * d->Win;
+    for (int n = 0; n < d->N; ++n)
+        for (int c = 0; c < d->Cin; ++c)
+            for (size_t i = 0; i < plane; ++i) {
+                const size_t at = ((size_t)n * d->Cin + c) * plane + i;
+                dX[at] = dq2(acc_out[at], s_w, s_chan[c]);
+            }
+    return REF_OK;
+}
+
 /* Algorithm 1: q(G_W) = q(X') (dilated conv) vq(G'), then vectorized
  * de-quantization  G_W[co] = acc[co] * s_x/127 * s_chan[co]/127. */
 int daq_ref_conv_bwd_filter_int8(const ref_conv_desc* d, const int8_t* qX, float s_x, const int8_t* vq,

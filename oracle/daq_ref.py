@@ -306,6 +306,21 @@ def conv_bwd_data_int8(d: ConvDesc, qG, s_global, qW, s_w):
     return dX, acc, bool(ovf.value)
 
 
+def conv_bwd_data_int8_chan(d: ConvDesc, vq, s_chan, qW, s_w):
+    """Depthwise layers only: data gradient from the per-channel copy, de-quantized per channel."""
+    vq, qW = _i8(vq), _i8(qW)
+    sc = _f32(s_chan)
+    assert vq.shape == d.y_shape and qW.shape == d.w_shape and sc.shape == (d.Cout,)
+    dX = np.zeros(d.x_shape, np.float32)
+    acc = np.zeros(d.x_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv_bwd_data_int8_chan(C.byref(dd), _p(vq, C.c_int8), _p(sc, C.c_float), _p(qW, C.c_int8),
+                                               C.c_float(s_w), _p(dX, C.c_float), _p(acc, C.c_int32), C.byref(ovf)),
+         "conv_bwd_data_int8_chan")
+    return dX, acc, bool(ovf.value)
+
+
 def conv_bwd_filter_int8(d: ConvDesc, qX, s_x, vq, s_chan):
     qX, vq = _i8(qX), _i8(vq)
     s_chan = _f32(s_chan)

@@ -208,3 +208,45 @@ def test_bf16_rounding_matches_the_library_conversion_and_the_tie_rule(ref):
     assert ref.bf16_bits(even)[0] == 0x3F80 and ref.bf16_bits(odd)[0] == 0x3F82
     just_above = np.array([0x3F800000 | 0x8001], np.uint32).view(np.float32)
     assert ref.bf16_bits(just_above)[0] == 0x3F81
+
+
+def test_depthwise_data_gradient_from_the_per_channel_copy(ref):
+    # groups = Cin = Cout: channel c of G_X depends on channel c of G alone.  Each channel run by itself as a dense
+    # one-channel layer through the pinned data gradient, with that channel's clip value as THE scale, must give the
+    # same bits; the per-channel call is then also closer to fp32 than the global one on channels of mixed spread.
+    for (N, Cch, H, W, k, s, p) in ((2, 5, 9, 8, 3, 1, 1), (1, 4, 11, 11, 3, 2, 1), (2, 3, 7, 7, 5, 1, 2)):
+        d = ref.ConvDesc(N, Cch, H, W, Cch, k, k, s, s, p, p, 1, 1, Cch)
+        rng = np.random.default_rng(100 + H)
+        qW, vq = _rand_codes(rng, d.w_shape), _rand_codes(rng, d.y_shape)
+        s_c = (10.0 ** rng.uniform(-4, -1, Cch)).astype(np.float32)
+        s_w = 0.37
+        dX, acc, ovf = ref.conv_bwd_data_int8_chan(d, vq, s_c, qW, s_w)
+        assert not ovf and np.array_equal(acc, ref.conv_bwd_data_acc(d, vq, qW)[0])
+        one = ref.ConvDesc(N, 1, H, W, 1, k, k, s, s, p, p, 1, 1, 1)
+        for c in range(Cch):
+            dXc, accc, _ = ref.conv_bwd_data_int8(one, vq[:, c:c + 1], float(s_c[c]), qW[c:c + 1], s_w)
+            assert np.array_equal(acc[:, c:c + 1], accc) and np.array_equal(dX[:, c:c + 1], dXc)
+    # not a depthwise layer: refused
+    dense = ref.ConvDesc(1, 4, 6, 6, 4, 3, 3, 1, 1, 1, 1)
+    with pytest.raises(Exception):
+        ref.conv_bwd_data_int8_chan(dense, _rand_codes(rng, dense.y_shape), np.ones(4, np.float32),
+                                    _rand_codes(rng, dense.w_shape), 1.0)
+
+
+def test_per_channel_scales_help_the_depthwise_data_gradient(ref):
+    # channels of very different spread: quantizing G per channel reconstructs the fp32 data gradient of a
+    # depthwise layer better than the global scale does (the argument for the variant)
+    N, Cch, H, W = 2, 6, 12, 12
+    d = ref.ConvDesc(N, Cch, H, W, Cch, 3, 3, 1, 1, 1, 1, 1, 1, Cch)
+    rng = np.random.default_rng(31)
+    G = (rng.normal(0, 1, d.y_shape) * (10.0 ** np.linspace(-4, -1, Cch)).reshape(1, -1, 1, 1)).astype(np.float32)
+    Wt = rng.normal(0, 0.2, d.w_shape).astype(np.float32)
+    q = ref.quantize_grad(G, np.zeros(Cch, np.float32))
+    qW, s_w = ref.quantize_tensor(Wt)
+    exact = torch.nn.grad.conv2d_input(d.x_shape, torch.from_numpy(Wt).double(), torch.from_numpy(G).double(),
+                                       stride=1, padding=1, groups=Cch).numpy()
+    dX_c = ref.conv_bwd_data_int8_chan(d, q.vq, q.s_chan, qW, s_w)[0]
+    dX_g = ref.conv_bwd_data_int8(d, q.qg, q.s_global, qW, s_w)[0]
+    rel = lambda a: np.abs(a - exact).mean(axis=(0, 2, 3)) / np.abs(exact).mean(axis=(0, 2, 3))
+    assert np.all(rel(dX_c) < 0.05)
+    assert np.median(rel(dX_g)) > 5 * np.median(rel(dX_c))
