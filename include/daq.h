@@ -286,6 +286,25 @@ daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, const int8_t* 
                                        size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_conv_bwd_data_int8_chan -- data gradient of a depthwise layer (groups = Cin = Cout, the
+ * MobileNetV2 paragraph's layers) from the PER-CHANNEL copy of dY.  There channel c of the data
+ * gradient is a function of channel c of dY alone, so the vectorized quantization and its
+ * de-quantization carry over from Eq. "gw" to Eq. "gx":
+ *   acc as in daq_conv_bwd_data_int8 with vq in the place of qg;
+ *   dX[n,c,:,:] = acc[n,c,:,:] * ((s_w/127) * (s_chan[c]/127)).
+ * An option beside Algorithm 1, which takes the global |g|max for the data gradient: channels of
+ * small spread keep their resolution, and a caller that uses it needs no global copy for the layer.
+ * DAQ_ERR_UNSUPPORTED for any other layer, and for depthwise layers the channel-major kernels do
+ * not serve (filters above 7 x 7, strides that are not one power of two for both axes).
+ *
+ *   vq        in   int8 daq_layout_vq        s_chan in fp32 [Cout]
+ *   other arguments, alignment and the workspace as for daq_conv_bwd_data_int8
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* vq, const float* s_chan,
+                                       const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every
  * kernel the library launches is bracketed by a HIP event pair on its stream.  daq_prof_end()
  * waits for those events and fills one row per distinct kernel name.  Not thread-safe.

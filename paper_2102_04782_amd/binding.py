@@ -27,7 +27,7 @@ LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_prof_begin", "daq_prof_end", "daq_status_string",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string",
 ]
 
 
@@ -176,6 +176,7 @@ def lib():
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
+        L.daq_conv_bwd_data_int8_chan.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
         L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
@@ -353,6 +354,20 @@ def conv_bwd_data_int8_bf16(d: ConvDesc, qg: torch.Tensor, s_global: torch.Tenso
     rc = lib().daq_conv_bwd_data_int8_bf16(C.byref(d), _ptr(qg), _ptr(s_global), _ptr(qw), _ptr(s_w), _ptr(dX),
                                            _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "daq_conv_bwd_data_int8_bf16")
+    return dX
+
+
+def conv_bwd_data_int8_chan(d: ConvDesc, vq: torch.Tensor, s_chan: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,
+                            dX: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Depthwise layers: the data gradient from the per-channel copy (ERR_UNSUPPORTED for any other layer)."""
+    if dX is None:
+        dX = torch.empty(d.x_shape, dtype=torch.float32, device=vq.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD_DATA, d), vq.device)
+    rc = lib().daq_conv_bwd_data_int8_chan(C.byref(d), _ptr(vq), _ptr(s_chan), _ptr(qw), _ptr(s_w), _ptr(dX), _ptr(acc),
+                                           _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_data_int8_chan")
     return dX
 
 

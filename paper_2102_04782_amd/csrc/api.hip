@@ -102,3 +102,16 @@ extern "C" daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, con
     return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, reinterpret_cast<float*>(dX_bf16), nullptr,
                               (hipStream_t)stream, nullptr, true);
 }
+
+extern "C" daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* vq, const float* s_chan,
+                                                  const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
+                                                  void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !vq || !s_chan || !qw_packed || !s_w || !dX) return DAQ_ERR_INVALID_ARG;
+    if (!a16(vq) || !a16(qw_packed) || !a16(dX) || !a16(acc_out)) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    // only where a channel of the data gradient depends on one channel of dY: groups = Cin = Cout
+    if (!is_depthwise(*desc) || !depthwise_dx_supported(*desc)) return DAQ_ERR_UNSUPPORTED;
+    return conv_bwd_data_depthwise(*desc, vq, s_chan, qw_packed, s_w, dX, acc_out, (hipStream_t)stream, true);
+}

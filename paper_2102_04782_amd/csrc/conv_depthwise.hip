@@ -49,8 +49,9 @@ struct DxArgs {
     int s_log2;            // log2 of the (square, power-of-two) stride
     FastDiv div_wq, div_h, div_c;
     int wq;                // quads of output columns per row
-    const float* s_g;
+    const float* s_g;      // one scale, or one per channel (per_chan)
     const float* s_w;
+    int per_chan;          // the gradient is the per-channel copy: channel c is de-quantized with s_g[c]
     float* dX;
     int32_t* acc_out;
     int nt;                // large result: streaming stores
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
         acc[2] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 2), wr, acc[2]);
         acc[3] = dot4((int)__builtin_amdgcn_alignbyte(hi, lo, 3), wr, acc[3]);
     }
-    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
         const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
             }
         }
     }
-    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
         const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_any(DxArgs p) {
             }
         }
     }
-    const float scale = (*p.s_w / 127.0f) * (*p.s_g / 127.0f);
+    const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -355,7 +356,7 @@ bool depthwise_dx_supported(const daq_conv_desc& d) {
 }
 
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel) {
     daq_layout Lg;
     daq_wpack_layout Lw;
     if (daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK || Lg.kind != DAQ_LAYOUT_CNHW)
@@ -373,6 +374,7 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     a.div_h = make_fastdiv((uint32_t)d.Hin);
     a.div_c = make_fastdiv((uint32_t)d.Cin);
     a.s_g = s_g; a.s_w = s_w; a.dX = dX; a.acc_out = acc;
+    a.per_chan = per_channel ? 1 : 0;
     a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
     const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
     const dim3 grid((unsigned)ceil_div(threads, kBlock));

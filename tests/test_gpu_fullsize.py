@@ -63,6 +63,9 @@ def test_sampled_outputs_at_full_size(config, index):
     dX1 = daq.conv_bwd_data_int8(d, q.qg, q.s_global, f.qw, f.s_w)
     torch.cuda.synchronize()
     assert torch.equal(dW, dW1) and torch.equal(dX, dX1)
+    if layer.groups > 1 and layer.groups == layer.Cin == layer.Cout:
+        # depthwise: the data gradient from the per-channel copy (all scales are 127 here, so the same bits)
+        assert torch.equal(daq.conv_bwd_data_int8_chan(d, q.vq, q.s_chan, f.qw, f.s_w), dX)
     assert f.s_x.item() == 127.0 and f.s_w.item() == 127.0 and q.s_global.item() == 127.0
     assert bool((q.s_chan == 127.0).all())
 

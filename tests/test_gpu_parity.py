@@ -222,6 +222,40 @@ def test_layerwise_clipping_takes_the_long_tailed_branch():
     assert np.all(r.s_chan == r.s_chan[0]) and np.all(r.s_state == r.s_chan[0])
 
 
+DW_LAYERS = [
+    wl.Layer("dw_big", 6, 40, 28, 28, 40, 3, 3, 1, 1, 1, 40),
+    wl.Layer("dw_s2_big", 4, 24, 30, 30, 24, 3, 3, 2, 1, 1, 24),
+    wl.Layer("dw_5x5", 2, 8, 14, 14, 8, 5, 5, 1, 2, 1, 8),
+]
+
+
+@pytest.mark.parametrize("layer", DW_LAYERS, ids=lambda l: l.name)
+def test_depthwise_data_gradient_from_the_per_channel_copy_end_to_end(layer):
+    # quantizer -> data gradient, both on the GPU, against the same chain in the oracle
+    d, rd = descs(layer)
+    seed = wl.seed_for(12, DW_LAYERS.index(layer))
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    Wt = wl.make_W(layer, seed, kaiming=True)
+    X = wl.make_X(layer, seed, post_relu=True)
+    f = daq.conv_fwd_int8(d, t(X), t(Wt))
+    q = daq.quantize_grad(d, t(dY), t(st.copy()))
+    dX = daq.conv_bwd_data_int8_chan(d, q.vq, q.s_chan, f.qw, f.s_w)
+    torch.cuda.synchronize()
+    rq = ref.quantize_grad(dY, st)
+    qW, s_w = ref.quantize_tensor(Wt)
+    want = ref.conv_bwd_data_int8_chan(rd, rq.vq, rq.s_chan, qW, s_w)[0]
+    got = dX.cpu().numpy()
+    for c in range(layer.Cin):
+        close(got[:, c], want[:, c], f"channel {c}")
+    # and it is the better gradient on channels of small spread: the typical channel is far closer to the fp32 one
+    exact = torch.nn.grad.conv2d_input(d.x_shape, torch.from_numpy(Wt).double(), torch.from_numpy(dY).double(),
+                                       stride=layer.stride, padding=layer.pad, dilation=layer.dil, groups=layer.groups).numpy()
+    glob = daq.conv_bwd_data_int8(d, q.qg, q.s_global, f.qw, f.s_w).cpu().numpy()
+    err = lambda a: np.abs(a - exact).mean(axis=(0, 2, 3))
+    assert np.median(err(got) / err(glob)) < 0.5
+
+
 def test_unknown_scheme_is_refused():
     layer, X, W, dY, st = wl.make_inputs(1)
     d, _ = descs(layer)
@@ -304,6 +338,23 @@ def run_convs_on_codes(layer, qX, qW, qG, s_x, s_w, s_g, s_c):
     close(dW3.cpu().numpy(), rdW, "dW, combined call")
     close(dX3.cpu().numpy(), rdX, "dX, combined call")
     assert torch.equal(dW3, dW) and torch.equal(dX3, dX) and torch.equal(dW4, dW) and torch.equal(dX4, dX)
+    # depthwise layers: the data gradient from the per-channel copy, de-quantized per channel
+    depthwise = layer.groups > 1 and layer.groups == layer.Cin == layer.Cout
+    if depthwise and layer.kH <= 7 and layer.kW <= 7 and layer.stride & (layer.stride - 1) == 0:
+        accX5 = torch.full_like(accX, -1)
+        dX5 = daq.conv_bwd_data_int8_chan(d, vq, s_c_d, qw, s_w_d, acc=accX5)
+        dX6 = daq.conv_bwd_data_int8_chan(d, vq, s_c_d, qw, s_w_d)
+        torch.cuda.synchronize()
+        rdX5, raccX5, o5 = ref.conv_bwd_data_int8_chan(rd, qG, s_c, qW, s_w)
+        assert not o5 and np.array_equal(accX5.cpu().numpy(), raccX5), "dX accumulators, per-channel copy"
+        got = dX5.cpu().numpy()
+        for c in range(layer.Cin):                      # the tolerance is relative to each channel's own magnitude
+            close(got[:, c], rdX5[:, c], f"dX from the per-channel copy, channel {c}")
+        assert torch.equal(dX5, dX6)
+    else:   # dense and grouped layers, and depthwise ones outside the channel-major kernels (documented)
+        with pytest.raises(daq.DaqError) as e:
+            daq.conv_bwd_data_int8_chan(d, vq, s_c_d, qw, s_w_d)
+        assert e.value.code == daq.ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("layer", CONV_LAYERS, ids=lambda l: l.name)

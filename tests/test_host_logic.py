@@ -179,6 +179,9 @@ def test_workspace_and_validation_without_a_gpu():
                                                                             one, one, one, None, ws, wsb, None)
     assert sch(4) == daq.ERR_INVALID_ARG and sch(-1) == daq.ERR_INVALID_ARG
     assert all(sch(s, wsb=8) == daq.ERR_WORKSPACE for s in range(4))           # a known scheme gets as far as the workspace check
+    chan = lambda desc=d, vq=one: lib.daq_conv_bwd_data_int8_chan(C.byref(desc), vq, one, one, one, one, None, one, 1 << 20, None)
+    assert chan() == daq.ERR_UNSUPPORTED                                       # a dense layer
+    assert chan(vq=None) == daq.ERR_INVALID_ARG and chan(vq=odd) == daq.ERR_INVALID_ARG and chan(desc=bad) == daq.ERR_INVALID_ARG
     assert daq.status_string(daq.ERR_WORKSPACE).startswith("workspace")
 
 
