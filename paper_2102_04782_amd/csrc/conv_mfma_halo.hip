@@ -375,6 +375,41 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     const int rowbase = row0 + wr * 64 + 4 * lh;
     const int HWd = p.Hd * p.Wd;
     const bool full_rows = row0 + ROWS <= p.Crow;
+    if (ST == 2 && p.zfill && !p.bf16 && !p.acc_out && (p.Wd & 1) == 0) {   // uniform
+        // Strided 1 x 1 layers, even rows: a pixel's 2 x 2 block leaves as (value, 0) and (0, 0), 8 bytes each.  The
+        // result is four times the class image, so the lines a wave has touched but not yet completed outgrow the
+        // L2 when its pixel fragments are written one after the other; here the fragments of one row (channel) are
+        // written back to back instead, and the lines they share complete within a few instructions.
+        float* o[BF];
+        bool ok[BF], h1[BF];
+#pragma unroll
+        for (int y = 0; y < BF; ++y) {
+            const int q = wp * PXW + 32 * y + l32;
+            const int img = (int)fdiv((uint32_t)q, p.div_thw);
+            const int rem = q - img * p.TH * p.TW;
+            const int th = (int)fdiv((uint32_t)rem, p.div_tw);
+            const int tw = rem - th * p.TW;
+            const int n = n0 + img, h = (h0 + th) * ST, w = (w0 + tw) * ST;
+            ok[y] = !(img >= p.NI || n >= p.N || h >= p.Hd || w >= p.Wd);
+            h1[y] = h + 1 < p.Hd;
+            o[y] = p.out + (((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w);
+        }
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                if (rowbase + dr >= p.Crow) continue;
+#pragma unroll
+                for (int y = 0; y < BF; ++y) {
+                    if (!ok[y]) continue;
+                    float* z = o[y] + (int64_t)dr * HWd;
+                    *reinterpret_cast<float2*>(z) = make_float2((float)acc[x][y][r] * scale, 0.0f);
+                    if (h1[y]) *reinterpret_cast<float2*>(z + p.Wd) = make_float2(0.0f, 0.0f);
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int y = 0; y < BF; ++y) {
         const int q = wp * PXW + 32 * y + l32;
