@@ -49,6 +49,9 @@ struct DxArgs {
     int s_log2;            // log2 of the (square, power-of-two) stride
     FastDiv div_wq, div_h, div_c;
     int wq;                // quads of output columns per row
+    FastDiv div_hq;        // block kernel: by hq
+    int hq;                // block kernel: quads of output rows per plane
+    int Ho;                // block kernel: rows of the gradient
     const float* s_g;      // one scale, or one per channel (per_chan)
     const float* s_w;
     int per_chan;          // the gradient is the per-channel copy: channel c is de-quantized with s_g[c]
@@ -177,6 +180,73 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
                 p.dX[o + j] = (float)acc[j] * scale;
                 if (p.acc_out) p.acc_out[o + j] = acc[j];
             }
+    }
+}
+
+// Data gradient, 3 x 3, stride 2, padding 1, row length a multiple of four (MobileNetV2's strided layers): a thread
+// produces a 4 x 4 block of outputs.  With h = 2a + i, w = 2b + j the live taps of an output depend only on the
+// parities: (i, j) = (0, 0) reads g[a][b] W11;  (0, 1): g[a][b] W12 + g[a][b+1] W10;  (1, 0): g[a][b] W21 + g[a+1][b] W01;
+// (1, 1): g[a][b] W22 + g[a][b+1] W20 + g[a+1][b] W02 + g[a+1][b+1] W00.  So the four outputs of a 2 x 2 block are four
+// dot4 products of ONE dword - the gradient's 2 x 2 neighbourhood (g[a][b], g[a][b+1], g[a+1][b], g[a+1][b+1]) - with
+// four weight dwords that are the same for every block of the channel.  The 4 x 4 outputs need three gradient rows of
+// three bytes each: three loads, four byte permutes and sixteen dot4 in place of the sixteen-odd instructions per
+// output of the row kernel above (which was bound by its instruction count, not by the result it writes).
+// Rows past the gradient's last one are never needed for a stored output; their index is clamped to the zero row
+// that follows every image.
+__global__ __launch_bounds__(kBlock) void k_dwise_dx_s2_block(DxArgs p) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t rq = fdiv(i, p.div_wq);
+    const int m = (int)(i - rq * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(rq, p.div_hq);
+    if (nc >= (uint32_t)p.N * p.C) return;
+    const int A = (int)(rq - nc * (uint32_t)p.hq);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+
+    const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
+    // gradient rows 2A, 2A+1, 2A+2 from column 2m on: bytes 0..2 of R[k] are columns 2m..2m+2
+    unsigned R[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int r = min(2 * A + k, p.Ho);
+        const int64_t off = (int64_t)((int)n * p.img_rows + r) * p.row_pitch + 2 * m;
+        const v2i_a4 d = *reinterpret_cast<const v2i_a4*>(g + (off & ~(int64_t)3));
+        R[k] = __builtin_amdgcn_alignbyte((unsigned)d[1], (unsigned)d[0], (unsigned)(off & 3));
+    }
+    // weight dwords by output parity (byte t of the filter is W[t/3][t%3]; bytes past the ninth are not selected)
+    unsigned wlo, whi;
+    load8(p.qw, (int64_t)c * 9, wlo, whi);
+    const unsigned w22 = (unsigned)(uint8_t)p.qw[c * 9 + 8];
+    const int Wee = (int)__builtin_amdgcn_perm(whi, wlo, 0x0c0c0c04u);           // W11 . . .
+    const int Weo = (int)__builtin_amdgcn_perm(whi, wlo, 0x0c0c0305u);           // W12 W10 . .
+    const int Woe = (int)__builtin_amdgcn_perm(whi, wlo, 0x0c010c07u);           // W21 . W01 .
+    const int Woo = (int)(__builtin_amdgcn_perm(whi, wlo, 0x0002060cu) | w22);   // W22 W20 W02 W00
+    int acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        // 2 x 2 neighbourhoods of the two blocks of row pair a: (g[a][b], g[a][b+1], g[a+1][b], g[a+1][b+1]), b = 0, 1
+        const int P0 = (int)__builtin_amdgcn_perm(R[a + 1], R[a], 0x05040100u);
+        const int P1 = (int)__builtin_amdgcn_perm(R[a + 1], R[a], 0x06050201u);
+        acc[2 * a][0] = dot4(P0, Wee, 0);
+        acc[2 * a][1] = dot4(P0, Weo, 0);
+        acc[2 * a][2] = dot4(P1, Wee, 0);
+        acc[2 * a][3] = dot4(P1, Weo, 0);
+        acc[2 * a + 1][0] = dot4(P0, Woe, 0);
+        acc[2 * a + 1][1] = dot4(P0, Woo, 0);
+        acc[2 * a + 1][2] = dot4(P1, Woe, 0);
+        acc[2 * a + 1][3] = dot4(P1, Woo, 0);
+    }
+    const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int h = 4 * A + rr;
+        if (h >= p.Hin) break;
+        const int64_t o = ((int64_t)nc * p.Hin + h) * p.Win + 4 * m;
+        const v4f res = {(float)acc[rr][0] * scale, (float)acc[rr][1] * scale, (float)acc[rr][2] * scale,
+                         (float)acc[rr][3] * scale};
+        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
+        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[rr][0], acc[rr][1], acc[rr][2], acc[rr][3]);
     }
 }
 
@@ -382,6 +452,15 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     // strided form: the columns four outputs can read, (3 + kW - 1) / stride + 1 of them, must fit the 8-byte load
     const bool strided = d.strideH > 1 && d.dilH == 1 && d.dilW == 1 && (3 + d.kW - 1) / d.strideH + 2 <= 8;
     const bool k33 = d.kH == 3 && d.kW == 3;
+    if (strided && k33 && d.strideH == 2 && d.padH == 1 && d.padW == 1 && d.Win % 4 == 0) {
+        a.hq = (int)ceil_div(d.Hin, 4);
+        a.div_hq = make_fastdiv((uint32_t)a.hq);
+        a.Ho = daq_out_h(&d);
+        const int64_t blocks4 = (int64_t)d.N * d.Cin * a.hq * a.wq;   // fewer than `threads`, which the caller bounded
+        DAQ_LAUNCH("conv_bwd_data_depthwise", st,
+                   hipLaunchKernelGGL(k_dwise_dx_s2_block, dim3((unsigned)ceil_div(blocks4, kBlock)), dim3(kBlock), 0, st, a));
+        return DAQ_OK;
+    }
     if (unit && k33)
         DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL((k_dwise_dx_unit<3, 3>), grid, dim3(kBlock), 0, st, a));
     else if (unit)

@@ -288,6 +288,9 @@ CONV_LAYERS = [
     wl.Layer("c1x1_pad", 2, 16, 6, 6, 16, 1, 1, 1, 1),            # padded 1x1
     wl.Layer("dw_big", 6, 40, 28, 28, 40, 3, 3, 1, 1, 1, 40),     # depthwise, several slabs per channel
     wl.Layer("dw_s2_big", 4, 24, 30, 30, 24, 3, 3, 2, 1, 1, 24),
+    wl.Layer("dw_s2_blk", 3, 20, 26, 28, 20, 3, 3, 2, 1, 1, 20),    # strided depthwise, 4 x 4 output blocks; ragged last row quad
+    wl.Layer("dw_s2_blk_odd", 2, 8, 13, 16, 8, 3, 3, 2, 1, 1, 8),   # the same with an odd number of rows
+    wl.Layer("dw_s2_blk_4", 1, 4, 4, 4, 4, 3, 3, 2, 1, 1, 4),       # a single block per plane
     wl.Layer("dw_5x5", 2, 8, 14, 14, 8, 5, 5, 1, 2, 1, 8),
     wl.Layer("dw_w7", 3, 16, 7, 7, 16, 3, 3, 1, 1, 1, 16),        # rows that are not a multiple of four outputs
     wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
