@@ -183,6 +183,65 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
     }
 }
 
+// Data gradient, 3 x 3, unit stride and dilation, padding 1, row length a multiple of four: a thread produces a 4 x 4
+// block of outputs from the six gradient rows h0-1 .. h0+4 it touches.  Each row is fetched once (8 bytes from column
+// w0-1), its four 4-byte windows are derived once, and it feeds the up to three output rows that read it: the same
+// dot4 per (output, filter row) as the row kernel above with half the loads and shifts and a quarter of the index
+// arithmetic per output.  Rows past the image are never needed for a stored output; their index is clamped to the
+// zero row that follows every image.
+__global__ __launch_bounds__(kBlock) void k_dwise_dx_unit_block(DxArgs p) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t rq = fdiv(i, p.div_wq);
+    const int w0 = 4 * (int)(i - rq * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(rq, p.div_hq);
+    if (nc >= (uint32_t)p.N * p.C) return;
+    const int h0 = 4 * (int)(rq - nc * (uint32_t)p.hq);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+
+    const int8_t* g = p.qg + (int64_t)c * p.chan_pitch + p.lead;
+    const int8_t* wrow = p.qw + c * 9;
+    int wr[3];   // reversed filter rows: byte m = W[kh][2 - m], byte 3 zero
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh) {
+        typedef int i1 __attribute__((ext_vector_type(1), aligned(1)));
+        const int raw = (*reinterpret_cast<const i1*>(wrow + kh * 3))[0];
+        wr[kh] = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, 0x0c000102u);
+    }
+    int acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+        // gradient row h0 - 1 + k serves output row h0 + a through filter row kh = a + 2 - k
+        const int r = min(h0 - 1 + k, p.Hin);
+        unsigned lo, hi;
+        load8(g, (int64_t)((int)n * p.img_rows + r) * p.row_pitch + (w0 - 1), lo, hi);
+        const int win[4] = {(int)lo, (int)__builtin_amdgcn_alignbyte(hi, lo, 1), (int)__builtin_amdgcn_alignbyte(hi, lo, 2),
+                            (int)__builtin_amdgcn_alignbyte(hi, lo, 3)};
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int kh = a + 2 - k;
+            if (kh < 0 || kh > 2) continue;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[a][b] = dot4(win[b], wr[kh], acc[a][b]);
+        }
+    }
+    const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const int h = h0 + a;
+        if (h >= p.Hin) break;
+        const int64_t o = ((int64_t)nc * p.Hin + h) * p.Win + w0;
+        const v4f res = {(float)acc[a][0] * scale, (float)acc[a][1] * scale, (float)acc[a][2] * scale, (float)acc[a][3] * scale};
+        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
+        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[a][0], acc[a][1], acc[a][2], acc[a][3]);
+    }
+}
+
 // Data gradient, 3 x 3, stride 2, padding 1, row length a multiple of four (MobileNetV2's strided layers): a thread
 // produces a 4 x 4 block of outputs.  With h = 2a + i, w = 2b + j the live taps of an output depend only on the
 // parities: (i, j) = (0, 0) reads g[a][b] W11;  (0, 1): g[a][b] W12 + g[a][b+1] W10;  (1, 0): g[a][b] W21 + g[a+1][b] W01;
@@ -452,13 +511,18 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     // strided form: the columns four outputs can read, (3 + kW - 1) / stride + 1 of them, must fit the 8-byte load
     const bool strided = d.strideH > 1 && d.dilH == 1 && d.dilW == 1 && (3 + d.kW - 1) / d.strideH + 2 <= 8;
     const bool k33 = d.kH == 3 && d.kW == 3;
-    if (strided && k33 && d.strideH == 2 && d.padH == 1 && d.padW == 1 && d.Win % 4 == 0) {
+    const bool block_s2 = strided && k33 && d.strideH == 2 && d.padH == 1 && d.padW == 1 && d.Win % 4 == 0;
+    const bool block_s1 = unit && k33 && d.padH == 1 && d.padW == 1 && d.Win % 4 == 0;
+    if (block_s2 || block_s1) {
         a.hq = (int)ceil_div(d.Hin, 4);
         a.div_hq = make_fastdiv((uint32_t)a.hq);
         a.Ho = daq_out_h(&d);
         const int64_t blocks4 = (int64_t)d.N * d.Cin * a.hq * a.wq;   // fewer than `threads`, which the caller bounded
-        DAQ_LAUNCH("conv_bwd_data_depthwise", st,
-                   hipLaunchKernelGGL(k_dwise_dx_s2_block, dim3((unsigned)ceil_div(blocks4, kBlock)), dim3(kBlock), 0, st, a));
+        const dim3 bgrid((unsigned)ceil_div(blocks4, kBlock));
+        if (block_s2)
+            DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_s2_block, bgrid, dim3(kBlock), 0, st, a));
+        else
+            DAQ_LAUNCH("conv_bwd_data_depthwise", st, hipLaunchKernelGGL(k_dwise_dx_unit_block, bgrid, dim3(kBlock), 0, st, a));
         return DAQ_OK;
     }
     if (unit && k33)

@@ -291,6 +291,9 @@ CONV_LAYERS = [
     wl.Layer("dw_s2_blk", 3, 20, 26, 28, 20, 3, 3, 2, 1, 1, 20),    # strided depthwise, 4 x 4 output blocks; ragged last row quad
     wl.Layer("dw_s2_blk_odd", 2, 8, 13, 16, 8, 3, 3, 2, 1, 1, 8),   # the same with an odd number of rows
     wl.Layer("dw_s2_blk_4", 1, 4, 4, 4, 4, 3, 3, 2, 1, 1, 4),       # a single block per plane
+    wl.Layer("dw_blk_ragged", 2, 12, 10, 12, 12, 3, 3, 1, 1, 1, 12),  # unit stride, 4 x 4 output blocks; last row quad has two rows
+    wl.Layer("dw_blk_odd", 3, 6, 5, 8, 6, 3, 3, 1, 1, 1, 6),          # ... one row
+    wl.Layer("dw_blk_4", 1, 4, 4, 4, 4, 3, 3, 1, 1, 1, 4),
     wl.Layer("dw_5x5", 2, 8, 14, 14, 8, 5, 5, 1, 2, 1, 8),
     wl.Layer("dw_w7", 3, 16, 7, 7, 16, 3, 3, 1, 1, 1, 16),        # rows that are not a multiple of four outputs
     wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
