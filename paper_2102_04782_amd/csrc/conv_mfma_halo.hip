@@ -527,6 +527,85 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// 1 x 1 data gradient at unit stride with a short contraction axis (at most 64 output channels: the projection
+// layers of MobileNetV2, conv2_x of ResNet-50).  Such a layer is one or two multiplies per 32 x 32 block of its
+// result and is bound by that fp32 result; as a tile kernel (one step per workgroup) it spent as long in set-up as in
+// stores.  Here a wave streams: a unit of work is (32 consecutive pixels, one 32-row block of the result) - the
+// pixel fragment is 16 bytes per lane straight from the NHWC gradient (coalesced, no LDS), the filter fragment 16
+// bytes per lane from the fragment-order copy (a few KB, cache resident), one or two v_mfma_i32_32x32x32_i8, sixteen
+// stores of 128-byte runs - and waves loop over the units with a grid stride.  Consecutive units share the pixels.
+// ---------------------------------------------------------------------------------------------
+struct StreamArgs {
+    const int8_t* src;    // NHWC gradient, [pixels][cp]
+    const int8_t* wfrag;  // filter in fragment order (one tap, one 64-byte chunk): [RB][2][1024]
+    uint32_t src_bytes, wfrag_bytes;
+    int cp, Crow, RB, HW;
+    uint32_t total_px, units;   // units = ceil(total_px / 32) * RB
+    FastDiv div_rb, div_hw;
+    const float* s_a;
+    const float* s_b;
+    float* out;
+    int32_t* acc_out;
+    int nt;
+    DwTail tail;          // tail.blocks > 0: that many workgroups behind the first main_blocks finish a deferred filter gradient
+    int main_blocks;
+};
+
+__global__ __launch_bounds__(256) void k_dx_1x1_stream(StreamArgs p) {
+    __shared__ int32_t l_role[256];
+    if (p.tail.blocks > 0 && (int)blockIdx.x >= p.main_blocks) {   // uniform
+        dw_reduce_role(p.tail, (int)blockIdx.x - p.main_blocks, l_role);
+        return;
+    }
+    const int lane = threadIdx.x % kWave, l32 = lane & 31, lh = lane >> 5;
+    const uint32_t wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const uint32_t waves = (uint32_t)p.main_blocks * (blockDim.x / kWave);
+    const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
+    const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
+    const bool second = p.cp > 32;   // uniform: contraction bytes 32..63 exist
+    for (uint32_t u = wave; u < p.units; u += waves) {
+        const uint32_t grp = fdiv(u, p.div_rb);
+        const int rb = (int)(u - grp * (uint32_t)p.RB);
+        const uint32_t P = grp * 32u + (uint32_t)l32;
+        const bool valid = P < p.total_px;
+        // contraction bytes 16*lh .. +15 of sub-chunk `sub` of the pixel; bytes past the channel pitch belong to the next pixel
+        const uint32_t boff = valid ? P * (uint32_t)p.cp + 16u * lh : kOob;
+        const v4i b0 = buffer_load16(rs_src, (16 * lh < p.cp) ? boff : kOob, 0);
+        const v4i a0 = buffer_load16(rs_w, (uint32_t)(rb * 2048 + lane * 16), 0);
+        v16i acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0;
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
+        if (second) {
+            const v4i b1 = buffer_load16(rs_src, (32 + 16 * lh < p.cp) ? boff : kOob, 32);
+            const v4i a1 = buffer_load16(rs_w, (uint32_t)(rb * 2048 + 1024 + lane * 16), 0);
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+        }
+        if (!valid) continue;
+        const uint32_t n = fdiv(P, p.div_hw);
+        const uint32_t r0 = P - n * (uint32_t)p.HW;
+        const int rowbase = 32 * rb + 4 * lh;
+        float* o = p.out + ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int dr = 8 * (r >> 2) + (r & 3);
+            if (rowbase + dr >= p.Crow) continue;
+            if (p.nt) __builtin_nontemporal_store((float)acc[r] * scale, &o[(int64_t)dr * p.HW]);
+            else o[(int64_t)dr * p.HW] = (float)acc[r] * scale;
+        }
+        if (p.acc_out) {
+            int32_t* ao = p.acc_out + ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                if (rowbase + dr < p.Crow) ao[(int64_t)dr * p.HW] = acc[r];
+            }
+        }
+    }
+}
+
 // Workgroups of one row tile: one per pixel tile, times the parity classes of a strided data gradient (whose tiles are
 // padded to groups of eight, see the kernel's block decoding).
 int64_t blocks_per_row_tile(const HaloArgs& a) {
@@ -722,6 +801,41 @@ Geometry plan_fwd(const daq_conv_desc& d) {
     return g;
 }
 
+// The streaming form serves: 1 x 1, unit stride, no padding, dense, at most 64 output channels.
+bool stream_applies(const daq_conv_desc& d, const daq_layout& Lg) {
+    return d.groups == 1 && d.kH == 1 && d.kW == 1 && d.strideH == 1 && d.strideW == 1 && d.padH == 0 && d.padW == 0 &&
+           Lg.kind == DAQ_LAYOUT_NHWC && Lg.c_pitch <= 64 && (int64_t)d.N * d.Hin * d.Win < ((int64_t)1 << 31) - 64 &&
+           ceil_div((int64_t)d.N * d.Hin * d.Win, 32) * ceil_div(d.Cin, 32) < ((int64_t)1 << 31);
+}
+
+daq_status launch_stream(const daq_conv_desc& d, const daq_layout& Lg, const daq_wpack_layout& Lw, const int8_t* qg,
+                         const float* s_g, const int8_t* qw, const float* s_w, float* dX, int32_t* acc, hipStream_t st,
+                         const DwTail* tail) {
+    StreamArgs a{};
+    a.src = qg;
+    a.wfrag = qw + Lw.off_bwd_frag;
+    a.src_bytes = (uint32_t)Lg.bytes;
+    a.wfrag_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd_frag);
+    a.cp = Lg.c_pitch;
+    a.Crow = d.Cin;
+    a.RB = (int)ceil_div(d.Cin, 32);
+    a.HW = d.Hin * d.Win;
+    a.total_px = (uint32_t)((int64_t)d.N * a.HW);
+    a.units = (uint32_t)(ceil_div((int64_t)a.total_px, 32) * a.RB);
+    a.div_rb = make_fastdiv((uint32_t)a.RB);
+    a.div_hw = make_fastdiv((uint32_t)a.HW);
+    a.s_a = s_w; a.s_b = s_g;
+    a.out = dX; a.acc_out = acc;
+    a.nt = (int64_t)d.N * d.Cin * a.HW * 4 >= kStreamBytes;
+    // eight waves per SIMD at most; a wave should have several units so that its set-up is amortised
+    const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.units, 4 * 2), 256 * 8));
+    if (tail) a.tail = *tail;
+    a.main_blocks = (int)wgs;
+    DAQ_LAUNCH("conv_bwd_data_mfma", st,
+               hipLaunchKernelGGL(k_dx_1x1_stream, dim3((unsigned)(wgs + a.tail.blocks)), dim3(256), 0, st, a));
+    return DAQ_OK;
+}
+
 }  // namespace
 
 bool bwd_data_halo_supported(const daq_conv_desc& d) { return plan_bwd(d).ok; }
@@ -733,6 +847,9 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     g.a.bf16 = bf16 ? 1 : 0;
     daq_wpack_layout Lw;
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
+    daq_layout Lg;
+    if (!bf16 && daq_layout_qg(&d, &Lg) == DAQ_OK && stream_applies(d, Lg))
+        return launch_stream(d, Lg, Lw, qg, s_g, qw, s_w, dX, acc, st, tail);
     g.a.src = qg;
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;

@@ -286,6 +286,10 @@ CONV_LAYERS = [
     wl.Layer("c1x1_s2_big", 8, 64, 28, 28, 128, 1, 1, 2, 0),      # strided projection shortcut
     wl.Layer("c3x3_s2_dil2", 2, 16, 15, 14, 16, 3, 3, 2, 2, 2),   # stride and dilation together
     wl.Layer("c1x1_pad", 2, 16, 6, 6, 16, 1, 1, 1, 1),            # padded 1x1
+    wl.Layer("c1x1_thin16", 3, 40, 10, 12, 16, 1, 1, 1, 0),       # thin 1x1 (streaming data gradient): 16-byte pixel records, ragged row block
+    wl.Layer("c1x1_thin24", 2, 144, 9, 7, 24, 1, 1, 1, 0),        # 32-byte records; groups of 32 pixels straddle images; ragged last group
+    wl.Layer("c1x1_thin48", 1, 33, 5, 5, 48, 1, 1, 1, 0),         # 48-byte records: the last 16 contraction bytes are another pixel's
+    wl.Layer("c1x1_thin64", 2, 96, 8, 8, 64, 1, 1, 1, 0),         # full 64-byte records, two multiplies per block
     wl.Layer("dw_big", 6, 40, 28, 28, 40, 3, 3, 1, 1, 1, 40),     # depthwise, several slabs per channel
     wl.Layer("dw_s2_big", 4, 24, 30, 30, 24, 3, 3, 2, 1, 1, 24),
     wl.Layer("dw_s2_blk", 3, 20, 26, 28, 20, 3, 3, 2, 1, 1, 20),    # strided depthwise, 4 x 4 output blocks; ragged last row quad
