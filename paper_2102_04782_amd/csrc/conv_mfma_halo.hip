@@ -528,21 +528,24 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
 }
 
 // ---------------------------------------------------------------------------------------------
-// 1 x 1 data gradient at unit stride with a short contraction axis (at most 64 output channels: the projection
-// layers of MobileNetV2, conv2_x of ResNet-50).  Such a layer is one or two multiplies per 32 x 32 block of its
-// result and is bound by that fp32 result; as a tile kernel (one step per workgroup) it spent as long in set-up as in
-// stores.  Here a wave streams: a unit of work is (32 consecutive pixels, one 32-row block of the result) - the
-// pixel fragment is 16 bytes per lane straight from the NHWC gradient (coalesced, no LDS), the filter fragment 16
-// bytes per lane from the fragment-order copy (a few KB, cache resident), one or two v_mfma_i32_32x32x32_i8, sixteen
-// stores of 128-byte runs - and waves loop over the units with a grid stride.  Consecutive units share the pixels.
+// 1 x 1 data gradient at unit stride with a short contraction axis (at most 256 output channels: the projection
+// layers of MobileNetV2, the 1 x 1 layers of ResNet-50 that reduce to 64 - 256 channels).  Such a layer is a few
+// multiplies per 32 x 32 block of its result and is bound by that fp32 result; as a tile kernel (one to four steps
+// per workgroup) it spent as long in set-up as in stores.  Here a wave streams: it keeps the filter fragments of
+// two 32-row blocks of the result in registers (16 bytes per lane and 32-byte contraction step, from the
+// fragment-order copy) and walks over groups of 32 consecutive pixels with a stride - the pixel fragments are 16
+// bytes per lane straight from the NHWC gradient (coalesced, no LDS; the next group's are requested before the
+// current group's multiplies), then 2 x KS v_mfma_i32_32x32x32_i8 and 32 stores of 128-byte runs per group.
+// Waves of a workgroup hold neighbouring row blocks of the same pixel groups.
 // ---------------------------------------------------------------------------------------------
 struct StreamArgs {
     const int8_t* src;    // NHWC gradient, [pixels][cp]
-    const int8_t* wfrag;  // filter in fragment order (one tap, one 64-byte chunk): [RB][2][1024]
+    const int8_t* wfrag;  // filter in fragment order (one tap): [cp/64][RB][2][1024]
     uint32_t src_bytes, wfrag_bytes;
     int cp, Crow, RB, HW;
-    uint32_t total_px, units;   // units = ceil(total_px / 32) * RB
-    FastDiv div_rb, div_hw;
+    int RP, S;            // pairs of row blocks; pixel-group phases (a wave takes groups s, s + S, ...)
+    uint32_t total_px, groups;
+    FastDiv div_rp, div_hw;
     const float* s_a;
     const float* s_b;
     float* out;
@@ -552,6 +555,8 @@ struct StreamArgs {
     int main_blocks;
 };
 
+// KS = 32-byte contraction steps (cp <= 32 * KS)
+template <int KS>
 __global__ __launch_bounds__(256) void k_dx_1x1_stream(StreamArgs p) {
     __shared__ int32_t l_role[256];
     if (p.tail.blocks > 0 && (int)blockIdx.x >= p.main_blocks) {   // uniform
@@ -560,49 +565,64 @@ __global__ __launch_bounds__(256) void k_dx_1x1_stream(StreamArgs p) {
     }
     const int lane = threadIdx.x % kWave, l32 = lane & 31, lh = lane >> 5;
     const uint32_t wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const uint32_t waves = (uint32_t)p.main_blocks * (blockDim.x / kWave);
+    const uint32_t s = fdiv(wave, p.div_rp);
+    const int rp = (int)(wave - s * (uint32_t)p.RP);
+    if (s >= (uint32_t)p.S) return;   // uniform per wave
     const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
     const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
-    const bool second = p.cp > 32;   // uniform: contraction bytes 32..63 exist
-    for (uint32_t u = wave; u < p.units; u += waves) {
-        const uint32_t grp = fdiv(u, p.div_rb);
-        const int rb = (int)(u - grp * (uint32_t)p.RB);
+
+    v4i A[2][KS];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int rb = 2 * rp + j;
+            const bool live = rb < p.RB && 32 * ks < p.cp;
+            A[j][ks] = buffer_load16(rs_w, live ? (uint32_t)((((ks >> 1) * p.RB + rb) * 2 + (ks & 1)) * 1024 + lane * 16) : kOob, 0);
+        }
+    // contraction bytes 32*ks + 16*lh .. +15 of the lane's pixel; bytes past the channel pitch belong to the next pixel
+    auto fetch = [&](uint32_t grp, v4i (&B)[KS]) {
         const uint32_t P = grp * 32u + (uint32_t)l32;
-        const bool valid = P < p.total_px;
-        // contraction bytes 16*lh .. +15 of sub-chunk `sub` of the pixel; bytes past the channel pitch belong to the next pixel
-        const uint32_t boff = valid ? P * (uint32_t)p.cp + 16u * lh : kOob;
-        const v4i b0 = buffer_load16(rs_src, (16 * lh < p.cp) ? boff : kOob, 0);
-        const v4i a0 = buffer_load16(rs_w, (uint32_t)(rb * 2048 + lane * 16), 0);
-        v16i acc;
+        const bool valid = grp < p.groups && P < p.total_px;
+        const uint32_t boff = P * (uint32_t)p.cp + 16u * lh;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = 0;
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc, 0, 0, 0);
-        if (second) {
-            const v4i b1 = buffer_load16(rs_src, (32 + 16 * lh < p.cp) ? boff : kOob, 32);
-            const v4i a1 = buffer_load16(rs_w, (uint32_t)(rb * 2048 + 1024 + lane * 16), 0);
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc, 0, 0, 0);
+        for (int ks = 0; ks < KS; ++ks) B[ks] = buffer_load16(rs_src, (valid && 32 * ks + 16 * lh < p.cp) ? boff : kOob, 32u * ks);
+    };
+    v4i B[KS];
+    fetch(s, B);
+    for (uint32_t grp = s; grp < p.groups; grp += (uint32_t)p.S) {
+        v4i Bn[KS];
+        fetch(grp + (uint32_t)p.S, Bn);
+        v16i acc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[j][ks], B[ks], acc[j], 0, 0, 0);
         }
-        if (!valid) continue;
-        const uint32_t n = fdiv(P, p.div_hw);
-        const uint32_t r0 = P - n * (uint32_t)p.HW;
-        const int rowbase = 32 * rb + 4 * lh;
-        float* o = p.out + ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
+        const uint32_t P = grp * 32u + (uint32_t)l32;
+        if (P < p.total_px) {
+            const uint32_t n = fdiv(P, p.div_hw);
+            const uint32_t r0 = P - n * (uint32_t)p.HW;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int dr = 8 * (r >> 2) + (r & 3);
-            if (rowbase + dr >= p.Crow) continue;
-            if (p.nt) __builtin_nontemporal_store((float)acc[r] * scale, &o[(int64_t)dr * p.HW]);
-            else o[(int64_t)dr * p.HW] = (float)acc[r] * scale;
-        }
-        if (p.acc_out) {
-            int32_t* ao = p.acc_out + ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
+            for (int j = 0; j < 2; ++j) {
+                const int rowbase = 32 * (2 * rp + j) + 4 * lh;
+                const int64_t at = ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = 8 * (r >> 2) + (r & 3);
-                if (rowbase + dr < p.Crow) ao[(int64_t)dr * p.HW] = acc[r];
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr >= p.Crow) continue;
+                    float* z = p.out + at + (int64_t)dr * p.HW;
+                    if (p.nt) __builtin_nontemporal_store((float)acc[j][r] * scale, z);
+                    else *z = (float)acc[j][r] * scale;
+                    if (p.acc_out) p.acc_out[at + (int64_t)dr * p.HW] = acc[j][r];
+                }
             }
         }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) B[ks] = Bn[ks];
     }
 }
 
@@ -801,11 +821,11 @@ Geometry plan_fwd(const daq_conv_desc& d) {
     return g;
 }
 
-// The streaming form serves: 1 x 1, unit stride, no padding, dense, at most 64 output channels.
+// The streaming form serves: 1 x 1, unit stride, no padding, dense, at most 256 output channels.
 bool stream_applies(const daq_conv_desc& d, const daq_layout& Lg) {
     return d.groups == 1 && d.kH == 1 && d.kW == 1 && d.strideH == 1 && d.strideW == 1 && d.padH == 0 && d.padW == 0 &&
-           Lg.kind == DAQ_LAYOUT_NHWC && Lg.c_pitch <= 64 && (int64_t)d.N * d.Hin * d.Win < ((int64_t)1 << 31) - 64 &&
-           ceil_div((int64_t)d.N * d.Hin * d.Win, 32) * ceil_div(d.Cin, 32) < ((int64_t)1 << 31);
+           Lg.kind == DAQ_LAYOUT_NHWC && Lg.c_pitch <= 256 && (int64_t)d.N * d.Hin * d.Win < ((int64_t)1 << 31) - 64 &&
+           ceil_div(d.Cin, 64) <= 4096;
 }
 
 daq_status launch_stream(const daq_conv_desc& d, const daq_layout& Lg, const daq_wpack_layout& Lw, const int8_t* qg,
@@ -821,18 +841,27 @@ daq_status launch_stream(const daq_conv_desc& d, const daq_layout& Lg, const daq
     a.RB = (int)ceil_div(d.Cin, 32);
     a.HW = d.Hin * d.Win;
     a.total_px = (uint32_t)((int64_t)d.N * a.HW);
-    a.units = (uint32_t)(ceil_div((int64_t)a.total_px, 32) * a.RB);
-    a.div_rb = make_fastdiv((uint32_t)a.RB);
+    a.groups = (uint32_t)ceil_div((int64_t)a.total_px, 32);
+    a.RP = (int)ceil_div(a.RB, 2);
+    const int ks = (int)ceil_div(a.cp, 32);
+    // waves the chip holds at this form's register count; a wave should get several groups for its filter fragments
+    const int64_t target = ks <= 2 ? 8192 : ks <= 4 ? 4096 : 2048;
+    a.S = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.groups, 2), target / a.RP));
+    a.div_rp = make_fastdiv((uint32_t)a.RP);
     a.div_hw = make_fastdiv((uint32_t)a.HW);
     a.s_a = s_w; a.s_b = s_g;
     a.out = dX; a.acc_out = acc;
     a.nt = (int64_t)d.N * d.Cin * a.HW * 4 >= kStreamBytes;
-    // eight waves per SIMD at most; a wave should have several units so that its set-up is amortised
-    const int64_t wgs = std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.units, 4 * 2), 256 * 8));
+    const int64_t wgs = ceil_div((int64_t)a.RP * a.S, 4);
     if (tail) a.tail = *tail;
     a.main_blocks = (int)wgs;
-    DAQ_LAUNCH("conv_bwd_data_mfma", st,
-               hipLaunchKernelGGL(k_dx_1x1_stream, dim3((unsigned)(wgs + a.tail.blocks)), dim3(256), 0, st, a));
+    const dim3 grid((unsigned)(wgs + a.tail.blocks));
+#define DAQ_STREAM(KSV) DAQ_LAUNCH("conv_bwd_data_mfma", st, hipLaunchKernelGGL((k_dx_1x1_stream<KSV>), grid, dim3(256), 0, st, a))
+    if (ks <= 1) DAQ_STREAM(1);
+    else if (ks <= 2) DAQ_STREAM(2);
+    else if (ks <= 4) DAQ_STREAM(4);
+    else DAQ_STREAM(8);
+#undef DAQ_STREAM
     return DAQ_OK;
 }
 

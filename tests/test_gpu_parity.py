@@ -290,6 +290,9 @@ CONV_LAYERS = [
     wl.Layer("c1x1_thin24", 2, 144, 9, 7, 24, 1, 1, 1, 0),        # 32-byte records; groups of 32 pixels straddle images; ragged last group
     wl.Layer("c1x1_thin48", 1, 33, 5, 5, 48, 1, 1, 1, 0),         # 48-byte records: the last 16 contraction bytes are another pixel's
     wl.Layer("c1x1_thin64", 2, 96, 8, 8, 64, 1, 1, 1, 0),         # full 64-byte records, two multiplies per block
+    wl.Layer("c1x1_thin96", 3, 70, 6, 7, 96, 1, 1, 1, 0),         # three contraction steps on the four-step form; three row blocks (a dead one in the last pair)
+    wl.Layer("c1x1_thin160", 2, 200, 5, 5, 160, 1, 1, 1, 0),      # five steps on the eight-step form
+    wl.Layer("c1x1_thin256", 1, 64, 12, 12, 256, 1, 1, 1, 0),     # all eight steps
     wl.Layer("dw_big", 6, 40, 28, 28, 40, 3, 3, 1, 1, 1, 40),     # depthwise, several slabs per channel
     wl.Layer("dw_s2_big", 4, 24, 30, 30, 24, 3, 3, 2, 1, 1, 24),
     wl.Layer("dw_s2_blk", 3, 20, 26, 28, 20, 3, 3, 2, 1, 1, 20),    # strided depthwise, 4 x 4 output blocks; ragged last row quad
