@@ -26,11 +26,11 @@ PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a copy
 # kernel of known size; keyed by (workload, kernel).  See profiles/ for the runs these come from.
 MEASURED_TRAFFIC = {
-    ("config2", "conv_bwd_data_mfma"): 45.20e6,    # with the filter gradient's last stage on the same launch (35.6e6 alone)
-    ("config2", "conv_bwd_filter_mfma"): 23.83e6,
+    ("config2", "conv_bwd_data_mfma"): 45.23e6,    # with the filter gradient's last stage on the same launch (35.6e6 alone)
+    ("config2", "conv_bwd_filter_mfma"): 23.61e6,
     ("config2", "stats"): 25.78e6,
-    ("config2", "count_qg"): 33.99e6,
-    ("config2", "pack_vq"): 32.91e6,
+    ("config2", "count_qg"): 34.01e6,
+    ("config2", "pack_vq"): 32.89e6,
 }
 
 
