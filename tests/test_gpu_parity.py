@@ -512,6 +512,46 @@ def test_random_descriptors(layer):
     check_forward(layer, seed)
 
 
+def _random_special_layers(count, seed):
+    """Seeded random descriptors inside the domains of the specialised kernels: 1 x 1 layers at unit stride with up to 256
+    output channels (streaming data gradient, every contraction-step count), strided 1 x 1 without padding (zero-filling
+    epilogue), 3 x 3 depthwise at stride 1 and 2 with padding 1 and rows a multiple of four (4 x 4 output blocks), with
+    ragged channel counts, image sizes and batch sizes."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        kind = rng.choice(["thin1x1", "thin1x1", "s2_1x1", "dw_s1", "dw_s2"])
+        n = int(rng.integers(1, 5))
+        if kind == "thin1x1":
+            cout = int(rng.choice([int(rng.integers(1, 33)), int(rng.integers(33, 65)), int(rng.integers(65, 129)),
+                                   int(rng.integers(129, 257))]))
+            L = wl.Layer(f"sp{len(out)}", n, int(rng.integers(1, 200)), int(rng.integers(1, 15)), int(rng.integers(1, 15)), cout,
+                         1, 1, 1, 0)
+        elif kind == "s2_1x1":
+            L = wl.Layer(f"sp{len(out)}", n, int(rng.integers(1, 150)), int(rng.integers(2, 20)), int(rng.integers(2, 20)),
+                         int(rng.integers(1, 150)), 1, 1, 2, 0)
+        else:
+            ch = int(rng.integers(1, 48))
+            L = wl.Layer(f"sp{len(out)}", n, ch, int(rng.integers(2, 23)), 4 * int(rng.integers(1, 8)), ch, 3, 3,
+                         1 if kind == "dw_s1" else 2, 1, 1, ch)
+        out.append(L)
+    return out
+
+
+SPECIAL_LAYERS = _random_special_layers(40, 20210205)
+
+
+@pytest.mark.parametrize("layer", SPECIAL_LAYERS, ids=lambda l: f"{l.name}-N{l.N}c{l.Cin}>{l.Cout}h{l.Hin}w{l.Win}k{l.kH}s{l.stride}g{l.groups}")
+def test_random_descriptors_of_the_specialised_kernels(layer):
+    seed = wl.seed_for(13, SPECIAL_LAYERS.index(layer))
+    rng = np.random.default_rng(seed)
+    qX = rng.integers(-127, 128, layer.x_shape).astype(np.int8)
+    qW = rng.integers(-127, 128, layer.w_shape).astype(np.int8)
+    qG = rng.integers(-127, 128, layer.y_shape).astype(np.int8)
+    s_c = (10.0 ** rng.uniform(-4, -1, layer.Cout)).astype(np.float32)
+    run_convs_on_codes(layer, qX, qW, qG, 0.9, 0.3, 0.05, s_c)
+
+
 def test_early_per_channel_copy_on_small_shapes():
     """The counting pass writes the per-channel copy itself only for large gradients; DAQ_EARLY_VQ_MIN=0 (read once
     per process) turns that on for every size, so the quantizer tests above are run again in a child process with it:
