@@ -528,8 +528,8 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
 }
 
 // ---------------------------------------------------------------------------------------------
-// 1 x 1 data gradient at unit stride with a short contraction axis (at most 256 output channels: the projection
-// layers of MobileNetV2, the 1 x 1 layers of ResNet-50 that reduce to 64 - 256 channels).  Such a layer is a few
+// 1 x 1 data gradient (and forward pass) at unit stride with a short contraction axis (at most 256 channels: for the
+// data gradient the projection layers of MobileNetV2 and the 1 x 1 layers of ResNet-50 that reduce to 64 - 256 channels).  Such a layer is a few
 // multiplies per 32 x 32 block of its result and is bound by that fp32 result; as a tile kernel (one to four steps
 // per workgroup) it spent as long in set-up as in stores.  Here a wave streams: it keeps the filter fragments of
 // two 32-row blocks of the result in registers (16 bytes per lane and 32-byte contraction step, from the
@@ -825,20 +825,21 @@ Geometry plan_fwd(const daq_conv_desc& d) {
 bool stream_applies(const daq_conv_desc& d, const daq_layout& Lg) {
     return d.groups == 1 && d.kH == 1 && d.kW == 1 && d.strideH == 1 && d.strideW == 1 && d.padH == 0 && d.padW == 0 &&
            Lg.kind == DAQ_LAYOUT_NHWC && Lg.c_pitch <= 256 && (int64_t)d.N * d.Hin * d.Win < ((int64_t)1 << 31) - 64 &&
-           ceil_div(d.Cin, 64) <= 4096;
+           ceil_div(std::max(d.Cin, d.Cout), 64) <= 4096;
 }
 
-daq_status launch_stream(const daq_conv_desc& d, const daq_layout& Lg, const daq_wpack_layout& Lw, const int8_t* qg,
-                         const float* s_g, const int8_t* qw, const float* s_w, float* dX, int32_t* acc, hipStream_t st,
-                         const DwTail* tail) {
+// src: the NHWC operand (layout Ls); wfrag: the fragment-order filter copy whose rows are the result's `rows` channels
+daq_status launch_stream(const char* name, const daq_conv_desc& d, const daq_layout& Ls, const int8_t* src,
+                         const int8_t* wfrag, int64_t wfrag_bytes, int rows, const float* s_a, const float* s_b, float* out,
+                         int32_t* acc, hipStream_t st, const DwTail* tail) {
     StreamArgs a{};
-    a.src = qg;
-    a.wfrag = qw + Lw.off_bwd_frag;
-    a.src_bytes = (uint32_t)Lg.bytes;
-    a.wfrag_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd_frag);
-    a.cp = Lg.c_pitch;
-    a.Crow = d.Cin;
-    a.RB = (int)ceil_div(d.Cin, 32);
+    a.src = src;
+    a.wfrag = wfrag;
+    a.src_bytes = (uint32_t)Ls.bytes;
+    a.wfrag_bytes = (uint32_t)wfrag_bytes;
+    a.cp = Ls.c_pitch;
+    a.Crow = rows;
+    a.RB = (int)ceil_div(rows, 32);
     a.HW = d.Hin * d.Win;
     a.total_px = (uint32_t)((int64_t)d.N * a.HW);
     a.groups = (uint32_t)ceil_div((int64_t)a.total_px, 32);
@@ -849,14 +850,14 @@ daq_status launch_stream(const daq_conv_desc& d, const daq_layout& Lg, const daq
     a.S = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.groups, 2), target / a.RP));
     a.div_rp = make_fastdiv((uint32_t)a.RP);
     a.div_hw = make_fastdiv((uint32_t)a.HW);
-    a.s_a = s_w; a.s_b = s_g;
-    a.out = dX; a.acc_out = acc;
-    a.nt = (int64_t)d.N * d.Cin * a.HW * 4 >= kStreamBytes;
+    a.s_a = s_a; a.s_b = s_b;
+    a.out = out; a.acc_out = acc;
+    a.nt = (int64_t)d.N * rows * a.HW * 4 >= kStreamBytes;
     const int64_t wgs = ceil_div((int64_t)a.RP * a.S, 4);
     if (tail) a.tail = *tail;
     a.main_blocks = (int)wgs;
     const dim3 grid((unsigned)(wgs + a.tail.blocks));
-#define DAQ_STREAM(KSV) DAQ_LAUNCH("conv_bwd_data_mfma", st, hipLaunchKernelGGL((k_dx_1x1_stream<KSV>), grid, dim3(256), 0, st, a))
+#define DAQ_STREAM(KSV) DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_dx_1x1_stream<KSV>), grid, dim3(256), 0, st, a))
     if (ks <= 1) DAQ_STREAM(1);
     else if (ks <= 2) DAQ_STREAM(2);
     else if (ks <= 4) DAQ_STREAM(4);
@@ -878,7 +879,8 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lg;
     if (!bf16 && daq_layout_qg(&d, &Lg) == DAQ_OK && stream_applies(d, Lg))
-        return launch_stream(d, Lg, Lw, qg, s_g, qw, s_w, dX, acc, st, tail);
+        return launch_stream("conv_bwd_data_mfma", d, Lg, qg, qw + Lw.off_bwd_frag, Lw.bytes - Lw.off_bwd_frag, d.Cin, s_w, s_g, dX, acc,
+                             st, tail);
     g.a.src = qg;
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;
@@ -894,6 +896,10 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     Geometry g = plan_fwd(d);
     daq_wpack_layout Lw;
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
+    daq_layout Lx;
+    if (daq_layout_qx_nhwc(&d, &Lx) == DAQ_OK && stream_applies(d, Lx))   // thin 1 x 1 layers: the streaming kernel, rows = Cout
+        return launch_stream("conv_fwd_mfma", d, Lx, qx, qw + Lw.off_fwd_frag, Lw.off_bwd_frag - Lw.off_fwd_frag, d.Cout, s_x, s_w, Y,
+                             acc, st, nullptr);
     g.a.src = qx;
     g.a.wfrag = qw + Lw.off_fwd_frag;
     g.a.s_a = s_x; g.a.s_b = s_w;
