@@ -27,6 +27,7 @@ extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* 
     rc = quantize_filter(*desc, W, qw_packed, s_w, workspace, st);
     if (rc != DAQ_OK) return rc;
     if (fwd_halo_supported(*desc)) return conv_fwd_halo(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
+    if (depthwise_fwd_supported(*desc)) return conv_fwd_depthwise(*desc, qx_cnhw, qw_packed, s_x, s_w, Y, acc_out, st);
     if (fwd_mfma_supported(*desc)) return conv_fwd_mfma(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
     return conv_fwd_generic(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
 }

@@ -55,6 +55,8 @@ struct DxArgs {
     const float* s_g;      // one scale, or one per channel (per_chan)
     const float* s_w;
     int per_chan;          // the gradient is the per-channel copy: channel c is de-quantized with s_g[c]
+    int flip;              // 3 x 3 kernels at unit stride: apply the filter rotated by 180 degrees - the forward convolution of a
+                           // 3 x 3, padding-1 layer is its data gradient with the rotated filter (planes are then activations)
     float* dX;
     int32_t* acc_out;
     int nt;                // large result: streaming stores
@@ -88,8 +90,8 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
         if (KW == 3) {
             // bytes W0 W1 W2 and one byte of whatever follows (the packed filter has further copies behind this one)
             typedef int i1 __attribute__((ext_vector_type(1), aligned(1)));
-            const int raw = (*reinterpret_cast<const i1*>(wrow + kh * 3))[0];
-            wr = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, 0x0c000102u);
+            const int raw = (*reinterpret_cast<const i1*>(wrow + (p.flip ? 2 - kh : kh) * 3))[0];
+            wr = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, p.flip ? 0x0c020100u : 0x0c000102u);   // flip: see DxArgs
         } else {
             for (int m = 0; m < kW; ++m) wr |= ((int)(uint8_t)wrow[kh * kW + (kW - 1 - m)]) << (8 * m);
         }
@@ -205,8 +207,8 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit_block(DxArgs p) {
 #pragma unroll
     for (int kh = 0; kh < 3; ++kh) {
         typedef int i1 __attribute__((ext_vector_type(1), aligned(1)));
-        const int raw = (*reinterpret_cast<const i1*>(wrow + kh * 3))[0];
-        wr[kh] = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, 0x0c000102u);
+        const int raw = (*reinterpret_cast<const i1*>(wrow + (p.flip ? 2 - kh : kh) * 3))[0];
+        wr[kh] = (int)__builtin_amdgcn_perm(0u, (unsigned)raw, p.flip ? 0x0c020100u : 0x0c000102u);
     }
     int acc[4][4];
 #pragma unroll
@@ -482,6 +484,49 @@ bool depthwise_dx_supported(const daq_conv_desc& d) {
     if (!is_depthwise(d) || d.strideH != d.strideW || log2_exact(d.strideH) < 0) return false;
     if (d.kH > kMaxK || d.kW > kMaxK) return false;
     return (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
+}
+
+// Forward pass of the 3 x 3, unit-stride, padding-1 depthwise layers: the data-gradient kernels on the channel-major
+// activation planes, with the filter rotated by 180 degrees (4 x 4 output blocks where rows are a multiple of four,
+// four outputs of a row per thread otherwise).
+bool depthwise_fwd_supported(const daq_conv_desc& d) {
+    return is_depthwise(d) && d.kH == 3 && d.kW == 3 && d.strideH == 1 && d.strideW == 1 && d.dilH == 1 && d.dilW == 1 &&
+           d.padH == 1 && d.padW == 1 && (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
+}
+
+daq_status conv_fwd_depthwise(const daq_conv_desc& d, const int8_t* qx_cnhw, const int8_t* qw, const float* s_x,
+                              const float* s_w, float* Y, int32_t* acc, hipStream_t st) {
+    daq_layout Lx;
+    daq_wpack_layout Lw;
+    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK || Lx.phases_h != 1 || Lx.phases_w != 1)
+        return DAQ_ERR_INVALID_ARG;
+    DxArgs a{};
+    a.qg = qx_cnhw;
+    a.qw = qw + Lw.off_plain;
+    a.chan_pitch = Lx.chan_pitch;
+    a.lead = (int)Lx.lead; a.img_rows = Lx.img_rows; a.row_pitch = Lx.row_pitch;
+    a.N = d.N; a.C = d.Cin; a.Hin = d.Hin; a.Win = d.Win;   // the result has the input's extent
+    a.kH = 3; a.kW = 3; a.pH = 1; a.pW = 1; a.dH = 1; a.dW = 1;
+    a.wq = (int)ceil_div(d.Win, 4);
+    a.hq = (int)ceil_div(d.Hin, 4);
+    a.div_wq = make_fastdiv((uint32_t)a.wq);
+    a.div_hq = make_fastdiv((uint32_t)a.hq);
+    a.div_h = make_fastdiv((uint32_t)d.Hin);
+    a.div_c = make_fastdiv((uint32_t)d.Cin);
+    a.Ho = d.Hin;
+    a.s_g = s_x; a.s_w = s_w; a.dX = Y; a.acc_out = acc;
+    a.flip = 1;
+    a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
+    if (d.Win % 4 == 0) {
+        const int64_t blocks4 = (int64_t)d.N * d.Cin * a.hq * a.wq;
+        DAQ_LAUNCH("conv_fwd_depthwise", st,
+                   hipLaunchKernelGGL(k_dwise_dx_unit_block, dim3((unsigned)ceil_div(blocks4, kBlock)), dim3(kBlock), 0, st, a));
+    } else {
+        const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
+        DAQ_LAUNCH("conv_fwd_depthwise", st,
+                   hipLaunchKernelGGL((k_dwise_dx_unit<3, 3>), dim3((unsigned)ceil_div(threads, kBlock)), dim3(kBlock), 0, st, a));
+    }
+    return DAQ_OK;
 }
 
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,

@@ -155,6 +155,9 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx_nhwc, const in
 bool depthwise_dx_supported(const daq_conv_desc& d);
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
                                    const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel = false);
+bool depthwise_fwd_supported(const daq_conv_desc& d);
+daq_status conv_fwd_depthwise(const daq_conv_desc& d, const int8_t* qx_cnhw, const int8_t* qw, const float* s_x,
+                              const float* s_w, float* Y, int32_t* acc, hipStream_t st);
 bool depthwise_dw_supported(const daq_conv_desc& d);
 size_t depthwise_dw_ws_bytes(const daq_conv_desc& d);
 daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
