@@ -486,20 +486,94 @@ bool depthwise_dx_supported(const daq_conv_desc& d) {
     return (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
 }
 
+// Forward pass, 3 x 3, stride 2, padding 1, on the channel-major activation planes (one plane per parity of the padded
+// row and column, so a tap is a unit-stride read): tap (kh, kw) of output (ho, wo) is element (ho + kh/2, wo + kw/2)
+// of plane (kh % 2, kw % 2).  A thread produces four adjacent outputs of a row from six 8-byte fetches (two rows of
+// planes (0, 0) and (0, 1), one row of (1, 0) and (1, 1)); which byte a tap reads is the same for every thread.
+struct FwdS2Args {
+    const int8_t* qx;      // [C][4 planes][plane_pitch]
+    const int8_t* qw;      // plain filter copy, [C][9]
+    int64_t chan_pitch, plane_pitch;
+    int lead, img_rows, row_pitch;
+    int N, C, Ho, Wo, wq;
+    FastDiv div_wq, div_ho, div_c;
+    const float* s_x;
+    const float* s_w;
+    float* Y;
+    int32_t* acc_out;
+};
+
+__global__ __launch_bounds__(kBlock) void k_dwise_fwd_s2(FwdS2Args p) {
+    const uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t row = fdiv(i, p.div_wq);
+    if (row >= (uint32_t)p.N * p.C * p.Ho) return;
+    const int wo0 = 4 * (int)(i - row * (uint32_t)p.wq);
+    const uint32_t nc = fdiv(row, p.div_ho);
+    const int ho = (int)(row - nc * (uint32_t)p.Ho);
+    const uint32_t n = fdiv(nc, p.div_c);
+    const int c = (int)(nc - n * (uint32_t)p.C);
+    const int8_t* x = p.qx + (int64_t)c * p.chan_pitch + p.lead;
+    const int8_t* wf = p.qw + c * 9;
+    const int64_t at = (int64_t)((int)n * p.img_rows + ho) * p.row_pitch + wo0;
+    int acc[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int kh = 0; kh < 3; ++kh)
+#pragma unroll
+        for (int pw = 0; pw < 2; ++pw) {
+            // plane (kh % 2, pw), row ho + kh / 2: serves kw = pw (column shift 0) and, for pw = 0, kw = 2 (shift 1)
+            unsigned lo, hi;
+            load8(x + (int64_t)((kh & 1) * 2 + pw) * p.plane_pitch, at + (int64_t)(kh >> 1) * p.row_pitch, lo, hi);
+            const int w_a = wf[kh * 3 + pw];
+            const int w_b = pw == 0 ? wf[kh * 3 + 2] : 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[j] += __builtin_amdgcn_sbfe((int)lo, 8 * j, 8) * w_a;
+                if (pw == 0) acc[j] += __builtin_amdgcn_sbfe((int)(j < 3 ? lo : hi), 8 * ((j + 1) & 3), 8) * w_b;
+            }
+        }
+    const float scale = (*p.s_x / 127.0f) * (*p.s_w / 127.0f);
+    const int64_t o = (int64_t)row * p.Wo + wo0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (wo0 + j < p.Wo) {
+            p.Y[o + j] = (float)acc[j] * scale;
+            if (p.acc_out) p.acc_out[o + j] = acc[j];
+        }
+}
+
 // Forward pass of the 3 x 3, unit-stride, padding-1 depthwise layers: the data-gradient kernels on the channel-major
 // activation planes, with the filter rotated by 180 degrees (4 x 4 output blocks where rows are a multiple of four,
 // four outputs of a row per thread otherwise).
 bool depthwise_fwd_supported(const daq_conv_desc& d) {
-    return is_depthwise(d) && d.kH == 3 && d.kW == 3 && d.strideH == 1 && d.strideW == 1 && d.dilH == 1 && d.dilW == 1 &&
-           d.padH == 1 && d.padW == 1 && (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
+    return is_depthwise(d) && d.kH == 3 && d.kW == 3 && d.strideH == d.strideW && (d.strideH == 1 || d.strideH == 2) &&
+           d.dilH == 1 && d.dilW == 1 && d.padH == 1 && d.padW == 1 &&
+           (int64_t)d.N * d.Cin * d.Hin * ceil_div(d.Win, 4) < ((int64_t)1 << 31);
 }
 
 daq_status conv_fwd_depthwise(const daq_conv_desc& d, const int8_t* qx_cnhw, const int8_t* qw, const float* s_x,
                               const float* s_w, float* Y, int32_t* acc, hipStream_t st) {
     daq_layout Lx;
     daq_wpack_layout Lw;
-    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK || Lx.phases_h != 1 || Lx.phases_w != 1)
-        return DAQ_ERR_INVALID_ARG;
+    if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
+    if (d.strideH == 2) {
+        if (Lx.phases_h != 2 || Lx.phases_w != 2) return DAQ_ERR_INVALID_ARG;
+        FwdS2Args f{};
+        f.qx = qx_cnhw;
+        f.qw = qw + Lw.off_plain;
+        f.chan_pitch = Lx.chan_pitch; f.plane_pitch = Lx.plane_pitch;
+        f.lead = (int)Lx.lead; f.img_rows = Lx.img_rows; f.row_pitch = Lx.row_pitch;
+        f.N = d.N; f.C = d.Cin; f.Ho = daq_out_h(&d); f.Wo = daq_out_w(&d);
+        f.wq = (int)ceil_div(f.Wo, 4);
+        f.div_wq = make_fastdiv((uint32_t)f.wq);
+        f.div_ho = make_fastdiv((uint32_t)f.Ho);
+        f.div_c = make_fastdiv((uint32_t)d.Cin);
+        f.s_x = s_x; f.s_w = s_w; f.Y = Y; f.acc_out = acc;
+        const int64_t threads = (int64_t)d.N * d.Cin * f.Ho * f.wq;
+        DAQ_LAUNCH("conv_fwd_depthwise", st,
+                   hipLaunchKernelGGL(k_dwise_fwd_s2, dim3((unsigned)ceil_div(threads, kBlock)), dim3(kBlock), 0, st, f));
+        return DAQ_OK;
+    }
+    if (Lx.phases_h != 1 || Lx.phases_w != 1) return DAQ_ERR_INVALID_ARG;
     DxArgs a{};
     a.qg = qx_cnhw;
     a.qw = qw + Lw.off_plain;
