@@ -34,13 +34,18 @@ MEASURED_TRAFFIC = {
 }
 
 
-def quantizer_for(scheme: str):
+def quantizer_for(scheme: str, dy_bf16: bool = False):
     """(callable, entry point name): daq_quantize_grad, or daq_quantize_grad_scheme bound to an ablation variant."""
     from paper_2102_04782_amd import binding as daq
 
+    code = {"daq": daq.SCHEME_DAQ, "gq": daq.SCHEME_GQ, "gvq": daq.SCHEME_GVQ, "mcs": daq.SCHEME_MCS}[scheme]
+    if dy_bf16:
+        def quantize16(d, dY, st, **kw):
+            return daq.quantize_grad_bf16(d, dY, st, code, **kw)
+
+        return quantize16, f"daq_quantize_grad_bf16({scheme})"
     if scheme == "daq":
         return daq.quantize_grad, "daq_quantize_grad"
-    code = {"gq": daq.SCHEME_GQ, "gvq": daq.SCHEME_GVQ, "mcs": daq.SCHEME_MCS}[scheme]
 
     def quantize(d, dY, st, **kw):
         return daq.quantize_grad_scheme(d, dY, st, code, **kw)
@@ -59,7 +64,7 @@ def sweep(args, dev) -> int:
     from paper_2102_04782_amd import workloads as wl
 
     layers = wl.config_layers(args.config)
-    quantize, _ = quantizer_for(args.scheme)
+    quantize, _ = quantizer_for(args.scheme, args.dy_bf16)
     steps = max(3, min(args.steps, 20))
     seen, out_layers = {}, []
     tot_wall = tot_ops = 0.0
@@ -71,6 +76,8 @@ def sweep(args, dev) -> int:
             gen = torch.Generator(device=dev)
             gen.manual_seed(wl.seed_for(args.config, li))
             dY = torch.randn(d.y_shape, device=dev, generator=gen) * 1e-2
+            if args.dy_bf16:
+                dY = dY.to(torch.bfloat16)
             st = torch.zeros(d.Cout, device=dev)
             qx = torch.randint(-127, 128, (daq.layout_qx_cnhw(d).bytes,), dtype=torch.int8, device=dev, generator=gen)
             qw = torch.randint(-127, 128, (daq.layout_qw(d).bytes,), dtype=torch.int8, device=dev, generator=gen)
@@ -164,6 +171,9 @@ def main() -> int:
     ap.add_argument("--scheme", default="daq", choices=("daq", "gq", "gvq", "mcs"),
                     help="rule for the per-channel clip values: Algorithm 1 (default) or one of the ablation study's "
                          "variants through daq_quantize_grad_scheme (global baseline, per-channel maximum, layer-wise clipping)")
+    ap.add_argument("--dy-bf16", action="store_true",
+                    help="hand the output gradient over as bfloat16 (daq_quantize_grad_bf16: same algorithm on the widened "
+                         "values, 2 instead of 4 bytes read per element and sweep; reported for comparison, never the default)")
     ap.add_argument("--graph", type=int, default=0, choices=(0, 1),
                     help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--sweep", action="store_true",
@@ -191,7 +201,7 @@ def main() -> int:
     daq.lib()  # fail loudly if the HIP library is missing
     if args.sweep:
         return sweep(args, dev)
-    quantize, quantize_name = quantizer_for(args.scheme)
+    quantize, quantize_name = quantizer_for(args.scheme, args.dy_bf16)
 
     layer, X, W, dY, st = wl.make_inputs(args.config, args.layer)
     d = daq.ConvDesc.make(*layer.desc_fields())
@@ -200,6 +210,9 @@ def main() -> int:
     del X_d
     R = max(1, args.rotate)
     dYs = [torch.from_numpy(dY).to(dev)] + [torch.from_numpy(dY).to(dev).clone() for _ in range(R - 1)]
+    if args.dy_bf16:
+        dYs = [g.to(torch.bfloat16) for g in dYs]
+        dY = dYs[0].float().cpu().numpy()   # what the oracle of the cpu_baseline leg sees: the widened values
     states = [torch.from_numpy(st.copy()).to(dev) for _ in range(R)]
     outs = [daq.alloc_quantize_grad(d, dev, want_stats=False) for _ in range(R)]
     dWs = [torch.empty(d.w_shape, dtype=torch.float32, device=dev) for _ in range(R)]
@@ -297,16 +310,17 @@ def main() -> int:
         del ca, cb
 
     E_Y = int(np.prod(d.y_shape))
+    eb_y = 2.0 if args.dy_bf16 else 4.0   # bytes read per element of dY and sweep
     E_X = int(np.prod(d.x_shape))
     E_W = int(np.prod(d.w_shape))
     ops_per_conv = 2.0 * layer.macs
     ops_per_step = 2.0 * ops_per_conv          # dX + dW
     # algorithmic bytes / ops of one launch of each kernel
     alg_bytes = {
-        "stats": 4.0 * E_Y,
-        "count_qg": 5.0 * E_Y if daq.layout_qg(d).kind == daq.LAYOUT_NHWC else 4.0 * E_Y,
-        "pack_vq": 5.0 * E_Y,
-        "pack_qg": 5.0 * E_Y,
+        "stats": eb_y * E_Y,
+        "count_qg": (eb_y + 1.0) * E_Y if daq.layout_qg(d).kind == daq.LAYOUT_NHWC else eb_y * E_Y,
+        "pack_vq": (eb_y + 1.0) * E_Y,
+        "pack_qg": (eb_y + 1.0) * E_Y,
     }
     # convolutions: int8 operands read once, fp32 result written once
     conv_bytes = {"conv_bwd_data": E_Y + E_W + (2.0 if args.dx_bf16 else 4.0) * E_X, "conv_bwd_filter": E_X + E_Y + 4.0 * E_W}
@@ -369,7 +383,7 @@ def main() -> int:
                                f"{layer.Hin}x{layer.Win} k{layer.kH} s{layer.stride} p{layer.pad}",
                    "rotate": R, "rounding": "nearest", "k": 1.0, "A": 0.8, "lambda": 0.3,
                    "streams": args.streams, "hip_graph": bool(args.graph),
-                   "dX": "bf16" if args.dx_bf16 else "fp32",
+                   "dX": "bf16" if args.dx_bf16 else "fp32", "dY": "bf16" if args.dy_bf16 else "fp32",
                    "scheme": args.scheme,
                    "calls": f"{quantize_name} + daq_conv_bwd_int8" if combined else
                             f"{quantize_name} + daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8"},

@@ -207,6 +207,23 @@ daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, 
                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_bf16 -- daq_quantize_grad_scheme for an output gradient stored as bfloat16
+ * (what a mixed-precision backward pass hands over).  A bfloat16 value is the upper half of an fp32
+ * pattern, so widening is exact: every output equals, bit for bit, what daq_quantize_grad_scheme
+ * returns for the widened tensor - statistics, classes, clip values, both int8 copies, and the
+ * random numbers of stochastic rounding (still indexed by the NCHW position).  The three sweeps
+ * read 2 instead of 4 bytes per element.
+ *
+ *   dY_bf16   in   bfloat16 NCHW, 2-byte aligned (8-byte alignment lets the packing pass load
+ *                  whole vectors)
+ *   all other arguments, the workspace and the error codes as for daq_quantize_grad_scheme
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_quantize_grad_bf16(const daq_conv_desc* desc, const uint16_t* dY_bf16, float* s_state, float k, float A,
+                                  float lambda, daq_round mode, uint64_t seed, daq_scheme scheme, int8_t* vq,
+                                  int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * daq_conv_fwd_int8 -- forward pass of the quantized layer (dataflow figure; the inputs that
  * Algorithm 1 requires).  s_x = max|X|, s_w = max|W| (global quantization, nearest rounding),
  * Y = (int32 conv of the codes) * (s_x/127) * (s_w/127).

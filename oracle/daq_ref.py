@@ -199,6 +199,17 @@ def quantize_grad(dY, s_state, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0
     return QuantGrad(vq, qg, s_chan, float(s_glob[0]), cls, stats, st, frag)
 
 
+def widen_bf16(bits) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> the fp32 values they denote: a bfloat16 is the upper half of an fp32 pattern."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32)
+
+
+def quantize_grad_bf16(dY_bits, s_state, **kw) -> QuantGrad:
+    """The quantizer on a gradient stored as bfloat16: by definition the fp32 algorithm on the widened values."""
+    return quantize_grad(widen_bf16(dY_bits), s_state, **kw)
+
+
 def quantize_tensor(x):
     x = _f32(x)
     q = np.zeros(x.shape, np.int8)

@@ -26,7 +26,7 @@ LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
-    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
     "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string",
 ]
 
@@ -173,6 +173,7 @@ def lib():
                                         vp, vp, sz, vp]
         L.daq_quantize_grad_scheme.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.c_int, vp, vp,
                                                vp, vp, vp, vp, vp, sz, vp]
+        L.daq_quantize_grad_bf16.argtypes = L.daq_quantize_grad_scheme.argtypes
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
@@ -265,6 +266,20 @@ def quantize_grad(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, k=1.0, A
                                  _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
                                  _ptr(out.workspace), out.workspace.numel(), _stream(stream))
     _check(rc, "daq_quantize_grad")
+    return out
+
+
+def quantize_grad_bf16(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, scheme: int = SCHEME_DAQ, k=1.0, A=0.8, lam=0.3,
+                       mode=ROUND_NEAREST, seed=0, out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
+    """daq_quantize_grad_bf16: ``dY`` is a bfloat16 tensor.  ``s_state`` is updated in place."""
+    assert dY.is_cuda and dY.dtype == torch.bfloat16 and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    if out is None:
+        out = alloc_quantize_grad(d, dY.device)
+    rc = lib().daq_quantize_grad_bf16(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, scheme, _ptr(out.vq),
+                                      _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
+                                      _ptr(out.workspace), out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_quantize_grad_bf16")
     return out
 
 

@@ -136,8 +136,32 @@ __device__ __forceinline__ uint32_t pack4(uint32_t a, uint32_t b, uint32_t c, ui
 // anything past the extent) returns 0.0f, which is how ragged tiles and padding positions are read
 // without branches or selects on the loaded value.  Tensors must be smaller than 2 GiB.
 constexpr uint32_t kOobOff = 0x80000000u;
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t f32_rsrc(const float* p, uint32_t bytes) {
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t f32_rsrc(const void* p, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc((void*)p, 0, (int)bytes, 0x00020000);
+}
+// The tensor to quantize is fp32 (T = float) or bfloat16 (T = uint16_t, the upper half of the fp32 pattern: widening
+// is exact, so everything downstream is the fp32 arithmetic on the widened values).  Offsets are in bytes of T.
+__device__ __forceinline__ float widen_bf16(uint32_t b) { return __uint_as_float(b << 16); }
+template <typename T>
+__device__ __forceinline__ float buf_ld(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
+    if constexpr (sizeof(T) == 4) return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
+    else return widen_bf16((uint32_t)(uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, (int)voff, (int)soff, 0));
+}
+// four consecutive elements as fp32 bit patterns / one element, or zeros (see ld16_or_zero)
+template <typename T>
+__device__ __forceinline__ uint4 ld4_or_zero(const T* p, bool ok) {
+    if constexpr (sizeof(T) == 4) {
+        return ld16_or_zero(p, ok);
+    } else {
+        typedef uint32_t u2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+        const u2_a2 v = *reinterpret_cast<const u2_a2*>(ok ? (const void*)p : (const void*)g_zero64);
+        return make_uint4(v[0] << 16, v[0] & 0xffff0000u, v[1] << 16, v[1] & 0xffff0000u);
+    }
+}
+template <typename T>
+__device__ __forceinline__ float ld1_or_zero(const T* p, bool ok) {
+    if constexpr (sizeof(T) == 4) return ldf_or_zero(p, ok);
+    else return widen_bf16(*(ok ? p : reinterpret_cast<const uint16_t*>(g_zero64)));
 }
 __device__ __forceinline__ float buf_ldf(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff) {
     return __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, (int)soff, 0));
@@ -186,8 +210,8 @@ __device__ __forceinline__ void block_reduce(float& mx, double& s1, double& s2) 
 // instead of waiting for a reduction launch.  Channel c runs on XCD c % 8 in every pass over dY.
 // ---------------------------------------------------------------------------------------------
 // TAIL: the plane size is not a multiple of four (the last group of a plane needs the move-back and the mask).
-template <bool VEC4, bool TAIL>
-__global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, int N, int C, int HW, FastDiv div_hw,
+template <typename T, bool VEC4, bool TAIL>
+__global__ __launch_bounds__(kBlock) void k_stats(const T* __restrict__ g, int N, int C, int HW, FastDiv div_hw,
                                                   QuantWs ws) {
     constexpr int NV = VEC4 ? 4 : 16;
     const int b = blockIdx.x;
@@ -215,7 +239,7 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
                 const int qc = ok ? q4 : 0;
                 const int n = (int)fdiv((uint32_t)qc, div_hw), gi = qc - n * G4;   // div_hw divides by G4 here
                 const int i = TAIL ? min(4 * gi, HW - 4) : 4 * gi;
-                uint4 r = ld16_or_zero(g + ((int64_t)n * C + c) * HW + i, ok);
+                uint4 r = ld4_or_zero<T>(g + ((int64_t)n * C + c) * HW + i, ok);
                 if (TAIL) {
                     const int skip = 4 * gi - i;   // > 0 only in a plane's last group
                     r.x = skip > 0 ? 0u : r.x;
@@ -228,7 +252,7 @@ __global__ __launch_bounds__(kBlock) void k_stats(const float* __restrict__ g, i
                 const bool ok = live && m < M;
                 const int mc = ok ? m : 0;
                 const int n = (int)fdiv((uint32_t)mc, div_hw), i = mc - n * HW;
-                dst[u].x = __float_as_uint(ldf_or_zero(g + ((int64_t)n * C + c) * HW + i, ok));
+                dst[u].x = __float_as_uint(ld1_or_zero<T>(g + ((int64_t)n * C + c) * HW + i, ok));
             }
         }
     };
@@ -340,8 +364,8 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
 // final decision), quantizes with it and stores the bytes of the real elements; the packing pass, which takes the
 // decision, then only rewrites the channels whose guess was wrong (and writes the padding).  A correct guess saves
 // the third sweep over dY for that channel; a wrong one costs nothing but the bytes written here.
-template <bool STOCH, bool WRITE_QG, bool COUNT, bool EARLY = false>
-__global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g, int N, int C, int HW, int c_pitch,
+template <typename T, bool STOCH, bool WRITE_QG, bool COUNT, bool EARLY = false>
+__global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, int N, int C, int HW, int c_pitch,
                                                      FastDiv div_hw, QuantWs ws, const float* __restrict__ scale_ptr,
                                                      int8_t* __restrict__ qg, uint64_t seed,
                                                      const float* __restrict__ s_state, float* __restrict__ s_global,
@@ -355,8 +379,11 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
     const int cb = blockIdx.x / ws.cgroups;
     const int c0 = cb * 64 + 16 * wave;
     const uint32_t M = (uint32_t)N * (uint32_t)HW;
-    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(g, (uint32_t)M * (uint32_t)C * 4u);
-    const uint32_t chan_bytes = (uint32_t)HW * 4u;
+    constexpr uint32_t EB = sizeof(T);   // bytes of a source element
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(g, (uint32_t)M * (uint32_t)C * EB);
+    const uint32_t chan_bytes = (uint32_t)HW * EB;
+    // (measured: a gain where the kernel only counts or writes one copy, a loss in the form that writes both copies)
+    const bool dword16 = EB == 2 && !EARLY && (HW & 1) == 0 && ((uintptr_t)g & 3u) == 0;
 
     float x[16];
     uint32_t n_cur = 0, px_cur = 0;
@@ -367,13 +394,24 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const float* __restrict__ g
         const uint32_t Pc = valid ? P : 0u;
         n = fdiv(Pc, div_hw);
         px = Pc - n * (uint32_t)HW;
-        const uint32_t off = valid ? ((n * (uint32_t)C + (uint32_t)c0) * (uint32_t)HW + px) * 4u : kOobOff;
-        if (c0 + 16 <= C) {   // uniform per wave
+        const uint32_t off = valid ? ((n * (uint32_t)C + (uint32_t)c0) * (uint32_t)HW + px) * EB : kOobOff;
+        if (EB == 2 && dword16) {   // uniform
+            // bfloat16 through dword loads (two-byte loads run at a fraction of the rate): the lane fetches the aligned
+            // dword that holds its element - its neighbour fetches the same one - and keeps one half.  Planes start on
+            // dword boundaries here (even plane size, aligned tensor), so the half is the same for all 16 channels.
+            const uint32_t offa = valid ? (off & ~3u) : kOobOff;
+            const bool upper = (off & 2u) != 0;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dst[i] = buf_ldf(rs, off, (uint32_t)i * chan_bytes);
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t raw = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, (int)((c0 + i < C) ? offa : kOobOff), (int)((uint32_t)i * chan_bytes), 0);
+                dst[i] = __uint_as_float(upper ? (raw & 0xffff0000u) : (raw << 16));
+            }
+        } else if (c0 + 16 <= C) {   // uniform per wave
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dst[i] = buf_ld<T>(rs, off, (uint32_t)i * chan_bytes);
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) dst[i] = buf_ldf(rs, c0 + i < C ? off : kOobOff, (uint32_t)i * chan_bytes);
+            for (int i = 0; i < 16; ++i) dst[i] = buf_ld<T>(rs, c0 + i < C ? off : kOobOff, (uint32_t)i * chan_bytes);
         }
     };
     fetch(p, x, n_cur, px_cur, v_cur);
@@ -685,8 +723,8 @@ struct PackArgs {
     uint64_t seed;
 };
 
-template <bool STOCH, bool CLIP>
-__global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ src, CnhwView L,
+template <typename T, bool STOCH, bool CLIP>
+__global__ __launch_bounds__(kBlock) void k_pack_cnhw(const T* __restrict__ src, CnhwView L,
                                                       const float* __restrict__ scale, int8_t* __restrict__ dst,
                                                       PackArgs pa, QuantWs ws, ClipArgs ca) {
     __shared__ uint32_t l_cnt[kBlock / kWave];
@@ -701,18 +739,19 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
     const int plane_dw = (int)(L.plane_pitch >> 2);
     const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
     const uint32_t HW = (uint32_t)(L.H * L.W);
-    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * 4u);
+    constexpr uint32_t EB = sizeof(T);   // bytes of a source element
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * EB);
 
     // All index products below have factors under 2^24 and results under 2^31 (checked by the host), so the
     // full-rate 24-bit multiplier serves.  A destination row (n, r) reads source row h = r*phases_h + ph - org_h
     // of image n; stepping to the next destination row moves the source offset by one of two launch constants.
-    const uint32_t W4 = (uint32_t)L.W * 4u;
+    const uint32_t W4 = (uint32_t)L.W * EB;
     const uint32_t step_row = (uint32_t)L.phases_h * W4;                                  // next row, same image
-    const uint32_t step_img = (uint32_t)L.C * HW * 4u - (uint32_t)(L.img_rows - 1) * step_row;  // row 0 of the next image
+    const uint32_t step_img = (uint32_t)L.C * HW * EB - (uint32_t)(L.img_rows - 1) * step_row;  // row 0 of the next image
     const int h_first = ph - L.org_h, w_first = pw - L.org_w;
 
     float x[4][4];
-    uint32_t eoff[4][4];   // byte offset of the element in the source (also its index * 4), or >= kOobOff
+    uint32_t eoff[4][4];   // byte offset of the element in the source (its index times the element size), or >= kOobOff
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int d = jb * 1024 + tid + 256 * u;   // dword inside the plane
@@ -727,15 +766,15 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
         int h = (int)__umul24(r, (uint32_t)L.phases_h) + h_first;
         // n and h may be negative here (leading padding): signed multiplies keep the offset linear modulo 2^32,
         // so the row steps below land on the right value once the walk reaches a real row
-        uint32_t raw = (uint32_t)(__mul24(__mul24(n, L.C) + c, (int)HW) + __mul24(h, L.W)) * 4u;
+        uint32_t raw = (uint32_t)(__mul24(__mul24(n, L.C) + c, (int)HW) + __mul24(h, L.W)) * EB;
         int w = (int)__umul24((uint32_t)col, (uint32_t)L.phases_w) + w_first;
         int nn = n, rr = (int)r, cc = col;
         const bool live = d < plane_dw;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const bool ok = live & ((unsigned)nn < (unsigned)L.N) & ((unsigned)h < (unsigned)L.H) & ((unsigned)w < (unsigned)L.W);
-            eoff[u][i] = ok ? raw + 4u * (uint32_t)w : kOobOff;
-            x[u][i] = buf_ldf(rs, eoff[u][i], 0u);
+            eoff[u][i] = ok ? raw + EB * (uint32_t)w : kOobOff;
+            x[u][i] = buf_ld<T>(rs, eoff[u][i], 0u);
             // step to the next byte of the plane: next column, possibly next row, possibly next image
             const bool wrap = cc + 1 == L.row_pitch;
             const bool last = wrap & (rr + 1 == L.img_rows);
@@ -761,7 +800,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const float* __restrict__ 
         const int d = jb * 1024 + tid + 256 * u;
         uint32_t bits[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u][i] >> 2));
+        for (int i = 0; i < 4; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u][i] / EB));
         if (d < plane_dw) *reinterpret_cast<uint32_t*>(plane + 4 * (int64_t)d) = pack4(bits[0], bits[1], bits[2], bits[3]);
     }
 }
@@ -802,8 +841,8 @@ __device__ __forceinline__ void store_codes(int8_t* p, uint32_t w) {
     }
 }
 
-template <bool STOCH, bool CLIP, int V>
-__global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ src, CnhwView L,
+template <typename T, bool STOCH, bool CLIP, int V>
+__global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src, CnhwView L,
                                                       const float* __restrict__ scale, int8_t* __restrict__ dst,
                                                       RowsArgs pa, QuantWs ws, ClipArgs ca) {
     __shared__ uint32_t l_cnt[kBlock / kWave];
@@ -857,7 +896,8 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
     const uint32_t HW = (uint32_t)(L.H * L.W), HWV = HW / V, WV = (uint32_t)L.W / V;
     const uint32_t groups = (uint32_t)L.N * HWV;
     const int padw = L.row_pitch - L.W;
-    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * 4u);
+    constexpr uint32_t EB = sizeof(T);   // bytes of a source element
+    const __amdgpu_buffer_rsrc_t rs = f32_rsrc(src, (uint32_t)L.N * (uint32_t)L.C * HW * EB);
 
   // one pass unless the grid was cut down (early mode: the few channels left to do are walked by a few workgroups)
   for (int jb = jb0; jb < pa.per_chan; jb += pa.grid_per_chan) {
@@ -874,16 +914,26 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
         const uint32_t h = fdiv(rem, pa.div_wv);
         const uint32_t wv = rem - __umul24(h, WV);
         row_end[u] = live[u] & (wv + 1 == WV);
-        eoff[u] = live[u] ? __umul24(__umul24(n, (uint32_t)L.C) + (uint32_t)c, HW) * 4u + rem * (4u * V) : kOobOff;
+        eoff[u] = live[u] ? __umul24(__umul24(n, (uint32_t)L.C) + (uint32_t)c, HW) * EB + rem * (EB * V) : kOobOff;
         doff[u] = (uint32_t)L.lead + __umul24(__umul24(n, (uint32_t)L.img_rows) + h, (uint32_t)L.row_pitch) + wv * V;
-        if (V == 4) {
+        if constexpr (EB == 4 && V == 4) {
             const v4u raw = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)eoff[u], 0, 0);
 #pragma unroll
             for (int i = 0; i < V; ++i) x[u][i] = __uint_as_float(raw[i]);
-        } else {
+        } else if constexpr (EB == 4) {
             const v2u raw = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)eoff[u], 0, 0);
 #pragma unroll
             for (int i = 0; i < V; ++i) x[u][i] = __uint_as_float(raw[i]);
+        } else if constexpr (V == 4) {   // four bfloat16 in two dwords
+            const v2u raw = __builtin_amdgcn_raw_buffer_load_b64(rs, (int)eoff[u], 0, 0);
+            x[u][0] = __uint_as_float(raw[0] << 16);
+            x[u][1] = __uint_as_float(raw[0] & 0xffff0000u);
+            x[u][2] = __uint_as_float(raw[1] << 16);
+            x[u][3] = __uint_as_float(raw[1] & 0xffff0000u);
+        } else {                          // two bfloat16 in one dword
+            const uint32_t raw = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, (int)eoff[u], 0, 0);
+            x[u][0] = __uint_as_float(raw << 16);
+            x[u][1] = __uint_as_float(raw & 0xffff0000u);
         }
     }
 
@@ -891,7 +941,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
     for (int u = 0; u < 4; ++u) {
         uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u] >> 2) + i);
+        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u] / EB) + i);
         if (live[u]) store_codes<V>(plane + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
         if (row_end[u])
             for (int k = 0; k < padw; ++k) plane[doff[u] + V + k] = 0;
@@ -903,7 +953,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const float* __restrict__ 
             uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < V; ++i)
-                bits[i] = quant_bits<STOCH>(x[u][i], inv2, pa.seed, pa.tensor2, (uint64_t)(eoff[u] >> 2) + i);
+                bits[i] = quant_bits<STOCH>(x[u][i], inv2, pa.seed, pa.tensor2, (uint64_t)(eoff[u] / EB) + i);
             if (live[u]) store_codes<V>(plane2 + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
             if (row_end[u])
                 for (int k = 0; k < padw; ++k) plane2[doff[u] + V + k] = 0;
@@ -1010,13 +1060,14 @@ bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31)
 
 
 // Elements per thread of the source-driven row kernel (4 or 2), or 0 when the layout needs the output-driven one.
-int rows_vector(const daq_layout& Ld, const float* src) {
+int rows_vector(const daq_layout& Ld, const void* src, int elem_bytes = 4) {
     const int64_t lim24 = (int64_t)1 << 24;
     const bool unsplit = Ld.phases_h == 1 && Ld.phases_w == 1 && Ld.org_h == 0 && Ld.org_w == 0 &&
                          (int64_t)Ld.N * Ld.img_rows < lim24 && (int64_t)Ld.H * Ld.W < lim24 &&
                          (int64_t)(Ld.N + 1) * Ld.C < lim24 && Ld.plane_pitch < ((int64_t)1 << 31);
-    if (unsplit && Ld.W % 4 == 0 && ((uintptr_t)src & 15u) == 0) return 4;
-    if (unsplit && Ld.W % 2 == 0 && ((uintptr_t)src & 7u) == 0) return 2;
+    // the vector of 4 or 2 source elements a thread loads must be aligned as a whole
+    if (unsplit && Ld.W % 4 == 0 && ((uintptr_t)src & (uintptr_t)(4 * elem_bytes - 1)) == 0) return 4;
+    if (unsplit && Ld.W % 2 == 0 && ((uintptr_t)src & (uintptr_t)(2 * elem_bytes - 1)) == 0) return 2;
     return 0;
 }
 
@@ -1024,13 +1075,14 @@ int rows_vector(const daq_layout& Ld, const float* src) {
 // layout allows it, the output-driven kernel otherwise.
 // With dst2 the same pass also writes a second copy quantized with the per-tensor scale scale2 (random stream
 // tensor2); *fused tells whether that happened - the output-driven kernel writes one copy per launch.
-daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src, const daq_layout& Ld,
+template <typename T>
+daq_status launch_pack(const char* name, bool stoch, bool clip, const T* src, const daq_layout& Ld,
                        const float* scale, int per_channel_scale, int8_t* dst, uint32_t tensor, uint64_t seed,
                        const QuantWs& ws, const ClipArgs& ca, hipStream_t st, int8_t* dst2 = nullptr,
                        const float* scale2 = nullptr, uint32_t tensor2 = 0, bool* fused = nullptr, bool early = false) {
     if (fused) *fused = false;
     const CnhwView V = cnhw_view(Ld);
-    const int v = rows_vector(Ld, src);
+    const int v = rows_vector(Ld, src, (int)sizeof(T));
     if (early && !v) return DAQ_ERR_INVALID_ARG;   // the caller checks rows_vector before it asks for the early copy
     if (v) {
         RowsArgs ra{};
@@ -1050,7 +1102,7 @@ daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src
         if (fused) *fused = dst2 != nullptr;
         const dim3 grid((unsigned)(round_up(Ld.C, kXcd) * (ra.grid_per_chan + 1)));
 #define DAQ_ROWS(S, CL, VV) \
-    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_rows<S, CL, VV>), grid, dim3(kBlock), 0, st, src, V, scale, dst, ra, ws, ca))
+    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_rows<T, S, CL, VV>), grid, dim3(kBlock), 0, st, src, V, scale, dst, ra, ws, ca))
         if (v == 4) {
             if (stoch) { if (clip) DAQ_ROWS(true, true, 4); else DAQ_ROWS(true, false, 4); }
             else { if (clip) DAQ_ROWS(false, true, 4); else DAQ_ROWS(false, false, 4); }
@@ -1065,7 +1117,7 @@ daq_status launch_pack(const char* name, bool stoch, bool clip, const float* src
     const PackArgs pa = pack_args(Ld, per_channel_scale, tensor, seed);
     const dim3 grid = pack_grid(Ld);
 #define DAQ_PACK(S, CL) \
-    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_cnhw<S, CL>), grid, dim3(kBlock), 0, st, src, V, scale, dst, pa, ws, ca))
+    DAQ_LAUNCH(name, st, hipLaunchKernelGGL((k_pack_cnhw<T, S, CL>), grid, dim3(kBlock), 0, st, src, V, scale, dst, pa, ws, ca))
     if (stoch) { if (clip) DAQ_PACK(true, true); else DAQ_PACK(true, false); }
     else { if (clip) DAQ_PACK(false, true); else DAQ_PACK(false, false); }
 #undef DAQ_PACK
@@ -1099,7 +1151,7 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
     const int CB = (int)ceil_div(d.Cin, 64);
     QuantWs geo = carve_quant_ws(nullptr, d.Cin, d.N, HW);  // only the tile geometry is used: nothing is counted here
     DAQ_LAUNCH("quant_nhwc", st,
-               hipLaunchKernelGGL((k_count_qg<false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
+               hipLaunchKernelGGL((k_count_qg<float, false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
                                   d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
                                   (uint64_t)0, (const float*)nullptr, (float*)nullptr, EarlyVq{}));
     const daq_status prc = launch_pack("pack_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st);
@@ -1133,16 +1185,20 @@ using namespace daq;
 // ---------------------------------------------------------------------------------------------
 // Algorithm 1, per-channel loop + vectorized and global quantization
 // ---------------------------------------------------------------------------------------------
-extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,
-                                               float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
-                                               int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
-                                               float* stats, void* workspace, size_t workspace_bytes, void* stream) {
+namespace {
+
+// T = float or uint16_t (bfloat16): the element type of dY
+template <typename T>
+daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_state, float k, float A, float lambda,
+                              daq_round mode, uint64_t seed, daq_scheme scheme, int8_t* vq, int8_t* qg, float* s_chan,
+                              float* s_global, uint8_t* cls, float* stats, void* workspace, size_t workspace_bytes,
+                              void* stream) {
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
     if (scheme != DAQ_SCHEME_DAQ && scheme != DAQ_SCHEME_GQ && scheme != DAQ_SCHEME_GVQ && scheme != DAQ_SCHEME_MCS)
         return DAQ_ERR_INVALID_ARG;
-    if (((uintptr_t)dY & 3u) || ((uintptr_t)vq & 15u) || ((uintptr_t)qg & 15u)) return DAQ_ERR_INVALID_ARG;
+    if (((uintptr_t)dY & (sizeof(T) - 1)) || ((uintptr_t)vq & 15u) || ((uintptr_t)qg & 15u)) return DAQ_ERR_INVALID_ARG;
     daq_layout Lv, Lg;
     daq_status rc = daq_layout_vq(desc, &Lv);
     if (rc != DAQ_OK) return rc;
@@ -1169,11 +1225,11 @@ extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const 
     const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.slabs);
     const FastDiv div_g4 = make_fastdiv((uint32_t)((HW + 3) / 4));
     if (vec4 && HW % 4 == 0)
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<T, true, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
     else if (vec4)
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<true, true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<T, true, true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
     else
-        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<false, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
+        DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<T, false, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_hw, ws));
 
     if (scheme == DAQ_SCHEME_MCS)
         DAQ_LAUNCH("layer_stats", st, hipLaunchKernelGGL(k_layer_stats, dim3(1), dim3(kBlock), 0, st, ws, C, Mtot));
@@ -1187,7 +1243,7 @@ extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const 
     // latency, not by bytes, and keep the leaner counting kernel.
     static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");   // tuning override, read once: smallest gradient (elements)
     const int64_t early_min = early_env ? atoll(early_env) : kEarlyVqMinElems;
-    const bool early = scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY) != 0 && (int64_t)N * C * HW >= early_min &&
+    const bool early = scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY, (int)sizeof(T)) != 0 && (int64_t)N * C * HW >= early_min &&
                        Lv.lead + (int64_t)N * Lv.img_rows * Lv.row_pitch < ((int64_t)1 << 32);
     EarlyVq ev{};
     if (early) {
@@ -1198,7 +1254,7 @@ extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const 
     }
 #define DAQ_COUNT_LAUNCH(S, Q, E)                                                                                    \
     DAQ_LAUNCH("count_qg", st,                                                                                       \
-               hipLaunchKernelGGL((k_count_qg<S, Q, true, E>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,             \
+               hipLaunchKernelGGL((k_count_qg<T, S, Q, true, E>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,             \
                                   qg_nhwc ? Lg.c_pitch : 0, div_hw, ws, no_scale, qg, seed, (const float*)s_state,   \
                                   s_global, ev))
     if (early) {
@@ -1226,6 +1282,24 @@ extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const 
     if (!qg_nhwc && !fused)
         rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, seed, ws, ClipArgs{}, st);
     return rc;
+}
+
+}  // namespace
+
+extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,
+                                               float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
+                                               int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
+                                               float* stats, void* workspace, size_t workspace_bytes, void* stream) {
+    return quantize_grad_impl<float>(desc, dY, s_state, k, A, lambda, mode, seed, scheme, vq, qg, s_chan, s_global, cls, stats,
+                                     workspace, workspace_bytes, stream);
+}
+
+extern "C" daq_status daq_quantize_grad_bf16(const daq_conv_desc* desc, const uint16_t* dY_bf16, float* s_state, float k,
+                                             float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
+                                             int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
+                                             float* stats, void* workspace, size_t workspace_bytes, void* stream) {
+    return quantize_grad_impl<uint16_t>(desc, dY_bf16, s_state, k, A, lambda, mode, seed, scheme, vq, qg, s_chan, s_global, cls,
+                                        stats, workspace, workspace_bytes, stream);
 }
 
 extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,

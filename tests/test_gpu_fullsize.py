@@ -181,3 +181,29 @@ def test_ablation_schemes_at_benchmark_sizes(config, scheme):
     want_g = torch.from_numpy(r.qg).to(device)
     assert torch.equal(_logical_view(Lv, out.vq), want_v), "vq codes"
     assert torch.equal(_logical_view(Lg, out.qg), want_g), "qg codes"
+
+
+@pytest.mark.parametrize("config,index", [(2, 0), (4, 3), (4, 12), (5, 0), (5, 1), (5, 3)], ids=str)
+def test_bf16_gradient_at_full_size(config, index):
+    """daq_quantize_grad_bf16 on full-size gradients (the early per-channel copy, depthwise and strided layouts included):
+    every output equals what the fp32 entry point - itself checked against the oracle above - returns for the widened tensor."""
+    device = torch.device("cuda:0")
+    layer = wl.config_layers(config)[index]
+    d = daq.ConvDesc.make(*layer.desc_fields())
+    seed = wl.seed_for(config, index)
+    dY = torch.from_numpy(wl.make_dY(layer, seed)).to(device).to(torch.bfloat16)
+    st = wl.make_state(dY.float().cpu().numpy(), seed)
+    s1, s2 = torch.from_numpy(st.copy()).to(device), torch.from_numpy(st.copy()).to(device)
+    a = daq.quantize_grad_bf16(d, dY, s1)
+    b = daq.quantize_grad(d, dY.float().contiguous(), s2)
+    torch.cuda.synchronize()
+    Lv, Lg = daq.layout_vq(d), daq.layout_qg(d)
+    assert torch.equal(_logical_view(Lv, a.vq), _logical_view(Lv, b.vq)), "vq codes"
+    assert torch.equal(_logical_view(Lg, a.qg), _logical_view(Lg, b.qg)), "qg codes"
+    assert torch.equal(a.stats, b.stats) and torch.equal(a.cls, b.cls) and torch.equal(a.s_chan, b.s_chan)
+    assert torch.equal(s1, s2) and torch.equal(a.s_global, b.s_global)
+    if config == 2:   # and against the oracle itself
+        r = ref.quantize_grad(dY.float().cpu().numpy(), st)
+        assert torch.equal(_logical_view(Lv, a.vq), torch.from_numpy(r.vq).to(device))
+        assert torch.equal(_logical_view(Lg, a.qg), torch.from_numpy(r.qg).to(device))
+        assert np.array_equal(a.cls.cpu().numpy(), r.cls) and np.array_equal(a.stats.cpu().numpy(), r.stats)

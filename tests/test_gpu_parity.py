@@ -256,6 +256,73 @@ def test_depthwise_data_gradient_from_the_per_channel_copy_end_to_end(layer):
     assert np.median(err(got) / err(glob)) < 0.5
 
 
+# ------------------------------------------------------------------------------------------------ bfloat16 gradients
+
+def check_quantize_grad_bf16(layer, dY, st, scheme=daq.SCHEME_DAQ, misalign=0, **kw):
+    """dY rounded to bfloat16 goes to daq_quantize_grad_bf16 and, widened, to the oracle: every output bit for bit."""
+    d, _ = descs(layer)
+    bits = ref.bf16_bits(dY).astype(np.uint16)
+    buf = torch.zeros(bits.size + 8, dtype=torch.bfloat16, device=dev())
+    g = buf[misalign:misalign + bits.size].view(dY.shape)
+    g.copy_(torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev()).view(dY.shape))
+    st_dev = t(st.copy())
+    out = daq.quantize_grad_bf16(d, g, st_dev, scheme, **kw)
+    torch.cuda.synchronize()
+    r = ref.quantize_grad_bf16(bits, st, scheme=scheme, **kw)
+    assert np.array_equal(out.stats.cpu().numpy(), r.stats), "statistics"
+    assert np.array_equal(out.cls.cpu().numpy(), r.cls), "classes"
+    close(out.s_chan.cpu().numpy(), r.s_chan, "s_chan")
+    close(st_dev.cpu().numpy(), r.s_state, "s_state")
+    close(out.s_global.cpu().numpy(), [r.s_global], "s_global")
+    Lv, Lg = daq.layout_vq(d), daq.layout_qg(d)
+    assert np.array_equal(Lv.unpack(out.vq), r.vq), "vq codes"
+    assert np.array_equal(Lg.unpack(out.qg), r.qg), "qg codes"
+    assert Lv.padding_is_zero(out.vq)
+    # and the same bits as the fp32 entry point on the widened tensor
+    st2 = t(st.copy())
+    wide = daq.quantize_grad_scheme(d, g.float().contiguous(), st2, scheme, **kw)
+    torch.cuda.synchronize()
+    assert np.array_equal(Lv.unpack(wide.vq), Lv.unpack(out.vq)) and np.array_equal(Lg.unpack(wide.qg), Lg.unpack(out.qg))
+    assert torch.equal(wide.s_chan, out.s_chan) and torch.equal(st2, st_dev) and torch.equal(wide.cls, out.cls)
+    assert torch.equal(wide.stats, out.stats) and torch.equal(wide.s_global, out.s_global)
+
+
+def test_quantize_grad_bf16_config1_all_modes():
+    layer, X, W, dY, st = wl.make_inputs(1)
+    check_quantize_grad_bf16(layer, dY, st)
+    check_quantize_grad_bf16(layer, dY, np.zeros_like(st))
+    check_quantize_grad_bf16(layer, dY, st, k=1.5, A=0.8)
+    check_quantize_grad_bf16(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=7)
+    check_quantize_grad_bf16(layer, dY, st, lam=0.0)
+    check_quantize_grad_bf16(layer, dY, st, lam=1.0)
+    for scheme, _ in SCHEMES[1:]:
+        check_quantize_grad_bf16(layer, dY, st, scheme=scheme)
+
+
+@pytest.mark.parametrize("layer", ODD_LAYERS, ids=lambda l: l.name)
+def test_quantize_grad_bf16_ragged_shapes(layer):
+    seed = wl.seed_for(14, ODD_LAYERS.index(layer))
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    check_quantize_grad_bf16(layer, dY, st)
+    check_quantize_grad_bf16(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=99)
+    for shift in (1, 2, 3):                       # sources that are only 2-, 4- or 6-byte aligned
+        check_quantize_grad_bf16(layer, dY, st, misalign=shift)
+
+
+def test_quantize_grad_bf16_degenerate_tensors():
+    layer = wl.Layer("deg", 2, 4, 8, 8, 6, 3, 3, 1, 1)
+    rng = np.random.default_rng(3)
+    dY = rng.normal(0, 1e-2, layer.y_shape).astype(np.float32)
+    dY[:, 0] = 0.0
+    dY[:, 1] = 0.5
+    dY[:, 2] = np.float32(1e-38)
+    dY[:, 3, 0, 0] = 1e4
+    st = np.zeros(6, np.float32)
+    check_quantize_grad_bf16(layer, dY, st)
+    check_quantize_grad_bf16(layer, np.zeros_like(dY), st)
+
+
 def test_unknown_scheme_is_refused():
     layer, X, W, dY, st = wl.make_inputs(1)
     d, _ = descs(layer)

@@ -440,3 +440,32 @@ def test_ablation_ordering_of_quantization_error(ref):
     # without history the first iteration clips at |g|max everywhere: Algorithm 1 and its layer-wise form
     # coincide with GVQ and GQ there
     assert np.array_equal(err["daq"], err["gvq"]) and np.array_equal(err["mcs"], err["gq"])
+
+
+# ----------------------------------------------------------------------------- bfloat16 gradients
+
+def test_bf16_widening_is_the_library_conversion_on_every_pattern(ref):
+    import torch
+
+    bits = np.arange(65536, dtype=np.uint16)
+    want = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).float().numpy()
+    got = ref.widen_bf16(bits)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))           # bit patterns, NaNs included
+    # rounding to bfloat16 and widening again is the identity on bfloat16 values, and a projection on fp32
+    finite = np.isfinite(got)
+    assert np.array_equal(ref.bf16_bits(got[finite]), bits[finite])
+
+
+def test_quantizer_on_bf16_gradient_is_the_fp32_algorithm_on_the_widened_values(ref):
+    g = _mixed_gradient(41)
+    bits = ref.bf16_bits(g).astype(np.uint16)
+    wide = ref.widen_bf16(bits)
+    assert np.max(np.abs(wide - g) / np.abs(g)) <= 2.0 ** -8                    # bfloat16 keeps 8 significant bits
+    C = g.shape[1]
+    a = ref.quantize_grad_bf16(bits, np.zeros(C, np.float32), mode=ref.ROUND_STOCHASTIC, seed=3)
+    b = ref.quantize_grad(wide, np.zeros(C, np.float32), mode=ref.ROUND_STOCHASTIC, seed=3)
+    assert np.array_equal(a.vq, b.vq) and np.array_equal(a.qg, b.qg) and np.array_equal(a.s_chan, b.s_chan)
+    # the largest element of a channel is a bfloat16 value itself, so it still maps to a grid end
+    c = ref.quantize_grad_bf16(bits, np.zeros(C, np.float32))
+    assert np.array_equal(c.s_chan, np.abs(wide).max(axis=(0, 2, 3)))
+    assert all(np.abs(c.vq[:, ch]).max() == 127 for ch in range(C))
