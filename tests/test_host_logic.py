@@ -182,6 +182,10 @@ def test_workspace_and_validation_without_a_gpu():
     chan = lambda desc=d, vq=one: lib.daq_conv_bwd_data_int8_chan(C.byref(desc), vq, one, one, one, one, None, one, 1 << 20, None)
     assert chan() == daq.ERR_UNSUPPORTED                                       # a dense layer
     assert chan(vq=None) == daq.ERR_INVALID_ARG and chan(vq=odd) == daq.ERR_INVALID_ARG and chan(desc=bad) == daq.ERR_INVALID_ARG
+    b16 = lambda dY=one, scheme=0, wsb=1 << 20: lib.daq_quantize_grad_bf16(C.byref(d), dY, one, 1.0, 0.8, 0.3, 0, 0, scheme, one, one,
+                                                                        one, one, one, None, one, wsb, None)
+    assert b16(dY=None) == daq.ERR_INVALID_ARG and b16(dY=odd) == daq.ERR_INVALID_ARG and b16(scheme=9) == daq.ERR_INVALID_ARG
+    assert b16(wsb=8) == daq.ERR_WORKSPACE
     assert daq.status_string(daq.ERR_WORKSPACE).startswith("workspace")
 
 
