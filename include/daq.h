@@ -176,7 +176,8 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  * Schedule (results do not depend on it): three sweeps over dY - statistics; count + qg; vq.  For
  * gradients of 16 Mi elements and more the second sweep also writes vq under a class guessed from
  * |g|max / sigma, and the third only redoes the channels whose guess was wrong.  The environment
- * variable DAQ_EARLY_VQ_MIN (elements, read once per process) overrides that size.
+ * variable DAQ_EARLY_VQ_MIN (elements, read once per process) overrides that size (and the size from which
+ * daq_conv_fwd_int8 writes both layouts of q(X) in one sweep).
  * ------------------------------------------------------------------------------------------- */
 daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
                              float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg, float* s_chan,

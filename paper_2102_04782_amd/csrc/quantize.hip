@@ -448,6 +448,8 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
         // layer-wise clipping compares every element with the standard deviation of the whole tensor
         l_sigma[tid] = ws.scheme == DAQ_SCHEME_MCS ? ws.layer[2] : sig;
     }
+    // forward pass (nothing is counted, the scale is given): the channel-major copy takes the same per-tensor scale
+    if (!COUNT && EARLY && tid < 64) l_inv[tid] = inv_scale(sg);
     __syncthreads();
     if (!scale_ptr) sg = fmaxf(fmaxf(l_max[0], l_max[1]), fmaxf(l_max[2], l_max[3]));
     const float sg_raw = sg;
@@ -875,7 +877,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
     // The counting pass guessed this channel's class: its bytes are in place if the guess was right (same clip rule
     // on the same inputs, hence the same scale and the same codes), and then nothing of dY is read here.
     float s = 0.0f;
-    if (CLIP && pa.early) {
+    if (pa.early) {
         // the data workgroups of a correctly guessed channel return below: the zero bytes between the rows, which they
         // would have written along with the codes, are shared out among them first
         const uint32_t pw = (uint32_t)(L.row_pitch - L.W), rows = (uint32_t)L.N * (uint32_t)L.H;
@@ -885,9 +887,13 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
             plane[at] = 0;
             if (plane2) plane2[at] = 0;
         }
-        int klass;
-        s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt, &klass);
-        if ((uint32_t)klass == ws.pred[c]) return;   // uniform
+        if constexpr (!CLIP) {
+            return;   // a copy under a given scale (forward pass) is complete once its padding is written
+        } else {
+            int klass;
+            s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt, &klass);
+            if ((uint32_t)klass == ws.pred[c]) return;   // uniform
+        }
     }
     if (CLIP && !pa.early) s = clip_value(ws, ca, c, (double)L.N * (double)L.H * (double)L.W, jb0 == 0, l_cnt);
     else if (!CLIP) s = pa.per_channel_scale ? scale[c] : scale[0];
@@ -1150,6 +1156,20 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
     const int HW = d.Hin * d.Win;
     const int CB = (int)ceil_div(d.Cin, 64);
     QuantWs geo = carve_quant_ws(nullptr, d.Cin, d.N, HW);  // only the tile geometry is used: nothing is counted here
+    // Unit-stride layers whose channel-major layout the row kernel serves: one sweep over X writes both copies (the
+    // mechanism of the early per-channel copy of dY, with the per-tensor scale), then the padding bytes are filled in.
+    // (from 8 Mi elements on: below that the two lean passes are faster, as for dY; DAQ_EARLY_VQ_MIN overrides both sizes)
+    static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");
+    if (n >= (early_env ? atoll(early_env) : ((int64_t)8 << 20)) && rows_vector(Lc, X) != 0 && Lc.lead + (int64_t)d.N * Lc.img_rows * Lc.row_pitch < ((int64_t)1 << 32)) {
+        const EarlyVq ev{qx_cnhw, Lc.chan_pitch, (int32_t)Lc.lead, Lc.img_rows, Lc.row_pitch, Lc.W, make_fastdiv((uint32_t)Lc.W),
+                         0.0f, 0.0f, 0.0f, Lc.W % 4 == 0 ? 1 : 0};
+        DAQ_LAUNCH("quant_both", st,
+                   hipLaunchKernelGGL((k_count_qg<float, false, true, false, true>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X,
+                                      d.N, d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
+                                      (uint64_t)0, (const float*)nullptr, (float*)nullptr, ev));
+        return launch_pack("pad_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st, nullptr, nullptr,
+                           0, nullptr, true);
+    }
     DAQ_LAUNCH("quant_nhwc", st,
                hipLaunchKernelGGL((k_count_qg<float, false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
                                   d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,

@@ -622,7 +622,8 @@ def test_random_descriptors_of_the_specialised_kernels(layer):
 def test_early_per_channel_copy_on_small_shapes():
     """The counting pass writes the per-channel copy itself only for large gradients; DAQ_EARLY_VQ_MIN=0 (read once
     per process) turns that on for every size, so the quantizer tests above are run again in a child process with it:
-    ragged shapes, degenerate channels, both rounding modes, wrong guesses (lambda 0 and 1)."""
+    ragged shapes, degenerate channels, both rounding modes, wrong guesses (lambda 0 and 1).  The forward pass writes
+    both layouts of q(X) in one sweep under the same switch, so its layer tests run there too."""
     import os
     import subprocess
     import sys
@@ -630,7 +631,8 @@ def test_early_per_channel_copy_on_small_shapes():
     env = dict(os.environ, DAQ_EARLY_VQ_MIN="0")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     res = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "gpu", "-p", "no:cacheprovider", __file__, "-k",
-                          "quantize_grad or state_carries"], cwd=root, env=env, capture_output=True, text=True, timeout=600)
+                          "quantize_grad or state_carries or forward_layer"], cwd=root, env=env, capture_output=True, text=True,
+                         timeout=600)
     assert res.returncode == 0, res.stdout[-3000:] + res.stderr[-2000:]
 
 
