@@ -53,6 +53,57 @@ def quantizer_for(scheme: str, dy_bf16: bool = False):
     return quantize, f"daq_quantize_grad_scheme({scheme})"
 
 
+def sweep_forward(args, dev) -> int:
+    """The forward entry point (daq_conv_fwd_int8: max of X and W, both layouts of q(X), packed q(W), Y) over every conv
+    layer of a config, distinct shapes timed once.  Not the benchmark's metric: it produces the operands the backward
+    step starts from; reported so that the figures in the design notes can be reproduced."""
+    import torch
+
+    from paper_2102_04782_amd import binding as daq
+    from paper_2102_04782_amd import workloads as wl
+
+    layers = wl.config_layers(args.config)
+    steps = max(3, min(args.steps, 20))
+    seen, rows_out = {}, []
+    tot = {"conv": 0.0, "quantize_x": 0.0, "quantize_w": 0.0}
+    for li, L in enumerate(layers):
+        key = L.desc_fields()
+        if key not in seen:
+            d = daq.ConvDesc.make(*key)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(wl.seed_for(args.config, li))
+            X = torch.randn(d.x_shape, device=dev, generator=gen)
+            W = torch.randn(d.w_shape, device=dev, generator=gen)
+            out = daq.alloc_fwd(d, dev)
+            for _ in range(3):
+                daq.conv_fwd_int8(d, X, W, out=out)
+            torch.cuda.synchronize()
+            daq.prof_begin()
+            for _ in range(steps):
+                daq.conv_fwd_int8(d, X, W, out=out)
+            rows = daq.prof_end()
+            ev = rows.pop("(empty event pair)", (0.0, 1))
+            ev_us = 1e3 * ev[0] / ev[1]
+            # per step: a name launched twice (fill, absmax, scale run for X and for W) counts twice
+            t = {k: (1e3 * v[0] / v[1] - ev_us) * (v[1] / steps) for k, v in rows.items()}
+            conv = sum(v for k, v in t.items() if k.startswith("conv"))
+            qw = t.get("pack_w", 0.0)
+            seen[key] = (conv, sum(t.values()) - conv - qw, qw)
+            del X, W, out
+        conv, qx, qw = seen[key]
+        tot["conv"] += conv
+        tot["quantize_x"] += qx
+        tot["quantize_w"] += qw
+        rows_out.append({"layer": L.name, "conv_us": round(conv, 1), "quantize_us": round(qx + qw, 1)})
+    total = sum(tot.values())
+    print(json.dumps({"metric": "forward entry point, kernel time (HIP events)", "value": round(1e-3 * total, 4), "unit": "ms",
+                      "higher_is_better": False, "n_gpus": 1, "data": "synthetic", "dtype": "int8",
+                      "config": {"workload": f"config{args.config}: all {len(layers)} conv layers, {len(seen)} distinct shapes, "
+                                             f"N={layers[0].N}, daq_conv_fwd_int8 once each"},
+                      "kernel_us_total": {k: round(v, 1) for k, v in tot.items()}, "layers": rows_out}))
+    return 0
+
+
 def sweep(args, dev) -> int:
     """Whole-network pass: the backward step of every conv layer of a config, back to back per shape.
 
@@ -178,6 +229,8 @@ def main() -> int:
                     help="1: capture one step into a HIP graph and time replays of it")
     ap.add_argument("--sweep", action="store_true",
                     help="time the step of every layer of --config (distinct shapes once) and report the network total")
+    ap.add_argument("--forward", action="store_true",
+                    help="with --sweep: time the forward entry point (daq_conv_fwd_int8) of every layer instead of the backward step")
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="after the timed region, run 5 device-to-device copies of this many MiB: the plain copy "
                          "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
@@ -200,7 +253,7 @@ def main() -> int:
     torch.cuda.set_device(dev)
     daq.lib()  # fail loudly if the HIP library is missing
     if args.sweep:
-        return sweep(args, dev)
+        return sweep_forward(args, dev) if args.forward else sweep(args, dev)
     quantize, quantize_name = quantizer_for(args.scheme, args.dy_bf16)
 
     layer, X, W, dY, st = wl.make_inputs(args.config, args.layer)
