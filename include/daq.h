@@ -173,11 +173,9 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  *   stats     out  optional (may be NULL) fp32 [Cout][4] = |g|max, mean, sigma, P
  * Hyper-parameters of the paper: k = 1, A = 0.8, lambda = 0.3.
  *
- * Schedule (results do not depend on it): three sweeps over dY - statistics; count + qg; vq.  For
- * gradients of 16 Mi elements and more the second sweep also writes vq under a class guessed from
- * |g|max / sigma, and the third only redoes the channels whose guess was wrong.  The environment
- * variable DAQ_EARLY_VQ_MIN (elements, read once per process) overrides that size (and the size from which
- * daq_conv_fwd_int8 writes both layouts of q(X) in one sweep).
+ * Schedule (results do not depend on it, see daq_schedule): three sweeps over dY - statistics;
+ * count + qg; vq.  For gradients of 16 Mi elements and more the second sweep also writes vq under a
+ * class guessed from |g|max / sigma, and the third only redoes the channels whose guess was wrong.
  * ------------------------------------------------------------------------------------------- */
 daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
                              float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg, float* s_chan,
@@ -206,6 +204,35 @@ daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, 
                                     float lambda, daq_round mode, uint64_t seed, daq_scheme scheme, int8_t* vq,
                                     int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats,
                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_ex -- the quantizer with every option explicit; the three entry points around it
+ * forward to it.  The library reads no environment variable and keeps no tuning state: which kernels
+ * run is a function of the arguments alone.
+ *
+ *   opts->scheme    daq_scheme (rule for the per-channel clip values)
+ *   opts->schedule  daq_schedule: how the sweeps over dY are shared out among the launches.  The
+ *                   results are the same bits under every schedule.
+ *                     DAQ_SCHEDULE_AUTO          the library picks by size (what the other entry points do)
+ *                     DAQ_SCHEDULE_THREE_SWEEPS  statistics; count + qg; vq
+ *                     DAQ_SCHEDULE_EARLY_COPY    the counting sweep also writes vq under a guessed class
+ *                   A schedule the layer cannot take (the early copy needs Algorithm 1's rule, an NHWC
+ *                   global copy and an unsplit channel-major layout with rows of even length) falls
+ *                   back to three sweeps.
+ *   opts->dy_bf16   0: dY is fp32; 1: dY is bfloat16 (see daq_quantize_grad_bf16)
+ *   opts->reserved  must be 0
+ *   opts == NULL    Algorithm 1, automatic schedule, fp32
+ * Other arguments, the workspace and the error codes as for daq_quantize_grad; an unknown scheme or
+ * schedule is DAQ_ERR_INVALID_ARG.
+ * ------------------------------------------------------------------------------------------- */
+typedef enum { DAQ_SCHEDULE_AUTO = 0, DAQ_SCHEDULE_THREE_SWEEPS = 1, DAQ_SCHEDULE_EARLY_COPY = 2 } daq_schedule;
+typedef struct {
+    int32_t scheme, schedule, dy_bf16, reserved;
+} daq_quantize_opts;
+daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void* dY, float* s_state, float k, float A, float lambda,
+                                daq_round mode, uint64_t seed, const daq_quantize_opts* opts, int8_t* vq, int8_t* qg,
+                                float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
+                                size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * daq_quantize_grad_bf16 -- daq_quantize_grad_scheme for an output gradient stored as bfloat16
@@ -239,6 +266,13 @@ daq_status daq_quantize_grad_bf16(const daq_conv_desc* desc, const uint16_t* dY_
 daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
                              int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y, int32_t* acc_out,
                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* daq_conv_fwd_int8 with the schedule of its activation quantizer explicit: DAQ_SCHEDULE_EARLY_COPY
+ * writes both layouts of q(X) in one sweep over X (taken by default from 8 Mi elements on, where
+ * the channel-major layout is unsplit), DAQ_SCHEDULE_THREE_SWEEPS one sweep per layout.  Same bits. */
+daq_status daq_conv_fwd_int8_ex(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
+                                int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y, int32_t* acc_out,
+                                daq_schedule schedule, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * daq_conv_bwd_data_int8 -- Eq. "gx" on int8 codes with int32 accumulation:
@@ -325,7 +359,9 @@ daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* 
 /* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every
  * kernel the library launches is bracketed by a HIP event pair on its stream.  daq_prof_end()
- * waits for those events and fills one row per distinct kernel name.  Not thread-safe.
+ * waits for those events and fills one row per distinct kernel name.  The list of pending event
+ * pairs is the only state the library keeps between calls; it is guarded by a mutex, and while no
+ * measurement is open the entry points do not touch it.
  * ------------------------------------------------------------------------------------------- */
 typedef struct {
     char name[64];
@@ -334,6 +370,17 @@ typedef struct {
 } daq_prof_row;
 daq_status daq_prof_begin(void);
 daq_status daq_prof_end(daq_prof_row* rows, int32_t max_rows, int32_t* n_rows);
+
+/* Machine ceilings, for pricing the kernels against what this GPU delivers rather than against data-sheet peaks only.
+ * Both enqueue one kernel on `stream` and return at once; the caller times them (events around the call).
+ *   daq_ceiling_mfma_i8: `blocks` workgroups of four waves, each wave `iters` x 4 independent 32x32x32 int8 matrix-core
+ *     multiply-accumulates on register operands; *ops receives the int8 operations (2 per multiply-add) of the launch.
+ *   daq_ceiling_stream: mode 0 reads `bytes` of src, mode 1 writes `bytes` to dst, mode 2 copies src to dst, as 16-byte
+ *     accesses from `blocks` workgroups.  src / dst are device memory, 16-byte aligned.
+ *   sink: 4 bytes of device memory the kernels may write (never in practice; it keeps their work alive). */
+daq_status daq_ceiling_mfma_i8(int32_t blocks, int32_t iters, void* sink, double* ops, void* stream);
+daq_status daq_ceiling_stream(int32_t mode, const void* src, void* dst, size_t bytes, int32_t blocks, void* sink,
+                              void* stream);
 
 /* Human-readable name of a status code (static storage). */
 const char* daq_status_string(daq_status s);

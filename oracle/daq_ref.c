@@ -669,11 +669,58 @@ int daq_ref_conv_bwd_filter_acc_at(const ref_conv_desc* d, const int8_t* qX, con
     return REF_OK;
 }
 
+/* Forward accumulators at single positions: idx[i] is the linear NCHW index into Y
+ * (the integer convolution of daq_ref_conv_fwd_acc, one output per index). */
+int daq_ref_conv_fwd_acc_at(const ref_conv_desc* d, const int8_t* qX, const int8_t* qW, const int64_t* idx,
+                            int64_t count, int32_t* out) {
+    if (!desc_ok(d) || !qX || !qW || !idx || !out || count < 0) return REF_BAD_ARG;
+    const int Ho = daq_ref_out_h(d), Wo = daq_ref_out_w(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    const int64_t total = (int64_t)d->N * d->Cout * Ho * Wo;
+    for (int64_t i = 0; i < count; ++i)
+        if (idx[i] < 0 || idx[i] >= total) return REF_BAD_ARG;
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t i = 0; i < count; ++i) {
+        int64_t r = idx[i];
+        const int wo = (int)(r % Wo); r /= Wo;
+        const int ho = (int)(r % Ho); r /= Ho;
+        const int co = (int)(r % d->Cout);
+        const int n = (int)(r / d->Cout);
+        const int g = co / cog;
+        int64_t a = 0;
+        for (int cl = 0; cl < cig; ++cl) {
+            const int ci = g * cig + cl;
+            for (int kh = 0; kh < d->kH; ++kh) {
+                const int h = ho * d->strideH + kh * d->dilH - d->padH;
+                if (h < 0 || h >= d->Hin) continue;
+                for (int kw = 0; kw < d->kW; ++kw) {
+                    const int w = wo * d->strideW + kw * d->dilW - d->padW;
+                    if (w < 0 || w >= d->Win) continue;
+                    a += (int64_t)qX[(((size_t)n * d->Cin + ci) * d->Hin + h) * d->Win + w] *
+                         (int64_t)qW[(((size_t)co * cig + cl) * d->kH + kh) * d->kW + kw];
+                }
+            }
+        }
+        int o = 0;
+        out[i] = wrap32(a, &o);
+    }
+    return REF_OK;
+}
+
 /* ------------------------------------------------------------------------- */
 /* De-quantization of an accumulator: acc * (s_a/127) * (s_b/127), evaluated   */
 /* in fp32 as  (float)acc * ((s_a/127) * (s_b/127)).                           */
 /* ------------------------------------------------------------------------- */
 static float dq2(int32_t acc, float sa, float sb) { return (float)acc * ((sa / 127.0f) * (sb / 127.0f)); }
+
+/* The same product for a list of accumulators: out[i] = acc[i] * (s_a/127) * (s_b[i]/127).  s_b carries one
+ * scale per element, so that the caller can hand over the per-tensor scale of the data gradient or the clip
+ * value of each element's output channel (the vectorized de-quantization of the filter gradient). */
+int daq_ref_dequantize_acc(const int32_t* acc, int64_t count, float s_a, const float* s_b, float* out) {
+    if (!acc || !s_b || !out || count < 0) return REF_BAD_ARG;
+    for (int64_t i = 0; i < count; ++i) out[i] = dq2(acc[i], s_a, s_b[i]);
+    return REF_OK;
+}
 
 /* Forward pass of one layer: quantize X and W per tensor, integer convolution,
  * Y = acc * s_x/127 * s_w/127.  qX, qW, s_x, s_w are what the backward pass

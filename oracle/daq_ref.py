@@ -276,6 +276,28 @@ def conv_bwd_filter_acc_at(d: ConvDesc, qX, qG, idx):
     return out
 
 
+def conv_fwd_acc_at(d: ConvDesc, qX, qW, idx):
+    """Accumulators of the forward convolution at the linear NCHW indices ``idx`` of Y only."""
+    qX, qW = _i8(qX), _i8(qW)
+    assert qX.shape == d.x_shape and qW.shape == d.w_shape
+    idx = np.ascontiguousarray(idx, dtype=np.int64)
+    out = np.zeros(idx.size, np.int32)
+    dd = d.c()
+    _chk(lib().daq_ref_conv_fwd_acc_at(C.byref(dd), _p(qX, C.c_int8), _p(qW, C.c_int8), _p(idx, C.c_int64),
+                                       C.c_int64(idx.size), _p(out, C.c_int32)), "conv_fwd_acc_at")
+    return out
+
+
+def dequantize_acc(acc, s_a: float, s_b) -> np.ndarray:
+    """acc * (s_a/127) * (s_b/127) in the oracle's fp32 operation order; ``s_b`` is a scalar or one scale per element."""
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    sb = np.ascontiguousarray(np.broadcast_to(np.asarray(s_b, dtype=np.float32), acc.shape), dtype=np.float32)
+    out = np.zeros(acc.shape, np.float32)
+    _chk(lib().daq_ref_dequantize_acc(_p(acc, C.c_int32), C.c_int64(acc.size), C.c_float(s_a), _p(sb, C.c_float),
+                                      _p(out, C.c_float)), "dequantize_acc")
+    return out
+
+
 @dataclass
 class Fwd:
     qX: np.ndarray

@@ -23,11 +23,12 @@ SCHEME_DAQ, SCHEME_GQ, SCHEME_GVQ, SCHEME_MCS = range(4)
 CLASS_GAUSS, CLASS_INVT = 0, 1
 OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER, OP_CONV_BWD = range(5)
 LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
+SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY = range(3)
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
-    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_conv_fwd_int8", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
 ]
 
 
@@ -147,6 +148,10 @@ class WPackLayout(C.Structure):
         return flat[self.off_plain:self.off_plain + n].reshape(d.w_shape)
 
 
+class QuantizeOpts(C.Structure):
+    _fields_ = [("scheme", C.c_int32), ("schedule", C.c_int32), ("dy_bf16", C.c_int32), ("reserved", C.c_int32)]
+
+
 class ProfRow(C.Structure):
     _fields_ = [("name", C.c_char * 64), ("total_ms", C.c_double), ("launches", C.c_int32)]
 
@@ -174,13 +179,18 @@ def lib():
         L.daq_quantize_grad_scheme.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.c_int, vp, vp,
                                                vp, vp, vp, vp, vp, sz, vp]
         L.daq_quantize_grad_bf16.argtypes = L.daq_quantize_grad_scheme.argtypes
+        L.daq_quantize_grad_ex.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.POINTER(QuantizeOpts),
+                                           vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
+        L.daq_conv_fwd_int8_ex.argtypes = [C.POINTER(ConvDesc)] + [vp] * 9 + [C.c_int, vp, sz, vp]
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_filter_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_data_int8_chan.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
         L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
+        L.daq_ceiling_mfma_i8.argtypes = [C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), vp]
+        L.daq_ceiling_stream.argtypes = [C.c_int32, vp, vp, sz, C.c_int32, vp, vp]
         _lib = L
     return _lib
 
@@ -269,6 +279,22 @@ def quantize_grad(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, k=1.0, A
     return out
 
 
+def quantize_grad_ex(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, scheme: int = SCHEME_DAQ,
+                     schedule: int = SCHEDULE_AUTO, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0,
+                     out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
+    """daq_quantize_grad_ex: every option explicit; ``dY`` is fp32 or bfloat16.  ``s_state`` is updated in place."""
+    assert dY.is_cuda and dY.dtype in (torch.float32, torch.bfloat16) and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    if out is None:
+        out = alloc_quantize_grad(d, dY.device)
+    opts = QuantizeOpts(scheme, schedule, 1 if dY.dtype == torch.bfloat16 else 0, 0)
+    rc = lib().daq_quantize_grad_ex(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, C.byref(opts), _ptr(out.vq),
+                                    _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
+                                    _ptr(out.workspace), out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_quantize_grad_ex")
+    return out
+
+
 def quantize_grad_bf16(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, scheme: int = SCHEME_DAQ, k=1.0, A=0.8, lam=0.3,
                        mode=ROUND_NEAREST, seed=0, out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
     """daq_quantize_grad_bf16: ``dY`` is a bfloat16 tensor.  ``s_state`` is updated in place."""
@@ -320,15 +346,22 @@ def alloc_fwd(d: ConvDesc, device="cuda", want_acc=False) -> Fwd:
 
 
 def conv_fwd_int8(d: ConvDesc, X: torch.Tensor, W: torch.Tensor, out: Optional[Fwd] = None, want_acc=False,
-                  stream=None) -> Fwd:
+                  stream=None, schedule: Optional[int] = None) -> Fwd:
+    """daq_conv_fwd_int8, or daq_conv_fwd_int8_ex when a ``schedule`` is given."""
     assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and tuple(X.shape) == d.x_shape
     assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == d.w_shape
     if out is None:
         out = alloc_fwd(d, X.device, want_acc)
-    rc = lib().daq_conv_fwd_int8(C.byref(d), _ptr(X), _ptr(W), _ptr(out.qx_nhwc), _ptr(out.qx_cnhw), _ptr(out.qw),
-                                 _ptr(out.s_x), _ptr(out.s_w), _ptr(out.Y), _ptr(out.acc), _ptr(out.workspace),
-                                 out.workspace.numel(), _stream(stream))
-    _check(rc, "daq_conv_fwd_int8")
+    if schedule is None:
+        rc = lib().daq_conv_fwd_int8(C.byref(d), _ptr(X), _ptr(W), _ptr(out.qx_nhwc), _ptr(out.qx_cnhw), _ptr(out.qw),
+                                     _ptr(out.s_x), _ptr(out.s_w), _ptr(out.Y), _ptr(out.acc), _ptr(out.workspace),
+                                     out.workspace.numel(), _stream(stream))
+        _check(rc, "daq_conv_fwd_int8")
+    else:
+        rc = lib().daq_conv_fwd_int8_ex(C.byref(d), _ptr(X), _ptr(W), _ptr(out.qx_nhwc), _ptr(out.qx_cnhw), _ptr(out.qw),
+                                        _ptr(out.s_x), _ptr(out.s_w), _ptr(out.Y), _ptr(out.acc), schedule,
+                                        _ptr(out.workspace), out.workspace.numel(), _stream(stream))
+        _check(rc, "daq_conv_fwd_int8_ex")
     return out
 
 
@@ -417,3 +450,17 @@ def prof_end(max_rows: int = 64):
     n = C.c_int32(0)
     _check(lib().daq_prof_end(rows, max_rows, C.byref(n)), "daq_prof_end")
     return {rows[i].name.decode(): (rows[i].total_ms, rows[i].launches) for i in range(n.value)}
+
+
+def ceiling_mfma_i8(blocks: int, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueue the register-resident int8 matrix-core loop; returns the int8 operations of the launch."""
+    ops = C.c_double(0.0)
+    _check(lib().daq_ceiling_mfma_i8(blocks, iters, _ptr(sink), C.byref(ops), _stream(stream)), "daq_ceiling_mfma_i8")
+    return ops.value
+
+
+def ceiling_stream(mode: int, src: Optional[torch.Tensor], dst: Optional[torch.Tensor], nbytes: int, blocks: int,
+                   sink: torch.Tensor, stream=None) -> None:
+    """Enqueue a streaming read (mode 0), write (1) or copy (2) of ``nbytes``."""
+    _check(lib().daq_ceiling_stream(mode, _ptr(src), _ptr(dst), nbytes, blocks, _ptr(sink), _stream(stream)),
+           "daq_ceiling_stream")

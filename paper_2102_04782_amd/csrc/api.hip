@@ -11,18 +11,23 @@ bool a16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 bool a4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
 }  // namespace
 
-extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
-                                        int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y,
-                                        int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+extern "C" daq_status daq_conv_fwd_int8_ex(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
+                                           int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y,
+                                           int32_t* acc_out, daq_schedule schedule, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !X || !W || !qx_nhwc || !qx_cnhw || !qw_packed || !s_x || !s_w || !Y)
         return DAQ_ERR_INVALID_ARG;
     if (!a4(X) || !a4(W) || !a16(qx_nhwc) || !a16(qx_cnhw) || !a16(qw_packed) || !a16(Y) || !a16(acc_out))
         return DAQ_ERR_INVALID_ARG;
+    if (schedule != DAQ_SCHEDULE_AUTO && schedule != DAQ_SCHEDULE_THREE_SWEEPS && schedule != DAQ_SCHEDULE_EARLY_COPY)
+        return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_FWD, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    daq_status rc = quantize_activation_check(*desc, X);   // nothing is launched for a tensor the quantizers cannot take
+    if (rc != DAQ_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    daq_status rc = quantize_activation(*desc, X, qx_nhwc, qx_cnhw, s_x, workspace, st);
+    rc = quantize_activation(*desc, X, qx_nhwc, qx_cnhw, s_x, workspace, st, schedule);
     if (rc != DAQ_OK) return rc;
     rc = quantize_filter(*desc, W, qw_packed, s_w, workspace, st);
     if (rc != DAQ_OK) return rc;
@@ -30,6 +35,13 @@ extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* 
     if (depthwise_fwd_supported(*desc)) return conv_fwd_depthwise(*desc, qx_cnhw, qw_packed, s_x, s_w, Y, acc_out, st);
     if (fwd_mfma_supported(*desc)) return conv_fwd_mfma(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
     return conv_fwd_generic(*desc, qx_nhwc, qw_packed, s_x, s_w, Y, acc_out, st);
+}
+
+extern "C" daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
+                                        int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y,
+                                        int32_t* acc_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return daq_conv_fwd_int8_ex(desc, X, W, qx_nhwc, qx_cnhw, qw_packed, s_x, s_w, Y, acc_out, DAQ_SCHEDULE_AUTO, workspace,
+                                workspace_bytes, stream);
 }
 
 extern "C" daq_status daq_conv_bwd_data_int8(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,

@@ -835,7 +835,7 @@ daq_status launch_dw(const Plan& pl, const DwArgs& a, int wq4, hipStream_t st) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
-        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
+        DAQ_LAUNCH("conv_bwd_filter_frag", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
         return DAQ_OK;                                                                                            \
     }
     DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
@@ -852,7 +852,7 @@ daq_status launch_dw_direct(const Plan& pl, const DwArgs& a, int wq4, hipStream_
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
-        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
+        DAQ_LAUNCH("conv_bwd_filter_direct_frag", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));   \
         return DAQ_OK;                                                                                            \
     }
     DAQ_DW_CASE(0) DAQ_DW_CASE(1) DAQ_DW_CASE(2) DAQ_DW_CASE(3)
@@ -866,7 +866,7 @@ daq_status launch_dw_taps(const Plan& pl, const DwArgs& a, const TapTable& tt, h
     auto kern = k_dw_taps<TW, NB, PFD, WTAPS, WAVES>;
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
         return DAQ_ERR_HIP;
-    DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WAVES), pl.lds_bytes, st, a, tt));
+    DAQ_LAUNCH("conv_bwd_filter_taps", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WAVES), pl.lds_bytes, st, a, tt));
     return DAQ_OK;
 }
 

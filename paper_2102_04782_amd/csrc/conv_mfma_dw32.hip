@@ -588,7 +588,7 @@ daq_status launch32(const Plan32& pl, const Dw32Args& a, int wq4, hipStream_t st
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
-        DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WN * WK), pl.lds_bytes, st, a)); \
+        DAQ_LAUNCH("conv_bwd_filter_dw32", st, hipLaunchKernelGGL(kern, grid, dim3(64 * WM * WN * WK), pl.lds_bytes, st, a)); \
         return DAQ_OK;                                                                                            \
     }
     DAQ_DW32_CASE(0) DAQ_DW32_CASE(1) DAQ_DW32_CASE(2) DAQ_DW32_CASE(3)
@@ -639,12 +639,12 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
             auto kern = k_dw11<2, 2, 1, 1>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
                 return DAQ_ERR_HIP;
-            DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));
+            DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));
         } else {
             auto kern = k_dw11<1, 1, 8, 3>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
                 return DAQ_ERR_HIP;
-            DAQ_LAUNCH("conv_bwd_filter_mfma", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
+            DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
         }
         if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits))
             *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};

@@ -183,11 +183,12 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     auto fetch_a = [&](int slot) {
         const bool live = f_s < NS;
         const int id = p.tap_id[phase][live ? f_j : 0];
-        const uint32_t base = live ? (uint32_t)(((f_kc * p.T + id) * p.RB) * 2048) : kOob;
+        // a dead prefetch is sent out of range through the VECTOR offset, the one the hardware checks against the extent
+        const uint32_t base = live ? (uint32_t)(((f_kc * p.T + id) * p.RB) * 2048) : 0u;
 #pragma unroll
         for (int x = 0; x < 2; ++x)
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+            for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
         ++f_s;
         if (++f_j == taps) { f_j = 0; ++f_kc; }
     };
@@ -220,11 +221,11 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         v4i ra1[kRing1][2][2], rw[kRing1][kU1];
         auto fetch_1 = [&](int slot, int kc) {
             const bool live = kc < nkc;
-            const uint32_t base = live ? (uint32_t)((kc * p.RB) * 2048) : kOob;
+            const uint32_t base = live ? (uint32_t)((kc * p.RB) * 2048) : 0u;
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) ra1[slot][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+                for (int sub = 0; sub < 2; ++sub) ra1[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
             const bool kok = live && kc * kKc + 16 * sc < p.cp;
 #pragma unroll
             for (int i = 0; i < kU1; ++i)
@@ -282,11 +283,12 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         for (int y = 0; y < BF; ++y) bbyte[y] = bslot[y] * kPitch + 16 * lh;
         v4i rt[TAPS][2][2];   // [tap][x][sub]
         auto fetch_t = [&](int t, int kc) {
-            const uint32_t base = kc < nkc ? (uint32_t)(((kc * p.T + t_id[t]) * p.RB) * 2048) : kOob;
+            const bool live = kc < nkc;
+            const uint32_t base = live ? (uint32_t)(((kc * p.T + t_id[t]) * p.RB) * 2048) : 0u;
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) rt[t][x][sub] = buffer_load16(rs_w, aoff[x][sub], base);
+                for (int sub = 0; sub < 2; ++sub) rt[t][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
         };
         v4i bq[2][2][BF];     // [set][sub][y]
         auto read_b = [&](int set, int buf, int t) {
@@ -742,7 +744,9 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     a.div_tiles_w = make_fastdiv((uint32_t)a.tiles_w);
     a.div_tiles_hw = make_fastdiv((uint32_t)(a.tiles_h * a.tiles_w));
     const int64_t pt = blocks_per_row_tile(a);
-    if (pt * ceil_div(Crow, 64) >= ((int64_t)1 << 31)) return g;
+    // room for the workgroups of a deferred filter-gradient reduction (at most 4096, dw_tail_worthwhile) is kept here,
+    // so that the grid-size test of the launch cannot fail once an entry point has started launching
+    if (pt * ceil_div(Crow, 64) >= ((int64_t)1 << 31) - 4096) return g;
     a.div_ptiles = make_fastdiv((uint32_t)pt);
     g.ok = true;
     return g;
@@ -879,14 +883,14 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lg;
     if (!bf16 && daq_layout_qg(&d, &Lg) == DAQ_OK && stream_applies(d, Lg))
-        return launch_stream("conv_bwd_data_mfma", d, Lg, qg, qw + Lw.off_bwd_frag, Lw.bytes - Lw.off_bwd_frag, d.Cin, s_w, s_g, dX, acc,
+        return launch_stream("conv_bwd_data_stream", d, Lg, qg, qw + Lw.off_bwd_frag, Lw.bytes - Lw.off_bwd_frag, d.Cin, s_w, s_g, dX, acc,
                              st, tail);
     g.a.src = qg;
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;
     g.a.out = dX; g.a.acc_out = acc;
     g.a.nt = !bf16 && (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
-    return launch(g, st, "conv_bwd_data_mfma");
+    return launch(g, st, "conv_bwd_data_halo");
 }
 
 bool fwd_halo_supported(const daq_conv_desc& d) { return plan_fwd(d).ok; }
@@ -898,14 +902,14 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lx;
     if (daq_layout_qx_nhwc(&d, &Lx) == DAQ_OK && stream_applies(d, Lx))   // thin 1 x 1 layers: the streaming kernel, rows = Cout
-        return launch_stream("conv_fwd_mfma", d, Lx, qx, qw + Lw.off_fwd_frag, Lw.off_bwd_frag - Lw.off_fwd_frag, d.Cout, s_x, s_w, Y,
+        return launch_stream("conv_fwd_stream", d, Lx, qx, qw + Lw.off_fwd_frag, Lw.off_bwd_frag - Lw.off_fwd_frag, d.Cout, s_x, s_w, Y,
                              acc, st, nullptr);
     g.a.src = qx;
     g.a.wfrag = qw + Lw.off_fwd_frag;
     g.a.s_a = s_x; g.a.s_b = s_w;
     g.a.out = Y; g.a.acc_out = acc;
     g.a.nt = (int64_t)d.N * d.Cout * daq_out_h(&d) * daq_out_w(&d) * 4 >= kStreamBytes;
-    return launch(g, st, "conv_fwd_mfma");
+    return launch(g, st, "conv_fwd_halo");
 }
 
 }  // namespace daq

@@ -323,7 +323,7 @@ daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const fl
     a.out = dX; a.acc_out = acc;
     a.src_bytes = (uint32_t)Lg.bytes;
     a.wpk_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd);
-    return launch(a, d.dilH, d.dilW, st, "conv_bwd_data_mfma");
+    return launch(a, d.dilH, d.dilW, st, "conv_bwd_data_nhwc");
 }
 
 bool fwd_mfma_supported(const daq_conv_desc& d) { return nhwc_supported(d); }
@@ -345,7 +345,7 @@ daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     a.out = Y; a.acc_out = acc;
     a.src_bytes = (uint32_t)Lx.bytes;
     a.wpk_bytes = (uint32_t)(Lw.bytes - Lw.off_fwd);
-    return launch(a, d.dilH, d.dilW, st, "conv_fwd_mfma");
+    return launch(a, d.dilH, d.dilW, st, "conv_fwd_nhwc");
 }
 
 }  // namespace daq

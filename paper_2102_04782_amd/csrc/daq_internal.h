@@ -104,8 +104,9 @@ inline NhwcView nhwc_view(const daq_layout& L) { return NhwcView{L.c_pitch, L.C,
 // quantize.hip
 size_t quantize_grad_ws_bytes(const daq_conv_desc& d);
 size_t fwd_quant_ws_bytes(const daq_conv_desc& d);
+daq_status quantize_activation_check(const daq_conv_desc& d, const float* X);   // host only: can this X be quantized?
 daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* qx_nhwc, int8_t* qx_cnhw, float* s_x,
-                               void* ws, hipStream_t st);
+                               void* ws, hipStream_t st, daq_schedule schedule);
 daq_status quantize_filter(const daq_conv_desc& d, const float* W, int8_t* qw_packed, float* s_w, void* ws,
                            hipStream_t st);
 

@@ -1,6 +1,8 @@
 // Measurement aid: optional HIP-event bracketing of every kernel launch of the library.
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -13,14 +15,16 @@ struct Span {
     std::string name;
     hipEvent_t start, stop;
 };
-bool g_active = false;
+std::atomic<bool> g_active{false};
+std::mutex g_mu;            // guards everything below
 bool g_calibrated = false;
 std::vector<Span> g_spans;
 }  // namespace
 
-bool prof_active() { return g_active; }
+bool prof_active() { return g_active.load(std::memory_order_relaxed); }
 
 void prof_push(const char* name, hipStream_t s) {
+    std::lock_guard<std::mutex> lock(g_mu);
     if (!g_calibrated) {
         // An event pair with nothing between it measures what the bracketing itself adds to every span.
         g_calibrated = true;
@@ -41,6 +45,7 @@ void prof_push(const char* name, hipStream_t s) {
 }
 
 void prof_pop(hipStream_t s) {
+    std::lock_guard<std::mutex> lock(g_mu);
     if (!g_spans.empty()) (void)hipEventRecord(g_spans.back().stop, s);
 }
 
@@ -49,6 +54,7 @@ void prof_pop(hipStream_t s) {
 extern "C" {
 
 daq_status daq_prof_begin(void) {
+    std::lock_guard<std::mutex> lock(daq::g_mu);
     for (auto& sp : daq::g_spans) {
         (void)hipEventDestroy(sp.start);
         (void)hipEventDestroy(sp.stop);
@@ -61,6 +67,7 @@ daq_status daq_prof_begin(void) {
 
 daq_status daq_prof_end(daq_prof_row* rows, int32_t max_rows, int32_t* n_rows) {
     daq::g_active = false;
+    std::lock_guard<std::mutex> lock(daq::g_mu);
     if (!rows || !n_rows || max_rows <= 0) return DAQ_ERR_INVALID_ARG;
     int n = 0;
     daq_status rc = DAQ_OK;

@@ -8,7 +8,6 @@
 // -ffp-contract=off: the rounding of every fp32/fp64 expression below is part of the contract.
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 
 #include "daq_internal.h"
 
@@ -1141,8 +1140,20 @@ size_t fwd_quant_ws_bytes(const daq_conv_desc&) { return 256; }
 // ---------------------------------------------------------------------------------------------
 // forward-side quantization of X (two layouts) and W (packed)
 // ---------------------------------------------------------------------------------------------
+// Whether the forward pass can quantize this activation: everything that could fail is decided here, before the
+// first launch, so that an unsupported problem leaves every output untouched.
+daq_status quantize_activation_check(const daq_conv_desc& d, const float* X) {
+    daq_layout Ln, Lc;
+    if (daq_layout_qx_nhwc(&d, &Ln) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lc) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
+    if (!f32_tensor_supported((int64_t)d.N * d.Cin * d.Hin * d.Win)) return DAQ_ERR_UNSUPPORTED;
+    if (rows_vector(Lc, X) == 0 && !pack_supported(Lc)) return DAQ_ERR_UNSUPPORTED;
+    return DAQ_OK;
+}
+
 daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* qx_nhwc, int8_t* qx_cnhw, float* s_x,
-                               void* wsp, hipStream_t st) {
+                               void* wsp, hipStream_t st, daq_schedule schedule) {
+    const daq_status ok = quantize_activation_check(d, X);
+    if (ok != DAQ_OK) return ok;
     uint32_t* bits = (uint32_t*)wsp;
     const int64_t n = (int64_t)d.N * d.Cin * d.Hin * d.Win;
     DAQ_LAUNCH("fill", st, hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, bits, (int64_t)1, 0u));
@@ -1152,15 +1163,14 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
 
     daq_layout Ln, Lc;
     if (daq_layout_qx_nhwc(&d, &Ln) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lc) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
-    if (!f32_tensor_supported(n)) return DAQ_ERR_UNSUPPORTED;
     const int HW = d.Hin * d.Win;
     const int CB = (int)ceil_div(d.Cin, 64);
     QuantWs geo = carve_quant_ws(nullptr, d.Cin, d.N, HW);  // only the tile geometry is used: nothing is counted here
     // Unit-stride layers whose channel-major layout the row kernel serves: one sweep over X writes both copies (the
     // mechanism of the early per-channel copy of dY, with the per-tensor scale), then the padding bytes are filled in.
-    // (from 8 Mi elements on: below that the two lean passes are faster, as for dY; DAQ_EARLY_VQ_MIN overrides both sizes)
-    static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");
-    if (n >= (early_env ? atoll(early_env) : ((int64_t)8 << 20)) && rows_vector(Lc, X) != 0 && Lc.lead + (int64_t)d.N * Lc.img_rows * Lc.row_pitch < ((int64_t)1 << 32)) {
+    // (by default from 8 Mi elements on: below that the two lean passes are faster, as for dY)
+    const bool want_early = schedule == DAQ_SCHEDULE_EARLY_COPY || (schedule == DAQ_SCHEDULE_AUTO && n >= ((int64_t)8 << 20));
+    if (want_early && rows_vector(Lc, X) != 0 && Lc.lead + (int64_t)d.N * Lc.img_rows * Lc.row_pitch < ((int64_t)1 << 32)) {
         const EarlyVq ev{qx_cnhw, Lc.chan_pitch, (int32_t)Lc.lead, Lc.img_rows, Lc.row_pitch, Lc.W, make_fastdiv((uint32_t)Lc.W),
                          0.0f, 0.0f, 0.0f, Lc.W % 4 == 0 ? 1 : 0};
         DAQ_LAUNCH("quant_both", st,
@@ -1210,13 +1220,15 @@ namespace {
 // T = float or uint16_t (bfloat16): the element type of dY
 template <typename T>
 daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_state, float k, float A, float lambda,
-                              daq_round mode, uint64_t seed, daq_scheme scheme, int8_t* vq, int8_t* qg, float* s_chan,
-                              float* s_global, uint8_t* cls, float* stats, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+                              daq_round mode, uint64_t seed, daq_scheme scheme, daq_schedule schedule, int8_t* vq,
+                              int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
+                              size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
     if (scheme != DAQ_SCHEME_DAQ && scheme != DAQ_SCHEME_GQ && scheme != DAQ_SCHEME_GVQ && scheme != DAQ_SCHEME_MCS)
+        return DAQ_ERR_INVALID_ARG;
+    if (schedule != DAQ_SCHEDULE_AUTO && schedule != DAQ_SCHEDULE_THREE_SWEEPS && schedule != DAQ_SCHEDULE_EARLY_COPY)
         return DAQ_ERR_INVALID_ARG;
     if (((uintptr_t)dY & (sizeof(T) - 1)) || ((uintptr_t)vq & 15u) || ((uintptr_t)qg & 15u)) return DAQ_ERR_INVALID_ARG;
     daq_layout Lv, Lg;
@@ -1227,8 +1239,11 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     const size_t need = daq_workspace_bytes(DAQ_OP_QUANTIZE_GRAD, desc);
     if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 255u)) return DAQ_ERR_WORKSPACE;
 
-    if (!f32_tensor_supported((int64_t)desc->N * desc->Cout * daq_out_h(desc) * daq_out_w(desc)))
+    // the kernels address dY with 32-bit byte offsets
+    if (!((int64_t)desc->N * desc->Cout * daq_out_h(desc) * daq_out_w(desc) * (int64_t)sizeof(T) < ((int64_t)1 << 31)))
         return DAQ_ERR_UNSUPPORTED;
+    // the packing pass is the last launch: what it cannot serve is refused here, before the first one
+    if (rows_vector(Lv, dY, (int)sizeof(T)) == 0 && !pack_supported(Lv)) return DAQ_ERR_UNSUPPORTED;
 
     hipStream_t st = (hipStream_t)stream;
     const int N = desc->N, C = desc->Cout, Ho = daq_out_h(desc), Wo = daq_out_w(desc);
@@ -1261,9 +1276,8 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     // Large gradients: the counting pass also writes the per-channel copy under a guessed class (see k_count_qg), so
     // that the third sweep over dY only touches the channels whose guess was wrong.  Small ones are bound by launch
     // latency, not by bytes, and keep the leaner counting kernel.
-    static const char* early_env = getenv("DAQ_EARLY_VQ_MIN");   // tuning override, read once: smallest gradient (elements)
-    const int64_t early_min = early_env ? atoll(early_env) : kEarlyVqMinElems;
-    const bool early = scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY, (int)sizeof(T)) != 0 && (int64_t)N * C * HW >= early_min &&
+    const bool want_early = schedule == DAQ_SCHEDULE_EARLY_COPY || (schedule == DAQ_SCHEDULE_AUTO && (int64_t)N * C * HW >= kEarlyVqMinElems);
+    const bool early = want_early && scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY, (int)sizeof(T)) != 0 &&
                        Lv.lead + (int64_t)N * Lv.img_rows * Lv.row_pitch < ((int64_t)1 << 32);
     EarlyVq ev{};
     if (early) {
@@ -1306,26 +1320,44 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
 
 }  // namespace
 
+extern "C" daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void* dY, float* s_state, float k, float A,
+                                           float lambda, daq_round mode, uint64_t seed, const daq_quantize_opts* opts,
+                                           int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
+                                           float* stats, void* workspace, size_t workspace_bytes, void* stream) {
+    const daq_quantize_opts def{DAQ_SCHEME_DAQ, DAQ_SCHEDULE_AUTO, 0, 0};
+    const daq_quantize_opts& o = opts ? *opts : def;
+    if (o.dy_bf16 != 0 && o.dy_bf16 != 1) return DAQ_ERR_INVALID_ARG;
+    if (o.dy_bf16)
+        return quantize_grad_impl<uint16_t>(desc, static_cast<const uint16_t*>(dY), s_state, k, A, lambda, mode, seed,
+                                            (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls,
+                                            stats, workspace, workspace_bytes, stream);
+    return quantize_grad_impl<float>(desc, static_cast<const float*>(dY), s_state, k, A, lambda, mode, seed,
+                                     (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls, stats,
+                                     workspace, workspace_bytes, stream);
+}
+
 extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,
                                                float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
                                                int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
                                                float* stats, void* workspace, size_t workspace_bytes, void* stream) {
-    return quantize_grad_impl<float>(desc, dY, s_state, k, A, lambda, mode, seed, scheme, vq, qg, s_chan, s_global, cls, stats,
-                                     workspace, workspace_bytes, stream);
+    const daq_quantize_opts o{(int32_t)scheme, DAQ_SCHEDULE_AUTO, 0, 0};
+    return daq_quantize_grad_ex(desc, dY, s_state, k, A, lambda, mode, seed, &o, vq, qg, s_chan, s_global, cls, stats,
+                                workspace, workspace_bytes, stream);
 }
 
 extern "C" daq_status daq_quantize_grad_bf16(const daq_conv_desc* desc, const uint16_t* dY_bf16, float* s_state, float k,
                                              float A, float lambda, daq_round mode, uint64_t seed, daq_scheme scheme,
                                              int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
                                              float* stats, void* workspace, size_t workspace_bytes, void* stream) {
-    return quantize_grad_impl<uint16_t>(desc, dY_bf16, s_state, k, A, lambda, mode, seed, scheme, vq, qg, s_chan, s_global, cls,
-                                        stats, workspace, workspace_bytes, stream);
+    const daq_quantize_opts o{(int32_t)scheme, DAQ_SCHEDULE_AUTO, 1, 0};
+    return daq_quantize_grad_ex(desc, dY_bf16, s_state, k, A, lambda, mode, seed, &o, vq, qg, s_chan, s_global, cls, stats,
+                                workspace, workspace_bytes, stream);
 }
 
 extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
                                         float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg,
                                         float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
                                         size_t workspace_bytes, void* stream) {
-    return daq_quantize_grad_scheme(desc, dY, s_state, k, A, lambda, mode, seed, DAQ_SCHEME_DAQ, vq, qg, s_chan, s_global,
-                                    cls, stats, workspace, workspace_bytes, stream);
+    return daq_quantize_grad_ex(desc, dY, s_state, k, A, lambda, mode, seed, nullptr, vq, qg, s_chan, s_global, cls, stats,
+                                workspace, workspace_bytes, stream);
 }

@@ -1,14 +1,18 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
 Whole-tensor oracle runs are out of reach for ResNet-50 / MobileNetV2 layers at N = 64 / 128, so
-the check is exact on SAMPLED outputs: the oracle evaluates a few thousand elements of G_X and a few
-hundred of G_W one by one from the definition, and the raw int32 accumulators of the GPU must match
-bit for bit.
+the check is exact on SAMPLED outputs: the oracle evaluates a few thousand elements of G_X and Y and
+a few hundred of G_W one by one from the definition; the raw int32 accumulators of the GPU must match
+bit for bit and the de-quantized values within 1e-5 per element.
 
 The int8 operands reach the device layouts through the library's own quantizers.  The inputs are
-fp32 tensors that hold integers in [-127, 127] with a +-127 in every channel, so every scale is
-exactly 127 and every code equals its input (with k*A = 1 the Inverted-T rule returns |g|max as
-well): the logical int8 tensors the oracle needs are the inputs themselves.
+fp32 tensors that hold integers in [-127, 127] with a +-127 in every channel, multiplied by powers
+of two: X by 2^-3, W by 2^-5 and channel c of dY by 2^-(c % 8).  Every scale is then 127 times a
+power of two - a different one for each tensor and for neighbouring channels - every code of q(X),
+q(W) and the per-channel copy equals the integer it came from (with k*A = 1 the Inverted-T rule
+returns |g|max as well), and the global copy of dY is the oracle's per-tensor quantization of the
+scaled gradient.  A second backward call then takes arbitrary scales (a random clip value per channel)
+on the same codes, so that a scale picked from the wrong channel or the wrong tensor cannot pass.
 """
 import numpy as np
 import pytest
@@ -19,6 +23,9 @@ from paper_2102_04782_amd import binding as daq
 from paper_2102_04782_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5   # per element, on every fp32 value (the benchmark spec's tolerance)
+
 
 def _distinct_layers():
     """One (config, index) per distinct convolution of ResNet-50 (N = 64) and MobileNetV2 (N = 128): 23 + 34 shapes,
@@ -39,6 +46,11 @@ def _codes(shape, gen, device):
     return q
 
 
+def _near(got, want, what):
+    got, want = np.asarray(got, np.float32), np.asarray(want, np.float32)
+    assert np.allclose(got, want, rtol=RTOL, atol=0), f"{what}: {np.abs(got - want).max():g} off"
+
+
 @pytest.mark.parametrize("config,index", _distinct_layers(), ids=lambda v: str(v))
 def test_sampled_outputs_at_full_size(config, index):
     device = torch.device("cuda:0")
@@ -50,10 +62,13 @@ def test_sampled_outputs_at_full_size(config, index):
     X, G = _codes(d.x_shape, gen, device), _codes(d.y_shape, gen, device)
     W = torch.randint(-127, 128, d.w_shape, dtype=torch.int8, device=device, generator=gen)
     W.view(-1)[0] = 127
+    chan_pow = torch.arange(d.Cout, device=device) % 8
+    chan_scale = torch.pow(2.0, -chan_pow.float()).view(1, -1, 1, 1)
 
-    f = daq.conv_fwd_int8(d, X.float(), W.float())
+    f = daq.conv_fwd_int8(d, X.float() * 2.0 ** -3, W.float() * 2.0 ** -5, want_acc=True)
     state = torch.zeros(d.Cout, device=device)
-    q = daq.quantize_grad(d, G.float(), state, k=1.0, A=1.0)
+    Gs = G.float() * chan_scale
+    q = daq.quantize_grad(d, Gs, state, k=1.0, A=1.0)
     accW = torch.empty(d.w_shape, dtype=torch.int32, device=device)
     accX = torch.empty(d.x_shape, dtype=torch.int32, device=device)
     # the call the benchmark times: both gradients at once
@@ -63,26 +78,62 @@ def test_sampled_outputs_at_full_size(config, index):
     dX1 = daq.conv_bwd_data_int8(d, q.qg, q.s_global, f.qw, f.s_w)
     torch.cuda.synchronize()
     assert torch.equal(dW, dW1) and torch.equal(dX, dX1)
-    if layer.groups > 1 and layer.groups == layer.Cin == layer.Cout:
-        # depthwise: the data gradient from the per-channel copy (all scales are 127 here, so the same bits)
-        assert torch.equal(daq.conv_bwd_data_int8_chan(d, q.vq, q.s_chan, f.qw, f.s_w), dX)
-    assert f.s_x.item() == 127.0 and f.s_w.item() == 127.0 and q.s_global.item() == 127.0
-    assert bool((q.s_chan == 127.0).all())
+    s_x, s_w, s_g = f.s_x.item(), f.s_w.item(), q.s_global.item()
+    assert s_x == 127.0 / 8 and s_w == 127.0 / 32 and s_g == 127.0
+    s_c = q.s_chan.cpu().numpy()
+    assert np.array_equal(s_c, (127.0 * chan_scale.view(-1)).cpu().numpy())
+    assert np.array_equal(state.cpu().numpy(), s_c), "clip state after the call"
 
     rng = np.random.default_rng(wl.seed_for(config, index))
     Xh, Wh, Gh = X.cpu().numpy(), W.cpu().numpy(), G.cpu().numpy()
+    # the global copy: the oracle's per-tensor quantization of the scaled gradient (its maximum is 127 as well)
+    Gq, s_ref = ref.quantize_tensor(Gs.cpu().numpy())
+    assert s_ref == 127.0
+    del Gs
+    depthwise = layer.groups > 1 and layer.groups == layer.Cin == layer.Cout
+
+    # arbitrary scales on the same codes, for the second call
+    s_c2 = (10.0 ** rng.uniform(-4, -1, d.Cout)).astype(np.float32)
+    s_x2, s_w2, s_g2 = 2.5, 0.11, 0.03
+    dev_f = lambda v: torch.tensor(np.atleast_1d(v), dtype=torch.float32, device=device)
+    dW2, dX2 = daq.conv_bwd_int8(d, f.qx_cnhw, dev_f(s_x2), q.vq, dev_f(s_c2), q.qg, dev_f(s_g2), f.qw, dev_f(s_w2))
+    dW3 = daq.conv_bwd_filter_int8(d, f.qx_cnhw, dev_f(s_x2), q.vq, dev_f(s_c2))
+    dX3 = daq.conv_bwd_data_int8(d, q.qg, dev_f(s_g2), f.qw, dev_f(s_w2))
+    torch.cuda.synchronize()
+    assert torch.equal(dW2, dW3) and torch.equal(dX2, dX3)
+
     ix = rng.choice(accX.numel(), size=min(4096, accX.numel()), replace=False)
-    want = ref.conv_bwd_data_acc_at(rd, Gh, Wh, ix)
+    want = ref.conv_bwd_data_acc_at(rd, Gq, Wh, ix)
     ix_d = torch.from_numpy(ix).to(device)
     assert np.array_equal(accX.view(-1)[ix_d].cpu().numpy(), want), "G_X accumulators at sampled positions"
-    # all scales are 127: the de-quantized value is the accumulator itself
-    assert np.array_equal(dX.view(-1)[ix_d].cpu().numpy(), want.astype(np.float32))
+    _near(dX.view(-1)[ix_d].cpu().numpy(), ref.dequantize_acc(want, s_w, s_g), "G_X")
+    _near(dX2.view(-1)[ix_d].cpu().numpy(), ref.dequantize_acc(want, s_w2, s_g2), "G_X under arbitrary scales")
+    if depthwise:
+        # the data gradient from the per-channel copy: the codes of vq, each channel's own clip value
+        ci = (ix // (d.Hin * d.Win)) % d.Cin
+        want_c = ref.conv_bwd_data_acc_at(rd, Gh, Wh, ix)
+        accC = torch.empty(d.x_shape, dtype=torch.int32, device=device)
+        dXc = daq.conv_bwd_data_int8_chan(d, q.vq, q.s_chan, f.qw, f.s_w, acc=accC)
+        dXc2 = daq.conv_bwd_data_int8_chan(d, q.vq, dev_f(s_c2), f.qw, dev_f(s_w2))
+        torch.cuda.synchronize()
+        assert np.array_equal(accC.view(-1)[ix_d].cpu().numpy(), want_c), "G_X accumulators from the per-channel copy"
+        _near(dXc.view(-1)[ix_d].cpu().numpy(), ref.dequantize_acc(want_c, s_w, s_c[ci]), "G_X from the per-channel copy")
+        _near(dXc2.view(-1)[ix_d].cpu().numpy(), ref.dequantize_acc(want_c, s_w2, s_c2[ci]), "the same under arbitrary scales")
 
     iw = rng.choice(accW.numel(), size=min(256, accW.numel()), replace=False)
     want = ref.conv_bwd_filter_acc_at(rd, Xh, Gh, iw)
     iw_d = torch.from_numpy(iw).to(device)
+    co = iw // (accW.numel() // d.Cout)
     assert np.array_equal(accW.view(-1)[iw_d].cpu().numpy(), want), "G_W accumulators at sampled positions"
-    assert np.array_equal(dW.view(-1)[iw_d].cpu().numpy(), want.astype(np.float32))
+    _near(dW.view(-1)[iw_d].cpu().numpy(), ref.dequantize_acc(want, s_x, s_c[co]), "G_W")
+    _near(dW2.view(-1)[iw_d].cpu().numpy(), ref.dequantize_acc(want, s_x2, s_c2[co]), "G_W under arbitrary scales")
+
+    # the forward pass that produced the saved operands: accumulators and Y at sampled positions
+    iy = rng.choice(f.acc.numel(), size=min(4096, f.acc.numel()), replace=False)
+    want = ref.conv_fwd_acc_at(rd, Xh, Wh, iy)
+    iy_d = torch.from_numpy(iy).to(device)
+    assert np.array_equal(f.acc.view(-1)[iy_d].cpu().numpy(), want), "Y accumulators at sampled positions"
+    _near(f.Y.view(-1)[iy_d].cpu().numpy(), ref.dequantize_acc(want, s_x, s_w), "Y")
 
 
 def _logical_view(L, buf):

@@ -109,6 +109,8 @@ def test_against_scatter_form_and_torch(ref, case):
     assert np.array_equal(ref.conv_bwd_data_acc_at(d, qG, qW, ix), tdX.numpy().astype(np.int64).ravel()[ix])
     iw = rng.permutation(accW.size)
     assert np.array_equal(ref.conv_bwd_filter_acc_at(d, qX, qG, iw), tdW.numpy().astype(np.int64).ravel()[iw])
+    iy = rng.permutation(accY.size)
+    assert np.array_equal(ref.conv_fwd_acc_at(d, qX, qW, iy), tY.numpy().astype(np.int64).ravel()[iy])
 
 
 def test_one_by_one_is_a_matrix_product(ref):
@@ -151,6 +153,13 @@ def test_dequantization_closed_form(ref):
     tol = 3 * 2.0 ** -24
     assert np.all(np.abs(dW - eW) <= tol * np.abs(eW) + 1e-45)
     assert np.all(np.abs(dX - eX) <= tol * np.abs(eX) + 1e-45)
+    # the list form used for sampled checks at full size: the same bits as the layer routines, scale picked per element
+    co = np.arange(accW.size) // (accW.size // d.Cout)
+    assert np.array_equal(ref.dequantize_acc(accW.ravel(), float(s_x), s_c[co]), dW.ravel())
+    assert np.array_equal(ref.dequantize_acc(accX, float(s_w), float(s_g)), dX)
+    # a transposed pairing (the input channel's clip value, or the scales of the other product) must not pass
+    ci = (np.arange(accW.size) // 9) % d.Cin
+    assert not np.array_equal(ref.dequantize_acc(accW.ravel(), float(s_x), s_c[ci]), dW.ravel())
     # the filter gradient is scaled per OUTPUT channel, the data gradient by two scalars
     assert np.array_equal(accW, ref.conv_bwd_filter_acc(d, qX, qG)[0])
     assert np.array_equal(accX, ref.conv_bwd_data_acc(d, qG, qW)[0])
