@@ -33,6 +33,7 @@ COLD_BYTES = 512 << 20    # a workload whose dY is smaller is replicated until t
 
 QUANT_KERNELS = ("stats", "count_qg", "pack_vq", "pack_qg", "layer_stats", "layer_decide")
 SCHEMES = {"daq": 0, "gq": 1, "gvq": 2, "mcs": 3}
+SCHEDULES = {"auto": 0, "three_sweeps": 1, "early_copy": 2}
 
 
 # ------------------------------------------------------------------------------------------------ helpers
@@ -153,7 +154,7 @@ def layer_step(args, s, mode, seed):
     """Algorithm 1 for one layer."""
     from paper_2102_04782_amd import binding as daq
 
-    q = daq.quantize_grad_ex(s.d, s.dY, s.state, SCHEMES[args.scheme], daq.SCHEDULE_AUTO, mode=mode, seed=seed, out=s.out)
+    q = daq.quantize_grad_ex(s.d, s.dY, s.state, SCHEMES[args.scheme], SCHEDULES[args.schedule], mode=mode, seed=seed, out=s.out)
     if s.bf16_ok:
         daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f)
         daq.conv_bwd_data_int8_bf16(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dXh, workspace=s.ws_d)
@@ -274,9 +275,10 @@ def run_network(args, dev) -> int:
             ph = "quantize" if k in QUANT_KERNELS else "dW" if (k.startswith("conv_bwd_filter") or k == "dw_reduce") else "dX"
             phases[ph] += us * n
             row[ph + "_us"] = round(row.get(ph + "_us", 0.0) + us * n, 1)
+            row.setdefault("kernels_us", {})[k] = round(us * n, 1)
         layer_rows.append(row)
     ridge = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    traffic = measured_traffic(config) if (args.rounding == "stochastic" and not (args.dy_bf16 or args.dx_bf16 or args.separate or args.scheme != "daq")) else {}
+    traffic = measured_traffic(config) if (args.rounding == "stochastic" and not (args.dy_bf16 or args.dx_bf16 or args.separate or args.scheme != "daq" or args.schedule != "auto")) else {}
     table = {}
     for k, e in kernels.items():
         t = e["us"] * 1e-6
@@ -326,7 +328,7 @@ def run_network(args, dev) -> int:
                    "rounding": args.rounding, "k": 1.0, "A": 0.8, "lambda": 0.3, "buffer_sets": R,
                    "dY_bytes_per_step": int(dy_b * E_Y_total), "cold": bool(R * dy_b * E_Y_total >= COLD_BYTES),
                    "dX": "bf16 where served" if args.dx_bf16 else "fp32", "dY": "bf16" if args.dy_bf16 else "fp32",
-                   "scheme": args.scheme,
+                   "scheme": args.scheme, "schedule": args.schedule,
                    "calls": "daq_quantize_grad_ex + " + ("daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8" if (args.separate or args.dx_bf16)
                                                          else "daq_conv_bwd_int8")},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
@@ -574,6 +576,8 @@ def main() -> int:
                          "which returns fp32 gradients; reported for comparison, never the default)")
     ap.add_argument("--scheme", default="daq", choices=tuple(SCHEMES),
                     help="rule for the per-channel clip values: Algorithm 1 (default) or one of the ablation study's variants")
+    ap.add_argument("--schedule", default="auto", choices=tuple(SCHEDULES),
+                    help="how the quantizer shares its sweeps over dY among its launches (daq_quantize_grad_ex); same results")
     ap.add_argument("--dy-bf16", action="store_true",
                     help="hand the output gradient over as bfloat16 (same algorithm on the widened values; reported for "
                          "comparison, never the default)")

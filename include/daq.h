@@ -161,9 +161,9 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  * Then  vq = Q(dY, s_c) per channel,  qg = Q(dY, s_global),  s_global = max_c |g|max_c,
  * Q being Eq. "suq" evaluated in fp32 as round(clamp(x * (127/s), -127, 127)).
  * A scale below 2^-100 is reported as 0 and produces all-zero codes.
- * Stochastic rounding draws u in [0,1) from SplitMix64's output function applied to
- *   seed + 0x9E3779B97F4A7C15*(i+1) + 0xD1B54A32D192ED03*t   (i = NCHW index, t = 0 for vq, 1 for qg),
- * keeps the top 24 bits, and rounds up iff frac(x*127/s) > u.
+ * Stochastic rounding draws one 64-bit number z per element, SplitMix64's output function applied to
+ *   seed + 0x9E3779B97F4A7C15*(i+1)   (i = NCHW index: output i+1 of SplitMix64 seeded with `seed`),
+ * takes u = bits 63..40 of z (vq) or bits 39..16 (qg) times 2^-24, and rounds up iff frac(x*127/s) > u.
  *
  *   dY        in   fp32 NCHW
  *   s_state   i/o  fp32 [Cout]  clip values of the previous iteration, replaced by this iteration's

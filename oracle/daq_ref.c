@@ -85,11 +85,15 @@ static int desc_ok(const ref_conv_desc* d) {
 /* ------------------------------------------------------------------------- */
 /* Counter-based uniform generator for stochastic rounding.                   */
 /*                                                                             */
-/* u(seed, tensor, idx) is a 24-bit uniform in [0,1): the SplitMix64 output    */
-/* function (Steele, Lea, Flood 2014; Vigna's public-domain constants) applied */
-/* to the counter  seed + GOLDEN*(idx+1) + TENSOR_MIX*tensor  (mod 2^64), of   */
-/* which the top 24 bits are kept.  idx is the element's NCHW linear index,    */
-/* tensor is 0 for the per-channel copy and 1 for the per-tensor copy.         */
+/* The paper asks for stochastic rounding of the gradients and names no        */
+/* generator.  Reading: element idx (its NCHW linear index) of a call with     */
+/* `seed` gets ONE 64-bit draw, the SplitMix64 output function (Steele, Lea,   */
+/* Flood 2014; Vigna's public-domain constants) applied to the counter         */
+/*     seed + GOLDEN * (idx + 1)   (mod 2^64),                                 */
+/* i.e. the (idx+1)-th output of SplitMix64 seeded with `seed`.  The two int8  */
+/* copies of the gradient take disjoint bit fields of that draw as their       */
+/* 24-bit uniforms in [0,1): bits 63..40 for the per-channel copy (tensor 0),  */
+/* bits 39..16 for the per-tensor copy (tensor 1).                             */
 /* ------------------------------------------------------------------------- */
 static uint64_t mix64(uint64_t z) {
     z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
@@ -98,9 +102,10 @@ static uint64_t mix64(uint64_t z) {
 }
 
 float daq_ref_uniform24(uint64_t seed, uint32_t tensor, uint64_t idx) {
-    uint64_t ctr = seed + UINT64_C(0x9E3779B97F4A7C15) * (idx + 1) + UINT64_C(0xD1B54A32D192ED03) * (uint64_t)tensor;
+    uint64_t ctr = seed + UINT64_C(0x9E3779B97F4A7C15) * (idx + 1);
     uint64_t z = mix64(ctr);
-    return (float)(z >> 40) * 5.9604644775390625e-08f; /* 2^-24, exact */
+    uint64_t bits = tensor == 0u ? (z >> 40) : ((z >> 16) & UINT64_C(0xFFFFFF));
+    return (float)bits * 5.9604644775390625e-08f; /* 2^-24, exact */
 }
 
 /* ------------------------------------------------------------------------- */

@@ -91,24 +91,28 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     return z ^ (z >> 31);
 }
 
-// 24-bit uniform in [0,1) keyed by (seed, tensor, element index): SplitMix64 output function of a counter.
-__device__ __forceinline__ float uniform24(uint64_t seed, uint32_t tensor, uint64_t idx) {
-    const uint64_t ctr = seed + 0x9E3779B97F4A7C15ull * (idx + 1) + 0xD1B54A32D192ED03ull * (uint64_t)tensor;
-    return (float)(uint32_t)(mix64(ctr) >> 40) * 5.9604644775390625e-08f;
+// Stochastic rounding draws ONE 64-bit number per element: the SplitMix64 output function of the counter
+// seed + GOLDEN * (i + 1), i = the element's NCHW index (below 2^31).  The per-channel copy (tensor 0) takes bits
+// 63..40 of it as its 24-bit uniform in [0,1), the per-tensor copy (tensor 1) bits 39..16, so a kernel that writes
+// both copies hashes once, and consecutive elements' counters differ by a constant (an addition, not a multiply).
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+__device__ __forceinline__ uint64_t rng_counter(uint64_t seed, uint32_t idx) { return seed + kGolden * (uint64_t)(idx + 1u); }
+__device__ __forceinline__ float rng_uniform(uint64_t z, uint32_t tensor) {
+    const uint32_t bits = tensor == 0u ? (uint32_t)(z >> 40) : ((uint32_t)(z >> 16) & 0xFFFFFFu);
+    return (float)bits * 5.9604644775390625e-08f;
 }
 
 // 127/s, or 0 when the scale is treated as zero (then every code is 0).
 __device__ __forceinline__ float inv_scale(float s) { return (s >= kTinyScale) ? 127.0f / s : 0.0f; }
 
-// Eq. "suq" in code space: round(clamp(x*inv, -127, 127)).
+// Eq. "suq" in code space: round(clamp(x*inv, -127, 127)); u is the element's uniform under stochastic rounding.
 template <bool STOCH>
-__device__ __forceinline__ int quant_code(float x, float inv, uint64_t seed, uint32_t tensor, uint64_t idx) {
+__device__ __forceinline__ int quant_code(float x, float inv, float u) {
     float t = x * inv;
     t = fminf(fmaxf(t, -127.0f), 127.0f);
     if (STOCH) {
         const float f = floorf(t);
         const float frac = t - f;
-        const float u = uniform24(seed, tensor, idx);
         return (int)(f + (frac > u ? 1.0f : 0.0f));
     }
     return (int)rintf(t);
@@ -119,8 +123,8 @@ __device__ __forceinline__ int quant_code(float x, float inv, uint64_t seed, uin
 // and leaves that integer in two's complement in the low mantissa bits - one instruction instead of
 // round + convert + mask.
 template <bool STOCH>
-__device__ __forceinline__ uint32_t quant_bits(float x, float inv, uint64_t seed, uint32_t tensor, uint64_t idx) {
-    if (STOCH) return (uint32_t)quant_code<true>(x, inv, seed, tensor, idx);
+__device__ __forceinline__ uint32_t quant_bits(float x, float inv, float u) {
+    if (STOCH) return (uint32_t)quant_code<true>(x, inv, u);
     const float t = __builtin_amdgcn_fmed3f(x * inv, -127.0f, 127.0f);
     return __float_as_uint(t + 12582912.0f);
 }
@@ -475,31 +479,28 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
     uint32_t cnt[16];   // wave-uniform counters
 #pragma unroll
     for (int i = 0; i < 16; ++i) cnt[i] = 0;
+    const uint64_t plane_step = kGolden * (uint64_t)(uint32_t)HW;
     for (int tile = p; tile < ws.tiles; tile += ws.cgroups) {
         float nx[16];
         uint32_t n_nxt, px_nxt;
         bool v_nxt;
         fetch(tile + ws.cgroups, nx, n_nxt, px_nxt, v_nxt);
-        uint32_t b[16];
+        uint32_t b[16], vb[16];
+        // the lane's 16 elements are one plane apart: their counters differ by GOLDEN * HW
+        uint64_t ctr = STOCH ? rng_counter(seed, (n_cur * (uint32_t)C + (uint32_t)c0) * (uint32_t)HW + px_cur) : 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             if (COUNT) cnt[i] += (uint32_t)__popcll(__ballot(fabsf(x[i]) > sig[i]));
-            if (WRITE_QG) {
-                const uint64_t idx = STOCH ? (uint64_t)(((int64_t)n_cur * C + c0 + i) * HW + px_cur) : 0;
-                b[i] = quant_bits<STOCH>(x[i], inv, seed, 1u, idx);
-            }
+            const uint64_t z = STOCH ? mix64(ctr) : 0;   // one draw serves both copies
+            ctr += plane_step;
+            if (WRITE_QG) b[i] = quant_bits<STOCH>(x[i], inv, STOCH ? rng_uniform(z, 1u) : 0.0f);
+            if (EARLY) vb[i] = quant_bits<STOCH>(x[i], inv_c[i], STOCH ? rng_uniform(z, 0u) : 0.0f);
         }
         if (EARLY) {
             // channel-major copy: the lane's pixel sits at the same offset of each of its 16 channel planes
             const uint32_t h = fdiv(px_cur, ev.div_w);
             int8_t* dst = ev.vq + (int64_t)c0 * ev.chan_pitch + (uint32_t)ev.lead +
                           (n_cur * (uint32_t)ev.img_rows + h) * (uint32_t)ev.row_pitch + (px_cur - h * (uint32_t)ev.W);
-            uint32_t vb[16];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint64_t idx = STOCH ? (uint64_t)(((int64_t)n_cur * C + c0 + i) * HW + px_cur) : 0;
-                vb[i] = quant_bits<STOCH>(x[i], inv_c[i], seed, 0u, idx);
-            }
             if (ev.quad) {   // uniform
                 // Four adjacent lanes hold four consecutive pixels of one row.  Their 4 x 16 codes are transposed inside
                 // the quad - dwords between lanes, then bytes between dwords - so that lane r of the quad ends up with
@@ -801,7 +802,8 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const T* __restrict__ src,
         const int d = jb * 1024 + tid + 256 * u;
         uint32_t bits[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u][i] / EB));
+        for (int i = 0; i < 4; ++i)
+            bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_uniform(mix64(rng_counter(pa.seed, eoff[u][i] / EB)), pa.tensor) : 0.0f);
         if (d < plane_dw) *reinterpret_cast<uint32_t*>(plane + 4 * (int64_t)d) = pack4(bits[0], bits[1], bits[2], bits[3]);
     }
 }
@@ -942,11 +944,21 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
         }
     }
 
+    uint64_t z[4][V];   // one draw per element; the two copies take disjoint fields of it
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        uint64_t ctr = STOCH ? rng_counter(pa.seed, eoff[u] / EB) : 0;   // the V elements are consecutive
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            z[u][i] = STOCH ? mix64(ctr) : 0;
+            ctr += kGolden;
+        }
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, pa.seed, pa.tensor, (uint64_t)(eoff[u] / EB) + i);
+        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_uniform(z[u][i], pa.tensor) : 0.0f);
         if (live[u]) store_codes<V>(plane + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
         if (row_end[u])
             for (int k = 0; k < padw; ++k) plane[doff[u] + V + k] = 0;
@@ -957,8 +969,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
         for (int u = 0; u < 4; ++u) {
             uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int i = 0; i < V; ++i)
-                bits[i] = quant_bits<STOCH>(x[u][i], inv2, pa.seed, pa.tensor2, (uint64_t)(eoff[u] / EB) + i);
+            for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv2, STOCH ? rng_uniform(z[u][i], pa.tensor2) : 0.0f);
             if (live[u]) store_codes<V>(plane2 + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
             if (row_end[u])
                 for (int k = 0; k < padw; ++k) plane2[doff[u] + V + k] = 0;
@@ -1020,7 +1031,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_w(const float* __restrict__ W, 
     const int g = co / cog, col = co % cog;
     const int ci = g * cig + cl;
     const float inv = inv_scale(*s_w);
-    const int8_t code = (int8_t)quant_code<false>(W[i], inv, 0, 0, 0);
+    const int8_t code = (int8_t)quant_code<false>(W[i], inv, 0.0f);
     out[L.off_plain + i] = code;
     out[L.off_fwd + ((int64_t)tap * Cout + co) * L.cig_pitch + cl] = code;
     out[L.off_bwd + ((int64_t)tap * Cin + ci) * L.cog_pitch + col] = code;

@@ -139,6 +139,16 @@ def test_uniform24_is_uniform_and_keyed(ref):
     # generator's published first outputs for seed 0 appear as the first draws.
     first = 0xE220A8397B1DCDAF  # first output of SplitMix64 seeded with 0 (Vigna's reference)
     assert ref.uniform24(0, 0, 0) == (first >> 40) * 2.0 ** -24
+    # the per-tensor copy takes the next 24 bits of the same draw
+    assert ref.uniform24(0, 1, 0) == ((first >> 16) & 0xFFFFFF) * 2.0 ** -24
+    second = 0x6E789E6AA1B965F4  # second output of the same reference stream: element 1
+    assert ref.uniform24(0, 0, 1) == (second >> 40) * 2.0 ** -24
+    assert ref.uniform24(0, 1, 1) == ((second >> 16) & 0xFFFFFF) * 2.0 ** -24
+    # the seed enters as the generator's state: element i of seed s is output i + 1 of SplitMix64 seeded with s
+    golden = 0x9E3779B97F4A7C15
+    assert ref.uniform24(golden, 0, 0) == (second >> 40) * 2.0 ** -24
+    assert np.all(v * 2 ** 24 == np.floor(v * 2 ** 24)) and v.min() >= 0.0 and v.max() < 1.0
+    assert abs(v.mean() - 0.5) < 0.03
 
 
 # ----------------------------------------------------------------------------- statistics
