@@ -372,7 +372,7 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
                                                      FastDiv div_hw, QuantWs ws, const float* __restrict__ scale_ptr,
                                                      int8_t* __restrict__ qg, uint64_t seed,
                                                      const float* __restrict__ s_state, float* __restrict__ s_global,
-                                                     EarlyVq ev) {
+                                                     EarlyVq ev, int qg_tail) {
     __shared__ float l_sigma[64];
     __shared__ float l_inv[64];
     __shared__ float l_max[kBlock / kWave];
@@ -465,6 +465,8 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
             ws.layer[0] = sg_raw;
         }
     }
+    // the NHWC buffer is a multiple of 256 bytes long: the bytes behind the last pixel hold no element and are zero
+    if (WRITE_QG && blockIdx.x == 0 && tid < qg_tail) qg[(int64_t)M * c_pitch + tid] = 0;
     const float inv = inv_scale(sg);
     // sigma of the wave's 16 channels.  Lanes without a pixel and channels past C hold x = 0, and
     // 0 > sigma is false for every sigma >= 0, so the comparison needs no validity mask.
@@ -1075,6 +1077,9 @@ bool pack_supported(const daq_layout& L) {
 bool f32_tensor_supported(int64_t elems) { return elems * 4 < ((int64_t)1 << 31); }
 
 
+// Bytes of an NHWC buffer behind its last pixel (the buffer is rounded up to 256 bytes).
+int nhwc_tail(const daq_layout& L) { return (int)(L.bytes - (int64_t)L.N * L.H * L.W * L.c_pitch); }
+
 // Elements per thread of the source-driven row kernel (4 or 2), or 0 when the layout needs the output-driven one.
 int rows_vector(const daq_layout& Ld, const void* src, int elem_bytes = 4) {
     const int64_t lim24 = (int64_t)1 << 24;
@@ -1187,14 +1192,14 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
         DAQ_LAUNCH("quant_both", st,
                    hipLaunchKernelGGL((k_count_qg<float, false, true, false, true>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X,
                                       d.N, d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
-                                      (uint64_t)0, (const float*)nullptr, (float*)nullptr, ev));
+                                      (uint64_t)0, (const float*)nullptr, (float*)nullptr, ev, nhwc_tail(Ln)));
         return launch_pack("pad_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st, nullptr, nullptr,
                            0, nullptr, true);
     }
     DAQ_LAUNCH("quant_nhwc", st,
                hipLaunchKernelGGL((k_count_qg<float, false, true, false>), dim3(CB * geo.cgroups), dim3(kBlock), 0, st, X, d.N,
                                   d.Cin, HW, Ln.c_pitch, make_fastdiv((uint32_t)HW), geo, (const float*)s_x, qx_nhwc,
-                                  (uint64_t)0, (const float*)nullptr, (float*)nullptr, EarlyVq{}));
+                                  (uint64_t)0, (const float*)nullptr, (float*)nullptr, EarlyVq{}, nhwc_tail(Ln)));
     const daq_status prc = launch_pack("pack_cnhw", false, false, X, Lc, (const float*)s_x, 0, qx_cnhw, 0u, 0, geo, ClipArgs{}, st);
     if (prc != DAQ_OK) return prc;
     return DAQ_OK;
@@ -1301,7 +1306,7 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     DAQ_LAUNCH("count_qg", st,                                                                                       \
                hipLaunchKernelGGL((k_count_qg<T, S, Q, true, E>), cgrid, dim3(kBlock), 0, st, dY, N, C, HW,             \
                                   qg_nhwc ? Lg.c_pitch : 0, div_hw, ws, no_scale, qg, seed, (const float*)s_state,   \
-                                  s_global, ev))
+                                  s_global, ev, qg_nhwc ? nhwc_tail(Lg) : 0))
     if (early) {
         if (stoch) DAQ_COUNT_LAUNCH(true, true, true);
         else DAQ_COUNT_LAUNCH(false, true, true);

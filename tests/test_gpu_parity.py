@@ -69,8 +69,7 @@ def check_quantize_grad(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, ch
     assert np.array_equal(Lg.unpack(out.qg), r.qg), "qg codes"
     if check_padding:
         assert Lv.padding_is_zero(out.vq), "vq padding bytes must be zero"
-        if Lg.kind == daq.LAYOUT_CNHW:
-            assert Lg.padding_is_zero(out.qg)
+        assert Lg.padding_is_zero(out.qg), "qg bytes that hold no element must be zero"
     return out, r
 
 
@@ -459,7 +458,7 @@ def check_forward(layer, seed, schedule=None):
     assert not r.overflow
     close(f.s_x.cpu().numpy(), [r.s_x], "s_x")
     close(f.s_w.cpu().numpy(), [r.s_w], "s_w")
-    assert np.array_equal(daq.layout_qx_nhwc(d).unpack(f.qx_nhwc), r.qX)
+    assert np.array_equal(daq.layout_qx_nhwc(d).unpack(f.qx_nhwc), r.qX) and daq.layout_qx_nhwc(d).padding_is_zero(f.qx_nhwc)
     Lc = daq.layout_qx_cnhw(d)
     assert np.array_equal(Lc.unpack(f.qx_cnhw), r.qX) and Lc.padding_is_zero(f.qx_cnhw)
     Lw = daq.layout_qw(d)
