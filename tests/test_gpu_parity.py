@@ -44,12 +44,15 @@ def check_quantize_grad(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, ch
                         scheme=None, schedule=None):
     d, _ = descs(layer)
     st_dev = t(st.copy())
+    out = daq.alloc_quantize_grad(d, dev())
+    out.vq.fill_(55)      # every byte of the two copies, padding included, has to come from the call
+    out.qg.fill_(55)
     if schedule is not None:
-        out = daq.quantize_grad_ex(d, t(dY), st_dev, scheme or daq.SCHEME_DAQ, schedule, k, A, lam, mode, seed)
+        daq.quantize_grad_ex(d, t(dY), st_dev, scheme or daq.SCHEME_DAQ, schedule, k, A, lam, mode, seed, out=out)
     elif scheme is None:
-        out = daq.quantize_grad(d, t(dY), st_dev, k, A, lam, mode, seed)
+        daq.quantize_grad(d, t(dY), st_dev, k, A, lam, mode, seed, out=out)
     else:
-        out = daq.quantize_grad_scheme(d, t(dY), st_dev, scheme, k, A, lam, mode, seed)
+        daq.quantize_grad_scheme(d, t(dY), st_dev, scheme, k, A, lam, mode, seed, out=out)
     torch.cuda.synchronize()
     r = ref.quantize_grad(dY, st, k, A, lam, mode, seed, scheme=scheme or ref.SCHEME_DAQ)
     # sigma == 0 channels are fragile by construction (any negative threshold counts everything)
@@ -452,7 +455,10 @@ def test_backward_convs_on_random_codes(layer):
 def check_forward(layer, seed, schedule=None):
     d, rd = descs(layer)
     X, W = wl.make_X(layer, seed, post_relu=False), wl.make_W(layer, seed)
-    f = daq.conv_fwd_int8(d, t(X), t(W), want_acc=True, schedule=schedule)
+    f = daq.alloc_fwd(d, dev(), want_acc=True)
+    for buf in (f.qx_nhwc, f.qx_cnhw, f.qw):
+        buf.fill_(55)
+    daq.conv_fwd_int8(d, t(X), t(W), out=f, schedule=schedule)
     torch.cuda.synchronize()
     r = ref.conv_fwd_int8(rd, X, W)
     assert not r.overflow
