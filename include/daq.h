@@ -60,7 +60,8 @@ typedef enum {
     DAQ_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, inconsistent descriptor, bad enum */
     DAQ_ERR_WORKSPACE = 2,   /* workspace missing, misaligned or smaller than daq_workspace_bytes() */
     DAQ_ERR_UNSUPPORTED = 3, /* valid problem the library has no kernel for (sizes beyond 2^31 elements) */
-    DAQ_ERR_HIP = 4          /* a HIP call or kernel launch reported an error */
+    DAQ_ERR_HIP = 4,         /* a HIP call or kernel launch reported an error */
+    DAQ_ERR_SCRATCH_LIMIT = 5 /* daq_quantize_grad_noalloc: the problem needs more scratch than DAQ_STATIC_SCRATCH_BYTES */
 } daq_status;
 
 /* Rounding of the gradient quantizer (text after Eq. "suq": stochastic rounding for
@@ -233,6 +234,29 @@ daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void* dY, float
                                 daq_round mode, uint64_t seed, const daq_quantize_opts* opts, int8_t* vq, int8_t* qg,
                                 float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
                                 size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_noalloc -- daq_quantize_grad for callers that cannot allocate device memory and
+ * so cannot provide a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The scratch of the three sweeps (statistics and count partials) lives in a
+ * fixed array of DAQ_STATIC_SCRATCH_BYTES in the library's device image instead; the call allocates
+ * and frees nothing.  Same kernels, same results, bit for bit, as daq_quantize_grad.
+ *
+ *   - A problem whose daq_workspace_bytes(DAQ_OP_QUANTIZE_GRAD) exceeds DAQ_STATIC_SCRATCH_BYTES is
+ *     refused with DAQ_ERR_SCRATCH_LIMIT before anything is launched (every layer of ResNet-50 at
+ *     batch 64 and MobileNetV2 at batch 128 needs less than 0.4 MiB).
+ *   - Each GPU has its own copy of the array; the one of the CURRENT device is used, so the device
+ *     that `stream` belongs to must be current.  Its address is looked up on the first call on a
+ *     device (not an allocation; make that first call outside graph capture).
+ *   - All calls on one GPU share the array: two calls whose kernels overlap in time - different
+ *     streams, or threads - race.  Calls on one stream are ordered and safe.  Nothing in the array
+ *     needs clearing between calls.
+ *   arguments as for daq_quantize_grad, without the workspace
+ * ------------------------------------------------------------------------------------------- */
+#define DAQ_STATIC_SCRATCH_BYTES (1 << 20)
+daq_status daq_quantize_grad_noalloc(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
+                                     float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg, float* s_chan,
+                                     float* s_global, uint8_t* cls, float* stats, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * daq_quantize_grad_bf16 -- daq_quantize_grad_scheme for an output gradient stored as bfloat16

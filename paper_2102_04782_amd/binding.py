@@ -17,7 +17,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdaq.so")
 
-OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(5)
+OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH_LIMIT = range(6)
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 SCHEME_DAQ, SCHEME_GQ, SCHEME_GVQ, SCHEME_MCS = range(4)
 CLASS_GAUSS, CLASS_INVT = 0, 1
@@ -27,7 +27,7 @@ SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY = range(3)
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
-    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
     "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
 ]
 
@@ -181,6 +181,8 @@ def lib():
         L.daq_quantize_grad_bf16.argtypes = L.daq_quantize_grad_scheme.argtypes
         L.daq_quantize_grad_ex.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.POINTER(QuantizeOpts),
                                            vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.daq_quantize_grad_noalloc.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, vp, vp, vp, vp, vp,
+                                                vp, vp]
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
         L.daq_conv_fwd_int8_ex.argtypes = [C.POINTER(ConvDesc)] + [vp] * 9 + [C.c_int, vp, sz, vp]
         L.daq_conv_bwd_data_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
@@ -292,6 +294,17 @@ def quantize_grad_ex(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, schem
                                     _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
                                     _ptr(out.workspace), out.workspace.numel(), _stream(stream))
     _check(rc, "daq_quantize_grad_ex")
+    return out
+
+
+def quantize_grad_noalloc(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, out: QuantGrad, k=1.0, A=0.8, lam=0.3,
+                          mode=ROUND_NEAREST, seed=0, stream=None) -> QuantGrad:
+    """daq_quantize_grad_noalloc: the outputs are the caller's (``out``; its workspace is not used), nothing is allocated."""
+    assert dY.is_cuda and dY.dtype == torch.float32 and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    rc = lib().daq_quantize_grad_noalloc(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, _ptr(out.vq), _ptr(out.qg),
+                                         _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats), _stream(stream))
+    _check(rc, "daq_quantize_grad_noalloc")
     return out
 
 

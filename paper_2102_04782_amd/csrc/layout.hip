@@ -192,6 +192,7 @@ const char* daq_status_string(daq_status s) {
         case DAQ_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case DAQ_ERR_UNSUPPORTED: return "unsupported problem size";
         case DAQ_ERR_HIP: return "HIP error";
+        case DAQ_ERR_SCRATCH_LIMIT: return "problem needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }

@@ -8,6 +8,7 @@
 // -ffp-contract=off: the rounding of every fp32/fp64 expression below is part of the contract.
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "daq_internal.h"
 
@@ -1376,4 +1377,47 @@ extern "C" daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* 
                                         size_t workspace_bytes, void* stream) {
     return daq_quantize_grad_ex(desc, dY, s_state, k, A, lambda, mode, seed, nullptr, vq, qg, s_chan, s_global, cls, stats,
                                 workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The quantizer for callers that cannot allocate: its scratch is a fixed array in device memory.
+// ---------------------------------------------------------------------------------------------
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[DAQ_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, looked up on first use
+
+// Address of the current device's copy of the array.  In host code the array's name is only a handle for this
+// lookup, never a device address: kernels, fills and copies get the pointer returned here.
+daq_status static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DAQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DAQ_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DAQ_OK;
+}
+}  // namespace
+
+extern "C" daq_status daq_quantize_grad_noalloc(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,
+                                                float lambda, daq_round mode, uint64_t seed, int8_t* vq, int8_t* qg,
+                                                float* s_chan, float* s_global, uint8_t* cls, float* stats, void* stream) {
+    if (!desc_valid(desc)) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_QUANTIZE_GRAD, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (need > (size_t)DAQ_STATIC_SCRATCH_BYTES) return DAQ_ERR_SCRATCH_LIMIT;
+    void* ws = nullptr;
+    const daq_status rc = static_scratch(&ws);
+    if (rc != DAQ_OK) return rc;
+    // The kernels take the array through the same workspace argument as in daq_quantize_grad.  Nothing in it has to
+    // start at zero: every partial result is written before it is read (no counters, no atomics).
+    return daq_quantize_grad_ex(desc, dY, s_state, k, A, lambda, mode, seed, nullptr, vq, qg, s_chan, s_global, cls, stats, ws,
+                                (size_t)DAQ_STATIC_SCRATCH_BYTES, stream);
 }
