@@ -155,6 +155,18 @@ def layer_step(args, s, mode, seed):
     from paper_2102_04782_amd import binding as daq
 
     q = daq.quantize_grad_ex(s.d, s.dY, s.state, SCHEMES[args.scheme], SCHEDULES[args.schedule], mode=mode, seed=seed, out=s.out)
+    if args.streams == 2:
+        # the filter gradient needs the per-channel copy, the data gradient the global one: once dY is quantized the two
+        # share no data, and the filter gradient (off the critical path of a backward pass) moves to a second stream
+        import torch
+        main = torch.cuda.current_stream()
+        args.side.wait_stream(main)
+        daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f, stream=args.side)
+        if s.bf16_ok:
+            daq.conv_bwd_data_int8_bf16(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dXh, workspace=s.ws_d)
+        else:
+            daq.conv_bwd_data_int8(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dX, workspace=s.ws_d)
+        return
     if s.bf16_ok:
         daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f)
         daq.conv_bwd_data_int8_bf16(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dXh, workspace=s.ws_d)
@@ -174,6 +186,8 @@ def timed_run(args, net, n_layers, R, mode, steps, warmup):
         r = i % R
         for s in reversed(net[r * n_layers:(r + 1) * n_layers]):   # backward order: last layer first
             layer_step(args, s, mode, seed=i)
+        if args.streams == 2:
+            torch.cuda.current_stream().wait_stream(args.side)    # the step ends when both streams have
 
     for i in range(warmup):
         step(i)
@@ -241,9 +255,27 @@ def run_network(args, dev) -> int:
     E_Y_total = sum(float(np.prod(L.y_shape)) for L in layers)
 
     sec, step = timed_run(args, net, nL, R, modes[args.rounding], args.steps, args.warmup)
+    if args.only_timed:
+        # for runs under rocprofv3: nothing but the warm-up and the timed steps is launched after the set-up, so every
+        # dispatch of a backward kernel belongs to one of W + K identical steps
+        if args.copy_calib_mib > 0:   # the plain copy of known size that scales the FETCH_SIZE / WRITE_SIZE readings
+            ca = torch.zeros(args.copy_calib_mib << 20, dtype=torch.uint8, device=dev)
+            cb = torch.empty_like(ca)
+            for _ in range(5):
+                cb.copy_(ca)
+            torch.cuda.synchronize()
+        print(json.dumps({"metric": "INT8 conv-backward TOPS incl. grad quantization", "value": round(ops_per_step / sec / 1e12, 3),
+                          "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * sec, 5),
+                          "config": {"workload": f"config{config}", "rounding": args.rounding, "streams": args.streams}}))
+        return 0
     n_stat = max(100, args.steps) if sec * max(100, args.steps) < 30.0 else args.steps
     med_ms, min_ms = step_statistics(step, n_stat)
     sec_other, _ = timed_run(args, net, nL, R, modes[other], args.steps, min(args.warmup, 3))
+    sec_two = None
+    if args.streams == 1:   # the same steps with the filter gradients on a second stream, reported beside the headline
+        args.streams, args.side = 2, torch.cuda.Stream()
+        sec_two, _ = timed_run(args, net, nL, R, modes[args.rounding], args.steps, min(args.warmup, 3))
+        args.streams, args.side = 1, None
 
     # the two ways of calling the convolutions must agree bit for bit (first layer of the network, timed tensors)
     s0 = net[0]
@@ -328,12 +360,14 @@ def run_network(args, dev) -> int:
                    "rounding": args.rounding, "k": 1.0, "A": 0.8, "lambda": 0.3, "buffer_sets": R,
                    "dY_bytes_per_step": int(dy_b * E_Y_total), "cold": bool(R * dy_b * E_Y_total >= COLD_BYTES),
                    "dX": "bf16 where served" if args.dx_bf16 else "fp32", "dY": "bf16" if args.dy_bf16 else "fp32",
-                   "scheme": args.scheme, "schedule": args.schedule,
+                   "scheme": args.scheme, "schedule": args.schedule, "streams": args.streams,
                    "calls": "daq_quantize_grad_ex + " + ("daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8" if (args.separate or args.dx_bf16)
                                                          else "daq_conv_bwd_int8")},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "step_ms_median": round(med_ms, 5), "step_ms_min": round(min_ms, 5), "stat_steps": n_stat,
         other: {"ms_per_step": round(1e3 * sec_other, 5), "value": round(ops_per_step / sec_other / 1e12, 3)},
+        "two_streams": None if sec_two is None else {"ms_per_step": round(1e3 * sec_two, 5), "value": round(ops_per_step / sec_two / 1e12, 3),
+                                                     "what": "filter gradients on a second stream"},
         "phase_us_per_step": {k: round(v, 1) for k, v in phases.items()},
         "launch_gap_us_per_step": round(1e6 * sec - sum(phases.values()), 1),
         "quant_GBps_effective_6B": round(6.0 * E_Y_total / (phases["quantize"] * 1e-6) / 1e9, 1) if phases["quantize"] else None,
@@ -576,6 +610,13 @@ def main() -> int:
                          "which returns fp32 gradients; reported for comparison, never the default)")
     ap.add_argument("--scheme", default="daq", choices=tuple(SCHEMES),
                     help="rule for the per-channel clip values: Algorithm 1 (default) or one of the ablation study's variants")
+    ap.add_argument("--only-timed", action="store_true",
+                    help="set-up, warm-up and the timed steps only, short JSON line: for runs under rocprofv3")
+    ap.add_argument("--copy-calib-mib", type=int, default=0,
+                    help="with --only-timed: afterwards run 5 device-to-device copies of this many MiB, the plain copy "
+                         "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
+                    help="2: the filter gradients run on a second stream beside the quantizer and the data gradients")
     ap.add_argument("--schedule", default="auto", choices=tuple(SCHEDULES),
                     help="how the quantizer shares its sweeps over dY among its launches (daq_quantize_grad_ex); same results")
     ap.add_argument("--dy-bf16", action="store_true",
@@ -602,6 +643,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     daq.lib()  # fail loudly if the HIP library is missing
+    args.side = torch.cuda.Stream() if args.streams == 2 else None
     if args.ceilings:
         return ceilings(args, dev)
     if args.sweep:
