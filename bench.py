@@ -31,9 +31,9 @@ PEAK_INT8_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s
 PEAK_HBM_GBS = 8000.0     # MI355X HBM3E, GB/s
 COLD_BYTES = 512 << 20    # a workload whose dY is smaller is replicated until the copies exceed twice the Infinity Cache
 
-QUANT_KERNELS = ("stats", "count_qg", "pack_vq", "pack_qg", "layer_stats", "layer_decide")
+QUANT_KERNELS = ("stats", "count_qg", "pack_vq", "pack_qg", "layer_stats", "layer_decide", "chan_resident", "global_copy")
 SCHEMES = {"daq": 0, "gq": 1, "gvq": 2, "mcs": 3}
-SCHEDULES = {"auto": 0, "three_sweeps": 1, "early_copy": 2}
+SCHEDULES = {"auto": 0, "three_sweeps": 1, "early_copy": 2, "channel_resident": 3}
 
 
 # ------------------------------------------------------------------------------------------------ helpers
@@ -67,7 +67,7 @@ def kernel_work(layer, d, name: str, dy_bytes: float, dx_bytes: float, qg_nhwc: 
         return dy_bytes * E_Y, 0.0
     if name == "count_qg":
         return (dy_bytes + (1.0 if qg_nhwc else 0.0)) * E_Y, 0.0
-    if name in ("pack_vq", "pack_qg"):
+    if name in ("pack_vq", "pack_qg", "chan_resident", "global_copy"):
         return (dy_bytes + 1.0) * E_Y, 0.0
     if name.startswith("conv_bwd_data"):
         return E_Y + E_W + dx_bytes * E_X, ops

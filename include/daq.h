@@ -162,9 +162,9 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  * Then  vq = Q(dY, s_c) per channel,  qg = Q(dY, s_global),  s_global = max_c |g|max_c,
  * Q being Eq. "suq" evaluated in fp32 as round(clamp(x * (127/s), -127, 127)).
  * A scale below 2^-100 is reported as 0 and produces all-zero codes.
- * Stochastic rounding draws one 64-bit number z per element, SplitMix64's output function applied to
- *   seed + 0x9E3779B97F4A7C15*(i+1)   (i = NCHW index: output i+1 of SplitMix64 seeded with `seed`),
- * takes u = bits 63..40 of z (vq) or bits 39..16 (qg) times 2^-24, and rounds up iff frac(x*127/s) > u.
+ * Stochastic rounding: with fmix32 the 32-bit finalizer of MurmurHash3 and, per copy t (0 = vq, 1 = qg),
+ *   key_t = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9*(t+1))),
+ * element i (its NCHW index) draws u = (fmix32(i ^ key_t) >> 8) * 2^-24 and rounds up iff frac(x*127/s) > u.
  *
  *   dY        in   fp32 NCHW
  *   s_state   i/o  fp32 [Cout]  clip values of the previous iteration, replaced by this iteration's
@@ -217,6 +217,13 @@ daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, 
  *                     DAQ_SCHEDULE_AUTO          the library picks by size (what the other entry points do)
  *                     DAQ_SCHEDULE_THREE_SWEEPS  statistics; count + qg; vq
  *                     DAQ_SCHEDULE_EARLY_COPY    the counting sweep also writes vq under a guessed class
+ *                     DAQ_SCHEDULE_CHANNEL_RESIDENT  one workgroup per channel keeps the channel in registers,
+ *                                                so that statistics, count, decision and vq take ONE read of dY;
+ *                                                a second launch writes qg.  For channels of at most 65536
+ *                                                elements (N*Hout*Wout; 16384 where Hout*Wout is not a multiple
+ *                                                of four or dY is not a 16-byte aligned fp32 tensor) whose int8
+ *                                                plane is at most 96 KiB, under Algorithm 1's rule with an NHWC
+ *                                                global copy; taken by default where it applies.
  *                   A schedule the layer cannot take (the early copy needs Algorithm 1's rule, an NHWC
  *                   global copy and an unsplit channel-major layout with rows of even length) falls
  *                   back to three sweeps.
@@ -226,7 +233,9 @@ daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, 
  * Other arguments, the workspace and the error codes as for daq_quantize_grad; an unknown scheme or
  * schedule is DAQ_ERR_INVALID_ARG.
  * ------------------------------------------------------------------------------------------- */
-typedef enum { DAQ_SCHEDULE_AUTO = 0, DAQ_SCHEDULE_THREE_SWEEPS = 1, DAQ_SCHEDULE_EARLY_COPY = 2 } daq_schedule;
+typedef enum {
+    DAQ_SCHEDULE_AUTO = 0, DAQ_SCHEDULE_THREE_SWEEPS = 1, DAQ_SCHEDULE_EARLY_COPY = 2, DAQ_SCHEDULE_CHANNEL_RESIDENT = 3
+} daq_schedule;
 typedef struct {
     int32_t scheme, schedule, dy_bf16, reserved;
 } daq_quantize_opts;
@@ -293,7 +302,8 @@ daq_status daq_conv_fwd_int8(const daq_conv_desc* desc, const float* X, const fl
 
 /* daq_conv_fwd_int8 with the schedule of its activation quantizer explicit: DAQ_SCHEDULE_EARLY_COPY
  * writes both layouts of q(X) in one sweep over X (taken by default from 8 Mi elements on, where
- * the channel-major layout is unsplit), DAQ_SCHEDULE_THREE_SWEEPS one sweep per layout.  Same bits. */
+ * the channel-major layout is unsplit), DAQ_SCHEDULE_THREE_SWEEPS (and DAQ_SCHEDULE_CHANNEL_RESIDENT, which has no
+ * forward form) one sweep per layout.  Same bits. */
 daq_status daq_conv_fwd_int8_ex(const daq_conv_desc* desc, const float* X, const float* W, int8_t* qx_nhwc,
                                 int8_t* qx_cnhw, int8_t* qw_packed, float* s_x, float* s_w, float* Y, int32_t* acc_out,
                                 daq_schedule schedule, void* workspace, size_t workspace_bytes, void* stream);

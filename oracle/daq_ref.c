@@ -86,25 +86,27 @@ static int desc_ok(const ref_conv_desc* d) {
 /* Counter-based uniform generator for stochastic rounding.                   */
 /*                                                                             */
 /* The paper asks for stochastic rounding of the gradients and names no        */
-/* generator.  Reading: element idx (its NCHW linear index) of a call with     */
-/* `seed` gets ONE 64-bit draw, the SplitMix64 output function (Steele, Lea,   */
-/* Flood 2014; Vigna's public-domain constants) applied to the counter         */
-/*     seed + GOLDEN * (idx + 1)   (mod 2^64),                                 */
-/* i.e. the (idx+1)-th output of SplitMix64 seeded with `seed`.  The two int8  */
-/* copies of the gradient take disjoint bit fields of that draw as their       */
-/* 24-bit uniforms in [0,1): bits 63..40 for the per-channel copy (tensor 0),  */
-/* bits 39..16 for the per-tensor copy (tensor 1).                             */
+/* generator.  Reading: a keyed hash of the element's position.  fmix32 is the */
+/* 32-bit finalizer of MurmurHash3 (Appleby, public domain): a bijection of    */
+/* 32-bit words in which every input bit reaches every output bit.  A call     */
+/* with `seed` has one key per int8 copy t (0: per-channel, 1: per-tensor),    */
+/*     key_t = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9 * (t + 1))),       */
+/* and element idx (its NCHW linear index, below 2^31) of copy t draws the     */
+/* 24-bit uniform  u = (fmix32(idx ^ key_t) >> 8) * 2^-24  in [0,1).           */
 /* ------------------------------------------------------------------------- */
-static uint64_t mix64(uint64_t z) {
-    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
-    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
-    return z ^ (z >> 31);
+uint32_t daq_ref_fmix32(uint32_t h) {
+    h ^= h >> 16;
+    h *= UINT32_C(0x85EBCA6B);
+    h ^= h >> 13;
+    h *= UINT32_C(0xC2B2AE35);
+    h ^= h >> 16;
+    return h;
 }
 
 float daq_ref_uniform24(uint64_t seed, uint32_t tensor, uint64_t idx) {
-    uint64_t ctr = seed + UINT64_C(0x9E3779B97F4A7C15) * (idx + 1);
-    uint64_t z = mix64(ctr);
-    uint64_t bits = tensor == 0u ? (z >> 40) : ((z >> 16) & UINT64_C(0xFFFFFF));
+    uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+    uint32_t key = daq_ref_fmix32(lo ^ daq_ref_fmix32(hi ^ (UINT32_C(0x9E3779B9) * (tensor + 1u))));
+    uint32_t bits = daq_ref_fmix32((uint32_t)idx ^ key) >> 8;
     return (float)bits * 5.9604644775390625e-08f; /* 2^-24, exact */
 }
 

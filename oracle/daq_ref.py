@@ -89,6 +89,8 @@ def lib():
         _lib = C.CDLL(build())
         _lib.daq_ref_uniform24.restype = C.c_float
         _lib.daq_ref_uniform24.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64]
+        _lib.daq_ref_fmix32.restype = C.c_uint32
+        _lib.daq_ref_fmix32.argtypes = [C.c_uint32]
         _lib.daq_ref_quantize_one.restype = C.c_int8
         _lib.daq_ref_quantize_one.argtypes = [C.c_float, C.c_float, C.c_int, C.c_float]
         _lib.daq_ref_dequantize_one.restype = C.c_float
@@ -120,6 +122,10 @@ def _i8(a):
 
 def num_threads() -> int:
     return int(lib().daq_ref_num_threads())
+
+
+def fmix32(h: int) -> int:
+    return int(lib().daq_ref_fmix32(h & 0xFFFFFFFF))
 
 
 def uniform24(seed: int, tensor: int, idx: int) -> float:

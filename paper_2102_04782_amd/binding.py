@@ -23,7 +23,7 @@ SCHEME_DAQ, SCHEME_GQ, SCHEME_GVQ, SCHEME_MCS = range(4)
 CLASS_GAUSS, CLASS_INVT = 0, 1
 OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER, OP_CONV_BWD = range(5)
 LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
-SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY = range(3)
+SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESIDENT = range(4)
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",

@@ -19,7 +19,8 @@ extern "C" daq_status daq_conv_fwd_int8_ex(const daq_conv_desc* desc, const floa
         return DAQ_ERR_INVALID_ARG;
     if (!a4(X) || !a4(W) || !a16(qx_nhwc) || !a16(qx_cnhw) || !a16(qw_packed) || !a16(Y) || !a16(acc_out))
         return DAQ_ERR_INVALID_ARG;
-    if (schedule != DAQ_SCHEDULE_AUTO && schedule != DAQ_SCHEDULE_THREE_SWEEPS && schedule != DAQ_SCHEDULE_EARLY_COPY)
+    if (schedule != DAQ_SCHEDULE_AUTO && schedule != DAQ_SCHEDULE_THREE_SWEEPS && schedule != DAQ_SCHEDULE_EARLY_COPY &&
+        schedule != DAQ_SCHEDULE_CHANNEL_RESIDENT)   // the last has no forward form: one sweep per layout
         return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_FWD, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;

@@ -627,10 +627,10 @@ def test_random_descriptors_of_the_specialised_kernels(layer):
     run_convs_on_codes(layer, qX, qW, qG, 0.9, 0.3, 0.05, s_c)
 
 
-SCHEDULES = [daq.SCHEDULE_THREE_SWEEPS, daq.SCHEDULE_EARLY_COPY]
+SCHEDULES = [daq.SCHEDULE_THREE_SWEEPS, daq.SCHEDULE_EARLY_COPY, daq.SCHEDULE_CHANNEL_RESIDENT]
 
 
-@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy"])
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy", "channel_resident"])
 def test_schedules_on_config1_all_modes(schedule):
     """Each schedule of the quantizer asked for explicitly (daq_quantize_grad_ex), on a size where the automatic choice
     would not take the early per-channel copy: wrong class guesses (lambda 0 and 1), both roundings, the clip-rule corners."""
@@ -646,7 +646,7 @@ def test_schedules_on_config1_all_modes(schedule):
         check_quantize_grad(layer, dY, st, scheme=scheme, schedule=schedule)
 
 
-@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy"])
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy", "channel_resident"])
 @pytest.mark.parametrize("layer", ODD_LAYERS, ids=lambda l: l.name)
 def test_schedules_on_ragged_shapes(layer, schedule):
     seed = wl.seed_for(15, ODD_LAYERS.index(layer))
@@ -658,7 +658,7 @@ def test_schedules_on_ragged_shapes(layer, schedule):
     check_quantize_grad(layer, dY, st, lam=0.0, schedule=schedule)
 
 
-@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy"])
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy", "channel_resident"])
 def test_schedules_on_degenerate_channels_and_carried_state(schedule):
     layer = wl.Layer("deg", 2, 4, 8, 8, 6, 3, 3, 1, 1)
     rng = np.random.default_rng(3)
@@ -682,7 +682,7 @@ def test_schedules_on_degenerate_channels_and_carried_state(schedule):
     assert np.array_equal(daq.layout_vq(d).unpack(b.vq), r2.vq)
 
 
-@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy"])
+@pytest.mark.parametrize("schedule", SCHEDULES, ids=["three_sweeps", "early_copy", "channel_resident"])
 @pytest.mark.parametrize("layer", CONV_LAYERS, ids=lambda l: l.name)
 def test_forward_layer_under_each_schedule(layer, schedule):
     """daq_conv_fwd_int8_ex: both layouts of q(X) from one sweep, or one sweep per layout; same bits."""
@@ -693,7 +693,7 @@ def test_unknown_schedule_is_refused():
     layer, X, W, dY, st = wl.make_inputs(1)
     d, _ = descs(layer)
     with pytest.raises(daq.DaqError) as e:
-        daq.quantize_grad_ex(d, t(dY), t(st.copy()), schedule=3)
+        daq.quantize_grad_ex(d, t(dY), t(st.copy()), schedule=4)
     assert e.value.code == daq.ERR_INVALID_ARG
     with pytest.raises(daq.DaqError) as e:
         daq.conv_fwd_int8(d, t(X), t(W), schedule=7)

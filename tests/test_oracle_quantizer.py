@@ -135,20 +135,31 @@ def test_uniform24_is_uniform_and_keyed(ref):
     v = np.array([ref.uniform24(42, 1, i) for i in range(2000)])
     w = np.array([ref.uniform24(43, 0, i) for i in range(2000)])
     assert abs(np.corrcoef(u[:2000], v)[0, 1]) < 0.08 and abs(np.corrcoef(u[:2000], w)[0, 1]) < 0.08
-    # SplitMix64 reference stream: with seed 0 the counter of element i is GOLDEN*(i+1), so the
-    # generator's published first outputs for seed 0 appear as the first draws.
-    first = 0xE220A8397B1DCDAF  # first output of SplitMix64 seeded with 0 (Vigna's reference)
-    assert ref.uniform24(0, 0, 0) == (first >> 40) * 2.0 ** -24
-    # the per-tensor copy takes the next 24 bits of the same draw
-    assert ref.uniform24(0, 1, 0) == ((first >> 16) & 0xFFFFFF) * 2.0 ** -24
-    second = 0x6E789E6AA1B965F4  # second output of the same reference stream: element 1
-    assert ref.uniform24(0, 0, 1) == (second >> 40) * 2.0 ** -24
-    assert ref.uniform24(0, 1, 1) == ((second >> 16) & 0xFFFFFF) * 2.0 ** -24
-    # the seed enters as the generator's state: element i of seed s is output i + 1 of SplitMix64 seeded with s
-    golden = 0x9E3779B97F4A7C15
-    assert ref.uniform24(golden, 0, 0) == (second >> 40) * 2.0 ** -24
     assert np.all(v * 2 ** 24 == np.floor(v * 2 ** 24)) and v.min() >= 0.0 and v.max() < 1.0
-    assert abs(v.mean() - 0.5) < 0.03
+    assert abs(v.mean() - 0.5) < 0.03 and abs(w.mean() - 0.5) < 0.03
+    # neighbouring seeds (a training loop counts its steps) and seeds that differ in the upper word are unrelated streams
+    for other in (43, 42 + 2 ** 32, 42 + 2 ** 63):
+        w2 = np.array([ref.uniform24(other, 0, i) for i in range(2000)])
+        assert abs(np.corrcoef(u[:2000], w2)[0, 1]) < 0.08
+        assert abs(np.corrcoef(u[1:2001], w2)[0, 1]) < 0.08 and abs(np.corrcoef(u[:2000], w2[::-1])[0, 1]) < 0.08
+    # lag-1 autocorrelation along the tensor
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.03
+
+
+def test_the_mixer_is_the_published_murmur3_finalizer(ref):
+    # MurmurHash3_x86_32 of the EMPTY message is fmix32(seed): its published verification values pin the mixer
+    assert ref.fmix32(0) == 0
+    assert ref.fmix32(1) == 0x514E28B7
+    assert ref.fmix32(0xFFFFFFFF) == 0x81F16F39
+    # a bijection: distinct words stay distinct (every position of a tensor gets its own draw)
+    xs = np.arange(200000, dtype=np.uint64)
+    assert len({ref.fmix32(int(x)) for x in xs[:50000]}) == 50000
+    # the uniform of element i is the top 24 bits of fmix32(i ^ key), with the key built from both halves of the seed
+    seed = 0x0123456789ABCDEF
+    for t in (0, 1):
+        key = ref.fmix32((seed & 0xFFFFFFFF) ^ ref.fmix32((seed >> 32) ^ ((0x9E3779B9 * (t + 1)) & 0xFFFFFFFF)))
+        for i in (0, 1, 77, 2 ** 31 - 1):
+            assert ref.uniform24(seed, t, i) == (ref.fmix32(i ^ key) >> 8) * 2.0 ** -24
 
 
 # ----------------------------------------------------------------------------- statistics
