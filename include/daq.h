@@ -356,20 +356,24 @@ daq_status daq_conv_bwd_int8(const daq_conv_desc* desc, const int8_t* qx_cnhw, c
                              size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * daq_conv_bwd_data_int8_bf16 -- daq_conv_bwd_data_int8 with a narrow result: the same int32
- * accumulators and the same fp32 product acc * ((s_w/127) * (s_global/127)), stored as bfloat16
- * (round to nearest, ties to even).  An option beside the method, not part of it: Algorithm 1
- * returns full-precision gradients; the data gradient's fp32 result is the largest stream of the
- * backward pass (4 bytes per input element), and a consumer that takes bf16 halves it.
- * Served for dense (groups = 1) layers at unit stride, and at stride 2 for the layers
- * daq_conv_bwd_data_int8 runs on its halo-tile kernel; DAQ_ERR_UNSUPPORTED otherwise.
+ * daq_conv_bwd_data_int8_bf16 / daq_conv_bwd_filter_int8_bf16 -- the two gradients with a narrow
+ * result: the same int32 accumulators and the same fp32 products acc * ((s_w/127) * (s_global/127))
+ * and acc * ((s_x/127) * (s_chan[co]/127)), stored as bfloat16 (round to nearest, ties to even).
+ * An option beside the method, not part of it: Algorithm 1 returns full-precision gradients; the
+ * data gradient's fp32 result is the largest stream of the backward pass (4 bytes per input
+ * element), and a consumer that takes bf16 halves it.  Every layer daq_conv_bwd_data_int8 /
+ * daq_conv_bwd_filter_int8 serve is served, by the same kernels.
  *
- *   dX_bf16   out  bfloat16 NCHW, 4-byte aligned
- *   other arguments and the workspace as for daq_conv_bwd_data_int8
+ *   dX_bf16   out  bfloat16 NCHW, 16-byte aligned
+ *   dW_bf16   out  bfloat16 [Cout][Cin/groups][kH][kW], 2-byte aligned
+ *   other arguments and the workspace as for the fp32 entry points
  * ------------------------------------------------------------------------------------------- */
 daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, const int8_t* qg, const float* s_global,
                                        const int8_t* qw_packed, const float* s_w, uint16_t* dX_bf16, void* workspace,
                                        size_t workspace_bytes, void* stream);
+daq_status daq_conv_bwd_filter_int8_bf16(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
+                                         const int8_t* vq, const float* s_chan, uint16_t* dW_bf16, void* workspace,
+                                         size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * daq_conv_bwd_data_int8_chan -- data gradient of a depthwise layer (groups = Cin = Cout, the

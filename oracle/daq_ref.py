@@ -389,3 +389,10 @@ def conv_bwd_data_int8_bf16(d: ConvDesc, qG, s_global, qW, s_w) -> np.ndarray:
     dX, _, ovf = conv_bwd_data_int8(d, qG, s_global, qW, s_w)
     assert not ovf
     return bf16_bits(dX)
+
+
+def conv_bwd_filter_int8_bf16(d: ConvDesc, qX, s_x, vq, s_chan) -> np.ndarray:
+    """The filter gradient of conv_bwd_filter_int8, stored as bfloat16 bit patterns."""
+    dW, _, ovf = conv_bwd_filter_int8(d, qX, s_x, vq, s_chan)
+    assert not ovf
+    return bf16_bits(dW)

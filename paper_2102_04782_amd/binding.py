@@ -28,7 +28,7 @@ SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESI
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
 ]
 
 
@@ -190,6 +190,7 @@ def lib():
         L.daq_conv_bwd_data_int8_chan.argtypes = [C.POINTER(ConvDesc)] + [vp] * 7 + [sz, vp]
         L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
         L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
+        L.daq_conv_bwd_filter_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
         L.daq_ceiling_mfma_i8.argtypes = [C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), vp]
         L.daq_ceiling_stream.argtypes = [C.c_int32, vp, vp, sz, C.c_int32, vp, vp]
@@ -407,7 +408,7 @@ def conv_bwd_filter_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, 
 def conv_bwd_data_int8_bf16(d: ConvDesc, qg: torch.Tensor, s_global: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,
                             dX: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                             stream=None) -> torch.Tensor:
-    """The data gradient stored as bfloat16 (raises DaqError with ERR_UNSUPPORTED where no kernel has that epilogue)."""
+    """The data gradient stored as bfloat16."""
     if dX is None:
         dX = torch.empty(d.x_shape, dtype=torch.bfloat16, device=qg.device)
     if workspace is None:
@@ -416,6 +417,20 @@ def conv_bwd_data_int8_bf16(d: ConvDesc, qg: torch.Tensor, s_global: torch.Tenso
                                            _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "daq_conv_bwd_data_int8_bf16")
     return dX
+
+
+def conv_bwd_filter_int8_bf16(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, vq: torch.Tensor, s_chan: torch.Tensor,
+                              dW: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                              stream=None) -> torch.Tensor:
+    """The filter gradient stored as bfloat16."""
+    if dW is None:
+        dW = torch.empty(d.w_shape, dtype=torch.bfloat16, device=vq.device)
+    if workspace is None:
+        workspace = _ws(workspace_bytes(OP_CONV_BWD_FILTER, d), vq.device)
+    rc = lib().daq_conv_bwd_filter_int8_bf16(C.byref(d), _ptr(qx_cnhw), _ptr(s_x), _ptr(vq), _ptr(s_chan), _ptr(dW),
+                                             _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv_bwd_filter_int8_bf16")
+    return dW
 
 
 def conv_bwd_data_int8_chan(d: ConvDesc, vq: torch.Tensor, s_chan: torch.Tensor, qw: torch.Tensor, s_w: torch.Tensor,

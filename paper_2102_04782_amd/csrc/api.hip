@@ -108,13 +108,38 @@ extern "C" daq_status daq_conv_bwd_data_int8_bf16(const daq_conv_desc* desc, con
                                                   const int8_t* qw_packed, const float* s_w, uint16_t* dX_bf16,
                                                   void* workspace, size_t workspace_bytes, void* stream) {
     if (!desc_valid(desc) || !qg || !s_global || !qw_packed || !s_w || !dX_bf16) return DAQ_ERR_INVALID_ARG;
-    if (!a16(qg) || !a16(qw_packed) || !a4(dX_bf16)) return DAQ_ERR_INVALID_ARG;
+    if (!a16(qg) || !a16(qw_packed) || !a16(dX_bf16)) return DAQ_ERR_INVALID_ARG;
     const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, desc);
     if (need == 0) return DAQ_ERR_UNSUPPORTED;
     if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
-    if (!bwd_data_halo_supported(*desc)) return DAQ_ERR_UNSUPPORTED;   // only the halo-tile kernel has the narrow epilogue
-    return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, reinterpret_cast<float*>(dX_bf16), nullptr,
-                              (hipStream_t)stream, nullptr, true);
+    // the kernels of daq_conv_bwd_data_int8, each with its narrow epilogue
+    hipStream_t st = (hipStream_t)stream;
+    float* out = reinterpret_cast<float*>(dX_bf16);
+    if (bwd_data_halo_supported(*desc))
+        return conv_bwd_data_halo(*desc, qg, s_global, qw_packed, s_w, out, nullptr, st, nullptr, true);
+    if (bwd_data_mfma_supported(*desc)) return conv_bwd_data_mfma(*desc, qg, s_global, qw_packed, s_w, out, nullptr, st, true);
+    if (depthwise_dx_supported(*desc))
+        return conv_bwd_data_depthwise(*desc, qg, s_global, qw_packed, s_w, out, nullptr, st, false, true);
+    return conv_bwd_data_generic(*desc, qg, s_global, qw_packed, s_w, out, nullptr, st, true);
+}
+
+extern "C" daq_status daq_conv_bwd_filter_int8_bf16(const daq_conv_desc* desc, const int8_t* qx_cnhw, const float* s_x,
+                                                    const int8_t* vq, const float* s_chan, uint16_t* dW_bf16,
+                                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (!desc_valid(desc) || !qx_cnhw || !s_x || !vq || !s_chan || !dW_bf16) return DAQ_ERR_INVALID_ARG;
+    if (!a16(qx_cnhw) || !a16(vq) || ((uintptr_t)dW_bf16 & 1u)) return DAQ_ERR_INVALID_ARG;
+    const size_t need = daq_workspace_bytes(DAQ_OP_CONV_BWD_FILTER, desc);
+    if (need == 0) return DAQ_ERR_UNSUPPORTED;
+    if (!ws_ok(workspace, workspace_bytes, need)) return DAQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float* out = reinterpret_cast<float*>(dW_bf16);
+    if (bwd_filter_lds_supported(*desc))
+        return conv_bwd_filter_lds(*desc, qx_cnhw, s_x, vq, s_chan, out, nullptr, workspace, st, nullptr, true);
+    if (bwd_filter_mfma_supported(*desc))
+        return conv_bwd_filter_mfma(*desc, qx_cnhw, s_x, vq, s_chan, out, nullptr, workspace, st, true);
+    if (depthwise_dw_supported(*desc))
+        return conv_bwd_filter_depthwise(*desc, qx_cnhw, s_x, vq, s_chan, out, nullptr, workspace, st, true);
+    return conv_bwd_filter_generic(*desc, qx_cnhw, s_x, vq, s_chan, out, nullptr, st, true);
 }
 
 extern "C" daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* vq, const float* s_chan,

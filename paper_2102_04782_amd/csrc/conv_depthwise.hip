@@ -60,6 +60,7 @@ struct DxArgs {
     float* dX;
     int32_t* acc_out;
     int nt;                // large result: streaming stores
+    int bf16;              // dX is bfloat16 storage
 };
 
 // Data gradient, unit stride and dilation, kW <= 4: a thread produces four adjacent outputs of one row.
@@ -107,15 +108,13 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit(DxArgs p) {
     const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
-        const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
-        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
-        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        store_result4(p.dX, o, (float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale, p.bf16, p.nt);
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (w0 + j < p.Win) {
-                p.dX[o + j] = (float)acc[j] * scale;
+                store_result(p.dX, o + j, (float)acc[j] * scale, p.bf16);
                 if (p.acc_out) p.acc_out[o + j] = acc[j];
             }
     }
@@ -171,15 +170,13 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_strided(DxArgs p) {
     const float scale = (*p.s_w / 127.0f) * (p.s_g[p.per_chan ? c : 0] / 127.0f);
     const int64_t o = (int64_t)row * p.Win + w0;
     if (w0 + 4 <= p.Win && ((p.Win & 3) == 0)) {
-        const v4f res = {(float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale};
-        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
-        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        store_result4(p.dX, o, (float)acc[0] * scale, (float)acc[1] * scale, (float)acc[2] * scale, (float)acc[3] * scale, p.bf16, p.nt);
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[0], acc[1], acc[2], acc[3]);
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (w0 + j < p.Win) {
-                p.dX[o + j] = (float)acc[j] * scale;
+                store_result(p.dX, o + j, (float)acc[j] * scale, p.bf16);
                 if (p.acc_out) p.acc_out[o + j] = acc[j];
             }
     }
@@ -237,9 +234,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_unit_block(DxArgs p) {
         const int h = h0 + a;
         if (h >= p.Hin) break;
         const int64_t o = ((int64_t)nc * p.Hin + h) * p.Win + w0;
-        const v4f res = {(float)acc[a][0] * scale, (float)acc[a][1] * scale, (float)acc[a][2] * scale, (float)acc[a][3] * scale};
-        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
-        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        store_result4(p.dX, o, (float)acc[a][0] * scale, (float)acc[a][1] * scale, (float)acc[a][2] * scale, (float)acc[a][3] * scale, p.bf16, p.nt);
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[a][0], acc[a][1], acc[a][2], acc[a][3]);
     }
 }
@@ -303,10 +298,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_s2_block(DxArgs p) {
         const int h = 4 * A + rr;
         if (h >= p.Hin) break;
         const int64_t o = ((int64_t)nc * p.Hin + h) * p.Win + 4 * m;
-        const v4f res = {(float)acc[rr][0] * scale, (float)acc[rr][1] * scale, (float)acc[rr][2] * scale,
-                         (float)acc[rr][3] * scale};
-        if (p.nt) __builtin_nontemporal_store(res, reinterpret_cast<v4f*>(p.dX + o));
-        else *reinterpret_cast<v4f*>(p.dX + o) = res;
+        store_result4(p.dX, o, (float)acc[rr][0] * scale, (float)acc[rr][1] * scale, (float)acc[rr][2] * scale, (float)acc[rr][3] * scale, p.bf16, p.nt);
         if (p.acc_out) *reinterpret_cast<int4*>(p.acc_out + o) = make_int4(acc[rr][0], acc[rr][1], acc[rr][2], acc[rr][3]);
     }
 }
@@ -348,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dx_any(DxArgs p) {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         if (w0 + j < p.Win) {
-            p.dX[o + j] = (float)acc[j] * scale;
+            store_result(p.dX, o + j, (float)acc[j] * scale, p.bf16);
             if (p.acc_out) p.acc_out[o + j] = acc[j];
         }
 }
@@ -450,7 +442,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dw(DwiseDwArgs p) {
 // One wave per filter element: its lanes take the slabs (independent loads, all in flight), then a shuffle tree.
 __global__ __launch_bounds__(kBlock) void k_dwise_dw_reduce(const int32_t* __restrict__ part, int C, int slabs, int T,
                                                             const float* s_x, const float* __restrict__ s_chan,
-                                                            float* __restrict__ dW, int32_t* __restrict__ acc_out) {
+                                                            float* __restrict__ dW, int32_t* __restrict__ acc_out, int bf16) {
     const int lane = threadIdx.x % kWave;
     const int i = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;   // filter element (c, t)
     if (i >= C * T) return;
@@ -460,7 +452,7 @@ __global__ __launch_bounds__(kBlock) void k_dwise_dw_reduce(const int32_t* __res
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) a += __shfl_down(a, o);
     if (lane != 0) return;
-    dW[i] = (float)a * ((*s_x / 127.0f) * (s_chan[c] / 127.0f));
+    store_result(dW, i, (float)a * ((*s_x / 127.0f) * (s_chan[c] / 127.0f)), bf16);
     if (acc_out) acc_out[i] = a;
 }
 
@@ -604,7 +596,7 @@ daq_status conv_fwd_depthwise(const daq_conv_desc& d, const int8_t* qx_cnhw, con
 }
 
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel) {
+                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel, bool bf16) {
     daq_layout Lg;
     daq_wpack_layout Lw;
     if (daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK || Lg.kind != DAQ_LAYOUT_CNHW)
@@ -623,7 +615,8 @@ daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, con
     a.div_c = make_fastdiv((uint32_t)d.Cin);
     a.s_g = s_g; a.s_w = s_w; a.dX = dX; a.acc_out = acc;
     a.per_chan = per_channel ? 1 : 0;
-    a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
+    a.bf16 = bf16 ? 1 : 0;
+    a.nt = (int64_t)d.N * d.Cin * d.Hin * d.Win * (bf16 ? 2 : 4) >= kStreamBytes;
     const int64_t threads = (int64_t)d.N * d.Cin * d.Hin * a.wq;
     const dim3 grid((unsigned)ceil_div(threads, kBlock));
     const bool unit = d.strideH == 1 && d.dilH == 1 && d.dilW == 1 && d.kW <= 4;
@@ -671,7 +664,7 @@ size_t depthwise_dw_ws_bytes(const daq_conv_desc& d) {
 }
 
 daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                     const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st) {
+                                     const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, bool bf16) {
     daq_layout Lx, Lg;
     if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
     DwiseDwArgs a{};
@@ -703,7 +696,7 @@ daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, c
     else DAQ_LAUNCH("conv_bwd_filter_depthwise", st, hipLaunchKernelGGL(k_dwise_dw<-1>, grid, dim3(kBlock), 0, st, a));
     DAQ_LAUNCH("dw_reduce", st,
                hipLaunchKernelGGL(k_dwise_dw_reduce, dim3((unsigned)ceil_div(d.Cout * a.T, kBlock / kWave)), dim3(kBlock), 0, st,
-                                  a.part, d.Cout, a.slabs, a.T, s_x, s_chan, dW, acc));
+                                  a.part, d.Cout, a.slabs, a.T, s_x, s_chan, dW, acc, bf16 ? 1 : 0));
     return DAQ_OK;
 }
 

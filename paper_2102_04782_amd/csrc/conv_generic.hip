@@ -58,7 +58,7 @@ template <bool G_NHWC>
 __global__ __launch_bounds__(kBlock) void k_bwd_data(Geo g, NhwcView Gn, CnhwView Gc, const int8_t* __restrict__ qg,
                                                      const int8_t* __restrict__ qw, const float* s_g,
                                                      const float* s_w, float* __restrict__ dX,
-                                                     int32_t* __restrict__ acc_out) {
+                                                     int32_t* __restrict__ acc_out, int bf16) {
     const int64_t total = (int64_t)g.N * g.Cin * g.Hin * g.Win;
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= total) return;
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_data(Geo g, NhwcView Gn, CnhwVie
             }
         }
     }
-    dX[i] = dq2(a, *s_w, *s_g);
+    store_result(dX, i, dq2(a, *s_w, *s_g), bf16);
     if (acc_out) acc_out[i] = a;
 }
 
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_data(Geo g, NhwcView Gn, CnhwVie
 __global__ __launch_bounds__(kBlock) void k_bwd_filter(Geo g, CnhwView X, CnhwView G, const int8_t* __restrict__ qx,
                                                        const int8_t* __restrict__ vq, const float* s_x,
                                                        const float* __restrict__ s_chan, float* __restrict__ dW,
-                                                       int32_t* __restrict__ acc_out) {
+                                                       int32_t* __restrict__ acc_out, int bf16) {
     const int64_t e = blockIdx.x;
     const int kw = (int)(e % g.kW);
     const int kh = (int)((e / g.kW) % g.kH);
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(kBlock) void k_bwd_filter(Geo g, CnhwView X, CnhwVi
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int w = 1; w < kBlock / kWave; ++w) a += part[w];
-        dW[e] = dq2(a, *s_x, s_chan[co]);
+        store_result(dW, e, dq2(a, *s_x, s_chan[co]), bf16);
         if (acc_out) acc_out[e] = a;
     }
 }
@@ -140,7 +140,7 @@ daq_status conv_fwd_generic(const daq_conv_desc& d, const int8_t* qx, const int8
 }
 
 daq_status conv_bwd_data_generic(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                                 const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+                                 const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool bf16) {
     daq_layout L;
     if (daq_layout_qg(&d, &L) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
     const Geo g = geo_of(d);
@@ -149,23 +149,23 @@ daq_status conv_bwd_data_generic(const daq_conv_desc& d, const int8_t* qg, const
     if (L.kind == DAQ_LAYOUT_NHWC)
         DAQ_LAUNCH("conv_bwd_data_direct", st,
                    hipLaunchKernelGGL((k_bwd_data<true>), grid, dim3(kBlock), 0, st, g, nhwc_view(L), CnhwView{}, qg,
-                                      qw, s_g, s_w, dX, acc));
+                                      qw, s_g, s_w, dX, acc, bf16 ? 1 : 0));
     else
         DAQ_LAUNCH("conv_bwd_data_direct", st,
                    hipLaunchKernelGGL((k_bwd_data<false>), grid, dim3(kBlock), 0, st, g, NhwcView{}, cnhw_view(L), qg,
-                                      qw, s_g, s_w, dX, acc));
+                                      qw, s_g, s_w, dX, acc, bf16 ? 1 : 0));
     return DAQ_OK;
 }
 
 daq_status conv_bwd_filter_generic(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                   const float* s_chan, float* dW, int32_t* acc, hipStream_t st) {
+                                   const float* s_chan, float* dW, int32_t* acc, hipStream_t st, bool bf16) {
     daq_layout Lx, Lg;
     if (daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK || daq_layout_vq(&d, &Lg) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
     const Geo g = geo_of(d);
     const int64_t total = (int64_t)g.Cout * g.cig * g.kH * g.kW;
     DAQ_LAUNCH("conv_bwd_filter_direct", st,
                hipLaunchKernelGGL(k_bwd_filter, dim3((unsigned)total), dim3(kBlock), 0, st, g, cnhw_view(Lx),
-                                  cnhw_view(Lg), qx, vq, s_x, s_chan, dW, acc));
+                                  cnhw_view(Lg), qx, vq, s_x, s_chan, dW, acc, bf16 ? 1 : 0));
     return DAQ_OK;
 }
 

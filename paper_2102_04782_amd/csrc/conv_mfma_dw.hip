@@ -55,7 +55,7 @@ struct DwArgs {
     const float* s_x;
     const float* s_chan;
     float* dW;
-    int32_t* acc_out;
+    int32_t* acc_out;    int bf16;             // dW is bfloat16 storage
 };
 
 __device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void k_dw_mfma(DwArgs p) {
                     const float sc = sx * (p.s_chan[co] / 127.0f);
 #pragma unroll
                     for (int t = 0; t < T; ++t) {
-                        p.dW[off + t] = (float)acc[m][nb * T + t][r] * sc;
+                        store_result(p.dW, off + t, (float)acc[m][nb * T + t][r] * sc, p.bf16);
                         if (p.acc_out) p.acc_out[off + t] = acc[m][nb * T + t][r];
                     }
                 }
@@ -449,7 +449,7 @@ __global__ __launch_bounds__(256) void k_dw_direct(DwArgs p) {
                             const float sc = sx * (p.s_chan[co] / 127.0f);
 #pragma unroll
                             for (int t = 0; t < T; ++t) {
-                                p.dW[off + t] = (float)acc[m][nb * T + t][r] * sc;
+                                store_result(p.dW, off + t, (float)acc[m][nb * T + t][r] * sc, p.bf16);
                                 if (p.acc_out) p.acc_out[off + t] = acc[m][nb * T + t][r];
                             }
                         }
@@ -624,7 +624,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
                             off = (((int64_t)co * p.Cin + cin) * T + tap) * tt.row_kw + (R - cin * tt.row_kw);
                         }
                         if (cin < p.Cin && co < p.Cout) {
-                            p.dW[off] = (float)v * (sx * (p.s_chan[co] / 127.0f));
+                            store_result(p.dW, off, (float)v * (sx * (p.s_chan[co] / 127.0f)), p.bf16);
                             if (p.acc_out) p.acc_out[off] = v;
                         }
                     }
@@ -674,7 +674,7 @@ __global__ __launch_bounds__(64 * WAVES) void k_dw_taps(DwArgs p, TapTable tt) {
 __global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ part, int64_t runs, int splits, int tiles_n, int wgn,
                                                    int nb_per_wave, int T, int row_kw, int Cout, int Cin, const float* s_x,
                                                    const float* __restrict__ s_chan, float* __restrict__ dW,
-                                                   int32_t* __restrict__ acc_out) {
+                                                   int32_t* __restrict__ acc_out, int bf16) {
     const int lane = threadIdx.x % kWave, grp = threadIdx.x / kWave;
     const int NT = nb_per_wave * T;
     const int per_wave = 16 * NT * kWave;
@@ -723,7 +723,7 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const int32_t* __restrict__ p
         off = (((int64_t)co * Cin + ci) * T + t) * row_kw + (R - ci * row_kw);
     }
     if (co >= Cout || ci >= Cin) return;
-    dW[off] = (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f));
+    store_result(dW, off, (float)a * ((*s_x / 127.0f) * (s_chan[co] / 127.0f)), bf16);
     if (acc_out) acc_out[off] = a;
 }
 
@@ -914,7 +914,7 @@ size_t bwd_filter_mfma_ws_bytes(const daq_conv_desc& d) {
 }
 
 daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st) {
+                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, bool bf16) {
     const Plan pl = make_plan(d);
     if (!pl.ok) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lx, Lg;
@@ -937,6 +937,7 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
     a.s_chan = s_chan;
     a.dW = dW;
     a.acc_out = acc;
+    a.bf16 = bf16 ? 1 : 0;
     daq_status rc;
     const int wq4 = Lx.row_pitch & 3;
     if (pl.general) {
@@ -957,7 +958,7 @@ daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const 
         DAQ_LAUNCH("dw_reduce", st,
                    hipLaunchKernelGGL(k_dw_reduce, dim3(rblocks), dim3(256), 0, st,
                                       a.part, runs, pl.splits, pl.tiles_n, wgn, pl.nb, pl.row_kw ? d.kH : T, pl.row_kw, d.Cout, d.Cin,
-                                      s_x, s_chan, dW, acc));
+                                      s_x, s_chan, dW, acc, bf16 ? 1 : 0));
     }
     return DAQ_OK;
 }

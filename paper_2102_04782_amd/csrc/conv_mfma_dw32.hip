@@ -51,7 +51,7 @@ struct Dw32Args {
     const float* s_x;
     const float* s_chan;
     float* dW;
-    int32_t* acc_out;
+    int32_t* acc_out;    int bf16;              // dW is bfloat16 storage
 };
 
 __device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
             const int64_t off = ((int64_t)co * p.Cin + ci0) * kT;
             for (int j = lane; j < ncol; j += kWave) {
                 const int v = red[row * ROWW + j];
-                p.dW[off + j] = (float)v * sc;
+                store_result(p.dW, off + j, (float)v * sc, p.bf16);
                 if (p.acc_out) p.acc_out[off + j] = v;
             }
         }
@@ -309,7 +309,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
             const float sc = sx * (p.s_chan[co] / 127.0f);
 #pragma unroll
             for (int t = 0; t < kT; ++t) {
-                p.dW[off + t] = (float)acc[t][r] * sc;
+                store_result(p.dW, off + t, (float)acc[t][r] * sc, p.bf16);
                 if (p.acc_out) p.acc_out[off + t] = acc[t][r];
             }
         }
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(256) void k_dw_reduce(DwTail t) {
     int co;
     const int64_t off = dw_tail_element(t, e, lane, co);
     if (off < 0) return;
-    t.dW[off] = (float)a * ((*t.s_x / 127.0f) * (t.s_chan[co] / 127.0f));
+    store_result(t.dW, off, (float)a * ((*t.s_x / 127.0f) * (t.s_chan[co] / 127.0f)), t.bf16);
     if (t.acc_out) t.acc_out[off] = a;
 }
 
@@ -507,7 +507,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
             const int ci = ci0 + wn * 64 + 32 * ((q / 16) % 2) + l32;
             if (co < p.Cout && ci < p.Cin) {
                 const int64_t off = (int64_t)co * p.Cin + ci;   // 32 lanes = 32 consecutive ci: 128-byte runs
-                p.dW[off] = (float)v * (sx * (p.s_chan[co] / 127.0f));
+                store_result(p.dW, off, (float)v * (sx * (p.s_chan[co] / 127.0f)), p.bf16);
                 if (p.acc_out) p.acc_out[off] = v;
             }
         }
@@ -607,7 +607,7 @@ size_t bwd_filter_lds_ws_bytes(const daq_conv_desc& d) {
 }
 
 daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, DwTail* defer) {
+                               const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, DwTail* defer, bool bf16) {
     if (defer) defer->blocks = 0;
     const Plan32 pl = make_plan32(d);
     if (!pl.ok) return DAQ_ERR_UNSUPPORTED;
@@ -632,6 +632,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.s_chan = s_chan;
     a.dW = dW;
     a.acc_out = acc;
+    a.bf16 = bf16 ? 1 : 0;
     const int wq4 = Lx.row_pitch & 3;
     if (pl.k11) {
         const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
@@ -647,9 +648,9 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
             DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
         }
         if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits))
-            *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
+            *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc, bf16 ? 1 : 0};
         else if (pl.splits > 1) {
-            const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc};
+            const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 1, s_x, s_chan, dW, acc, bf16 ? 1 : 0};
             const unsigned blocks = pl.splits > kDwReducePerWave ? (unsigned)t.blocks : (unsigned)ceil_div(t.blocks, 4);
             DAQ_LAUNCH("dw_reduce", st, hipLaunchKernelGGL(k_dw_reduce, dim3(blocks), dim3(256), 0, st, t));
         }
@@ -658,9 +659,9 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits)) {
-        *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
+        *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc, bf16 ? 1 : 0};
     } else if (pl.splits > 1) {
-        const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc};
+        const DwTail t{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc, bf16 ? 1 : 0};
         const unsigned blocks = pl.splits > kDwReducePerWave ? (unsigned)t.blocks : (unsigned)ceil_div(t.blocks, 4);
         DAQ_LAUNCH("dw_reduce", st, hipLaunchKernelGGL(k_dw_reduce, dim3(blocks), dim3(256), 0, st, t));
     }

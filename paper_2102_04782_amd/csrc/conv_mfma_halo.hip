@@ -68,12 +68,6 @@ struct HaloArgs {
     int nt;               // the result is large: streaming stores, so that it does not push the next kernels' operands out of the caches
 };
 
-// fp32 -> bfloat16 bits, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
 __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 0);
 }
@@ -555,6 +549,7 @@ struct StreamArgs {
     int nt;
     DwTail tail;          // tail.blocks > 0: that many workgroups behind the first main_blocks finish a deferred filter gradient
     int main_blocks;
+    int bf16;             // the result is bfloat16 storage
 };
 
 // KS = 32-byte contraction steps (cp <= 32 * KS)
@@ -612,6 +607,34 @@ __global__ __launch_bounds__(256) void k_dx_1x1_stream(StreamArgs p) {
             for (int j = 0; j < 2; ++j) {
                 const int rowbase = 32 * (2 * rp + j) + 4 * lh;
                 const int64_t at = ((int64_t)n * p.Crow + rowbase) * p.HW + r0;
+                if (p.bf16) {   // uniform
+                    uint16_t* ob = reinterpret_cast<uint16_t*>(p.out) + at;
+                    if ((p.HW & 1) == 0) {
+                        // Even planes: lanes 2k and 2k+1 hold pixels r0 (even) and r0 + 1 of one plane.  They trade values so
+                        // that the even lane stores the pair of row dr and the odd lane the pair of row dr + 1, each as one
+                        // aligned dword: half the store instructions, twice the bytes each.
+                        const bool odd = l32 & 1;
+#pragma unroll
+                        for (int r = 0; r < 16; r += 2) {
+                            const uint32_t v0 = bf16_bits((float)acc[j][r] * scale), v1 = bf16_bits((float)acc[j][r + 1] * scale);
+                            const uint32_t got = (uint32_t)__builtin_amdgcn_mov_dpp((int)(odd ? v0 : v1), 0xB1, 0xF, 0xF, false);
+                            const uint32_t word = odd ? (got | (v1 << 16)) : (v0 | (got << 16));
+                            const int dr = 8 * (r >> 2) + (r & 3) + (odd ? 1 : 0);
+                            if (rowbase + dr < p.Crow) {
+                                uint32_t* z = reinterpret_cast<uint32_t*>(ob + (int64_t)dr * p.HW - (odd ? 1 : 0));
+                                if (p.nt) __builtin_nontemporal_store(word, z);
+                                else *z = word;
+                            }
+                        }
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const int dr = 8 * (r >> 2) + (r & 3);
+                            if (rowbase + dr < p.Crow) ob[(int64_t)dr * p.HW] = (uint16_t)bf16_bits((float)acc[j][r] * scale);
+                        }
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 8 * (r >> 2) + (r & 3);
@@ -835,7 +858,7 @@ bool stream_applies(const daq_conv_desc& d, const daq_layout& Lg) {
 // src: the NHWC operand (layout Ls); wfrag: the fragment-order filter copy whose rows are the result's `rows` channels
 daq_status launch_stream(const char* name, const daq_conv_desc& d, const daq_layout& Ls, const int8_t* src,
                          const int8_t* wfrag, int64_t wfrag_bytes, int rows, const float* s_a, const float* s_b, float* out,
-                         int32_t* acc, hipStream_t st, const DwTail* tail) {
+                         int32_t* acc, hipStream_t st, const DwTail* tail, bool bf16 = false) {
     StreamArgs a{};
     a.src = src;
     a.wfrag = wfrag;
@@ -856,7 +879,8 @@ daq_status launch_stream(const char* name, const daq_conv_desc& d, const daq_lay
     a.div_hw = make_fastdiv((uint32_t)a.HW);
     a.s_a = s_a; a.s_b = s_b;
     a.out = out; a.acc_out = acc;
-    a.nt = (int64_t)d.N * rows * a.HW * 4 >= kStreamBytes;
+    a.bf16 = bf16 ? 1 : 0;
+    a.nt = (int64_t)d.N * rows * a.HW * (bf16 ? 2 : 4) >= kStreamBytes;
     const int64_t wgs = ceil_div((int64_t)a.RP * a.S, 4);
     if (tail) a.tail = *tail;
     a.main_blocks = (int)wgs;
@@ -882,9 +906,9 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     daq_wpack_layout Lw;
     if (!g.ok || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_UNSUPPORTED;
     daq_layout Lg;
-    if (!bf16 && daq_layout_qg(&d, &Lg) == DAQ_OK && stream_applies(d, Lg))
+    if (daq_layout_qg(&d, &Lg) == DAQ_OK && stream_applies(d, Lg))
         return launch_stream("conv_bwd_data_stream", d, Lg, qg, qw + Lw.off_bwd_frag, Lw.bytes - Lw.off_bwd_frag, d.Cin, s_w, s_g, dX, acc,
-                             st, tail);
+                             st, tail, bf16);
     g.a.src = qg;
     g.a.wfrag = qw + Lw.off_bwd_frag;
     g.a.s_a = s_w; g.a.s_b = s_g;

@@ -58,6 +58,7 @@ struct NhwcArgs {
     const float* s_b;
     float* out;          // fp32 [N][Crow][Hd][Wd]
     int32_t* acc_out;    // optional raw accumulators, same shape
+    int bf16;            // the result is bfloat16 storage
 };
 
 constexpr uint32_t kOob = 0x80000000u;  // a buffer offset past every extent: such a load returns zeros
@@ -238,7 +239,15 @@ __global__ __launch_bounds__(256) void k_nhwc_mfma(NhwcArgs p) {
         const uint32_t rem = P - (uint32_t)n * (uint32_t)HWd;
         const int64_t pix = ((int64_t)n * p.Crow + rowbase) * HWd + rem;
         float* o = p.out + pix;
-        if (full_rows) {
+        if (p.bf16) {   // uniform: the narrow result, one 2-byte store per value
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
+                    if (rowbase + dr < p.Crow) store_result(p.out, pix + (int64_t)dr * HWd, (float)acc[x][y][r] * scale, 1);
+                }
+        } else if (full_rows) {
 #pragma unroll
             for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -307,7 +316,7 @@ bool nhwc_supported(const daq_conv_desc& d) {
 bool bwd_data_mfma_supported(const daq_conv_desc& d) { return nhwc_supported(d); }
 
 daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st) {
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool bf16) {
     daq_layout Lg;
     daq_wpack_layout Lw;
     if (daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return DAQ_ERR_INVALID_ARG;
@@ -321,6 +330,7 @@ daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const fl
     a.backward = 1;
     a.s_a = s_w; a.s_b = s_g;
     a.out = dX; a.acc_out = acc;
+    a.bf16 = bf16 ? 1 : 0;
     a.src_bytes = (uint32_t)Lg.bytes;
     a.wpk_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd);
     return launch(a, d.dilH, d.dilW, st, "conv_bwd_data_nhwc");

@@ -51,6 +51,35 @@ __device__ __forceinline__ float ldf_or_zero(const float* p, bool ok) {
     return *(ok ? p : reinterpret_cast<const float*>(g_zero64));
 }
 
+// ---- results that are fp32 or, on request, bfloat16 -------------------------------------------
+// fp32 -> bfloat16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits(float f) {
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+// Element `off` of a result tensor whose storage is fp32, or bfloat16 when `bf16` is set (uniform).
+__device__ __forceinline__ void store_result(float* base, int64_t off, float v, int bf16) {
+    if (bf16) reinterpret_cast<uint16_t*>(base)[off] = (uint16_t)bf16_bits(v);
+    else base[off] = v;
+}
+// Four consecutive results starting at element `off`, a multiple of four: one 16-byte store, or one 8-byte store of
+// four bfloat16; `nt` asks for a streaming store.
+typedef float daq_v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t daq_v2u __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_result4(float* base, int64_t off, float a, float b, float c, float d, int bf16, int nt) {
+    if (bf16) {
+        const daq_v2u w = {bf16_bits(a) | (bf16_bits(b) << 16), bf16_bits(c) | (bf16_bits(d) << 16)};
+        daq_v2u* z = reinterpret_cast<daq_v2u*>(reinterpret_cast<uint16_t*>(base) + off);
+        if (nt) __builtin_nontemporal_store(w, z);
+        else *z = w;
+    } else {
+        const daq_v4f w = {a, b, c, d};
+        daq_v4f* z = reinterpret_cast<daq_v4f*>(base + off);
+        if (nt) __builtin_nontemporal_store(w, z);
+        else *z = w;
+    }
+}
+
 // ---- division by a launch-invariant divisor ---------------------------------------------------
 // Exact unsigned division by an invariant divisor (Granlund-Montgomery round-up multiplier).
 struct FastDiv {
@@ -113,19 +142,20 @@ daq_status quantize_filter(const daq_conv_desc& d, const float* W, int8_t* qw_pa
 // conv_generic.hip: direct kernels, any descriptor
 daq_status conv_fwd_generic(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
                             const float* s_w, float* Y, int32_t* acc, hipStream_t st);
+// With `bf16` the result pointer of a gradient routine (dX, dW) is bfloat16 storage: same product, rounded to nearest even.
 daq_status conv_bwd_data_generic(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                                 const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+                                 const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool bf16 = false);
 daq_status conv_bwd_filter_generic(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                   const float* s_chan, float* dW, int32_t* acc, hipStream_t st);
+                                   const float* s_chan, float* dW, int32_t* acc, hipStream_t st, bool bf16 = false);
 
 // conv_mfma_*.hip: int8 MFMA kernels; *_supported() says whether a descriptor is covered
 bool bwd_filter_mfma_supported(const daq_conv_desc& d);
 size_t bwd_filter_mfma_ws_bytes(const daq_conv_desc& d);
 daq_status conv_bwd_filter_mfma(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st);
+                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, bool bf16 = false);
 bool bwd_data_mfma_supported(const daq_conv_desc& d);
 daq_status conv_bwd_data_mfma(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                              const float* s_w, float* dX, int32_t* acc, hipStream_t st);
+                              const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool bf16 = false);
 bool fwd_mfma_supported(const daq_conv_desc& d);
 daq_status conv_fwd_mfma(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
                          const float* s_w, float* Y, int32_t* acc, hipStream_t st);
@@ -139,7 +169,7 @@ size_t bwd_filter_lds_ws_bytes(const daq_conv_desc& d);
 struct DwTail;
 daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
                                const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st,
-                               DwTail* defer = nullptr);
+                               DwTail* defer = nullptr, bool bf16 = false);
 
 // conv_mfma_halo.hip: halo-tile form of the channel-contracting kernel (unit stride; stride 2 for the data gradient)
 bool bwd_data_halo_supported(const daq_conv_desc& d);
@@ -155,13 +185,14 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx_nhwc, const in
 // conv_depthwise.hip: groups == channels, both operands channel-major
 bool depthwise_dx_supported(const daq_conv_desc& d);
 daq_status conv_bwd_data_depthwise(const daq_conv_desc& d, const int8_t* qg, const float* s_g, const int8_t* qw,
-                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel = false);
+                                   const float* s_w, float* dX, int32_t* acc, hipStream_t st, bool per_channel = false,
+                                   bool bf16 = false);
 bool depthwise_fwd_supported(const daq_conv_desc& d);
 daq_status conv_fwd_depthwise(const daq_conv_desc& d, const int8_t* qx_cnhw, const int8_t* qw, const float* s_x,
                               const float* s_w, float* Y, int32_t* acc, hipStream_t st);
 bool depthwise_dw_supported(const daq_conv_desc& d);
 size_t depthwise_dw_ws_bytes(const daq_conv_desc& d);
 daq_status conv_bwd_filter_depthwise(const daq_conv_desc& d, const int8_t* qx, const float* s_x, const int8_t* vq,
-                                     const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st);
+                                     const float* s_chan, float* dW, int32_t* acc, void* ws, hipStream_t st, bool bf16 = false);
 
 }  // namespace daq

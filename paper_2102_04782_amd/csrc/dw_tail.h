@@ -25,6 +25,7 @@ struct DwTail {
     const float* s_chan;
     float* dW;
     int32_t* acc_out;
+    int bf16;              // dW is bfloat16 storage
 };
 
 // Whether the role should replace the reduction launch: one workgroup per entry, each with more than 32 splits.
@@ -87,7 +88,7 @@ __device__ __forceinline__ void dw_reduce_role(const DwTail& t, int e, int32_t* 
     int co;
     const int64_t off = dw_tail_element(t, e, lane, co);
     if (off < 0) return;
-    t.dW[off] = (float)a * ((*t.s_x / 127.0f) * (t.s_chan[co] / 127.0f));
+    store_result(t.dW, off, (float)a * ((*t.s_x / 127.0f) * (t.s_chan[co] / 127.0f)), t.bf16);
     if (t.acc_out) t.acc_out[off] = a;
 }
 

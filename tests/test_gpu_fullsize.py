@@ -128,6 +128,13 @@ def test_sampled_outputs_at_full_size(config, index):
     _near(dW.view(-1)[iw_d].cpu().numpy(), ref.dequantize_acc(want, s_x, s_c[co]), "G_W")
     _near(dW2.view(-1)[iw_d].cpu().numpy(), ref.dequantize_acc(want, s_x2, s_c2[co]), "G_W under arbitrary scales")
 
+    # the narrow results of the same calls: the fp32 values above rounded to bfloat16, at the same positions
+    dXh = daq.conv_bwd_data_int8_bf16(d, q.qg, dev_f(s_g2), f.qw, dev_f(s_w2))
+    dWh = daq.conv_bwd_filter_int8_bf16(d, f.qx_cnhw, dev_f(s_x2), q.vq, dev_f(s_c2))
+    torch.cuda.synchronize()
+    assert torch.equal(dXh, dX2.to(torch.bfloat16)) and torch.equal(dWh, dW2.to(torch.bfloat16)), "bfloat16 results, whole tensors"
+    del dXh, dWh
+
     # the forward pass that produced the saved operands: accumulators and Y at sampled positions
     iy = rng.choice(f.acc.numel(), size=min(4096, f.acc.numel()), replace=False)
     want = ref.conv_fwd_acc_at(rd, Xh, Wh, iy)

@@ -700,34 +700,27 @@ def test_unknown_schedule_is_refused():
     assert e.value.code == daq.ERR_INVALID_ARG
 
 
-BF16_LAYERS = [l for l in CONV_LAYERS if l.name in ("c3x3", "c3x3_ragged", "c1x1", "c3x3_s2", "c1x1_s2", "nopad", "c3x3_64", "c3x3_7x7",
-                                                    "c1x1_wide", "c5x5", "c3x3_s2_big", "c1x1_s2_big", "c3x3_huge")]
-
-
-@pytest.mark.parametrize("layer", BF16_LAYERS, ids=lambda l: l.name)
-def test_data_gradient_with_bf16_result(layer):
-    """The optional narrow output: the same accumulators and fp32 product, stored as bfloat16 (nearest even).  The
-    fp32 products of the two sides are computed by the same operations, so the bit patterns must agree."""
+@pytest.mark.parametrize("layer", CONV_LAYERS + RANDOM_LAYERS[:16] + SPECIAL_LAYERS[:16], ids=lambda l: l.name)
+def test_gradients_with_bf16_results(layer):
+    """The optional narrow outputs of both gradients, on every kernel path: the same accumulators and fp32 products,
+    stored as bfloat16 (nearest even).  The fp32 products of the two sides are computed by the same operations, so the
+    bit patterns must agree with the oracle's rounding of its own fp32 result."""
     d, rd = descs(layer)
-    rng = np.random.default_rng(wl.seed_for(5, CONV_LAYERS.index(layer)))
+    rng = np.random.default_rng(wl.seed_for(5, len(layer.name) + layer.Cin + 7 * layer.Cout))
+    qX = rng.integers(-127, 128, layer.x_shape).astype(np.int8)
     qW = rng.integers(-127, 128, layer.w_shape).astype(np.int8)
     qG = rng.integers(-127, 128, layer.y_shape).astype(np.int8)
-    s_g, s_w = 0.03, 0.11
-    s_g_d, s_w_d = (torch.tensor([v], dtype=torch.float32, device=dev()) for v in (s_g, s_w))
+    s_g, s_w, s_x = 0.03, 0.11, 2.5
+    s_c = (10.0 ** rng.uniform(-4, -1, layer.Cout)).astype(np.float32)
+    s_g_d, s_w_d, s_x_d = (torch.tensor([v], dtype=torch.float32, device=dev()) for v in (s_g, s_w, s_x))
     qg, qw = t(daq.layout_qg(d).pack(qG)), t(daq.layout_qw(d).pack(d, qW))
     got = torch.full(d.x_shape, float("nan"), dtype=torch.bfloat16, device=dev())
     daq.conv_bwd_data_int8_bf16(d, qg, s_g_d, qw, s_w_d, dX=got)
+    vq, qx = t(daq.layout_vq(d).pack(qG)), t(daq.layout_qx_cnhw(d).pack(qX))
+    gotW = torch.full(d.w_shape, float("nan"), dtype=torch.bfloat16, device=dev())
+    daq.conv_bwd_filter_int8_bf16(d, qx, s_x_d, vq, t(s_c), dW=gotW)
     torch.cuda.synchronize()
     want = ref.conv_bwd_data_int8_bf16(rd, qG, s_g, qW, s_w)
-    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want)
-
-
-def test_bf16_result_is_refused_where_no_kernel_has_it():
-    layer = [l for l in CONV_LAYERS if l.name == "dw"][0]
-    d, _ = descs(layer)
-    one = torch.ones(1, dtype=torch.float32, device=dev())
-    qg = torch.zeros(daq.layout_qg(d).bytes, dtype=torch.int8, device=dev())
-    qw = torch.zeros(daq.layout_qw(d).bytes, dtype=torch.int8, device=dev())
-    with pytest.raises(daq.DaqError) as e:
-        daq.conv_bwd_data_int8_bf16(d, qg, one, qw, one)
-    assert e.value.code == daq.ERR_UNSUPPORTED
+    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want), "dX as bfloat16"
+    wantW = ref.conv_bwd_filter_int8_bf16(rd, qX, s_x, qG, s_c)
+    assert np.array_equal(gotW.view(torch.int16).cpu().numpy().view(np.uint16), wantW), "dW as bfloat16"
