@@ -73,7 +73,8 @@ enum { DAQ_CLASS_GAUSS = 0, DAQ_CLASS_INVT = 1 };
 
 typedef enum {
     DAQ_OP_QUANTIZE_GRAD = 0, DAQ_OP_CONV_FWD = 1, DAQ_OP_CONV_BWD_DATA = 2, DAQ_OP_CONV_BWD_FILTER = 3,
-    DAQ_OP_CONV_BWD = 4 /* both gradients in one call */
+    DAQ_OP_CONV_BWD = 4, /* both gradients in one call */
+    DAQ_OP_CLIP_SEARCH = 5
 } daq_op;
 
 /* ---------------------------------------------------------------------------------------------
@@ -393,6 +394,29 @@ daq_status daq_conv_bwd_filter_int8_bf16(const daq_conv_desc* desc, const int8_t
 daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* vq, const float* s_chan,
                                        const int8_t* qw_packed, const float* s_w, float* dX, int32_t* acc_out,
                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * daq_clip_search -- the objective behind the Magnitude-aware Clipping Strategy, minimised by search.
+ * For every output channel c of dY and every candidate clip value
+ *     s_j = |g|max_c * (j / J),   j = 1 .. J   (fp32; s_J = |g|max_c),
+ * the magnitude-weighted quantization error of Eq. "e" for the given alpha,
+ *     E_c(s_j) = (1/M) * sum over (n, h, w) of  |g - g^| * exp(alpha * |g|),    M = N*Hout*Wout,
+ *     g^ = round(clamp(g * (127/s_j), -127, 127)) * (s_j/127)      (Eq. "suq", nearest rounding, fp32),
+ * with the difference, the weight and the sum in fp64; then best_j[c] = the j of the smallest error (the smallest j
+ * among equals) and best_s[c] = s_{best_j}.  A channel whose |g|max is below 2^-100 has all errors equal and best_j = 1.
+ * Not a step of Algorithm 1, whose clip values come from the closed-form rules that this objective led to (alpha does
+ * not appear there): an analysis tool for comparing the two on real gradients.
+ *
+ *   dY      in   fp32 NCHW (Cout channels), 4-byte aligned
+ *   alpha   in   >= 0 (alpha * |g|max above about 700 overflows the fp64 weights);   J in 1 .. 64
+ *   err     out  optional (may be NULL) fp64 [Cout][J], 8-byte aligned
+ *   best_s  out  fp32 [Cout];   best_j out int32 [Cout]
+ *   workspace: daq_workspace_bytes(DAQ_OP_CLIP_SEARCH, desc)
+ * fp64 sums are taken in a fixed order (same bits in every run) that differs from a sequential sum: errors agree with
+ * a sequential evaluation to about 1e-12 relative.
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_clip_search(const daq_conv_desc* desc, const float* dY, float alpha, int32_t J, double* err, float* best_s,
+                           int32_t* best_j, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  Between daq_prof_begin() and daq_prof_end() every

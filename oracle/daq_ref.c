@@ -455,6 +455,43 @@ int daq_ref_quantize_grad_scheme(const float* dY, int N, int C, int H, int W, fl
 /* s = max|x| (reading: the paper defers the forward rule to earlier work and  */
 /* calls it global quantization; max-abs is taken), nearest rounding.          */
 /* ------------------------------------------------------------------------- */
+/* ------------------------------------------------------------------------- */
+/* The objective of the Magnitude-aware Clipping Strategy, Eq. "e", minimised  */
+/* by search: for channel c and candidate s_j = |g|max_c * (j / J), j = 1..J,  */
+/*   E_c(s_j) = (1/M) sum |g - g^| * exp(alpha |g|),  g^ = Q(g, s_j) * s_j/127 */
+/* (Q and the de-quantization as above, nearest rounding; difference, weight   */
+/* and sum in fp64, elements in NCHW order).  best_j = first j of the smallest */
+/* error, best_s = s_{best_j}.                                                 */
+/* ------------------------------------------------------------------------- */
+int daq_ref_clip_search(const float* g, int N, int C, int H, int W, float alpha, int J, double* err, float* best_s,
+                        int32_t* best_j) {
+    if (!g || !err || !best_s || !best_j || N <= 0 || C <= 0 || H <= 0 || W <= 0 || J < 1 || !(alpha >= 0.0f)) return REF_BAD_ARG;
+    const size_t HW = (size_t)H * W;
+    const double M = (double)N * (double)HW;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int c = 0; c < C; ++c) {
+        float gmax = 0.0f;
+        for (int n = 0; n < N; ++n)
+            for (size_t i = 0; i < HW; ++i) gmax = fmaxf(gmax, fabsf(g[((size_t)n * C + c) * HW + i]));
+        int arg = 0;
+        for (int j = 1; j <= J; ++j) {
+            const float s = gmax * ((float)j / (float)J);
+            double sum = 0.0;
+            for (int n = 0; n < N; ++n)
+                for (size_t i = 0; i < HW; ++i) {
+                    const float x = g[((size_t)n * C + c) * HW + i];
+                    const float gh = daq_ref_dequantize_one(daq_ref_quantize_one(x, s, REF_ROUND_NEAREST, 0.0f), s >= REF_TINY_SCALE ? s : 0.0f);
+                    sum += fabs((double)x - (double)gh) * exp((double)alpha * (double)fabsf(x));
+                }
+            err[(size_t)c * J + (j - 1)] = sum / M;
+            if (j > 1 && err[(size_t)c * J + (j - 1)] < err[(size_t)c * J + arg]) arg = j - 1;
+        }
+        best_j[c] = arg + 1;
+        best_s[c] = gmax * ((float)(arg + 1) / (float)J);
+    }
+    return REF_OK;
+}
+
 int daq_ref_quantize_tensor(const float* x, size_t n, int8_t* q, float* s_out) {
     if (!x || !q || !s_out) return REF_BAD_ARG;
     float m = 0.0f;

@@ -396,3 +396,15 @@ def conv_bwd_filter_int8_bf16(d: ConvDesc, qX, s_x, vq, s_chan) -> np.ndarray:
     dW, _, ovf = conv_bwd_filter_int8(d, qX, s_x, vq, s_chan)
     assert not ovf
     return bf16_bits(dW)
+
+
+def clip_search(dY, alpha: float, J: int):
+    """Eq. "e" on a grid of J clip values per channel: (err [C, J] fp64, best_s [C] fp32, best_j [C] int32, 1-based)."""
+    g = _f32(dY)
+    N, Cc, H, W = g.shape
+    err = np.zeros((Cc, J), np.float64)
+    best_s = np.zeros(Cc, np.float32)
+    best_j = np.zeros(Cc, np.int32)
+    _chk(lib().daq_ref_clip_search(_p(g, C.c_float), N, Cc, H, W, C.c_float(alpha), J, _p(err, C.c_double), _p(best_s, C.c_float),
+                                   _p(best_j, C.c_int32)), "clip_search")
+    return err, best_s, best_j

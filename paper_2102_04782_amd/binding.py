@@ -21,14 +21,14 @@ OK, ERR_INVALID_ARG, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP, ERR_SCRATCH_LIMIT 
 ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
 SCHEME_DAQ, SCHEME_GQ, SCHEME_GVQ, SCHEME_MCS = range(4)
 CLASS_GAUSS, CLASS_INVT = 0, 1
-OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER, OP_CONV_BWD = range(5)
+OP_QUANTIZE_GRAD, OP_CONV_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_FILTER, OP_CONV_BWD, OP_CLIP_SEARCH = range(6)
 LAYOUT_NHWC, LAYOUT_CNHW = 0, 1
 SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESIDENT = range(4)
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_clip_search", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
 ]
 
 
@@ -191,6 +191,7 @@ def lib():
         L.daq_conv_bwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 13 + [sz, vp]
         L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_conv_bwd_filter_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
+        L.daq_clip_search.argtypes = [C.POINTER(ConvDesc), vp, f32, C.c_int32, vp, vp, vp, vp, sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
         L.daq_ceiling_mfma_i8.argtypes = [C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), vp]
         L.daq_ceiling_stream.argtypes = [C.c_int32, vp, vp, sz, C.c_int32, vp, vp]
@@ -464,6 +465,19 @@ def conv_bwd_int8(d: ConvDesc, qx_cnhw: torch.Tensor, s_x: torch.Tensor, vq: tor
                                  _ptr(workspace), workspace.numel(), _stream(stream))
     _check(rc, "daq_conv_bwd_int8")
     return dW, dX
+
+
+def clip_search(d: ConvDesc, dY: torch.Tensor, alpha: float, J: int, want_err=True, stream=None):
+    """daq_clip_search: (err [Cout, J] fp64 or None, best_s [Cout] fp32, best_j [Cout] int32)."""
+    assert dY.is_cuda and dY.dtype == torch.float32 and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    err = torch.empty((d.Cout, J), dtype=torch.float64, device=dY.device) if want_err else None
+    best_s = torch.empty(d.Cout, dtype=torch.float32, device=dY.device)
+    best_j = torch.empty(d.Cout, dtype=torch.int32, device=dY.device)
+    ws = _ws(workspace_bytes(OP_CLIP_SEARCH, d), dY.device)
+    rc = lib().daq_clip_search(C.byref(d), _ptr(dY), alpha, J, _ptr(err), _ptr(best_s), _ptr(best_j), _ptr(ws), ws.numel(),
+                               _stream(stream))
+    _check(rc, "daq_clip_search")
+    return err, best_s, best_j
 
 
 # ------------------------------------------------------------------------------------------------

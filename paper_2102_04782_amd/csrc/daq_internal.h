@@ -139,6 +139,9 @@ daq_status quantize_activation(const daq_conv_desc& d, const float* X, int8_t* q
 daq_status quantize_filter(const daq_conv_desc& d, const float* W, int8_t* qw_packed, float* s_w, void* ws,
                            hipStream_t st);
 
+// clip_search.hip
+size_t clip_search_ws_bytes(const daq_conv_desc& d);
+
 // conv_generic.hip: direct kernels, any descriptor
 daq_status conv_fwd_generic(const daq_conv_desc& d, const int8_t* qx_nhwc, const int8_t* qw, const float* s_x,
                             const float* s_w, float* Y, int32_t* acc, hipStream_t st);

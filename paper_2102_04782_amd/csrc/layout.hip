@@ -181,6 +181,7 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* d) {
         case DAQ_OP_CONV_BWD_DATA: return 256;
         case DAQ_OP_CONV_BWD_FILTER: return 256 + std::max({bwd_filter_mfma_ws_bytes(*d), bwd_filter_lds_ws_bytes(*d), depthwise_dw_ws_bytes(*d)});
         case DAQ_OP_CONV_BWD: return daq_workspace_bytes(DAQ_OP_CONV_BWD_FILTER, d) + daq_workspace_bytes(DAQ_OP_CONV_BWD_DATA, d);
+        case DAQ_OP_CLIP_SEARCH: return clip_search_ws_bytes(*d);
         default: return 0;
     }
 }

@@ -265,3 +265,22 @@ def test_bf16_gradient_at_full_size(config, index):
         assert torch.equal(_logical_view(Lv, a.vq), torch.from_numpy(r.vq).to(device))
         assert torch.equal(_logical_view(Lg, a.qg), torch.from_numpy(r.qg).to(device))
         assert np.array_equal(a.cls.cpu().numpy(), r.cls) and np.array_equal(a.stats.cpu().numpy(), r.stats)
+
+
+def test_clip_search_at_benchmark_size():
+    """daq_clip_search on config 2's gradient (6.4 M elements, several slabs per channel) against the oracle."""
+    device = torch.device("cuda:0")
+    layer = wl.config_layers(2)[0]
+    d = daq.ConvDesc.make(*layer.desc_fields())
+    dY = wl.make_dY(layer, wl.seed_for(2, 0))
+    alpha, J = 3.0, 12
+    assert alpha * np.abs(dY).max() < 600
+    err, best_s, best_j = daq.clip_search(d, torch.from_numpy(dY).to(device), alpha, J)
+    torch.cuda.synchronize()
+    rerr, rs, rj = ref.clip_search(dY, alpha, J)
+    assert np.allclose(err.cpu().numpy(), rerr, rtol=1e-9, atol=0)
+    bj = best_j.cpu().numpy()
+    assert np.all(rerr[np.arange(layer.Cout), bj - 1] <= rerr.min(axis=1) * (1 + 1e-9))
+    assert np.array_equal(best_s.cpu().numpy(), np.abs(dY).max(axis=(0, 2, 3)) * (bj.astype(np.float32) / np.float32(J)))
+    # the channels the generator draws long-tailed (odd) want a clip well below |g|max at this alpha, the bell-shaped ones do not
+    assert np.median(bj[1::2]) < np.median(bj[0::2])

@@ -724,3 +724,42 @@ def test_gradients_with_bf16_results(layer):
     assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want), "dX as bfloat16"
     wantW = ref.conv_bwd_filter_int8_bf16(rd, qX, s_x, qG, s_c)
     assert np.array_equal(gotW.view(torch.int16).cpu().numpy().view(np.uint16), wantW), "dW as bfloat16"
+
+
+# ------------------------------------------------------------------------------------------------ clip-value search
+
+@pytest.mark.parametrize("layer", [CONV_LAYERS[0], ODD_LAYERS[0], ODD_LAYERS[1], ODD_LAYERS[7], ODD_LAYERS[10],
+                                   wl.Layer("cs_big", 16, 8, 28, 28, 70, 3, 3, 1, 1)], ids=lambda l: l.name)
+@pytest.mark.parametrize("alpha,J", [(0.0, 64), (0.7, 16), (5.0, 1), (2.5, 37)])
+def test_clip_search_against_the_oracle(layer, alpha, J):
+    """daq_clip_search: the error table within 1e-9 of the oracle's sequential fp64 sums (the GPU sums in a fixed tree
+    order, and its exp may differ from the host library's in the last bit), the chosen clip value exactly that of the
+    chosen candidate, and the chosen candidate a minimiser of the ORACLE's table up to that tolerance (where two
+    candidates tie to the last bits either is right)."""
+    d, _ = descs(layer)
+    seed = wl.seed_for(17, len(layer.name) + J)
+    dY = wl.make_dY(layer, seed)
+    dY[:, 0] = 0.0 if layer.Cout > 2 else dY[:, 0]          # an all-zero channel: every candidate is the zero scale
+    assert alpha * np.abs(dY).max() < 600, "the weights must stay finite for the comparison to mean anything"
+    err, best_s, best_j = daq.clip_search(d, t(dY), alpha, J)
+    torch.cuda.synchronize()
+    rerr, rs, rj = ref.clip_search(dY, alpha, J)
+    err, best_s, best_j = err.cpu().numpy(), best_s.cpu().numpy(), best_j.cpu().numpy()
+    assert np.allclose(err, rerr, rtol=1e-9, atol=0), f"error table: {np.abs(err / np.maximum(rerr, 1e-300) - 1).max():g} off"
+    gm = np.abs(dY).max(axis=(0, 2, 3))
+    assert np.array_equal(best_s, gm * (best_j.astype(np.float32) / np.float32(J)))
+    rows = np.arange(layer.Cout)
+    assert np.all(rerr[rows, best_j - 1] <= rerr.min(axis=1) * (1 + 1e-9))
+    assert np.all((best_j >= 1) & (best_j <= J))
+    same = best_j == rj
+    assert same.mean() > 0.99 or layer.Cout < 100 and same.sum() >= layer.Cout - 1
+
+
+def test_clip_search_refuses_bad_arguments():
+    layer = CONV_LAYERS[0]
+    d, _ = descs(layer)
+    g = torch.zeros(d.y_shape, device=dev())
+    for alpha, J in ((1.0, 0), (1.0, 65), (-1.0, 8), (float("nan"), 8)):
+        with pytest.raises(daq.DaqError) as e:
+            daq.clip_search(d, g, alpha, J)
+        assert e.value.code == daq.ERR_INVALID_ARG
