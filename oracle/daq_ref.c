@@ -840,3 +840,192 @@ int daq_ref_conv_bwd_filter_int8(const ref_conv_desc* d, const int8_t* qX, float
         for (size_t i = 0; i < per; ++i) dW[co * per + i] = dq2(acc_out[co * per + i], s_x, s_chan[co]);
     return REF_OK;
 }
+
+
+/* ========================================================================= */
+/* 3-D convolution (the video-classification experiment: the depth axis is    */
+/* treated like height and width).  Tensors: X in (N, Cin, Din, Hin, Win),     */
+/* W in (Cout, Cin/groups, kD, kH, kW), Y and G in (N, Cout, Do, Ho, Wo).      */
+/* Same definitions as the 2-D routines with one more spatial axis; the        */
+/* quantizer needs no 3-D form: its statistics run over all of (n, d, h, w),   */
+/* which is the 2-D routine on the tensor viewed as (N, C, D*H, W).            */
+/* ========================================================================= */
+typedef struct {
+    int N, Cin, Din, Hin, Win;
+    int Cout, kD, kH, kW;
+    int strideD, strideH, strideW;
+    int padD, padH, padW;
+    int dilD, dilH, dilW;
+    int groups;
+} ref_conv3d_desc;
+
+int daq_ref_out_d3(const ref_conv3d_desc* d) { return out_dim(d->Din, d->padD, d->dilD, d->kD, d->strideD); }
+int daq_ref_out_h3(const ref_conv3d_desc* d) { return out_dim(d->Hin, d->padH, d->dilH, d->kH, d->strideH); }
+int daq_ref_out_w3(const ref_conv3d_desc* d) { return out_dim(d->Win, d->padW, d->dilW, d->kW, d->strideW); }
+
+static int desc3_ok(const ref_conv3d_desc* d) {
+    if (!d) return 0;
+    if (d->N <= 0 || d->Cin <= 0 || d->Din <= 0 || d->Hin <= 0 || d->Win <= 0 || d->Cout <= 0) return 0;
+    if (d->kD <= 0 || d->kH <= 0 || d->kW <= 0 || d->strideD <= 0 || d->strideH <= 0 || d->strideW <= 0) return 0;
+    if (d->padD < 0 || d->padH < 0 || d->padW < 0 || d->dilD <= 0 || d->dilH <= 0 || d->dilW <= 0 || d->groups <= 0) return 0;
+    if (d->Cin % d->groups || d->Cout % d->groups) return 0;
+    if (daq_ref_out_d3(d) <= 0 || daq_ref_out_h3(d) <= 0 || daq_ref_out_w3(d) <= 0) return 0;
+    return 1;
+}
+
+/* forward: acc[n,co,do,ho,wo] = sum over (ci in the group, kd, kh, kw) of qX[n,ci,do*s+kd*dil-p,...] * qW[co,cl,kd,kh,kw] */
+int daq_ref_conv3d_fwd_acc(const ref_conv3d_desc* d, const int8_t* qX, const int8_t* qW, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !qX || !qW || !acc || !overflow) return REF_BAD_ARG;
+    const int Do = daq_ref_out_d3(d), Ho = daq_ref_out_h3(d), Wo = daq_ref_out_w3(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    int ovf = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : ovf)
+    for (int n = 0; n < d->N; ++n)
+        for (int co = 0; co < d->Cout; ++co) {
+            const int g = co / cog;
+            for (int od = 0; od < Do; ++od)
+                for (int ho = 0; ho < Ho; ++ho)
+                    for (int wo = 0; wo < Wo; ++wo) {
+                        int64_t a = 0;
+                        for (int cl = 0; cl < cig; ++cl) {
+                            const int ci = g * cig + cl;
+                            for (int kd = 0; kd < d->kD; ++kd) {
+                                const int z = od * d->strideD + kd * d->dilD - d->padD;
+                                if (z < 0 || z >= d->Din) continue;
+                                for (int kh = 0; kh < d->kH; ++kh) {
+                                    const int h = ho * d->strideH + kh * d->dilH - d->padH;
+                                    if (h < 0 || h >= d->Hin) continue;
+                                    for (int kw = 0; kw < d->kW; ++kw) {
+                                        const int w = wo * d->strideW + kw * d->dilW - d->padW;
+                                        if (w < 0 || w >= d->Win) continue;
+                                        a += (int64_t)qX[((((size_t)n * d->Cin + ci) * d->Din + z) * d->Hin + h) * d->Win + w] *
+                                             (int64_t)qW[((((size_t)co * cig + cl) * d->kD + kd) * d->kH + kh) * d->kW + kw];
+                                    }
+                                }
+                            }
+                        }
+                        int o = 0;
+                        acc[((((size_t)n * d->Cout + co) * Do + od) * Ho + ho) * Wo + wo] = wrap32(a, &o);
+                        ovf |= o;
+                    }
+        }
+    *overflow = ovf;
+    return REF_OK;
+}
+
+/* data gradient: acc[n,ci,z,h,w] = sum over (co in the group, kd, kh, kw) of qG[n,co,od,ho,wo] * qW[co,cl,kd,kh,kw]
+ * where od*stride + kd*dil - pad == z with od integral and inside the output (same for the other two axes) */
+int daq_ref_conv3d_bwd_data_acc(const ref_conv3d_desc* d, const int8_t* qG, const int8_t* qW, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !qG || !qW || !acc || !overflow) return REF_BAD_ARG;
+    const int Do = daq_ref_out_d3(d), Ho = daq_ref_out_h3(d), Wo = daq_ref_out_w3(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    int ovf = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : ovf)
+    for (int n = 0; n < d->N; ++n)
+        for (int ci = 0; ci < d->Cin; ++ci) {
+            const int g = ci / cig, cl = ci % cig;
+            for (int z = 0; z < d->Din; ++z)
+                for (int h = 0; h < d->Hin; ++h)
+                    for (int w = 0; w < d->Win; ++w) {
+                        int64_t a = 0;
+                        for (int col = 0; col < cog; ++col) {
+                            const int co = g * cog + col;
+                            for (int kd = 0; kd < d->kD; ++kd) {
+                                const int zn = z + d->padD - kd * d->dilD;
+                                if (zn < 0 || zn % d->strideD || zn / d->strideD >= Do) continue;
+                                for (int kh = 0; kh < d->kH; ++kh) {
+                                    const int hn = h + d->padH - kh * d->dilH;
+                                    if (hn < 0 || hn % d->strideH || hn / d->strideH >= Ho) continue;
+                                    for (int kw = 0; kw < d->kW; ++kw) {
+                                        const int wn = w + d->padW - kw * d->dilW;
+                                        if (wn < 0 || wn % d->strideW || wn / d->strideW >= Wo) continue;
+                                        a += (int64_t)qG[((((size_t)n * d->Cout + co) * Do + zn / d->strideD) * Ho + hn / d->strideH) * Wo + wn / d->strideW] *
+                                             (int64_t)qW[((((size_t)co * cig + cl) * d->kD + kd) * d->kH + kh) * d->kW + kw];
+                                    }
+                                }
+                            }
+                        }
+                        int o = 0;
+                        acc[((((size_t)n * d->Cin + ci) * d->Din + z) * d->Hin + h) * d->Win + w] = wrap32(a, &o);
+                        ovf |= o;
+                    }
+        }
+    *overflow = ovf;
+    return REF_OK;
+}
+
+/* filter gradient: acc[co,cl,kd,kh,kw] = sum over (n, od, ho, wo) of qX[n,ci,od*s+kd*dil-p,...] * qG[n,co,od,ho,wo] */
+int daq_ref_conv3d_bwd_filter_acc(const ref_conv3d_desc* d, const int8_t* qX, const int8_t* qG, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !qX || !qG || !acc || !overflow) return REF_BAD_ARG;
+    const int Do = daq_ref_out_d3(d), Ho = daq_ref_out_h3(d), Wo = daq_ref_out_w3(d);
+    const int cig = d->Cin / d->groups, cog = d->Cout / d->groups;
+    int ovf = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : ovf)
+    for (int co = 0; co < d->Cout; ++co)
+        for (int cl = 0; cl < cig; ++cl) {
+            const int ci = (co / cog) * cig + cl;
+            for (int kd = 0; kd < d->kD; ++kd)
+                for (int kh = 0; kh < d->kH; ++kh)
+                    for (int kw = 0; kw < d->kW; ++kw) {
+                        int64_t a = 0;
+                        for (int n = 0; n < d->N; ++n)
+                            for (int od = 0; od < Do; ++od) {
+                                const int z = od * d->strideD + kd * d->dilD - d->padD;
+                                if (z < 0 || z >= d->Din) continue;
+                                for (int ho = 0; ho < Ho; ++ho) {
+                                    const int h = ho * d->strideH + kh * d->dilH - d->padH;
+                                    if (h < 0 || h >= d->Hin) continue;
+                                    for (int wo = 0; wo < Wo; ++wo) {
+                                        const int w = wo * d->strideW + kw * d->dilW - d->padW;
+                                        if (w < 0 || w >= d->Win) continue;
+                                        a += (int64_t)qX[((((size_t)n * d->Cin + ci) * d->Din + z) * d->Hin + h) * d->Win + w] *
+                                             (int64_t)qG[((((size_t)n * d->Cout + co) * Do + od) * Ho + ho) * Wo + wo];
+                                    }
+                                }
+                            }
+                        int o = 0;
+                        acc[((((size_t)co * cig + cl) * d->kD + kd) * d->kH + kh) * d->kW + kw] = wrap32(a, &o);
+                        ovf |= o;
+                    }
+        }
+    *overflow = ovf;
+    return REF_OK;
+}
+
+/* The three layer routines: the 2-D ones with the 3-D products (same quantizers, same de-quantization pairing). */
+int daq_ref_conv3d_fwd_int8(const ref_conv3d_desc* d, const float* X, const float* Wt, int8_t* qX, int8_t* qW, float* s_x,
+                            float* s_w, float* Y, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !X || !Wt || !qX || !qW || !s_x || !s_w || !Y || !acc || !overflow) return REF_BAD_ARG;
+    const size_t nx = (size_t)d->N * d->Cin * d->Din * d->Hin * d->Win;
+    const size_t nw = (size_t)d->Cout * (d->Cin / d->groups) * d->kD * d->kH * d->kW;
+    const size_t ny = (size_t)d->N * d->Cout * daq_ref_out_d3(d) * daq_ref_out_h3(d) * daq_ref_out_w3(d);
+    int rc = daq_ref_quantize_tensor(X, nx, qX, s_x);
+    if (rc) return rc;
+    rc = daq_ref_quantize_tensor(Wt, nw, qW, s_w);
+    if (rc) return rc;
+    rc = daq_ref_conv3d_fwd_acc(d, qX, qW, acc, overflow);
+    if (!rc)
+        for (size_t i = 0; i < ny; ++i) Y[i] = dq2(acc[i], *s_x, *s_w);
+    return rc;
+}
+
+int daq_ref_conv3d_bwd_data_int8(const ref_conv3d_desc* d, const int8_t* qG, float s_global, const int8_t* qW, float s_w,
+                                 float* dX, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !dX || !acc) return REF_BAD_ARG;
+    int rc = daq_ref_conv3d_bwd_data_acc(d, qG, qW, acc, overflow);
+    if (rc) return rc;
+    const size_t nx = (size_t)d->N * d->Cin * d->Din * d->Hin * d->Win;
+    for (size_t i = 0; i < nx; ++i) dX[i] = dq2(acc[i], s_w, s_global);
+    return REF_OK;
+}
+
+int daq_ref_conv3d_bwd_filter_int8(const ref_conv3d_desc* d, const int8_t* qX, float s_x, const int8_t* vq, const float* s_chan,
+                                   float* dW, int32_t* acc, int* overflow) {
+    if (!desc3_ok(d) || !dW || !acc || !s_chan) return REF_BAD_ARG;
+    int rc = daq_ref_conv3d_bwd_filter_acc(d, qX, vq, acc, overflow);
+    if (rc) return rc;
+    const size_t per = (size_t)(d->Cin / d->groups) * d->kD * d->kH * d->kW;
+    for (int co = 0; co < d->Cout; ++co)
+        for (size_t i = 0; i < per; ++i) dW[co * per + i] = dq2(acc[co * per + i], s_x, s_chan[co]);
+    return REF_OK;
+}

@@ -408,3 +408,148 @@ def clip_search(dY, alpha: float, J: int):
     _chk(lib().daq_ref_clip_search(_p(g, C.c_float), N, Cc, H, W, C.c_float(alpha), J, _p(err, C.c_double), _p(best_s, C.c_float),
                                    _p(best_j, C.c_int32)), "clip_search")
     return err, best_s, best_j
+
+
+# --------------------------------------------------------------------------------------------- 3-D convolution
+
+class _Desc3(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("N", "Cin", "Din", "Hin", "Win", "Cout", "kD", "kH", "kW", "strideD", "strideH", "strideW",
+                                       "padD", "padH", "padW", "dilD", "dilH", "dilW", "groups")]
+
+
+@dataclass(frozen=True)
+class Conv3dDesc:
+    N: int
+    Cin: int
+    Din: int
+    Hin: int
+    Win: int
+    Cout: int
+    kD: int
+    kH: int
+    kW: int
+    strideD: int = 1
+    strideH: int = 1
+    strideW: int = 1
+    padD: int = 0
+    padH: int = 0
+    padW: int = 0
+    dilD: int = 1
+    dilH: int = 1
+    dilW: int = 1
+    groups: int = 1
+
+    def fields(self):
+        return (self.N, self.Cin, self.Din, self.Hin, self.Win, self.Cout, self.kD, self.kH, self.kW, self.strideD, self.strideH,
+                self.strideW, self.padD, self.padH, self.padW, self.dilD, self.dilH, self.dilW, self.groups)
+
+    def c(self) -> _Desc3:
+        return _Desc3(*self.fields())
+
+    @staticmethod
+    def _out(i, p, dil, k, s):
+        return (i + 2 * p - dil * (k - 1) - 1) // s + 1
+
+    @property
+    def Do(self):
+        return self._out(self.Din, self.padD, self.dilD, self.kD, self.strideD)
+
+    @property
+    def Ho(self):
+        return self._out(self.Hin, self.padH, self.dilH, self.kH, self.strideH)
+
+    @property
+    def Wo(self):
+        return self._out(self.Win, self.padW, self.dilW, self.kW, self.strideW)
+
+    @property
+    def x_shape(self):
+        return (self.N, self.Cin, self.Din, self.Hin, self.Win)
+
+    @property
+    def w_shape(self):
+        return (self.Cout, self.Cin // self.groups, self.kD, self.kH, self.kW)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.Cout, self.Do, self.Ho, self.Wo)
+
+
+def conv3d_fwd_acc(d: Conv3dDesc, qX, qW):
+    qX, qW = _i8(qX), _i8(qW)
+    assert qX.shape == d.x_shape and qW.shape == d.w_shape
+    acc = np.zeros(d.y_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_fwd_acc(C.byref(dd), _p(qX, C.c_int8), _p(qW, C.c_int8), _p(acc, C.c_int32), C.byref(ovf)), "conv3d_fwd_acc")
+    return acc, bool(ovf.value)
+
+
+def conv3d_bwd_data_acc(d: Conv3dDesc, qG, qW):
+    qG, qW = _i8(qG), _i8(qW)
+    assert qG.shape == d.y_shape and qW.shape == d.w_shape
+    acc = np.zeros(d.x_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_bwd_data_acc(C.byref(dd), _p(qG, C.c_int8), _p(qW, C.c_int8), _p(acc, C.c_int32), C.byref(ovf)),
+         "conv3d_bwd_data_acc")
+    return acc, bool(ovf.value)
+
+
+def conv3d_bwd_filter_acc(d: Conv3dDesc, qX, qG):
+    qX, qG = _i8(qX), _i8(qG)
+    assert qX.shape == d.x_shape and qG.shape == d.y_shape
+    acc = np.zeros(d.w_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_bwd_filter_acc(C.byref(dd), _p(qX, C.c_int8), _p(qG, C.c_int8), _p(acc, C.c_int32), C.byref(ovf)),
+         "conv3d_bwd_filter_acc")
+    return acc, bool(ovf.value)
+
+
+def conv3d_fwd_int8(d: Conv3dDesc, X, Wt) -> Fwd:
+    X, Wt = _f32(X), _f32(Wt)
+    assert X.shape == d.x_shape and Wt.shape == d.w_shape
+    qX, qW = np.zeros(d.x_shape, np.int8), np.zeros(d.w_shape, np.int8)
+    sx, sw = np.zeros(1, np.float32), np.zeros(1, np.float32)
+    Y, acc = np.zeros(d.y_shape, np.float32), np.zeros(d.y_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_fwd_int8(C.byref(dd), _p(X, C.c_float), _p(Wt, C.c_float), _p(qX, C.c_int8), _p(qW, C.c_int8),
+                                       _p(sx, C.c_float), _p(sw, C.c_float), _p(Y, C.c_float), _p(acc, C.c_int32), C.byref(ovf)),
+         "conv3d_fwd_int8")
+    return Fwd(qX, qW, float(sx[0]), float(sw[0]), Y, acc, bool(ovf.value))
+
+
+def conv3d_bwd_data_int8(d: Conv3dDesc, qG, s_global, qW, s_w):
+    qG, qW = _i8(qG), _i8(qW)
+    assert qG.shape == d.y_shape and qW.shape == d.w_shape
+    dX, acc = np.zeros(d.x_shape, np.float32), np.zeros(d.x_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_bwd_data_int8(C.byref(dd), _p(qG, C.c_int8), C.c_float(s_global), _p(qW, C.c_int8), C.c_float(s_w),
+                                            _p(dX, C.c_float), _p(acc, C.c_int32), C.byref(ovf)), "conv3d_bwd_data_int8")
+    return dX, acc, bool(ovf.value)
+
+
+def conv3d_bwd_filter_int8(d: Conv3dDesc, qX, s_x, vq, s_chan):
+    qX, vq = _i8(qX), _i8(vq)
+    s_chan = _f32(s_chan)
+    assert qX.shape == d.x_shape and vq.shape == d.y_shape and s_chan.shape == (d.Cout,)
+    dW, acc = np.zeros(d.w_shape, np.float32), np.zeros(d.w_shape, np.int32)
+    ovf = C.c_int(0)
+    dd = d.c()
+    _chk(lib().daq_ref_conv3d_bwd_filter_int8(C.byref(dd), _p(qX, C.c_int8), C.c_float(s_x), _p(vq, C.c_int8), _p(s_chan, C.c_float),
+                                              _p(dW, C.c_float), _p(acc, C.c_int32), C.byref(ovf)), "conv3d_bwd_filter_int8")
+    return dW, acc, bool(ovf.value)
+
+
+def quantize_grad3d(dY, s_state, **kw) -> QuantGrad:
+    """Algorithm 1's quantizer on an (N, C, D, H, W) gradient: its statistics run over (n, d, h, w), i.e. the 2-D routine
+    on the tensor viewed as (N, C, D*H, W); the codes are returned in the 5-D shape."""
+    g = _f32(dY)
+    N, Cc, D, H, W = g.shape
+    q = quantize_grad(g.reshape(N, Cc, D * H, W), s_state, **kw)
+    q.vq = q.vq.reshape(g.shape)
+    q.qg = q.qg.reshape(g.shape)
+    return q
