@@ -396,6 +396,55 @@ daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* 
                                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * 3-D convolution layers (the video-classification experiment: "treating depth dimension in the same
+ * way as height and width").  X in (N, Cin, Din, Hin, Win), W in (Cout, Cin/groups, kD, kH, kW), Y and
+ * G = dY in (N, Cout, Do, Ho, Wo); fp32 tensors are dense in that order.  Algorithm 1 is unchanged:
+ * its statistics run over all of (n, d, h, w), so the quantizer is the 2-D one on the gradient viewed
+ * as (N, Cout, Do*Ho, Wo), and the two gradients are Eq. "gx" / Eq. "gw" with one more spatial axis.
+ *
+ * int8 layouts: those of two 2-D "carrier" problems, daq_conv3d_carriers():
+ *   cx  describes the activation side: daq_layout_qx_nhwc(cx) / daq_layout_qx_cnhw(cx) are the layouts of q(X);
+ *   cg  describes the gradient side:   daq_layout_vq(cg) / daq_layout_qg(cg) are the layouts of vq and qg.
+ * Return value 1: the layer IS the 2-D problem cx == cg on reinterpreted tensors - a filter with kH = kW = 1 at unit
+ * stride and no padding in height and width (time-only filters, pointwise layers: depth becomes the row axis, a whole
+ * frame the column axis), or a volume of depth one - and every 3-D entry point forwards to its 2-D counterpart, the
+ * matrix-core kernels included; q(W) is then packed as daq_layout_qw(cx).  Return value 0: any other layer; the
+ * carriers are 1 x 1 problems that see (N, Cin, Din*Hin, Win) and (N, Cout, Do*Ho, Wo), q(W) is the plain
+ * [Cout][Cin/groups][kD][kH][kW] array of codes, and the products run on direct integer kernels (exact; far from
+ * the matrix-core rate).  -1: invalid descriptor or sizes beyond 2^31 elements.
+ *
+ * Entry points: arguments, alignment, error codes and results as for the 2-D entry point of the same name, with
+ * workspaces of daq_conv3d_workspace_bytes(op, desc) and q(W) buffers of daq_conv3d_qw_bytes(desc).
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t N, Cin, Din, Hin, Win;
+    int32_t Cout, kD, kH, kW;
+    int32_t strideD, strideH, strideW;
+    int32_t padD, padH, padW;
+    int32_t dilD, dilH, dilW;
+    int32_t groups;
+} daq_conv3d_desc;
+int32_t daq_conv3d_out_d(const daq_conv3d_desc* desc);
+int32_t daq_conv3d_out_h(const daq_conv3d_desc* desc);
+int32_t daq_conv3d_out_w(const daq_conv3d_desc* desc);
+int32_t daq_conv3d_carriers(const daq_conv3d_desc* desc, daq_conv_desc* cx, daq_conv_desc* cg);
+int64_t daq_conv3d_qw_bytes(const daq_conv3d_desc* desc);
+size_t daq_conv3d_workspace_bytes(daq_op op, const daq_conv3d_desc* desc);
+daq_status daq_quantize_grad3d(const daq_conv3d_desc* desc, const void* dY, float* s_state, float k, float A, float lambda,
+                               daq_round mode, uint64_t seed, const daq_quantize_opts* opts, int8_t* vq, int8_t* qg,
+                               float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
+                               size_t workspace_bytes, void* stream);
+daq_status daq_conv3d_fwd_int8(const daq_conv3d_desc* desc, const float* X, const float* W, int8_t* qx_nhwc, int8_t* qx_cnhw,
+                               int8_t* qw, float* s_x, float* s_w, float* Y, int32_t* acc_out, void* workspace,
+                               size_t workspace_bytes, void* stream);
+daq_status daq_conv3d_bwd_data_int8(const daq_conv3d_desc* desc, const int8_t* qg, const float* s_global, const int8_t* qw,
+                                    const float* s_w, float* dX, int32_t* acc_out, void* workspace, size_t workspace_bytes,
+                                    void* stream);
+daq_status daq_conv3d_bwd_filter_int8(const daq_conv3d_desc* desc, const int8_t* qx_cnhw, const float* s_x, const int8_t* vq,
+                                      const float* s_chan, float* dW, int32_t* acc_out, void* workspace,
+                                      size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * daq_clip_search -- the objective behind the Magnitude-aware Clipping Strategy, minimised by search.
  * For every output channel c of dY and every candidate clip value
  *     s_j = |g|max_c * (j / J),   j = 1 .. J   (fp32; s_J = |g|max_c),

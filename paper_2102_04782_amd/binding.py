@@ -28,7 +28,9 @@ SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESI
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
     "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
-    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_clip_search", "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
+    "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_clip_search", "daq_conv3d_out_d", "daq_conv3d_out_h", "daq_conv3d_out_w", "daq_conv3d_carriers", "daq_conv3d_qw_bytes",
+    "daq_conv3d_workspace_bytes", "daq_quantize_grad3d", "daq_conv3d_fwd_int8", "daq_conv3d_bwd_data_int8", "daq_conv3d_bwd_filter_int8",
+    "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
 ]
 
 
@@ -65,6 +67,35 @@ class ConvDesc(C.Structure):
     @property
     def y_shape(self):
         return (self.N, self.Cout, self.Ho, self.Wo)
+
+
+class Conv3dDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("N", "Cin", "Din", "Hin", "Win", "Cout", "kD", "kH", "kW", "strideD", "strideH", "strideW",
+                                         "padD", "padH", "padW", "dilD", "dilH", "dilW", "groups")]
+
+    @property
+    def Do(self):
+        return int(lib().daq_conv3d_out_d(C.byref(self)))
+
+    @property
+    def Ho(self):
+        return int(lib().daq_conv3d_out_h(C.byref(self)))
+
+    @property
+    def Wo(self):
+        return int(lib().daq_conv3d_out_w(C.byref(self)))
+
+    @property
+    def x_shape(self):
+        return (self.N, self.Cin, self.Din, self.Hin, self.Win)
+
+    @property
+    def w_shape(self):
+        return (self.Cout, self.Cin // self.groups, self.kD, self.kH, self.kW)
+
+    @property
+    def y_shape(self):
+        return (self.N, self.Cout, self.Do, self.Ho, self.Wo)
 
 
 class Layout(C.Structure):
@@ -192,6 +223,16 @@ def lib():
         L.daq_conv_bwd_data_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_conv_bwd_filter_int8_bf16.argtypes = [C.POINTER(ConvDesc)] + [vp] * 6 + [sz, vp]
         L.daq_clip_search.argtypes = [C.POINTER(ConvDesc), vp, f32, C.c_int32, vp, vp, vp, vp, sz, vp]
+        L.daq_conv3d_carriers.argtypes = [C.POINTER(Conv3dDesc), C.POINTER(ConvDesc), C.POINTER(ConvDesc)]
+        L.daq_conv3d_qw_bytes.restype = C.c_int64
+        L.daq_conv3d_qw_bytes.argtypes = [C.POINTER(Conv3dDesc)]
+        L.daq_conv3d_workspace_bytes.restype = C.c_size_t
+        L.daq_conv3d_workspace_bytes.argtypes = [C.c_int, C.POINTER(Conv3dDesc)]
+        L.daq_quantize_grad3d.argtypes = [C.POINTER(Conv3dDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.POINTER(QuantizeOpts),
+                                          vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.daq_conv3d_fwd_int8.argtypes = [C.POINTER(Conv3dDesc)] + [vp] * 10 + [sz, vp]
+        L.daq_conv3d_bwd_data_int8.argtypes = [C.POINTER(Conv3dDesc)] + [vp] * 7 + [sz, vp]
+        L.daq_conv3d_bwd_filter_int8.argtypes = [C.POINTER(Conv3dDesc)] + [vp] * 7 + [sz, vp]
         L.daq_prof_end.argtypes = [C.POINTER(ProfRow), C.c_int32, C.POINTER(C.c_int32)]
         L.daq_ceiling_mfma_i8.argtypes = [C.c_int32, C.c_int32, vp, C.POINTER(C.c_double), vp]
         L.daq_ceiling_stream.argtypes = [C.c_int32, vp, vp, sz, C.c_int32, vp, vp]
@@ -478,6 +519,66 @@ def clip_search(d: ConvDesc, dY: torch.Tensor, alpha: float, J: int, want_err=Tr
                                _stream(stream))
     _check(rc, "daq_clip_search")
     return err, best_s, best_j
+
+
+# ------------------------------------------------------------------------------------------------
+# 3-D convolution layers
+# ------------------------------------------------------------------------------------------------
+def conv3d_carriers(d: Conv3dDesc):
+    """(kind, cx, cg): the two 2-D problems whose layouts the int8 tensors of the 3-D layer use; kind 1 = the layer is
+    that 2-D problem, 0 = layouts only."""
+    cx, cg = ConvDesc(), ConvDesc()
+    kind = int(lib().daq_conv3d_carriers(C.byref(d), C.byref(cx), C.byref(cg)))
+    if kind < 0:
+        raise DaqError(ERR_INVALID_ARG, "daq_conv3d_carriers")
+    return kind, cx, cg
+
+
+def conv3d_fwd_int8(d: Conv3dDesc, X: torch.Tensor, W: torch.Tensor, want_acc=False, stream=None) -> Fwd:
+    assert X.is_cuda and X.dtype == torch.float32 and X.is_contiguous() and tuple(X.shape) == d.x_shape
+    assert W.is_cuda and W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == d.w_shape
+    kind, cx, cg = conv3d_carriers(d)
+    dev = X.device
+    i8 = dict(dtype=torch.int8, device=dev)
+    out = Fwd(qx_nhwc=torch.empty(layout_qx_nhwc(cx).bytes, **i8), qx_cnhw=torch.empty(layout_qx_cnhw(cx).bytes, **i8),
+              qw=torch.empty(int(lib().daq_conv3d_qw_bytes(C.byref(d))), **i8), s_x=torch.empty(1, device=dev), s_w=torch.empty(1, device=dev),
+              Y=torch.empty(d.y_shape, device=dev), acc=torch.empty(d.y_shape, dtype=torch.int32, device=dev) if want_acc else None,
+              workspace=_ws(int(lib().daq_conv3d_workspace_bytes(OP_CONV_FWD, C.byref(d))), dev))
+    rc = lib().daq_conv3d_fwd_int8(C.byref(d), _ptr(X), _ptr(W), _ptr(out.qx_nhwc), _ptr(out.qx_cnhw), _ptr(out.qw), _ptr(out.s_x),
+                                   _ptr(out.s_w), _ptr(out.Y), _ptr(out.acc), _ptr(out.workspace), out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_conv3d_fwd_int8")
+    return out
+
+
+def quantize_grad3d(d: Conv3dDesc, dY: torch.Tensor, s_state: torch.Tensor, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0,
+                    stream=None) -> QuantGrad:
+    assert dY.is_cuda and dY.dtype == torch.float32 and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    kind, cx, cg = conv3d_carriers(d)
+    out = alloc_quantize_grad(cg, dY.device)
+    out.workspace = _ws(int(lib().daq_conv3d_workspace_bytes(OP_QUANTIZE_GRAD, C.byref(d))), dY.device)
+    rc = lib().daq_quantize_grad3d(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, None, _ptr(out.vq), _ptr(out.qg),
+                                   _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats), _ptr(out.workspace),
+                                   out.workspace.numel(), _stream(stream))
+    _check(rc, "daq_quantize_grad3d")
+    return out
+
+
+def conv3d_bwd_data_int8(d: Conv3dDesc, qg, s_global, qw, s_w, acc: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    dX = torch.empty(d.x_shape, dtype=torch.float32, device=qg.device)
+    ws = _ws(int(lib().daq_conv3d_workspace_bytes(OP_CONV_BWD_DATA, C.byref(d))), qg.device)
+    rc = lib().daq_conv3d_bwd_data_int8(C.byref(d), _ptr(qg), _ptr(s_global), _ptr(qw), _ptr(s_w), _ptr(dX), _ptr(acc), _ptr(ws),
+                                        ws.numel(), _stream(stream))
+    _check(rc, "daq_conv3d_bwd_data_int8")
+    return dX
+
+
+def conv3d_bwd_filter_int8(d: Conv3dDesc, qx_cnhw, s_x, vq, s_chan, acc: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    dW = torch.empty(d.w_shape, dtype=torch.float32, device=vq.device)
+    ws = _ws(int(lib().daq_conv3d_workspace_bytes(OP_CONV_BWD_FILTER, C.byref(d))), vq.device)
+    rc = lib().daq_conv3d_bwd_filter_int8(C.byref(d), _ptr(qx_cnhw), _ptr(s_x), _ptr(vq), _ptr(s_chan), _ptr(dW), _ptr(acc), _ptr(ws),
+                                          ws.numel(), _stream(stream))
+    _check(rc, "daq_conv3d_bwd_filter_int8")
+    return dW
 
 
 # ------------------------------------------------------------------------------------------------
