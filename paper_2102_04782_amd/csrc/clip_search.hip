@@ -34,12 +34,12 @@ CsWs carve(void* base, int C, int64_t M) {
     w.S = (int)std::max<int64_t>(1, std::min<int64_t>(want, ceil_div(M, 4 * kBlock)));
     w.per_slab = (int)round_up(ceil_div(M, w.S), kBlock);
     w.S = (int)ceil_div(M, w.per_slab);
-    char* p = (char*)base;
-    w.pmax = (float*)p;
-    p += round_up((int64_t)C * w.S * 4, 256);
-    w.perr = (double*)p;
-    p += round_up((int64_t)C * w.S * kMaxJ * 8, 256);
-    w.bytes = p - (char*)base;
+    const int64_t o_err = round_up((int64_t)C * w.S * 4, 256);
+    w.bytes = o_err + round_up((int64_t)C * w.S * kMaxJ * 8, 256);
+    if (base) {   // a size query passes no buffer
+        w.pmax = (float*)base;
+        w.perr = (double*)((char*)base + o_err);
+    }
     return w;
 }
 

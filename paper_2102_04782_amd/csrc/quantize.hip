@@ -51,7 +51,6 @@ struct QuantWs {
 
 QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     QuantWs w{};
-    char* p = (char*)base;
     const int64_t M = (int64_t)N * HW;
     // statistics sweep groups of four elements per plane (k_stats): the axis is padded to whole groups
     const int64_t Mstats = HW >= 4 ? (int64_t)N * ((HW + 3) / 4) * 4 : M;
@@ -63,23 +62,33 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     const int want = std::max(1, kCountGrid / cb);
     const int titers = (int)ceil_div(w.tiles, want);
     w.cgroups = (int)ceil_div(w.tiles, titers);
-    w.gmax = (float*)p;
-    w.mean = w.gmax + C;
-    w.sigma = w.mean + C;
-    w.s_prev = w.sigma + C;
-    w.pred = (uint32_t*)(w.s_prev + C);
-    w.layer = (float*)(w.pred + C);
-    p += round_up(((int64_t)5 * C + 8) * 4, 256);
-    w.part_s1 = (double*)p;
-    w.part_s2 = w.part_s1 + (int64_t)C * w.slabs;
-    p += round_up((int64_t)2 * C * w.slabs * 8, 256);
-    w.part_max = (float*)p;
-    p += round_up((int64_t)C * w.slabs * 4, 256);
-    w.part_cnt = (uint32_t*)p;
-    p += round_up((int64_t)C * w.cgroups * 4, 256);
-    w.layer_cnt = (uint32_t*)p;
-    p += round_up((int64_t)cb * w.cgroups * (kBlock / kWave) * 4, 256);
-    w.total_bytes = p - (char*)base;
+    // byte offsets first; pointers only when there is a buffer (a size query passes none)
+    int64_t off = 0;
+    const int64_t o_head = off;
+    off += round_up(((int64_t)5 * C + 8) * 4, 256);
+    const int64_t o_s1 = off;
+    off += round_up((int64_t)2 * C * w.slabs * 8, 256);
+    const int64_t o_max = off;
+    off += round_up((int64_t)C * w.slabs * 4, 256);
+    const int64_t o_cnt = off;
+    off += round_up((int64_t)C * w.cgroups * 4, 256);
+    const int64_t o_lcnt = off;
+    off += round_up((int64_t)cb * w.cgroups * (kBlock / kWave) * 4, 256);
+    w.total_bytes = off;
+    if (base) {
+        char* p = (char*)base;
+        w.gmax = (float*)(p + o_head);
+        w.mean = w.gmax + C;
+        w.sigma = w.mean + C;
+        w.s_prev = w.sigma + C;
+        w.pred = (uint32_t*)(w.s_prev + C);
+        w.layer = (float*)(w.pred + C);
+        w.part_s1 = (double*)(p + o_s1);
+        w.part_s2 = w.part_s1 + (int64_t)C * w.slabs;
+        w.part_max = (float*)(p + o_max);
+        w.part_cnt = (uint32_t*)(p + o_cnt);
+        w.layer_cnt = (uint32_t*)(p + o_lcnt);
+    }
     return w;
 }
 
@@ -1528,7 +1537,11 @@ extern "C" daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void
                                            float* stats, void* workspace, size_t workspace_bytes, void* stream) {
     const daq_quantize_opts def{DAQ_SCHEME_DAQ, DAQ_SCHEDULE_AUTO, 0, 0};
     const daq_quantize_opts& o = opts ? *opts : def;
+    // the options arrive as plain integers: they are checked as integers, before anything treats them as enumerators
     if (o.dy_bf16 != 0 && o.dy_bf16 != 1) return DAQ_ERR_INVALID_ARG;
+    if (o.scheme < DAQ_SCHEME_DAQ || o.scheme > DAQ_SCHEME_MCS || o.schedule < DAQ_SCHEDULE_AUTO || o.schedule > DAQ_SCHEDULE_CHANNEL_RESIDENT ||
+        o.reserved != 0)
+        return DAQ_ERR_INVALID_ARG;
     if (o.dy_bf16)
         return quantize_grad_impl<uint16_t>(desc, static_cast<const uint16_t*>(dY), s_state, k, A, lambda, mode, seed,
                                             (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls,
