@@ -99,6 +99,11 @@ def build_network(args, dev, config, want_sample):
     from paper_2102_04782_amd import workloads as wl
 
     layers = wl.config_layers(config)
+    first = 0
+    if args.layer >= 0:   # one layer of the config on its own (per-layer profiles); it keeps its seed
+        if args.layer >= len(layers):
+            raise SystemExit(f"bench.py: config {config} has {len(layers)} layers")
+        first, layers = args.layer, layers[args.layer:args.layer + 1]
     dy_total = sum(4 * L.N * L.Cout * L.Ho * L.Wo for L in layers)
     R = args.rotate if args.rotate > 0 else max(1, -(-COLD_BYTES // dy_total))
     n_s = max(1, layers[0].N // 16)
@@ -106,7 +111,7 @@ def build_network(args, dev, config, want_sample):
     for r in range(R):
         for li, L in enumerate(layers):
             d = daq.ConvDesc.make(*L.desc_fields())
-            seed = wl.seed_for(config, li) + 7919 * r
+            seed = wl.seed_for(config, first + li) + 7919 * r
             gen = torch.Generator(device=dev)
             gen.manual_seed(seed)
             X = torch.randn(d.x_shape, device=dev, generator=gen)
@@ -271,11 +276,13 @@ def run_network(args, dev) -> int:
     n_stat = max(100, args.steps) if sec * max(100, args.steps) < 30.0 else args.steps
     med_ms, min_ms = step_statistics(step, n_stat)
     sec_other, _ = timed_run(args, net, nL, R, modes[other], args.steps, min(args.warmup, 3))
-    sec_two = None
-    if args.streams == 1:   # the same steps with the filter gradients on a second stream, reported beside the headline
-        args.streams, args.side = 2, torch.cuda.Stream()
-        sec_two, _ = timed_run(args, net, nL, R, modes[args.rounding], args.steps, min(args.warmup, 3))
-        args.streams, args.side = 1, None
+    # the same steps with the other stream count, reported beside the headline; the per-kernel pass below always runs on
+    # one stream, where a launch's duration is its own
+    head_streams = args.streams
+    args.streams, args.side = (1, None) if head_streams == 2 else (2, torch.cuda.Stream())
+    sec_alt, _ = timed_run(args, net, nL, R, modes[args.rounding], args.steps, min(args.warmup, 3))
+    args.streams, args.side = 1, None
+    sec_one = sec if head_streams == 1 else sec_alt
 
     # the two ways of calling the convolutions must agree bit for bit (first layer of the network, timed tensors)
     s0 = net[0]
@@ -310,7 +317,7 @@ def run_network(args, dev) -> int:
             row.setdefault("kernels_us", {})[k] = round(us * n, 1)
         layer_rows.append(row)
     ridge = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    traffic = measured_traffic(config) if (args.rounding == "stochastic" and not (args.dy_bf16 or args.dx_bf16 or args.separate or args.scheme != "daq" or args.schedule != "auto")) else {}
+    traffic = measured_traffic(config) if (args.rounding == "stochastic" and args.layer < 0 and not (args.dy_bf16 or args.dx_bf16 or args.separate or args.scheme != "daq" or args.schedule != "auto")) else {}
     table = {}
     for k, e in kernels.items():
         t = e["us"] * 1e-6
@@ -360,16 +367,19 @@ def run_network(args, dev) -> int:
                    "rounding": args.rounding, "k": 1.0, "A": 0.8, "lambda": 0.3, "buffer_sets": R,
                    "dY_bytes_per_step": int(dy_b * E_Y_total), "cold": bool(R * dy_b * E_Y_total >= COLD_BYTES),
                    "dX": "bf16 where served" if args.dx_bf16 else "fp32", "dY": "bf16" if args.dy_bf16 else "fp32",
-                   "scheme": args.scheme, "schedule": args.schedule, "streams": args.streams,
-                   "calls": "daq_quantize_grad_ex + " + ("daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8" if (args.separate or args.dx_bf16)
-                                                         else "daq_conv_bwd_int8")},
+                   "scheme": args.scheme, "schedule": args.schedule, "streams": head_streams,
+                   "calls": "daq_quantize_grad_ex + " + (
+                       "daq_conv_bwd_data_int8, and daq_conv_bwd_filter_int8 on a second stream" if head_streams == 2 else
+                       "daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8" if (args.separate or args.dx_bf16) else "daq_conv_bwd_int8")},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "step_ms_median": round(med_ms, 5), "step_ms_min": round(min_ms, 5), "stat_steps": n_stat,
         other: {"ms_per_step": round(1e3 * sec_other, 5), "value": round(ops_per_step / sec_other / 1e12, 3)},
-        "two_streams": None if sec_two is None else {"ms_per_step": round(1e3 * sec_two, 5), "value": round(ops_per_step / sec_two / 1e12, 3),
-                                                     "what": "filter gradients on a second stream"},
+        ("one_stream" if head_streams == 2 else "two_streams"): {
+            "ms_per_step": round(1e3 * sec_alt, 5), "value": round(ops_per_step / sec_alt / 1e12, 3),
+            "what": "every launch on one stream" if head_streams == 2 else "filter gradients on a second stream"},
         "phase_us_per_step": {k: round(v, 1) for k, v in phases.items()},
-        "launch_gap_us_per_step": round(1e6 * sec - sum(phases.values()), 1),
+        "phase_note": "sums of single launch durations measured on one stream",
+        "launch_gap_us_per_step": round(1e6 * sec_one - sum(phases.values()), 1),
         "quant_GBps_effective_6B": round(6.0 * E_Y_total / (phases["quantize"] * 1e-6) / 1e9, 1) if phases["quantize"] else None,
         "event_pair_overhead_us": round(ev_us, 3),
         "kernels": table,
@@ -595,6 +605,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload of BASELINE.json (1-5); 4 = ResNet-50 at batch 64")
+    ap.add_argument("--layer", type=int, default=-1, help="restrict the workload to this layer of the config (0-based)")
     ap.add_argument("--rounding", default="stochastic", choices=("stochastic", "nearest"),
                     help="rounding of the gradient quantizer in the reported step (the paper prescribes stochastic rounding "
                          "for gradients); the other mode is timed as well and reported beside it")
@@ -615,8 +626,10 @@ def main() -> int:
     ap.add_argument("--copy-calib-mib", type=int, default=0,
                     help="with --only-timed: afterwards run 5 device-to-device copies of this many MiB, the plain copy "
                          "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
-    ap.add_argument("--streams", type=int, default=1, choices=(1, 2),
-                    help="2: the filter gradients run on a second stream beside the quantizer and the data gradients")
+    ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
+                    help="2 (default): once a layer's dY is quantized its filter gradient, which nothing downstream in a "
+                         "backward pass waits for, runs on a second stream beside the data gradient and the next layer's "
+                         "quantizer; 1: every launch on one stream.  The other count is timed too and reported beside")
     ap.add_argument("--schedule", default="auto", choices=tuple(SCHEDULES),
                     help="how the quantizer shares its sweeps over dY among its launches (daq_quantize_grad_ex); same results")
     ap.add_argument("--dy-bf16", action="store_true",

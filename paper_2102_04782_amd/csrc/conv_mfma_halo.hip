@@ -173,6 +173,9 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             aoff[x][sub] = rb < p.RB ? (uint32_t)((rb * 2 + sub) * 1024 + lane * 16) : kOob;
         }
     v4i ra[kRingA][2][2];   // [ring slot][x][sub]
+    // A wave whose second 32-row block lies wholly past the last row (results with a handful of channels: the data
+    // gradient of a network's first layer) neither fetches nor multiplies it - dynamic-tap form only.
+    const int nx = (row0 + wr * 64 + 32 < p.Crow) ? 2 : 1;   // uniform
     int f_j = 0, f_kc = 0, f_s = 0;
     auto fetch_a = [&](int slot) {
         const bool live = f_s < NS;
@@ -181,8 +184,10 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         const uint32_t base = live ? (uint32_t)(((f_kc * p.T + id) * p.RB) * 2048) : 0u;
 #pragma unroll
         for (int x = 0; x < 2; ++x)
+            if (x < nx) {
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
+                for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
+            }
         ++f_s;
         if (++f_j == taps) { f_j = 0; ++f_kc; }
     };
@@ -347,9 +352,11 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
                             b[y] = *reinterpret_cast<const v4i*>(H + (bslot[y] + ts) * kPitch + 32 * sub);
     #pragma unroll
                         for (int x = 0; x < 2; ++x)
+                            if (x < nx) {
     #pragma unroll
-                            for (int y = 0; y < BF; ++y)
-                                acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
+                                for (int y = 0; y < BF; ++y)
+                                    acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
+                            }
                     }
                     if (j + 1 == taps) {
                         if (DB && kci + 1 < nkc) {
