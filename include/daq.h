@@ -163,9 +163,10 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  * Then  vq = Q(dY, s_c) per channel,  qg = Q(dY, s_global),  s_global = max_c |g|max_c,
  * Q being Eq. "suq" evaluated in fp32 as round(clamp(x * (127/s), -127, 127)).
  * A scale below 2^-100 is reported as 0 and produces all-zero codes.
- * Stochastic rounding: with fmix32 the 32-bit finalizer of MurmurHash3 and, per copy t (0 = vq, 1 = qg),
- *   key_t = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9*(t+1))),
- * element i (its NCHW index) draws u = (fmix32(i ^ key_t) >> 8) * 2^-24 and rounds up iff frac(x*127/s) > u.
+ * Stochastic rounding: with fmix32 the 32-bit finalizer of MurmurHash3 and
+ *   key = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9)),
+ * element i (its NCHW index) hashes once, h = fmix32(i ^ key); vq draws u = (h >> 16) * 2^-16, qg draws
+ * u = (h & 0xFFFF) * 2^-16, and a copy rounds up iff frac(x*127/s) > u.
  *
  *   dY        in   fp32 NCHW
  *   s_state   i/o  fp32 [Cout]  clip values of the previous iteration, replaced by this iteration's

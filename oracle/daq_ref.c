@@ -85,14 +85,17 @@ static int desc_ok(const ref_conv_desc* d) {
 /* ------------------------------------------------------------------------- */
 /* Counter-based uniform generator for stochastic rounding.                   */
 /*                                                                             */
-/* The paper asks for stochastic rounding of the gradients and names no        */
-/* generator.  Reading: a keyed hash of the element's position.  fmix32 is the */
-/* 32-bit finalizer of MurmurHash3 (Appleby, public domain): a bijection of    */
-/* 32-bit words in which every input bit reaches every output bit.  A call     */
-/* with `seed` has one key per int8 copy t (0: per-channel, 1: per-tensor),    */
-/*     key_t = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9 * (t + 1))),       */
-/* and element idx (its NCHW linear index, below 2^31) of copy t draws the     */
-/* 24-bit uniform  u = (fmix32(idx ^ key_t) >> 8) * 2^-24  in [0,1).           */
+/* The paper asks for stochastic rounding of the gradients and names neither a  */
+/* generator nor the number of random bits.  Reading: a keyed hash of the      */
+/* element's position, 16 bits per draw.  fmix32 is the 32-bit finalizer of    */
+/* MurmurHash3 (Appleby, public domain): a bijection of 32-bit words in which  */
+/* every input bit reaches every output bit.  A call with `seed` has the key   */
+/*     key = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9)),                    */
+/* element idx (its NCHW linear index, below 2^31) hashes once,                */
+/*     h = fmix32(idx ^ key),                                                   */
+/* and the two int8 copies take disjoint halves of the word: the per-channel   */
+/* copy (t = 0) draws u = (h >> 16) * 2^-16, the per-tensor copy (t = 1)       */
+/* u = (h & 0xFFFF) * 2^-16, both in [0,1).                                    */
 /* ------------------------------------------------------------------------- */
 uint32_t daq_ref_fmix32(uint32_t h) {
     h ^= h >> 16;
@@ -103,11 +106,12 @@ uint32_t daq_ref_fmix32(uint32_t h) {
     return h;
 }
 
-float daq_ref_uniform24(uint64_t seed, uint32_t tensor, uint64_t idx) {
+float daq_ref_uniform16(uint64_t seed, uint32_t tensor, uint64_t idx) {
     uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    uint32_t key = daq_ref_fmix32(lo ^ daq_ref_fmix32(hi ^ (UINT32_C(0x9E3779B9) * (tensor + 1u))));
-    uint32_t bits = daq_ref_fmix32((uint32_t)idx ^ key) >> 8;
-    return (float)bits * 5.9604644775390625e-08f; /* 2^-24, exact */
+    uint32_t key = daq_ref_fmix32(lo ^ daq_ref_fmix32(hi ^ UINT32_C(0x9E3779B9)));
+    uint32_t h = daq_ref_fmix32((uint32_t)idx ^ key);
+    uint32_t bits = tensor == 0u ? h >> 16 : h & UINT32_C(0xFFFF);
+    return (float)bits * 1.52587890625e-05f; /* 2^-16, exact */
 }
 
 /* ------------------------------------------------------------------------- */
@@ -115,7 +119,8 @@ float daq_ref_uniform24(uint64_t seed, uint32_t tensor, uint64_t idx) {
 /*   q(x) = round(127 * clamp(x, s) / s)                                       */
 /* evaluated in fp32 as: inv = 127/s (one IEEE division per scale), t = x*inv, */
 /* t clamped to [-127, 127] (same set of x as clamping x to [-s, s]), then     */
-/* rounded.  Nearest = ties-to-even.  Stochastic = floor(t) + [frac(t) > u].   */
+/* rounded.  Nearest = ties-to-even.  Stochastic = floor(t) + [frac(t) > u],    */
+/* the bracket evaluated exactly.                                              */
 /* ------------------------------------------------------------------------- */
 int8_t daq_ref_quantize_one(float x, float s, int mode, float u) {
     if (!(s >= REF_TINY_SCALE)) return 0;
@@ -123,9 +128,12 @@ int8_t daq_ref_quantize_one(float x, float s, int mode, float u) {
     float t = x * inv;
     t = fminf(fmaxf(t, -127.0f), 127.0f);
     if (mode == REF_ROUND_STOCHASTIC) {
+        /* frac(t) > u, decided without rounding: t - floor(t) is not always an fp32 number (t = -2^-30 has the        */
+        /* fraction 1 - 2^-30), so both sides are scaled by 2^16 and compared as doubles, where t * 2^16 is exact and */
+        /* floor(t) * 2^16 + u * 2^16 is an exact integer for every 16-bit draw u.                                      */
         float f = floorf(t);
-        float frac = t - f; /* exact: 0 <= frac < 1 */
-        return (int8_t)(int)(f + (frac > u ? 1.0f : 0.0f));
+        double lhs = (double)t * 65536.0, rhs = (double)f * 65536.0 + (double)u * 65536.0;
+        return (int8_t)((int)f + (lhs > rhs ? 1 : 0));
     }
     return (int8_t)(int)rintf(t);
 }
@@ -291,8 +299,8 @@ int daq_ref_quantize_grad(const float* dY, int N, int C, int H, int W, float* s_
                 const size_t idx = base + i;
                 float u0 = 0.0f, u1 = 0.0f;
                 if (mode == REF_ROUND_STOCHASTIC) {
-                    u0 = daq_ref_uniform24(seed, 0u, (uint64_t)idx);
-                    u1 = daq_ref_uniform24(seed, 1u, (uint64_t)idx);
+                    u0 = daq_ref_uniform16(seed, 0u, (uint64_t)idx);
+                    u1 = daq_ref_uniform16(seed, 1u, (uint64_t)idx);
                 }
                 vq[idx] = daq_ref_quantize_one(dY[idx], sc, mode, u0);
                 qg[idx] = daq_ref_quantize_one(dY[idx], sglob, mode, u1);
@@ -439,8 +447,8 @@ int daq_ref_quantize_grad_scheme(const float* dY, int N, int C, int H, int W, fl
                 const size_t idx = base + i;
                 float u0 = 0.0f, u1 = 0.0f;
                 if (mode == REF_ROUND_STOCHASTIC) {
-                    u0 = daq_ref_uniform24(seed, 0u, (uint64_t)idx);
-                    u1 = daq_ref_uniform24(seed, 1u, (uint64_t)idx);
+                    u0 = daq_ref_uniform16(seed, 0u, (uint64_t)idx);
+                    u1 = daq_ref_uniform16(seed, 1u, (uint64_t)idx);
                 }
                 vq[idx] = daq_ref_quantize_one(dY[idx], s_chan[c], mode, u0);
                 qg[idx] = daq_ref_quantize_one(dY[idx], *s_global, mode, u1);

@@ -87,8 +87,8 @@ def lib():
     global _lib
     if _lib is None:
         _lib = C.CDLL(build())
-        _lib.daq_ref_uniform24.restype = C.c_float
-        _lib.daq_ref_uniform24.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64]
+        _lib.daq_ref_uniform16.restype = C.c_float
+        _lib.daq_ref_uniform16.argtypes = [C.c_uint64, C.c_uint32, C.c_uint64]
         _lib.daq_ref_fmix32.restype = C.c_uint32
         _lib.daq_ref_fmix32.argtypes = [C.c_uint32]
         _lib.daq_ref_quantize_one.restype = C.c_int8
@@ -128,8 +128,8 @@ def fmix32(h: int) -> int:
     return int(lib().daq_ref_fmix32(h & 0xFFFFFFFF))
 
 
-def uniform24(seed: int, tensor: int, idx: int) -> float:
-    return float(lib().daq_ref_uniform24(seed, tensor, idx))
+def uniform16(seed: int, tensor: int, idx: int) -> float:
+    return float(lib().daq_ref_uniform16(seed, tensor, idx))
 
 
 def quantize_one(x: float, s: float, mode: int = ROUND_NEAREST, u: float = 0.0) -> int:

@@ -96,10 +96,12 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
 // device helpers
 // ---------------------------------------------------------------------------------------------
 // Stochastic rounding: a counter-based generator on 32-bit arithmetic.  fmix32 is the finalizer of MurmurHash3
-// (Appleby, public domain), a bijection of 32-bit words with full avalanche.  A launch derives one key per int8 copy
-// from the caller's 64-bit seed (round_keys, on the host); element i (its NCHW index, below 2^31) of copy t draws
-//     u = (fmix32(i ^ key_t) >> 8) * 2^-24,
-// a 24-bit uniform in [0,1).  Two multiplies per draw, and nothing is carried from one element to the next.
+// (Appleby, public domain), a bijection of 32-bit words with full avalanche.  A launch derives one key from the
+// caller's 64-bit seed (round_key, on the host); element i (its NCHW index, below 2^31) hashes once,
+//     h = fmix32(i ^ key),
+// and the two int8 copies take disjoint halves of the word as 16-bit uniforms: the per-channel copy (t = 0) U = h >> 16,
+// the per-tensor copy (t = 1) U = h & 0xFFFF, u = U * 2^-16.  A kernel that writes both copies of an element pays for
+// one hash (the calls below are pure, the compiler merges them); nothing is carried from one element to the next.
 __host__ __device__ __forceinline__ uint32_t fmix32(uint32_t h) {
     h ^= h >> 16;
     h *= 0x85EBCA6Bu;
@@ -108,30 +110,30 @@ __host__ __device__ __forceinline__ uint32_t fmix32(uint32_t h) {
     h ^= h >> 16;
     return h;
 }
-// key of copy t: fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9 * (t + 1))); both keys travel in one 64-bit kernel
-// argument, the per-channel copy's (t = 0) in the upper half
+// key = fmix32(seed_lo ^ fmix32(seed_hi ^ 0x9E3779B9)); it travels in the kernels' 64-bit seed argument
 inline uint64_t round_keys(uint64_t seed) {
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-    const uint32_t k0 = fmix32(lo ^ fmix32(hi ^ 0x9E3779B9u)), k1 = fmix32(lo ^ fmix32(hi ^ (0x9E3779B9u * 2u)));
-    return ((uint64_t)k0 << 32) | k1;
+    return (uint64_t)fmix32(lo ^ fmix32(hi ^ 0x9E3779B9u));
 }
-__device__ __forceinline__ float rng_u(uint64_t keys, uint32_t tensor, uint32_t idx) {
-    const uint32_t key = tensor == 0u ? (uint32_t)(keys >> 32) : (uint32_t)keys;
-    return (float)(fmix32(idx ^ key) >> 8) * 5.9604644775390625e-08f;
+__device__ __forceinline__ uint32_t rng_u(uint64_t keys, uint32_t tensor, uint32_t idx) {
+    const uint32_t h = fmix32(idx ^ (uint32_t)keys);
+    return tensor == 0u ? h >> 16 : h & 0xFFFFu;
 }
 
 // 127/s, or 0 when the scale is treated as zero (then every code is 0).
 __device__ __forceinline__ float inv_scale(float s) { return (s >= kTinyScale) ? 127.0f / s : 0.0f; }
 
-// Eq. "suq" in code space: round(clamp(x*inv, -127, 127)); u is the element's uniform under stochastic rounding.
+// Eq. "suq" in code space: round(clamp(x*inv, -127, 127)).  Stochastic rounding: floor(t) + [frac(t) > U * 2^-16] with
+// the element's 16-bit draw U, evaluated in integers: with c = ceil(t * 2^16) (exact: |t| <= 127) the bracket is
+// [c mod 2^16 > U] - a fraction of exactly 0 never rounds up, one above U * 2^-16 always - so the code is
+// (c + 65535 - U) >> 16 with an arithmetic shift.
 template <bool STOCH>
-__device__ __forceinline__ int quant_code(float x, float inv, float u) {
+__device__ __forceinline__ int quant_code(float x, float inv, uint32_t U) {
     float t = x * inv;
     t = fminf(fmaxf(t, -127.0f), 127.0f);
     if (STOCH) {
-        const float f = floorf(t);
-        const float frac = t - f;
-        return (int)(f + (frac > u ? 1.0f : 0.0f));
+        const int nc = (int)floorf(t * -65536.0f);   // -ceil(t * 2^16)
+        return (65535 - (int)U - nc) >> 16;
     }
     return (int)rintf(t);
 }
@@ -141,8 +143,8 @@ __device__ __forceinline__ int quant_code(float x, float inv, float u) {
 // and leaves that integer in two's complement in the low mantissa bits - one instruction instead of
 // round + convert + mask.
 template <bool STOCH>
-__device__ __forceinline__ uint32_t quant_bits(float x, float inv, float u) {
-    if (STOCH) return (uint32_t)quant_code<true>(x, inv, u);
+__device__ __forceinline__ uint32_t quant_bits(float x, float inv, uint32_t U) {
+    if (STOCH) return (uint32_t)quant_code<true>(x, inv, U);
     const float t = __builtin_amdgcn_fmed3f(x * inv, -127.0f, 127.0f);
     return __float_as_uint(t + 12582912.0f);
 }
@@ -386,7 +388,7 @@ __device__ __forceinline__ uint32_t quad_swap(uint32_t v) {
 // decision, then only rewrites the channels whose guess was wrong (and writes the padding).  A correct guess saves
 // the third sweep over dY for that channel; a wrong one costs nothing but the bytes written here.
 template <typename T, bool STOCH, bool WRITE_QG, bool COUNT, bool EARLY = false>
-__global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, int N, int C, int HW, int c_pitch,
+__global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g, int N, int C, int HW, int c_pitch,
                                                      FastDiv div_hw, QuantWs ws, const float* __restrict__ scale_ptr,
                                                      int8_t* __restrict__ qg, uint64_t seed,
                                                      const float* __restrict__ s_state, float* __restrict__ s_global,
@@ -488,13 +490,15 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
     const float inv = inv_scale(sg);
     // sigma of the wave's 16 channels.  Lanes without a pixel and channels past C hold x = 0, and
     // 0 > sigma is false for every sigma >= 0, so the comparison needs no validity mask.
+    // (both arrays are the same in every lane of the wave: moved to scalar registers, they cost no vector ones)
+    auto uniform = [](float v) { return __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v))); };
     float sig[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sig[i] = COUNT ? l_sigma[16 * wave + i] : 0.0f;
+    for (int i = 0; i < 16; ++i) sig[i] = COUNT ? uniform(l_sigma[16 * wave + i]) : 0.0f;
 
     float inv_c[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) inv_c[i] = EARLY ? l_inv[16 * wave + i] : 0.0f;
+    for (int i = 0; i < 16; ++i) inv_c[i] = EARLY ? uniform(l_inv[16 * wave + i]) : 0.0f;
 
     uint32_t cnt[16];   // wave-uniform counters
 #pragma unroll
@@ -510,8 +514,8 @@ __global__ __launch_bounds__(kBlock) void k_count_qg(const T* __restrict__ g, in
         for (int i = 0; i < 16; ++i) {
             if (COUNT) cnt[i] += (uint32_t)__popcll(__ballot(fabsf(x[i]) > sig[i]));
             const uint32_t idx = idx0 + (uint32_t)i * (uint32_t)HW;
-            if (WRITE_QG) b[i] = quant_bits<STOCH>(x[i], inv, STOCH ? rng_u(seed, 1u, idx) : 0.0f);
-            if (EARLY) vb[i] = quant_bits<STOCH>(x[i], inv_c[i], STOCH ? rng_u(seed, 0u, idx) : 0.0f);
+            if (WRITE_QG) b[i] = quant_bits<STOCH>(x[i], inv, STOCH ? rng_u(seed, 1u, idx) : 0u);
+            if (EARLY) vb[i] = quant_bits<STOCH>(x[i], inv_c[i], STOCH ? rng_u(seed, 0u, idx) : 0u);
         }
         if (EARLY) {
             // channel-major copy: the lane's pixel sits at the same offset of each of its 16 channel planes
@@ -820,7 +824,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_cnhw(const T* __restrict__ src,
         uint32_t bits[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_u(pa.seed, pa.tensor, eoff[u][i] / EB) : 0.0f);
+            bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_u(pa.seed, pa.tensor, eoff[u][i] / EB) : 0u);
         if (d < plane_dw) *reinterpret_cast<uint32_t*>(plane + 4 * (int64_t)d) = pack4(bits[0], bits[1], bits[2], bits[3]);
     }
 }
@@ -965,7 +969,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
     for (int u = 0; u < 4; ++u) {
         uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_u(pa.seed, pa.tensor, eoff[u] / EB + i) : 0.0f);
+        for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv, STOCH ? rng_u(pa.seed, pa.tensor, eoff[u] / EB + i) : 0u);
         if (live[u]) store_codes<V>(plane + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
         if (row_end[u])
             for (int k = 0; k < padw; ++k) plane[doff[u] + V + k] = 0;
@@ -976,7 +980,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_rows(const T* __restrict__ src,
         for (int u = 0; u < 4; ++u) {
             uint32_t bits[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv2, STOCH ? rng_u(pa.seed, pa.tensor2, eoff[u] / EB + i) : 0.0f);
+            for (int i = 0; i < V; ++i) bits[i] = quant_bits<STOCH>(x[u][i], inv2, STOCH ? rng_u(pa.seed, pa.tensor2, eoff[u] / EB + i) : 0u);
             if (live[u]) store_codes<V>(plane2 + doff[u], pack4(bits[0], bits[1], bits[2], bits[3]));
             if (row_end[u])
                 for (int k = 0; k < padw; ++k) plane2[doff[u] + V + k] = 0;
@@ -1116,7 +1120,7 @@ __global__ __launch_bounds__(TH) void k_chan_resident(const T* __restrict__ g, C
             const uint32_t idx = (n * (uint32_t)ra.C + (uint32_t)c) * (uint32_t)HW + px;   // NCHW index: keys stochastic rounding
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
-                l_img[pos] = (int8_t)quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0.0f);
+                l_img[pos] = (int8_t)quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0u);
                 const bool wrap = ++col == (uint32_t)L.W;   // a unit stays inside its image, but may run on into the next row
                 col = wrap ? 0u : col;
                 pos += wrap ? (uint32_t)(L.row_pitch - L.W) + 1u : 1u;
@@ -1181,7 +1185,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_w(const float* __restrict__ W, 
     const int g = co / cog, col = co % cog;
     const int ci = g * cig + cl;
     const float inv = inv_scale(*s_w);
-    const int8_t code = (int8_t)quant_code<false>(W[i], inv, 0.0f);
+    const int8_t code = (int8_t)quant_code<false>(W[i], inv, 0u);
     out[L.off_plain + i] = code;
     out[L.off_fwd + ((int64_t)tap * Cout + co) * L.cig_pitch + cl] = code;
     out[L.off_bwd + ((int64_t)tap * Cin + ci) * L.cog_pitch + col] = code;

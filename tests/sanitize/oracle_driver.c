@@ -20,7 +20,7 @@ int main(void) {
     /* quantizer pieces */
     for (int i = 0; i < 2000; ++i) {
         float x = frand() * 3.0f, s = fabsf(frand()) + 1e-3f;
-        sum += daq_ref_quantize_one(x, s, i & 1, daq_ref_uniform24((uint64_t)i * 77u, (uint32_t)(i & 1), (uint64_t)i));
+        sum += daq_ref_quantize_one(x, s, i & 1, daq_ref_uniform16((uint64_t)i * 77u, (uint32_t)(i & 1), (uint64_t)i));
         sum += daq_ref_dequantize_one((int8_t)(i % 255 - 127), s);
         sum += daq_ref_clip_value(i & 1, s, frand(), 1.0f + (float)(i % 3) * 0.25f, 0.8f);
         sum += daq_ref_classify((uint32_t)i, 2000.0, 0.3f);

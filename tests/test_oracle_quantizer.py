@@ -111,7 +111,7 @@ def test_stochastic_rounding_brackets_and_is_unbiased(ref):
     acc = np.zeros(len(xs))
     reps = 300
     for r in range(reps):
-        us = [ref.uniform24(1234 + r, 0, i) for i in range(len(xs))]
+        us = [ref.uniform16(1234 + r, 0, i) for i in range(len(xs))]
         q = _qvec(ref, xs, s, mode=1, us=us)
         assert np.all((q == np.floor(t)) | (q == np.floor(t) + 1))
         assert q.min() >= -127 and q.max() <= 127
@@ -125,21 +125,44 @@ def test_stochastic_rounding_brackets_and_is_unbiased(ref):
     assert ref.quantize_one(3.0, 127.0, 1, 0.0) == 3  # exact integers never move
 
 
-def test_uniform24_is_uniform_and_keyed(ref):
-    u = np.array([ref.uniform24(42, 0, i) for i in range(20000)])
+def test_stochastic_decision_is_taken_exactly(ref):
+    """floor(t) + [frac(t) > u] in exact arithmetic: fractions close to a 16-bit grid point, where an fp32 subtraction
+    t - floor(t) would round onto the grid, and random values against rational arithmetic."""
+    from fractions import Fraction
+
+    s = 127.0   # inv = 1: t = x
+    u = 65535 / 65536
+    x_hi = float(np.float32(-(2.0 ** -16 - 2.0 ** -40)))   # frac = 1 - 2^-16 + 2^-40 > u
+    x_lo = float(np.float32(-(2.0 ** -16 + 2.0 ** -40)))   # frac = 1 - 2^-16 - 2^-40 < u
+    assert ref.quantize_one(x_hi, s, 1, u) == 0 and ref.quantize_one(x_lo, s, 1, u) == -1
+    assert ref.quantize_one(float(np.float32(-2.0 ** -30)), s, 1, u) == 0          # frac = 1 - 2^-30 > u
+    assert ref.quantize_one(float(np.float32(2.0 ** -30)), s, 1, 0.0) == 1         # any positive fraction beats u = 0
+    assert ref.quantize_one(0.0, s, 1, 0.0) == 0 and ref.quantize_one(-0.0, s, 1, 0.0) == 0
+    rng = np.random.default_rng(77)
+    xs = np.concatenate([rng.uniform(-130, 130, 300), rng.uniform(-1, 1, 300) * 10.0 ** rng.uniform(-12, 0, 300)]).astype(np.float32)
+    us = rng.integers(0, 65536, len(xs))
+    for x, U in zip(xs, us):
+        t = Fraction(float(np.float32(min(max(float(x), -127.0), 127.0))))
+        k = math.floor(t)
+        want = k + (1 if t - k > Fraction(int(U), 65536) else 0)
+        assert ref.quantize_one(float(x), s, 1, int(U) / 65536) == want
+
+
+def test_uniform16_is_uniform_and_keyed(ref):
+    u = np.array([ref.uniform16(42, 0, i) for i in range(20000)])
     assert u.min() >= 0.0 and u.max() < 1.0
     assert abs(u.mean() - 0.5) < 0.01 and abs(u.var() - 1 / 12) < 0.005
     hist, _ = np.histogram(u, bins=16, range=(0, 1))
     assert hist.min() > 0.85 * 20000 / 16
-    assert np.all(u * 2 ** 24 == np.floor(u * 2 ** 24))  # 24-bit grid
-    v = np.array([ref.uniform24(42, 1, i) for i in range(2000)])
-    w = np.array([ref.uniform24(43, 0, i) for i in range(2000)])
+    assert np.all(u * 2 ** 16 == np.floor(u * 2 ** 16))  # 16-bit grid
+    v = np.array([ref.uniform16(42, 1, i) for i in range(2000)])
+    w = np.array([ref.uniform16(43, 0, i) for i in range(2000)])
     assert abs(np.corrcoef(u[:2000], v)[0, 1]) < 0.08 and abs(np.corrcoef(u[:2000], w)[0, 1]) < 0.08
-    assert np.all(v * 2 ** 24 == np.floor(v * 2 ** 24)) and v.min() >= 0.0 and v.max() < 1.0
+    assert np.all(v * 2 ** 16 == np.floor(v * 2 ** 16)) and v.min() >= 0.0 and v.max() < 1.0
     assert abs(v.mean() - 0.5) < 0.03 and abs(w.mean() - 0.5) < 0.03
     # neighbouring seeds (a training loop counts its steps) and seeds that differ in the upper word are unrelated streams
     for other in (43, 42 + 2 ** 32, 42 + 2 ** 63):
-        w2 = np.array([ref.uniform24(other, 0, i) for i in range(2000)])
+        w2 = np.array([ref.uniform16(other, 0, i) for i in range(2000)])
         assert abs(np.corrcoef(u[:2000], w2)[0, 1]) < 0.08
         assert abs(np.corrcoef(u[1:2001], w2)[0, 1]) < 0.08 and abs(np.corrcoef(u[:2000], w2[::-1])[0, 1]) < 0.08
     # lag-1 autocorrelation along the tensor
@@ -154,12 +177,14 @@ def test_the_mixer_is_the_published_murmur3_finalizer(ref):
     # a bijection: distinct words stay distinct (every position of a tensor gets its own draw)
     xs = np.arange(200000, dtype=np.uint64)
     assert len({ref.fmix32(int(x)) for x in xs[:50000]}) == 50000
-    # the uniform of element i is the top 24 bits of fmix32(i ^ key), with the key built from both halves of the seed
+    # one hash per element, fmix32(i ^ key) with the key built from both halves of the seed; the per-channel copy draws
+    # its upper 16 bits, the per-tensor copy its lower 16
     seed = 0x0123456789ABCDEF
-    for t in (0, 1):
-        key = ref.fmix32((seed & 0xFFFFFFFF) ^ ref.fmix32((seed >> 32) ^ ((0x9E3779B9 * (t + 1)) & 0xFFFFFFFF)))
-        for i in (0, 1, 77, 2 ** 31 - 1):
-            assert ref.uniform24(seed, t, i) == (ref.fmix32(i ^ key) >> 8) * 2.0 ** -24
+    key = ref.fmix32((seed & 0xFFFFFFFF) ^ ref.fmix32((seed >> 32) ^ 0x9E3779B9))
+    for i in (0, 1, 77, 2 ** 31 - 1):
+        h = ref.fmix32(i ^ key)
+        assert ref.uniform16(seed, 0, i) == (h >> 16) * 2.0 ** -16
+        assert ref.uniform16(seed, 1, i) == (h & 0xFFFF) * 2.0 ** -16
 
 
 # ----------------------------------------------------------------------------- statistics
@@ -339,7 +364,7 @@ def test_quantize_grad_stochastic_mode(ref):
     # spot-check one element against the documented counter: NCHW linear index, tensor id 0
     n, ch, h, w = 1, 2, 3, 4
     idx = ((n * 3 + ch) * 8 + h) * 8 + w
-    u = ref.uniform24(11, 0, idx)
+    u = ref.uniform16(11, 0, idx)
     assert a.vq[n, ch, h, w] == ref.quantize_one(float(g[n, ch, h, w]), float(a.s_chan[ch]), 1, u)
 
 
@@ -444,7 +469,7 @@ def test_schemes_in_stochastic_mode_and_scheme_zero(ref):
     assert d.max() == 1 and 0.05 < (d > 0).mean() < 0.6
     n, c, h, w = 2, 3, 4, 5
     idx = ((n * C + c) * g.shape[2] + h) * g.shape[3] + w
-    assert q.vq[n, c, h, w] == ref.quantize_one(float(g[n, c, h, w]), q.s_global, 1, ref.uniform24(5, 0, idx))
+    assert q.vq[n, c, h, w] == ref.quantize_one(float(g[n, c, h, w]), q.s_global, 1, ref.uniform16(5, 0, idx))
 
 
 def test_ablation_ordering_of_quantization_error(ref):
