@@ -52,11 +52,13 @@ def measured_traffic(config: int):
     return out
 
 
-def kernel_work(layer, d, name: str, dy_bytes: float, dx_bytes: float, qg_nhwc: bool):
+def kernel_work(layer, d, name: str, dy_bytes: float, dx_bytes: float, qg_nhwc: bool, early: bool = False):
     """(algorithmic HBM bytes, int8 operations) of one launch of kernel `name` on `layer`.
 
-    Quantizer sweeps: dY read once per sweep plus the int8 bytes the sweep writes.  Convolutions: int8 operands read
-    once, result written once; ops = 2 x true multiply-accumulates."""
+    Quantizer sweeps: dY read once per sweep plus the int8 bytes the sweep writes.  `early`: the counting sweep also wrote
+    the per-channel copy, and the packing launch after it only repairs the channels whose class was guessed wrong (no
+    bytes are attributed to it).  Convolutions: int8 operands read once, result written once; ops = 2 x true
+    multiply-accumulates."""
     import numpy as np
 
     E_Y = float(np.prod(d.y_shape))
@@ -66,7 +68,9 @@ def kernel_work(layer, d, name: str, dy_bytes: float, dx_bytes: float, qg_nhwc: 
     if name == "stats":
         return dy_bytes * E_Y, 0.0
     if name == "count_qg":
-        return (dy_bytes + (1.0 if qg_nhwc else 0.0)) * E_Y, 0.0
+        return (dy_bytes + (1.0 if qg_nhwc else 0.0) + (1.0 if early else 0.0)) * E_Y, 0.0
+    if name == "pack_vq" and early:
+        return 0.0, 0.0
     if name in ("pack_vq", "pack_qg", "chan_resident", "global_copy"):
         return (dy_bytes + 1.0) * E_Y, 0.0
     if name.startswith("conv_bwd_data"):
@@ -305,7 +309,11 @@ def run_network(args, dev) -> int:
         row = {"layer": L.name, "shape": f"N{L.N} {L.Cin}->{L.Cout} {L.Hin}x{L.Win} k{L.kH} s{L.stride} g{L.groups}"}
         for k, (us, n) in per[li].items():
             dx_b = 2.0 if (net[li].bf16_ok and k.startswith("conv_bwd_data")) else 4.0
-            b, o = kernel_work(L, d, k, dy_b, dx_b, qg_nhwc)
+            # the library's rule for the early per-channel copy (gradients of 16 Mi elements and more, NHWC global copy,
+            # rows of an even number of pixels); a layer without a channel-resident launch took the sweeps
+            early = (args.scheme == "daq" and qg_nhwc and "chan_resident" not in per[li] and L.Wo % 2 == 0 and
+                     (args.schedule == "early_copy" or (args.schedule == "auto" and float(np.prod(d.y_shape)) >= 16 * 2 ** 20)))
+            b, o = kernel_work(L, d, k, dy_b, dx_b, qg_nhwc, early)
             e = kernels.setdefault(k, {"us": 0.0, "launches": 0.0, "bytes": 0.0, "ops": 0.0})
             e["us"] += us * n
             e["launches"] += n

@@ -782,8 +782,16 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     return g;
 }
 
-daq_status launch(Geometry& g, hipStream_t st, const char* name) {
+// Profile labels, one per kernel form (they are different instantiations with different bounds): the tile kernel with
+// a run-time tap list at unit stride, by parity classes at stride 2, on 128-row tiles, and the two constant-tap forms.
+struct HaloNames { const char *dyn, *s2, *r128, *k1, *k9; };
+constexpr HaloNames kBwdNames{"conv_bwd_data_halo", "conv_bwd_data_halo_s2", "conv_bwd_data_halo_r128", "conv_bwd_data_halo_1x1",
+                              "conv_bwd_data_halo_3x3"};
+constexpr HaloNames kFwdNames{"conv_fwd_halo", "conv_fwd_halo", "conv_fwd_halo_r128", "conv_fwd_halo_1x1", "conv_fwd_halo_3x3"};
+
+daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
     const HaloArgs& a = g.a;
+    const char* name = g.rows == 128 ? names.r128 : a.stride == 2 ? names.s2 : names.dyn;
     const int64_t ptiles = blocks_per_row_tile(a);
     const int64_t blocks = ptiles * ceil_div(a.Crow, g.rows) + a.tail.blocks;
     if (blocks >= ((int64_t)1 << 31)) return DAQ_ERR_UNSUPPORTED;
@@ -807,14 +815,14 @@ daq_status launch(Geometry& g, hipStream_t st, const char* name) {
         auto kern = k_conv_halo<1, true, 1, 4, 1>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
             return DAQ_ERR_HIP;
-        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
+        DAQ_LAUNCH(names.k1, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
         return DAQ_OK;
     }
     if (a.stride == 1 && a.ph_taps[0] == 9 && a.double_buffer && g.rows == 64) {
         auto kern = k_conv_halo<1, true, 1, 4, 9>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
             return DAQ_ERR_HIP;
-        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
+        DAQ_LAUNCH(names.k9, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
         return DAQ_OK;
     }
     if (g.rows == 128) {
@@ -921,7 +929,7 @@ daq_status conv_bwd_data_halo(const daq_conv_desc& d, const int8_t* qg, const fl
     g.a.s_a = s_w; g.a.s_b = s_g;
     g.a.out = dX; g.a.acc_out = acc;
     g.a.nt = !bf16 && (int64_t)d.N * d.Cin * d.Hin * d.Win * 4 >= kStreamBytes;
-    return launch(g, st, "conv_bwd_data_halo");
+    return launch(g, st, kBwdNames);
 }
 
 bool fwd_halo_supported(const daq_conv_desc& d) { return plan_fwd(d).ok; }
@@ -940,7 +948,7 @@ daq_status conv_fwd_halo(const daq_conv_desc& d, const int8_t* qx, const int8_t*
     g.a.s_a = s_x; g.a.s_b = s_w;
     g.a.out = Y; g.a.acc_out = acc;
     g.a.nt = (int64_t)d.N * d.Cout * daq_out_h(&d) * daq_out_w(&d) * 4 >= kStreamBytes;
-    return launch(g, st, "conv_fwd_halo");
+    return launch(g, st, kFwdNames);
 }
 
 }  // namespace daq

@@ -1012,7 +1012,7 @@ struct ResArgs {
 // A load unit is four consecutive elements of one plane (VEC4: planes of a multiple of four elements in a 16-byte
 // aligned fp32 tensor) or one element; a thread holds NU units, a workgroup has TH threads.
 template <typename T, bool STOCH, bool VEC4, int NU, int TH>
-__global__ __launch_bounds__(TH) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
+__global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
                                                       ResArgs ra, QuantWs ws, ClipArgs ca) {
     extern __shared__ __align__(16) int8_t l_img[];   // the channel's plane as it will sit in memory
     __shared__ float l_mx[TH / kWave];
