@@ -275,7 +275,8 @@ def run_network(args, dev) -> int:
             torch.cuda.synchronize()
         print(json.dumps({"metric": "INT8 conv-backward TOPS incl. grad quantization", "value": round(ops_per_step / sec / 1e12, 3),
                           "unit": "TOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(1e3 * sec, 5),
-                          "config": {"workload": f"config{config}", "rounding": args.rounding, "streams": args.streams}}))
+                          "config": {"workload": f"config{config}" + (f": {layers[0].name}" if nL == 1 else f": all {nL} conv layers"),
+                                     "rounding": args.rounding, "streams": args.streams}}))
         return 0
     n_stat = max(100, args.steps) if sec * max(100, args.steps) < 30.0 else args.steps
     med_ms, min_ms = step_statistics(step, n_stat)
