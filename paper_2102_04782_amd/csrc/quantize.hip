@@ -62,6 +62,7 @@ QuantWs carve_quant_ws(void* base, int C, int N, int HW) {
     const int want = std::max(1, kCountGrid / cb);
     const int titers = (int)ceil_div(w.tiles, want);
     w.cgroups = (int)ceil_div(w.tiles, titers);
+    if (w.cgroups >= 2 * kXcd) w.cgroups = (int)round_up(w.cgroups, kXcd);   // whole rounds over the XCDs (see k_count_qg)
     // byte offsets first; pointers only when there is a buffer (a size query passes none)
     int64_t off = 0;
     const int64_t o_head = off;
@@ -408,12 +409,25 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     // (measured: a gain where the kernel only counts or writes one copy, a loss in the form that writes both copies)
     const bool dword16 = EB == 2 && !EARLY && (HW & 1) == 0 && ((uintptr_t)g & 3u) == 0;
 
+    // Which tiles the workgroup walks.  A tile's 256-byte pieces of its channel planes start wherever the plane starts, so
+    // neighbouring tiles share cache lines; with the workgroups of a channel block dealt round-robin over the tiles,
+    // neighbours ran on different XCDs and both L2s fetched the shared lines (1.4 x the tensor on 14 x 14 planes).  With
+    // a multiple of eight workgroups per block, workgroup p runs on XCD p % 8: each XCD takes one contiguous eighth of
+    // the tiles, and its workgroups p / 8 walk that range side by side.
+    int t_first = p, t_step = ws.cgroups, t_end = ws.tiles;
+    if ((ws.cgroups & (kXcd - 1)) == 0) {   // uniform
+        const int per_xcd = (ws.tiles + kXcd - 1) / kXcd, xcd = p % kXcd;
+        t_first = xcd * per_xcd + p / kXcd;
+        t_step = ws.cgroups / kXcd;
+        t_end = min(ws.tiles, (xcd + 1) * per_xcd);
+    }
+
     float x[16];
     uint32_t n_cur = 0, px_cur = 0;
     bool v_cur = false;
     auto fetch = [&](int tile, float (&dst)[16], uint32_t& n, uint32_t& px, bool& valid) {
         const uint32_t P = (uint32_t)tile * kWave + lane;
-        valid = tile < ws.tiles && P < M;
+        valid = tile < t_end && P < M;
         const uint32_t Pc = valid ? P : 0u;
         n = fdiv(Pc, div_hw);
         px = Pc - n * (uint32_t)HW;
@@ -437,7 +451,7 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
             for (int i = 0; i < 16; ++i) dst[i] = buf_ld<T>(rs, c0 + i < C ? off : kOobOff, (uint32_t)i * chan_bytes);
         }
     };
-    fetch(p, x, n_cur, px_cur, v_cur);
+    fetch(t_first, x, n_cur, px_cur, v_cur);
 
     // scale of the global copy: max_c |g|max from the statistics pass, or an explicit per-tensor scale
     float sg = 0.0f;
@@ -503,11 +517,11 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     uint32_t cnt[16];   // wave-uniform counters
 #pragma unroll
     for (int i = 0; i < 16; ++i) cnt[i] = 0;
-    for (int tile = p; tile < ws.tiles; tile += ws.cgroups) {
+    for (int tile = t_first; tile < t_end; tile += t_step) {
         float nx[16];
         uint32_t n_nxt, px_nxt;
         bool v_nxt;
-        fetch(tile + ws.cgroups, nx, n_nxt, px_nxt, v_nxt);
+        fetch(tile + t_step, nx, n_nxt, px_nxt, v_nxt);
         uint32_t b[16], vb[16];
         const uint32_t idx0 = (n_cur * (uint32_t)C + (uint32_t)c0) * (uint32_t)HW + px_cur;   // the lane's 16 elements are one plane apart
 #pragma unroll
