@@ -1033,7 +1033,11 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
     __shared__ double l_s1[TH / kWave], l_s2[TH / kWave];
     __shared__ uint32_t l_cnt[TH / kWave];
     __shared__ float l_bc[4];   // |g|max, mean, sigma, clip value
-    const int c = blockIdx.x;
+    // workgroup b runs on XCD b % 8: an XCD takes a contiguous eighth of the channels, whose planes are neighbours in
+    // every image and share cache lines where a plane is not a whole number of them
+    const int per_xcd = (ra.C + kXcd - 1) / kXcd;
+    const int c = ((int)blockIdx.x % kXcd) * per_xcd + (int)blockIdx.x / kXcd;
+    if ((int)blockIdx.x / kXcd >= per_xcd || c >= ra.C) return;   // uniform: padding of the grid
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int HW = ra.HW, M = ra.N * HW;
     constexpr uint32_t EB = sizeof(T);
@@ -1464,7 +1468,7 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
         auto kern = k_chan_resident<T, S, V, NUV, THV>;                                                              \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return DAQ_ERR_HIP;                                                                                      \
-        DAQ_LAUNCH("chan_resident", st, hipLaunchKernelGGL(kern, dim3((unsigned)C), dim3(THV), lds, st, dY, cnhw_view(Lv), vq, ra, ws, ca)); \
+        DAQ_LAUNCH("chan_resident", st, hipLaunchKernelGGL(kern, dim3((unsigned)round_up(C, kXcd)), dim3(THV), lds, st, dY, cnhw_view(Lv), vq, ra, ws, ca)); \
     }
 #define DAQ_RES_SIZE(S, V) { if (res_small) DAQ_RES_LAUNCH(S, V, 8, 512) else DAQ_RES_LAUNCH(S, V, 16, 1024) }
         if constexpr (sizeof(T) == 4) {
