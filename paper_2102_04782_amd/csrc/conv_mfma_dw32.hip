@@ -46,6 +46,8 @@ struct Dw32Args {
     int pb;               // LDS pitch of an activation row in bytes (a multiple of 4 with pb/4 odd)
     int b_units;          // 16-byte units of an activation row that are staged per chunk
     int nchunks, splits;
+    int bands_m, bands_n;  // > 0: fewer than eight K splits, the tile grid is cut into bands_m x bands_n rectangles (dw_block_map)
+    int band_m, band_n;    // tiles per rectangle along co and ci
     int tiles_n, tiles_m;
     int32_t* part;        // splits > 1: [tile][split][wave tile][slot = tap*16 + reg][lane]
     const float* s_x;
@@ -56,6 +58,37 @@ struct Dw32Args {
 
 __device__ __forceinline__ int alignbyte(int hi, int lo, int sh) {
     return (int)__builtin_amdgcn_alignbyte((unsigned)hi, (unsigned)lo, (unsigned)sh);
+}
+
+// Block -> (K split, output tile).  Workgroup b runs on XCD b % 8, and what an XCD's workgroups read together is what
+// its L2 has to fetch.  With eight or more splits an XCD takes whole splits: every tile of the split, i.e. one K slice
+// of every operand row - each byte of the operands enters exactly one L2.  With 1, 2 or 4 splits the eight XCDs share a
+// split among 8, 4 or 2 of them, and each takes a rectangle of the tile grid (bands_m x bands_n rectangles per split,
+// chosen on the host to minimise rows of G plus rows of X per rectangle) instead of tiles dealt round-robin, which
+// made every XCD read nearly all rows of one operand.  Returns false for the padding of the grid.
+__device__ __forceinline__ bool dw_block_map(const Dw32Args& p, int& split, int& tile) {
+    const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
+    const int x = b % kXcd, q = b / kXcd;
+    if (p.bands_m > 0) {
+        split = x % p.splits;
+        const int rect = x / p.splits;
+        const int rm = rect / p.bands_n, rn = rect % p.bands_n;
+        const int lm = q / p.band_n, ln = q % p.band_n;
+        const int tm = rm * p.band_m + lm, tn = rn * p.band_n + ln;
+        if (lm >= p.band_m || tm >= p.tiles_m || tn >= p.tiles_n) return false;
+        tile = tm * p.tiles_n + tn;
+        return true;
+    }
+    const int full = (p.splits / kXcd) * kXcd;
+    if (q < (full / kXcd) * tiles) {
+        split = (q / tiles) * kXcd + x;
+        tile = q % tiles;
+    } else {
+        const int rb = b - full * tiles;
+        split = full + rb % (p.splits - full);
+        tile = rb / (p.splits - full);
+    }
+    return true;
 }
 
 // WQ4 = row_pitch mod 4.  WM x WN x WK = 4 or 8 waves: tiles along co, along ci, split of the K steps.
@@ -77,21 +110,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
     const int B_BYTES = BN * p.pb;
     const int STAGE = A_BYTES + B_BYTES;
 
-    // workgroup i runs on XCD i % 8: all tiles of one K split share an L2
     int split, tile;
-    {
-        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
-        const int full = (p.splits / kXcd) * kXcd;
-        const int x = b % kXcd, q = b / kXcd;
-        if (q < (full / kXcd) * tiles) {
-            split = (q / tiles) * kXcd + x;
-            tile = q % tiles;
-        } else {
-            const int rb = b - full * tiles;
-            split = full + rb % (p.splits - full);
-            tile = rb / (p.splits - full);
-        }
-    }
+    if (!dw_block_map(p, split, tile)) return;   // uniform
     const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
     const int co0 = tm * BM, ci0 = tn * BN;
     const int per = p.nchunks / p.splits, rem = p.nchunks % p.splits;
@@ -366,19 +386,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
     const int l32 = lane & 31, lh = lane >> 5;
 
     int split, tile;
-    {
-        const int b = blockIdx.x, tiles = p.tiles_n * p.tiles_m;
-        const int full = (p.splits / kXcd) * kXcd;
-        const int x = b % kXcd, q = b / kXcd;
-        if (q < (full / kXcd) * tiles) {
-            split = (q / tiles) * kXcd + x;
-            tile = q % tiles;
-        } else {
-            const int rb = b - full * tiles;
-            split = full + rb % (p.splits - full);
-            tile = rb / (p.splits - full);
-        }
-    }
+    if (!dw_block_map(p, split, tile)) return;   // uniform
     const int tn = tile % p.tiles_n, tm = tile / p.tiles_n;
     const int co0 = tm * BM, ci0 = tn * BN;
     const int per = p.nchunks / p.splits, rem = p.nchunks % p.splits;
@@ -518,9 +526,30 @@ struct Plan32 {
     bool ok;
     bool k11;             // 1 x 1 filter: the plain GEMM kernel
     int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units;
+    int bands_m, bands_n, band_m, band_n;   // rectangles of the tile grid per K split when there are 1, 2 or 4 splits (else 0)
+    int64_t blocks;       // workgroups of the launch
     size_t lds_bytes;
     int64_t part_slots;   // int32 entries of one split's partial tiles
 };
+
+// Rectangles per split for 1, 2 or 4 splits (8, 4 or 2 XCDs share a split): the cut of the tile grid that makes an
+// XCD touch the fewest operand rows, rows of the two operands weighted by their tile heights.
+void choose_bands(Plan32& pl, int bm, int bn) {
+    pl.bands_m = pl.bands_n = pl.band_m = pl.band_n = 0;
+    pl.blocks = (int64_t)pl.tiles_m * pl.tiles_n * pl.splits;
+    if (pl.splits != 1 && pl.splits != 2 && pl.splits != 4) return;
+    const int rects = kXcd / pl.splits;
+    int64_t best = -1;
+    for (int rm = 1; rm <= rects; rm *= 2) {
+        const int rn = rects / rm;
+        if (rm > pl.tiles_m || rn > pl.tiles_n) continue;
+        const int64_t hm = ceil_div(pl.tiles_m, rm), hn = ceil_div(pl.tiles_n, rn);
+        const int64_t rows = hm * bm + hn * bn;
+        if (best < 0 || rows < best) { best = rows; pl.bands_m = rm; pl.bands_n = rn; pl.band_m = (int)hm; pl.band_n = (int)hn; }
+    }
+    if (best < 0) { pl.bands_m = pl.bands_n = 0; return; }
+    pl.blocks = (int64_t)kXcd * pl.band_m * pl.band_n;
+}
 
 Plan32 make_plan32(const daq_conv_desc& d) {
     Plan32 pl{};
@@ -550,6 +579,7 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         const size_t stage = (size_t)64 * (pl.wm + pl.wn) * kPA;
         pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // one-round combine
         pl.part_slots = tiles * pl.wm * pl.wn * 64 * kWave;
+        choose_bands(pl, 64 * pl.wm, 64 * pl.wn);
         pl.ok = true;
         return pl;
     }
@@ -575,13 +605,14 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * kT * 16 * kWave * 4 / rounds : 0);
     if (pl.lds_bytes > 150 * 1024) return pl;
     pl.part_slots = tiles * pl.wm * pl.wn * kT * 16 * kWave;
+    choose_bands(pl, bm, bn);
     pl.ok = true;
     return pl;
 }
 
 template <int WM, int WN, int WK, int PF>
 daq_status launch32(const Plan32& pl, const Dw32Args& a, int wq4, hipStream_t st) {
-    const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+    const dim3 grid((unsigned)pl.blocks);
 #define DAQ_DW32_CASE(Q)                                                                                          \
     if (wq4 == Q) {                                                                                               \
         auto kern = k_dw32<Q, WM, WN, WK, PF>;                                                                        \
@@ -627,6 +658,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.splits = pl.splits;
     a.tiles_n = pl.tiles_n;
     a.tiles_m = pl.tiles_m;
+    a.bands_m = pl.bands_m; a.bands_n = pl.bands_n; a.band_m = pl.band_m; a.band_n = pl.band_n;
     a.part = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
     a.s_x = s_x;
     a.s_chan = s_chan;
@@ -635,7 +667,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.bf16 = bf16 ? 1 : 0;
     const int wq4 = Lx.row_pitch & 3;
     if (pl.k11) {
-        const dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits));
+        const dim3 grid((unsigned)pl.blocks);
         if (pl.wk == 1) {
             auto kern = k_dw11<2, 2, 1, 1>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
