@@ -81,8 +81,10 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // then unrolled, the ring of filter tiles has one slot per tap (slot = tap, so each tile is requested TAPS - 1
 // steps before its use), the tap tables are read once, and the pixel fragments of the next tap are read from LDS
 // before the multiplies of the current one: with a single wave per SIMD nothing else hides those latencies.
-template <int WR, bool DB, int ST, int WAVES, int TAPS = 0>
-__global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(HaloArgs p) {
+// NX = 32-row blocks of a wave that can hold result rows: 1 for results of at most 32 channels (the data gradient of a
+// network's first layer), whose second block would only multiply zeros - dynamic-tap form on 64-row tiles only.
+template <int WR, bool DB, int ST, int WAVES, int TAPS = 0, int NX = 2>
+__global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = WAVES / WR;
     constexpr int SPT = 16 * WAVES;   // window slots one pass of the workgroup stages (four lanes per slot)
@@ -166,16 +168,13 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
     // ---- filter fragments: tile (x, sub) of this wave is 1 KiB at ((row block)*2 + sub)*1024, lane*16 inside ----
     uint32_t aoff[2][2];
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < NX; ++x)
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             const int rb = (row0 + wr * 64) / 32 + x;
             aoff[x][sub] = rb < p.RB ? (uint32_t)((rb * 2 + sub) * 1024 + lane * 16) : kOob;
         }
     v4i ra[kRingA][2][2];   // [ring slot][x][sub]
-    // A wave whose second 32-row block lies wholly past the last row (results with a handful of channels: the data
-    // gradient of a network's first layer) neither fetches nor multiplies it - dynamic-tap form only.
-    const int nx = (row0 + wr * 64 + 32 < p.Crow) ? 2 : 1;   // uniform
     int f_j = 0, f_kc = 0, f_s = 0;
     auto fetch_a = [&](int slot) {
         const bool live = f_s < NS;
@@ -183,11 +182,9 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         // a dead prefetch is sent out of range through the VECTOR offset, the one the hardware checks against the extent
         const uint32_t base = live ? (uint32_t)(((f_kc * p.T + id) * p.RB) * 2048) : 0u;
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
-            if (x < nx) {
+        for (int x = 0; x < NX; ++x)
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
-            }
+            for (int sub = 0; sub < 2; ++sub) ra[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
         ++f_s;
         if (++f_j == taps) { f_j = 0; ++f_kc; }
     };
@@ -222,7 +219,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             const bool live = kc < nkc;
             const uint32_t base = live ? (uint32_t)((kc * p.RB) * 2048) : 0u;
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub) ra1[slot][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
             const bool kok = live && kc * kKc + 16 * sc < p.cp;
@@ -258,7 +255,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
 #pragma unroll
                     for (int y = 0; y < BF; ++y) b[y] = *reinterpret_cast<const v4i*>(H + bbyte[y] + 32 * sub);
 #pragma unroll
-                    for (int x = 0; x < 2; ++x)
+                    for (int x = 0; x < NX; ++x)
 #pragma unroll
                         for (int y = 0; y < BF; ++y)
                             acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra1[u][x][sub], b[y], acc[x][y], 0, 0, 0);
@@ -285,7 +282,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             const bool live = kc < nkc;
             const uint32_t base = live ? (uint32_t)(((kc * p.T + t_id[t]) * p.RB) * 2048) : 0u;
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub) rt[t][x][sub] = buffer_load16(rs_w, live ? aoff[x][sub] : kOob, base);
         };
@@ -314,7 +311,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
 #pragma unroll
                 for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-                    for (int x = 0; x < 2; ++x)
+                    for (int x = 0; x < NX; ++x)
 #pragma unroll
                         for (int y = 0; y < BF; ++y)
                             acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(rt[t][x][sub], bq[t & 1][sub][y], acc[x][y], 0, 0, 0);
@@ -351,12 +348,10 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
                         for (int y = 0; y < BF; ++y)
                             b[y] = *reinterpret_cast<const v4i*>(H + (bslot[y] + ts) * kPitch + 32 * sub);
     #pragma unroll
-                        for (int x = 0; x < 2; ++x)
-                            if (x < nx) {
+                        for (int x = 0; x < NX; ++x)
     #pragma unroll
-                                for (int y = 0; y < BF; ++y)
-                                    acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
-                            }
+                            for (int y = 0; y < BF; ++y)
+                                acc[x][y] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ra[u][x][sub], b[y], acc[x][y], 0, 0, 0);
                     }
                     if (j + 1 == taps) {
                         if (DB && kci + 1 < nkc) {
@@ -398,7 +393,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             o[y] = p.out + (((int64_t)n * p.Crow + rowbase) * HWd + h * p.Wd + w);
         }
 #pragma unroll
-        for (int x = 0; x < 2; ++x)
+        for (int x = 0; x < NX; ++x)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
@@ -431,7 +426,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
                 // lane the pair of row dr+1, each as one aligned dword: half the store instructions, twice the bytes each.
                 const bool odd = l32 & 1;
 #pragma unroll
-                for (int x = 0; x < 2; ++x)
+                for (int x = 0; x < NX; ++x)
 #pragma unroll
                     for (int r = 0; r < 16; r += 2) {
                         const uint32_t v0 = bf16_bits((float)acc[x][y][r] * scale), v1 = bf16_bits((float)acc[x][y][r + 1] * scale);
@@ -446,7 +441,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             const bool w1 = w + 1 < p.Wd, h1 = h + 1 < p.Hd;
             const bool pairs = (p.Wd & 1) == 0;   // even rows: (value, 0) and (0, 0) go out as aligned 4-byte stores
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
@@ -472,18 +467,18 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             // written below together with the zeros of the 2 x 2 block
         } else if (full_rows && p.nt) {
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     __builtin_nontemporal_store((float)acc[x][y][r] * scale, &o[(32 * x + 8 * (r >> 2) + (r & 3)) * HWd]);
         } else if (full_rows) {
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) o[(32 * x + 8 * (r >> 2) + (r & 3)) * HWd] = (float)acc[x][y][r] * scale;
         } else {
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
@@ -493,7 +488,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
         if (p.acc_out) {
             int32_t* ao = p.acc_out + pix;
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
@@ -505,7 +500,7 @@ __global__ __launch_bounds__(64 * WAVES, TAPS == 1 ? 2 : 1) void k_conv_halo(Hal
             const bool w1 = w + 1 < p.Wd, h1 = h + 1 < p.Hd;
             const bool pairs = (p.Wd & 1) == 0;   // even rows: (value, 0) and (0, 0) go out as aligned 8-byte stores
 #pragma unroll
-            for (int x = 0; x < 2; ++x)
+            for (int x = 0; x < NX; ++x)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int dr = 32 * x + 8 * (r >> 2) + (r & 3);
@@ -830,6 +825,17 @@ daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
         a8.units = (int)ceil_div((int64_t)g.a.NI * g.a.SH * g.a.SW, 128);
         const HaloArgs& a = a8;
         if (a.double_buffer) DAQ_HALO_CASE(2, true, 8) else DAQ_HALO_CASE(2, false, 8)
+    } else if (a.Crow <= 32) {
+#define DAQ_HALO_NARROW(DBV)                                                                                         \
+    {                                                                                                                \
+        auto kern = a.stride == 2 ? k_conv_halo<1, DBV, 2, 4, 0, 1> : k_conv_halo<1, DBV, 1, 4, 0, 1>;               \
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) !=  \
+            hipSuccess)                                                                                              \
+            return DAQ_ERR_HIP;                                                                                      \
+        DAQ_LAUNCH(name, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));                         \
+    }
+        if (a.double_buffer) DAQ_HALO_NARROW(true) else DAQ_HALO_NARROW(false)
+#undef DAQ_HALO_NARROW
     } else {
         if (a.double_buffer) DAQ_HALO_CASE(1, true, 4) else DAQ_HALO_CASE(1, false, 4)
     }
