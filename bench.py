@@ -2,15 +2,19 @@
 """Benchmark of the INT8 conv backward hot path on one MI355X.
 
 One step = the backward pass (Algorithm 1) of EVERY conv layer of a network, last layer first: per layer
-daq_quantize_grad (statistics, discriminator, clip values, per-channel and global int8 copies of dY, stochastic
-rounding as the paper prescribes for gradients) + daq_conv_bwd_int8 (filter gradient and data gradient).  Every layer
-has its own tensors, as in a real backward pass: fp32 dY, the int8 activation / filter and their scales saved by the
-forward entry point, the clip state, the results.  All of it is resident in HBM before the timed region starts.  The
-default workload is ResNet-50 at batch 64 (53 conv layers, 2.8 GB of fp32 dY per step, far beyond the 256 MB Infinity
-Cache, so every sweep starts cold).  Prints ONE JSON line.
+daq_quantize_grad_ex (statistics, discriminator, clip values, per-channel and global int8 copies of dY, stochastic
+rounding as the paper prescribes for gradients), then the data gradient (daq_conv_bwd_data_int8) and, on a second
+stream, the filter gradient (daq_conv_bwd_filter_int8): once dY is quantized the two share no data, and nothing
+downstream in a backward pass waits for dW.  (--streams 1: every launch on one stream, both gradients through
+daq_conv_bwd_int8; that step is timed as well and reported beside the headline.)  Every layer has its own tensors, as
+in a real backward pass: fp32 dY, the int8 activation / filter and their scales saved by the forward entry point, the
+clip state, the results.  All of it is resident in HBM before the timed region starts.  The default workload is
+ResNet-50 at batch 64 (53 conv layers, 2.8 GB of fp32 dY per step, far beyond the 256 MB Infinity Cache, so every
+sweep starts cold).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--rounding stochastic|nearest]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--rounding stochastic|nearest] [--streams 2|1]
     python bench.py --config 2              # a single layer; its buffers are rotated through enough copies to stay cold
+    python bench.py --config 3 --layer 0    # one layer of a config
     python bench.py --sweep --config 4      # every distinct layer shape on its own, one line with per-layer times
     python bench.py --sweep --forward       # the forward entry point over the same layers
     python bench.py --ceilings              # what the GPU delivers: int8 MFMA loop, streaming read / write / copy
