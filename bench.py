@@ -617,7 +617,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="workload of BASELINE.json (1-5); 4 = ResNet-50 at batch 64")
+    ap.add_argument("--config", type=int, default=4, help="workload 1-5: 1 tiny layer, 2 and 3 single ResNet-50 layers, 4 = ResNet-50 at batch 64, 5 = MobileNetV2 at batch 128")
     ap.add_argument("--layer", type=int, default=-1, help="restrict the workload to this layer of the config (0-based)")
     ap.add_argument("--rounding", default="stochastic", choices=("stochastic", "nearest"),
                     help="rounding of the gradient quantizer in the reported step (the paper prescribes stochastic rounding "
