@@ -380,6 +380,10 @@ CONV_LAYERS = [
     wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
     wl.Layer("c3x3_wide", 1, 16, 8, 130, 16, 3, 3, 1, 1),         # rows too long for the LDS window: global-fragment form
     wl.Layer("c3x3_wide_huge", 1, 768, 2, 130, 1024, 3, 3, 1, 1),  # the same with enough tiles for its LDS-staged sibling
+    # filter gradients with many output tiles and fewer than eight K splits: each XCD takes a rectangle of the tile grid
+    wl.Layer("c1x1_rect_1", 2, 512, 5, 5, 520, 1, 1, 1, 0),       # 9 x 8 tiles of 64 x 64 (ragged), one split, eight rectangles
+    wl.Layer("c1x1_rect_2", 8, 320, 12, 12, 200, 1, 1, 1, 0),     # 4 x 5 tiles, a short flat axis: two splits, four rectangles each
+    wl.Layer("c3x3_rect_1", 1, 232, 6, 6, 200, 3, 3, 1, 1),       # 7 x 8 tiles of 32 x 32 (ragged), one split
 ]
 
 
