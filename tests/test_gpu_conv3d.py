@@ -26,6 +26,10 @@ LAYERS = {
     "depthwise3d": ((1, 10, 5, 7, 7, 10, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 10), 0),
     "stem_3x7x7": ((1, 3, 8, 20, 20, 16, 3, 7, 7, 1, 2, 2, 1, 3, 3, 1, 1, 1, 1), 0),
     "ragged": ((3, 5, 4, 7, 5, 19, 2, 3, 2, 1, 1, 1, 0, 1, 0, 1, 1, 1, 1), 0),
+    "grouped16": ((1, 32, 3, 6, 5, 48, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 2), 0),      # whole 16-channel records per group: dot4 forms
+    "wide_rows": ((1, 20, 3, 5, 23, 33, 3, 3, 3, 1, 1, 1, 1, 1, 1, 1, 1, 1, 1), 0),     # rows that are not a multiple of four positions
+    "h_strided": ((2, 6, 6, 9, 10, 10, 3, 3, 3, 2, 2, 1, 1, 1, 1, 1, 1, 1, 1), 0),      # strides in depth and height, unit stride along w
+    "big_pad": ((1, 4, 4, 5, 6, 5, 3, 3, 3, 1, 1, 1, 2, 2, 2, 1, 1, 1, 1), 0),          # padding wider than the filter's reach
 }
 
 
@@ -62,7 +66,24 @@ def test_layer_against_the_oracle(name):
     assert np.array_equal(_unpack(daq.layout_qx_nhwc(cx), f.qx_nhwc, rd.x_shape), rf.qX), "q(X), channels innermost"
     assert np.array_equal(_unpack(daq.layout_qx_cnhw(cx), f.qx_cnhw, rd.x_shape), rf.qX), "q(X), channel-major"
     if kind == 0:
-        assert np.array_equal(f.qw.cpu().numpy()[:rf.qW.size], rf.qW.ravel()) and not f.qw.cpu().numpy()[rf.qW.size:].any()
+        # q(W) three times: plain [Cout][Cin/g][taps], then [tap][Cout][Cin/g up to 16] and [tap][Cin][Cout/g up to 16],
+        # each part rounded up to 256 bytes, every byte that holds no code zero
+        qw = f.qw.cpu().numpy()
+        taps, cig, cog = rd.kD * rd.kH * rd.kW, rd.Cin // rd.groups, rd.Cout // rd.groups
+        cigp, cogp = -(-cig // 16) * 16, -(-cog // 16) * 16
+        up = lambda v: -(-v // 256) * 256
+        codes = rf.qW.reshape(rd.Cout, cig, taps)
+        fwd = np.zeros((taps, rd.Cout, cigp), np.int8)
+        fwd[:, :, :cig] = codes.transpose(2, 0, 1)
+        bwd = np.zeros((taps, rd.Cin, cogp), np.int8)
+        for co in range(rd.Cout):
+            gq = co // cog
+            bwd[:, gq * cig:(gq + 1) * cig, co % cog] = codes[co].T
+        want = np.zeros(up(codes.size) + up(fwd.size) + up(bwd.size), np.int8)
+        want[:codes.size] = codes.ravel()
+        want[up(codes.size):up(codes.size) + fwd.size] = fwd.ravel()
+        want[up(codes.size) + up(fwd.size):up(codes.size) + up(fwd.size) + bwd.size] = bwd.ravel()
+        assert qw.size == want.size and np.array_equal(qw, want), "q(W): plain codes and the two channel-contraction copies"
     assert np.array_equal(f.acc.cpu().numpy(), rf.acc), "forward accumulators"
     _near(f.Y.cpu().numpy(), rf.Y, "Y")
 
