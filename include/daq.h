@@ -410,9 +410,12 @@ daq_status daq_conv_bwd_data_int8_chan(const daq_conv_desc* desc, const int8_t* 
  * stride and no padding in height and width (time-only filters, pointwise layers: depth becomes the row axis, a whole
  * frame the column axis), or a volume of depth one - and every 3-D entry point forwards to its 2-D counterpart, the
  * matrix-core kernels included; q(W) is then packed as daq_layout_qw(cx).  Return value 0: any other layer; the
- * carriers are 1 x 1 problems that see (N, Cin, Din*Hin, Win) and (N, Cout, Do*Ho, Wo), q(W) is the plain
- * [Cout][Cin/groups][kD][kH][kW] array of codes, and the products run on direct integer kernels (exact; far from
- * the matrix-core rate).  -1: invalid descriptor or sizes beyond 2^31 elements.
+ * carriers are 1 x 1 problems that see (N, Cin, Din*Hin, Win) and (N, Cout, Do*Ho, Wo), and the products run on
+ * direct integer kernels (4-wide int8 dot products where the shapes allow; exact; far from the matrix-core rate).
+ * q(W) then holds the codes three times, each part rounded up to 256 bytes and zero where it holds no code: the
+ * plain [Cout][Cin/groups][kD][kH][kW] array, [tap][Cout][Cin/groups rounded up to 16] and
+ * [tap][Cin][Cout/groups rounded up to 16], tap = (kd*kH + kh)*kW + kw.  -1: invalid descriptor or sizes beyond
+ * 2^31 elements.
  *
  * Entry points: arguments, alignment, error codes and results as for the 2-D entry point of the same name, with
  * workspaces of daq_conv3d_workspace_bytes(op, desc) and q(W) buffers of daq_conv3d_qw_bytes(desc).
