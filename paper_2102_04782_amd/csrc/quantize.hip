@@ -1025,7 +1025,9 @@ struct ResArgs {
 
 // A load unit is four consecutive elements of one plane (VEC4: planes of a multiple of four elements in a 16-byte
 // aligned fp32 tensor) or one element; a thread holds NU units, a workgroup has TH threads.
-template <typename T, bool STOCH, bool VEC4, int NU, int TH>
+// FLAT (with VEC4): the plane has no padding between rows or images (1 x 1 layers), so element m of the channel sits at
+// byte lead + m and a unit's four codes are one aligned dword of the plane: they go straight to memory, no LDS image.
+template <typename T, bool STOCH, bool VEC4, int NU, int TH, bool FLAT = false>
 __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
                                                       ResArgs ra, QuantWs ws, ClipArgs ca) {
     extern __shared__ __align__(16) int8_t l_img[];   // the channel's plane as it will sit in memory
@@ -1044,6 +1046,7 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
     constexpr int PER = VEC4 ? 4 : 1;
     const __amdgpu_buffer_rsrc_t rs = f32_rsrc(g, (uint32_t)M * (uint32_t)ra.C * EB);
     const int units = (M + PER - 1) / PER;
+    const uint32_t skip = (uint32_t)(ra.C - 1) * (uint32_t)HW, first = (uint32_t)c * (uint32_t)HW;   // the other channels' planes of an image
 
     // ---- S1: the channel comes in, all loads of the thread in flight at once ----
     float x[NU][PER];
@@ -1053,7 +1056,7 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
         const bool ok = q < units;
         const uint32_t m = ok ? (uint32_t)q * PER : 0u;
         const uint32_t n = fdiv(m, ra.div_hw);
-        const uint32_t off = ok ? ((n * (uint32_t)ra.C + (uint32_t)c) * (uint32_t)HW + (m - n * (uint32_t)HW)) * EB : kOobOff;
+        const uint32_t off = ok ? (m + n * skip + first) * EB : kOobOff;   // NCHW index (n*C + c)*HW + (m - n*HW)
         if constexpr (VEC4) {
             const v4u raw = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0);
 #pragma unroll
@@ -1071,14 +1074,15 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
             mx = fmaxf(mx, fabsf(x[u][e]));
             const double a = x[u][e];
             s1 += a;
-            s2 += a * a;
+            s2 = __builtin_fma(a, a, s2);   // the square of a widened fp32 is exact in fp64: the same sum as s2 + a * a, one instruction
         }
     mx = wave_max(mx);
     s1 = wave_sum(s1);
     s2 = wave_sum(s2);
     if (lane == 0) { l_mx[wave] = mx; l_s1[wave] = s1; l_s2[wave] = s2; }
     // the padding of the plane image, while the partials settle
-    for (int i = tid; i < (int)(L.plane_pitch >> 4); i += TH) reinterpret_cast<uint4*>(l_img)[i] = make_uint4(0u, 0u, 0u, 0u);
+    if constexpr (!FLAT)
+        for (int i = tid; i < (int)(L.plane_pitch >> 4); i += TH) reinterpret_cast<uint4*>(l_img)[i] = make_uint4(0u, 0u, 0u, 0u);
     __syncthreads();
     if (tid == 0) {
         for (int w = 1; w < TH / kWave; ++w) { mx = fmaxf(mx, l_mx[w]); s1 += l_s1[w]; s2 += l_s2[w]; }
@@ -1094,12 +1098,11 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
     const float gm = l_bc[0], sigma = l_bc[2];
 
     // ---- S2: tail mass (a zero never exceeds sigma, so the units past the channel need no mask) ----
-    uint32_t cnt = 0;
+    uint32_t cnt = 0;   // of the whole wave: a scalar counter
 #pragma unroll
     for (int u = 0; u < NU; ++u)
 #pragma unroll
-        for (int e = 0; e < PER; ++e) cnt += fabsf(x[u][e]) > sigma ? 1u : 0u;
-    cnt = wave_sum_u32(cnt);
+        for (int e = 0; e < PER; ++e) cnt += (uint32_t)__popcll(__ballot(fabsf(x[u][e]) > sigma));
     if (lane == 0) l_cnt[wave] = cnt;
     __syncthreads();
     if (tid == 0) {
@@ -1123,6 +1126,29 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
     __syncthreads();
     const float inv = inv_scale(l_bc[3]);
 
+    if constexpr (FLAT) {
+        // ---- S5, plane without padding: a unit's four codes are dword q of the plane's payload ----
+        uint32_t* plane32 = reinterpret_cast<uint32_t*>(vq + (int64_t)c * L.chan_pitch);   // chan_pitch is a multiple of 256
+        uint32_t* pay = plane32 + (L.lead >> 2);
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const int q = u * TH + tid;
+            if (q < units) {
+                const uint32_t m = (uint32_t)q * 4u;
+                const uint32_t n = fdiv(m, ra.div_hw);
+                const uint32_t idx = m + n * skip + first;   // NCHW index: keys stochastic rounding
+                uint32_t b[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) b[e] = quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0u);
+                pay[q] = pack4(b[0], b[1], b[2], b[3]);
+            }
+        }
+        // the zeros in front of and behind the payload
+        const int head = (int)(L.lead >> 2), tail = head + units, total = (int)(L.plane_pitch >> 2);
+        for (int i = tid; i < head; i += TH) plane32[i] = 0u;
+        for (int i = tail + tid; i < total; i += TH) plane32[i] = 0u;
+        return;
+    }
     // ---- S5: the per-channel codes go to their places in the plane image ----
     const uint32_t slot = (uint32_t)(L.img_rows * L.row_pitch);
 #pragma unroll
@@ -1135,7 +1161,7 @@ __global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T
             uint32_t r = fdiv(px, ra.div_w);
             uint32_t col = px - r * (uint32_t)L.W;
             uint32_t pos = (uint32_t)L.lead + n * slot + r * (uint32_t)L.row_pitch + col;
-            const uint32_t idx = (n * (uint32_t)ra.C + (uint32_t)c) * (uint32_t)HW + px;   // NCHW index: keys stochastic rounding
+            const uint32_t idx = m + n * skip + first;   // NCHW index: keys stochastic rounding
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
                 l_img[pos] = (int8_t)quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0u);
@@ -1462,9 +1488,14 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
         ws.slabs = 1;   // one |g|max partial per channel
         const ResArgs ra{div_hw, make_fastdiv((uint32_t)Wo), N, C, HW, k, A, lambda, keys};
         const ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
-        const size_t lds = (size_t)Lv.plane_pitch;
+        // planes without padding between rows and images hold element m at byte lead + m
+        const bool res_flat = res_v4 && Lv.row_pitch == Lv.W && Lv.img_rows == Lv.H && (Lv.lead & 3) == 0 && (Lv.plane_pitch & 3) == 0 &&
+                              Lv.lead + (int64_t)N * HW <= Lv.plane_pitch;
+        const size_t lds = res_flat ? 0 : (size_t)Lv.plane_pitch;
 #define DAQ_RES_LAUNCH(S, V, NUV, THV)                                                                               \
-    {                                                                                                                \
+    if (V && res_flat) {                                                                                             \
+        DAQ_LAUNCH("chan_resident", st, hipLaunchKernelGGL((k_chan_resident<T, S, V, NUV, THV, V>), dim3((unsigned)round_up(C, kXcd)), dim3(THV), 0, st, dY, cnhw_view(Lv), vq, ra, ws, ca)); \
+    } else {                                                                                                         \
         auto kern = k_chan_resident<T, S, V, NUV, THV>;                                                              \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) \
             return DAQ_ERR_HIP;                                                                                      \
