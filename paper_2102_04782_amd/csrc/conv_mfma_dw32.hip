@@ -118,6 +118,16 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
     const int c_begin = split * per + min(split, rem);
     const int c_end = c_begin + per + (split < rem ? 1 : 0);
 
+    // a complete tile is de-quantized here: its scales are requested now, long before they are needed
+    float sx = 0.0f, sc_row[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (p.splits == 1) {   // uniform
+        sx = *p.s_x / 127.0f;
+        if constexpr (WK > 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sc_row[i] = p.s_chan[min(co0 + wave + WAVES * i, p.Cout - 1)];   // the rows this wave stores
+        }
+    }
+
     // ---- staging assignment ----
     // gradient: unit u = tid + 256*i -> row u / 16, 16-byte column u % 16
     uint32_t a_src[A_PER_T];
@@ -294,12 +304,12 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
             }
         }
         __syncthreads();
-        const float sx = *p.s_x / 127.0f;
         const int ncol = min(32, p.Cin - ci0) * kT;   // valid ints of a row
-        for (int row = wave; row < 32; row += WAVES) {
-            const int co = co0 + row;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = wave + WAVES * i, co = co0 + row;
             if (co >= p.Cout) break;
-            const float sc = sx * (p.s_chan[co] / 127.0f);
+            const float sc = sx * (sc_row[i] / 127.0f);
             const int64_t off = ((int64_t)co * p.Cin + ci0) * kT;
             for (int j = lane; j < ncol; j += kWave) {
                 const int v = red[row * ROWW + j];
@@ -318,7 +328,6 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
             for (int r = 0; r < 16; ++r) dst[(t * 16 + r) * kWave] = acc[t][r];
         return;
     }
-    const float sx = *p.s_x / 127.0f;
     const int ci = ci0 + wn * 32 + l32;
     if (ci >= p.Cin) return;
 #pragma unroll
@@ -371,13 +380,17 @@ __global__ __launch_bounds__(256) void k_dw_reduce(DwTail t) {
 // A wave owns 64 (co) x 64 (ci): four 32 x 32 tiles, so every fragment it reads feeds two multiplies.
 // Same ring, K-split and wave-combine scheme as above.
 // ---------------------------------------------------------------------------------------------
-template <int WM, int WN, int WK, int PF>
+template <int WM, int WN, int WK, int PF, int CH>
 __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
     constexpr int WAVES = WM * WN * WK, NT = 64 * WAVES;
     static_assert(WAVES == 4 || WAVES == 8, "four or eight waves");
     constexpr int BM = 64 * WM, BN = 64 * WN;
-    constexpr int UNITS = (BM + BN) * (kKC / 16) / NT;   // 16-byte units of the two tiles per thread
-    constexpr int STAGE = (BM + BN) * kPA;
+    constexpr int KCS = CH * kKC;                           // K bytes of a stage: CH chunks between two barriers
+    constexpr int PAS = KCS + 16;                           // LDS row pitch of a stage
+    constexpr int UPR = KCS / 16;                           // 16-byte units per staged row
+    constexpr int UNITS = (BM + BN) * UPR / NT;             // 16-byte units of the two tiles per thread
+    constexpr int STAGE = (BM + BN) * PAS;
+    static_assert(NT % UPR == 0, "a thread's units all sit in the same 16-byte column of their rows");
     extern __shared__ __align__(16) int8_t lds[];
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -394,30 +407,45 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
     const int c_end = c_begin + per + (split < rem ? 1 : 0);
     const int c_last = max(c_end - 1, 0);
 
-    // unit u = tid + NT*i -> row u / 16 of the stacked (gradient, activation) tile, 16-byte column u % 16
+    // a complete tile is de-quantized here: its scales are requested now, long before they are needed
+    float sx = 0.0f, sc_own[WK > 1 ? 8 : 1];
+    if (WK > 1 && p.splits == 1) {   // uniform
+        sx = *p.s_x;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int q = wk * 8 + e, r = q % 16;
+            const int co = co0 + wm * 64 + 32 * (q / 32) + 8 * (r >> 2) + 4 * lh + (r & 3);
+            sc_own[e] = p.s_chan[co < p.Cout ? co : 0];
+        }
+    }
+
+    // unit u = tid + NT*i -> row u / UPR of the stacked (gradient, activation) tile, 16-byte column u % UPR of the stage;
+    // the column - and with it the chunk of the stage the unit belongs to - is the same for all units of a thread
+    const int c16 = tid % UPR, sub = c16 / (kKC / 16);
     const int8_t* u_src[UNITS];
     int u_dst[UNITS];
 #pragma unroll
     for (int i = 0; i < UNITS; ++i) {
-        const int u = tid + NT * i;
-        const int row = u >> 4, c16 = u & 15;
+        const int row = (tid + NT * i) / UPR;
         if (row < BM) {   // rows past Cout / Cin recompute row 0 and are never stored
             const int co = co0 + row;
-            u_src[i] = p.g + (int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * c16;
+            u_src[i] = p.g + (int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * (c16 % (kKC / 16));
         } else {
             const int ci = ci0 + row - BM;
-            u_src[i] = p.x + (int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * c16;
+            u_src[i] = p.x + (int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * (c16 % (kKC / 16));
         }
-        u_dst[i] = row * kPA + 16 * c16;
+        u_dst[i] = row * PAS + 16 * c16;
     }
+    // Every call issues the same loads (past the end the last chunk is fetched again, which the caches absorb, and
+    // never multiplied): only then can the compiler count the loads in flight and wait for exactly the oldest set.
     v4i ring[PF][UNITS];
-    auto load_chunk = [&](int chunk, int set) {
-        const int64_t k0 = (int64_t)min(chunk, c_last) * kKC;
+    auto load_stage = [&](int chunk, int set) {   // chunk: the first of the stage
+        const int64_t k0 = (int64_t)min(chunk + sub, c_last) * kKC;
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) ring[set][i] = *reinterpret_cast<const v4i*>(u_src[i] + k0);
         __builtin_amdgcn_sched_barrier(0);   // keep the sets in program order
     };
-    auto store_chunk = [&](int buf, int set) {
+    auto store_stage = [&](int buf, int set) {
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) *reinterpret_cast<v4i*>(lds + buf * STAGE + u_dst[i]) = ring[set][i];
     };
@@ -430,42 +458,49 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
 
-    load_chunk(c_begin, 0);
-    store_chunk(0, 0);
+    load_stage(c_begin, 0);
+    store_stage(0, 0);
 #pragma unroll
-    for (int i = 1; i <= PF; ++i) load_chunk(c_begin + i, i % PF);
+    for (int i = 1; i <= PF; ++i) load_stage(c_begin + i * CH, i % PF);
     __syncthreads();
 
-    const int arow = (wm * 64 + l32) * kPA + 16 * lh;
-    const int brow = (BM + wn * 64 + l32) * kPA + 16 * lh;
-    for (int base = c_begin; base < c_end; base += PF) {
+    const int arow = (wm * 64 + l32) * PAS + 16 * lh;
+    const int brow = (BM + wn * 64 + l32) * PAS + 16 * lh;
+    int buf = 0;
+    for (int base = c_begin; base < c_end; base += PF * CH) {
 #pragma unroll
       for (int u = 0; u < PF; ++u) {
-        const int chunk = base + u;
+        const int chunk = base + u * CH;
         if (chunk >= c_end) break;   // uniform
-        const int buf = (chunk - c_begin) & 1;
         const int8_t* A = lds + buf * STAGE + arow;
         const int8_t* B = lds + buf * STAGE + brow;
         constexpr int KS = (kKC / 32) / WK;
-        v4i fa[KS][2], fb[KS][2];
+        v4i fa[CH][KS][2], fb[CH][KS][2];
 #pragma unroll
-        for (int i = 0; i < KS; ++i) {
-            const int ks = wk + i * WK;
+        for (int j = 0; j < CH; ++j)
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                fa[i][t] = *reinterpret_cast<const v4i*>(A + t * 32 * kPA + 32 * ks);
-                fb[i][t] = *reinterpret_cast<const v4i*>(B + t * 32 * kPA + 32 * ks);
+            for (int i = 0; i < KS; ++i) {
+                const int ks = wk + i * WK;
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    fa[j][i][t] = *reinterpret_cast<const v4i*>(A + t * 32 * PAS + j * kKC + 32 * ks);
+                    fb[j][i][t] = *reinterpret_cast<const v4i*>(B + t * 32 * PAS + j * kKC + 32 * ks);
+                }
             }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (j > 0 && chunk + j >= c_end) break;   // uniform: the stage's later chunks lie past this split's share
+#pragma unroll
+            for (int i = 0; i < KS; ++i)
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+#pragma unroll
+                    for (int b = 0; b < 2; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[j][i][a], fb[j][i][b], acc[a][b], 0, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < KS; ++i)
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i][a], fb[i][b], acc[a][b], 0, 0, 0);
-        store_chunk(buf ^ 1, (u + 1) % PF);
-        load_chunk(chunk + 1 + PF, (u + 1) % PF);
+        store_stage(buf ^ 1, (u + 1) % PF);
+        load_stage(chunk + (1 + PF) * CH, (u + 1) % PF);
+        buf ^= 1;
         __syncthreads();
       }
     }
@@ -502,7 +537,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
         }
     }
     int32_t* dst = p.part + (((int64_t)tile * p.splits + split) * (WM * WN) + wm * WN + wn) * SLOTS * kWave + lane;
-    const float sx = *p.s_x / 127.0f;
+    if (WK == 1 && p.splits == 1) sx = *p.s_x;
+    sx = sx / 127.0f;
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
         if (WK > 1 && q / 8 != wk) continue;   // uniform: not this wave's slot
@@ -515,7 +551,8 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
             const int ci = ci0 + wn * 64 + 32 * ((q / 16) % 2) + l32;
             if (co < p.Cout && ci < p.Cin) {
                 const int64_t off = (int64_t)co * p.Cin + ci;   // 32 lanes = 32 consecutive ci: 128-byte runs
-                store_result(p.dW, off, (float)v * (sx * (p.s_chan[co] / 127.0f)), p.bf16);
+                const float sc = WK > 1 ? sc_own[q % 8] : p.s_chan[co];
+                store_result(p.dW, off, (float)v * (sx * (sc / 127.0f)), p.bf16);
                 if (p.acc_out) p.acc_out[off] = v;
             }
         }
@@ -525,7 +562,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
 struct Plan32 {
     bool ok;
     bool k11;             // 1 x 1 filter: the plain GEMM kernel
-    int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units;
+    int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units, ch;
     int bands_m, bands_n, band_m, band_n;   // rectangles of the tile grid per K split when there are 1, 2 or 4 splits (else 0)
     int64_t blocks;       // workgroups of the launch
     size_t lds_bytes;
@@ -576,7 +613,11 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         int64_t s = ceil_div(256, tiles);
         s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
         pl.splits = (int)std::max<int64_t>(1, s);
-        const size_t stage = (size_t)64 * (pl.wm + pl.wn) * kPA;
+        // One chunk per LDS stage.  (Two chunks per barrier were measured on the late ResNet-50 layers: the K loop of a
+        // workgroup takes as long either way - 13 chunks of 32 KiB in 7 us on every CU at once, about 14 TB/s out of the L2s
+        // chip-wide, which is what bounds these 64 x 64 tiles - and the first stage arrives later.)
+        pl.ch = 1;
+        const size_t stage = (size_t)64 * (pl.wm + pl.wn) * (pl.ch * kKC + 16);
         pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // one-round combine
         pl.part_slots = tiles * pl.wm * pl.wn * 64 * kWave;
         choose_bands(pl, 64 * pl.wm, 64 * pl.wn);
@@ -669,12 +710,12 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     if (pl.k11) {
         const dim3 grid((unsigned)pl.blocks);
         if (pl.wk == 1) {
-            auto kern = k_dw11<2, 2, 1, 1>;
+            auto kern = k_dw11<2, 2, 1, 1, 1>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));
         } else {
-            auto kern = k_dw11<1, 1, 8, 3>;
+            auto kern = k_dw11<1, 1, 8, 3, 1>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));

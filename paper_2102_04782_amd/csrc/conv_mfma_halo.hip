@@ -131,6 +131,8 @@ __global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_
 
     const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
+    // the de-quantization factor is requested here, not in the epilogue, where its latency would show
+    const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
 
     // ---- window staging: unit i of a thread is chunk (tid & 3) of slot (tid >> 2) + SPT*i ----
     const int sc = tid & 3;
@@ -369,7 +371,6 @@ __global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_
     }
 
     // epilogue: register r of tile (x, y) is row 32x + 8*(r/4) + 4*lh + r%4, destination pixel q = wp*PXW + 32y + l32
-    const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
     const int rowbase = row0 + wr * 64 + 4 * lh;
     const int HWd = p.Hd * p.Wd;
     const bool full_rows = row0 + ROWS <= p.Crow;

@@ -401,7 +401,14 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int p = blockIdx.x % ws.cgroups;
     const int cb = blockIdx.x / ws.cgroups;
-    const int c0 = cb * 64 + 16 * wave;
+    // At most 32 channels (a network's first blocks): the tensor has one or two groups of 16 channels and two or three of
+    // the four waves would idle.  The waves take four (or two) different pixel tiles instead, and since an NHWC record
+    // is then 16 (or 32) bytes, a lane's codes are a whole record (or half of one): stored directly, no transposition
+    // through LDS, no barrier in the loop.
+    const int narrow = (WRITE_QG && C <= 32 && c_pitch == (C <= 16 ? 16 : 32)) ? (C <= 16 ? 1 : 2) : 0;   // uniform: groups of 16 channels
+    const int sub = narrow ? wave / narrow : 0, nsub = narrow ? 4 / narrow : 1;   // the wave's pixel tile among the workgroup's
+    const int c0 = narrow ? 16 * (wave % narrow) : cb * 64 + 16 * wave;
+    const int wg_tiles = (ws.tiles + nsub - 1) / nsub;
     const uint32_t M = (uint32_t)N * (uint32_t)HW;
     constexpr uint32_t EB = sizeof(T);   // bytes of a source element
     const __amdgpu_buffer_rsrc_t rs = f32_rsrc(g, (uint32_t)M * (uint32_t)C * EB);
@@ -414,19 +421,19 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     // neighbours ran on different XCDs and both L2s fetched the shared lines (1.4 x the tensor on 14 x 14 planes).  With
     // a multiple of eight workgroups per block, workgroup p runs on XCD p % 8: each XCD takes one contiguous eighth of
     // the tiles, and its workgroups p / 8 walk that range side by side.
-    int t_first = p, t_step = ws.cgroups, t_end = ws.tiles;
+    int t_first = p, t_step = ws.cgroups, t_end = wg_tiles;
     if ((ws.cgroups & (kXcd - 1)) == 0) {   // uniform
-        const int per_xcd = (ws.tiles + kXcd - 1) / kXcd, xcd = p % kXcd;
+        const int per_xcd = (wg_tiles + kXcd - 1) / kXcd, xcd = p % kXcd;
         t_first = xcd * per_xcd + p / kXcd;
         t_step = ws.cgroups / kXcd;
-        t_end = min(ws.tiles, (xcd + 1) * per_xcd);
+        t_end = min(wg_tiles, (xcd + 1) * per_xcd);
     }
 
     float x[16];
     uint32_t n_cur = 0, px_cur = 0;
     bool v_cur = false;
     auto fetch = [&](int tile, float (&dst)[16], uint32_t& n, uint32_t& px, bool& valid) {
-        const uint32_t P = (uint32_t)tile * kWave + lane;
+        const uint32_t P = (uint32_t)(nsub * tile + sub) * kWave + lane;
         valid = tile < t_end && P < M;
         const uint32_t Pc = valid ? P : 0u;
         n = fdiv(Pc, div_hw);
@@ -508,11 +515,11 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     auto uniform = [](float v) { return __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v))); };
     float sig[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) sig[i] = COUNT ? uniform(l_sigma[16 * wave + i]) : 0.0f;
+    for (int i = 0; i < 16; ++i) sig[i] = COUNT ? uniform(l_sigma[c0 - cb * 64 + i]) : 0.0f;
 
     float inv_c[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) inv_c[i] = EARLY ? uniform(l_inv[16 * wave + i]) : 0.0f;
+    for (int i = 0; i < 16; ++i) inv_c[i] = EARLY ? uniform(l_inv[c0 - cb * 64 + i]) : 0.0f;
 
     uint32_t cnt[16];   // wave-uniform counters
 #pragma unroll
@@ -574,7 +581,12 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
                     if (c0 + i < C) dst[(int64_t)i * ev.chan_pitch] = (int8_t)vb[i];
             }
         }
-        if (WRITE_QG) {
+        if (WRITE_QG && narrow) {
+            const uint4 w = make_uint4(pack4(b[0], b[1], b[2], b[3]), pack4(b[4], b[5], b[6], b[7]),
+                                       pack4(b[8], b[9], b[10], b[11]), pack4(b[12], b[13], b[14], b[15]));
+            const uint32_t P = (uint32_t)(nsub * tile + sub) * kWave + lane;
+            if (v_cur) *reinterpret_cast<uint4*>(qg + (int64_t)P * c_pitch + c0) = w;   // bytes of channels past C are codes of 0.0f: zeros
+        } else if (WRITE_QG) {
             // A lane holds 16 channel bytes of ONE pixel, so a direct store would put 16 bytes into each of 64 different
             // lines.  The 64-pixel x 64-channel tile goes through LDS instead (80-byte pitch: conflict free both ways)
             // and leaves as whole 64-byte runs: four adjacent lanes write the 64 channel bytes of one pixel.
@@ -598,7 +610,18 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
 #pragma unroll
         for (int i = 0; i < 16; ++i) mine = (lane == i) ? cnt[i] : mine;
         const bool mine_ok = lane < 16 && c0 + lane < C;
-        if (mine_ok) ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = mine;
+        if (narrow) {   // uniform: waves counted the same channels on different tiles
+            uint32_t* l_c = reinterpret_cast<uint32_t*>(l_tile);
+            if (lane < 16) l_c[16 * wave + lane] = mine;
+            __syncthreads();
+            if (sub == 0 && mine_ok) {
+                uint32_t all = 0;
+                for (int w = wave; w < 4; w += narrow) all += l_c[16 * w + lane];
+                ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = all;
+            }
+        } else if (mine_ok) {
+            ws.part_cnt[(int64_t)(c0 + lane) * ws.cgroups + p] = mine;
+        }
         if (ws.scheme == DAQ_SCHEME_MCS) {   // uniform: one population; its count is the sum over all counting waves
             const uint32_t all = wave_sum_u32(mine_ok ? mine : 0u);
             if (lane == 0) ws.layer_cnt[blockIdx.x * (kBlock / kWave) + wave] = all;
@@ -1028,7 +1051,7 @@ struct ResArgs {
 // FLAT (with VEC4): the plane has no padding between rows or images (1 x 1 layers), so element m of the channel sits at
 // byte lead + m and a unit's four codes are one aligned dword of the plane: they go straight to memory, no LDS image.
 template <typename T, bool STOCH, bool VEC4, int NU, int TH, bool FLAT = false>
-__global__ __launch_bounds__(TH, TH == 512 ? 8 : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
+__global__ __launch_bounds__(TH, NU <= 8 ? 8 : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
                                                       ResArgs ra, QuantWs ws, ClipArgs ca) {
     extern __shared__ __align__(16) int8_t l_img[];   // the channel's plane as it will sit in memory
     __shared__ float l_mx[TH / kWave];
@@ -1474,11 +1497,11 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
 
     // Channels that fit in LDS: one read of dY serves statistics, count, decision and the per-channel copy
     // (k_chan_resident); the global copy follows in the counting kernel's copy-only form.
-    // a workgroup of 512 threads x 8 load units or 1024 x 16 holds the channel; a unit is four elements where planes are a
+    // a workgroup of 512 threads x 8 or 16 load units, or 1024 x 16, holds the channel; a unit is four elements where planes are a
     // multiple of four elements long in a 16-byte aligned fp32 tensor, else one element
     const bool res_v4 = sizeof(T) == 4 && HW % 4 == 0 && ((uintptr_t)dY & 15u) == 0;
     const int64_t res_units = ceil_div((int64_t)N * HW, res_v4 ? 4 : 1);
-    const bool res_small = res_units <= 8 * 512;
+    const bool res_small = res_units <= 8 * 512, res_mid = res_units <= 16 * 512;
     const bool resident_ok = scheme == DAQ_SCHEME_DAQ && qg_nhwc && res_units <= 16 * 1024 && Lv.plane_pitch <= kResidentMaxLds &&
                              (Lv.plane_pitch & 15) == 0 && (Lv.chan_pitch & 15) == 0;
     // (The 1024-thread form runs one workgroup per CU, whose load, count and packing phases follow each other with nothing
@@ -1501,7 +1524,7 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
             return DAQ_ERR_HIP;                                                                                      \
         DAQ_LAUNCH("chan_resident", st, hipLaunchKernelGGL(kern, dim3((unsigned)round_up(C, kXcd)), dim3(THV), lds, st, dY, cnhw_view(Lv), vq, ra, ws, ca)); \
     }
-#define DAQ_RES_SIZE(S, V) { if (res_small) DAQ_RES_LAUNCH(S, V, 8, 512) else DAQ_RES_LAUNCH(S, V, 16, 1024) }
+#define DAQ_RES_SIZE(S, V) { if (res_small) DAQ_RES_LAUNCH(S, V, 8, 512) else if (res_mid) DAQ_RES_LAUNCH(S, V, 16, 512) else DAQ_RES_LAUNCH(S, V, 16, 1024) }
         if constexpr (sizeof(T) == 4) {
             if (stoch) { if (res_v4) DAQ_RES_SIZE(true, true) else DAQ_RES_SIZE(true, false) }
             else { if (res_v4) DAQ_RES_SIZE(false, true) else DAQ_RES_SIZE(false, false) }

@@ -101,6 +101,8 @@ ODD_LAYERS = [
     wl.Layer("w14", 3, 8, 14, 14, 20, 3, 3, 1, 1),             # rows of 14: two codes per store
     wl.Layer("w14_1x1", 4, 16, 14, 14, 70, 1, 1, 1, 0),        # no padding rows or columns at all
     wl.Layer("long_m", 40, 4, 56, 56, 4, 3, 3, 1, 1),          # workgroups loop over several chunks / tiles
+    wl.Layer("c24_long", 6, 8, 41, 39, 24, 1, 1, 1, 0),        # two groups of 16 channels: waves pair up on pixel tiles, ragged last tile
+    wl.Layer("c32", 3, 8, 17, 19, 32, 1, 1, 1, 0),             # two full groups
 ]
 
 
