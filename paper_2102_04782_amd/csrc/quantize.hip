@@ -401,13 +401,14 @@ __global__ __launch_bounds__(kBlock, 4) void k_count_qg(const T* __restrict__ g,
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int p = blockIdx.x % ws.cgroups;
     const int cb = blockIdx.x / ws.cgroups;
-    // At most 32 channels (a network's first blocks): the tensor has one or two groups of 16 channels and two or three of
-    // the four waves would idle.  The waves take four (or two) different pixel tiles instead, and since an NHWC record
-    // is then 16 (or 32) bytes, a lane's codes are a whole record (or half of one): stored directly, no transposition
-    // through LDS, no barrier in the loop.
-    const int narrow = (WRITE_QG && C <= 32 && c_pitch == (C <= 16 ? 16 : 32)) ? (C <= 16 ? 1 : 2) : 0;   // uniform: groups of 16 channels
+    // A last block of at most 32 channels (thin tensors; channel counts like 96 or 144) has one or two groups of 16 channels,
+    // and two or three of the four waves would idle.  Its waves take four (or two) different pixel tiles instead, and
+    // since the block's share of an NHWC record is then 16 (or 32) bytes, a lane's codes are that share (or half of it):
+    // stored directly, no transposition through LDS, no barrier in the loop.
+    const int left = C - cb * 64;
+    const int narrow = left <= 16 ? 1 : left <= 32 ? 2 : 0;   // uniform: groups of 16 channels
     const int sub = narrow ? wave / narrow : 0, nsub = narrow ? 4 / narrow : 1;   // the wave's pixel tile among the workgroup's
-    const int c0 = narrow ? 16 * (wave % narrow) : cb * 64 + 16 * wave;
+    const int c0 = cb * 64 + 16 * (narrow ? wave % narrow : wave);
     const int wg_tiles = (ws.tiles + nsub - 1) / nsub;
     const uint32_t M = (uint32_t)N * (uint32_t)HW;
     constexpr uint32_t EB = sizeof(T);   // bytes of a source element
@@ -1233,6 +1234,21 @@ __global__ __launch_bounds__(kBlock) void k_absmax(const float* __restrict__ x, 
     }
 }
 
+// Scale of the per-tensor copy from the per-channel maxima of the channel-resident pass (one workgroup).
+__global__ __launch_bounds__(kBlock) void k_fold_max(QuantWs ws, int C, float* __restrict__ s_global) {
+    __shared__ float l_m[kBlock / kWave];
+    float m = 0.0f;
+    for (int i = threadIdx.x; i < C; i += kBlock) m = fmaxf(m, ws.part_max[i]);
+    m = wave_max(m);
+    if (threadIdx.x % kWave == 0) l_m[threadIdx.x / kWave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(l_m[0], l_m[1]), fmaxf(l_m[2], l_m[3]));
+        ws.layer[0] = m;
+        *s_global = (m >= kTinyScale) ? m : 0.0f;
+    }
+}
+
 __global__ void k_scale_from_bits(const uint32_t* bits, float* s) {
     const float v = __uint_as_float(*bits);
     *s = (v >= kTinyScale) ? v : 0.0f;
@@ -1502,7 +1518,7 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     const bool res_v4 = sizeof(T) == 4 && HW % 4 == 0 && ((uintptr_t)dY & 15u) == 0;
     const int64_t res_units = ceil_div((int64_t)N * HW, res_v4 ? 4 : 1);
     const bool res_small = res_units <= 8 * 512, res_mid = res_units <= 16 * 512;
-    const bool resident_ok = scheme == DAQ_SCHEME_DAQ && qg_nhwc && res_units <= 16 * 1024 && Lv.plane_pitch <= kResidentMaxLds &&
+    const bool resident_ok = scheme == DAQ_SCHEME_DAQ && res_units <= 16 * 1024 && Lv.plane_pitch <= kResidentMaxLds &&
                              (Lv.plane_pitch & 15) == 0 && (Lv.chan_pitch & 15) == 0;
     // (The 1024-thread form runs one workgroup per CU, whose load, count and packing phases follow each other with nothing
     // to overlap them: on 128 -> 512 at 28 x 28, batch 64, it takes 59 + 27 us against 31 + 50 + 8 us for the sweeps - level -
@@ -1533,6 +1549,11 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
         }
 #undef DAQ_RES_SIZE
 #undef DAQ_RES_LAUNCH
+        if (!qg_nhwc) {
+            // depthwise layers: the per-tensor copy is channel-major too; its scale is folded from the channel maxima first
+            DAQ_LAUNCH("fold_max", st, hipLaunchKernelGGL(k_fold_max, dim3(1), dim3(kBlock), 0, st, ws, C, s_global));
+            return launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, keys, ws, ClipArgs{}, st);
+        }
         const dim3 cgrid((unsigned)(CB * ws.cgroups));
 #define DAQ_COPY_LAUNCH(S)                                                                                           \
     DAQ_LAUNCH("global_copy", st,                                                                                    \
