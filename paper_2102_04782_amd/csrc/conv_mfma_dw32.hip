@@ -41,6 +41,7 @@ struct Dw32Args {
     const int8_t* x;      // q(X'), [Cin][x_chan_pitch]
     int64_t klen;
     int64_t x_chan_pitch;
+    int64_t x_plane_pitch;   // stride 2: bytes of one stride-phase plane of an activation channel
     int Cout, Cin;
     int row_pitch;
     int pb;               // LDS pitch of an activation row in bytes (a multiple of 4 with pb/4 odd)
@@ -93,21 +94,29 @@ __device__ __forceinline__ bool dw_block_map(const Dw32Args& p, int& split, int&
 
 // WQ4 = row_pitch mod 4.  WM x WN x WK = 4 or 8 waves: tiles along co, along ci, split of the K steps.
 // PF = chunks whose global loads are in flight beyond the one being written to LDS (register ring).
-template <int WQ4, int WM, int WN, int WK, int PF>
+//
+// S2: the same product for a 3 x 3 filter at stride 2.  The activation is stored as its four stride-phase planes
+// (row parity, column parity), each with the gradient's slot geometry, so tap (kh, kw) pairs gradient byte f with byte
+// f + (kh/2)*row_pitch + kw/2 of plane (kh%2, kw%2): still shifted correlations over the flat axis, now against four
+// staged rows per input channel (windows of 256 + row_pitch + 1 bytes).  Six 24-byte reads per K step - one per
+// (plane, row shift) - serve the nine taps.
+template <int WQ4, int WM, int WN, int WK, int PF, bool S2 = false>
 __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
     constexpr int WAVES = WM * WN * WK, NT = 64 * WAVES;
     static_assert(WAVES == 4 || WAVES == 8, "four or eight waves");
+    static_assert(!S2 || (WM == 1 && WN == 1 && WK == 8), "the strided form shares one tile among eight waves");
     constexpr int BM = 32 * WM, BN = 32 * WN;
+    constexpr int PL = S2 ? 4 : 1;                    // staged rows per input channel (stride-phase planes)
     constexpr int A_PER_T = BM * (kKC / 16) / NT;    // 16-byte units of the gradient tile per thread
     constexpr int A_BYTES = BM * kPA;
-    constexpr int B_MAX = 4 * WN * 256 / NT;          // 16-byte units of the activation tile per thread, at most
+    constexpr int B_MAX = S2 ? 5 : 4 * WN * 256 / NT;  // 16-byte units of the activation tile per thread, at most
     extern __shared__ __align__(16) int8_t lds[];
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wk = wave % WK, wn = (wave / WK) % WN, wm = wave / (WK * WN);
     const int l32 = lane & 31, lh = lane >> 5;
-    const int B_BYTES = BN * p.pb;
+    const int B_BYTES = PL * BN * p.pb;
     const int STAGE = A_BYTES + B_BYTES;
 
     int split, tile;
@@ -143,14 +152,14 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
     // activation: unit u = tid + 256*i of the BN x b_units tile (row-major): consecutive lanes, consecutive 16 bytes
     uint32_t b_src[B_MAX];
     int b_dst[B_MAX];
-    const int b_total = BN * p.b_units;
+    const int b_total = PL * BN * p.b_units;
 #pragma unroll
     for (int i = 0; i < B_MAX; ++i) {
         const int u = tid + NT * i;
         const int uc = u < b_total ? u : 0;
-        const int row = uc / p.b_units, col = uc - row * p.b_units;
-        const int ci = ci0 + row;
-        b_src[i] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * col);
+        const int row = uc / p.b_units, col = uc - row * p.b_units;   // staged row = plane * BN + channel of the tile
+        const int ci = ci0 + row % BN;
+        b_src[i] = (uint32_t)((int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + (int64_t)(row / BN) * p.x_plane_pitch + 16 * col);
         b_dst[i] = u < b_total ? A_BYTES + row * p.pb + 16 * col : -1;
     }
     // Every call issues the same loads (past the end the last chunk is fetched again, which the caches absorb):
@@ -202,6 +211,40 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
         // All LDS reads of this wave's K steps are issued before the first multiply: with one wave per SIMD nothing
         // else hides their latency.
         constexpr int KS = (kKC / 32) / WK;
+        if constexpr (S2) {
+#pragma unroll
+            for (int i = 0; i < KS; ++i) {
+                const int ks = wk + i * WK;
+                const v4i fa = *reinterpret_cast<const v4i*>(A + 32 * ks);
+#pragma unroll
+                for (int pl = 0; pl < 4; ++pl) {
+                    const int ph_h = pl >> 1, ph_w = pl & 1;
+#pragma unroll
+                    for (int rs = 0; rs < 2; ++rs) {
+                        if (rs == 1 && ph_h == 1) continue;   // kh = 1 is the only tap row on the odd row planes
+                        const int kh = ph_h + 2 * rs;
+                        // 24 bytes from the dword at or below the first window of this (plane, row shift)
+                        const int8_t* src = B + pl * (BN * p.pb) + 32 * ks + ((rs * p.row_pitch) & ~3);
+                        const v4i_a4 lo = *reinterpret_cast<const v4i_a4*>(src);
+                        const v2i_a4 hi = *reinterpret_cast<const v2i_a4*>(src + 16);
+                        const int d[6] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1]};
+#pragma unroll
+                        for (int cs = 0; cs < 2; ++cs) {
+                            if (cs == 1 && ph_w == 1) continue;
+                            const int kw = ph_w + 2 * cs;
+                            const int sft = (rs ? WQ4 : 0) + cs, j = sft >> 2, sh = sft & 3;
+                            v4i bf;
+                            if (sh == 0)
+                                bf = v4i{d[j], d[j + 1], d[j + 2], d[j + 3]};
+                            else
+                                bf = v4i{alignbyte(d[j + 1], d[j], sh), alignbyte(d[j + 2], d[j + 1], sh),
+                                         alignbyte(d[j + 3], d[j + 2], sh), alignbyte(d[j + 4], d[j + 3], sh)};
+                            acc[kh * 3 + kw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa, bf, acc[kh * 3 + kw], 0, 0, 0);
+                        }
+                    }
+                }
+            }
+        } else {
         v4i fa[KS];
         int fd[KS][3][6];
 #pragma unroll
@@ -237,6 +280,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw32(Dw32Args p) {
                     acc[kh * 3 + kw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], bf, acc[kh * 3 + kw], 0, 0, 0);
                 }
             }
+        }
         }
         // chunk+1 sits in ring set (u+1) % PF: it goes to the other LDS buffer and the set is refilled PF chunks ahead
         store_chunk(buf ^ 1, (u + 1) % PF);
@@ -562,6 +606,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
 struct Plan32 {
     bool ok;
     bool k11;             // 1 x 1 filter: the plain GEMM kernel
+    bool s2;              // 3 x 3 filter at stride 2: four stride-phase planes per input channel
     int wm, wn, wk, splits, tiles_m, tiles_n, nchunks, pb, b_units, ch;
     int bands_m, bands_n, band_m, band_n;   // rectangles of the tile grid per K split when there are 1, 2 or 4 splits (else 0)
     int64_t blocks;       // workgroups of the launch
@@ -595,7 +640,8 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     // a 1 x 1 filter pairs gradient position f with byte f of the activation's first stride-phase plane whatever the
     // stride (and dilation means nothing), so the plain GEMM serves strided shortcuts too
     const bool k33 = unit && d.kH == 3 && d.kW == 3, k11 = d.kH == 1 && d.kW == 1;
-    if (!k33 && !k11) return pl;
+    const bool k33s2 = d.kH == 3 && d.kW == 3 && d.strideH == 2 && d.strideW == 2 && d.dilH == 1 && d.dilW == 1;
+    if (!k33 && !k11 && !k33s2) return pl;
     daq_layout Lg, Lx;
     if (daq_layout_vq(&d, &Lg) != DAQ_OK || daq_layout_qx_cnhw(&d, &Lx) != DAQ_OK) return pl;
     if (Lg.bytes >= ((int64_t)1 << 32) || Lx.bytes >= ((int64_t)1 << 32)) return pl;   // 32-bit per-lane offsets
@@ -624,23 +670,30 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         pl.ok = true;
         return pl;
     }
+    if (k33s2) {
+        // the strided form relies on the slot geometry the two operands share and on the four phase planes of a channel
+        if (Lx.phases_h != 2 || Lx.phases_w != 2 || Lx.row_pitch != Lg.row_pitch || Lx.img_rows != Lg.img_rows ||
+            Lx.lead != Lg.lead || Lx.chan_pitch != 4 * Lx.plane_pitch)
+            return pl;
+        pl.s2 = true;
+    }
     // bytes of an activation row a chunk needs: its own 256 plus the largest tap offset, plus the bytes the
     // six-dword reads of the last K step touch beyond that
-    const int need = kKC + 2 * Lx.row_pitch + 2 + 8;
+    const int need = kKC + (pl.s2 ? 1 : 2) * Lx.row_pitch + 2 + 8;
     pl.b_units = (int)ceil_div(need, 16);
     pl.pb = 16 * pl.b_units + 4;              // pitch/4 odd: the 32 rows of a fragment read fall into 32 different banks
     const int64_t t64 = ceil_div(d.Cout, 64) * ceil_div(d.Cin, 64);
-    if (t64 >= 256) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
+    if (t64 >= 256 && !pl.s2) { pl.wm = 2; pl.wn = 2; pl.wk = 1; }
     else { pl.wm = 1; pl.wn = 1; pl.wk = 8; }   // eight waves: two per SIMD, so that one's LDS phase overlaps the other's MFMAs
     const int bm = 32 * pl.wm, bn = 32 * pl.wn;
-    if ((int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile (B_MAX * threads)
+    if (pl.s2 ? 4 * bn * pl.b_units > 5 * 512 : (int64_t)bn * pl.b_units > 4 * pl.wn * 256) return pl;   // staging registers of the activation tile (B_MAX * threads)
     pl.tiles_m = (int)ceil_div(d.Cout, bm);
     pl.tiles_n = (int)ceil_div(d.Cin, bn);
     const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
     int64_t s = ceil_div(256, tiles);
     s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
     pl.splits = (int)std::max<int64_t>(1, s);
-    const size_t stage = (size_t)bm * kPA + (size_t)bn * pl.pb;
+    const size_t stage = (size_t)bm * kPA + (size_t)(pl.s2 ? 4 : 1) * bn * pl.pb;
     // hand-over area of the parallel combine: [owner][source][slot][lane]
     const int rounds = pl.wk > 4 ? 2 : 1;
     pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * kT * 16 * kWave * 4 / rounds : 0);
@@ -651,12 +704,12 @@ Plan32 make_plan32(const daq_conv_desc& d) {
     return pl;
 }
 
-template <int WM, int WN, int WK, int PF>
+template <int WM, int WN, int WK, int PF, bool S2 = false>
 daq_status launch32(const Plan32& pl, const Dw32Args& a, int wq4, hipStream_t st) {
     const dim3 grid((unsigned)pl.blocks);
 #define DAQ_DW32_CASE(Q)                                                                                          \
     if (wq4 == Q) {                                                                                               \
-        auto kern = k_dw32<Q, WM, WN, WK, PF>;                                                                        \
+        auto kern = k_dw32<Q, WM, WN, WK, PF, S2>;                                                                    \
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,                    \
                                 (int)pl.lds_bytes) != hipSuccess)                                                 \
             return DAQ_ERR_HIP;                                                                                   \
@@ -690,6 +743,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
     a.x = qx;
     a.klen = Lg.plane_pitch;
     a.x_chan_pitch = Lx.chan_pitch;
+    a.x_plane_pitch = Lx.plane_pitch;
     a.Cout = d.Cout;
     a.Cin = d.Cin;
     a.row_pitch = Lx.row_pitch;
@@ -729,7 +783,8 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
         }
         return DAQ_OK;
     }
-    const daq_status rc = pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
+    const daq_status rc = pl.s2 ? launch32<1, 1, 8, 2, true>(pl, a, wq4, st)
+                          : pl.wk == 1 ? launch32<2, 2, 1, 1>(pl, a, wq4, st) : launch32<1, 1, 8, 3>(pl, a, wq4, st);
     if (rc != DAQ_OK) return rc;
     if (pl.splits > 1 && defer && dw_tail_worthwhile((int)(pl.part_slots / kWave), pl.splits)) {
         *defer = DwTail{a.part, (int)(pl.part_slots / kWave), pl.splits, pl.tiles_n, pl.wm, pl.wn, d.Cout, d.Cin, 9, s_x, s_chan, dW, acc, bf16 ? 1 : 0};

@@ -359,6 +359,9 @@ CONV_LAYERS = [
     wl.Layer("stem_big", 4, 3, 64, 64, 64, 7, 7, 2, 3),           # 49 taps on eight waves, K split
     wl.Layer("c1x1_s2_big", 8, 64, 28, 28, 128, 1, 1, 2, 0),      # strided projection shortcut
     wl.Layer("c3x3_s2_dil2", 2, 16, 15, 14, 16, 3, 3, 2, 2, 2),   # stride and dilation together
+    wl.Layer("c3x3_s2_pad0", 3, 20, 13, 12, 40, 3, 3, 2, 0),      # strided without padding; ragged channel tiles
+    wl.Layer("c3x3_s2_w14", 2, 8, 14, 14, 24, 3, 3, 2, 1),        # row pitch 8: the shifted windows start on dword boundaries
+    wl.Layer("c3x3_s2_w16", 2, 40, 9, 16, 8, 3, 3, 2, 1),         # row pitch 9
     wl.Layer("c1x1_pad", 2, 16, 6, 6, 16, 1, 1, 1, 1),            # padded 1x1
     wl.Layer("c1x1_thin16", 3, 40, 10, 12, 16, 1, 1, 1, 0),       # thin 1x1 (streaming data gradient): 16-byte pixel records, ragged row block
     wl.Layer("c1x1_thin24", 2, 144, 9, 7, 24, 1, 1, 1, 0),        # 32-byte records; groups of 32 pixels straddle images; ragged last group
