@@ -542,7 +542,7 @@ struct StreamArgs {
     const int8_t* wfrag;  // filter in fragment order (one tap): [cp/64][RB][2][1024]
     uint32_t src_bytes, wfrag_bytes;
     int cp, Crow, RB, HW;
-    int RP, S;            // pairs of row blocks; pixel-group phases (a wave takes groups s, s + S, ...)
+    int RP, S;            // pairs of row blocks; pixel-group phases, a multiple of four (a wave takes groups s, s + S, ...)
     uint32_t total_px, groups;
     FastDiv div_rp, div_hw;
     const float* s_a;
@@ -564,10 +564,14 @@ __global__ __launch_bounds__(256) void k_dx_1x1_stream(StreamArgs p) {
         return;
     }
     const int lane = threadIdx.x % kWave, l32 = lane & 31, lh = lane >> 5;
-    const uint32_t wave = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const uint32_t s = fdiv(wave, p.div_rp);
-    const int rp = (int)(wave - s * (uint32_t)p.RP);
+    // the four waves of a workgroup take four neighbouring pixel groups of one pair of row blocks: together they
+    // write 512 consecutive bytes of each of the pair's 64 planes
+    const uint32_t quad = fdiv(blockIdx.x, p.div_rp);
+    const int rp = (int)(blockIdx.x - quad * (uint32_t)p.RP);
+    const uint32_t s = quad * 4u + threadIdx.x / kWave;
     if (s >= (uint32_t)p.S) return;   // uniform per wave
+    // (a wave takes groups s, s + S, ...: all waves together advance through the pixels as one window.  Giving every
+    // workgroup a contiguous range of its own instead measured 13 % slower over ResNet-50's 17 such layers.)
     const __amdgpu_buffer_rsrc_t rs_src = __builtin_amdgcn_make_buffer_rsrc((void*)p.src, 0, (int)p.src_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc((void*)p.wfrag, 0, (int)p.wfrag_bytes, 0x00020000);
     const float scale = (*p.s_a / 127.0f) * (*p.s_b / 127.0f);
@@ -896,14 +900,14 @@ daq_status launch_stream(const char* name, const daq_conv_desc& d, const daq_lay
     const int ks = (int)ceil_div(a.cp, 32);
     // waves the chip holds at this form's register count; a wave should get several groups for its filter fragments
     const int64_t target = ks <= 2 ? 8192 : ks <= 4 ? 4096 : 2048;
-    a.S = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.groups, 2), target / a.RP));
+    a.S = (int)round_up(std::max<int64_t>(1, std::min<int64_t>(ceil_div((int64_t)a.groups, 2), target / a.RP)), 4);
     a.div_rp = make_fastdiv((uint32_t)a.RP);
     a.div_hw = make_fastdiv((uint32_t)a.HW);
     a.s_a = s_a; a.s_b = s_b;
     a.out = out; a.acc_out = acc;
     a.bf16 = bf16 ? 1 : 0;
     a.nt = (int64_t)d.N * rows * a.HW * (bf16 ? 2 : 4) >= kStreamBytes;
-    const int64_t wgs = ceil_div((int64_t)a.RP * a.S, 4);
+    const int64_t wgs = (int64_t)a.RP * ceil_div(a.S, 4);
     if (tail) a.tail = *tail;
     a.main_blocks = (int)wgs;
     const dim3 grid((unsigned)(wgs + a.tail.blocks));
