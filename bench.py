@@ -307,6 +307,7 @@ def run_network(args, dev) -> int:
     per, ev_us = profile_pass(args, net, nL, R, modes[args.rounding], max(2, min(args.steps, 10)))
     dy_b = 2.0 if args.dy_bf16 else 4.0
     kernels, phases = {}, {"quantize": 0.0, "dW": 0.0, "dX": 0.0}
+    floors = {"quantize": 0.0, "dW": 0.0, "dX": 0.0}   # per phase: sum over launches of max(ops / int8 peak, algorithmic bytes / HBM peak)
     layer_rows = []
     for li, L in enumerate(layers):
         d = net[li].d
@@ -328,6 +329,12 @@ def run_network(args, dev) -> int:
             phases[ph] += us * n
             row[ph + "_us"] = round(row.get(ph + "_us", 0.0) + us * n, 1)
             row.setdefault("kernels_us", {})[k] = round(us * n, 1)
+            fl = 1e6 * n * max(o / (PEAK_INT8_TOPS * 1e12), b / (PEAK_HBM_GBS * 1e9))
+            floors[ph] += fl
+            row[ph + "_roofline_us"] = round(row.get(ph + "_roofline_us", 0.0) + fl, 2)
+        # fraction of the layer's roofline min(int8 peak, ops/byte x HBM peak) each phase reaches: floor time / measured time
+        row["frac_of_roofline"] = {ph: round(row[ph + "_roofline_us"] / row[ph + "_us"], 3) for ph in ("quantize", "dW", "dX")
+                                   if row.get(ph + "_us", 0.0) > 0}
         layer_rows.append(row)
     ridge = PEAK_INT8_TOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     traffic = measured_traffic(config) if (args.rounding == "stochastic" and args.layer < 0 and not (args.dy_bf16 or args.dx_bf16 or args.separate or args.scheme != "daq" or args.schedule != "auto")) else {}
@@ -398,6 +405,7 @@ def run_network(args, dev) -> int:
         "kernels": table,
         "roofline": roofline,
     }
+    result["frac_of_roofline_by_phase"] = {ph: round(floors[ph] / phases[ph], 3) for ph in phases if phases[ph] > 0}
     if args.layers:
         result["layers"] = layer_rows
 
