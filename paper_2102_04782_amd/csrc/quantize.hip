@@ -133,7 +133,9 @@ __device__ __forceinline__ int quant_code(float x, float inv, uint32_t U) {
     float t = x * inv;
     t = fminf(fmaxf(t, -127.0f), 127.0f);
     if (STOCH) {
-        const int nc = (int)floorf(t * -65536.0f);   // -ceil(t * 2^16)
+        // -ceil(t * 2^16) = floor(-t * 2^16), floor and conversion in one instruction (|t * 2^16| < 2^23: exact)
+        int nc;
+        asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(nc) : "v"(t * -65536.0f));
         return (65535 - (int)U - nc) >> 16;
     }
     return (int)rintf(t);
