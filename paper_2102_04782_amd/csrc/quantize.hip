@@ -1054,7 +1054,7 @@ struct ResArgs {
 // FLAT (with VEC4): the plane has no padding between rows or images (1 x 1 layers), so element m of the channel sits at
 // byte lead + m and a unit's four codes are one aligned dword of the plane: they go straight to memory, no LDS image.
 template <typename T, bool STOCH, bool VEC4, int NU, int TH, bool FLAT = false>
-__global__ __launch_bounds__(TH, NU <= 8 ? 8 : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
+__global__ __launch_bounds__(TH, NU <= 8 ? (VEC4 ? 6 : 8) : 4) void k_chan_resident(const T* __restrict__ g, CnhwView L, int8_t* __restrict__ vq,
                                                       ResArgs ra, QuantWs ws, ClipArgs ca) {
     extern __shared__ __align__(16) int8_t l_img[];   // the channel's plane as it will sit in memory
     __shared__ float l_mx[TH / kWave];
@@ -1091,6 +1091,36 @@ __global__ __launch_bounds__(TH, NU <= 8 ? 8 : 4) void k_chan_resident(const T* 
             x[u][0] = buf_ld<T>(rs, off, 0u);
         }
     }
+    if constexpr (STOCH) __builtin_amdgcn_sched_barrier(0);   // every load of the channel is requested before the hashes below start
+    // Stochastic rounding: an element's draw depends on its index alone, so the hashes are computed here, while the
+    // loads are on their way and the vector ALU has nothing else to do, and kept as 16-bit halves (element k of the
+    // thread in half k % 2 of word k / 2).
+    uint32_t draw[STOCH ? (NU * PER + 1) / 2 : 1];
+    if constexpr (STOCH) {
+#pragma unroll
+        for (int k = 0; k < NU * PER; k += 2) {
+            uint32_t h[2] = {0u, 0u};
+#pragma unroll
+            for (int t = 0; t < 2 && k + t < NU * PER; ++t) {
+                const int u = (k + t) / PER, e = (k + t) % PER;
+                const uint32_t m = (uint32_t)(u * TH + tid) * PER;   // (units past the channel hash a number nobody uses)
+                const uint32_t n = fdiv(m, ra.div_hw);
+                h[t] = fmix32((m + n * skip + first + (uint32_t)e) ^ (uint32_t)ra.seed);
+            }
+            draw[k / 2] = (h[0] >> 16) | (h[1] & 0xffff0000u);   // the per-channel copy draws from the upper half of the hash
+        }
+        // (without this the compiler moves the hashes down to where they are used, behind the barriers; only where
+        // the registers allow it: planes without padding, and three quarters of the draws of the large forms)
+        constexpr int PIN = !FLAT ? 0 : NU <= 8 ? (NU * PER + 1) / 2 : 3 * ((NU * PER + 1) / 2) / 4;
+#pragma unroll
+        for (int k = 0; k < PIN; ++k) asm volatile("" : "+v"(draw[k]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    auto draw_of = [&](int u, int e) -> uint32_t {
+        if constexpr (!STOCH) return 0u;
+        const int k = u * PER + e;
+        return (k & 1) ? draw[k / 2] >> 16 : draw[k / 2] & 0xffffu;
+    };
     float mx = 0.0f;
     double s1 = 0.0, s2 = 0.0;
 #pragma unroll
@@ -1160,12 +1190,9 @@ __global__ __launch_bounds__(TH, NU <= 8 ? 8 : 4) void k_chan_resident(const T* 
         for (int u = 0; u < NU; ++u) {
             const int q = u * TH + tid;
             if (q < units) {
-                const uint32_t m = (uint32_t)q * 4u;
-                const uint32_t n = fdiv(m, ra.div_hw);
-                const uint32_t idx = m + n * skip + first;   // NCHW index: keys stochastic rounding
                 uint32_t b[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) b[e] = quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0u);
+                for (int e = 0; e < 4; ++e) b[e] = quant_bits<STOCH>(x[u][e], inv, draw_of(u, e));
                 pay[q] = pack4(b[0], b[1], b[2], b[3]);
             }
         }
@@ -1187,10 +1214,9 @@ __global__ __launch_bounds__(TH, NU <= 8 ? 8 : 4) void k_chan_resident(const T* 
             uint32_t r = fdiv(px, ra.div_w);
             uint32_t col = px - r * (uint32_t)L.W;
             uint32_t pos = (uint32_t)L.lead + n * slot + r * (uint32_t)L.row_pitch + col;
-            const uint32_t idx = m + n * skip + first;   // NCHW index: keys stochastic rounding
 #pragma unroll
             for (int e = 0; e < PER; ++e) {
-                l_img[pos] = (int8_t)quant_bits<STOCH>(x[u][e], inv, STOCH ? rng_u(ra.seed, 0u, idx + e) : 0u);
+                l_img[pos] = (int8_t)quant_bits<STOCH>(x[u][e], inv, draw_of(u, e));
                 const bool wrap = ++col == (uint32_t)L.W;   // a unit stays inside its image, but may run on into the next row
                 col = wrap ? 0u : col;
                 pos += wrap ? (uint32_t)(L.row_pitch - L.W) + 1u : 1u;
