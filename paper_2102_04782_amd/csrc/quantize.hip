@@ -1109,9 +1109,10 @@ __global__ __launch_bounds__(TH, NU <= 8 ? (VEC4 ? 6 : 8) : 4) void k_chan_resid
             }
             draw[k / 2] = (h[0] >> 16) | (h[1] & 0xffff0000u);   // the per-channel copy draws from the upper half of the hash
         }
-        // (without this the compiler moves the hashes down to where they are used, behind the barriers; only where
-        // the registers allow it: planes without padding, and three quarters of the draws of the large forms)
-        constexpr int PIN = !FLAT ? 0 : NU <= 8 ? (NU * PER + 1) / 2 : 3 * ((NU * PER + 1) / 2) / 4;
+        // (without this the compiler moves the hashes down to where they are used, behind the barriers; as many of
+        // them as the registers of the form allow)
+        constexpr int W = (NU * PER + 1) / 2;
+        constexpr int PIN = NU <= 8 ? (FLAT || !VEC4 ? W : W / 2) : FLAT ? 3 * W / 4 : W / 2;
 #pragma unroll
         for (int k = 0; k < PIN; ++k) asm volatile("" : "+v"(draw[k]));
         __builtin_amdgcn_sched_barrier(0);
