@@ -315,10 +315,10 @@ def run_network(args, dev) -> int:
         row = {"layer": L.name, "shape": f"N{L.N} {L.Cin}->{L.Cout} {L.Hin}x{L.Win} k{L.kH} s{L.stride} g{L.groups}"}
         for k, (us, n) in per[li].items():
             dx_b = 2.0 if (net[li].bf16_ok and k.startswith("conv_bwd_data")) else 4.0
-            # the library's rule for the early per-channel copy (gradients of 16 Mi elements and more, NHWC global copy,
+            # the library's rule for the early per-channel copy (gradients of 8 Mi elements and more, NHWC global copy,
             # rows of an even number of pixels); a layer without a channel-resident launch took the sweeps
             early = (args.scheme == "daq" and qg_nhwc and "chan_resident" not in per[li] and L.Wo % 2 == 0 and
-                     (args.schedule == "early_copy" or (args.schedule == "auto" and float(np.prod(d.y_shape)) >= 16 * 2 ** 20)))
+                     (args.schedule == "early_copy" or (args.schedule == "auto" and float(np.prod(d.y_shape)) >= 8 * 2 ** 20)))
             b, o = kernel_work(L, d, k, dy_b, dx_b, qg_nhwc, early)
             e = kernels.setdefault(k, {"us": 0.0, "launches": 0.0, "bytes": 0.0, "ops": 0.0})
             e["us"] += us * n

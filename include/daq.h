@@ -177,7 +177,7 @@ size_t daq_workspace_bytes(daq_op op, const daq_conv_desc* desc);
  * Hyper-parameters of the paper: k = 1, A = 0.8, lambda = 0.3.
  *
  * Schedule (results do not depend on it, see daq_schedule): three sweeps over dY - statistics;
- * count + qg; vq.  For gradients of 16 Mi elements and more the second sweep also writes vq under a
+ * count + qg; vq.  For gradients of 8 Mi elements and more the second sweep also writes vq under a
  * class guessed from |g|max / sigma, and the third only redoes the channels whose guess was wrong.
  * ------------------------------------------------------------------------------------------- */
 daq_status daq_quantize_grad(const daq_conv_desc* desc, const float* dY, float* s_state, float k, float A,

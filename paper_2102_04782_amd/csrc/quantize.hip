@@ -23,7 +23,7 @@ constexpr int kBlock = 256;
 constexpr int kStatsElems = 4096;  // elements one statistics workgroup sweeps per iteration (16 per thread, all in flight)
 constexpr int kMaxSlabs = 16;      // statistics partials per channel (every consumer re-folds them)
 constexpr int kCountGrid = 1024;   // workgroups the counting pass aims for; one count partial per channel each
-constexpr int64_t kEarlyVqMinElems = (int64_t)16 << 20;   // gradients from this size on take the early per-channel copy
+constexpr int64_t kEarlyVqMinElems = (int64_t)8 << 20;   // gradients from this size on take the early per-channel copy
 
 // ---------------------------------------------------------------------------------------------
 // workspace carving
