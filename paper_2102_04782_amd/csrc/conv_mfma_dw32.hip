@@ -660,9 +660,8 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         s = std::min<int64_t>(s, std::max(1, pl.nchunks / 2));
         pl.splits = (int)std::max<int64_t>(1, s);
         // One chunk per LDS stage.  (Two chunks per barrier were measured on the late ResNet-50 layers: the K loop of a
-        // workgroup - 13 chunks of 32 KiB in 7 us on every CU at once, most of it waiting for operand lines that several
-        // CUs of the XCD want from its L2 at the same time - gets a quarter shorter per byte, and the first stage arrives
-        // that much later.)
+        // workgroup - 13 chunks of 32 KiB in 7 us on every CU at once, bound by the staging through registers and LDS and
+        // its two waits per chunk - gets a quarter shorter per byte, and the first stage arrives that much later.)
         pl.ch = 1;
         const size_t stage = (size_t)64 * (pl.wm + pl.wn) * (pl.ch * kKC + 16);
         pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // one-round combine
