@@ -424,7 +424,11 @@ __global__ __launch_bounds__(256) void k_dw_reduce(DwTail t) {
 // A wave owns 64 (co) x 64 (ci): four 32 x 32 tiles, so every fragment it reads feeds two multiplies.
 // Same ring, K-split and wave-combine scheme as above.
 // ---------------------------------------------------------------------------------------------
-template <int WM, int WN, int WK, int PF, int CH>
+// DMA (the eight-wave form): the operands go from global memory straight into LDS (global_load_lds_dwordx4, the 64
+// lanes' 16-byte pieces land in 64 consecutive slots), four stage buffers of unpadded 256-byte rows, three stages on
+// their way; no staging registers, no LDS stores, one barrier per chunk.  Slot column c of row r holds the row's
+// 16-byte column c ^ (r % 16), so that the 16 lanes of a fragment read still fall into different banks.
+template <int WM, int WN, int WK, int PF, int CH, bool DMA = false>
 __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
     constexpr int WAVES = WM * WN * WK, NT = 64 * WAVES;
     static_assert(WAVES == 4 || WAVES == 8, "four or eight waves");
@@ -463,6 +467,68 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
         }
     }
 
+    v16i acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
+
+    if constexpr (DMA) {
+        static_assert(WM == 1 && WN == 1 && WK == 8 && CH == 1, "the direct-to-LDS form is the eight-wave one");
+        typedef __attribute__((address_space(3))) void* lds_ptr;
+        constexpr int D = 4;                     // stage buffers
+        constexpr int SB = (BM + BN) * kKC;      // bytes of a stage
+        // request i of wave w fills rows 16w + 4i .. + 3 of the stage: lane l -> row + l / 16, slot column l % 16
+        const int8_t* src[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * wave + 4 * i + lane / 16;
+            const int col = (lane % 16) ^ (row & 15);
+            if (row < BM) {   // rows past Cout / Cin recompute row 0 and are never stored
+                const int co = co0 + row;
+                src[i] = p.g + (int64_t)(co < p.Cout ? co : 0) * p.klen + 16 * col;
+            } else {
+                const int ci = ci0 + row - BM;
+                src[i] = p.x + (int64_t)(ci < p.Cin ? ci : 0) * p.x_chan_pitch + 16 * col;
+            }
+        }
+        // every call issues four requests (past the end the last chunk again, into a buffer nobody reads), so that the
+        // count of outstanding requests below is a constant
+        auto issue = [&](int chunk, int buf) {
+            const int64_t k0 = (int64_t)min(chunk, c_last) * kKC;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_global_load_lds(src[i] + k0, (lds_ptr)(lds + buf * SB + (16 * wave + 4 * i) * kKC), 16, 0, 0);
+        };
+#pragma unroll
+        for (int st = 0; st < D - 1; ++st) issue(c_begin + st, st);
+        // fragment of K step wk: row l32 (+ 32 t), the row's column 2 wk + lh
+        const int fcol = 16 * ((2 * wk + lh) ^ (l32 & 15));
+        const int arow = l32 * kKC + fcol, brow = (BM + l32) * kKC + fcol;
+        int buf = 0;
+        for (int chunk = c_begin; chunk < c_end; ++chunk) {
+            asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // this wave's share of the chunk has landed; two more stages may be on their way
+            __builtin_amdgcn_s_barrier();                       // everybody's share has, and the buffer refilled next has been read out
+                                                                // (the plain barrier: __syncthreads would wait for the stages on their way too)
+            issue(chunk + D - 1, (buf + D - 1) % D);
+            const int8_t* A = lds + buf * SB + arow;
+            const int8_t* B = lds + buf * SB + brow;
+            v4i fa[2], fb[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fa[t] = *reinterpret_cast<const v4i*>(A + t * 32 * kKC);
+                fb[t] = *reinterpret_cast<const v4i*>(B + t * 32 * kKC);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[a], fb[b], acc[a][b], 0, 0, 0);
+            buf = (buf + 1) % D;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests past the end have landed before LDS is put to other use
+    } else {
     // unit u = tid + NT*i -> row u / UPR of the stacked (gradient, activation) tile, 16-byte column u % UPR of the stage;
     // the column - and with it the chunk of the stage the unit belongs to - is the same for all units of a thread
     const int c16 = tid % UPR, sub = c16 / (kKC / 16);
@@ -493,14 +559,6 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
 #pragma unroll
         for (int i = 0; i < UNITS; ++i) *reinterpret_cast<v4i*>(lds + buf * STAGE + u_dst[i]) = ring[set][i];
     };
-
-    v16i acc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0;
 
     load_stage(c_begin, 0);
     store_stage(0, 0);
@@ -547,6 +605,7 @@ __global__ __launch_bounds__(64 * WM * WN * WK) void k_dw11(Dw32Args p) {
         buf ^= 1;
         __syncthreads();
       }
+    }
     }
 
     // slot q = (a*2 + b)*16 + r: tile (a, b) of the wave, register r -> row (co) 32a + 8*(r/4) + 4*lh + r%4, column (ci) 32b + l32
@@ -664,7 +723,7 @@ Plan32 make_plan32(const daq_conv_desc& d) {
         // its two waits per chunk - gets a quarter shorter per byte, and the first stage arrives that much later.)
         pl.ch = 1;
         const size_t stage = (size_t)64 * (pl.wm + pl.wn) * (pl.ch * kKC + 16);
-        pl.lds_bytes = std::max<size_t>(2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // one-round combine
+        pl.lds_bytes = std::max<size_t>(pl.wk > 1 ? (size_t)4 * 128 * kKC : 2 * stage, pl.wk > 1 ? (size_t)(pl.wk - 1) * 64 * kWave * 4 : 0);   // staging (four unpadded stages in the direct-to-LDS form); one-round combine
         pl.part_slots = tiles * pl.wm * pl.wn * 64 * kWave;
         choose_bands(pl, 64 * pl.wm, 64 * pl.wn);
         pl.ok = true;
@@ -769,7 +828,7 @@ daq_status conv_bwd_filter_lds(const daq_conv_desc& d, const int8_t* qx, const f
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(256), pl.lds_bytes, st, a));
         } else {
-            auto kern = k_dw11<1, 1, 8, 3, 1>;
+            auto kern = k_dw11<1, 1, 8, 3, 1, true>;
             if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds_bytes) != hipSuccess)
                 return DAQ_ERR_HIP;
             DAQ_LAUNCH("conv_bwd_filter_dw11", st, hipLaunchKernelGGL(kern, grid, dim3(512), pl.lds_bytes, st, a));
