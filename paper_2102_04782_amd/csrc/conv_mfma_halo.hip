@@ -29,7 +29,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kPxWg = 256;         // destination pixels per workgroup
+constexpr int kPxWg = 256;         // destination pixels per workgroup (128 in the small-tile form of 1 x 1 filters)
 constexpr int kKc = 64;            // contraction bytes per step (two MFMA K-steps of 32)
 constexpr int kPitch = kKc + 16;   // LDS pitch of a window slot: eight consecutive slots cover all banks
 constexpr int kMaxTaps = 49;
@@ -83,12 +83,14 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // before the multiplies of the current one: with a single wave per SIMD nothing else hides those latencies.
 // NX = 32-row blocks of a wave that can hold result rows: 1 for results of at most 32 channels (the data gradient of a
 // network's first layer), whose second block would only multiply zeros - dynamic-tap form on 64-row tiles only.
-template <int WR, bool DB, int ST, int WAVES, int TAPS = 0, int NX = 2>
+// PX = destination pixels per workgroup: 128 (a wave then owns 64 rows x 32 pixels) for 1 x 1 layers with so few
+// pixels that 256-pixel tiles would leave CUs without a workgroup.
+template <int WR, bool DB, int ST, int WAVES, int TAPS = 0, int NX = 2, int PX = kPxWg>
 __global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = WAVES / WR;
     constexpr int SPT = 16 * WAVES;   // window slots one pass of the workgroup stages (four lanes per slot)
-    constexpr int PXW = kPxWg / WPX;
+    constexpr int PXW = PX / WPX;
     constexpr int BF = PXW / 32;
     extern __shared__ __align__(16) int8_t lds[];   // one or two window buffers of S slots
 
@@ -215,7 +217,7 @@ __global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_
         // 1 x 1 filters: a step is a chunk, and every chunk needs a new window.  With the window requested only one
         // step ahead each chunk would wait out a full memory latency; here window registers and filter tiles both
         // sit in rings of kRing1 chunks (slot = chunk % kRing1), requested kRing1 - 1 chunks before their use.
-        constexpr int kRing1 = 4, kU1 = 4;   // kU1: 16-byte window units per thread (no halo: at most 256 slots)
+        constexpr int kRing1 = 4, kU1 = PX / 64;   // kU1: 16-byte window units per thread (no halo: at most PX slots)
         v4i ra1[kRing1][2][2], rw[kRing1][kU1];
         auto fetch_1 = [&](int slot, int kc) {
             const bool live = kc < nkc;
@@ -674,13 +676,22 @@ struct Geometry {
     HaloArgs a;
     size_t lds_bytes;
     int rows;
+    int px;   // destination pixels per workgroup
 };
+
+// 1 x 1 filters at unit stride with several contraction chunks, on 64-row tiles: the form with rings of chunks
+bool ring1_applies(const Geometry& g) {
+    const HaloArgs& a = g.a;
+    return a.stride == 1 && a.T == 1 && a.ph_taps[0] == 1 && a.tap_slot[0][0] == 0 && a.double_buffer &&
+           a.units <= g.px / 64 && g.rows == 64;
+}
 
 // backward: destination (h, w) of parity class (pa, pb), h = 2*th + pa, reads source row th + (pa + pad - kh*dil)/stride
 // for every kh that makes the quotient exact.  forward (unit stride): source row = h - pad + kh*dil.
 Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int Crow, int kH, int kW, int sH, int sW,
-              int pH, int pW, int dH, int dW) {
+              int pH, int pW, int dH, int dW, int px = kPxWg) {
     Geometry g{};
+    g.px = px;
     HaloArgs& a = g.a;
     if (sH != sW || (sH != 1 && !(sH == 2 && backward)) || kH * kW > kMaxTaps) return g;
     // strided 1x1: three of four parity classes are empty; served when the live one is class (0, 0) (no padding),
@@ -730,17 +741,17 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     const int PH = (int)ceil_div(Hd, s), PW = (int)ceil_div(Wd, s);
     double best = 0.0;
     int bTH = 0, bTW = 0, bNI = 0;
-    if (PH * PW <= kPxWg) {
-        bTH = PH; bTW = PW; bNI = kPxWg / (PH * PW);
+    if (PH * PW <= px) {
+        bTH = PH; bTW = PW; bNI = px / (PH * PW);
         if ((int64_t)bNI * (bTH + span_h) * (bTW + span_w) > 64 * kMaxUnits) bNI = (64 * kMaxUnits) / ((bTH + span_h) * (bTW + span_w));
         if (bNI < 1) return g;
     } else {
         // widest tile among the best covers: the result is stored in runs of TW pixels
         for (int tw = std::min(PW, 128); tw >= 4; --tw) {
-            const int th = std::min(kPxWg / tw, PH);
+            const int th = std::min(px / tw, PH);
             if (th < 1) continue;
             if ((int64_t)(th + span_h) * (tw + span_w) > 64 * kMaxUnits) continue;
-            const double eff = (double)PH * PW / ((double)ceil_div(PH, th) * ceil_div(PW, tw) * kPxWg);
+            const double eff = (double)PH * PW / ((double)ceil_div(PH, th) * ceil_div(PW, tw) * px);
             if (eff > best + 0.02) { best = eff; bTH = th; bTW = tw; }
         }
         bNI = 1;
@@ -766,7 +777,15 @@ Geometry plan(bool backward, int N, int Hs, int Ws, int cp, int Hd, int Wd, int 
     if (g.lds_bytes > 150 * 1024) return g;
     // 128-row tiles reuse each pixel fragment twice as often, but only pay off when they still fill the chip
     const int64_t blocks128 = (int64_t)a.groups * a.tiles_h * a.tiles_w * (a.zfill ? 1 : s * s) * ceil_div(Crow, 128);
-    g.rows = (Crow > 64 && blocks128 >= 256) ? 128 : 64;
+    g.rows = (Crow > 64 && blocks128 >= 256 && px == kPxWg) ? 128 : 64;
+    // 1 x 1 filters with several contraction chunks do hardly any arithmetic per chunk, so a workgroup is as fast as its
+    // requests come back: the ring form (64-row tiles, chunks requested three ahead, two workgroups per CU) was
+    // measured faster than 128-row tiles up to a thousand of those (ResNet-50's 128 -> 512 at 28 x 28 and 1024 -> 512
+    // at 14 x 14, N = 64: 19.9 -> 18.2 and 29.7 -> 23.2 us), slower beyond (256 -> 512 at 56 x 56: 103 -> 120 us)
+    if (g.rows == 128 && blocks128 <= 1024) {
+        g.rows = 64;
+        if (!ring1_applies(g)) g.rows = 128;
+    }
     a.div_tw = make_fastdiv((uint32_t)a.TW);
     a.div_thw = make_fastdiv((uint32_t)(a.TH * a.TW));
     a.div_sw = make_fastdiv((uint32_t)a.SW);
@@ -788,6 +807,18 @@ struct HaloNames { const char *dyn, *s2, *r128, *k1, *k9; };
 constexpr HaloNames kBwdNames{"conv_bwd_data_halo", "conv_bwd_data_halo_s2", "conv_bwd_data_halo_r128", "conv_bwd_data_halo_1x1",
                               "conv_bwd_data_halo_3x3"};
 constexpr HaloNames kFwdNames{"conv_fwd_halo", "conv_fwd_halo", "conv_fwd_halo_r128", "conv_fwd_halo_1x1", "conv_fwd_halo_3x3"};
+
+// The ring form holds two workgroups per CU.  A layer whose 256-pixel tiles give far fewer than that (the late 1 x 1
+// layers of a classification network: few pixels, long contraction) is cut into 128-pixel tiles instead.  Measured
+// on ResNet-50's last stages, N = 64: 512 -> 2048 at 7 x 7 (104 tiles) 23.3 -> 17.2 us, 256 -> 1024 at 14 x 14 (256
+// tiles) 14.6 -> 14.5 us cold and 12.4 -> 11.6 us warm, 2048 -> 512 at 7 x 7 (416 tiles) 14.0 -> 15.1 us: not there.
+template <typename Plan>
+Geometry plan_small(Geometry g, Plan replan) {
+    if (!g.ok || !ring1_applies(g)) return g;
+    if (blocks_per_row_tile(g.a) * ceil_div(g.a.Crow, 64) >= 384) return g;
+    Geometry s = replan(128);
+    return s.ok && ring1_applies(s) ? s : g;
+}
 
 daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
     const HaloArgs& a = g.a;
@@ -811,8 +842,10 @@ daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
     // needs fewer registers, lets more workgroups overlap theirs; 128-row tiles stay on the eight-wave form.)
     // 1 x 1 filters at unit stride with several contraction chunks, on 64-row tiles: the form with rings of chunks
     // (on 128-row tiles, which are chosen when the grid is large, it measured no better than the dynamic form)
-    if (a.stride == 1 && a.T == 1 && a.ph_taps[0] == 1 && a.tap_slot[0][0] == 0 && a.double_buffer && a.units <= 4 && g.rows == 64) {
-        auto kern = k_conv_halo<1, true, 1, 4, 1>;
+    const bool ring1 = ring1_applies(g);
+    if (g.px != kPxWg && !ring1) return DAQ_ERR_UNSUPPORTED;   // small tiles exist in the ring form only (see plan_small)
+    if (ring1) {
+        auto kern = g.px == kPxWg ? k_conv_halo<1, true, 1, 4, 1> : k_conv_halo<1, true, 1, 4, 1, 2, 128>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
             return DAQ_ERR_HIP;
         DAQ_LAUNCH(names.k1, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
@@ -854,8 +887,11 @@ Geometry plan_bwd(const daq_conv_desc& d) {
     Geometry g{};
     if (d.groups != 1 || daq_layout_qg(&d, &Lg) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return g;
     if (Lg.kind != DAQ_LAYOUT_NHWC || Lg.bytes >= ((int64_t)1 << 31) || Lw.bytes - Lw.off_bwd_frag >= ((int64_t)1 << 31)) return g;
-    g = plan(true, d.N, Lg.H, Lg.W, Lg.c_pitch, d.Hin, d.Win, d.Cin, d.kH, d.kW, d.strideH, d.strideW, d.padH, d.padW,
-             d.dilH, d.dilW);
+    auto make = [&](int px) {
+        return plan(true, d.N, Lg.H, Lg.W, Lg.c_pitch, d.Hin, d.Win, d.Cin, d.kH, d.kW, d.strideH, d.strideW, d.padH, d.padW,
+                    d.dilH, d.dilW, px);
+    };
+    g = plan_small(make(kPxWg), make);
     g.a.src_bytes = (uint32_t)Lg.bytes;
     g.a.wfrag_bytes = (uint32_t)(Lw.bytes - Lw.off_bwd_frag);
     return g;
@@ -867,8 +903,11 @@ Geometry plan_fwd(const daq_conv_desc& d) {
     Geometry g{};
     if (d.groups != 1 || daq_layout_qx_nhwc(&d, &Lx) != DAQ_OK || daq_layout_qw(&d, &Lw) != DAQ_OK) return g;
     if (Lx.bytes >= ((int64_t)1 << 31) || Lw.off_bwd_frag - Lw.off_fwd_frag >= ((int64_t)1 << 31)) return g;
-    g = plan(false, d.N, d.Hin, d.Win, Lx.c_pitch, daq_out_h(&d), daq_out_w(&d), d.Cout, d.kH, d.kW, d.strideH, d.strideW,
-             d.padH, d.padW, d.dilH, d.dilW);
+    auto make = [&](int px) {
+        return plan(false, d.N, d.Hin, d.Win, Lx.c_pitch, daq_out_h(&d), daq_out_w(&d), d.Cout, d.kH, d.kW, d.strideH,
+                    d.strideW, d.padH, d.padW, d.dilH, d.dilW, px);
+    };
+    g = plan_small(make(kPxWg), make);
     g.a.src_bytes = (uint32_t)Lx.bytes;
     g.a.wfrag_bytes = (uint32_t)(Lw.off_bwd_frag - Lw.off_fwd_frag);
     return g;

@@ -382,6 +382,8 @@ CONV_LAYERS = [
     wl.Layer("dw_w7", 3, 16, 7, 7, 16, 3, 3, 1, 1, 1, 16),        # rows that are not a multiple of four outputs
     wl.Layer("dw_dil2", 2, 8, 12, 12, 8, 3, 3, 1, 2, 2, 8),
     wl.Layer("c1x1_huge", 1, 2048, 4, 4, 2048, 1, 1, 1, 0),       # enough 128 x 128 tiles for the four-wave GEMM form
+    wl.Layer("c1x1_px128_7x7", 5, 96, 7, 7, 320, 1, 1, 1, 0),     # few pixels, long contraction: 128-pixel tiles of two images, ragged last group and row tile
+    wl.Layer("c1x1_px128_14", 2, 288, 14, 14, 272, 1, 1, 1, 0),   # the same with a 9-row and a 5-row tile per image, in both directions
     wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
     wl.Layer("c3x3_wide", 1, 16, 8, 130, 16, 3, 3, 1, 1),         # rows too long for the LDS window: global-fragment form
     wl.Layer("c3x3_wide_huge", 1, 768, 2, 130, 1024, 3, 3, 1, 1),  # the same with enough tiles for its LDS-staged sibling
