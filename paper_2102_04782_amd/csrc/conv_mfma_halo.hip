@@ -77,7 +77,7 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // 64 x 64 wave tiles on eight waves - two per SIMD, so that the LDS reads of one overlap the multiplies of the other.
 // DB = the contraction axis has more than one 64-byte chunk (two window buffers, restaged per chunk).
 // ST = stride (1 or 2): with one parity class its tables are indexed with constants.
-// TAPS > 0 (unit stride only): the number of filter taps is this constant.  The loop over the taps of a chunk is
+// TAPS > 0 (unit stride; TAPS = 1 also stride 2 with a single live parity class): the number of filter taps is this constant.  The loop over the taps of a chunk is
 // then unrolled, the ring of filter tiles has one slot per tap (slot = tap, so each tile is requested TAPS - 1
 // steps before its use), the tap tables are read once, and the pixel fragments of the next tap are read from LDS
 // before the multiplies of the current one: with a single wave per SIMD nothing else hides those latencies.
@@ -679,10 +679,12 @@ struct Geometry {
     int px;   // destination pixels per workgroup
 };
 
-// 1 x 1 filters at unit stride with several contraction chunks, on 64-row tiles: the form with rings of chunks
+// 1 x 1 filters with several contraction chunks, on 64-row tiles: the form with rings of chunks.  Unit stride, or
+// stride 2 without padding (one live parity class whose workgroups also write the zeros of the other three: the
+// contraction loop is the same, only the block decoding and the epilogue know about the stride).
 bool ring1_applies(const Geometry& g) {
     const HaloArgs& a = g.a;
-    return a.stride == 1 && a.T == 1 && a.ph_taps[0] == 1 && a.tap_slot[0][0] == 0 && a.double_buffer &&
+    return (a.stride == 1 || a.zfill) && a.T == 1 && a.ph_taps[0] == 1 && a.tap_slot[0][0] == 0 && a.double_buffer &&
            a.units <= g.px / 64 && g.rows == 64;
 }
 
@@ -840,12 +842,13 @@ daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
     // Layers with several contraction chunks and 3 x 3 filters at unit stride, on 64-row tiles: the form with a
     // constant tap count.  (With a single chunk the kernel is all prologue and epilogue, and the dynamic form, which
     // needs fewer registers, lets more workgroups overlap theirs; 128-row tiles stay on the eight-wave form.)
-    // 1 x 1 filters at unit stride with several contraction chunks, on 64-row tiles: the form with rings of chunks
+    // 1 x 1 filters with several contraction chunks, on 64-row tiles: the form with rings of chunks
     // (on 128-row tiles, which are chosen when the grid is large, it measured no better than the dynamic form)
     const bool ring1 = ring1_applies(g);
     if (g.px != kPxWg && !ring1) return DAQ_ERR_UNSUPPORTED;   // small tiles exist in the ring form only (see plan_small)
     if (ring1) {
-        auto kern = g.px == kPxWg ? k_conv_halo<1, true, 1, 4, 1> : k_conv_halo<1, true, 1, 4, 1, 2, 128>;
+        auto kern = a.stride == 2 ? (g.px == kPxWg ? k_conv_halo<1, true, 2, 4, 1> : k_conv_halo<1, true, 2, 4, 1, 2, 128>)
+                                  : (g.px == kPxWg ? k_conv_halo<1, true, 1, 4, 1> : k_conv_halo<1, true, 1, 4, 1, 2, 128>);
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
             return DAQ_ERR_HIP;
         DAQ_LAUNCH(names.k1, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));

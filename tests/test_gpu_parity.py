@@ -384,6 +384,8 @@ CONV_LAYERS = [
     wl.Layer("c1x1_huge", 1, 2048, 4, 4, 2048, 1, 1, 1, 0),       # enough 128 x 128 tiles for the four-wave GEMM form
     wl.Layer("c1x1_px128_7x7", 5, 96, 7, 7, 320, 1, 1, 1, 0),     # few pixels, long contraction: 128-pixel tiles of two images, ragged last group and row tile
     wl.Layer("c1x1_px128_14", 2, 288, 14, 14, 272, 1, 1, 1, 0),   # the same with a 9-row and a 5-row tile per image, in both directions
+    wl.Layer("c1x1_s2_ring", 64, 384, 28, 28, 128, 1, 1, 2, 0),   # strided 1 x 1 with two contraction chunks and 384 tiles: 256-pixel tiles, chunks in rings
+    wl.Layer("c1x1_s2_ring_odd", 3, 64, 13, 11, 160, 1, 1, 2, 0),  # ... 128-pixel tiles, odd image width (zeros of the 2 x 2 blocks one by one)
     wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
     wl.Layer("c3x3_wide", 1, 16, 8, 130, 16, 3, 3, 1, 1),         # rows too long for the LDS window: global-fragment form
     wl.Layer("c3x3_wide_huge", 1, 768, 2, 130, 1024, 3, 3, 1, 1),  # the same with enough tiles for its LDS-staged sibling
