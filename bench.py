@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the INT8 conv backward hot path on one MI355X.
 
-One step = the backward pass (Algorithm 1) of EVERY conv layer of a network, last layer first: per layer
-daq_quantize_grad_ex (statistics, discriminator, clip values, per-channel and global int8 copies of dY, stochastic
-rounding as the paper prescribes for gradients), then the data gradient (daq_conv_bwd_data_int8) and, on a second
-stream, the filter gradient (daq_conv_bwd_filter_int8): once dY is quantized the two share no data, and nothing
-downstream in a backward pass waits for dW.  (--streams 1: every launch on one stream, both gradients through
-daq_conv_bwd_int8; that step is timed as well and reported beside the headline.)  Every layer has its own tensors, as
+One step = the backward pass (Algorithm 1) of EVERY conv layer of a network, last layer first: per layer the
+quantizer (statistics, discriminator, clip values, per-channel and global int8 copies of dY, stochastic rounding as
+the paper prescribes for gradients), then the data gradient (daq_conv_bwd_data_int8) and, on a second stream, the
+filter gradient (daq_conv_bwd_filter_int8): the two share no data, and nothing downstream in a backward pass waits
+for dW.  The quantizer is daq_quantize_grad_split, which already hands to the second stream the launches that only
+the filter gradient needs.  (--streams 1: every launch on one stream, daq_quantize_grad_ex and both gradients
+through daq_conv_bwd_int8; that step is timed as well and reported beside the headline.)  Every layer has its own tensors, as
 in a real backward pass: fp32 dY, the int8 activation / filter and their scales saved by the forward entry point, the
 clip state, the results.  All of it is resident in HBM before the timed region starts.  The default workload is
 ResNet-50 at batch 64 (53 conv layers, 2.8 GB of fp32 dY per step, far beyond the 256 MB Infinity Cache, so every
@@ -167,19 +168,19 @@ def layer_step(args, s, mode, seed):
     """Algorithm 1 for one layer."""
     from paper_2102_04782_amd import binding as daq
 
-    q = daq.quantize_grad_ex(s.d, s.dY, s.state, SCHEMES[args.scheme], SCHEDULES[args.schedule], mode=mode, seed=seed, out=s.out)
     if args.streams == 2:
-        # the filter gradient needs the per-channel copy, the data gradient the global one: once dY is quantized the two
-        # share no data, and the filter gradient (off the critical path of a backward pass) moves to a second stream
-        import torch
-        main = torch.cuda.current_stream()
-        args.side.wait_stream(main)
+        # the filter gradient needs the per-channel copy, the data gradient the global one: the two share no data, and
+        # the filter gradient (off the critical path of a backward pass) runs on a second stream, ordered there behind
+        # the quantizer's launches that it needs (the quantizer makes that stream wait for its own)
+        q = daq.quantize_grad_split(s.d, s.dY, s.state, args.side, SCHEMES[args.scheme], SCHEDULES[args.schedule], mode=mode,
+                                    seed=seed, out=s.out)
         daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f, stream=args.side)
         if s.bf16_ok:
             daq.conv_bwd_data_int8_bf16(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dXh, workspace=s.ws_d)
         else:
             daq.conv_bwd_data_int8(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dX, workspace=s.ws_d)
         return
+    q = daq.quantize_grad_ex(s.d, s.dY, s.state, SCHEMES[args.scheme], SCHEDULES[args.schedule], mode=mode, seed=seed, out=s.out)
     if s.bf16_ok:
         daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f)
         daq.conv_bwd_data_int8_bf16(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dXh, workspace=s.ws_d)
@@ -388,8 +389,8 @@ def run_network(args, dev) -> int:
                    "dY_bytes_per_step": int(dy_b * E_Y_total), "cold": bool(R * dy_b * E_Y_total >= COLD_BYTES),
                    "dX": "bf16 where served" if args.dx_bf16 else "fp32", "dY": "bf16" if args.dy_bf16 else "fp32",
                    "scheme": args.scheme, "schedule": args.schedule, "streams": head_streams,
-                   "calls": "daq_quantize_grad_ex + " + (
-                       "daq_conv_bwd_data_int8, and daq_conv_bwd_filter_int8 on a second stream" if head_streams == 2 else
+                   "calls": "daq_quantize_grad_split + daq_conv_bwd_data_int8, and daq_conv_bwd_filter_int8 on the second stream"
+                            if head_streams == 2 else "daq_quantize_grad_ex + " + (
                        "daq_conv_bwd_filter_int8 + daq_conv_bwd_data_int8" if (args.separate or args.dx_bf16) else "daq_conv_bwd_int8")},
         "frac_int8_mfma_peak": round(value / PEAK_INT8_TOPS, 5),
         "step_ms_median": round(med_ms, 5), "step_ms_min": round(min_ms, 5), "stat_steps": n_stat,
@@ -648,9 +649,9 @@ def main() -> int:
                     help="with --only-timed: afterwards run 5 device-to-device copies of this many MiB, the plain copy "
                          "kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     ap.add_argument("--streams", type=int, default=2, choices=(1, 2),
-                    help="2 (default): once a layer's dY is quantized its filter gradient, which nothing downstream in a "
-                         "backward pass waits for, runs on a second stream beside the data gradient and the next layer's "
-                         "quantizer; 1: every launch on one stream.  The other count is timed too and reported beside")
+                    help="2 (default): a layer's filter gradient, which nothing downstream in a backward pass waits for, and "
+                         "the quantizer launches only it needs run on a second stream beside the data gradient and the "
+                         "next layer's quantizer; 1: every launch on one stream.  The other count is timed too and reported beside")
     ap.add_argument("--schedule", default="auto", choices=tuple(SCHEDULES),
                     help="how the quantizer shares its sweeps over dY among its launches (daq_quantize_grad_ex); same results")
     ap.add_argument("--dy-bf16", action="store_true",

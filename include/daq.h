@@ -247,6 +247,29 @@ daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void* dY, float
                                 size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_split -- daq_quantize_grad_ex on two streams (Algorithm 1's two int8 copies have
+ * different consumers: Eq. "gx" reads qg, Eq. "gw" reads vq).  In a backward pass only the data
+ * gradient is on the critical path: the next layer's gradient waits for it, nothing waits for the
+ * filter gradient.  This entry point keeps on `stream` exactly the launches qg and s_global need,
+ * and moves the others to `side_stream`, which first waits (hipStreamWaitEvent on an event the
+ * library records on `stream`; one event per device, created at the first call and kept) for the
+ * launches before them.  When the call returns
+ *   qg, s_global                            are complete in the order of `stream`,
+ *   vq, s_chan, cls, stats, s_state         are complete in the order of `side_stream`:
+ * launch the data gradient on `stream` and the filter gradient on `side_stream`, with no further
+ * synchronisation between the two.  The caller orders the next use of s_state, of the outputs and
+ * of the workspace (the next call for this layer) behind BOTH streams.  Results: the same bits as
+ * daq_quantize_grad_ex.  side_stream NULL or equal to stream: daq_quantize_grad_ex.  Both streams
+ * belong to the current device.  A layer whose global copy is channel-major (depthwise) keeps every
+ * launch on `stream`, and `side_stream` waits for all of them.  Other arguments, workspace and
+ * error codes as for daq_quantize_grad_ex; a failing event call is DAQ_ERR_HIP.
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_quantize_grad_split(const daq_conv_desc* desc, const void* dY, float* s_state, float k, float A, float lambda,
+                                   daq_round mode, uint64_t seed, const daq_quantize_opts* opts, int8_t* vq, int8_t* qg,
+                                   float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
+                                   size_t workspace_bytes, void* stream, void* side_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * daq_quantize_grad_noalloc -- daq_quantize_grad for callers that cannot allocate device memory and
  * so cannot provide a workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  The scratch of the three sweeps (statistics and count partials) lives in a

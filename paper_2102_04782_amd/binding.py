@@ -27,7 +27,7 @@ SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESI
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
-    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_split", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
     "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_clip_search", "daq_conv3d_out_d", "daq_conv3d_out_h", "daq_conv3d_out_w", "daq_conv3d_carriers", "daq_conv3d_qw_bytes",
     "daq_conv3d_workspace_bytes", "daq_quantize_grad3d", "daq_conv3d_fwd_int8", "daq_conv3d_bwd_data_int8", "daq_conv3d_bwd_filter_int8",
     "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
@@ -212,6 +212,7 @@ def lib():
         L.daq_quantize_grad_bf16.argtypes = L.daq_quantize_grad_scheme.argtypes
         L.daq_quantize_grad_ex.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.POINTER(QuantizeOpts),
                                            vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.daq_quantize_grad_split.argtypes = L.daq_quantize_grad_ex.argtypes + [vp]
         L.daq_quantize_grad_noalloc.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, vp, vp, vp, vp, vp,
                                                 vp, vp]
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
@@ -337,6 +338,22 @@ def quantize_grad_ex(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, schem
                                     _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
                                     _ptr(out.workspace), out.workspace.numel(), _stream(stream))
     _check(rc, "daq_quantize_grad_ex")
+    return out
+
+
+def quantize_grad_split(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, side_stream, scheme: int = SCHEME_DAQ,
+                        schedule: int = SCHEDULE_AUTO, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0,
+                        out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
+    """daq_quantize_grad_split: ``qg`` and ``s_global`` are ordered on ``stream``, everything else on ``side_stream``."""
+    assert dY.is_cuda and dY.dtype in (torch.float32, torch.bfloat16) and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    if out is None:
+        out = alloc_quantize_grad(d, dY.device)
+    opts = QuantizeOpts(scheme, schedule, 1 if dY.dtype == torch.bfloat16 else 0, 0)
+    rc = lib().daq_quantize_grad_split(C.byref(d), _ptr(dY), _ptr(s_state), k, A, lam, mode, seed, C.byref(opts), _ptr(out.vq),
+                                       _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
+                                       _ptr(out.workspace), out.workspace.numel(), _stream(stream), _stream(side_stream))
+    _check(rc, "daq_quantize_grad_split")
     return out
 
 

@@ -86,7 +86,7 @@ __device__ __forceinline__ v4i buffer_load16(__amdgpu_buffer_rsrc_t rsrc, uint32
 // PX = destination pixels per workgroup: 128 (a wave then owns 64 rows x 32 pixels) for 1 x 1 layers with so few
 // pixels that 256-pixel tiles would leave CUs without a workgroup.
 template <int WR, bool DB, int ST, int WAVES, int TAPS = 0, int NX = 2, int PX = kPxWg>
-__global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1) ? 2 : 1) void k_conv_halo(HaloArgs p) {
+__global__ __launch_bounds__(64 * WAVES, (TAPS == 1 || NX == 1 || PX < kPxWg) ? 2 : 1) void k_conv_halo(HaloArgs p) {
     constexpr int ROWS = 64 * WR;
     constexpr int WPX = WAVES / WR;
     constexpr int SPT = 16 * WAVES;   // window slots one pass of the workgroup stages (four lanes per slot)
@@ -814,12 +814,26 @@ constexpr HaloNames kFwdNames{"conv_fwd_halo", "conv_fwd_halo", "conv_fwd_halo_r
 // layers of a classification network: few pixels, long contraction) is cut into 128-pixel tiles instead.  Measured
 // on ResNet-50's last stages, N = 64: 512 -> 2048 at 7 x 7 (104 tiles) 23.3 -> 17.2 us, 256 -> 1024 at 14 x 14 (256
 // tiles) 14.6 -> 14.5 us cold and 12.4 -> 11.6 us warm, 2048 -> 512 at 7 x 7 (416 tiles) 14.0 -> 15.1 us: not there.
+// The constant-tap 3 x 3 form (one workgroup per CU at 256 pixels) takes 128-pixel tiles below 192 tiles: 512 -> 512
+// at 7 x 7, N = 64, has 104.
+bool taps9_applies(const Geometry& g) {
+    const HaloArgs& a = g.a;
+    return a.stride == 1 && a.ph_taps[0] == 9 && a.double_buffer && g.rows == 64;
+}
+
 template <typename Plan>
 Geometry plan_small(Geometry g, Plan replan) {
-    if (!g.ok || !ring1_applies(g)) return g;
-    if (blocks_per_row_tile(g.a) * ceil_div(g.a.Crow, 64) >= 384) return g;
-    Geometry s = replan(128);
-    return s.ok && ring1_applies(s) ? s : g;
+    if (!g.ok) return g;
+    const int64_t blocks = blocks_per_row_tile(g.a) * ceil_div(g.a.Crow, 64);
+    if (ring1_applies(g) && blocks < 384) {
+        Geometry s = replan(128);
+        return s.ok && ring1_applies(s) ? s : g;
+    }
+    if (taps9_applies(g) && blocks < 192) {
+        Geometry s = replan(128);
+        return s.ok && taps9_applies(s) ? s : g;
+    }
+    return g;
 }
 
 daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
@@ -845,7 +859,7 @@ daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
     // 1 x 1 filters with several contraction chunks, on 64-row tiles: the form with rings of chunks
     // (on 128-row tiles, which are chosen when the grid is large, it measured no better than the dynamic form)
     const bool ring1 = ring1_applies(g);
-    if (g.px != kPxWg && !ring1) return DAQ_ERR_UNSUPPORTED;   // small tiles exist in the ring form only (see plan_small)
+    if (g.px != kPxWg && !ring1 && !taps9_applies(g)) return DAQ_ERR_UNSUPPORTED;   // small tiles exist in these two forms only (see plan_small)
     if (ring1) {
         auto kern = a.stride == 2 ? (g.px == kPxWg ? k_conv_halo<1, true, 2, 4, 1> : k_conv_halo<1, true, 2, 4, 1, 2, 128>)
                                   : (g.px == kPxWg ? k_conv_halo<1, true, 1, 4, 1> : k_conv_halo<1, true, 1, 4, 1, 2, 128>);
@@ -854,8 +868,8 @@ daq_status launch(Geometry& g, hipStream_t st, const HaloNames& names) {
         DAQ_LAUNCH(names.k1, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));
         return DAQ_OK;
     }
-    if (a.stride == 1 && a.ph_taps[0] == 9 && a.double_buffer && g.rows == 64) {
-        auto kern = k_conv_halo<1, true, 1, 4, 9>;
+    if (taps9_applies(g)) {
+        auto kern = g.px == kPxWg ? k_conv_halo<1, true, 1, 4, 9> : k_conv_halo<1, true, 1, 4, 9, 2, 128>;
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds_bytes) != hipSuccess)
             return DAQ_ERR_HIP;
         DAQ_LAUNCH(names.k9, st, hipLaunchKernelGGL(kern, grid, dim3(256), g.lds_bytes, st, a));

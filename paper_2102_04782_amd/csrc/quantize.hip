@@ -1497,12 +1497,26 @@ using namespace daq;
 // ---------------------------------------------------------------------------------------------
 namespace {
 
+// Orders everything launched on `later` from now on behind everything launched on `first` so far.  One event per
+// device, created on first use and kept: a wait refers to the state of the event at the time of the call, so the
+// next record does not disturb it.
+daq_status stream_follows(hipStream_t later, hipStream_t first) {
+    static std::mutex mu;
+    static hipEvent_t ev[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return DAQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ev[dev] && hipEventCreateWithFlags(&ev[dev], hipEventDisableTiming) != hipSuccess) return DAQ_ERR_HIP;
+    if (hipEventRecord(ev[dev], first) != hipSuccess || hipStreamWaitEvent(later, ev[dev], 0) != hipSuccess) return DAQ_ERR_HIP;
+    return DAQ_OK;
+}
+
 // T = float or uint16_t (bfloat16): the element type of dY
 template <typename T>
 daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_state, float k, float A, float lambda,
                               daq_round mode, uint64_t seed, daq_scheme scheme, daq_schedule schedule, int8_t* vq,
                               int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+                              size_t workspace_bytes, void* stream, void* side_stream = nullptr) {
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
@@ -1527,6 +1541,9 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     if (rows_vector(Lv, dY, (int)sizeof(T)) == 0 && !pack_supported(Lv)) return DAQ_ERR_UNSUPPORTED;
 
     hipStream_t st = (hipStream_t)stream;
+    // With a side stream, what only the filter gradient consumes leaves the stream of the data gradient: from the
+    // point where qg and s_global need nothing more, the side stream waits for `st` and takes the remaining launches.
+    hipStream_t side = (side_stream && side_stream != stream) ? (hipStream_t)side_stream : nullptr;
     const int N = desc->N, C = desc->Cout, Ho = daq_out_h(desc), Wo = daq_out_w(desc);
     const int HW = Ho * Wo;
     const bool stoch = (mode == DAQ_ROUND_STOCHASTIC);
@@ -1578,6 +1595,8 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
         }
 #undef DAQ_RES_SIZE
 #undef DAQ_RES_LAUNCH
+        // the per-channel copy, its scales, classes and clip state are complete here; the global copy follows on `st`
+        if (side && stream_follows(side, st) != DAQ_OK) return DAQ_ERR_HIP;
         if (!qg_nhwc) {
             // depthwise layers: the per-tensor copy is channel-major too; its scale is folded from the channel maxima first
             DAQ_LAUNCH("fold_max", st, hipLaunchKernelGGL(k_fold_max, dim3(1), dim3(kBlock), 0, st, ws, C, s_global));
@@ -1647,11 +1666,19 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     // depthwise layers, whose data gradient also runs channel-major)
     ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
     bool fused = false;
-    rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, keys, ws, ca, st, qg_nhwc ? nullptr : qg, s_global,
+    // an NHWC global copy is complete here: the packing launch can move to the side stream.  (A channel-major global
+    // copy is written by the packing launches themselves: they stay, and the side stream follows at the end.)
+    hipStream_t sp = st;
+    if (side && qg_nhwc) {
+        if (stream_follows(side, st) != DAQ_OK) return DAQ_ERR_HIP;
+        sp = side;
+    }
+    rc = launch_pack("pack_vq", stoch, true, dY, Lv, nullptr, 1, vq, 0u, keys, ws, ca, sp, qg_nhwc ? nullptr : qg, s_global,
                      1u, &fused, early);
     if (rc != DAQ_OK) return rc;
     if (!qg_nhwc && !fused)
         rc = launch_pack("pack_qg", stoch, false, dY, Lv, s_global, 0, qg, 1u, keys, ws, ClipArgs{}, st);
+    if (rc == DAQ_OK && side && !qg_nhwc && stream_follows(side, st) != DAQ_OK) return DAQ_ERR_HIP;
     return rc;
 }
 
@@ -1675,6 +1702,26 @@ extern "C" daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void
     return quantize_grad_impl<float>(desc, static_cast<const float*>(dY), s_state, k, A, lambda, mode, seed,
                                      (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls, stats,
                                      workspace, workspace_bytes, stream);
+}
+
+extern "C" daq_status daq_quantize_grad_split(const daq_conv_desc* desc, const void* dY, float* s_state, float k, float A,
+                                              float lambda, daq_round mode, uint64_t seed, const daq_quantize_opts* opts,
+                                              int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls,
+                                              float* stats, void* workspace, size_t workspace_bytes, void* stream,
+                                              void* side_stream) {
+    const daq_quantize_opts def{DAQ_SCHEME_DAQ, DAQ_SCHEDULE_AUTO, 0, 0};
+    const daq_quantize_opts& o = opts ? *opts : def;
+    if (o.dy_bf16 != 0 && o.dy_bf16 != 1) return DAQ_ERR_INVALID_ARG;
+    if (o.scheme < DAQ_SCHEME_DAQ || o.scheme > DAQ_SCHEME_MCS || o.schedule < DAQ_SCHEDULE_AUTO || o.schedule > DAQ_SCHEDULE_CHANNEL_RESIDENT ||
+        o.reserved != 0)
+        return DAQ_ERR_INVALID_ARG;
+    if (o.dy_bf16)
+        return quantize_grad_impl<uint16_t>(desc, static_cast<const uint16_t*>(dY), s_state, k, A, lambda, mode, seed,
+                                            (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls,
+                                            stats, workspace, workspace_bytes, stream, side_stream);
+    return quantize_grad_impl<float>(desc, static_cast<const float*>(dY), s_state, k, A, lambda, mode, seed,
+                                     (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls, stats,
+                                     workspace, workspace_bytes, stream, side_stream);
 }
 
 extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,

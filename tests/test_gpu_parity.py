@@ -41,13 +41,17 @@ def t(a):
 # ------------------------------------------------------------------------------------------------ quantizer
 
 def check_quantize_grad(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, check_padding=True, degenerate=False,
-                        scheme=None, schedule=None):
+                        scheme=None, schedule=None, side=None):
     d, _ = descs(layer)
     st_dev = t(st.copy())
     out = daq.alloc_quantize_grad(d, dev())
     out.vq.fill_(55)      # every byte of the two copies, padding included, has to come from the call
     out.qg.fill_(55)
-    if schedule is not None:
+    if side is not None:
+        torch.cuda.synchronize()   # the fills above ran on the current stream; the side stream knows nothing of them
+        daq.quantize_grad_split(d, t(dY), st_dev, side, scheme or daq.SCHEME_DAQ, schedule or daq.SCHEDULE_AUTO, k, A, lam, mode,
+                                seed, out=out)
+    elif schedule is not None:
         daq.quantize_grad_ex(d, t(dY), st_dev, scheme or daq.SCHEME_DAQ, schedule, k, A, lam, mode, seed, out=out)
     elif scheme is None:
         daq.quantize_grad(d, t(dY), st_dev, k, A, lam, mode, seed, out=out)
@@ -384,6 +388,7 @@ CONV_LAYERS = [
     wl.Layer("c1x1_huge", 1, 2048, 4, 4, 2048, 1, 1, 1, 0),       # enough 128 x 128 tiles for the four-wave GEMM form
     wl.Layer("c1x1_px128_7x7", 5, 96, 7, 7, 320, 1, 1, 1, 0),     # few pixels, long contraction: 128-pixel tiles of two images, ragged last group and row tile
     wl.Layer("c1x1_px128_14", 2, 288, 14, 14, 272, 1, 1, 1, 0),   # the same with a 9-row and a 5-row tile per image, in both directions
+    wl.Layer("c3x3_px128", 5, 96, 7, 7, 128, 3, 3, 1, 1),          # 3 x 3 with few tiles: 128-pixel tiles of two images with their halos
     wl.Layer("c1x1_s2_ring", 64, 384, 28, 28, 128, 1, 1, 2, 0),   # strided 1 x 1 with two contraction chunks and 384 tiles: 256-pixel tiles, chunks in rings
     wl.Layer("c1x1_s2_ring_odd", 3, 64, 13, 11, 160, 1, 1, 2, 0),  # ... 128-pixel tiles, odd image width (zeros of the 2 x 2 blocks one by one)
     wl.Layer("c3x3_huge", 1, 1024, 4, 4, 1024, 3, 3, 1, 1),       # enough 64 x 64 tiles for the four-wave 3x3 form
@@ -700,6 +705,51 @@ def test_schedules_on_degenerate_channels_and_carried_state(schedule):
 def test_forward_layer_under_each_schedule(layer, schedule):
     """daq_conv_fwd_int8_ex: both layouts of q(X) from one sweep, or one sweep per layout; same bits."""
     check_forward(layer, wl.seed_for(7, CONV_LAYERS.index(layer)), schedule=schedule)
+
+
+@pytest.mark.parametrize("schedule", [daq.SCHEDULE_AUTO] + SCHEDULES, ids=["auto", "three_sweeps", "early_copy", "channel_resident"])
+@pytest.mark.parametrize("layer", [ODD_LAYERS[0], ODD_LAYERS[-2], CONV_LAYERS[9], CONV_LAYERS[11]], ids=lambda l: l.name)
+def test_quantizer_on_two_streams(layer, schedule):
+    """daq_quantize_grad_split: the launches only the filter gradient needs run on a second stream; same bits as the
+    oracle under every schedule, for NHWC and channel-major (depthwise) global copies."""
+    seed = wl.seed_for(21, layer.N * 1000 + layer.Cout)
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    side = torch.cuda.Stream()
+    check_quantize_grad(layer, dY, st, schedule=schedule, side=side)
+    check_quantize_grad(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=5, schedule=schedule, side=side)
+    check_quantize_grad(layer, dY, st, scheme=daq.SCHEME_MCS, schedule=schedule, side=side)
+
+
+def test_backward_step_on_two_streams():
+    """Algorithm 1 for one layer as a training loop runs it: the quantizer split over two streams, the data gradient
+    behind it on the first, the filter gradient on the second, no synchronisation in between - against the same
+    three calls on one stream."""
+    for cfg, schedule in ((1, daq.SCHEDULE_AUTO), (1, daq.SCHEDULE_THREE_SWEEPS), (2, daq.SCHEDULE_AUTO), (2, daq.SCHEDULE_EARLY_COPY)):
+        layer, X, W, dY, st = wl.make_inputs(cfg)
+        d, _ = descs(layer)
+        f = daq.alloc_fwd(d, dev())
+        daq.conv_fwd_int8(d, t(X), t(W), out=f)
+        g = t(dY)
+        s1, s2 = t(st.copy()), t(st.copy())
+        a = daq.quantize_grad_ex(d, g, s1, schedule=schedule, mode=daq.ROUND_STOCHASTIC, seed=3)
+        dW_a = daq.conv_bwd_filter_int8(d, f.qx_cnhw, f.s_x, a.vq, a.s_chan)
+        dX_a = daq.conv_bwd_data_int8(d, a.qg, a.s_global, f.qw, f.s_w)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        for _ in range(3):   # repeated, so that a missing wait has several chances to show
+            out = daq.alloc_quantize_grad(d, dev())
+            dW_b = torch.full(d.w_shape, 7.0, device=dev())
+            dX_b = torch.full(d.x_shape, 7.0, device=dev())
+            s2.copy_(t(st.copy()))
+            torch.cuda.synchronize()
+            b = daq.quantize_grad_split(d, g, s2, side, schedule=schedule, mode=daq.ROUND_STOCHASTIC, seed=3, out=out)
+            daq.conv_bwd_filter_int8(d, f.qx_cnhw, f.s_x, b.vq, b.s_chan, dW=dW_b, stream=side)
+            daq.conv_bwd_data_int8(d, b.qg, b.s_global, f.qw, f.s_w, dX=dX_b)
+            torch.cuda.synchronize()
+            assert torch.equal(dW_a, dW_b) and torch.equal(dX_a, dX_b)
+            assert torch.equal(a.vq, b.vq) and torch.equal(a.qg, b.qg) and torch.equal(s1, s2)
+            assert torch.equal(a.s_chan, b.s_chan) and torch.equal(a.cls, b.cls) and torch.equal(a.stats, b.stats)
 
 
 def test_unknown_schedule_is_refused():
