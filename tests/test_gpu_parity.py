@@ -752,6 +752,16 @@ def test_backward_step_on_two_streams():
             assert torch.equal(a.s_chan, b.s_chan) and torch.equal(a.cls, b.cls) and torch.equal(a.stats, b.stats)
 
 
+def test_split_quantizer_with_a_single_stream_and_bad_options():
+    """side_stream equal to stream: the plain entry point; options are checked as in daq_quantize_grad_ex."""
+    layer, X, W, dY, st = wl.make_inputs(1)
+    check_quantize_grad(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=11, side=torch.cuda.current_stream())
+    d, _ = descs(layer)
+    with pytest.raises(daq.DaqError) as e:
+        daq.quantize_grad_split(d, t(dY), t(st.copy()), torch.cuda.Stream(), schedule=9)
+    assert e.value.code == daq.ERR_INVALID_ARG
+
+
 def test_unknown_schedule_is_refused():
     layer, X, W, dY, st = wl.make_inputs(1)
     d, _ = descs(layer)
