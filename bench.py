@@ -168,6 +168,13 @@ def layer_step(args, s, mode, seed):
     """Algorithm 1 for one layer."""
     from paper_2102_04782_amd import binding as daq
 
+    if getattr(args, "given_stats", False):
+        # the producer of dY has the channel statistics: one sweep over dY is left (daq_quantize_grad_from_stats)
+        q = daq.quantize_grad_from_stats(s.d, s.dY, s.ch_absmax, s.ch_sum, s.ch_sumsq, s.state, args.side, SCHEMES[args.scheme],
+                                         SCHEDULES[args.schedule], mode=mode, seed=seed, out=s.out)
+        daq.conv_bwd_filter_int8(s.d, s.qx_cnhw, s.s_x, q.vq, q.s_chan, dW=s.dW, workspace=s.ws_f, stream=args.side)
+        daq.conv_bwd_data_int8(s.d, q.qg, q.s_global, s.qw, s.s_w, dX=s.dX, workspace=s.ws_d)
+        return
     if args.streams == 2:
         # the filter gradient needs the per-channel copy, the data gradient the global one: the two share no data, and
         # the filter gradient (off the critical path of a backward pass) runs on a second stream, ordered there behind
@@ -291,6 +298,19 @@ def run_network(args, dev) -> int:
     head_streams = args.streams
     args.streams, args.side = (1, None) if head_streams == 2 else (2, torch.cuda.Stream())
     sec_alt, _ = timed_run(args, net, nL, R, modes[args.rounding], args.steps, min(args.warmup, 3))
+    # and with the channel statistics of dY handed over by its producer (computed here, before the timed region, as a
+    # fused producer would have them): what is left of the quantizer is one sweep.  Reported beside the headline only.
+    sec_given = None
+    if not (args.dy_bf16 or args.dx_bf16 or args.scheme != "daq"):
+        for s_ in net:
+            g64 = s_.dY.double()
+            s_.ch_absmax = s_.dY.abs().amax(dim=(0, 2, 3)).float().contiguous()
+            s_.ch_sum = g64.sum(dim=(0, 2, 3)).contiguous()
+            s_.ch_sumsq = (g64 * g64).sum(dim=(0, 2, 3)).contiguous()
+            del g64
+        args.streams, args.side, args.given_stats = 2, torch.cuda.Stream(), True
+        sec_given, _ = timed_run(args, net, nL, R, modes[args.rounding], args.steps, min(args.warmup, 3))
+        args.given_stats = False
     args.streams, args.side = 1, None
     sec_one = sec if head_streams == 1 else sec_alt
 
@@ -398,6 +418,10 @@ def run_network(args, dev) -> int:
         ("one_stream" if head_streams == 2 else "two_streams"): {
             "ms_per_step": round(1e3 * sec_alt, 5), "value": round(ops_per_step / sec_alt / 1e12, 3),
             "what": "every launch on one stream" if head_streams == 2 else "filter gradients on a second stream"},
+        "producer_statistics": None if sec_given is None else {
+            "ms_per_step": round(1e3 * sec_given, 5), "value": round(ops_per_step / sec_given / 1e12, 3),
+            "what": "not the headline: daq_quantize_grad_from_stats, |g|max / sum / sum of squares per channel supplied by the "
+                    "producer of dY (computed before the timed region), two streams"},
         "phase_us_per_step": {k: round(v, 1) for k, v in phases.items()},
         "phase_note": "sums of single launch durations measured on one stream",
         "launch_gap_us_per_step": round(1e6 * sec_one - sum(phases.values()), 1),

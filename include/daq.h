@@ -270,6 +270,36 @@ daq_status daq_quantize_grad_split(const daq_conv_desc* desc, const void* dY, fl
                                    size_t workspace_bytes, void* stream, void* side_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * daq_quantize_grad_from_stats -- Algorithm 1 from its second step on, for a producer of dY that
+ * already has the channel statistics ("Infer |g|max and sigma" is then no sweep of its own; the
+ * paper notes that the two quantizations "can be easily optimized with kernel fusion").  A kernel
+ * that writes dY (the backward of a normalisation or activation layer) can reduce, per channel c over
+ * all of (n, h, w),
+ *   ch_absmax[c] = max |g|          fp32, device, [Cout]
+ *   ch_sum[c]    = sum g            fp64, device, [Cout], 8-byte aligned
+ *   ch_sumsq[c]  = sum g*g          fp64, device, [Cout], 8-byte aligned   (g widened to fp64 first)
+ * on its way; the three arrays are read, never written.  From them mu = sum/M, sigma =
+ * fp32(sqrt(max(0, sumsq/M - mu*mu))) in fp64, exactly as the other entry points derive them from
+ * their own sums, and everything after (tail mass, Eq. "judge", Eq. "gaus"/"fats", both int8 copies)
+ * is the same code.  One sweep over dY remains: it counts and writes both copies (the per-channel
+ * one under a guessed class, redone for the channels whose guess was wrong), 6 bytes per element
+ * instead of 10; layers whose copies that sweep cannot write (channel-major global copy, ablation
+ * rules, rows the vector path does not serve) and opts->schedule = DAQ_SCHEDULE_THREE_SWEEPS keep a
+ * counting and a packing sweep.  Results: those of daq_quantize_grad_ex bit for bit when the
+ * statistics are the channel's (fp64 sums taken in another order can differ in their last bits;
+ * sigma is rounded to fp32, so that shows only where an element's magnitude or a channel's count
+ * sits exactly on the threshold); for other values, the algorithm's result for those statistics.
+ * stream / side_stream as for daq_quantize_grad_split (side_stream may be NULL).  Null or
+ * misaligned statistics: DAQ_ERR_INVALID_ARG; other arguments, workspace and error codes as for
+ * daq_quantize_grad_ex.
+ * ------------------------------------------------------------------------------------------- */
+daq_status daq_quantize_grad_from_stats(const daq_conv_desc* desc, const void* dY, const float* ch_absmax,
+                                        const double* ch_sum, const double* ch_sumsq, float* s_state, float k, float A,
+                                        float lambda, daq_round mode, uint64_t seed, const daq_quantize_opts* opts,
+                                        int8_t* vq, int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats,
+                                        void* workspace, size_t workspace_bytes, void* stream, void* side_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * daq_quantize_grad_noalloc -- daq_quantize_grad for callers that cannot allocate device memory and
  * so cannot provide a workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  The scratch of the three sweeps (statistics and count partials) lives in a

@@ -27,7 +27,7 @@ SCHEDULE_AUTO, SCHEDULE_THREE_SWEEPS, SCHEDULE_EARLY_COPY, SCHEDULE_CHANNEL_RESI
 
 EXPORTS = [
     "daq_out_h", "daq_out_w", "daq_layout_vq", "daq_layout_qg", "daq_layout_qx_nhwc", "daq_layout_qx_cnhw",
-    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_split", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
+    "daq_layout_qw", "daq_workspace_bytes", "daq_quantize_grad", "daq_quantize_grad_scheme", "daq_quantize_grad_bf16", "daq_quantize_grad_ex", "daq_quantize_grad_split", "daq_quantize_grad_from_stats", "daq_quantize_grad_noalloc", "daq_conv_fwd_int8", "daq_conv_fwd_int8_ex", "daq_conv_bwd_data_int8",
     "daq_conv_bwd_filter_int8", "daq_conv_bwd_int8", "daq_conv_bwd_data_int8_bf16", "daq_conv_bwd_filter_int8_bf16", "daq_conv_bwd_data_int8_chan", "daq_clip_search", "daq_conv3d_out_d", "daq_conv3d_out_h", "daq_conv3d_out_w", "daq_conv3d_carriers", "daq_conv3d_qw_bytes",
     "daq_conv3d_workspace_bytes", "daq_quantize_grad3d", "daq_conv3d_fwd_int8", "daq_conv3d_bwd_data_int8", "daq_conv3d_bwd_filter_int8",
     "daq_prof_begin", "daq_prof_end", "daq_status_string", "daq_ceiling_mfma_i8", "daq_ceiling_stream",
@@ -213,6 +213,8 @@ def lib():
         L.daq_quantize_grad_ex.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, C.POINTER(QuantizeOpts),
                                            vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.daq_quantize_grad_split.argtypes = L.daq_quantize_grad_ex.argtypes + [vp]
+        L.daq_quantize_grad_from_stats.argtypes = [C.POINTER(ConvDesc), vp, vp, vp, vp, vp, f32, f32, f32, C.c_int, u64,
+                                                   C.POINTER(QuantizeOpts), vp, vp, vp, vp, vp, vp, vp, sz, vp, vp]
         L.daq_quantize_grad_noalloc.argtypes = [C.POINTER(ConvDesc), vp, vp, f32, f32, f32, C.c_int, u64, vp, vp, vp, vp, vp,
                                                 vp, vp]
         L.daq_conv_fwd_int8.argtypes = [C.POINTER(ConvDesc)] + [vp] * 10 + [sz, vp]
@@ -354,6 +356,28 @@ def quantize_grad_split(d: ConvDesc, dY: torch.Tensor, s_state: torch.Tensor, si
                                        _ptr(out.qg), _ptr(out.s_chan), _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats),
                                        _ptr(out.workspace), out.workspace.numel(), _stream(stream), _stream(side_stream))
     _check(rc, "daq_quantize_grad_split")
+    return out
+
+
+def quantize_grad_from_stats(d: ConvDesc, dY: torch.Tensor, ch_absmax: torch.Tensor, ch_sum: torch.Tensor,
+                             ch_sumsq: torch.Tensor, s_state: torch.Tensor, side_stream=None, scheme: int = SCHEME_DAQ,
+                             schedule: int = SCHEDULE_AUTO, k=1.0, A=0.8, lam=0.3, mode=ROUND_NEAREST, seed=0,
+                             out: Optional[QuantGrad] = None, stream=None) -> QuantGrad:
+    """daq_quantize_grad_from_stats: the producer of ``dY`` supplies |g|max (fp32), sum and sum of squares (fp64) per channel."""
+    assert dY.is_cuda and dY.dtype in (torch.float32, torch.bfloat16) and dY.is_contiguous() and tuple(dY.shape) == d.y_shape
+    assert s_state.is_cuda and s_state.dtype == torch.float32 and s_state.numel() == d.Cout
+    assert ch_absmax.is_cuda and ch_absmax.dtype == torch.float32 and ch_absmax.numel() == d.Cout and ch_absmax.is_contiguous()
+    for a in (ch_sum, ch_sumsq):
+        assert a.is_cuda and a.dtype == torch.float64 and a.numel() == d.Cout and a.is_contiguous()
+    if out is None:
+        out = alloc_quantize_grad(d, dY.device)
+    opts = QuantizeOpts(scheme, schedule, 1 if dY.dtype == torch.bfloat16 else 0, 0)
+    rc = lib().daq_quantize_grad_from_stats(C.byref(d), _ptr(dY), _ptr(ch_absmax), _ptr(ch_sum), _ptr(ch_sumsq), _ptr(s_state),
+                                            k, A, lam, mode, seed, C.byref(opts), _ptr(out.vq), _ptr(out.qg), _ptr(out.s_chan),
+                                            _ptr(out.s_global), _ptr(out.cls), _ptr(out.stats), _ptr(out.workspace),
+                                            out.workspace.numel(), _stream(stream),
+                                            _stream(side_stream) if side_stream is not None else None)
+    _check(rc, "daq_quantize_grad_from_stats")
     return out
 
 

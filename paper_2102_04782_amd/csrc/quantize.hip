@@ -1511,13 +1511,24 @@ daq_status stream_follows(hipStream_t later, hipStream_t first) {
     return DAQ_OK;
 }
 
+// Per-channel statistics that the producer of dY already has (S1 of Algorithm 1): |g|max, sum and sum of squares.
+struct ProducerStats {
+    const float* absmax;
+    const double* sum;
+    const double* sumsq;
+};
+
 // T = float or uint16_t (bfloat16): the element type of dY
 template <typename T>
 daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_state, float k, float A, float lambda,
                               daq_round mode, uint64_t seed, daq_scheme scheme, daq_schedule schedule, int8_t* vq,
                               int8_t* qg, float* s_chan, float* s_global, uint8_t* cls, float* stats, void* workspace,
-                              size_t workspace_bytes, void* stream, void* side_stream = nullptr) {
+                              size_t workspace_bytes, void* stream, void* side_stream = nullptr,
+                              const ProducerStats* given = nullptr) {
     if (!desc_valid(desc) || !dY || !s_state || !vq || !qg || !s_chan || !s_global || !cls)
+        return DAQ_ERR_INVALID_ARG;
+    if (given && (!given->absmax || !given->sum || !given->sumsq || ((uintptr_t)given->absmax & 3u) ||
+                  ((uintptr_t)given->sum & 7u) || ((uintptr_t)given->sumsq & 7u)))
         return DAQ_ERR_INVALID_ARG;
     if (mode != DAQ_ROUND_NEAREST && mode != DAQ_ROUND_STOCHASTIC) return DAQ_ERR_INVALID_ARG;
     if (scheme != DAQ_SCHEME_DAQ && scheme != DAQ_SCHEME_GQ && scheme != DAQ_SCHEME_GVQ && scheme != DAQ_SCHEME_MCS)
@@ -1569,7 +1580,7 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     // (The 1024-thread form runs one workgroup per CU, whose load, count and packing phases follow each other with nothing
     // to overlap them: on 128 -> 512 at 28 x 28, batch 64, it takes 59 + 27 us against 31 + 50 + 8 us for the sweeps - level -
     // but it saves a launch, and ResNet-50's backward pass as a whole measured 1 % faster with it than without.)
-    if (resident_ok && (schedule == DAQ_SCHEDULE_CHANNEL_RESIDENT || schedule == DAQ_SCHEDULE_AUTO)) {
+    if (!given && resident_ok && (schedule == DAQ_SCHEDULE_CHANNEL_RESIDENT || schedule == DAQ_SCHEDULE_AUTO)) {
         ws.slabs = 1;   // one |g|max partial per channel
         const ResArgs ra{div_hw, make_fastdiv((uint32_t)Wo), N, C, HW, k, A, lambda, keys};
         const ClipArgs ca{k, A, lambda, s_state, s_chan, cls, stats};
@@ -1613,11 +1624,16 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
         return DAQ_OK;
     }
 
-    // S1: statistics partials, at most 16 per channel
+    // S1: statistics partials, at most 16 per channel - or the producer's: one partial per channel, read in place
     const bool vec4 = HW >= 4;   // dword-aligned 16-byte loads run at full rate; only tiny planes take the scalar path
     const unsigned sblocks = (unsigned)(round_up(C, kXcd) * ws.slabs);
     const FastDiv div_g4 = make_fastdiv((uint32_t)((HW + 3) / 4));
-    if (vec4 && HW % 4 == 0)
+    if (given) {
+        ws.slabs = 1;
+        ws.part_max = const_cast<float*>(given->absmax);   // the consumers only read the partials
+        ws.part_s1 = const_cast<double*>(given->sum);
+        ws.part_s2 = const_cast<double*>(given->sumsq);
+    } else if (vec4 && HW % 4 == 0)
         DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<T, true, false>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
     else if (vec4)
         DAQ_LAUNCH("stats", st, hipLaunchKernelGGL((k_stats<T, true, true>), dim3(sblocks), dim3(kBlock), 0, st, dY, N, C, HW, div_g4, ws));
@@ -1632,7 +1648,9 @@ daq_status quantize_grad_impl(const daq_conv_desc* desc, const T* dY, float* s_s
     // Large gradients: the counting pass also writes the per-channel copy under a guessed class (see k_count_qg), so
     // that the third sweep over dY only touches the channels whose guess was wrong.  Small ones are bound by launch
     // latency, not by bytes, and keep the leaner counting kernel.
-    const bool want_early = schedule == DAQ_SCHEDULE_EARLY_COPY || (schedule == DAQ_SCHEDULE_AUTO && (int64_t)N * C * HW >= kEarlyVqMinElems);
+    // (With the producer's statistics the counting sweep is the only full read of dY: it always writes both copies.)
+    const bool want_early = schedule == DAQ_SCHEDULE_EARLY_COPY || (schedule == DAQ_SCHEDULE_AUTO && (int64_t)N * C * HW >= kEarlyVqMinElems) ||
+                            (given && schedule != DAQ_SCHEDULE_THREE_SWEEPS);
     const bool early = want_early && scheme == DAQ_SCHEME_DAQ && qg_nhwc && rows_vector(Lv, dY, (int)sizeof(T)) != 0 &&
                        Lv.lead + (int64_t)N * Lv.img_rows * Lv.row_pitch < ((int64_t)1 << 32);
     EarlyVq ev{};
@@ -1722,6 +1740,28 @@ extern "C" daq_status daq_quantize_grad_split(const daq_conv_desc* desc, const v
     return quantize_grad_impl<float>(desc, static_cast<const float*>(dY), s_state, k, A, lambda, mode, seed,
                                      (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls, stats,
                                      workspace, workspace_bytes, stream, side_stream);
+}
+
+extern "C" daq_status daq_quantize_grad_from_stats(const daq_conv_desc* desc, const void* dY, const float* ch_absmax,
+                                                   const double* ch_sum, const double* ch_sumsq, float* s_state, float k,
+                                                   float A, float lambda, daq_round mode, uint64_t seed,
+                                                   const daq_quantize_opts* opts, int8_t* vq, int8_t* qg, float* s_chan,
+                                                   float* s_global, uint8_t* cls, float* stats, void* workspace,
+                                                   size_t workspace_bytes, void* stream, void* side_stream) {
+    const daq_quantize_opts def{DAQ_SCHEME_DAQ, DAQ_SCHEDULE_AUTO, 0, 0};
+    const daq_quantize_opts& o = opts ? *opts : def;
+    if (o.dy_bf16 != 0 && o.dy_bf16 != 1) return DAQ_ERR_INVALID_ARG;
+    if (o.scheme < DAQ_SCHEME_DAQ || o.scheme > DAQ_SCHEME_MCS || o.schedule < DAQ_SCHEDULE_AUTO || o.schedule > DAQ_SCHEDULE_CHANNEL_RESIDENT ||
+        o.reserved != 0)
+        return DAQ_ERR_INVALID_ARG;
+    const ProducerStats ps{ch_absmax, ch_sum, ch_sumsq};
+    if (o.dy_bf16)
+        return quantize_grad_impl<uint16_t>(desc, static_cast<const uint16_t*>(dY), s_state, k, A, lambda, mode, seed,
+                                            (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls,
+                                            stats, workspace, workspace_bytes, stream, side_stream, &ps);
+    return quantize_grad_impl<float>(desc, static_cast<const float*>(dY), s_state, k, A, lambda, mode, seed,
+                                     (daq_scheme)o.scheme, (daq_schedule)o.schedule, vq, qg, s_chan, s_global, cls, stats,
+                                     workspace, workspace_bytes, stream, side_stream, &ps);
 }
 
 extern "C" daq_status daq_quantize_grad_scheme(const daq_conv_desc* desc, const float* dY, float* s_state, float k,

@@ -752,6 +752,74 @@ def test_backward_step_on_two_streams():
             assert torch.equal(a.s_chan, b.s_chan) and torch.equal(a.cls, b.cls) and torch.equal(a.stats, b.stats)
 
 
+def check_quantize_from_stats(layer, dY, st, k=1.0, A=0.8, lam=0.3, mode=0, seed=0, schedule=daq.SCHEDULE_AUTO, side=None):
+    """daq_quantize_grad_from_stats against the oracle taken step by step from the same statistics (Algorithm 1 after
+    its first line), and - the statistics being the tensor's own - against the oracle's whole quantizer."""
+    d, _ = descs(layer)
+    M = float(layer.N * d.Ho * d.Wo)
+    g64 = dY.astype(np.float64)
+    mx = np.abs(dY).max(axis=(0, 2, 3)).astype(np.float32)
+    s1, s2 = g64.sum(axis=(0, 2, 3)), (g64 * g64).sum(axis=(0, 2, 3))   # numpy's summation order, not the oracle's
+    mu = s1 / M
+    sigma = np.sqrt(np.maximum(s2 / M - mu * mu, 0.0)).astype(np.float32)
+    cnt = ref.tail_count(dY, sigma)
+    cls = np.array([ref.classify(int(c), M, lam) for c in cnt], np.uint8)
+    s_new = np.array([ref.clip_value(int(cls[c]), float(mx[c]), float(st[c]), k, A) for c in range(layer.Cout)], np.float32)
+    st_dev = t(st.copy())
+    out = daq.alloc_quantize_grad(d, dev())
+    out.vq.fill_(55)
+    out.qg.fill_(55)
+    torch.cuda.synchronize()
+    daq.quantize_grad_from_stats(d, t(dY), t(mx), t(s1), t(s2), st_dev, side, daq.SCHEME_DAQ, schedule, k, A, lam, mode, seed,
+                                 out=out)
+    torch.cuda.synchronize()
+    stats = out.stats.cpu().numpy()
+    assert np.array_equal(stats[:, 0], mx) and np.array_equal(stats[:, 1], mu.astype(np.float32))
+    assert np.array_equal(stats[:, 2], sigma), "sigma from the given sums"
+    assert np.array_equal(stats[:, 3], (cnt.astype(np.float64) / M).astype(np.float32)), "tail mass"
+    assert np.array_equal(out.cls.cpu().numpy(), cls)
+    close(st_dev.cpu().numpy(), s_new, "s_state")
+    r = ref.quantize_grad(dY, st, k, A, lam, mode, seed)
+    assert r.fragile.sum() == 0 and np.array_equal(r.cls, cls), "seed: the two summation orders must agree on the classes"
+    close(out.s_chan.cpu().numpy(), r.s_chan, "s_chan")
+    close(out.s_global.cpu().numpy(), [r.s_global], "s_global")
+    Lv, Lg = daq.layout_vq(d), daq.layout_qg(d)
+    assert np.array_equal(Lv.unpack(out.vq), r.vq) and Lv.padding_is_zero(out.vq), "vq codes"
+    assert np.array_equal(Lg.unpack(out.qg), r.qg) and Lg.padding_is_zero(out.qg), "qg codes"
+
+
+@pytest.mark.parametrize("schedule", [daq.SCHEDULE_AUTO, daq.SCHEDULE_THREE_SWEEPS], ids=["one_sweep", "two_sweeps"])
+@pytest.mark.parametrize("layer", [ODD_LAYERS[0], ODD_LAYERS[-2], CONV_LAYERS[9], CONV_LAYERS[11], CONV_LAYERS[2]], ids=lambda l: l.name)
+def test_quantizer_with_the_producers_statistics(layer, schedule):
+    seed = wl.seed_for(22, layer.N * 1000 + layer.Cout)
+    dY = wl.make_dY(layer, seed)
+    st = wl.make_state(dY, seed)
+    check_quantize_from_stats(layer, dY, st, schedule=schedule)
+    check_quantize_from_stats(layer, dY, st, mode=daq.ROUND_STOCHASTIC, seed=17, schedule=schedule, side=torch.cuda.Stream())
+    check_quantize_from_stats(layer, dY, st, lam=0.0, schedule=schedule)     # wrong guesses of the one-sweep form
+    check_quantize_from_stats(layer, dY, st, lam=1.0, k=1.5, schedule=schedule)
+
+
+def test_producers_statistics_on_config1_and_bad_pointers():
+    layer, X, W, dY, st = wl.make_inputs(1)
+    check_quantize_from_stats(layer, dY, st)
+    check_quantize_from_stats(layer, dY, np.zeros_like(st), mode=daq.ROUND_STOCHASTIC, seed=2 ** 40 + 1)
+    d, _ = descs(layer)
+    z32, z64 = torch.zeros(layer.Cout + 1, device=dev()), torch.zeros(layer.Cout + 1, dtype=torch.float64, device=dev())
+    out = daq.alloc_quantize_grad(d, dev())
+    lib = daq.lib()
+    import ctypes as C
+    opts = daq.QuantizeOpts(daq.SCHEME_DAQ, daq.SCHEDULE_AUTO, 0, 0)
+    def call(mxp, s1p, s2p):
+        return lib.daq_quantize_grad_from_stats(C.byref(d), t(dY).data_ptr(), mxp, s1p, s2p, t(st.copy()).data_ptr(), 1.0, 0.8, 0.3,
+                                                0, 0, C.byref(opts), out.vq.data_ptr(), out.qg.data_ptr(), out.s_chan.data_ptr(),
+                                                out.s_global.data_ptr(), out.cls.data_ptr(), out.stats.data_ptr(),
+                                                out.workspace.data_ptr(), out.workspace.numel(), None, None)
+    assert call(None, z64.data_ptr(), z64.data_ptr()) == daq.ERR_INVALID_ARG
+    assert call(z32.data_ptr(), z64.data_ptr() + 4, z64.data_ptr()) == daq.ERR_INVALID_ARG     # misaligned fp64 sums
+    torch.cuda.synchronize()
+
+
 def test_split_quantizer_with_a_single_stream_and_bad_options():
     """side_stream equal to stream: the plain entry point; options are checked as in daq_quantize_grad_ex."""
     layer, X, W, dY, st = wl.make_inputs(1)
