@@ -186,6 +186,20 @@ def test_quantize_grad_at_full_size(config, index):
     assert abs(out.s_global.item() - r.s_global) <= 1e-5 * r.s_global
     assert torch.equal(_logical_view(daq.layout_vq(d), out.vq), torch.from_numpy(r.vq).to(device)), "vq codes"
     assert torch.equal(_logical_view(daq.layout_qg(d), out.qg), torch.from_numpy(r.qg).to(device)), "qg codes"
+    # the same call with the channel statistics handed over (one sweep over dY): every output bit for bit.  The sums are
+    # torch's, taken in an order of its own.
+    g = torch.from_numpy(dY).to(device)
+    g64 = g.double()
+    mx, s1, s2 = g.abs().amax(dim=(0, 2, 3)).contiguous(), g64.sum(dim=(0, 2, 3)).contiguous(), (g64 * g64).sum(dim=(0, 2, 3)).contiguous()
+    del g64
+    st2 = torch.from_numpy(st.copy()).to(device)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    alt = daq.quantize_grad_from_stats(d, g, mx, s1, s2, st2, side)
+    torch.cuda.synchronize()
+    assert torch.equal(alt.stats, out.stats) and torch.equal(alt.cls, out.cls) and torch.equal(alt.s_chan, out.s_chan)
+    assert torch.equal(st2, st_dev) and torch.equal(alt.s_global, out.s_global)
+    assert torch.equal(alt.vq, out.vq) and torch.equal(alt.qg, out.qg), "codes with the producer's statistics"
 
 
 @pytest.mark.parametrize("shape,lam", [((64, 32, 92, 92), 1.0), ((64, 32, 92, 92), 0.0), ((64, 16, 130, 130), 1.0),
