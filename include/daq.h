@@ -261,7 +261,7 @@ daq_status daq_quantize_grad_ex(const daq_conv_desc* desc, const void* dY, float
  * of the workspace (the next call for this layer) behind BOTH streams.  Results: the same bits as
  * daq_quantize_grad_ex.  side_stream NULL or equal to stream: daq_quantize_grad_ex.  Both streams
  * belong to the current device.  A layer whose global copy is channel-major (depthwise) keeps every
- * launch on `stream`, and `side_stream` waits for all of them.  Other arguments, workspace and
+ * launch on `stream`, and `side_stream` waits for those that the per-channel outputs need.  Other arguments, workspace and
  * error codes as for daq_quantize_grad_ex; a failing event call is DAQ_ERR_HIP.
  * ------------------------------------------------------------------------------------------- */
 daq_status daq_quantize_grad_split(const daq_conv_desc* desc, const void* dY, float* s_state, float k, float A, float lambda,
