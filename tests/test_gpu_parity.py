@@ -805,6 +805,17 @@ def test_producers_statistics_on_config1_and_bad_pointers():
     check_quantize_from_stats(layer, dY, st)
     check_quantize_from_stats(layer, dY, np.zeros_like(st), mode=daq.ROUND_STOCHASTIC, seed=2 ** 40 + 1)
     d, _ = descs(layer)
+    # the ablation rules (checked against the oracle elsewhere) with the same statistics handed over: same bits
+    g = t(dY)
+    g64 = g.double()
+    mx, s1, s2 = g.abs().amax(dim=(0, 2, 3)).contiguous(), g64.sum(dim=(0, 2, 3)).contiguous(), (g64 * g64).sum(dim=(0, 2, 3)).contiguous()
+    for scheme, _ in SCHEMES[1:]:
+        sa, sb = t(st.copy()), t(st.copy())
+        a = daq.quantize_grad_scheme(d, g, sa, scheme, mode=daq.ROUND_STOCHASTIC, seed=9)
+        b = daq.quantize_grad_from_stats(d, g, mx, s1, s2, sb, None, scheme, mode=daq.ROUND_STOCHASTIC, seed=9)
+        torch.cuda.synchronize()
+        assert torch.equal(a.vq, b.vq) and torch.equal(a.qg, b.qg) and torch.equal(sa, sb) and torch.equal(a.s_chan, b.s_chan)
+        assert torch.equal(a.cls, b.cls) and torch.equal(a.stats, b.stats) and torch.equal(a.s_global, b.s_global)
     z32, z64 = torch.zeros(layer.Cout + 1, device=dev()), torch.zeros(layer.Cout + 1, dtype=torch.float64, device=dev())
     out = daq.alloc_quantize_grad(d, dev())
     lib = daq.lib()
